@@ -1,0 +1,193 @@
+/*
+ * spqr.h - C ABI of the SpQR inference library for AMD MI355X (gfx950).
+ *
+ * The library multiplies activations by a weight matrix W[m, n] (m = d_out,
+ * n = d_in) that is stored in the Sparse-Quantized Representation of
+ * "SpQR: A Sparse-Quantized Representation for Near-Lossless LLM Weight
+ * Compression" (Sec. 4.2):
+ *
+ *   (1) a b_w-bit code Q_ij for EVERY weight (outlier positions included),
+ *   (2) a 3-bit scale code and a 3-bit zero code per first-level group of
+ *       beta1 weights, and four 16-bit scalars (s_s, z_s, s_z, z_z) per tile
+ *       of beta2 first-level groups,
+ *   (3) a CSR-style outlier set: per outlier a 16-bit value and a 16-bit
+ *       column index, per row one 32-bit running count.
+ *
+ * Decode (Alg. 1, dequantize and fit_statistics):
+ *       s_hat = s_s * (s_q - z_s)        z_hat = s_z * (z_q - z_z)
+ *       W_hat_ij = s_hat_g * (Q_ij - z_hat_g)  (+ val_k where (i, j) is outlier k)
+ *       y = W_hat . x      with fp32 accumulation.
+ *
+ * Group geometry (group_axis):
+ *   0  a group is beta1 consecutive columns j of one row i (the paper's
+ *      Alg. 1 sweeps column blocks of width beta1); a tile is beta2 rows x
+ *      beta1 columns.
+ *   1  a group is beta1 consecutive rows i of one column j; a tile is beta1
+ *      rows x beta2 columns.
+ *
+ * Pointers are DEVICE pointers unless a parameter says "host".  The library
+ * never allocates, frees or keeps caller memory.  spqr_gemv,
+ * spqr_gemm_smallbatch and spqr_dequant_dense are asynchronous on the given
+ * HIP stream (a hipStream_t passed as void*; NULL = the default stream) and
+ * never synchronise.  Every entry point returns SPQR_OK (0) or a negative
+ * spqr_status; nothing throws, aborts or prints.
+ */
+#ifndef SPQR_H_
+#define SPQR_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum spqr_status {
+  SPQR_OK            =  0,
+  SPQR_ERR_NULL      = -1,  /* a required pointer is NULL                          */
+  SPQR_ERR_SHAPE     = -2,  /* m, n not positive multiples of the tile, n > 65536  */
+  SPQR_ERR_PARAM     = -3,  /* bit widths / group sizes / axis / layout unsupported */
+  SPQR_ERR_SIZE      = -4,  /* packed_bytes differs from spqr_packed_bytes(), nnz<0 */
+  SPQR_ERR_ALIGN     = -5,  /* packed not 16-byte aligned, other arrays misaligned  */
+  SPQR_ERR_CSR       = -6,  /* row_ptr not a valid prefix, column out of range or
+                               not strictly increasing inside a row                */
+  SPQR_ERR_NONFINITE = -7,  /* a 16-bit statistic or outlier value is inf / nan     */
+  SPQR_ERR_BATCH     = -8,  /* batch outside [1, SPQR_MAX_BATCH]                    */
+  SPQR_ERR_HIP       = -9,  /* a HIP runtime call or kernel launch failed           */
+  SPQR_ERR_DTYPE     = -10  /* unknown output dtype / dequant selector              */
+} spqr_status;
+
+#define SPQR_LAYOUT_V1   1
+#define SPQR_MAX_BATCH  16
+
+/* Output element types of y / Y. */
+#define SPQR_F32 0   /* IEEE binary32 (used for parity)            */
+#define SPQR_F16 1   /* IEEE binary16, round-to-nearest-even of the fp32 result */
+
+/*
+ * One matrix in SpQR form (Sec. 4.2; hyper-parameter names of App. B).
+ *
+ * Supported: w_bits in {3, 4}; s_bits = z_bits = 3; beta2 a multiple of 16;
+ * beta1 * beta2 * w_bits a multiple of 128; tile width even; n <= 65536;
+ * m, n multiples of the tile.  Everything else returns SPQR_ERR_PARAM/SHAPE.
+ *
+ * `packed` holds parts (1) and (2) in layout SPQR_LAYOUT_V1, written by
+ * spqr_pack_host():
+ *   - the matrix is cut into tiles (tile_rows x tile_cols as above), ordered
+ *     row-major over the tile grid; every run of up to 64 consecutive tiles of
+ *     one tile-row forms a block of L <= 64 tiles starting at byte
+ *     (first tile index) * tile_bytes;
+ *   - a tile owns KW = tile_rows*tile_cols*w_bits/128 16-byte code words and
+ *     SD = 3*beta2/16 + 2 statistic dwords; tile_bytes = 16*KW + 4*SD, which is
+ *     exactly (b_w + 6/beta1 + 64/(beta1*beta2)) * beta1*beta2 / 8 (App. D Eq. 4);
+ *   - inside a block, code word k of tile l sits at byte (k*L + l)*16; after
+ *     all code words come the floor(SD/4) full statistic words, word k of tile
+ *     l at (k*L + l)*16, then the SD%4 remaining dwords, dword k of tile l at
+ *     (k*L + l)*4  (so each load instruction of a 64-lane wavefront reads one
+ *     contiguous run);
+ *   - codes are stored as pairs: pair q = r*(tile_cols/2) + p holds the codes
+ *     of tile-local (row r, column 2p) in the low and (r, 2p+1) in the high
+ *     16-bit half of a dword, at the same bit offset.  w_bits=4: dword q/4,
+ *     offset 4*(q%4).  w_bits=3: triple t=q/16 of three dwords, e=q%16: for
+ *     e<15 dword 3t+e/5 at offset 3*(e%5); for e=15 bit i of the low (high)
+ *     code is bit 15 (31) of dword 3t+i;
+ *   - the 2*beta2 statistic codes of a tile, in the order s_q[0..beta2),
+ *     z_q[0..beta2) (group index along the tile), are stored as 3-bit pairs
+ *     in the same way; the last two statistic dwords are s_s | z_s<<16 and
+ *     s_z | z_z<<16 (binary16 bit patterns).
+ *
+ * Outliers: row_ptr[m+1] is the exclusive prefix of per-row counts
+ * (row_ptr[0] = 0, row_ptr[m] = nnz); col_idx / out_val are sorted by row then
+ * strictly increasing column.  With nnz = 0, col_idx and out_val may be NULL;
+ * row_ptr must still hold m+1 zeros.
+ *
+ * perm (optional, NULL = identity) is an input permutation of length n: the
+ * product is taken with x'[j] = x[perm[j]] (act-order checkpoints, Sec. 5).
+ */
+typedef struct spqr_matrix_t {
+  int32_t m, n;
+  int32_t w_bits, s_bits, z_bits;
+  int32_t beta1, beta2;
+  int32_t group_axis;
+  int32_t layout_version;
+  int32_t reserved;           /* must be 0 */
+  const void*     packed;     /* device, 16-byte aligned */
+  int64_t         packed_bytes;
+  const int32_t*  row_ptr;    /* device, m+1 entries */
+  const uint16_t* col_idx;    /* device, nnz entries */
+  const uint16_t* out_val;    /* device, nnz binary16 bit patterns */
+  int64_t         nnz;
+  const int32_t*  perm;       /* device, n entries, or NULL */
+} spqr_matrix_t;
+
+/* ---- host-side helpers (no GPU needed) ---------------------------------- */
+
+/* Bytes of the `packed` buffer for these parameters, or a negative
+ * spqr_status.  Equals m*n*(b_w + (b_s+b_z)/beta1 + 64/(beta1*beta2))/8,
+ * the outlier-free part of App. D Eq. 4, with no padding. */
+int64_t spqr_packed_bytes(int32_t m, int32_t n, int32_t w_bits, int32_t s_bits,
+                          int32_t z_bits, int32_t beta1, int32_t beta2,
+                          int32_t group_axis);
+
+/* Pack logical HOST arrays into layout V1 (HOST buffer `packed_out` of
+ * spqr_packed_bytes() bytes, fully overwritten).
+ *   Q      uint8 [m][n], codes < 2^w_bits
+ *   s_q,z_q uint8, [m][n/beta1] for group_axis 0, [m/beta1][n] for axis 1, < 8
+ *   s_s,z_s,s_z,z_z binary16 bit patterns, one per tile, [m/tile_rows][n/tile_cols]
+ * Returns SPQR_ERR_PARAM if a code exceeds its bit width. */
+int spqr_pack_host(int32_t m, int32_t n, int32_t w_bits, int32_t s_bits, int32_t z_bits,
+                   int32_t beta1, int32_t beta2, int32_t group_axis,
+                   const uint8_t* Q, const uint8_t* s_q, const uint8_t* z_q,
+                   const uint16_t* s_s, const uint16_t* z_s,
+                   const uint16_t* s_z, const uint16_t* z_z,
+                   void* packed_out, int64_t packed_bytes);
+
+const char* spqr_strerror(int status);
+
+/* Library / layout version: (major<<16) | layout version. */
+int32_t spqr_version(void);
+
+/* ---- device entry points ------------------------------------------------- */
+
+#define SPQR_CHECK_CSR        1u  /* O(nnz) validation of the outlier arrays (Sec. 4.2 ordering) */
+#define SPQR_CHECK_NONFINITE  2u  /* reject inf/nan in 16-bit statistics and outlier values       */
+#define SPQR_CHECK_PERM       4u  /* perm entries within [0, n)                                   */
+
+/* Validate a descriptor: O(1) parameter / size / alignment checks always,
+ * plus the device-side checks selected by `flags`.  Synchronises `stream`.
+ * Writes nothing the caller owns. */
+int spqr_pack_check(const spqr_matrix_t* A, uint32_t flags, void* stream);
+
+/* y[m] = W_hat . x  (batch 1; the token-by-token decode of Sec. 4.2,
+ * "Inference with SpQR", with the dense and the outlier part fused in one
+ * kernel).  x: n binary16 values.  y: m elements of y_dtype, overwritten. */
+int spqr_gemv(const spqr_matrix_t* A, const uint16_t* x_f16, void* y, int y_dtype,
+              void* stream);
+
+/* Y[b][m] = X[b][:] . W_hat^T for 1 <= b <= SPQR_MAX_BATCH, weights read once.
+ * X: [b][n] binary16 row-major.  Y: [b][m] of y_dtype, overwritten. */
+int spqr_gemm_smallbatch(const spqr_matrix_t* A, const uint16_t* X_f16, int b, void* Y,
+                         int y_dtype, void* stream);
+
+/* Debug decode.  `what` selects the output:
+ *   SPQR_OUT_CODES_U8   uint8  [m][n]   the b_w-bit codes
+ *   SPQR_OUT_SCALE_F32  float  group grid ([m][n/beta1] or [m/beta1][n]): s_hat
+ *   SPQR_OUT_ZERO_F32   float  group grid: z_hat
+ *   SPQR_OUT_DENSE_F32  float  [m][n]   s_hat*(Q - z_hat)
+ *   SPQR_OUT_DENSE_F16  binary16 [m][n] the same, rounded to nearest even
+ * OR-ing SPQR_OUT_WITH_OUTLIERS into a DENSE selector adds the outlier values
+ * before the final rounding.  Decoded statistics are binary32: the code and the
+ * second-level zero are widened, subtracted, then multiplied by the
+ * second-level scale, each step rounded once (no fused multiply-add). */
+#define SPQR_OUT_CODES_U8      0
+#define SPQR_OUT_SCALE_F32     1
+#define SPQR_OUT_ZERO_F32      2
+#define SPQR_OUT_DENSE_F32     3
+#define SPQR_OUT_DENSE_F16     4
+#define SPQR_OUT_WITH_OUTLIERS 0x100
+int spqr_dequant_dense(const spqr_matrix_t* A, int what, void* out, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif  /* SPQR_H_ */

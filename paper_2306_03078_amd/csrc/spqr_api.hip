@@ -1,0 +1,97 @@
+// C ABI entry points: descriptor validation and dispatch to the kernels.
+#include <hip/hip_runtime.h>
+
+#include <cstdlib>
+
+#include "../../include/spqr.h"
+#include "spqr_kernels.h"
+
+namespace {
+
+// O(1) checks shared by every device entry point.
+int to_device_matrix(const spqr_matrix_t* A, spqr::DevMatrix* D) {
+  if (!A) return SPQR_ERR_NULL;
+  if (A->layout_version != SPQR_LAYOUT_V1 || A->reserved != 0) return SPQR_ERR_PARAM;
+  int rc = spqr::make_geometry(A->m, A->n, A->w_bits, A->s_bits, A->z_bits, A->beta1, A->beta2,
+                               A->group_axis, &D->g);
+  if (rc) return rc;
+  if (!A->packed || !A->row_ptr) return SPQR_ERR_NULL;
+  if (A->nnz < 0 || A->nnz > (int64_t)A->m * A->n || A->nnz > 0x7FFFFFFFll) return SPQR_ERR_SIZE;
+  if (A->nnz > 0 && (!A->col_idx || !A->out_val)) return SPQR_ERR_NULL;
+  if (A->packed_bytes != (int64_t)D->g.ntr * D->g.ntc * D->g.tile_bytes) return SPQR_ERR_SIZE;
+  if (reinterpret_cast<uintptr_t>(A->packed) % 16 != 0) return SPQR_ERR_ALIGN;
+  if (reinterpret_cast<uintptr_t>(A->row_ptr) % 4 != 0) return SPQR_ERR_ALIGN;
+  if (reinterpret_cast<uintptr_t>(A->col_idx) % 2 != 0) return SPQR_ERR_ALIGN;
+  if (reinterpret_cast<uintptr_t>(A->out_val) % 2 != 0) return SPQR_ERR_ALIGN;
+  if (reinterpret_cast<uintptr_t>(A->perm) % 4 != 0) return SPQR_ERR_ALIGN;
+  D->packed = static_cast<const uint8_t*>(A->packed);
+  D->row_ptr = A->row_ptr;
+  D->col = A->col_idx;
+  D->val = A->out_val;
+  D->perm = A->perm;
+  D->nnz = A->nnz;
+  return SPQR_OK;
+}
+
+// SPQR_FORCE_GENERIC=1 in the environment routes products through the
+// element-wise fallback kernel (used by tests to cover it on tuned shapes).
+bool force_generic() {
+  static const bool v = [] { const char* e = std::getenv("SPQR_FORCE_GENERIC"); return e && e[0] == '1'; }();
+  return v;
+}
+
+}  // namespace
+
+extern "C" int spqr_pack_check(const spqr_matrix_t* A, uint32_t flags, void* stream) {
+  spqr::DevMatrix D;
+  int rc = to_device_matrix(A, &D);
+  if (rc) return rc;
+  if ((flags & ~(SPQR_CHECK_CSR | SPQR_CHECK_NONFINITE | SPQR_CHECK_PERM)) != 0) return SPQR_ERR_PARAM;
+  if (flags == 0) return SPQR_OK;
+  int words[3] = {0, 0, 0};
+  hipError_t e = spqr::run_checks(D, flags & SPQR_CHECK_CSR, flags & SPQR_CHECK_NONFINITE,
+                                  flags & SPQR_CHECK_PERM, words, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return SPQR_ERR_HIP;
+  if (words[0] != 0) return SPQR_ERR_CSR;
+  if (words[2] != 0) return SPQR_ERR_PARAM;
+  if (words[1] != 0) return SPQR_ERR_NONFINITE;
+  return SPQR_OK;
+}
+
+extern "C" int spqr_gemm_smallbatch(const spqr_matrix_t* A, const uint16_t* X_f16, int b, void* Y,
+                                    int y_dtype, void* stream) {
+  spqr::DevMatrix D;
+  int rc = to_device_matrix(A, &D);
+  if (rc) return rc;
+  if (!X_f16 || !Y) return SPQR_ERR_NULL;
+  if (b < 1 || b > SPQR_MAX_BATCH) return SPQR_ERR_BATCH;
+  if (y_dtype != SPQR_F32 && y_dtype != SPQR_F16) return SPQR_ERR_DTYPE;
+  if (reinterpret_cast<uintptr_t>(X_f16) % 16 != 0) return SPQR_ERR_ALIGN;
+  if (reinterpret_cast<uintptr_t>(Y) % (y_dtype == SPQR_F32 ? 4 : 2) != 0) return SPQR_ERR_ALIGN;
+  const size_t ysz = y_dtype == SPQR_F32 ? 4 : 2;
+  for (int k = 0; k < b; ++k) {
+    hipError_t e = spqr::launch_gemv(D, X_f16 + (size_t)k * D.g.n,
+                                     static_cast<uint8_t*>(Y) + (size_t)k * D.g.m * ysz, y_dtype,
+                                     static_cast<hipStream_t>(stream), force_generic());
+    if (e != hipSuccess) return SPQR_ERR_HIP;
+  }
+  return SPQR_OK;
+}
+
+extern "C" int spqr_gemv(const spqr_matrix_t* A, const uint16_t* x_f16, void* y, int y_dtype,
+                         void* stream) {
+  return spqr_gemm_smallbatch(A, x_f16, 1, y, y_dtype, stream);
+}
+
+extern "C" int spqr_dequant_dense(const spqr_matrix_t* A, int what, void* out, void* stream) {
+  spqr::DevMatrix D;
+  int rc = to_device_matrix(A, &D);
+  if (rc) return rc;
+  if (!out) return SPQR_ERR_NULL;
+  const int sel = what & 0xFF;
+  if ((what & ~(0xFF | SPQR_OUT_WITH_OUTLIERS)) != 0 || sel > SPQR_OUT_DENSE_F16) return SPQR_ERR_DTYPE;
+  if ((what & SPQR_OUT_WITH_OUTLIERS) && sel != SPQR_OUT_DENSE_F32 && sel != SPQR_OUT_DENSE_F16)
+    return SPQR_ERR_DTYPE;
+  hipError_t e = spqr::launch_dequant(D, what, out, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? SPQR_OK : SPQR_ERR_HIP;
+}

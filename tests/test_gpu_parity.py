@@ -1,0 +1,255 @@
+"""GPU parity: the HIP library (through its C ABI binding) against the CPU oracle,
+element by element on the same seeded inputs.
+
+Bars: bit-exact codes, decoded statistics (binary32 reading) and CSR handling;
+dense reconstruction within 1 binary16 ulp of the fp64 oracle; products within
+relative L2 <= 1e-3 per output vector.
+"""
+import numpy as np
+import pytest
+
+import spqr_synth as synth
+from oracle import spqr_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+REL_L2 = 1e-3
+
+
+@pytest.fixture(scope="module")
+def P():
+    import torch
+    import paper_2306_03078_amd as P
+    P.load_library()          # fails loudly if the HIP library is not built
+    assert torch.cuda.is_available()
+    return P
+
+
+def dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def rel_l2(got, ref):
+    got = np.asarray(got, dtype=np.float64); ref = np.asarray(ref, dtype=np.float64)
+    return float(np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-300))
+
+
+def f16_ulp(v):
+    """Spacing of binary16 at |v| (floor: the smallest normal's spacing)."""
+    a = np.maximum(np.abs(v), 2.0 ** -14)
+    return 2.0 ** (np.floor(np.log2(a)) - 10)
+
+
+# (w_bits, beta1, beta2, axis, tile-rows, tile-cols): several tiles, a ragged
+# last block (tile columns not a multiple of 64) and more than one step per wave.
+SHAPES = [
+    (3, 16, 16, 1, 3, 70), (3, 16, 16, 0, 2, 130), (4, 16, 16, 1, 2, 200), (4, 16, 16, 0, 3, 65),
+    (3, 8, 32, 1, 5, 67), (3, 8, 32, 0, 2, 1100), (4, 8, 32, 1, 2, 64), (4, 8, 32, 0, 1, 129),
+    (3, 16, 16, 1, 1, 1), (3, 16, 16, 1, 2, 1100),
+    (3, 16, 32, 0, 2, 5), (4, 32, 16, 1, 2, 9),          # no tuned kernel: generic path
+]
+
+
+def make(w, b1, b2, axis, ntr, ntc, rate=0.02, structure="uniform", seed=None):
+    tr, tc = synth.tile_shape(b1, b2, axis)
+    return synth.make_matrix(ntr * tr, ntc * tc, w_bits=w, beta1=b1, beta2=b2, group_axis=axis,
+                             outlier_rate=rate, outlier_structure=structure,
+                             seed=seed or (31, w, b1, b2, axis, ntr, ntc))
+
+
+@pytest.mark.parametrize("w,b1,b2,axis,ntr,ntc", SHAPES)
+def test_decode_is_bit_exact_and_dense_within_one_ulp(P, w, b1, b2, axis, ntr, ntc):
+    f = make(w, b1, b2, axis, ntr, min(ntc, 130))
+    A = P.SpQRMatrix.from_logical(f)
+    assert P.spqr_pack_check(A) == 0
+    codes = P.spqr_dequant_dense(A, P.SPQR_OUT_CODES_U8).cpu().numpy()
+    assert np.array_equal(codes, f.Q)
+    s32, z32 = orc.decode_stats_f32(f)
+    s_gpu = P.spqr_dequant_dense(A, P.SPQR_OUT_SCALE_F32).cpu().numpy()
+    z_gpu = P.spqr_dequant_dense(A, P.SPQR_OUT_ZERO_F32).cpu().numpy()
+    assert np.array_equal(s_gpu.view(np.uint32), s32.view(np.uint32))
+    assert np.array_equal(z_gpu.view(np.uint32), z32.view(np.uint32))
+    dense = orc.decode_dense(f)
+    full = orc.reconstruct(f)
+    d32 = P.spqr_dequant_dense(A, P.SPQR_OUT_DENSE_F32).cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(d32 - dense) <= 2.0 ** -20 * np.abs(dense) + 1e-30)
+    d16 = P.spqr_dequant_dense(A, P.SPQR_OUT_DENSE_F16).cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(d16 - dense) <= f16_ulp(dense))
+    o16 = P.spqr_dequant_dense(A, P.SPQR_OUT_DENSE_F16 | P.SPQR_OUT_WITH_OUTLIERS).cpu().numpy()
+    assert np.all(np.abs(o16.astype(np.float64) - full) <= f16_ulp(full))
+    o32 = P.spqr_dequant_dense(A, P.SPQR_OUT_DENSE_F32 | P.SPQR_OUT_WITH_OUTLIERS).cpu().numpy()
+    assert np.all(np.abs(o32.astype(np.float64) - full) <= 2.0 ** -20 * np.abs(full) + 1e-7)
+    # positions without an outlier are untouched by the outlier pass
+    mask = np.ones(full.shape, bool)
+    mask[orc.outlier_rows(f), f.col_idx.astype(np.int64)] = False
+    assert np.array_equal(o16[mask], P.spqr_dequant_dense(A, P.SPQR_OUT_DENSE_F16).cpu().numpy()[mask])
+
+
+@pytest.mark.parametrize("w,b1,b2,axis,ntr,ntc", SHAPES)
+def test_gemv_matches_oracle(P, w, b1, b2, axis, ntr, ntc):
+    import torch
+    f = make(w, b1, b2, axis, ntr, ntc)
+    A = P.SpQRMatrix.from_logical(f)
+    x = synth.make_x(f.n, 1, seed=(41, ntc))
+    ref = orc.matvec(f, x)[0]
+    y = P.spqr_gemv(A, dev(x[0]))
+    torch.cuda.synchronize()
+    y = y.cpu().numpy()
+    assert rel_l2(y, ref) <= REL_L2, rel_l2(y, ref)
+    # run-to-run determinism: fixed summation order, no atomics
+    y2 = P.spqr_gemv(A, dev(x[0])).cpu().numpy()
+    assert np.array_equal(y.view(np.uint32), y2.view(np.uint32))
+    # fp16 output = RNE of the fp32 output
+    yh = P.spqr_gemv(A, dev(x[0]), y_dtype=P.SPQR_F16).cpu().numpy()
+    assert np.array_equal(yh.view(np.uint16), y.astype(np.float16).view(np.uint16))
+
+
+@pytest.mark.parametrize("w,b1,b2,axis", [(3, 16, 16, 1), (3, 16, 16, 0), (4, 16, 16, 1), (3, 8, 32, 1),
+                                          (3, 8, 32, 0)])
+@pytest.mark.parametrize("b", [1, 2, 3, 4, 8, 16])
+def test_smallbatch_matches_oracle(P, w, b1, b2, axis, b):
+    f = make(w, b1, b2, axis, 3, 70)
+    A = P.SpQRMatrix.from_logical(f)
+    X = synth.make_x(f.n, b, seed=(43, b))
+    ref = orc.matvec(f, X)
+    Y = P.spqr_gemm_smallbatch(A, dev(X)).cpu().numpy()
+    assert Y.shape == (b, f.m)
+    for k in range(b):
+        assert rel_l2(Y[k], ref[k]) <= REL_L2, (k, rel_l2(Y[k], ref[k]))
+    Yh = P.spqr_gemm_smallbatch(A, dev(X), y_dtype=P.SPQR_F16).cpu().numpy()
+    assert np.array_equal(Yh.view(np.uint16), Y.astype(np.float16).view(np.uint16))
+
+
+@pytest.mark.parametrize("structure,rate", [("none", 0.0), ("rows8cols4", 0.03), ("cols64", 0.08),
+                                            ("zipf", 0.02), ("uniform", 0.3)])
+@pytest.mark.parametrize("axis", [0, 1])
+def test_outlier_structures(P, structure, rate, axis):
+    # full rows (heavy path, > 512 entries), full columns, Zipf row counts, dense-ish uniform
+    f = make(3, 16, 16, axis, 8, 72, rate=rate, structure=structure)
+    A = P.SpQRMatrix.from_logical(f)
+    assert P.spqr_pack_check(A) == 0
+    x = synth.make_x(f.n, 1, seed=(47,))
+    y = P.spqr_gemv(A, dev(x[0])).cpu().numpy()
+    assert rel_l2(y, orc.matvec(f, x)[0]) <= REL_L2
+
+
+@pytest.mark.parametrize("axis", [0, 1])
+def test_special_cases(P, axis):
+    f = make(3, 16, 16, axis, 2, 66, rate=0.02)
+    x = synth.make_x(f.n, 1, seed=(53,))
+    # zero codes and zero zero-point: only the outlier SpMV is left
+    g = make(3, 16, 16, axis, 2, 66, rate=0.02)
+    g.Q[:] = 0; g.z_q[:] = 0; g.z_z[:] = 0
+    y = P.spqr_gemv(P.SpQRMatrix.from_logical(g), dev(x[0])).cpu().numpy()
+    ref = orc.matvec_sparse_only(g, x)[0]
+    assert rel_l2(y, ref) <= REL_L2
+    # one-hot x extracts one column of W_hat.  With column groups the kernel
+    # rounds s_hat*x_j to binary16 once (relative 2^-11 of the dense part).
+    A = P.SpQRMatrix.from_logical(f)
+    W = orc.reconstruct(f)
+    D = orc.decode_dense(f)
+    for j in (0, 17, f.n - 1):
+        e = np.zeros(f.n, np.float16); e[j] = 1.0
+        y = P.spqr_gemv(A, dev(e)).cpu().numpy()
+        assert np.all(np.abs(y - W[:, j]) <= 2.0 ** -11 * np.abs(D[:, j]) + 1e-6)
+        assert rel_l2(y, W[:, j]) <= REL_L2
+    # all-zero x
+    y = P.spqr_gemv(A, dev(np.zeros(f.n, np.float16))).cpu().numpy()
+    assert np.all(y == 0)
+    # negative and zero decoded scales are legal
+    h = make(4, 16, 16, axis, 2, 10, rate=0.0)
+    h.s_s[0, 0] = 0.0; h.s_s[1, 1] = -0.04
+    xx = synth.make_x(h.n, 1, seed=(59,))
+    y = P.spqr_gemv(P.SpQRMatrix.from_logical(h), dev(xx[0])).cpu().numpy()
+    assert rel_l2(y, orc.matvec(h, xx)[0]) <= REL_L2
+
+
+def test_input_permutation(P):
+    f = make(3, 16, 16, 1, 2, 70)
+    rng = np.random.default_rng(3)
+    f.perm = rng.permutation(f.n).astype(np.int32)
+    A = P.SpQRMatrix.from_logical(f)
+    assert P.spqr_pack_check(A) == 0
+    x = synth.make_x(f.n, 2, seed=(61,))
+    Y = P.spqr_gemm_smallbatch(A, dev(x)).cpu().numpy()
+    ref = orc.matvec(f, x)
+    assert rel_l2(Y[0], ref[0]) <= REL_L2 and rel_l2(Y[1], ref[1]) <= REL_L2
+
+
+def test_pack_check_finds_planted_format_errors(P):
+    import torch
+    f = make(3, 16, 16, 1, 2, 4, rate=0.05)
+    A = P.SpQRMatrix.from_logical(f)
+    assert P.spqr_pack_check(A) == 0
+
+    def with_arrays(**kw):
+        g = make(3, 16, 16, 1, 2, 4, rate=0.05)
+        for k, v in kw.items():
+            setattr(g, k, v)
+        return P.SpQRMatrix.from_logical(g)
+
+    rp = f.row_ptr.copy(); rp[5] = rp[4] - 1 if rp[4] > 0 else rp[6] + 1
+    assert P.spqr_pack_check(with_arrays(row_ptr=rp)) == -6          # not monotone
+    rp = f.row_ptr.copy(); rp[-1] -= 1
+    assert P.spqr_pack_check(with_arrays(row_ptr=rp)) == -6          # does not end at nnz
+    r = int(np.argmax(np.diff(f.row_ptr) >= 2)); a = int(f.row_ptr[r])
+    col = f.col_idx.copy(); col[a], col[a + 1] = col[a + 1], col[a]
+    assert P.spqr_pack_check(with_arrays(col_idx=col)) == -6         # columns not increasing
+    col = f.col_idx.copy(); col[a + 1] = col[a]
+    assert P.spqr_pack_check(with_arrays(col_idx=col)) == -6         # duplicate position
+    col = f.col_idx.copy(); col[-1] = f.n
+    assert P.spqr_pack_check(with_arrays(col_idx=col)) == -6         # column out of range
+    val = f.val.copy(); val[3] = np.float16(np.inf)
+    assert P.spqr_pack_check(with_arrays(val=val)) == -7
+    assert P.spqr_pack_check(with_arrays(val=val), P.SPQR_CHECK_CSR) == 0
+    zs = f.z_s.copy(); zs[1, 2] = np.float16(np.nan)
+    assert P.spqr_pack_check(with_arrays(z_s=zs)) == -7
+    perm = np.arange(f.n, dtype=np.int32); perm[7] = f.n
+    assert P.spqr_pack_check(with_arrays(perm=perm)) == -3
+    # O(1) descriptor checks in every entry point
+    x = dev(synth.make_x(f.n, 1)[0])
+    A.desc.packed_bytes -= 4
+    with pytest.raises(P.SpQRError) as ei:
+        P.spqr_gemv(A, x)
+    assert ei.value.status == -4
+    A.desc.packed_bytes += 4
+    A.desc.packed += 4
+    with pytest.raises(P.SpQRError) as ei:
+        P.spqr_gemv(A, x)
+    assert ei.value.status == -5
+    A.desc.packed -= 4
+    lib = P.load_library()
+    import ctypes as C
+    y = torch.empty(f.m, dtype=torch.float32, device="cuda:0")
+    assert lib.spqr_gemm_smallbatch(C.byref(A.desc), x.data_ptr(), 17, y.data_ptr(), 0, None) == -8
+    assert lib.spqr_gemm_smallbatch(C.byref(A.desc), x.data_ptr(), 0, y.data_ptr(), 0, None) == -8
+    assert lib.spqr_gemv(C.byref(A.desc), x.data_ptr(), y.data_ptr(), 5, None) == -10
+    assert lib.spqr_dequant_dense(C.byref(A.desc), 9, y.data_ptr(), None) == -10
+    assert lib.spqr_dequant_dense(C.byref(A.desc), P.SPQR_OUT_CODES_U8 | 0x100, y.data_ptr(), None) == -10
+    assert lib.spqr_gemv(C.byref(A.desc), None, y.data_ptr(), 0, None) == -1
+
+
+def test_power_of_two_scaling_and_additivity(P):
+    f = make(3, 16, 16, 0, 2, 70)
+    A = P.SpQRMatrix.from_logical(f)
+    x1 = synth.make_x(f.n, 1, seed=(67,))[0]; x2 = synth.make_x(f.n, 1, seed=(71,))[0]
+    y1 = P.spqr_gemv(A, dev(x1)).cpu().numpy().astype(np.float64)
+    y4 = P.spqr_gemv(A, dev((x1 * np.float16(4)))).cpu().numpy().astype(np.float64)
+    assert rel_l2(y4, 4 * y1) <= 1e-6
+    xs = (x1.astype(np.float32) + x2.astype(np.float32)).astype(np.float16)
+    ys = P.spqr_gemv(A, dev(xs)).cpu().numpy()
+    assert rel_l2(ys, orc.matvec(f, xs)[0]) <= REL_L2
+
+
+def test_runs_on_a_side_stream(P):
+    import torch
+    f = make(3, 16, 16, 1, 2, 70)
+    A = P.SpQRMatrix.from_logical(f)
+    x = dev(synth.make_x(f.n, 1, seed=(73,))[0])
+    s = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        y = P.spqr_gemv(A, x, stream=s)
+    s.synchronize()
+    assert rel_l2(y.cpu().numpy(), orc.matvec(f, synth.make_x(f.n, 1, seed=(73,)))[0]) <= REL_L2

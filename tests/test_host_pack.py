@@ -1,0 +1,94 @@
+"""Host-side logic of the library (no GPU): size model, packer round trip
+through the oracle-side layout reader, descriptor validation, exported symbols."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2306_03078_amd as P
+import spqr_synth as synth
+from oracle import layout_reader, spqr_oracle as orc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "spqr.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = set(re.findall(r"\b(spqr_[a-z_0-9]+)\s*\(", hdr))
+    assert {"spqr_pack_check", "spqr_gemv", "spqr_gemm_smallbatch", "spqr_dequant_dense",
+            "spqr_pack_host", "spqr_packed_bytes", "spqr_strerror", "spqr_version"} <= names
+    lib = C.CDLL(P.library_path())
+    for nm in sorted(names):
+        assert hasattr(lib, nm), nm
+
+
+@pytest.mark.parametrize("w,b1,b2", [(3, 16, 16), (4, 16, 16), (3, 8, 32), (3, 16, 32), (3, 32, 16),
+                                     (4, 8, 16), (3, 64, 64), (3, 128, 128), (3, 8, 16), (3, 32, 128)])
+@pytest.mark.parametrize("axis", [0, 1])
+def test_packed_size_is_the_papers_size_model(w, b1, b2, axis):
+    # App. D Eq. 4 without outliers: b_w + (b_s+b_z)/beta1 + 64/(beta1*beta2), no padding.
+    tr, tc = synth.tile_shape(b1, b2, axis)
+    m, n = 3 * tr, 5 * tc
+    nbytes = P.packed_bytes(m, n, w, 3, 3, b1, b2, axis)
+    assert 8.0 * nbytes / (m * n) == orc.average_bits(w, 3, 3, b1, b2)
+
+
+def test_printed_bit_counts_for_config_tiles():
+    # 3.625 bits (beta1=beta2=16) and 4 bits (beta1=8, beta2=32), App. C table.
+    assert 8 * P.packed_bytes(4096, 4096, 3, 3, 3, 16, 16, 1) / 4096 ** 2 == 3.625
+    assert 8 * P.packed_bytes(8192, 8192, 3, 3, 3, 8, 32, 1) / 8192 ** 2 == 4.0
+    # an outlier costs 32 bits + the per-row 32-bit count: "32.03 to 32.1 bits" (Sec. 4.2)
+    f = synth.make_matrix(4096, 4096, outlier_rate=0.01, seed=(0, 0))
+    per_outlier = (f.col_idx.nbytes + f.val.nbytes + f.row_ptr.nbytes) * 8 / f.nnz
+    assert 32.0 < per_outlier < 32.9
+
+
+def test_unsupported_parameters_are_rejected():
+    assert P.load_library().spqr_packed_bytes(64, 64, 5, 3, 3, 16, 16, 0) == -3
+    assert P.load_library().spqr_packed_bytes(64, 64, 3, 4, 3, 16, 16, 0) == -3
+    assert P.load_library().spqr_packed_bytes(64, 64, 3, 3, 3, 16, 8, 0) == -3
+    assert P.load_library().spqr_packed_bytes(60, 64, 3, 3, 3, 16, 16, 0) == -2
+    assert P.load_library().spqr_packed_bytes(64, 1 << 17, 3, 3, 3, 16, 16, 0) == -2
+    assert "NULL" in P.spqr_strerror(-1)
+
+
+@pytest.mark.parametrize("w,b1,b2,axis,ntr,ntc", [
+    (3, 16, 16, 1, 2, 3), (3, 16, 16, 0, 3, 70), (4, 16, 16, 1, 2, 130), (4, 16, 16, 0, 1, 64),
+    (3, 8, 32, 1, 3, 65), (3, 8, 32, 0, 2, 129), (3, 16, 32, 0, 2, 5), (4, 32, 64, 1, 2, 3),
+])
+def test_pack_round_trip_through_independent_reader(w, b1, b2, axis, ntr, ntc):
+    tr, tc = synth.tile_shape(b1, b2, axis)
+    f = synth.make_matrix(ntr * tr, ntc * tc, w_bits=w, beta1=b1, beta2=b2, group_axis=axis,
+                          outlier_rate=0.0, seed=(21, w, b1, b2, axis))
+    buf = P.pack_host(f)
+    got = layout_reader.read_packed(buf, f.m, f.n, w, b1, b2, axis)
+    assert np.array_equal(got["Q"], f.Q)
+    assert np.array_equal(got["s_q"], f.s_q)
+    assert np.array_equal(got["z_q"], f.z_q)
+    for k in ("s_s", "z_s", "s_z", "z_z"):
+        assert np.array_equal(got[k].view(np.uint16), getattr(f, k).view(np.uint16)), k
+
+
+def test_packer_rejects_out_of_range_codes():
+    f = synth.make_matrix(32, 32, outlier_rate=0.0)
+    f.Q[3, 3] = 9
+    with pytest.raises(P.SpQRError) as ei:
+        P.pack_host(f)
+    assert ei.value.status == -3
+
+
+def test_host_side_descriptor_checks_need_no_gpu():
+    # NULL descriptor and bad parameters are refused before any HIP call.
+    lib = P.load_library()
+    assert lib.spqr_gemv(None, None, None, 0, None) == -1
+    d = P.binding.spqr_matrix_t()
+    d.m = d.n = 64; d.w_bits = 7; d.s_bits = d.z_bits = 3; d.beta1 = d.beta2 = 16
+    d.layout_version = 1
+    assert lib.spqr_gemv(C.byref(d), None, None, 0, None) == -3
+    d.w_bits = 3
+    assert lib.spqr_gemv(C.byref(d), None, None, 0, None) == -1      # packed is NULL
+    d.layout_version = 2
+    assert lib.spqr_dequant_dense(C.byref(d), 0, None, None) == -3
