@@ -1,0 +1,205 @@
+#!/usr/bin/env python3
+"""Benchmark of the SpQR decode GEMV on one MI355X.
+
+A step is one pass of the hot path over one batch of synthetic input: the two
+LLaMA-7B-shaped MLP projections of configuration 1 (11008x4096 and 4096x11008,
+3-bit codes, beta1=beta2=16 with column-wise 16-row groups, 0.5 % outliers half
+of them in 8 full rows and 4 full columns), batch 1, i.e. two spqr_gemv launches.
+Successive steps visit distinct copies of the weights (a pool larger than twice
+the 256 MB last-level cache) so that every launch streams from HBM.  Launches
+are replayed from a HIP graph on torch's current stream and timed with events
+on that stream.
+
+Prints ONE JSON line (see the keys below).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch read back from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# command (scaled by a copy kernel of known size); None until measured.
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = None
+
+
+def algorithmic_bytes(A, batch=1):
+    """Bytes the method must move for one product: packed tiles + CSR + x + y (fp32)."""
+    return A.compressed_bytes() + 2 * A.n * batch + 4 * A.m * batch
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=960)
+    ap.add_argument("--warmup", type=int, default=96)
+    ap.add_argument("--copies", type=int, default=16, help="distinct weight copies per layer")
+    ap.add_argument("--group-axis", type=int, default=1)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2306_03078_amd as P
+    import spqr_synth as synth
+
+    P.load_library()
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    cfg = 1
+    specs = synth.config_layers(cfg)
+    logical = [synth.make_config_layer(cfg, i, group_axis=args.group_axis) for i in range(len(specs))]
+    base = [P.SpQRMatrix.from_logical(f, dev) for f in logical]
+    for A in base:
+        assert P.spqr_pack_check(A) == 0
+    pool = [[A] + [A.clone() for _ in range(args.copies - 1)] for A in base]   # pool[layer][copy]
+    xs = [torch.from_numpy(synth.make_x(f.n, 1, seed=(cfg, i))[0]).to(dev) for i, f in enumerate(logical)]
+    ys = [torch.empty(f.m, dtype=torch.float32, device=dev) for f in logical]
+    bytes_layer = [algorithmic_bytes(A) for A in base]
+    pool_bytes = sum(bytes_layer) * args.copies
+
+    def run_step(k):
+        c = k % args.copies
+        for li in range(len(base)):
+            P.spqr_gemv(pool[li][c], xs[li], out=ys[li])
+
+    # parity on the very buffers that are timed (sampled rows, oracle one by one)
+    from oracle import spqr_oracle as orc
+    rng = np.random.default_rng(0)
+    run_step(args.copies - 1)
+    torch.cuda.synchronize()
+    parity = []
+    for li, f in enumerate(logical):
+        rows = np.sort(rng.choice(f.m, size=64, replace=False))
+        heavy = np.argsort(np.diff(f.row_ptr))[-4:]
+        rows = np.unique(np.concatenate([rows, heavy]))
+        ref = orc.matvec_rows(f, synth.make_x(f.n, 1, seed=(cfg, li)), rows)[0]
+        got = ys[li].cpu().numpy().astype(np.float64)[rows]
+        parity.append(float(np.linalg.norm(got - ref) / np.linalg.norm(ref)))
+    assert max(parity) <= 1e-3, f"parity failed on the timed buffers: {parity}"
+
+    stream = torch.cuda.current_stream()
+    chunk = args.copies                        # steps per graph replay: one sweep over the pool
+    use_graph = not args.no_graph
+    graph = None
+    if use_graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(stream)
+        with torch.cuda.stream(side):
+            for k in range(chunk):
+                run_step(k)                    # warm the allocator-free path before capture
+        stream.wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for k in range(chunk):
+                run_step(k)
+
+    def run_steps(nsteps, k0=0):
+        k = k0
+        if graph is not None:
+            while nsteps - (k - k0) >= chunk and (k % chunk) == 0:
+                graph.replay()
+                k += chunk
+        while k - k0 < nsteps:
+            run_step(k)
+            k += 1
+
+    run_steps(args.warmup)
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    run_steps(args.steps)
+    e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ev_ms = e0.elapsed_time(e1)
+    ms_per_step = ev_ms / args.steps
+    launches = args.steps * len(base)
+    avg_launch_s = ev_ms * 1e-3 / launches
+    step_bytes = sum(bytes_layer)
+    gbs = step_bytes / (ms_per_step * 1e-3) / 1e9
+
+    # per-layer figures: each layer alone, same pool rotation, eager events around a graph of one layer
+    per_layer = {}
+    for li, sp in enumerate(specs):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for c in range(args.copies):
+                P.spqr_gemv(pool[li][c], xs[li], out=ys[li])
+        for _ in range(3):
+            g.replay()
+        torch.cuda.synchronize()
+        a = torch.cuda.Event(enable_timing=True); b = torch.cuda.Event(enable_timing=True)
+        reps = max(1, args.steps // args.copies)
+        a.record()
+        for _ in range(reps):
+            g.replay()
+        b.record()
+        torch.cuda.synchronize()
+        us = a.elapsed_time(b) * 1e3 / (reps * args.copies)
+        per_layer[sp.name] = {"m": sp.m, "n": sp.n, "us": round(us, 3),
+                              "compressed_MB": round(bytes_layer[li] / 1e6, 3),
+                              "GBps": round(bytes_layer[li] / (us * 1e-6) / 1e9, 1),
+                              "frac_of_hbm_peak": round(bytes_layer[li] / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from threadpoolctl import threadpool_info
+        t = time.perf_counter()
+        for li, f in enumerate(logical):
+            orc.matvec(f, synth.make_x(f.n, 1, seed=(cfg, li)))
+        dt = time.perf_counter() - t
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        cpu = {"value": round(step_bytes / dt / 1e9, 4), "unit": "GB/s", "cores": int(threads),
+               "kind": "oracle",
+               "sample": "one full step (both layers, full size): fp64 decode to dense + outlier scatter + matvec, "
+                         f"{dt:.2f} s; host has {os.cpu_count()} logical cpus",
+               "seconds_per_step": round(dt, 3)}
+
+    out = {
+        "metric": "SpQR GEMV µs/layer + achieved HBM GB/s (% of peak), batch 1",
+        "value": round(gbs, 2),
+        "unit": "GB/s of compressed bytes (packed tiles + CSR + x + y) per second, whole step",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 6),
+        "us_per_layer": round(ms_per_step * 1e3 / len(base), 3),
+        "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "config 1: LLaMA-7B MLP projections 11008x4096 + 4096x11008, w=3, beta1=beta2=16, "
+                               f"group_axis={args.group_axis}, 0.5% outliers (8 rows + 4 cols + uniform), batch 1",
+                   "launches_per_step": len(base), "weight_copies": args.copies,
+                   "pool_MB": round(pool_bytes / 1e6, 1), "graph_replay": bool(use_graph),
+                   "wall_ms_per_step": round(wall * 1e3 / args.steps, 6),
+                   "parity_rel_l2_sampled_rows": [float(f"{p:.3e}") for p in parity]},
+        "layers": per_layer,
+        "roofline": {"bound": "hbm", "achieved": round(step_bytes / len(base) / avg_launch_s / 1e9, 2),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(step_bytes / len(base) / avg_launch_s / 1e9 / HBM_PEAK_GBS, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH,
+                     "kernel": "gemv_tile256_kernel<3,16,16,%d>" % args.group_axis,
+                     "algorithmic_bytes_per_launch": step_bytes // len(base),
+                     "avg_launch_us": round(avg_launch_s * 1e6, 3)},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -49,6 +49,10 @@ def load_library():
     global _lib
     if _lib is not None:
         return _lib
+    # PyTorch ships its own HIP runtime; importing it first makes the dynamic
+    # linker resolve libspqr.so against that same runtime instead of loading a
+    # second one (two runtimes in one process cannot share streams or memory).
+    import torch  # noqa: F401
     if not os.path.exists(_LIB_PATH):
         raise FileNotFoundError(
             f"{_LIB_PATH} is missing: build it with `python -m paper_2306_03078_amd.build`")
