@@ -21,8 +21,9 @@ int to_device_matrix(const spqr_matrix_t* A, spqr::DevMatrix* D) {
   if (A->packed_bytes != (int64_t)D->g.ntr * D->g.ntc * D->g.tile_bytes) return SPQR_ERR_SIZE;
   if (reinterpret_cast<uintptr_t>(A->packed) % 16 != 0) return SPQR_ERR_ALIGN;
   if (reinterpret_cast<uintptr_t>(A->row_ptr) % 4 != 0) return SPQR_ERR_ALIGN;
-  if (reinterpret_cast<uintptr_t>(A->col_idx) % 2 != 0) return SPQR_ERR_ALIGN;
-  if (reinterpret_cast<uintptr_t>(A->out_val) % 2 != 0) return SPQR_ERR_ALIGN;
+  // the kernels read the outlier arrays in aligned 16-byte granules
+  if (reinterpret_cast<uintptr_t>(A->col_idx) % 16 != 0) return SPQR_ERR_ALIGN;
+  if (reinterpret_cast<uintptr_t>(A->out_val) % 16 != 0) return SPQR_ERR_ALIGN;
   if (reinterpret_cast<uintptr_t>(A->perm) % 4 != 0) return SPQR_ERR_ALIGN;
   D->packed = static_cast<const uint8_t*>(A->packed);
   D->row_ptr = A->row_ptr;

@@ -21,39 +21,52 @@ namespace spqr {
 
 // ---------------------------------------------------------------------------
 // Pair extraction for 256-code tiles held in registers.
-// Returns the bit pattern of two binary16 numbers (1 + q_lo/2^W, 1 + q_hi/2^W).
+// Returns the bit pattern of two binary16 numbers (1 + q_lo/2^W, 1 + q_hi/2^W):
+// one shift puts the two codes on the top mantissa bits of each half-word, one
+// v_and_or_b32 masks them and sets the exponent of 1.0.
 // ---------------------------------------------------------------------------
+struct PairConsts {
+  uint32_t mask;     // SGPR: code bits inside both half-words
+  uint32_t magic;    // VGPR: 0x3C003C00, binary16 1.0 twice
+  uint32_t m0, m1, m2;   // SGPR: single-bit masks of the split pair of a 3-bit triple
+};
+
+// Keeps a constant in a scalar / vector register: gfx9 VOP3 encodings take no
+// literal and only one scalar operand, so v_and_or_b32 needs (vgpr, sgpr, vgpr).
+__device__ __forceinline__ uint32_t in_sgpr(uint32_t v) { asm volatile("" : "+s"(v)); return v; }
+__device__ __forceinline__ uint32_t in_vgpr(uint32_t v) { asm volatile("" : "+v"(v)); return v; }
+
 template <int W>
-__device__ __forceinline__ uint32_t pair_f16(const uint32_t* c, int q) {
+__device__ __forceinline__ PairConsts make_pair_consts() {
+  PairConsts k;
+  k.mask = in_sgpr(W == 4 ? 0x03C003C0u : 0x03800380u);
+  k.magic = in_vgpr(0x3C003C00u);
+  k.m0 = in_sgpr(0x00800080u); k.m1 = in_sgpr(0x01000100u); k.m2 = in_sgpr(0x02000200u);
+  return k;
+}
+
+template <int W>
+__device__ __forceinline__ uint32_t pair_f16(const uint32_t* c, int q, const PairConsts& k) {
   if constexpr (W == 4) {
     const uint32_t d = c[q >> 2];
     const int o = 4 * (q & 3);                       // code offset inside each half-word
     const uint32_t t = o < 6 ? (d << (6 - o)) : (d >> (o - 6));
-    return (t & 0x03C003C0u) | 0x3C003C00u;          // mantissa bits 9..6
+    return (t & k.mask) | k.magic;                   // mantissa bits 9..6
   } else {
     const int t3 = q >> 4, e = q & 15;
     if (e < 15) {
       const uint32_t d = c[3 * t3 + e / 5];
       const int o = 3 * (e % 5);
       const uint32_t t = o < 7 ? (d << (7 - o)) : (d >> (o - 7));
-      return (t & 0x03800380u) | 0x3C003C00u;        // mantissa bits 9..7
+      return (t & k.mask) | k.magic;                 // mantissa bits 9..7
     } else {
       const uint32_t d0 = c[3 * t3], d1 = c[3 * t3 + 1], d2 = c[3 * t3 + 2];
-      uint32_t t = ((d0 >> 8) & 0x00800080u) | 0x3C003C00u;
-      t |= (d1 >> 7) & 0x01000100u;
-      t |= (d2 >> 6) & 0x02000200u;
+      uint32_t t = ((d0 >> 8) & k.m0) | k.magic;
+      t = ((d1 >> 7) & k.m1) | t;
+      t = ((d2 >> 6) & k.m2) | t;
       return t;
     }
   }
-}
-
-// 3-bit statistic code number idx from the statistic dwords of a tile.
-__device__ __forceinline__ uint32_t stat3(const uint32_t* s, int idx) {
-  const int q = idx >> 1, hi = (idx & 1) * 16;
-  const int t3 = q >> 4, e = q & 15;
-  if (e < 15) return (s[3 * t3 + e / 5] >> (3 * (e % 5) + hi)) & 7u;
-  return ((s[3 * t3] >> (15 + hi)) & 1u) | (((s[3 * t3 + 1] >> (15 + hi)) & 1u) << 1)
-       | (((s[3 * t3 + 2] >> (15 + hi)) & 1u) << 2);
 }
 
 // ---------------------------------------------------------------------------
@@ -95,170 +108,243 @@ __device__ __forceinline__ void load_tile(TileRegs<W, TR, TC, AXIS>& t, const ui
     t.s[4 * T::SWF + k] = *reinterpret_cast<const uint32_t*>(rb + ((int64_t)k * L + lane) * 4);
 }
 
-// One tile's contribution.  acc[r] accumulates, per output row r of the strip:
-//   AXIS 1: sum_j (1 + q_rj/2^W) * u_j   with u_j = fp16(s_hat_j * x_j);  csum
+// One tile's contribution.  Codes enter the dot products as 1 + q/2^W and the
+// statistic codes as 1 + s_q/8, 1 + z_q/8 (exact binary16 values); the offsets
+// are removed with per-tile sums.  acc[r] accumulates, per output row r:
+//   AXIS 1: sum_j (1 + q_rj/2^W) * u_j  with u_j = fp16(s_hat_j * x_j); csum
 //           accumulates sum_j (2^W + z_hat_j) * u_j, so y_r = 2^W*acc[r] - csum.
 //   AXIS 0: s_hat_r * (2^W * sum_j (1 + q_rj/2^W) x_j - (2^W + z_hat_r) * sum_j x_j).
 template <int W, int TR, int TC, int AXIS>
 __device__ __forceinline__ void tile_fma(const TileRegs<W, TR, TC, AXIS>& t,
                                          const uint32_t* xpair /* TC/2 dwords in LDS */,
-                                         float (&acc)[TR], float& csum) {
+                                         float (&acc)[TR], float& csum, const PairConsts& k,
+                                         const PairConsts& k3) {
   using T = TileRegs<W, TR, TC, AXIS>;
   constexpr int PPR = TC / 2;
   constexpr float SCALE = (float)(1 << W);
+  const half2_t ones = as_half2(k.magic);
   const uint32_t a = t.s[T::SD - 2], b = t.s[T::SD - 1];
   const float s_s = h2f((uint16_t)(a & 0xFFFF)), z_s = h2f((uint16_t)(a >> 16));
   const float s_z = h2f((uint16_t)(b & 0xFFFF)), z_z = h2f((uint16_t)(b >> 16));
-  const float s_off = -s_s * z_s;             // s_hat = s_s*s_q + s_off
-  const float z_off = -s_z * z_z + SCALE;     // 2^W + z_hat = s_z*z_q + z_off
+  // s_hat = s_s*(s_q - z_s) = c1*(1 + s_q/8) + c2
+  const float c1 = 8.f * s_s, c2 = -s_s * z_s - c1;
 
   uint32_t xp[PPR];
 #pragma unroll
   for (int p = 0; p < PPR; p += 4) {
-    if constexpr (PPR % 4 == 0) {
-      u32x4 v = *reinterpret_cast<const u32x4*>(xpair + p);
-      xp[p] = v.x; xp[p + 1] = v.y; xp[p + 2] = v.z; xp[p + 3] = v.w;
-    }
+    u32x4 v = *reinterpret_cast<const u32x4*>(xpair + p);
+    xp[p] = v.x; xp[p + 1] = v.y; xp[p + 2] = v.z; xp[p + 3] = v.w;
   }
 
   if constexpr (AXIS == 1) {
     uint32_t up[PPR];
+    float U = 0.f, Zd = 0.f;
 #pragma unroll
     for (int p = 0; p < PPR; ++p) {
       const half2_t xv = as_half2(xp[p]);
-      const float s0 = fmaf(s_s, (float)stat3(t.s, 2 * p), s_off);
-      const float s1 = fmaf(s_s, (float)stat3(t.s, 2 * p + 1), s_off);
-      const float z0 = fmaf(s_z, (float)stat3(t.s, T::B2 + 2 * p), z_off);
-      const float z1 = fmaf(s_z, (float)stat3(t.s, T::B2 + 2 * p + 1), z_off);
+      const half2_t sq = as_half2(pair_f16<3>(t.s, p, k3));
+      const half2_t zq = as_half2(pair_f16<3>(t.s, T::B2 / 2 + p, k3));
       half2_t u;
-      u.x = (_Float16)(s0 * (float)xv.x);
-      u.y = (_Float16)(s1 * (float)xv.y);
+      u.x = (_Float16)(fmaf((float)sq.x, c1, c2) * (float)xv.x);
+      u.y = (_Float16)(fmaf((float)sq.y, c1, c2) * (float)xv.y);
       up[p] = __builtin_bit_cast(uint32_t, u);
-      csum = fmaf(z0, (float)u.x, csum);
-      csum = fmaf(z1, (float)u.y, csum);
+      U = __builtin_amdgcn_fdot2(u, ones, U, false);
+      Zd = __builtin_amdgcn_fdot2(u, zq, Zd, false);
     }
+    // sum_j (2^W + z_hat_j) u_j with z_hat_j = s_z*(z_q - z_z), sum_j z_q u_j = 8*(Zd - U)
+    csum = fmaf(SCALE - s_z * z_z - 8.f * s_z, U, fmaf(8.f * s_z, Zd, csum));
 #pragma unroll
     for (int r = 0; r < TR; ++r) {
       float d = acc[r];
 #pragma unroll
       for (int p = 0; p < PPR; ++p)
-        d = __builtin_amdgcn_fdot2(as_half2(pair_f16<W>(t.c, r * PPR + p)), as_half2(up[p]), d, false);
+        d = __builtin_amdgcn_fdot2(as_half2(pair_f16<W>(t.c, r * PPR + p, k)), as_half2(up[p]), d, false);
       acc[r] = d;
     }
   } else {
     float X = 0.f;
 #pragma unroll
-    for (int p = 0; p < PPR; ++p)
-      X = __builtin_amdgcn_fdot2(as_half2(xp[p]), as_half2(0x3C003C00u), X, false);
+    for (int p = 0; p < PPR; ++p) X = __builtin_amdgcn_fdot2(as_half2(xp[p]), ones, X, false);
+    // 2^W + z_hat = e1*(1 + z_q/8) + e2
+    const float e1 = 8.f * s_z, e2 = SCALE - s_z * z_z - e1;
 #pragma unroll
-    for (int r = 0; r < TR; ++r) {
-      float d = 0.f;
+    for (int r2 = 0; r2 < TR / 2; ++r2) {
+      const half2_t sq = as_half2(pair_f16<3>(t.s, r2, k3));
+      const half2_t zq = as_half2(pair_f16<3>(t.s, T::B2 / 2 + r2, k3));
 #pragma unroll
-      for (int p = 0; p < PPR; ++p)
-        d = __builtin_amdgcn_fdot2(as_half2(pair_f16<W>(t.c, r * PPR + p)), as_half2(xp[p]), d, false);
-      const float sh = fmaf(s_s, (float)stat3(t.s, r), s_off);
-      const float zo = fmaf(s_z, (float)stat3(t.s, T::B2 + r), z_off);
-      acc[r] = fmaf(sh, fmaf(SCALE, d, -zo * X), acc[r]);
+      for (int h = 0; h < 2; ++h) {
+        const int r = 2 * r2 + h;
+        float d = 0.f;
+#pragma unroll
+        for (int p = 0; p < PPR; ++p)
+          d = __builtin_amdgcn_fdot2(as_half2(pair_f16<W>(t.c, r * PPR + p, k)), as_half2(xp[p]), d, false);
+        const float sh = fmaf((float)(h ? sq.y : sq.x), c1, c2);
+        const float zo = fmaf((float)(h ? zq.y : zq.x), e1, e2);
+        acc[r] = fmaf(sh, fmaf(SCALE, d, -zo * X), acc[r]);
+      }
     }
   }
 }
 
-// A 4-bit tile needs 32 code registers (twice, with the prefetch of the next
-// step), which does not fit the 128 registers a 1024-thread workgroup allows.
+// ---------------------------------------------------------------------------
+// Outliers of one strip (Sec. 4.2 "Storing outliers": entries sorted by row,
+// then column; one 32-bit running count per row).  The strip's entries are one
+// contiguous CSR range.  It is cut into aligned chunks of 8 entries (16 bytes
+// of column indices + 16 bytes of values) dealt to the threads of the
+// workgroup one each, whatever the rows' lengths; a thread multiplies its 8
+// values with x and parks the 8 products in LDS at their CSR position.  After
+// one barrier 16 lanes per row add that row's contiguous slice of products in
+// a fixed order.  No atomics, no search, one global round trip.
+// ---------------------------------------------------------------------------
+
+// Products of the 8 entries of chunk c (global chunk index); entries outside
+// [e_lo, e_hi) give 0.
+__device__ __forceinline__ void chunk_products(const uint16_t* xs, int e_lo, int e_hi, int c,
+                                               const u32x4& c8, const u32x4& v8, float (&p)[8]) {
+  const uint32_t cw[4] = {c8.x, c8.y, c8.z, c8.w};
+  const uint32_t vw[4] = {v8.x, v8.y, v8.z, v8.w};
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int e = 8 * c + i;
+    const bool ok = e >= e_lo && e < e_hi;
+    const uint32_t col = (i & 1) ? (cw[i >> 1] >> 16) : (cw[i >> 1] & 0xFFFFu);
+    const uint32_t val = (i & 1) ? (vw[i >> 1] >> 16) : (vw[i >> 1] & 0xFFFFu);
+    const float xv = h2f(xs[ok ? col : 0u]);
+    p[i] = ok ? h2f((uint16_t)val) * xv : 0.f;
+  }
+}
+
+__device__ __forceinline__ void store_products(float* prod, int slot, const float (&p)[8]) {
+  typedef float f32x4 __attribute__((ext_vector_type(4)));
+  f32x4 lo = {p[0], p[1], p[2], p[3]}, hi = {p[4], p[5], p[6], p[7]};
+  reinterpret_cast<f32x4*>(prod)[2 * slot] = lo;
+  reinterpret_cast<f32x4*>(prod)[2 * slot + 1] = hi;
+}
+
+// Sum of prod[i] for i in [lo, hi) by the 16 lanes of a group, four reads in flight.
+__device__ __forceinline__ float strided16_sum(const float* prod, int lo, int hi, int l16) {
+  float s = 0.f;
+  for (int i = lo + l16; i < hi; i += 64) {
+    float v[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) v[k] = prod[min(i + 16 * k, hi - 1)];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) s += (i + 16 * k < hi) ? v[k] : 0.f;
+  }
+  return s;
+}
+
+// Workgroup size limits: 16 wavefronts leave the compiler 128 registers per
+// lane, 8 wavefronts 256; a 4-bit tile needs 32 code registers, twice with the
+// prefetch of the next step.
 template <int W> struct WavesPerGroup { static constexpr int MAX = W == 3 ? 16 : 8; };
 
 template <int W, int TR, int TC, int AXIS>
 __global__ void __launch_bounds__(64 * WavesPerGroup<W>::MAX)
-gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restrict__ y, int y_dtype) {
+gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restrict__ y, int y_dtype,
+                    int chunk_cap) {
   using T = TileRegs<W, TR, TC, AXIS>;
   static_assert(TR * TC == 256, "tile must hold 256 codes");
   static_assert((TC / 2) % 4 == 0, "x pairs are read as 16-byte LDS words");
   constexpr int TILE_BYTES = 16 * T::KW + 4 * T::SD;
   constexpr int MAX_WAVES = 16;
-  constexpr int LIGHT_MAX = 512;             // rows with more outliers use the whole workgroup
+  constexpr int XCH = 4;                     // 16-byte chunks of x a thread keeps in flight
+  constexpr int KR = 4;                      // outlier chunks per thread and round on the slow path
+  constexpr int LONG_ROW = 1024;             // rows with more entries are summed by all threads
 
+  // dynamic LDS: x | products of the outlier entries (8 floats per chunk)
   extern __shared__ __align__(16) uint8_t smem[];
   uint16_t* xs = reinterpret_cast<uint16_t*>(smem);
+  const int n = A.g.n, ntc = A.g.ntc;
+  const int xbytes = (n * 2 + 15) & ~15;
+  float* prod = reinterpret_cast<float*>(smem + xbytes);
   __shared__ float red[MAX_WAVES][TR];
   __shared__ float osum[TR];
   __shared__ float hred[MAX_WAVES];
-  __shared__ int rp[TR + 1];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int nthreads = blockDim.x, nwaves = nthreads >> 6;
+  const int l16 = tid & 15, g16 = tid >> 4, ngroups = nthreads >> 4;
   const int strip = blockIdx.x;
-  const int n = A.g.n, ntc = A.g.ntc;
   const int nsteps = (ntc + 63) >> 6;
   const uint8_t* strip_base = A.packed + (int64_t)strip * ntc * TILE_BYTES;
+  const int32_t* rpg = A.row_ptr + (int64_t)strip * TR;
 
-  // Issue the first tile load before anything else so it overlaps the staging.
-  T cur;
-  int step = wave;
-  bool have = false;
-  if (step < nsteps) {
-    const int L = min(64, ntc - 64 * step);
-    if (lane < L) { load_tile(cur, strip_base + (int64_t)64 * step * TILE_BYTES, L, lane); have = true; }
+  // ---- issue order: row pointers and x first (small, mostly cache hits), then
+  // the first tile, so that staging x never waits for the big loads -------------
+  const int e_lo = rpg[0], e_hi = rpg[TR];   // uniform: scalar loads
+  int ra = 0, rb = 0;                        // CSR range of the row this group of 16 lanes sums
+  if (g16 < TR) { ra = rpg[g16]; rb = rpg[g16 + 1]; }
+  const int nvec = n >> 3;                   // 16-byte chunks of x
+  u32x4 xr[XCH];
+  if (A.perm == nullptr) {
+#pragma unroll
+    for (int k = 0; k < XCH; ++k) {
+      const int i = tid + k * nthreads;
+      if (i < nvec) xr[k] = reinterpret_cast<const u32x4*>(x)[i];
+    }
   }
 
-  if (tid <= TR) rp[tid] = A.row_ptr[strip * TR + tid];
+  T t0, t1;
+  auto issue = [&](T& t, int st) -> bool {
+    if (st < nsteps) {
+      const int L = min(64, ntc - 64 * st);
+      if (lane < L) { load_tile(t, strip_base + (int64_t)64 * st * TILE_BYTES, L, lane); return true; }
+    }
+    return false;
+  };
+  int step = wave;
+  bool h0 = issue(t0, step), h1 = false;
 
-  // Stage x (binary16) in LDS, optionally through the input permutation.
   if (A.perm == nullptr) {
-    const int nvec = n >> 3;                 // 16-byte chunks; n is a multiple of the tile width (even)
-    const u32x4* src = reinterpret_cast<const u32x4*>(x);
     u32x4* dst = reinterpret_cast<u32x4*>(xs);
-    for (int i = tid; i < nvec; i += nthreads) dst[i] = src[i];
+#pragma unroll
+    for (int k = 0; k < XCH; ++k) {
+      const int i = tid + k * nthreads;
+      if (i < nvec) dst[i] = xr[k];
+    }
+    for (int i = tid + XCH * nthreads; i < nvec; i += nthreads) dst[i] = reinterpret_cast<const u32x4*>(x)[i];
     for (int j = (nvec << 3) + tid; j < n; j += nthreads) xs[j] = x[j];
   } else {
     for (int j = tid; j < n; j += nthreads) xs[j] = x[A.perm[j]];
   }
-  __syncthreads();
 
+  // ---- outliers: fetch this thread's chunk now, use it after the dense part -----
+  const int c_lo = e_lo >> 3;
+  const int nchunks = e_hi > e_lo ? ((e_hi - 1) >> 3) - c_lo + 1 : 0;
+  const u32x4* col8 = reinterpret_cast<const u32x4*>(A.col);
+  const u32x4* val8 = reinterpret_cast<const u32x4*>(A.val);
+  const int first_round = min(nchunks, nthreads);        // nthreads <= chunk_cap <= KR*nthreads
+  u32x4 pc = {0, 0, 0, 0}, pv = {0, 0, 0, 0};
+  if (tid < first_round) { pc = col8[c_lo + tid]; pv = val8[c_lo + tid]; }
+  __syncthreads();                           // x is staged
+
+  // ---- dense part -------------------------------------------------------------
   float acc[TR];
 #pragma unroll
   for (int r = 0; r < TR; ++r) acc[r] = 0.f;
   float csum = 0.f;
-
+  const PairConsts kc = make_pair_consts<W>();
+  const PairConsts k3 = make_pair_consts<3>();
   const uint32_t* xs32 = reinterpret_cast<const uint32_t*>(xs);
-  while (step < nsteps) {                    // wave-uniform loop
-    const int nstep = step + nwaves;
-    T nxt;
-    bool have_next = false;
-    if (nstep < nsteps) {
-      const int L = min(64, ntc - 64 * nstep);
-      if (lane < L) { load_tile(nxt, strip_base + (int64_t)64 * nstep * TILE_BYTES, L, lane); have_next = true; }
-    }
-    if (have) tile_fma<W, TR, TC, AXIS>(cur, xs32 + (64 * step + lane) * (TC / 2), acc, csum);
-    cur = nxt; have = have_next; step = nstep;
+  while (step < nsteps) {                    // wave-uniform; two steps per trip, registers ping-pong
+    h1 = issue(t1, step + nwaves);
+    if (h0) tile_fma<W, TR, TC, AXIS>(t0, xs32 + (64 * step + lane) * (TC / 2), acc, csum, kc, k3);
+    step += nwaves;
+    if (step >= nsteps) break;
+    h0 = issue(t0, step + nwaves);
+    if (h1) tile_fma<W, TR, TC, AXIS>(t1, xs32 + (64 * step + lane) * (TC / 2), acc, csum, kc, k3);
+    step += nwaves;
   }
 
-  // ---- outliers of this strip: CSR entries [rp[0], rp[TR]) ------------------
-  {
-    const int l16 = tid & 15, g16 = tid >> 4, ngroups = nthreads >> 4;
-    for (int r = g16; r < TR; r += ngroups) {
-      const int a = rp[r], b = rp[r + 1];
-      float p = 0.f;
-      if (b - a <= LIGHT_MAX)
-        for (int e = a + l16; e < b; e += 16) p = fmaf(h2f(A.val[e]), h2f(xs[A.col[e]]), p);
-      p = row16_allreduce(p, lane);
-      if (l16 == 0) osum[r] = p;
-    }
-    __syncthreads();
-    for (int r = 0; r < TR; ++r) {           // workgroup-uniform
-      const int a = rp[r], b = rp[r + 1];
-      if (b - a > LIGHT_MAX) {
-        float p = 0.f;
-        for (int e = a + tid; e < b; e += nthreads) p = fmaf(h2f(A.val[e]), h2f(xs[A.col[e]]), p);
-        p = wave_allreduce(p, lane);
-        if (lane == 0) hred[wave] = p;
-        __syncthreads();
-        if (tid == 0) { float s = 0.f; for (int w = 0; w < nwaves; ++w) s += hred[w]; osum[r] = s; }
-        __syncthreads();
-      }
-    }
+  // ---- outlier products of the first round -> LDS ------------------------------
+  if (tid < first_round) {
+    float p[8];
+    chunk_products(xs, e_lo, e_hi, c_lo + tid, pc, pv, p);
+    store_products(prod, tid, p);
   }
 
-  // ---- dense partials: lanes -> rows, then waves -> workgroup ---------------
+  // ---- dense partials: lanes -> rows ---------------------------------------------
   if constexpr (AXIS == 1) {
 #pragma unroll
     for (int r = 0; r < TR; ++r) acc[r] = fmaf((float)(1 << W), acc[r], -csum);
@@ -266,11 +352,79 @@ gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restric
   int row;
   const float rsum = wave_reduce_rows<TR>(acc, lane, &row);
   if ((lane & ((64 / TR) - 1)) == 0) red[wave][row] = rsum;
+
+  // One barrier publishes products and partials and tells every thread whether
+  // the strip needs the slow path (more chunks than one round, or a long row).
+  const bool slow = __syncthreads_or((nchunks > first_round) || (rb - ra > LONG_ROW)) != 0;
+  const int base = 8 * c_lo;                 // CSR index of prod[0] in the first round
+  if (!slow) {
+    // 16 lanes per row: the row's products, plus one dense partial per wavefront
+    for (int r = g16; r < TR; r += ngroups) {
+      const int a = r == g16 ? ra : rpg[r], b = r == g16 ? rb : rpg[r + 1];
+      float s = strided16_sum(prod, a - base, b - base, l16);
+      if (l16 < nwaves) s += red[l16][r];
+      s = row16_allreduce(s, lane);
+      if (l16 == 0) {
+        const int64_t i = (int64_t)strip * TR + r;
+        if (y_dtype == SPQR_F32) reinterpret_cast<float*>(y)[i] = s;
+        else reinterpret_cast<uint16_t*>(y)[i] = f2h_rne(s);
+      }
+    }
+    return;
+  }
+
+  // ---- slow path: rounds of chunk_cap chunks (up to KR per thread, all loads of a
+  // round in flight together); long rows summed by all threads ----------------------
+  if (tid < TR) osum[tid] = 0.f;
+  for (int c0 = 0; c0 < nchunks; c0 += chunk_cap) {      // workgroup-uniform
+    const int c1 = min(nchunks, c0 + chunk_cap);
+    if (c0 > 0) __syncthreads();                         // previous round's products are consumed
+    u32x4 cc[KR], vv[KR];
+#pragma unroll
+    for (int k = 0; k < KR; ++k) {
+      const int slot = tid + k * nthreads, j = c0 + slot;
+      if (slot < chunk_cap && j < c1 && (c0 > 0 || k > 0)) { cc[k] = col8[c_lo + j]; vv[k] = val8[c_lo + j]; }
+    }
+#pragma unroll
+    for (int k = 0; k < KR; ++k) {
+      const int slot = tid + k * nthreads, j = c0 + slot;
+      if (slot < chunk_cap && j < c1 && (c0 > 0 || k > 0)) {
+        float p[8];
+        chunk_products(xs, e_lo, e_hi, c_lo + j, cc[k], vv[k], p);
+        store_products(prod, slot, p);
+      }
+    }
+    __syncthreads();
+    const int e0 = 8 * (c_lo + c0), e1 = 8 * (c_lo + c1);   // CSR range covered by this round
+    for (int r = g16; r < TR; r += ngroups) {
+      const int a = max(rpg[r], e0), b = min(rpg[r + 1], e1);
+      if (b > a && b - a <= LONG_ROW) {
+        float s = strided16_sum(prod, a - e0, b - e0, l16);
+        s = row16_allreduce(s, lane);
+        if (l16 == 0) osum[r] += s;
+      }
+    }
+    for (int r = 0; r < TR; ++r) {                       // workgroup-uniform
+      const int a = max(rpg[r], e0), b = min(rpg[r + 1], e1);
+      if (b - a <= LONG_ROW) continue;
+      float s = 0.f;
+      for (int i = a - e0 + tid; i < b - e0; i += 4 * nthreads) {
+        float v[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) v[k] = prod[min(i + k * nthreads, b - e0 - 1)];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) s += (i + k * nthreads < b - e0) ? v[k] : 0.f;
+      }
+      s = wave_allreduce(s, lane);
+      if (lane == 0) hred[wave] = s;
+      __syncthreads();
+      if (tid == 0) { float t = 0.f; for (int w = 0; w < nwaves; ++w) t += hred[w]; osum[r] += t; }
+    }
+  }
   __syncthreads();
   if (tid < TR) {
-    float s = 0.f;
+    float s = osum[tid];
     for (int w = 0; w < nwaves; ++w) s += red[w][tid];
-    s += osum[tid];
     const int64_t i = (int64_t)strip * TR + tid;
     if (y_dtype == SPQR_F32) reinterpret_cast<float*>(y)[i] = s;
     else reinterpret_cast<uint16_t*>(y)[i] = f2h_rne(s);
@@ -426,19 +580,38 @@ static inline int pick_waves(int nsteps, int max_waves) {
   return best;
 }
 
+// LDS plan of the fused kernel: x, then 32 bytes per outlier chunk of a round.
+// A round holds at least one chunk per thread (the common, single-barrier path)
+// and up to 1024 chunks (a full row of 8192 outliers) where x leaves room.
+// Returns 0 if x and one chunk per thread do not fit.
+constexpr int kLdsBudget = 60 * 1024;
+static inline int outlier_chunk_cap(int n, int nthreads) {
+  const int xbytes = (n * 2 + 15) & ~15;
+  const int room = (kLdsBudget - xbytes) / 32;
+  if (room < nthreads) return 0;
+  int want = nthreads > 1024 ? nthreads : 1024;
+  if (want > 4 * nthreads) want = 4 * nthreads;
+  return room < want ? room : want;
+}
+
 template <int W, int TR, int TC, int AXIS>
 static hipError_t launch_tile256(const DevMatrix& A, const uint16_t* x, void* y, int y_dtype,
                                  hipStream_t stream) {
   const int nsteps = (A.g.ntc + 63) / 64;
   const int nw = pick_waves(nsteps, WavesPerGroup<W>::MAX);
-  const size_t lds = ((size_t)A.g.n * 2 + 15) & ~(size_t)15;
+  const int cap = outlier_chunk_cap(A.g.n, 64 * nw);
+  const size_t lds = (((size_t)A.g.n * 2 + 15) & ~(size_t)15) + (size_t)32 * cap;
   hipLaunchKernelGGL((gemv_tile256_kernel<W, TR, TC, AXIS>), dim3(A.g.ntr), dim3(64 * nw), lds,
-                     stream, A, x, y, y_dtype);
+                     stream, A, x, y, y_dtype, cap);
   return hipGetLastError();
 }
 
 bool has_tuned_gemv(const Geometry& g) {
-  if ((int64_t)g.n * 2 + 16 > 60 * 1024) return false;      // x must fit the LDS staging buffer
+  {                                                         // x and one round of outlier products must fit in LDS
+    const int nsteps = (g.ntc + 63) / 64;
+    const int maxw = g.w_bits == 3 ? 16 : 8;
+    if (outlier_chunk_cap(g.n, 64 * pick_waves(nsteps, maxw)) == 0) return false;
+  }
   if (g.tile_rows * g.tile_cols != 256) return false;
   if (g.axis == 1) return (g.tile_rows == 16 && g.tile_cols == 16) || (g.tile_rows == 8 && g.tile_cols == 32);
   return (g.tile_rows == 16 && g.tile_cols == 16) || (g.tile_rows == 32 && g.tile_cols == 8);

@@ -122,16 +122,24 @@ def test_smallbatch_matches_oracle(P, w, b1, b2, axis, b):
 
 
 @pytest.mark.parametrize("structure,rate", [("none", 0.0), ("rows8cols4", 0.03), ("cols64", 0.08),
-                                            ("zipf", 0.02), ("uniform", 0.3)])
-@pytest.mark.parametrize("axis", [0, 1])
-def test_outlier_structures(P, structure, rate, axis):
-    # full rows (heavy path, > 512 entries), full columns, Zipf row counts, dense-ish uniform
-    f = make(3, 16, 16, axis, 8, 72, rate=rate, structure=structure)
+                                            ("zipf", 0.02), ("uniform", 0.3), ("uniform", 0.003),
+                                            ("uniform", 0.95), ("zipf", 0.2)])
+@pytest.mark.parametrize("w,b1,b2,axis", [(3, 16, 16, 0), (3, 16, 16, 1), (3, 8, 32, 1), (4, 8, 32, 0)])
+def test_outlier_structures(P, structure, rate, w, b1, b2, axis):
+    # full rows, full columns, Zipf row counts, nearly empty rows (chunks spanning
+    # several rows, empty rows) and strips with more entries than one round holds
+    tr, tc = synth.tile_shape(b1, b2, axis)
+    f = make(w, b1, b2, axis, 128 // tr, 1152 // tc, rate=rate, structure=structure)
     A = P.SpQRMatrix.from_logical(f)
     assert P.spqr_pack_check(A) == 0
     x = synth.make_x(f.n, 1, seed=(47,))
     y = P.spqr_gemv(A, dev(x[0])).cpu().numpy()
     assert rel_l2(y, orc.matvec(f, x)[0]) <= REL_L2
+    # the outlier part alone (dense part switched off through zero statistics)
+    f.s_s[:] = 0
+    y = P.spqr_gemv(P.SpQRMatrix.from_logical(f), dev(x[0])).cpu().numpy()
+    ref = orc.matvec_sparse_only(f, x)[0]
+    assert np.linalg.norm(y - ref) <= 1e-5 * max(np.linalg.norm(ref), 1e-3)
 
 
 @pytest.mark.parametrize("axis", [0, 1])
