@@ -42,6 +42,8 @@ def main():
     ap.add_argument("--group-axis", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also run three 64 MiB device copies (a kernel of known traffic, for scaling rocprofv3 counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
@@ -157,6 +159,13 @@ def main():
                               "compressed_MB": round(bytes_layer[li] / 1e6, 3),
                               "GBps": round(bytes_layer[li] / (us * 1e-6) / 1e9, 1),
                               "frac_of_hbm_peak": round(bytes_layer[li] / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}
+
+    if args.calibrate:
+        src = torch.empty(64 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
 
     cpu = None
     if not args.no_cpu_baseline:
