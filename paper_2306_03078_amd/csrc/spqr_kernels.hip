@@ -91,11 +91,7 @@ template <int W, int TR, int TC, int AXIS>
 __device__ __forceinline__ void load_tile(TileRegs<W, TR, TC, AXIS>& t, const uint8_t* blk,
                                           int L, int lane) {
   using T = TileRegs<W, TR, TC, AXIS>;
-#pragma unroll
-  for (int k = 0; k < T::KW; ++k) {
-    u32x4 v = *reinterpret_cast<const u32x4*>(blk + ((int64_t)k * L + lane) * 16);
-    t.c[4 * k] = v.x; t.c[4 * k + 1] = v.y; t.c[4 * k + 2] = v.z; t.c[4 * k + 3] = v.w;
-  }
+  // statistics first: the tile's work starts with them (loads complete in order)
   const uint8_t* sb = blk + (int64_t)16 * T::KW * L;
 #pragma unroll
   for (int k = 0; k < T::SWF; ++k) {
@@ -106,6 +102,11 @@ __device__ __forceinline__ void load_tile(TileRegs<W, TR, TC, AXIS>& t, const ui
 #pragma unroll
   for (int k = 0; k < T::SR; ++k)
     t.s[4 * T::SWF + k] = *reinterpret_cast<const uint32_t*>(rb + ((int64_t)k * L + lane) * 4);
+#pragma unroll
+  for (int k = 0; k < T::KW; ++k) {
+    u32x4 v = *reinterpret_cast<const u32x4*>(blk + ((int64_t)k * L + lane) * 16);
+    t.c[4 * k] = v.x; t.c[4 * k + 1] = v.y; t.c[4 * k + 2] = v.z; t.c[4 * k + 3] = v.w;
+  }
 }
 
 // One tile's contribution.  Codes enter the dot products as 1 + q/2^W and the
@@ -221,15 +222,15 @@ __device__ __forceinline__ void store_products(float* prod, int slot, const floa
   reinterpret_cast<f32x4*>(prod)[2 * slot + 1] = hi;
 }
 
-// Sum of prod[i] for i in [lo, hi) by the 16 lanes of a group, four reads in flight.
+// Sum of prod[i] for i in [lo, hi) by the 16 lanes of a group, eight reads in flight.
 __device__ __forceinline__ float strided16_sum(const float* prod, int lo, int hi, int l16) {
   float s = 0.f;
-  for (int i = lo + l16; i < hi; i += 64) {
-    float v[4];
+  for (int i = lo + l16; i < hi; i += 128) {
+    float v[8];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) v[k] = prod[min(i + 16 * k, hi - 1)];
+    for (int k = 0; k < 8; ++k) v[k] = prod[min(i + 16 * k, hi - 1)];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) s += (i + 16 * k < hi) ? v[k] : 0.f;
+    for (int k = 0; k < 8; ++k) s += (i + 16 * k < hi) ? v[k] : 0.f;
   }
   return s;
 }
@@ -239,7 +240,7 @@ __device__ __forceinline__ float strided16_sum(const float* prod, int lo, int hi
 // prefetch of the next step.
 template <int W> struct WavesPerGroup { static constexpr int MAX = W == 3 ? 16 : 8; };
 
-template <int W, int TR, int TC, int AXIS>
+template <int W, int TR, int TC, int AXIS, bool PERM>
 __global__ void __launch_bounds__(64 * WavesPerGroup<W>::MAX)
 gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restrict__ y, int y_dtype,
                     int chunk_cap) {
@@ -250,7 +251,7 @@ gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restric
   constexpr int MAX_WAVES = 16;
   constexpr int XCH = 4;                     // 16-byte chunks of x a thread keeps in flight
   constexpr int KR = 4;                      // outlier chunks per thread and round on the slow path
-  constexpr int LONG_ROW = 1024;             // rows with more entries are summed by all threads
+  constexpr int LONG_ROW = 512;              // rows with more entries are summed by all threads
 
   // dynamic LDS: x | products of the outlier entries (8 floats per chunk)
   extern __shared__ __align__(16) uint8_t smem[];
@@ -260,7 +261,9 @@ gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restric
   float* prod = reinterpret_cast<float*>(smem + xbytes);
   __shared__ float red[MAX_WAVES][TR];
   __shared__ float osum[TR];
-  __shared__ float hred[MAX_WAVES];
+  __shared__ float hred[2][MAX_WAVES];
+  __shared__ float lred[TR][MAX_WAVES];
+  __shared__ int rp[TR + 1];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int nthreads = blockDim.x, nwaves = nthreads >> 6;
@@ -271,38 +274,42 @@ gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restric
   const int32_t* rpg = A.row_ptr + (int64_t)strip * TR;
 
   // ---- issue order: row pointers and x first (small, mostly cache hits), then
-  // the first tile, so that staging x never waits for the big loads -------------
+  // the first tile.  Everything up to the barrier is straight-line code with
+  // clamped indices instead of branches, so that the wait before staging x
+  // covers the x loads only and never the big tile loads behind them. ------------
   const int e_lo = rpg[0], e_hi = rpg[TR];   // uniform: scalar loads
-  int ra = 0, rb = 0;                        // CSR range of the row this group of 16 lanes sums
-  if (g16 < TR) { ra = rpg[g16]; rb = rpg[g16 + 1]; }
+  const int rp_mine = rpg[min(tid, TR)];     // thread r <= TR carries row pointer r into LDS
   const int nvec = n >> 3;                   // 16-byte chunks of x
   u32x4 xr[XCH];
-  if (A.perm == nullptr) {
+  if constexpr (!PERM) {
 #pragma unroll
-    for (int k = 0; k < XCH; ++k) {
-      const int i = tid + k * nthreads;
-      if (i < nvec) xr[k] = reinterpret_cast<const u32x4*>(x)[i];
-    }
+    for (int k = 0; k < XCH; ++k)
+      xr[k] = reinterpret_cast<const u32x4*>(x)[min(tid + k * nthreads, nvec - 1)];
   }
+  __builtin_amdgcn_sched_barrier(0);         // keep the x loads ahead of the tile loads
 
   T t0, t1;
   auto issue = [&](T& t, int st) -> bool {
     if (st < nsteps) {
       const int L = min(64, ntc - 64 * st);
-      if (lane < L) { load_tile(t, strip_base + (int64_t)64 * st * TILE_BYTES, L, lane); return true; }
+      load_tile(t, strip_base + (int64_t)64 * st * TILE_BYTES, L, min(lane, L - 1));
+      return lane < L;
     }
     return false;
   };
-  int step = wave;
-  bool h0 = issue(t0, step), h1 = false;
+  int step = wave;                           // wave < nwaves <= nsteps: the first step always exists
+  bool h1 = false;
+  const int L0 = min(64, ntc - 64 * step);
+  load_tile(t0, strip_base + (int64_t)64 * step * TILE_BYTES, L0, min(lane, L0 - 1));
+  bool h0 = lane < L0;
+  __builtin_amdgcn_sched_barrier(0);
+  rp[min(tid, TR)] = rp_mine;                // clamped duplicates store the same value again
 
-  if (A.perm == nullptr) {
+  if constexpr (!PERM) {
     u32x4* dst = reinterpret_cast<u32x4*>(xs);
 #pragma unroll
-    for (int k = 0; k < XCH; ++k) {
-      const int i = tid + k * nthreads;
-      if (i < nvec) dst[i] = xr[k];
-    }
+    for (int k = 0; k < XCH; ++k)            // clamped duplicates store the same value again
+      dst[min(tid + k * nthreads, nvec - 1)] = xr[k];
     for (int i = tid + XCH * nthreads; i < nvec; i += nthreads) dst[i] = reinterpret_cast<const u32x4*>(x)[i];
     for (int j = (nvec << 3) + tid; j < n; j += nthreads) xs[j] = x[j];
   } else {
@@ -327,14 +334,39 @@ gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restric
   const PairConsts kc = make_pair_consts<W>();
   const PairConsts k3 = make_pair_consts<3>();
   const uint32_t* xs32 = reinterpret_cast<const uint32_t*>(xs);
+  // A strip with more outlier chunks than threads fetches this thread's further
+  // chunks of the first round (slots tid + k*nthreads, k >= 1) into the tile
+  // buffer that is idle during the wavefront's last dense step.
+  static_assert(8 * (KR - 1) <= 4 * T::KW, "extra chunks must fit the idle tile buffer");
+  const bool heavy = nchunks > nthreads;     // workgroup-uniform
+  bool extra_in_t1 = false;
+  auto fetch_extra = [&](T& buf) {
+#pragma unroll
+    for (int k = 1; k < KR; ++k) {
+      const int slot = tid + k * nthreads;
+      if (slot < chunk_cap && slot < nchunks) {
+        const u32x4 c8 = col8[c_lo + slot], v8 = val8[c_lo + slot];
+        uint32_t* d = buf.c + 8 * (k - 1);
+        d[0] = c8.x; d[1] = c8.y; d[2] = c8.z; d[3] = c8.w;
+        d[4] = v8.x; d[5] = v8.y; d[6] = v8.z; d[7] = v8.w;
+      }
+    }
+  };
   while (step < nsteps) {                    // wave-uniform; two steps per trip, registers ping-pong
-    h1 = issue(t1, step + nwaves);
+    if (step + nwaves < nsteps) h1 = issue(t1, step + nwaves);
+    else if (heavy) { fetch_extra(t1); extra_in_t1 = true; }
     if (h0) tile_fma<W, TR, TC, AXIS>(t0, xs32 + (64 * step + lane) * (TC / 2), acc, csum, kc, k3);
     step += nwaves;
     if (step >= nsteps) break;
-    h0 = issue(t0, step + nwaves);
+    if (step + nwaves < nsteps) h0 = issue(t0, step + nwaves);
+    else if (heavy) { fetch_extra(t0); extra_in_t1 = false; }
     if (h1) tile_fma<W, TR, TC, AXIS>(t1, xs32 + (64 * step + lane) * (TC / 2), acc, csum, kc, k3);
     step += nwaves;
+  }
+  uint32_t ex[8 * (KR - 1)];                 // the prefetched extra chunks, out of the tile buffers
+  if (heavy) {
+#pragma unroll
+    for (int i = 0; i < 8 * (KR - 1); ++i) ex[i] = extra_in_t1 ? t1.c[i] : t0.c[i];
   }
 
   // ---- outlier products of the first round -> LDS ------------------------------
@@ -342,6 +374,19 @@ gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restric
     float p[8];
     chunk_products(xs, e_lo, e_hi, c_lo + tid, pc, pv, p);
     store_products(prod, tid, p);
+  }
+  if (heavy) {                               // the prefetched further chunks of the first round
+#pragma unroll
+    for (int k = 1; k < KR; ++k) {
+      const int slot = tid + k * nthreads;
+      if (slot < chunk_cap && slot < nchunks) {
+        const uint32_t* d = ex + 8 * (k - 1);
+        const u32x4 c8 = {d[0], d[1], d[2], d[3]}, v8 = {d[4], d[5], d[6], d[7]};
+        float p[8];
+        chunk_products(xs, e_lo, e_hi, c_lo + slot, c8, v8, p);
+        store_products(prod, slot, p);
+      }
+    }
   }
 
   // ---- dense partials: lanes -> rows ---------------------------------------------
@@ -354,14 +399,36 @@ gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restric
   if ((lane & ((64 / TR) - 1)) == 0) red[wave][row] = rsum;
 
   // One barrier publishes products and partials and tells every thread whether
-  // the strip needs the slow path (more chunks than one round, or a long row).
-  const bool slow = __syncthreads_or((nchunks > first_round) || (rb - ra > LONG_ROW)) != 0;
+  // some row of the strip is too long for 16 lanes.  Only a strip with more chunks
+  // than one round holds needs the slow path.
+  const int any_long = __syncthreads_or(tid < TR && rp[min(tid, TR - 1) + 1] - rp[min(tid, TR - 1)] > LONG_ROW);
+  const bool slow = nchunks > chunk_cap;     // workgroup-uniform
   const int base = 8 * c_lo;                 // CSR index of prod[0] in the first round
   if (!slow) {
+    if (any_long) {
+      // long rows: every thread adds a strided share, one partial per wavefront and row
+      for (int r = 0; r < TR; ++r) {         // workgroup-uniform
+        if (rp[r + 1] - rp[r] <= LONG_ROW) continue;
+        const int lo = rp[r] - base, hi = rp[r + 1] - base;
+        float s = 0.f;
+        for (int i = lo + tid; i < hi; i += 4 * nthreads) {
+          float v[4];
+#pragma unroll
+          for (int k = 0; k < 4; ++k) v[k] = prod[min(i + k * nthreads, hi - 1)];
+#pragma unroll
+          for (int k = 0; k < 4; ++k) s += (i + k * nthreads < hi) ? v[k] : 0.f;
+        }
+        s = wave_allreduce(s, lane);
+        if (lane == 0) lred[r][wave] = s;
+      }
+      __syncthreads();
+    }
     // 16 lanes per row: the row's products, plus one dense partial per wavefront
     for (int r = g16; r < TR; r += ngroups) {
-      const int a = r == g16 ? ra : rpg[r], b = r == g16 ? rb : rpg[r + 1];
-      float s = strided16_sum(prod, a - base, b - base, l16);
+      const int a = rp[r], b = rp[r + 1];
+      float s;
+      if (b - a > LONG_ROW) s = l16 < nwaves ? lred[r][l16] : 0.f;
+      else s = strided16_sum(prod, a - base, b - base, l16);
       if (l16 < nwaves) s += red[l16][r];
       s = row16_allreduce(s, lane);
       if (l16 == 0) {
@@ -376,22 +443,25 @@ gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restric
   // ---- slow path: rounds of chunk_cap chunks (up to KR per thread, all loads of a
   // round in flight together); long rows summed by all threads ----------------------
   if (tid < TR) osum[tid] = 0.f;
+  int par = 0;
   for (int c0 = 0; c0 < nchunks; c0 += chunk_cap) {      // workgroup-uniform
     const int c1 = min(nchunks, c0 + chunk_cap);
     if (c0 > 0) __syncthreads();                         // previous round's products are consumed
-    u32x4 cc[KR], vv[KR];
+    if (c0 > 0) {                                        // round 0 is already in LDS
+      u32x4 cc[KR], vv[KR];
 #pragma unroll
-    for (int k = 0; k < KR; ++k) {
-      const int slot = tid + k * nthreads, j = c0 + slot;
-      if (slot < chunk_cap && j < c1 && (c0 > 0 || k > 0)) { cc[k] = col8[c_lo + j]; vv[k] = val8[c_lo + j]; }
-    }
+      for (int k = 0; k < KR; ++k) {
+        const int slot = tid + k * nthreads, j = c0 + slot;
+        if (slot < chunk_cap && j < c1) { cc[k] = col8[c_lo + j]; vv[k] = val8[c_lo + j]; }
+      }
 #pragma unroll
-    for (int k = 0; k < KR; ++k) {
-      const int slot = tid + k * nthreads, j = c0 + slot;
-      if (slot < chunk_cap && j < c1 && (c0 > 0 || k > 0)) {
-        float p[8];
-        chunk_products(xs, e_lo, e_hi, c_lo + j, cc[k], vv[k], p);
-        store_products(prod, slot, p);
+      for (int k = 0; k < KR; ++k) {
+        const int slot = tid + k * nthreads, j = c0 + slot;
+        if (slot < chunk_cap && j < c1) {
+          float p[8];
+          chunk_products(xs, e_lo, e_hi, c_lo + j, cc[k], vv[k], p);
+          store_products(prod, slot, p);
+        }
       }
     }
     __syncthreads();
@@ -416,9 +486,10 @@ gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restric
         for (int k = 0; k < 4; ++k) s += (i + k * nthreads < b - e0) ? v[k] : 0.f;
       }
       s = wave_allreduce(s, lane);
-      if (lane == 0) hred[wave] = s;
+      if (lane == 0) hred[par][wave] = s;
       __syncthreads();
-      if (tid == 0) { float t = 0.f; for (int w = 0; w < nwaves; ++w) t += hred[w]; osum[r] += t; }
+      if (tid == 0) { float t = 0.f; for (int w = 0; w < nwaves; ++w) t += hred[par][w]; osum[r] += t; }
+      par ^= 1;                                          // the next long row must not overwrite what thread 0 reads
     }
   }
   __syncthreads();
@@ -582,16 +653,19 @@ static inline int pick_waves(int nsteps, int max_waves) {
 
 // LDS plan of the fused kernel: x, then 32 bytes per outlier chunk of a round.
 // A round holds at least one chunk per thread (the common, single-barrier path)
-// and up to 1024 chunks (a full row of 8192 outliers) where x leaves room.
+// and up to four.  The budget is the CU's 160 KB divided by the number of
+// workgroups its 16 wavefront slots can hold, so LDS never lowers occupancy.
 // Returns 0 if x and one chunk per thread do not fit.
-constexpr int kLdsBudget = 60 * 1024;
-static inline int outlier_chunk_cap(int n, int nthreads) {
+static inline int lds_budget(int nwaves) {
+  int groups = 16 / nwaves; if (groups < 1) groups = 1;
+  return 160 * 1024 / groups - 8192;         // static arrays and allocation granularity
+}
+static inline int outlier_chunk_cap(int n, int nwaves) {
+  const int nthreads = 64 * nwaves;
   const int xbytes = (n * 2 + 15) & ~15;
-  const int room = (kLdsBudget - xbytes) / 32;
+  const int room = (lds_budget(nwaves) - xbytes) / 32;
   if (room < nthreads) return 0;
-  int want = nthreads > 1024 ? nthreads : 1024;
-  if (want > 4 * nthreads) want = 4 * nthreads;
-  return room < want ? room : want;
+  return room < 4 * nthreads ? room : 4 * nthreads;
 }
 
 template <int W, int TR, int TC, int AXIS>
@@ -599,10 +673,26 @@ static hipError_t launch_tile256(const DevMatrix& A, const uint16_t* x, void* y,
                                  hipStream_t stream) {
   const int nsteps = (A.g.ntc + 63) / 64;
   const int nw = pick_waves(nsteps, WavesPerGroup<W>::MAX);
-  const int cap = outlier_chunk_cap(A.g.n, 64 * nw);
+  const int cap = outlier_chunk_cap(A.g.n, nw);
   const size_t lds = (((size_t)A.g.n * 2 + 15) & ~(size_t)15) + (size_t)32 * cap;
-  hipLaunchKernelGGL((gemv_tile256_kernel<W, TR, TC, AXIS>), dim3(A.g.ntr), dim3(64 * nw), lds,
-                     stream, A, x, y, y_dtype, cap);
+  // more than 64 KB of dynamic LDS needs an explicit opt-in, once per kernel
+  static bool opted[2] = {false, false};
+  const int pi = A.perm ? 1 : 0;
+  if (!opted[pi]) {
+    hipError_t e = A.perm
+        ? hipFuncSetAttribute(reinterpret_cast<const void*>(&gemv_tile256_kernel<W, TR, TC, AXIS, true>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024)
+        : hipFuncSetAttribute(reinterpret_cast<const void*>(&gemv_tile256_kernel<W, TR, TC, AXIS, false>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024);
+    if (e != hipSuccess) return e;
+    opted[pi] = true;
+  }
+  if (A.perm)
+    hipLaunchKernelGGL((gemv_tile256_kernel<W, TR, TC, AXIS, true>), dim3(A.g.ntr), dim3(64 * nw), lds,
+                       stream, A, x, y, y_dtype, cap);
+  else
+    hipLaunchKernelGGL((gemv_tile256_kernel<W, TR, TC, AXIS, false>), dim3(A.g.ntr), dim3(64 * nw), lds,
+                       stream, A, x, y, y_dtype, cap);
   return hipGetLastError();
 }
 
@@ -610,7 +700,7 @@ bool has_tuned_gemv(const Geometry& g) {
   {                                                         // x and one round of outlier products must fit in LDS
     const int nsteps = (g.ntc + 63) / 64;
     const int maxw = g.w_bits == 3 ? 16 : 8;
-    if (outlier_chunk_cap(g.n, 64 * pick_waves(nsteps, maxw)) == 0) return false;
+    if (outlier_chunk_cap(g.n, pick_waves(nsteps, maxw)) == 0) return false;
   }
   if (g.tile_rows * g.tile_cols != 256) return false;
   if (g.axis == 1) return (g.tile_rows == 16 && g.tile_cols == 16) || (g.tile_rows == 8 && g.tile_cols == 32);
