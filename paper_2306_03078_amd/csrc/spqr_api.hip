@@ -69,14 +69,8 @@ extern "C" int spqr_gemm_smallbatch(const spqr_matrix_t* A, const uint16_t* X_f1
   if (y_dtype != SPQR_F32 && y_dtype != SPQR_F16) return SPQR_ERR_DTYPE;
   if (reinterpret_cast<uintptr_t>(X_f16) % 16 != 0) return SPQR_ERR_ALIGN;
   if (reinterpret_cast<uintptr_t>(Y) % (y_dtype == SPQR_F32 ? 4 : 2) != 0) return SPQR_ERR_ALIGN;
-  const size_t ysz = y_dtype == SPQR_F32 ? 4 : 2;
-  for (int k = 0; k < b; ++k) {
-    hipError_t e = spqr::launch_gemv(D, X_f16 + (size_t)k * D.g.n,
-                                     static_cast<uint8_t*>(Y) + (size_t)k * D.g.m * ysz, y_dtype,
-                                     static_cast<hipStream_t>(stream), force_generic());
-    if (e != hipSuccess) return SPQR_ERR_HIP;
-  }
-  return SPQR_OK;
+  hipError_t e = spqr::launch_gemm(D, X_f16, b, Y, y_dtype, static_cast<hipStream_t>(stream), force_generic());
+  return e == hipSuccess ? SPQR_OK : SPQR_ERR_HIP;
 }
 
 extern "C" int spqr_gemv(const spqr_matrix_t* A, const uint16_t* x_f16, void* y, int y_dtype,

@@ -9,6 +9,8 @@ namespace spqr {
 bool has_tuned_gemv(const Geometry& g);
 hipError_t launch_gemv(const DevMatrix& A, const uint16_t* x, void* y, int y_dtype,
                        hipStream_t stream, bool force_generic);
+hipError_t launch_gemm(const DevMatrix& A, const uint16_t* X, int b, void* Y, int y_dtype,
+                       hipStream_t stream, bool force_generic);
 hipError_t launch_dequant(const DevMatrix& A, int what, void* out, hipStream_t stream);
 hipError_t run_checks(const DevMatrix& A, bool csr, bool finite, bool perm, int host_words[3],
                       hipStream_t stream);

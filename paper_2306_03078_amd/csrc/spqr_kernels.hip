@@ -109,17 +109,19 @@ __device__ __forceinline__ void load_tile(TileRegs<W, TR, TC, AXIS>& t, const ui
   }
 }
 
-// One tile's contribution.  Codes enter the dot products as 1 + q/2^W and the
-// statistic codes as 1 + s_q/8, 1 + z_q/8 (exact binary16 values); the offsets
-// are removed with per-tile sums.  acc[r] accumulates, per output row r:
-//   AXIS 1: sum_j (1 + q_rj/2^W) * u_j  with u_j = fp16(s_hat_j * x_j); csum
+// One tile's contribution for NB activation vectors (LDS rows of `xstride`
+// dwords).  Codes enter the dot products as 1 + q/2^W and the statistic codes as
+// 1 + s_q/8, 1 + z_q/8 (exact binary16 values); the offsets are removed with
+// per-tile sums.  acc[b][r] accumulates, per output row r and vector b:
+//   AXIS 1: sum_j (1 + q_rj/2^W) * u_j  with u_j = fp16(s_hat_j * x_j); csum[b]
 //           accumulates sum_j (2^W + z_hat_j) * u_j, so y_r = 2^W*acc[r] - csum.
 //   AXIS 0: s_hat_r * (2^W * sum_j (1 + q_rj/2^W) x_j - (2^W + z_hat_r) * sum_j x_j).
-template <int W, int TR, int TC, int AXIS>
+// A pair is extracted once and used by all NB vectors.
+template <int W, int TR, int TC, int AXIS, int NB>
 __device__ __forceinline__ void tile_fma(const TileRegs<W, TR, TC, AXIS>& t,
-                                         const uint32_t* xpair /* TC/2 dwords in LDS */,
-                                         float (&acc)[TR], float& csum, const PairConsts& k,
-                                         const PairConsts& k3) {
+                                         const uint32_t* xpair /* TC/2 dwords in LDS, vector 0 */,
+                                         int xstride, float (&acc)[NB][TR], float (&csum)[NB],
+                                         const PairConsts& k, const PairConsts& k3) {
   using T = TileRegs<W, TR, TC, AXIS>;
   constexpr int PPR = TC / 2;
   constexpr float SCALE = (float)(1 << W);
@@ -130,42 +132,62 @@ __device__ __forceinline__ void tile_fma(const TileRegs<W, TR, TC, AXIS>& t,
   // s_hat = s_s*(s_q - z_s) = c1*(1 + s_q/8) + c2
   const float c1 = 8.f * s_s, c2 = -s_s * z_s - c1;
 
-  uint32_t xp[PPR];
+  uint32_t xp[NB][PPR];
 #pragma unroll
-  for (int p = 0; p < PPR; p += 4) {
-    u32x4 v = *reinterpret_cast<const u32x4*>(xpair + p);
-    xp[p] = v.x; xp[p + 1] = v.y; xp[p + 2] = v.z; xp[p + 3] = v.w;
+  for (int bi = 0; bi < NB; ++bi) {
+#pragma unroll
+    for (int p = 0; p < PPR; p += 4) {
+      u32x4 v = *reinterpret_cast<const u32x4*>(xpair + bi * xstride + p);
+      xp[bi][p] = v.x; xp[bi][p + 1] = v.y; xp[bi][p + 2] = v.z; xp[bi][p + 3] = v.w;
+    }
   }
 
   if constexpr (AXIS == 1) {
-    uint32_t up[PPR];
-    float U = 0.f, Zd = 0.f;
+    float U[NB], Zd[NB];
+#pragma unroll
+    for (int bi = 0; bi < NB; ++bi) { U[bi] = 0.f; Zd[bi] = 0.f; }
 #pragma unroll
     for (int p = 0; p < PPR; ++p) {
-      const half2_t xv = as_half2(xp[p]);
       const half2_t sq = as_half2(pair_f16<3>(t.s, p, k3));
       const half2_t zq = as_half2(pair_f16<3>(t.s, T::B2 / 2 + p, k3));
-      half2_t u;
-      u.x = (_Float16)(fmaf((float)sq.x, c1, c2) * (float)xv.x);
-      u.y = (_Float16)(fmaf((float)sq.y, c1, c2) * (float)xv.y);
-      up[p] = __builtin_bit_cast(uint32_t, u);
-      U = __builtin_amdgcn_fdot2(u, ones, U, false);
-      Zd = __builtin_amdgcn_fdot2(u, zq, Zd, false);
+      const float s0 = fmaf((float)sq.x, c1, c2), s1 = fmaf((float)sq.y, c1, c2);
+#pragma unroll
+      for (int bi = 0; bi < NB; ++bi) {
+        const half2_t xv = as_half2(xp[bi][p]);
+        half2_t u;
+        u.x = (_Float16)(s0 * (float)xv.x);
+        u.y = (_Float16)(s1 * (float)xv.y);
+        xp[bi][p] = __builtin_bit_cast(uint32_t, u);   // x is not needed any more: keep u in its place
+        U[bi] = __builtin_amdgcn_fdot2(u, ones, U[bi], false);
+        Zd[bi] = __builtin_amdgcn_fdot2(u, zq, Zd[bi], false);
+      }
     }
     // sum_j (2^W + z_hat_j) u_j with z_hat_j = s_z*(z_q - z_z), sum_j z_q u_j = 8*(Zd - U)
-    csum = fmaf(SCALE - s_z * z_z - 8.f * s_z, U, fmaf(8.f * s_z, Zd, csum));
+#pragma unroll
+    for (int bi = 0; bi < NB; ++bi)
+      csum[bi] = fmaf(SCALE - s_z * z_z - 8.f * s_z, U[bi], fmaf(8.f * s_z, Zd[bi], csum[bi]));
 #pragma unroll
     for (int r = 0; r < TR; ++r) {
-      float d = acc[r];
+      float d[NB];
 #pragma unroll
-      for (int p = 0; p < PPR; ++p)
-        d = __builtin_amdgcn_fdot2(as_half2(pair_f16<W>(t.c, r * PPR + p, k)), as_half2(up[p]), d, false);
-      acc[r] = d;
+      for (int bi = 0; bi < NB; ++bi) d[bi] = acc[bi][r];
+#pragma unroll
+      for (int p = 0; p < PPR; ++p) {
+        const half2_t q2 = as_half2(pair_f16<W>(t.c, r * PPR + p, k));
+#pragma unroll
+        for (int bi = 0; bi < NB; ++bi) d[bi] = __builtin_amdgcn_fdot2(q2, as_half2(xp[bi][p]), d[bi], false);
+      }
+#pragma unroll
+      for (int bi = 0; bi < NB; ++bi) acc[bi][r] = d[bi];
     }
   } else {
-    float X = 0.f;
+    float X[NB];
 #pragma unroll
-    for (int p = 0; p < PPR; ++p) X = __builtin_amdgcn_fdot2(as_half2(xp[p]), ones, X, false);
+    for (int bi = 0; bi < NB; ++bi) {
+      X[bi] = 0.f;
+#pragma unroll
+      for (int p = 0; p < PPR; ++p) X[bi] = __builtin_amdgcn_fdot2(as_half2(xp[bi][p]), ones, X[bi], false);
+    }
     // 2^W + z_hat = e1*(1 + z_q/8) + e2
     const float e1 = 8.f * s_z, e2 = SCALE - s_z * z_z - e1;
 #pragma unroll
@@ -175,13 +197,19 @@ __device__ __forceinline__ void tile_fma(const TileRegs<W, TR, TC, AXIS>& t,
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
         const int r = 2 * r2 + h;
-        float d = 0.f;
+        float d[NB];
 #pragma unroll
-        for (int p = 0; p < PPR; ++p)
-          d = __builtin_amdgcn_fdot2(as_half2(pair_f16<W>(t.c, r * PPR + p, k)), as_half2(xp[p]), d, false);
+        for (int bi = 0; bi < NB; ++bi) d[bi] = 0.f;
+#pragma unroll
+        for (int p = 0; p < PPR; ++p) {
+          const half2_t q2 = as_half2(pair_f16<W>(t.c, r * PPR + p, k));
+#pragma unroll
+          for (int bi = 0; bi < NB; ++bi) d[bi] = __builtin_amdgcn_fdot2(q2, as_half2(xp[bi][p]), d[bi], false);
+        }
         const float sh = fmaf((float)(h ? sq.y : sq.x), c1, c2);
         const float zo = fmaf((float)(h ? zq.y : zq.x), e1, e2);
-        acc[r] = fmaf(sh, fmaf(SCALE, d, -zo * X), acc[r]);
+#pragma unroll
+        for (int bi = 0; bi < NB; ++bi) acc[bi][r] = fmaf(sh, fmaf(SCALE, d[bi], -zo * X[bi]), acc[bi][r]);
       }
     }
   }
@@ -237,11 +265,14 @@ __device__ __forceinline__ float strided16_sum(const float* prod, int lo, int hi
 
 // Workgroup size limits: 16 wavefronts leave the compiler 128 registers per
 // lane, 8 wavefronts 256; a 4-bit tile needs 32 code registers, twice with the
-// prefetch of the next step.
-template <int W> struct WavesPerGroup { static constexpr int MAX = W == 3 ? 16 : 8; };
+// prefetch of the next step, and every further activation vector TR more
+// accumulators.
+template <int W, int NB> struct WavesPerGroup { static constexpr int MAX = (W == 3 && NB == 1) ? 16 : 8; };
 
-template <int W, int TR, int TC, int AXIS, bool PERM>
-__global__ void __launch_bounds__(64 * WavesPerGroup<W>::MAX)
+// NB activation vectors per launch: X holds NB rows of n binary16 values (row
+// stride n), Y NB rows of m outputs (row stride m).  NB = 1 is the GEMV.
+template <int W, int TR, int TC, int AXIS, bool PERM, int NB>
+__global__ void __launch_bounds__((64 * WavesPerGroup<W, NB>::MAX))
 gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restrict__ y, int y_dtype,
                     int chunk_cap) {
   using T = TileRegs<W, TR, TC, AXIS>;
@@ -253,16 +284,18 @@ gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restric
   constexpr int KR = 4;                      // outlier chunks per thread and round on the slow path
   constexpr int LONG_ROW = 512;              // rows with more entries are summed by all threads
 
-  // dynamic LDS: x | products of the outlier entries (8 floats per chunk)
+  // dynamic LDS: the NB x vectors | products of the outlier entries (8 floats per
+  // chunk and vector)
   extern __shared__ __align__(16) uint8_t smem[];
   uint16_t* xs = reinterpret_cast<uint16_t*>(smem);
-  const int n = A.g.n, ntc = A.g.ntc;
-  const int xbytes = (n * 2 + 15) & ~15;
+  const int n = A.g.n, ntc = A.g.ntc, m = A.g.m;
+  const int xbytes = (NB * n * 2 + 15) & ~15;
   float* prod = reinterpret_cast<float*>(smem + xbytes);
-  __shared__ float red[MAX_WAVES][TR];
-  __shared__ float osum[TR];
+  const int pstride = 8 * chunk_cap;         // floats of products per vector
+  __shared__ float red[MAX_WAVES][NB][TR];
+  __shared__ float osum[NB][TR];
   __shared__ float hred[2][MAX_WAVES];
-  __shared__ float lred[TR][MAX_WAVES];
+  __shared__ float lred[NB][TR][MAX_WAVES];
   __shared__ int rp[TR + 1];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -279,7 +312,7 @@ gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restric
   // covers the x loads only and never the big tile loads behind them. ------------
   const int e_lo = rpg[0], e_hi = rpg[TR];   // uniform: scalar loads
   const int rp_mine = rpg[min(tid, TR)];     // thread r <= TR carries row pointer r into LDS
-  const int nvec = n >> 3;                   // 16-byte chunks of x
+  const int nvec = (NB * n) >> 3;            // 16-byte chunks of the NB contiguous x vectors
   u32x4 xr[XCH];
   if constexpr (!PERM) {
 #pragma unroll
@@ -311,9 +344,9 @@ gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restric
     for (int k = 0; k < XCH; ++k)            // clamped duplicates store the same value again
       dst[min(tid + k * nthreads, nvec - 1)] = xr[k];
     for (int i = tid + XCH * nthreads; i < nvec; i += nthreads) dst[i] = reinterpret_cast<const u32x4*>(x)[i];
-    for (int j = (nvec << 3) + tid; j < n; j += nthreads) xs[j] = x[j];
+    for (int j = (nvec << 3) + tid; j < NB * n; j += nthreads) xs[j] = x[j];
   } else {
-    for (int j = tid; j < n; j += nthreads) xs[j] = x[A.perm[j]];
+    for (int j = tid; j < NB * n; j += nthreads) xs[j] = x[(j / n) * n + A.perm[j % n]];
   }
 
   // ---- outliers: fetch this thread's chunk now, use it after the dense part -----
@@ -327,10 +360,13 @@ gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restric
   __syncthreads();                           // x is staged
 
   // ---- dense part -------------------------------------------------------------
-  float acc[TR];
+  float acc[NB][TR], csum[NB];
 #pragma unroll
-  for (int r = 0; r < TR; ++r) acc[r] = 0.f;
-  float csum = 0.f;
+  for (int bi = 0; bi < NB; ++bi) {
+    csum[bi] = 0.f;
+#pragma unroll
+    for (int r = 0; r < TR; ++r) acc[bi][r] = 0.f;
+  }
   const PairConsts kc = make_pair_consts<W>();
   const PairConsts k3 = make_pair_consts<3>();
   const uint32_t* xs32 = reinterpret_cast<const uint32_t*>(xs);
@@ -355,12 +391,12 @@ gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restric
   while (step < nsteps) {                    // wave-uniform; two steps per trip, registers ping-pong
     if (step + nwaves < nsteps) h1 = issue(t1, step + nwaves);
     else if (heavy) { fetch_extra(t1); extra_in_t1 = true; }
-    if (h0) tile_fma<W, TR, TC, AXIS>(t0, xs32 + (64 * step + lane) * (TC / 2), acc, csum, kc, k3);
+    if (h0) tile_fma<W, TR, TC, AXIS, NB>(t0, xs32 + (64 * step + lane) * (TC / 2), n >> 1, acc, csum, kc, k3);
     step += nwaves;
     if (step >= nsteps) break;
     if (step + nwaves < nsteps) h0 = issue(t0, step + nwaves);
     else if (heavy) { fetch_extra(t0); extra_in_t1 = false; }
-    if (h1) tile_fma<W, TR, TC, AXIS>(t1, xs32 + (64 * step + lane) * (TC / 2), acc, csum, kc, k3);
+    if (h1) tile_fma<W, TR, TC, AXIS, NB>(t1, xs32 + (64 * step + lane) * (TC / 2), n >> 1, acc, csum, kc, k3);
     step += nwaves;
   }
   uint32_t ex[8 * (KR - 1)];                 // the prefetched extra chunks, out of the tile buffers
@@ -371,9 +407,12 @@ gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restric
 
   // ---- outlier products of the first round -> LDS ------------------------------
   if (tid < first_round) {
-    float p[8];
-    chunk_products(xs, e_lo, e_hi, c_lo + tid, pc, pv, p);
-    store_products(prod, tid, p);
+#pragma unroll
+    for (int bi = 0; bi < NB; ++bi) {
+      float p[8];
+      chunk_products(xs + bi * n, e_lo, e_hi, c_lo + tid, pc, pv, p);
+      store_products(prod + bi * pstride, tid, p);
+    }
   }
   if (heavy) {                               // the prefetched further chunks of the first round
 #pragma unroll
@@ -382,21 +421,27 @@ gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restric
       if (slot < chunk_cap && slot < nchunks) {
         const uint32_t* d = ex + 8 * (k - 1);
         const u32x4 c8 = {d[0], d[1], d[2], d[3]}, v8 = {d[4], d[5], d[6], d[7]};
-        float p[8];
-        chunk_products(xs, e_lo, e_hi, c_lo + slot, c8, v8, p);
-        store_products(prod, slot, p);
+#pragma unroll
+        for (int bi = 0; bi < NB; ++bi) {
+          float p[8];
+          chunk_products(xs + bi * n, e_lo, e_hi, c_lo + slot, c8, v8, p);
+          store_products(prod + bi * pstride, slot, p);
+        }
       }
     }
   }
 
   // ---- dense partials: lanes -> rows ---------------------------------------------
-  if constexpr (AXIS == 1) {
 #pragma unroll
-    for (int r = 0; r < TR; ++r) acc[r] = fmaf((float)(1 << W), acc[r], -csum);
+  for (int bi = 0; bi < NB; ++bi) {
+    if constexpr (AXIS == 1) {
+#pragma unroll
+      for (int r = 0; r < TR; ++r) acc[bi][r] = fmaf((float)(1 << W), acc[bi][r], -csum[bi]);
+    }
+    int row;
+    const float rsum = wave_reduce_rows<TR>(acc[bi], lane, &row);
+    if ((lane & ((64 / TR) - 1)) == 0) red[wave][bi][row] = rsum;
   }
-  int row;
-  const float rsum = wave_reduce_rows<TR>(acc, lane, &row);
-  if ((lane & ((64 / TR) - 1)) == 0) red[wave][row] = rsum;
 
   // One barrier publishes products and partials and tells every thread whether
   // some row of the strip is too long for 16 lanes.  Only a strip with more chunks
@@ -410,31 +455,38 @@ gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restric
       for (int r = 0; r < TR; ++r) {         // workgroup-uniform
         if (rp[r + 1] - rp[r] <= LONG_ROW) continue;
         const int lo = rp[r] - base, hi = rp[r + 1] - base;
-        float s = 0.f;
-        for (int i = lo + tid; i < hi; i += 4 * nthreads) {
-          float v[4];
 #pragma unroll
-          for (int k = 0; k < 4; ++k) v[k] = prod[min(i + k * nthreads, hi - 1)];
+        for (int bi = 0; bi < NB; ++bi) {
+          const float* pb = prod + bi * pstride;
+          float s = 0.f;
+          for (int i = lo + tid; i < hi; i += 4 * nthreads) {
+            float v[4];
 #pragma unroll
-          for (int k = 0; k < 4; ++k) s += (i + k * nthreads < hi) ? v[k] : 0.f;
+            for (int k = 0; k < 4; ++k) v[k] = pb[min(i + k * nthreads, hi - 1)];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) s += (i + k * nthreads < hi) ? v[k] : 0.f;
+          }
+          s = wave_allreduce(s, lane);
+          if (lane == 0) lred[bi][r][wave] = s;
         }
-        s = wave_allreduce(s, lane);
-        if (lane == 0) lred[r][wave] = s;
       }
       __syncthreads();
     }
     // 16 lanes per row: the row's products, plus one dense partial per wavefront
     for (int r = g16; r < TR; r += ngroups) {
       const int a = rp[r], b = rp[r + 1];
-      float s;
-      if (b - a > LONG_ROW) s = l16 < nwaves ? lred[r][l16] : 0.f;
-      else s = strided16_sum(prod, a - base, b - base, l16);
-      if (l16 < nwaves) s += red[l16][r];
-      s = row16_allreduce(s, lane);
-      if (l16 == 0) {
-        const int64_t i = (int64_t)strip * TR + r;
-        if (y_dtype == SPQR_F32) reinterpret_cast<float*>(y)[i] = s;
-        else reinterpret_cast<uint16_t*>(y)[i] = f2h_rne(s);
+#pragma unroll
+      for (int bi = 0; bi < NB; ++bi) {
+        float s;
+        if (b - a > LONG_ROW) s = l16 < nwaves ? lred[bi][r][l16] : 0.f;
+        else s = strided16_sum(prod + bi * pstride, a - base, b - base, l16);
+        if (l16 < nwaves) s += red[l16][bi][r];
+        s = row16_allreduce(s, lane);
+        if (l16 == 0) {
+          const int64_t i = (int64_t)bi * m + (int64_t)strip * TR + r;
+          if (y_dtype == SPQR_F32) reinterpret_cast<float*>(y)[i] = s;
+          else reinterpret_cast<uint16_t*>(y)[i] = f2h_rne(s);
+        }
       }
     }
     return;
@@ -442,7 +494,7 @@ gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restric
 
   // ---- slow path: rounds of chunk_cap chunks (up to KR per thread, all loads of a
   // round in flight together); long rows summed by all threads ----------------------
-  if (tid < TR) osum[tid] = 0.f;
+  if (tid < NB * TR) (&osum[0][0])[tid] = 0.f;
   int par = 0;
   for (int c0 = 0; c0 < nchunks; c0 += chunk_cap) {      // workgroup-uniform
     const int c1 = min(nchunks, c0 + chunk_cap);
@@ -458,9 +510,12 @@ gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restric
       for (int k = 0; k < KR; ++k) {
         const int slot = tid + k * nthreads, j = c0 + slot;
         if (slot < chunk_cap && j < c1) {
-          float p[8];
-          chunk_products(xs, e_lo, e_hi, c_lo + j, cc[k], vv[k], p);
-          store_products(prod, slot, p);
+#pragma unroll
+          for (int bi = 0; bi < NB; ++bi) {
+            float p[8];
+            chunk_products(xs + bi * n, e_lo, e_hi, c_lo + j, cc[k], vv[k], p);
+            store_products(prod + bi * pstride, slot, p);
+          }
         }
       }
     }
@@ -469,34 +524,41 @@ gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restric
     for (int r = g16; r < TR; r += ngroups) {
       const int a = max(rpg[r], e0), b = min(rpg[r + 1], e1);
       if (b > a && b - a <= LONG_ROW) {
-        float s = strided16_sum(prod, a - e0, b - e0, l16);
-        s = row16_allreduce(s, lane);
-        if (l16 == 0) osum[r] += s;
+#pragma unroll
+        for (int bi = 0; bi < NB; ++bi) {
+          float s = strided16_sum(prod + bi * pstride, a - e0, b - e0, l16);
+          s = row16_allreduce(s, lane);
+          if (l16 == 0) osum[bi][r] += s;
+        }
       }
     }
     for (int r = 0; r < TR; ++r) {                       // workgroup-uniform
       const int a = max(rpg[r], e0), b = min(rpg[r + 1], e1);
       if (b - a <= LONG_ROW) continue;
-      float s = 0.f;
-      for (int i = a - e0 + tid; i < b - e0; i += 4 * nthreads) {
-        float v[4];
+      for (int bi = 0; bi < NB; ++bi) {
+        const float* pb = prod + bi * pstride;
+        float s = 0.f;
+        for (int i = a - e0 + tid; i < b - e0; i += 4 * nthreads) {
+          float v[4];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) v[k] = prod[min(i + k * nthreads, b - e0 - 1)];
+          for (int k = 0; k < 4; ++k) v[k] = pb[min(i + k * nthreads, b - e0 - 1)];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) s += (i + k * nthreads < b - e0) ? v[k] : 0.f;
+          for (int k = 0; k < 4; ++k) s += (i + k * nthreads < b - e0) ? v[k] : 0.f;
+        }
+        s = wave_allreduce(s, lane);
+        if (lane == 0) hred[par][wave] = s;
+        __syncthreads();
+        if (tid == 0) { float t = 0.f; for (int w = 0; w < nwaves; ++w) t += hred[par][w]; osum[bi][r] += t; }
+        par ^= 1;                                        // the next sum must not overwrite what thread 0 reads
       }
-      s = wave_allreduce(s, lane);
-      if (lane == 0) hred[par][wave] = s;
-      __syncthreads();
-      if (tid == 0) { float t = 0.f; for (int w = 0; w < nwaves; ++w) t += hred[par][w]; osum[r] += t; }
-      par ^= 1;                                          // the next long row must not overwrite what thread 0 reads
     }
   }
   __syncthreads();
-  if (tid < TR) {
-    float s = osum[tid];
-    for (int w = 0; w < nwaves; ++w) s += red[w][tid];
-    const int64_t i = (int64_t)strip * TR + tid;
+  if (tid < NB * TR) {
+    const int bi = tid / TR, r = tid % TR;
+    float s = osum[bi][r];
+    for (int w = 0; w < nwaves; ++w) s += red[w][bi][r];
+    const int64_t i = (int64_t)bi * m + (int64_t)strip * TR + r;
     if (y_dtype == SPQR_F32) reinterpret_cast<float*>(y)[i] = s;
     else reinterpret_cast<uint16_t*>(y)[i] = f2h_rne(s);
   }
@@ -656,72 +718,114 @@ static inline int pick_waves(int nsteps, int max_waves) {
 // and up to four.  The budget is the CU's 160 KB divided by the number of
 // workgroups its 16 wavefront slots can hold, so LDS never lowers occupancy.
 // Returns 0 if x and one chunk per thread do not fit.
-static inline int lds_budget(int nwaves) {
-  int groups = 16 / nwaves; if (groups < 1) groups = 1;
-  return 160 * 1024 / groups - 8192;         // static arrays and allocation granularity
+// Static LDS of gemv_tile256_kernel (red, osum, hred, lred, rp), rounded up.
+static constexpr int static_lds_bytes(int tr, int nb) {
+  return ((16 * nb * tr + nb * tr + 32 + nb * tr * 16 + tr + 1) * 4 + 1023) & ~1023;
 }
-static inline int outlier_chunk_cap(int n, int nwaves) {
+static inline int lds_budget(int nwaves, int max_waves, int tr, int nb) {
+  int groups = max_waves / nwaves; if (groups < 1) groups = 1;
+  return 160 * 1024 / groups - static_lds_bytes(tr, nb) - 1024;   // dynamic bytes one workgroup may take
+}
+static inline int outlier_chunk_cap(int n, int nwaves, int nb, int max_waves, int tr) {
   const int nthreads = 64 * nwaves;
-  const int xbytes = (n * 2 + 15) & ~15;
-  const int room = (lds_budget(nwaves) - xbytes) / 32;
+  const int xbytes = (nb * n * 2 + 15) & ~15;
+  const int room = (lds_budget(nwaves, max_waves, tr, nb) - xbytes) / (32 * nb);
   if (room < nthreads) return 0;
   return room < 4 * nthreads ? room : 4 * nthreads;
 }
 
-template <int W, int TR, int TC, int AXIS>
+template <int W, int TR, int TC, int AXIS, int NB>
 static hipError_t launch_tile256(const DevMatrix& A, const uint16_t* x, void* y, int y_dtype,
                                  hipStream_t stream) {
+  constexpr int MAXW = WavesPerGroup<W, NB>::MAX;
   const int nsteps = (A.g.ntc + 63) / 64;
-  const int nw = pick_waves(nsteps, WavesPerGroup<W>::MAX);
-  const int cap = outlier_chunk_cap(A.g.n, nw);
-  const size_t lds = (((size_t)A.g.n * 2 + 15) & ~(size_t)15) + (size_t)32 * cap;
+  const int nw = pick_waves(nsteps, MAXW);
+  const int cap = outlier_chunk_cap(A.g.n, nw, NB, MAXW, TR);
+  if (cap == 0) return hipErrorInvalidValue;
+  const size_t lds = (((size_t)NB * A.g.n * 2 + 15) & ~(size_t)15) + (size_t)32 * NB * cap;
+  constexpr int MAX_DYNAMIC = 160 * 1024 - static_lds_bytes(TR, NB) - 1024;   // static + dynamic <= 160 KB
+  if (lds > (size_t)MAX_DYNAMIC) return hipErrorInvalidValue;
   // more than 64 KB of dynamic LDS needs an explicit opt-in, once per kernel
   static bool opted[2] = {false, false};
   const int pi = A.perm ? 1 : 0;
   if (!opted[pi]) {
     hipError_t e = A.perm
-        ? hipFuncSetAttribute(reinterpret_cast<const void*>(&gemv_tile256_kernel<W, TR, TC, AXIS, true>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024)
-        : hipFuncSetAttribute(reinterpret_cast<const void*>(&gemv_tile256_kernel<W, TR, TC, AXIS, false>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024);
+        ? hipFuncSetAttribute(reinterpret_cast<const void*>(&gemv_tile256_kernel<W, TR, TC, AXIS, true, NB>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, MAX_DYNAMIC)
+        : hipFuncSetAttribute(reinterpret_cast<const void*>(&gemv_tile256_kernel<W, TR, TC, AXIS, false, NB>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, MAX_DYNAMIC);
     if (e != hipSuccess) return e;
     opted[pi] = true;
   }
   if (A.perm)
-    hipLaunchKernelGGL((gemv_tile256_kernel<W, TR, TC, AXIS, true>), dim3(A.g.ntr), dim3(64 * nw), lds,
+    hipLaunchKernelGGL((gemv_tile256_kernel<W, TR, TC, AXIS, true, NB>), dim3(A.g.ntr), dim3(64 * nw), lds,
                        stream, A, x, y, y_dtype, cap);
   else
-    hipLaunchKernelGGL((gemv_tile256_kernel<W, TR, TC, AXIS, false>), dim3(A.g.ntr), dim3(64 * nw), lds,
+    hipLaunchKernelGGL((gemv_tile256_kernel<W, TR, TC, AXIS, false, NB>), dim3(A.g.ntr), dim3(64 * nw), lds,
                        stream, A, x, y, y_dtype, cap);
   return hipGetLastError();
 }
 
-bool has_tuned_gemv(const Geometry& g) {
-  {                                                         // x and one round of outlier products must fit in LDS
-    const int nsteps = (g.ntc + 63) / 64;
-    const int maxw = g.w_bits == 3 ? 16 : 8;
-    if (outlier_chunk_cap(g.n, pick_waves(nsteps, maxw)) == 0) return false;
+// Largest number of activation vectors (1, 2 or 4, at most `want`) one launch of
+// the tuned kernel can take for this geometry; 0 if there is no tuned kernel.
+int tuned_batch_width(const Geometry& g, int want) {
+  if (g.tile_rows * g.tile_cols != 256) return 0;
+  const bool shape_ok = g.axis == 1 ? ((g.tile_rows == 16 && g.tile_cols == 16) || (g.tile_rows == 8 && g.tile_cols == 32))
+                                    : ((g.tile_rows == 16 && g.tile_cols == 16) || (g.tile_rows == 32 && g.tile_cols == 8));
+  if (!shape_ok) return 0;
+  const int nsteps = (g.ntc + 63) / 64;
+  for (int nb = want >= 4 ? 4 : (want >= 2 ? 2 : 1); nb >= 1; nb >>= 1) {
+    const int maxw = (g.w_bits == 3 && nb == 1) ? 16 : 8;
+    if (outlier_chunk_cap(g.n, pick_waves(nsteps, maxw), nb, maxw, g.tile_rows) > 0) return nb;
   }
-  if (g.tile_rows * g.tile_cols != 256) return false;
-  if (g.axis == 1) return (g.tile_rows == 16 && g.tile_cols == 16) || (g.tile_rows == 8 && g.tile_cols == 32);
-  return (g.tile_rows == 16 && g.tile_cols == 16) || (g.tile_rows == 32 && g.tile_cols == 8);
+  return 0;
+}
+
+bool has_tuned_gemv(const Geometry& g) { return tuned_batch_width(g, 1) == 1; }
+
+template <int NB>
+static hipError_t launch_tuned(const DevMatrix& A, const uint16_t* x, void* y, int y_dtype, hipStream_t stream) {
+  const Geometry& g = A.g;
+#define SPQR_CASE(W_, TR_, TC_, AX_) \
+  if (g.w_bits == W_ && g.tile_rows == TR_ && g.tile_cols == TC_ && g.axis == AX_) \
+    return launch_tile256<W_, TR_, TC_, AX_, NB>(A, x, y, y_dtype, stream);
+  SPQR_CASE(3, 16, 16, 1) SPQR_CASE(4, 16, 16, 1) SPQR_CASE(3, 8, 32, 1) SPQR_CASE(4, 8, 32, 1)
+  SPQR_CASE(3, 16, 16, 0) SPQR_CASE(4, 16, 16, 0) SPQR_CASE(3, 32, 8, 0) SPQR_CASE(4, 32, 8, 0)
+#undef SPQR_CASE
+  return hipErrorInvalidValue;
+}
+
+// Y[b][m] = X[b][n] . W_hat^T.  The tuned kernel takes up to 4 activation vectors
+// per launch (weights stream once per launch); larger batches go in slices of 4.
+hipError_t launch_gemm(const DevMatrix& A, const uint16_t* X, int b, void* Y, int y_dtype,
+                       hipStream_t stream, bool force_generic) {
+  const Geometry& g = A.g;
+  const size_t ysz = y_dtype == SPQR_F32 ? 4 : 2;
+  int k = 0;
+  while (k < b) {
+    const uint16_t* xk = X + (size_t)k * g.n;
+    void* yk = static_cast<uint8_t*>(Y) + (size_t)k * g.m * ysz;
+    const int nb = force_generic ? 0 : tuned_batch_width(g, b - k);
+    hipError_t e;
+    int done = 1;
+    if (nb == 4) { e = launch_tuned<4>(A, xk, yk, y_dtype, stream); done = 4; }
+    else if (nb == 2) { e = launch_tuned<2>(A, xk, yk, y_dtype, stream); done = 2; }
+    else if (nb == 1) { e = launch_tuned<1>(A, xk, yk, y_dtype, stream); }
+    else {
+      const int rows_per_block = 4;
+      hipLaunchKernelGGL(gemv_generic_kernel, dim3((g.m + rows_per_block - 1) / rows_per_block),
+                         dim3(64 * rows_per_block), 0, stream, A, xk, yk, y_dtype);
+      e = hipGetLastError();
+    }
+    if (e != hipSuccess) return e;
+    k += done;
+  }
+  return hipSuccess;
 }
 
 hipError_t launch_gemv(const DevMatrix& A, const uint16_t* x, void* y, int y_dtype,
                        hipStream_t stream, bool force_generic) {
-  const Geometry& g = A.g;
-  if (!force_generic && has_tuned_gemv(g)) {
-#define SPQR_CASE(W_, TR_, TC_, AX_) \
-    if (g.w_bits == W_ && g.tile_rows == TR_ && g.tile_cols == TC_ && g.axis == AX_) \
-      return launch_tile256<W_, TR_, TC_, AX_>(A, x, y, y_dtype, stream);
-    SPQR_CASE(3, 16, 16, 1) SPQR_CASE(4, 16, 16, 1) SPQR_CASE(3, 8, 32, 1) SPQR_CASE(4, 8, 32, 1)
-    SPQR_CASE(3, 16, 16, 0) SPQR_CASE(4, 16, 16, 0) SPQR_CASE(3, 32, 8, 0) SPQR_CASE(4, 32, 8, 0)
-#undef SPQR_CASE
-  }
-  const int rows_per_block = 4;
-  hipLaunchKernelGGL(gemv_generic_kernel, dim3((g.m + rows_per_block - 1) / rows_per_block),
-                     dim3(64 * rows_per_block), 0, stream, A, x, y, y_dtype);
-  return hipGetLastError();
+  return launch_gemm(A, x, 1, y, y_dtype, stream, force_generic);
 }
 
 hipError_t launch_dequant(const DevMatrix& A, int what, void* out, hipStream_t stream) {
