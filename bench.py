@@ -33,6 +33,59 @@ def algorithmic_bytes(A, batch=1):
     return A.compressed_bytes() + 2 * A.n * batch + 4 * A.m * batch
 
 
+def time_layer(P, torch, A, X, copies, reps=6):
+    """Median-free simple timing: graph of one launch per weight copy, replayed `reps` times."""
+    pool = [A] + [A.clone() for _ in range(copies - 1)]
+    b = X.shape[0]
+    Y = torch.empty((b, A.m), dtype=torch.float32, device=X.device)
+    fn = (lambda M: P.spqr_gemv(M, X[0], out=Y[0])) if b == 1 else (lambda M: P.spqr_gemm_smallbatch(M, X, out=Y))
+    for M in pool:
+        fn(M)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for M in pool:
+            fn(M)
+    g.replay()
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        g.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / (reps * copies)
+
+
+def run_sweep(path, P, synth, torch, dev):
+    rows = []
+    for cfg in sorted(synth.CONFIGS):
+        seen = set()
+        for li, sp in enumerate(synth.config_layers(cfg)):
+            if (sp.m, sp.n) in seen:
+                continue
+            seen.add((sp.m, sp.n))
+            for axis in (1, 0):
+                f = synth.make_config_layer(cfg, li, group_axis=axis)
+                A = P.SpQRMatrix.from_logical(f, dev)
+                del f
+                copies = max(2, int(600e6 // A.compressed_bytes()) + 1)
+                for b in sp.batches:
+                    X = torch.from_numpy(synth.make_x(sp.n, b, seed=(cfg, li, b))).to(dev)
+                    us = time_layer(P, torch, A, X, copies)
+                    nbytes = algorithmic_bytes(A, b)
+                    rows.append({"config": cfg, "layer": sp.name, "m": sp.m, "n": sp.n, "w_bits": sp.w_bits,
+                                 "beta1": sp.beta1, "beta2": sp.beta2, "group_axis": axis, "batch": b,
+                                 "outliers": f"{sp.outlier_rate:g} {sp.outlier_structure}",
+                                 "compressed_MB": round(nbytes / 1e6, 2), "us": round(us, 2),
+                                 "GBps": round(nbytes / us / 1e3, 1),
+                                 "frac_of_hbm_peak": round(nbytes / us / 1e3 / HBM_PEAK_GBS, 4)})
+                del A
+                torch.cuda.empty_cache()
+    with open(path, "w") as fh:
+        json.dump(rows, fh, indent=1)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -42,6 +95,9 @@ def main():
     ap.add_argument("--group-axis", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
+    ap.add_argument("--sweep", metavar="PATH", default=None,
+                    help="also time every distinct layer of all five configurations (both group orientations, "
+                         "the batch sizes each configuration names) and write the table as JSON to PATH")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run three 64 MiB device copies (a kernel of known traffic, for scaling rocprofv3 counters)")
     args = ap.parse_args()
@@ -159,6 +215,9 @@ def main():
                               "compressed_MB": round(bytes_layer[li] / 1e6, 3),
                               "GBps": round(bytes_layer[li] / (us * 1e-6) / 1e9, 1),
                               "frac_of_hbm_peak": round(bytes_layer[li] / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}
+
+    if args.sweep:
+        run_sweep(args.sweep, P, synth, torch, dev)
 
     if args.calibrate:
         src = torch.empty(64 << 20, dtype=torch.uint8, device=dev).random_(0, 255)

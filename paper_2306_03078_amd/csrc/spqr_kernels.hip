@@ -13,6 +13,8 @@
 //   workgroup, so y is written once, without atomics, in a fixed order.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+
 #include "../../include/spqr.h"
 #include "spqr_device.h"
 #include "spqr_kernels.h"
@@ -702,67 +704,85 @@ __device__ int g_check_words[4];
 // ---------------------------------------------------------------------------
 // Launchers.
 // ---------------------------------------------------------------------------
-static inline int pick_waves(int nsteps, int max_waves) {
-  if (nsteps <= max_waves) return nsteps < 1 ? 1 : nsteps;
-  int best = max_waves; double best_eff = 0.0;
-  for (int w = max_waves; w >= max_waves / 2; --w) {
-    const int rounds = (nsteps + w - 1) / w;
-    const double eff = (double)nsteps / ((double)rounds * w);
-    if (eff > best_eff + 1e-9) { best_eff = eff; best = w; }
-  }
-  return best;
-}
-
-// LDS plan of the fused kernel: x, then 32 bytes per outlier chunk of a round.
-// A round holds at least one chunk per thread (the common, single-barrier path)
-// and up to four.  The budget is the CU's 160 KB divided by the number of
-// workgroups its 16 wavefront slots can hold, so LDS never lowers occupancy.
-// Returns 0 if x and one chunk per thread do not fit.
-// Static LDS of gemv_tile256_kernel (red, osum, hred, lred, rp), rounded up.
+// ---------------------------------------------------------------------------
+// Launch plan of the fused kernel.
+//
+// LDS: x (NB vectors), then 32 bytes per outlier chunk and vector of a round.  A
+// round holds at least one chunk per thread (the common, single-barrier path)
+// and up to four.  Static arrays (red, osum, hred, lred, rp) come on top; the
+// sum must stay within the CU's 160 KB.
+//
+// Wavefronts per workgroup: a strip has nsteps steps of 64 tiles.  With w
+// wavefronts a CU holds floor(slots / w) workgroups (slots = wavefront slots at
+// the kernel's register count, LDS permitting) and the steps split evenly only
+// if w divides them; the plan maximises useful concurrent wavefronts.
+// ---------------------------------------------------------------------------
+static constexpr int kCUs = 256;
 static constexpr int static_lds_bytes(int tr, int nb) {
   return ((16 * nb * tr + nb * tr + 32 + nb * tr * 16 + tr + 1) * 4 + 1023) & ~1023;
 }
-static inline int lds_budget(int nwaves, int max_waves, int tr, int nb) {
-  int groups = max_waves / nwaves; if (groups < 1) groups = 1;
-  return 160 * 1024 / groups - static_lds_bytes(tr, nb) - 1024;   // dynamic bytes one workgroup may take
-}
-static inline int outlier_chunk_cap(int n, int nwaves, int nb, int max_waves, int tr) {
-  const int nthreads = 64 * nwaves;
-  const int xbytes = (nb * n * 2 + 15) & ~15;
-  const int room = (lds_budget(nwaves, max_waves, tr, nb) - xbytes) / (32 * nb);
-  if (room < nthreads) return 0;
-  return room < 4 * nthreads ? room : 4 * nthreads;
+struct LaunchPlan { int nw; int cap; size_t lds; };
+
+static bool plan_launch(const Geometry& g, int nb, int max_waves, int slots, LaunchPlan* out) {
+  const int nsteps = (g.ntc + 63) / 64;
+  const int xbytes = (nb * g.n * 2 + 15) & ~15;
+  const int max_dynamic = 160 * 1024 - static_lds_bytes(g.tile_rows, nb) - 1024;
+  double best = -1.0;
+  // a plan whose x vectors leave LDS for only a sliver of a workgroup is not worth having
+  const int widest = max_waves < nsteps ? max_waves : nsteps;
+  if (xbytes + 32 * nb * 64 * ((widest + 1) / 2) > max_dynamic) return false;
+  for (int w = 1; w <= max_waves && w <= nsteps; ++w) {
+    int groups = slots / w; if (groups < 1) groups = 1;
+    // LDS one workgroup needs at least: x + one chunk per thread
+    const int need = xbytes + 32 * nb * 64 * w;
+    if (need > max_dynamic) continue;
+    const int by_lds = (160 * 1024) / (need + static_lds_bytes(g.tile_rows, nb) + 1024);
+    if (groups > by_lds) groups = by_lds;
+    if (groups < 1) continue;
+    const long concurrent = std::min<long>((long)g.ntr * w, (long)kCUs * w * groups);
+    const int per_wave = (nsteps + w - 1) / w;
+    const double score = (double)concurrent * nsteps / ((double)w * per_wave);
+    if (score > best * 1.0001 || (score > best * 0.9999 && w > out->nw)) {
+      best = score > best ? score : best;
+      // give the outlier products the LDS this occupancy leaves over, up to 4 chunks per thread
+      int room = ((160 * 1024) / groups - static_lds_bytes(g.tile_rows, nb) - 1024 - xbytes) / (32 * nb);
+      if (room > (max_dynamic - xbytes) / (32 * nb)) room = (max_dynamic - xbytes) / (32 * nb);
+      int cap = room < 4 * 64 * w ? room : 4 * 64 * w;
+      out->nw = w; out->cap = cap; out->lds = (size_t)xbytes + (size_t)32 * nb * cap;
+    }
+  }
+  return best > 0.0;
 }
 
 template <int W, int TR, int TC, int AXIS, int NB>
 static hipError_t launch_tile256(const DevMatrix& A, const uint16_t* x, void* y, int y_dtype,
                                  hipStream_t stream) {
   constexpr int MAXW = WavesPerGroup<W, NB>::MAX;
-  const int nsteps = (A.g.ntc + 63) / 64;
-  const int nw = pick_waves(nsteps, MAXW);
-  const int cap = outlier_chunk_cap(A.g.n, nw, NB, MAXW, TR);
-  if (cap == 0) return hipErrorInvalidValue;
-  const size_t lds = (((size_t)NB * A.g.n * 2 + 15) & ~(size_t)15) + (size_t)32 * NB * cap;
   constexpr int MAX_DYNAMIC = 160 * 1024 - static_lds_bytes(TR, NB) - 1024;   // static + dynamic <= 160 KB
-  if (lds > (size_t)MAX_DYNAMIC) return hipErrorInvalidValue;
-  // more than 64 KB of dynamic LDS needs an explicit opt-in, once per kernel
-  static bool opted[2] = {false, false};
+  // once per kernel: register count (-> wavefront slots per CU) and the opt-in for > 64 KB of dynamic LDS
+  static int slots[2] = {0, 0};
   const int pi = A.perm ? 1 : 0;
-  if (!opted[pi]) {
-    hipError_t e = A.perm
-        ? hipFuncSetAttribute(reinterpret_cast<const void*>(&gemv_tile256_kernel<W, TR, TC, AXIS, true, NB>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, MAX_DYNAMIC)
-        : hipFuncSetAttribute(reinterpret_cast<const void*>(&gemv_tile256_kernel<W, TR, TC, AXIS, false, NB>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, MAX_DYNAMIC);
+  if (slots[pi] == 0) {
+    const void* fn = A.perm ? reinterpret_cast<const void*>(&gemv_tile256_kernel<W, TR, TC, AXIS, true, NB>)
+                            : reinterpret_cast<const void*>(&gemv_tile256_kernel<W, TR, TC, AXIS, false, NB>);
+    hipFuncAttributes fa;
+    hipError_t e = hipFuncGetAttributes(&fa, fn);
     if (e != hipSuccess) return e;
-    opted[pi] = true;
+    e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, MAX_DYNAMIC);
+    if (e != hipSuccess) return e;
+    int regs = (fa.numRegs + 7) & ~7; if (regs < 64) regs = 64;
+    int per_simd = 512 / regs; if (per_simd > 8) per_simd = 8; if (per_simd < 1) per_simd = 1;
+    slots[pi] = 4 * per_simd;
   }
+  LaunchPlan plan = {0, 0, 0};
+  if (!plan_launch(A.g, NB, MAXW, slots[pi], &plan)) return hipErrorInvalidValue;
+  if (plan.lds > (size_t)MAX_DYNAMIC || plan.cap < 64 * plan.nw) return hipErrorInvalidValue;
   if (A.perm)
-    hipLaunchKernelGGL((gemv_tile256_kernel<W, TR, TC, AXIS, true, NB>), dim3(A.g.ntr), dim3(64 * nw), lds,
-                       stream, A, x, y, y_dtype, cap);
+    hipLaunchKernelGGL((gemv_tile256_kernel<W, TR, TC, AXIS, true, NB>), dim3(A.g.ntr), dim3(64 * plan.nw),
+                       plan.lds, stream, A, x, y, y_dtype, plan.cap);
   else
-    hipLaunchKernelGGL((gemv_tile256_kernel<W, TR, TC, AXIS, false, NB>), dim3(A.g.ntr), dim3(64 * nw), lds,
-                       stream, A, x, y, y_dtype, cap);
+    hipLaunchKernelGGL((gemv_tile256_kernel<W, TR, TC, AXIS, false, NB>), dim3(A.g.ntr), dim3(64 * plan.nw),
+                       plan.lds, stream, A, x, y, y_dtype, plan.cap);
   return hipGetLastError();
 }
 
@@ -773,10 +793,10 @@ int tuned_batch_width(const Geometry& g, int want) {
   const bool shape_ok = g.axis == 1 ? ((g.tile_rows == 16 && g.tile_cols == 16) || (g.tile_rows == 8 && g.tile_cols == 32))
                                     : ((g.tile_rows == 16 && g.tile_cols == 16) || (g.tile_rows == 32 && g.tile_cols == 8));
   if (!shape_ok) return 0;
-  const int nsteps = (g.ntc + 63) / 64;
   for (int nb = want >= 4 ? 4 : (want >= 2 ? 2 : 1); nb >= 1; nb >>= 1) {
+    LaunchPlan plan = {0, 0, 0};
     const int maxw = (g.w_bits == 3 && nb == 1) ? 16 : 8;
-    if (outlier_chunk_cap(g.n, pick_waves(nsteps, maxw), nb, maxw, g.tile_rows) > 0) return nb;
+    if (plan_launch(g, nb, maxw, 8, &plan)) return nb;   // 8 slots: the lowest occupancy any instance has
   }
   return 0;
 }
