@@ -283,7 +283,8 @@ gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restric
   constexpr int TILE_BYTES = 16 * T::KW + 4 * T::SD;
   constexpr int MAX_WAVES = 16;
   constexpr int XCH = 4;                     // 16-byte chunks of x a thread keeps in flight
-  constexpr int KR = 4;                      // outlier chunks per thread and round on the slow path
+  constexpr int KR = 4;                      // outlier chunks per thread fetched ahead of their use (1 + 3 extra)
+  constexpr int KMAX = 8;                    // outlier chunks per thread and round at most
   constexpr int LONG_ROW = 512;              // rows with more entries are summed by all threads
 
   // dynamic LDS: the NB x vectors | products of the outlier entries (8 floats per
@@ -356,7 +357,7 @@ gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restric
   const int nchunks = e_hi > e_lo ? ((e_hi - 1) >> 3) - c_lo + 1 : 0;
   const u32x4* col8 = reinterpret_cast<const u32x4*>(A.col);
   const u32x4* val8 = reinterpret_cast<const u32x4*>(A.val);
-  const int first_round = min(nchunks, nthreads);        // nthreads <= chunk_cap <= KR*nthreads
+  const int first_round = min(nchunks, nthreads);        // nthreads <= chunk_cap <= KMAX*nthreads
   u32x4 pc = {0, 0, 0, 0}, pv = {0, 0, 0, 0};
   if (tid < first_round) { pc = col8[c_lo + tid]; pv = val8[c_lo + tid]; }
   __syncthreads();                           // x is staged
@@ -417,6 +418,12 @@ gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restric
     }
   }
   if (heavy) {                               // the prefetched further chunks of the first round
+    u32x4 lc[KMAX - KR], lv[KMAX - KR];      // and, for very long strips, more chunks fetched only now
+#pragma unroll
+    for (int k = KR; k < KMAX; ++k) {
+      const int slot = tid + k * nthreads;
+      if (slot < chunk_cap && slot < nchunks) { lc[k - KR] = col8[c_lo + slot]; lv[k - KR] = val8[c_lo + slot]; }
+    }
 #pragma unroll
     for (int k = 1; k < KR; ++k) {
       const int slot = tid + k * nthreads;
@@ -427,6 +434,18 @@ gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restric
         for (int bi = 0; bi < NB; ++bi) {
           float p[8];
           chunk_products(xs + bi * n, e_lo, e_hi, c_lo + slot, c8, v8, p);
+          store_products(prod + bi * pstride, slot, p);
+        }
+      }
+    }
+#pragma unroll
+    for (int k = KR; k < KMAX; ++k) {
+      const int slot = tid + k * nthreads;
+      if (slot < chunk_cap && slot < nchunks) {
+#pragma unroll
+        for (int bi = 0; bi < NB; ++bi) {
+          float p[8];
+          chunk_products(xs + bi * n, e_lo, e_hi, c_lo + slot, lc[k - KR], lv[k - KR], p);
           store_products(prod + bi * pstride, slot, p);
         }
       }
@@ -494,7 +513,7 @@ gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restric
     return;
   }
 
-  // ---- slow path: rounds of chunk_cap chunks (up to KR per thread, all loads of a
+  // ---- slow path: rounds of chunk_cap chunks (up to KMAX per thread, all loads of a
   // round in flight together); long rows summed by all threads ----------------------
   if (tid < NB * TR) (&osum[0][0])[tid] = 0.f;
   int par = 0;
@@ -502,14 +521,14 @@ gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restric
     const int c1 = min(nchunks, c0 + chunk_cap);
     if (c0 > 0) __syncthreads();                         // previous round's products are consumed
     if (c0 > 0) {                                        // round 0 is already in LDS
-      u32x4 cc[KR], vv[KR];
+      u32x4 cc[KMAX], vv[KMAX];
 #pragma unroll
-      for (int k = 0; k < KR; ++k) {
+      for (int k = 0; k < KMAX; ++k) {
         const int slot = tid + k * nthreads, j = c0 + slot;
         if (slot < chunk_cap && j < c1) { cc[k] = col8[c_lo + j]; vv[k] = val8[c_lo + j]; }
       }
 #pragma unroll
-      for (int k = 0; k < KR; ++k) {
+      for (int k = 0; k < KMAX; ++k) {
         const int slot = tid + k * nthreads, j = c0 + slot;
         if (slot < chunk_cap && j < c1) {
 #pragma unroll
@@ -709,7 +728,7 @@ __device__ int g_check_words[4];
 //
 // LDS: x (NB vectors), then 32 bytes per outlier chunk and vector of a round.  A
 // round holds at least one chunk per thread (the common, single-barrier path)
-// and up to four.  Static arrays (red, osum, hred, lred, rp) come on top; the
+// and up to eight.  Static arrays (red, osum, hred, lred, rp) come on top; the
 // sum must stay within the CU's 160 KB.
 //
 // Wavefronts per workgroup: a strip has nsteps steps of 64 tiles.  With w
@@ -739,15 +758,17 @@ static bool plan_launch(const Geometry& g, int nb, int max_waves, int slots, Lau
     const int by_lds = (160 * 1024) / (need + static_lds_bytes(g.tile_rows, nb) + 1024);
     if (groups > by_lds) groups = by_lds;
     if (groups < 1) continue;
+    const int wanted = (g.ntr + kCUs - 1) / kCUs;      // a small grid never puts more workgroups on a CU
+    const int share = groups < wanted ? groups : wanted;
     const long concurrent = std::min<long>((long)g.ntr * w, (long)kCUs * w * groups);
     const int per_wave = (nsteps + w - 1) / w;
     const double score = (double)concurrent * nsteps / ((double)w * per_wave);
     if (score > best * 1.0001 || (score > best * 0.9999 && w > out->nw)) {
       best = score > best ? score : best;
       // give the outlier products the LDS this occupancy leaves over, up to 4 chunks per thread
-      int room = ((160 * 1024) / groups - static_lds_bytes(g.tile_rows, nb) - 1024 - xbytes) / (32 * nb);
+      int room = ((160 * 1024) / share - static_lds_bytes(g.tile_rows, nb) - 1024 - xbytes) / (32 * nb);
       if (room > (max_dynamic - xbytes) / (32 * nb)) room = (max_dynamic - xbytes) / (32 * nb);
-      int cap = room < 4 * 64 * w ? room : 4 * 64 * w;
+      int cap = room < 8 * 64 * w ? room : 8 * 64 * w;
       out->nw = w; out->cap = cap; out->lds = (size_t)xbytes + (size_t)32 * nb * cap;
     }
   }
