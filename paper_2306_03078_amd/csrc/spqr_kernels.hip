@@ -734,7 +734,7 @@ __device__ int g_check_words[4];
 // Wavefronts per workgroup: a strip has nsteps steps of 64 tiles.  With w
 // wavefronts a CU holds floor(slots / w) workgroups (slots = wavefront slots at
 // the kernel's register count, LDS permitting) and the steps split evenly only
-// if w divides them; the plan maximises useful concurrent wavefronts.
+// if w divides them; the plan maximises the wavefronts resident on a CU.
 // ---------------------------------------------------------------------------
 static constexpr int kCUs = 256;
 static constexpr int static_lds_bytes(int tr, int nb) {
@@ -760,9 +760,16 @@ static bool plan_launch(const Geometry& g, int nb, int max_waves, int slots, Lau
     if (groups < 1) continue;
     const int wanted = (g.ntr + kCUs - 1) / kCUs;      // a small grid never puts more workgroups on a CU
     const int share = groups < wanted ? groups : wanted;
-    const long concurrent = std::min<long>((long)g.ntr * w, (long)kCUs * w * groups);
+    // Score: wavefronts resident on a CU, with a bonus for a wavefront count that
+    // spreads evenly over the four SIMDs, for more than one workgroup per CU (one
+    // computes while another waits at a barrier or for its loads) and for an even
+    // split of the steps.  Weights fitted to timings on MI355X.
     const int per_wave = (nsteps + w - 1) / w;
-    const double score = (double)concurrent * nsteps / ((double)w * per_wave);
+    const double even = (double)nsteps / ((double)w * per_wave);
+    int resident = w * share; if (resident > slots) resident = slots;
+    double score = (double)resident * (0.75 + 0.25 * even);
+    if (w % 4 == 0) score *= 1.05;
+    if (share >= 2) score *= 1.03;
     if (score > best * 1.0001 || (score > best * 0.9999 && w > out->nw)) {
       best = score > best ? score : best;
       // give the outlier products the LDS this occupancy leaves over, up to 4 chunks per thread
