@@ -12,6 +12,7 @@
 //   The strip's outliers (a contiguous CSR range) are handled by the same
 //   workgroup, so y is written once, without atomics, in a fixed order.
 #include <hip/hip_runtime.h>
+#include <cstdlib>
 
 #include <algorithm>
 
@@ -118,12 +119,13 @@ __device__ __forceinline__ void load_tile(TileRegs<W, TR, TC, AXIS>& t, const ui
 //   AXIS 1: sum_j (1 + q_rj/2^W) * u_j  with u_j = fp16(s_hat_j * x_j); csum[b]
 //           accumulates sum_j (2^W + z_hat_j) * u_j, so y_r = 2^W*acc[r] - csum.
 //   AXIS 0: s_hat_r * (2^W * sum_j (1 + q_rj/2^W) x_j - (2^W + z_hat_r) * sum_j x_j).
-// A pair is extracted once and used by all NB vectors.
+// A pair is extracted once and used by all NB vectors.  `valid` false: the lane
+// adds exact zeros (every scale is forced to 0), so no branch surrounds the tile.
 template <int W, int TR, int TC, int AXIS, int NB>
 __device__ __forceinline__ void tile_fma(const TileRegs<W, TR, TC, AXIS>& t,
                                          const uint32_t* xpair /* TC/2 dwords in LDS, vector 0 */,
-                                         int xstride, float (&acc)[NB][TR], float (&csum)[NB],
-                                         const PairConsts& k, const PairConsts& k3) {
+                                         int xstride, bool valid, float (&acc)[NB][TR],
+                                         float (&csum)[NB], const PairConsts& k, const PairConsts& k3) {
   using T = TileRegs<W, TR, TC, AXIS>;
   constexpr int PPR = TC / 2;
   constexpr float SCALE = (float)(1 << W);
@@ -131,8 +133,9 @@ __device__ __forceinline__ void tile_fma(const TileRegs<W, TR, TC, AXIS>& t,
   const uint32_t a = t.s[T::SD - 2], b = t.s[T::SD - 1];
   const float s_s = h2f((uint16_t)(a & 0xFFFF)), z_s = h2f((uint16_t)(a >> 16));
   const float s_z = h2f((uint16_t)(b & 0xFFFF)), z_z = h2f((uint16_t)(b >> 16));
-  // s_hat = s_s*(s_q - z_s) = c1*(1 + s_q/8) + c2
-  const float c1 = 8.f * s_s, c2 = -s_s * z_s - c1;
+  // s_hat = s_s*(s_q - z_s) = c1*(1 + s_q/8) + c2.  A lane without a tile of its own
+  // (it holds a copy of the block's last tile) runs the same code with s_hat = 0.
+  const float c1 = valid ? 8.f * s_s : 0.f, c2 = valid ? -s_s * z_s - 8.f * s_s : 0.f;
 
   uint32_t xp[NB][PPR];
 #pragma unroll
@@ -283,7 +286,6 @@ gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restric
   constexpr int TILE_BYTES = 16 * T::KW + 4 * T::SD;
   constexpr int MAX_WAVES = 16;
   constexpr int XCH = 4;                     // 16-byte chunks of x a thread keeps in flight
-  constexpr int KR = 4;                      // outlier chunks per thread fetched ahead of their use (1 + 3 extra)
   constexpr int KMAX = 8;                    // outlier chunks per thread and round at most
   constexpr int LONG_ROW = 512;              // rows with more entries are summed by all threads
 
@@ -301,7 +303,8 @@ gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restric
   __shared__ float lred[NB][TR][MAX_WAVES];
   __shared__ int rp[TR + 1];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // scalar: step indices and tile bases stay in SGPRs
   const int nthreads = blockDim.x, nwaves = nthreads >> 6;
   const int l16 = tid & 15, g16 = tid >> 4, ngroups = nthreads >> 4;
   const int strip = blockIdx.x;
@@ -325,19 +328,22 @@ gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restric
   __builtin_amdgcn_sched_barrier(0);         // keep the x loads ahead of the tile loads
 
   T t0, t1;
-  auto issue = [&](T& t, int st) -> bool {
-    if (st < nsteps) {
-      const int L = min(64, ntc - 64 * st);
-      load_tile(t, strip_base + (int64_t)64 * st * TILE_BYTES, L, min(lane, L - 1));
-      return lane < L;
-    }
-    return false;
+  // Tile loads are never branched around: a step that does not exist loads one
+  // 16-byte word per load with all lanes on the strip's first tile (a single
+  // cache line, the result is ignored).  With no conditional load between a tile's
+  // loads and its use, the waits ahead of each code word count exactly the loads
+  // issued behind it, so a tile's arithmetic starts while its later words and the
+  // whole next tile are still in flight.
+  auto issue = [&](T& t, int st) -> int {    // returns the number of tiles in the step's block
+    const bool real = st < nsteps;           // wave-uniform
+    const int L = real ? min(64, ntc - 64 * st) : 1;
+    load_tile(t, strip_base + (int64_t)64 * (real ? st : 0) * TILE_BYTES, L, min(lane, L - 1));
+    asm volatile("" ::: "memory");           // the loads stay here, ahead of the arithmetic on the other buffer
+    return L;
   };
   int step = wave;                           // wave < nwaves <= nsteps: the first step always exists
-  bool h1 = false;
-  const int L0 = min(64, ntc - 64 * step);
+  int L0 = min(64, ntc - 64 * step), L1 = 1;
   load_tile(t0, strip_base + (int64_t)64 * step * TILE_BYTES, L0, min(lane, L0 - 1));
-  bool h0 = lane < L0;
   __builtin_amdgcn_sched_barrier(0);
   rp[min(tid, TR)] = rp_mine;                // clamped duplicates store the same value again
 
@@ -358,8 +364,13 @@ gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restric
   const u32x4* col8 = reinterpret_cast<const u32x4*>(A.col);
   const u32x4* val8 = reinterpret_cast<const u32x4*>(A.val);
   const int first_round = min(nchunks, nthreads);        // nthreads <= chunk_cap <= KMAX*nthreads
-  u32x4 pc = {0, 0, 0, 0}, pv = {0, 0, 0, 0};
-  if (tid < first_round) { pc = col8[c_lo + tid]; pv = val8[c_lo + tid]; }
+  u32x4 pc, pv;
+  {                                          // unconditional, like the tile loads: a thread without a chunk
+    const bool have = tid < first_round;     // reads 16 bytes of the strip's first tile instead
+    const u32x4* dummy = reinterpret_cast<const u32x4*>(strip_base);
+    pc = *(have ? col8 + c_lo + tid : dummy);
+    pv = *(have ? val8 + c_lo + tid : dummy);
+  }
   __syncthreads();                           // x is staged
 
   // ---- dense part -------------------------------------------------------------
@@ -373,42 +384,34 @@ gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restric
   const PairConsts kc = make_pair_consts<W>();
   const PairConsts k3 = make_pair_consts<3>();
   const uint32_t* xs32 = reinterpret_cast<const uint32_t*>(xs);
-  // A strip with more outlier chunks than threads fetches this thread's further
-  // chunks of the first round (slots tid + k*nthreads, k >= 1) into the tile
-  // buffer that is idle during the wavefront's last dense step.
-  static_assert(8 * (KR - 1) <= 4 * T::KW, "extra chunks must fit the idle tile buffer");
   const bool heavy = nchunks > nthreads;     // workgroup-uniform
-  bool extra_in_t1 = false;
-  auto fetch_extra = [&](T& buf) {
-#pragma unroll
-    for (int k = 1; k < KR; ++k) {
-      const int slot = tid + k * nthreads;
-      if (slot < chunk_cap && slot < nchunks) {
-        const u32x4 c8 = col8[c_lo + slot], v8 = val8[c_lo + slot];
-        uint32_t* d = buf.c + 8 * (k - 1);
-        d[0] = c8.x; d[1] = c8.y; d[2] = c8.z; d[3] = c8.w;
-        d[4] = v8.x; d[5] = v8.y; d[6] = v8.z; d[7] = v8.w;
-      }
-    }
-  };
-  while (step < nsteps) {                    // wave-uniform; two steps per trip, registers ping-pong
-    if (step + nwaves < nsteps) h1 = issue(t1, step + nwaves);
-    else if (heavy) { fetch_extra(t1); extra_in_t1 = true; }
-    if (h0) tile_fma<W, TR, TC, AXIS, NB>(t0, xs32 + (64 * step + lane) * (TC / 2), n >> 1, acc, csum, kc, k3);
-    step += nwaves;
-    if (step >= nsteps) break;
-    if (step + nwaves < nsteps) h0 = issue(t0, step + nwaves);
-    else if (heavy) { fetch_extra(t0); extra_in_t1 = false; }
-    if (h1) tile_fma<W, TR, TC, AXIS, NB>(t1, xs32 + (64 * step + lane) * (TC / 2), n >> 1, acc, csum, kc, k3);
-    step += nwaves;
+#define SPQR_TILE_FMA(t, L, st)                                                                           \
+  tile_fma<W, TR, TC, AXIS, NB>(t, xs32 + (64 * (st) + min(lane, (L) - 1)) * (TC / 2), n >> 1, lane < (L), \
+                                acc, csum, kc, k3)
+  // Two steps per trip, registers ping-pong; the loop has its one exit at the
+  // bottom (a second exit would be merged with it through a block that makes the
+  // compiler wait for every load at the top of the loop).  t0 holds step `step`.
+  while (step + nwaves < nsteps) {           // wave-uniform: at least two steps are left
+    L1 = issue(t1, step + nwaves);
+    SPQR_TILE_FMA(t0, L0, step);
+    L0 = issue(t0, step + 2 * nwaves);       // a dummy after the wavefront's last step
+    SPQR_TILE_FMA(t1, L1, step + nwaves);
+    step += 2 * nwaves;
   }
-  uint32_t ex[8 * (KR - 1)];                 // the prefetched extra chunks, out of the tile buffers
+  if (step < nsteps) SPQR_TILE_FMA(t0, L0, step);
+#undef SPQR_TILE_FMA
+
+  // ---- outlier products of the first round -> LDS.  A strip with more chunks
+  // than threads (slots tid + k*nthreads, k >= 1) fetches the further ones now,
+  // all together, and multiplies the chunk it already holds meanwhile. -----------
+  u32x4 lc[KMAX - 1], lv[KMAX - 1];
   if (heavy) {
 #pragma unroll
-    for (int i = 0; i < 8 * (KR - 1); ++i) ex[i] = extra_in_t1 ? t1.c[i] : t0.c[i];
+    for (int k = 1; k < KMAX; ++k) {
+      const int slot = tid + k * nthreads;
+      if (slot < chunk_cap && slot < nchunks) { lc[k - 1] = col8[c_lo + slot]; lv[k - 1] = val8[c_lo + slot]; }
+    }
   }
-
-  // ---- outlier products of the first round -> LDS ------------------------------
   if (tid < first_round) {
 #pragma unroll
     for (int bi = 0; bi < NB; ++bi) {
@@ -417,35 +420,15 @@ gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restric
       store_products(prod + bi * pstride, tid, p);
     }
   }
-  if (heavy) {                               // the prefetched further chunks of the first round
-    u32x4 lc[KMAX - KR], lv[KMAX - KR];      // and, for very long strips, more chunks fetched only now
+  if (heavy) {
 #pragma unroll
-    for (int k = KR; k < KMAX; ++k) {
-      const int slot = tid + k * nthreads;
-      if (slot < chunk_cap && slot < nchunks) { lc[k - KR] = col8[c_lo + slot]; lv[k - KR] = val8[c_lo + slot]; }
-    }
-#pragma unroll
-    for (int k = 1; k < KR; ++k) {
-      const int slot = tid + k * nthreads;
-      if (slot < chunk_cap && slot < nchunks) {
-        const uint32_t* d = ex + 8 * (k - 1);
-        const u32x4 c8 = {d[0], d[1], d[2], d[3]}, v8 = {d[4], d[5], d[6], d[7]};
-#pragma unroll
-        for (int bi = 0; bi < NB; ++bi) {
-          float p[8];
-          chunk_products(xs + bi * n, e_lo, e_hi, c_lo + slot, c8, v8, p);
-          store_products(prod + bi * pstride, slot, p);
-        }
-      }
-    }
-#pragma unroll
-    for (int k = KR; k < KMAX; ++k) {
+    for (int k = 1; k < KMAX; ++k) {
       const int slot = tid + k * nthreads;
       if (slot < chunk_cap && slot < nchunks) {
 #pragma unroll
         for (int bi = 0; bi < NB; ++bi) {
           float p[8];
-          chunk_products(xs + bi * n, e_lo, e_hi, c_lo + slot, lc[k - KR], lv[k - KR], p);
+          chunk_products(xs + bi * n, e_lo, e_hi, c_lo + slot, lc[k - 1], lv[k - 1], p);
           store_products(prod + bi * pstride, slot, p);
         }
       }
@@ -750,7 +733,11 @@ static bool plan_launch(const Geometry& g, int nb, int max_waves, int slots, Lau
   // a plan whose x vectors leave LDS for only a sliver of a workgroup is not worth having
   const int widest = max_waves < nsteps ? max_waves : nsteps;
   if (xbytes + 32 * nb * 64 * ((widest + 1) / 2) > max_dynamic) return false;
+  // SPQR_PLAN_WAVES=k in the environment pins the wavefronts per workgroup (tuning runs)
+  int pinned = 0;
+  if (const char* e = std::getenv("SPQR_PLAN_WAVES")) pinned = std::atoi(e);
   for (int w = 1; w <= max_waves && w <= nsteps; ++w) {
+    if (pinned > 0 && w != pinned && pinned <= max_waves && pinned <= nsteps) continue;
     int groups = slots / w; if (groups < 1) groups = 1;
     // LDS one workgroup needs at least: x + one chunk per thread
     const int need = xbytes + 32 * nb * 64 * w;
@@ -760,18 +747,18 @@ static bool plan_launch(const Geometry& g, int nb, int max_waves, int slots, Lau
     if (groups < 1) continue;
     const int wanted = (g.ntr + kCUs - 1) / kCUs;      // a small grid never puts more workgroups on a CU
     const int share = groups < wanted ? groups : wanted;
-    // Score: wavefronts resident on a CU, with a bonus for a wavefront count that
-    // spreads evenly over the four SIMDs, for more than one workgroup per CU (one
-    // computes while another waits at a barrier or for its loads) and for an even
-    // split of the steps.  Weights fitted to timings on MI355X.
-    const int per_wave = (nsteps + w - 1) / w;
-    const double even = (double)nsteps / ((double)w * per_wave);
+    // Score: closeness to the preferred workgroup width.  A wavefront pipelines its
+    // steps (the next tile's loads fly under the current tile's arithmetic), so few
+    // wide-enough workgroups beat many one-step wavefronts: 8 wavefronts when the
+    // strip has 8 steps or more, else 4 (both spread evenly over the four SIMDs and
+    // leave room for a second workgroup on the CU), else one per step.  Fitted to
+    // timings of the benchmark layers on MI355X.
+    const int cap8 = max_waves < 8 ? max_waves : 8;
+    const int target = nsteps < 4 ? nsteps : ((nsteps < cap8 ? nsteps : cap8) / 4) * 4;
     int resident = w * share; if (resident > slots) resident = slots;
-    double score = (double)resident * (0.75 + 0.25 * even);
-    if (w % 4 == 0) score *= 1.05;
-    if (share >= 2) score *= 1.03;
-    if (score > best * 1.0001 || (score > best * 0.9999 && w > out->nw)) {
-      best = score > best ? score : best;
+    double score = 100.0 - (w > target ? 1.5 * (w - target) : (target - w)) + 1e-3 * resident;
+    if (score > best) {
+      best = score;
       // give the outlier products the LDS this occupancy leaves over, up to 4 chunks per thread
       int room = ((160 * 1024) / share - static_lds_bytes(g.tile_rows, nb) - 1024 - xbytes) / (32 * nb);
       if (room > (max_dynamic - xbytes) / (32 * nb)) room = (max_dynamic - xbytes) / (32 * nb);
