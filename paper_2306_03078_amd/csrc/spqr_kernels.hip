@@ -286,6 +286,7 @@ gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restric
   constexpr int TILE_BYTES = 16 * T::KW + 4 * T::SD;
   constexpr int MAX_WAVES = 16;
   constexpr int XCH = 4;                     // 16-byte chunks of x a thread keeps in flight
+  constexpr int KR = 4;                      // outlier chunks per thread requested ahead of the last dense step
   constexpr int KMAX = 8;                    // outlier chunks per thread and round at most
   constexpr int LONG_ROW = 512;              // rows with more entries are summed by all threads
 
@@ -398,16 +399,25 @@ gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restric
     SPQR_TILE_FMA(t1, L1, step + nwaves);
     step += 2 * nwaves;
   }
-  if (step < nsteps) SPQR_TILE_FMA(t0, L0, step);
-#undef SPQR_TILE_FMA
-
-  // ---- outlier products of the first round -> LDS.  A strip with more chunks
-  // than threads (slots tid + k*nthreads, k >= 1) fetches the further ones now,
-  // all together, and multiplies the chunk it already holds meanwhile. -----------
+  // A strip with more outlier chunks than threads (slots tid + k*nthreads, k >= 1):
+  // the next KR-1 chunks of this thread are requested here, in the registers the
+  // other tile buffer has just left, and arrive under the wavefront's last dense
+  // step; the rest follow after it, all together.
   u32x4 lc[KMAX - 1], lv[KMAX - 1];
   if (heavy) {
 #pragma unroll
-    for (int k = 1; k < KMAX; ++k) {
+    for (int k = 1; k < KR; ++k) {
+      const int slot = tid + k * nthreads;
+      if (slot < chunk_cap && slot < nchunks) { lc[k - 1] = col8[c_lo + slot]; lv[k - 1] = val8[c_lo + slot]; }
+    }
+  }
+  if (step < nsteps) SPQR_TILE_FMA(t0, L0, step);
+#undef SPQR_TILE_FMA
+
+  // ---- outlier products of the first round -> LDS -------------------------------
+  if (heavy) {
+#pragma unroll
+    for (int k = KR; k < KMAX; ++k) {
       const int slot = tid + k * nthreads;
       if (slot < chunk_cap && slot < nchunks) { lc[k - 1] = col8[c_lo + slot]; lv[k - 1] = val8[c_lo + slot]; }
     }
@@ -757,6 +767,13 @@ static bool plan_launch(const Geometry& g, int nb, int max_waves, int slots, Lau
     const int target = nsteps < 4 ? nsteps : ((nsteps < cap8 ? nsteps : cap8) / 4) * 4;
     int resident = w * share; if (resident > slots) resident = slots;
     double score = 100.0 - (w > target ? 1.5 * (w - target) : (target - w)) + 1e-3 * resident;
+    if (nb > 1) {
+      // several activation vectors: arithmetic dominates, so what counts is wavefronts
+      // resident on the CU and an even split of the steps among them
+      const int per_wave = (nsteps + w - 1) / w;
+      const double even = (double)nsteps / ((double)w * per_wave);
+      score = (double)resident * (0.75 + 0.25 * even) * (w % 4 == 0 ? 1.05 : 1.0) * (share >= 2 ? 1.03 : 1.0) + 1e-3 * w;
+    }
     if (score > best) {
       best = score;
       // give the outlier products the LDS this occupancy leaves over, up to 4 chunks per thread
