@@ -404,12 +404,16 @@ gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restric
   // other tile buffer has just left, and arrive under the wavefront's last dense
   // step; the rest follow after it, all together.
   u32x4 lc[KMAX - 1], lv[KMAX - 1];
-  if (heavy) {
+  {                                          // unconditional like the tile loads (dummy: the strip's first tile),
+    const u32x4* dummy = reinterpret_cast<const u32x4*>(strip_base);   // so that the waits stay exact
 #pragma unroll
     for (int k = 1; k < KR; ++k) {
       const int slot = tid + k * nthreads;
-      if (slot < chunk_cap && slot < nchunks) { lc[k - 1] = col8[c_lo + slot]; lv[k - 1] = val8[c_lo + slot]; }
+      const bool have = slot < chunk_cap && slot < nchunks;
+      lc[k - 1] = *(have ? col8 + c_lo + slot : dummy);
+      lv[k - 1] = *(have ? val8 + c_lo + slot : dummy);
     }
+    asm volatile("" ::: "memory");
   }
   if (step < nsteps) SPQR_TILE_FMA(t0, L0, step);
 #undef SPQR_TILE_FMA
@@ -457,28 +461,40 @@ gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restric
     if ((lane & ((64 / TR) - 1)) == 0) red[wave][bi][row] = rsum;
   }
 
-  // One barrier publishes products and partials and tells every thread whether
-  // some row of the strip is too long for 16 lanes.  Only a strip with more chunks
+  // Rows too long for 16 lanes, as a bit mask every wavefront works out for itself
+  // from the row pointers in LDS (TR <= 32 lanes vote), and this thread's first
+  // output row: both read ahead of the barrier, off the critical path behind it.
+  static_assert(TR <= 32, "one lane per row votes");
+  const int vr = min(lane, TR - 1);
+  uint64_t longs = __builtin_amdgcn_ballot_w64(lane < TR && rp[vr + 1] - rp[vr] > LONG_ROW);
+  const int r_long = longs ? __builtin_ctzll(longs) : 0;
+  const int lo_long = rp[r_long], hi_long = rp[r_long + 1];
+  const int r_first = min(g16, TR - 1);
+  const int a_first = rp[r_first], b_first = rp[r_first + 1];
+  // One barrier publishes products and partials.  Only a strip with more chunks
   // than one round holds needs the slow path.
-  const int any_long = __syncthreads_or(tid < TR && rp[min(tid, TR - 1) + 1] - rp[min(tid, TR - 1)] > LONG_ROW);
+  __syncthreads();
   const bool slow = nchunks > chunk_cap;     // workgroup-uniform
   const int base = 8 * c_lo;                 // CSR index of prod[0] in the first round
   if (!slow) {
-    if (any_long) {
+    if (longs) {
       // long rows: every thread adds a strided share, one partial per wavefront and row
-      for (int r = 0; r < TR; ++r) {         // workgroup-uniform
-        if (rp[r + 1] - rp[r] <= LONG_ROW) continue;
-        const int lo = rp[r] - base, hi = rp[r + 1] - base;
+      bool first = true;
+      while (longs) {                        // workgroup-uniform
+        const int r = __builtin_ctzll(longs);
+        longs &= longs - 1;
+        const int lo = (first ? lo_long : rp[r]) - base, hi = (first ? hi_long : rp[r + 1]) - base;
+        first = false;
 #pragma unroll
         for (int bi = 0; bi < NB; ++bi) {
           const float* pb = prod + bi * pstride;
           float s = 0.f;
-          for (int i = lo + tid; i < hi; i += 4 * nthreads) {
-            float v[4];
+          for (int i = lo + tid; i < hi; i += 12 * nthreads) {
+            float v[12];
 #pragma unroll
-            for (int k = 0; k < 4; ++k) v[k] = pb[min(i + k * nthreads, hi - 1)];
+            for (int k = 0; k < 12; ++k) v[k] = pb[min(i + k * nthreads, hi - 1)];
 #pragma unroll
-            for (int k = 0; k < 4; ++k) s += (i + k * nthreads < hi) ? v[k] : 0.f;
+            for (int k = 0; k < 12; ++k) s += (i + k * nthreads < hi) ? v[k] : 0.f;
           }
           s = wave_allreduce(s, lane);
           if (lane == 0) lred[bi][r][wave] = s;
@@ -488,7 +504,7 @@ gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restric
     }
     // 16 lanes per row: the row's products, plus one dense partial per wavefront
     for (int r = g16; r < TR; r += ngroups) {
-      const int a = rp[r], b = rp[r + 1];
+      const int a = r == g16 ? a_first : rp[r], b = r == g16 ? b_first : rp[r + 1];
 #pragma unroll
       for (int bi = 0; bi < NB; ++bi) {
         float s;
