@@ -99,7 +99,11 @@ typedef enum spqr_status {
  * Outliers: row_ptr[m+1] is the exclusive prefix of per-row counts
  * (row_ptr[0] = 0, row_ptr[m] = nnz); col_idx / out_val are sorted by row then
  * strictly increasing column.  With nnz = 0, col_idx and out_val may be NULL;
- * row_ptr must still hold m+1 zeros.
+ * row_ptr must still hold m+1 zeros.  col_idx and out_val must be 16-byte
+ * aligned (SPQR_ERR_ALIGN otherwise): the product kernels read them in aligned
+ * 16-byte granules of 8 entries.  The granule holding the last entry is read
+ * whole; it shares its 16 aligned bytes, hence its page, with that entry, and
+ * what lies behind entry nnz-1 is ignored.
  *
  * perm (optional, NULL = identity) is an input permutation of length n: the
  * product is taken with x'[j] = x[perm[j]] (act-order checkpoints, Sec. 5).
@@ -114,8 +118,8 @@ typedef struct spqr_matrix_t {
   const void*     packed;     /* device, 16-byte aligned */
   int64_t         packed_bytes;
   const int32_t*  row_ptr;    /* device, m+1 entries */
-  const uint16_t* col_idx;    /* device, nnz entries */
-  const uint16_t* out_val;    /* device, nnz binary16 bit patterns */
+  const uint16_t* col_idx;    /* device, nnz entries, 16-byte aligned */
+  const uint16_t* out_val;    /* device, nnz binary16 bit patterns, 16-byte aligned */
   int64_t         nnz;
   const int32_t*  perm;       /* device, n entries, or NULL */
 } spqr_matrix_t;
