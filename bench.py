@@ -57,6 +57,68 @@ def time_layer(P, torch, A, X, copies, reps=6):
     return e0.elapsed_time(e1) * 1e3 / (reps * copies)
 
 
+def time_block(P, torch, mats, x_h, x_f, copies, fused, reps=4):
+    """One decoder block at batch 1: q, k, v (input x_h), o (x_h), gate, up (x_h), down (x_f).
+    `mats` maps the layer name to a list of `copies` weight copies.  fused=True issues q/k/v and
+    gate/up as one spqr_gemv_fused call each (4 launches per block instead of 7)."""
+    ys = {nm: torch.empty(ms[0].m, dtype=torch.float32, device=x_h.device) for nm, ms in mats.items()}
+
+    def block(c):
+        if fused:
+            P.spqr_gemv_fused([mats[nm][c] for nm in ("q", "k", "v")], x_h, outs=[ys[nm] for nm in ("q", "k", "v")])
+            P.spqr_gemv(mats["o"][c], x_h, out=ys["o"])
+            P.spqr_gemv_fused([mats[nm][c] for nm in ("gate", "up")], x_h, outs=[ys[nm] for nm in ("gate", "up")])
+        else:
+            for nm in ("q", "k", "v", "o", "gate", "up"):
+                P.spqr_gemv(mats[nm][c], x_h, out=ys[nm])
+        P.spqr_gemv(mats["down"][c], x_f, out=ys["down"])
+
+    for c in range(copies):
+        block(c)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for c in range(copies):
+            block(c)
+    g.replay()
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        g.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / (reps * copies)
+
+
+def run_block_sweep(rows, P, synth, torch, dev):
+    """Whole decoder blocks of configurations 2-4, seven separate launches against four (q/k/v and
+    gate/up fused)."""
+    for cfg in (2, 3, 4):
+        specs = synth.config_layers(cfg)
+        mats, nbytes = {}, 0
+        for li, sp in enumerate(specs):
+            A = P.SpQRMatrix.from_logical(synth.make_config_layer(cfg, li, group_axis=1), dev)
+            nbytes += algorithmic_bytes(A, 1)
+            mats[sp.name] = [A]
+        copies = max(2, int(512e6 // nbytes) + 1)
+        for nm in mats:
+            mats[nm] += [mats[nm][0].clone() for _ in range(copies - 1)]
+        h, f = specs[0].n, specs[-1].n
+        x_h = torch.from_numpy(synth.make_x(h, 1, seed=(cfg, 100))[0]).to(dev)
+        x_f = torch.from_numpy(synth.make_x(f, 1, seed=(cfg, 101))[0]).to(dev)
+        for fused in (False, True):
+            us = time_block(P, torch, mats, x_h, x_f, copies, fused)
+            rows.append({"config": cfg, "layer": "block(7 launches)" if not fused else "block(q/k/v, gate/up fused: 4 launches)",
+                         "m": 0, "n": 0, "w_bits": specs[0].w_bits, "beta1": specs[0].beta1, "beta2": specs[0].beta2,
+                         "group_axis": 1, "batch": 1, "outliers": f"{specs[0].outlier_rate:g} {specs[0].outlier_structure}",
+                         "compressed_MB": round(nbytes / 1e6, 2), "us": round(us, 2),
+                         "GBps": round(nbytes / us / 1e3, 1),
+                         "frac_of_hbm_peak": round(nbytes / us / 1e3 / HBM_PEAK_GBS, 4)})
+        del mats
+        torch.cuda.empty_cache()
+
+
 def run_sweep(path, P, synth, torch, dev):
     rows = []
     for cfg in sorted(synth.CONFIGS):
@@ -82,6 +144,7 @@ def run_sweep(path, P, synth, torch, dev):
                                  "frac_of_hbm_peak": round(nbytes / us / 1e3 / HBM_PEAK_GBS, 4)})
                 del A
                 torch.cuda.empty_cache()
+    run_block_sweep(rows, P, synth, torch, dev)
     with open(path, "w") as fh:
         json.dump(rows, fh, indent=1)
 

@@ -26,7 +26,7 @@
  *      rows x beta2 columns.
  *
  * Pointers are DEVICE pointers unless a parameter says "host".  The library
- * never allocates, frees or keeps caller memory.  spqr_gemv,
+ * never allocates, frees or keeps caller memory.  spqr_gemv, spqr_gemv_fused,
  * spqr_gemm_smallbatch and spqr_dequant_dense are asynchronous on the given
  * HIP stream (a hipStream_t passed as void*; NULL = the default stream) and
  * never synchronise.  Every entry point returns SPQR_OK (0) or a negative
@@ -168,10 +168,25 @@ int spqr_pack_check(const spqr_matrix_t* A, uint32_t flags, void* stream);
 int spqr_gemv(const spqr_matrix_t* A, const uint16_t* x_f16, void* y, int y_dtype,
               void* stream);
 
-/* Y[b][m] = X[b][:] . W_hat^T for 1 <= b <= SPQR_MAX_BATCH, weights read once.
+/* Y[b][m] = X[b][:] . W_hat^T for 1 <= b <= SPQR_MAX_BATCH; the weights are
+ * read once per slice of up to 4 activation vectors.
  * X: [b][n] binary16 row-major.  Y: [b][m] of y_dtype, overwritten. */
 int spqr_gemm_smallbatch(const spqr_matrix_t* A, const uint16_t* X_f16, int b, void* Y,
                          int y_dtype, void* stream);
+
+/* y[i][0..m_i) = W_hat_i . x for `count` (1..SPQR_MAX_FUSED) matrices that
+ * share the input vector: the q/k/v or the gate/up projections of a decoder
+ * block (Sec. 4.2 decodes token by token, layer by layer; matrices fed by the
+ * same activations need not wait for one another).  A and y are HOST arrays of
+ * `count` descriptor pointers / device output pointers.  The matrices must
+ * agree in n, w_bits, s_bits, z_bits, beta1, beta2, group_axis, layout_version
+ * and perm (SPQR_ERR_PARAM otherwise); m may differ.  When a tuned kernel
+ * exists and perm is NULL all strips of all matrices run in ONE launch, each
+ * workgroup doing exactly what it does in spqr_gemv; otherwise the call is
+ * `count` launches of spqr_gemv.  Results equal spqr_gemv's. */
+#define SPQR_MAX_FUSED 8
+int spqr_gemv_fused(const spqr_matrix_t* const* A, int count, const uint16_t* x_f16,
+                    void* const* y, int y_dtype, void* stream);
 
 /* Debug decode.  `what` selects the output:
  *   SPQR_OUT_CODES_U8   uint8  [m][n]   the b_w-bit codes

@@ -73,6 +73,8 @@ def load_library():
     lib.spqr_gemv.argtypes = [P, vp, vp, C.c_int, vp]
     lib.spqr_gemm_smallbatch.restype = C.c_int
     lib.spqr_gemm_smallbatch.argtypes = [P, vp, C.c_int, vp, C.c_int, vp]
+    lib.spqr_gemv_fused.restype = C.c_int
+    lib.spqr_gemv_fused.argtypes = [C.POINTER(P), C.c_int, vp, C.POINTER(vp), C.c_int, vp]
     lib.spqr_dequant_dense.restype = C.c_int
     lib.spqr_dequant_dense.argtypes = [P, C.c_int, vp, vp]
     _lib = lib
@@ -209,6 +211,21 @@ def spqr_gemm_smallbatch(A: SpQRMatrix, X, out=None, y_dtype: int = SPQR_F32, st
     _check(load_library().spqr_gemm_smallbatch(C.byref(A.desc), X.data_ptr(), b, out.data_ptr(),
                                                y_dtype, _stream_ptr(stream)), "spqr_gemm_smallbatch")
     return out
+
+
+def spqr_gemv_fused(As, x, outs=None, y_dtype: int = SPQR_F32, stream=None):
+    """y_i[m_i] = W_hat_i . x for matrices sharing the input vector; one launch when possible."""
+    import torch
+    As = list(As)
+    assert x.dtype == torch.float16 and x.is_contiguous() and x.numel() == As[0].n
+    if outs is None:
+        outs = [torch.empty(A.m, dtype=_out_dtype(y_dtype), device=x.device) for A in As]
+    lib = load_library()
+    k = len(As)
+    descs = (C.POINTER(spqr_matrix_t) * k)(*[C.pointer(A.desc) for A in As])
+    ys = (C.c_void_p * k)(*[o.data_ptr() for o in outs])
+    _check(lib.spqr_gemv_fused(descs, k, x.data_ptr(), ys, y_dtype, _stream_ptr(stream)), "spqr_gemv_fused")
+    return outs
 
 
 def spqr_dequant_dense(A: SpQRMatrix, what: int, stream=None):

@@ -78,6 +78,29 @@ extern "C" int spqr_gemv(const spqr_matrix_t* A, const uint16_t* x_f16, void* y,
   return spqr_gemm_smallbatch(A, x_f16, 1, y, y_dtype, stream);
 }
 
+extern "C" int spqr_gemv_fused(const spqr_matrix_t* const* A, int count, const uint16_t* x_f16,
+                               void* const* y, int y_dtype, void* stream) {
+  if (!A || !y || !x_f16) return SPQR_ERR_NULL;
+  if (count < 1 || count > SPQR_MAX_FUSED) return SPQR_ERR_PARAM;
+  if (y_dtype != SPQR_F32 && y_dtype != SPQR_F16) return SPQR_ERR_DTYPE;
+  if (reinterpret_cast<uintptr_t>(x_f16) % 16 != 0) return SPQR_ERR_ALIGN;
+  spqr::DevMatrix D[SPQR_MAX_FUSED];
+  for (int i = 0; i < count; ++i) {
+    if (!A[i] || !y[i]) return SPQR_ERR_NULL;
+    int rc = to_device_matrix(A[i], &D[i]);
+    if (rc) return rc;
+    if (reinterpret_cast<uintptr_t>(y[i]) % (y_dtype == SPQR_F32 ? 4 : 2) != 0) return SPQR_ERR_ALIGN;
+    const spqr_matrix_t *a = A[i], *a0 = A[0];
+    if (a->n != a0->n || a->w_bits != a0->w_bits || a->s_bits != a0->s_bits || a->z_bits != a0->z_bits ||
+        a->beta1 != a0->beta1 || a->beta2 != a0->beta2 || a->group_axis != a0->group_axis ||
+        a->layout_version != a0->layout_version || a->perm != a0->perm)
+      return SPQR_ERR_PARAM;
+  }
+  hipError_t e = spqr::launch_gemv_fused(D, count, x_f16, y, y_dtype, static_cast<hipStream_t>(stream),
+                                         force_generic());
+  return e == hipSuccess ? SPQR_OK : SPQR_ERR_HIP;
+}
+
 extern "C" int spqr_dequant_dense(const spqr_matrix_t* A, int what, void* out, void* stream) {
   spqr::DevMatrix D;
   int rc = to_device_matrix(A, &D);

@@ -276,10 +276,11 @@ template <int W, int NB> struct WavesPerGroup { static constexpr int MAX = (W ==
 
 // NB activation vectors per launch: X holds NB rows of n binary16 values (row
 // stride n), Y NB rows of m outputs (row stride m).  NB = 1 is the GEMV.
+// `strip` is the strip of A this workgroup owns.
 template <int W, int TR, int TC, int AXIS, bool PERM, int NB>
-__global__ void __launch_bounds__((64 * WavesPerGroup<W, NB>::MAX))
-gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restrict__ y, int y_dtype,
-                    int chunk_cap) {
+__device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint16_t* __restrict__ x,
+                                                  void* __restrict__ y, int y_dtype, int chunk_cap,
+                                                  const int strip) {
   using T = TileRegs<W, TR, TC, AXIS>;
   static_assert(TR * TC == 256, "tile must hold 256 codes");
   static_assert((TC / 2) % 4 == 0, "x pairs are read as 16-byte LDS words");
@@ -308,7 +309,6 @@ gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restric
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // scalar: step indices and tile bases stay in SGPRs
   const int nthreads = blockDim.x, nwaves = nthreads >> 6;
   const int l16 = tid & 15, g16 = tid >> 4, ngroups = nthreads >> 4;
-  const int strip = blockIdx.x;
   const int nsteps = (ntc + 63) >> 6;
   const uint8_t* strip_base = A.packed + (int64_t)strip * ntc * TILE_BYTES;
   const int32_t* rpg = A.row_ptr + (int64_t)strip * TR;
@@ -592,6 +592,39 @@ gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restric
     if (y_dtype == SPQR_F32) reinterpret_cast<float*>(y)[i] = s;
     else reinterpret_cast<uint16_t*>(y)[i] = f2h_rne(s);
   }
+}
+
+template <int W, int TR, int TC, int AXIS, bool PERM, int NB>
+__global__ void __launch_bounds__((64 * WavesPerGroup<W, NB>::MAX))
+gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restrict__ y, int y_dtype,
+                    int chunk_cap) {
+  gemv_tile256_body<W, TR, TC, AXIS, PERM, NB>(A, x, y, y_dtype, chunk_cap, blockIdx.x);
+}
+
+// Several matrices that share the input vector and the format (q/k/v, gate/up of
+// a decoder block) in one grid: strips [first[i], first[i+1]) belong to matrix i.
+// Every workgroup does exactly what it would do in a launch of its own matrix.
+struct FusedArgs {
+  int count;
+  int first[SPQR_MAX_FUSED + 1];
+  Geometry g;                                // of matrix 0; m and ntr differ per matrix and are not used by the body
+  const uint8_t* packed[SPQR_MAX_FUSED];
+  const int32_t* row_ptr[SPQR_MAX_FUSED];
+  const uint16_t* col[SPQR_MAX_FUSED];
+  const uint16_t* val[SPQR_MAX_FUSED];
+  void* y[SPQR_MAX_FUSED];
+};
+
+template <int W, int TR, int TC, int AXIS>
+__global__ void __launch_bounds__((64 * WavesPerGroup<W, 1>::MAX))
+gemv_tile256_fused_kernel(FusedArgs F, const uint16_t* __restrict__ x, int y_dtype, int chunk_cap) {
+  int i = 0;
+  while (i + 1 < F.count && (int)blockIdx.x >= F.first[i + 1]) ++i;   // workgroup-uniform, count <= SPQR_MAX_FUSED
+  DevMatrix A;
+  A.g = F.g;
+  A.packed = F.packed[i]; A.row_ptr = F.row_ptr[i]; A.col = F.col[i]; A.val = F.val[i];
+  A.perm = nullptr; A.nnz = 0;
+  gemv_tile256_body<W, TR, TC, AXIS, false, 1>(A, x, F.y[i], y_dtype, chunk_cap, (int)blockIdx.x - F.first[i]);
 }
 
 // ---------------------------------------------------------------------------
@@ -894,6 +927,65 @@ hipError_t launch_gemm(const DevMatrix& A, const uint16_t* X, int b, void* Y, in
 hipError_t launch_gemv(const DevMatrix& A, const uint16_t* x, void* y, int y_dtype,
                        hipStream_t stream, bool force_generic) {
   return launch_gemm(A, x, 1, y, y_dtype, stream, force_generic);
+}
+
+template <int W, int TR, int TC, int AXIS>
+static hipError_t launch_fused256(const DevMatrix* As, int count, const uint16_t* x, void* const* ys,
+                                  int y_dtype, hipStream_t stream) {
+  constexpr int MAXW = WavesPerGroup<W, 1>::MAX;
+  constexpr int MAX_DYNAMIC = 160 * 1024 - static_lds_bytes(TR, 1) - 1024;
+  static int slots = 0;
+  const void* fn = reinterpret_cast<const void*>(&gemv_tile256_fused_kernel<W, TR, TC, AXIS>);
+  if (slots == 0) {
+    hipFuncAttributes fa;
+    hipError_t e = hipFuncGetAttributes(&fa, fn);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, MAX_DYNAMIC);
+    if (e != hipSuccess) return e;
+    int regs = (fa.numRegs + 7) & ~7; if (regs < 64) regs = 64;
+    int per_simd = 512 / regs; if (per_simd > 8) per_simd = 8; if (per_simd < 1) per_simd = 1;
+    slots = 4 * per_simd;
+  }
+  FusedArgs F;
+  F.count = count;
+  F.g = As[0].g;
+  int total = 0;
+  for (int i = 0; i < count; ++i) {
+    F.first[i] = total;
+    total += As[i].g.ntr;
+    F.packed[i] = As[i].packed; F.row_ptr[i] = As[i].row_ptr; F.col[i] = As[i].col; F.val[i] = As[i].val;
+    F.y[i] = ys[i];
+  }
+  for (int i = count; i <= SPQR_MAX_FUSED; ++i) F.first[i] = total;
+  for (int i = count; i < SPQR_MAX_FUSED; ++i) {
+    F.packed[i] = nullptr; F.row_ptr[i] = nullptr; F.col[i] = nullptr; F.val[i] = nullptr; F.y[i] = nullptr;
+  }
+  Geometry all = As[0].g;                    // the plan sees the whole grid
+  all.ntr = total;
+  LaunchPlan plan = {0, 0, 0};
+  if (!plan_launch(all, 1, MAXW, slots, &plan)) return hipErrorInvalidValue;
+  if (plan.lds > (size_t)MAX_DYNAMIC || plan.cap < 64 * plan.nw) return hipErrorInvalidValue;
+  hipLaunchKernelGGL((gemv_tile256_fused_kernel<W, TR, TC, AXIS>), dim3(total), dim3(64 * plan.nw), plan.lds, stream,
+                     F, x, y_dtype, plan.cap);
+  return hipGetLastError();
+}
+
+hipError_t launch_gemv_fused(const DevMatrix* As, int count, const uint16_t* x, void* const* ys,
+                             int y_dtype, hipStream_t stream, bool force_generic) {
+  const Geometry& g = As[0].g;
+  if (count > 1 && !force_generic && As[0].perm == nullptr && tuned_batch_width(g, 1) == 1) {
+#define SPQR_CASE(W_, TR_, TC_, AX_) \
+    if (g.w_bits == W_ && g.tile_rows == TR_ && g.tile_cols == TC_ && g.axis == AX_) \
+      return launch_fused256<W_, TR_, TC_, AX_>(As, count, x, ys, y_dtype, stream);
+    SPQR_CASE(3, 16, 16, 1) SPQR_CASE(4, 16, 16, 1) SPQR_CASE(3, 8, 32, 1) SPQR_CASE(4, 8, 32, 1)
+    SPQR_CASE(3, 16, 16, 0) SPQR_CASE(4, 16, 16, 0) SPQR_CASE(3, 32, 8, 0) SPQR_CASE(4, 32, 8, 0)
+#undef SPQR_CASE
+  }
+  for (int i = 0; i < count; ++i) {
+    hipError_t e = launch_gemv(As[i], x, ys[i], y_dtype, stream, force_generic);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 hipError_t launch_dequant(const DevMatrix& A, int what, void* out, hipStream_t stream) {

@@ -261,3 +261,55 @@ def test_runs_on_a_side_stream(P):
         y = P.spqr_gemv(A, x, stream=s)
     s.synchronize()
     assert rel_l2(y.cpu().numpy(), orc.matvec(f, synth.make_x(f.n, 1, seed=(73,)))[0]) <= REL_L2
+
+
+@pytest.mark.parametrize("w,b1,b2,axis,ntc", [(3, 16, 16, 1, 70), (4, 16, 16, 0, 130), (3, 8, 32, 1, 67),
+                                              (3, 32, 16, 1, 9)])          # the last has no tuned kernel
+def test_fused_projections_share_one_input(P, w, b1, b2, axis, ntc):
+    """q/k/v-like: several matrices of different heights fed by one x, one call.
+    Every matrix must match the oracle and, bit for bit, its own spqr_gemv."""
+    import torch
+    tr, tc = synth.tile_shape(b1, b2, axis)
+    heights = (3, 1, 5, 2)                        # tile rows per matrix
+    structures = ("uniform", "rows8cols4", "none", "zipf")
+    fs = [synth.make_matrix(h * tr, ntc * tc, w_bits=w, beta1=b1, beta2=b2, group_axis=axis, outlier_rate=0.03,
+                            outlier_structure=st, seed=(57, w, b1, axis, k))
+          for k, (h, st) in enumerate(zip(heights, structures))]
+    As = [P.SpQRMatrix.from_logical(f) for f in fs]
+    xh = synth.make_x(fs[0].n, 1, seed=(58, ntc))
+    x = dev(xh[0])
+    ys = P.spqr_gemv_fused(As, x)
+    torch.cuda.synchronize()
+    for f, A, y in zip(fs, As, ys):
+        y = y.cpu().numpy()
+        assert y.shape == (f.m,)
+        assert rel_l2(y, orc.matvec(f, xh)[0]) <= REL_L2
+        alone = P.spqr_gemv(A, x).cpu().numpy()
+        assert rel_l2(y, alone) <= 1e-6            # same arithmetic; the launch plan may split a long strip differently
+    # a single matrix, fp16 output, and the descriptor checks
+    y1 = P.spqr_gemv_fused(As[:1], x, y_dtype=P.SPQR_F16)[0].cpu().numpy()
+    assert np.array_equal(y1.view(np.uint16), P.spqr_gemv(As[0], x, y_dtype=P.SPQR_F16).cpu().numpy().view(np.uint16))
+    other = P.SpQRMatrix.from_logical(synth.make_matrix(tr, (ntc + 1) * tc, w_bits=w, beta1=b1, beta2=b2,
+                                                        group_axis=axis, outlier_rate=0.0, seed=(59,)))
+    with pytest.raises(P.SpQRError):
+        P.spqr_gemv_fused([As[0], other], x)      # different n
+    with pytest.raises(P.SpQRError):
+        P.spqr_gemv_fused(As * 3, x)              # more than SPQR_MAX_FUSED
+
+
+def test_fused_projections_with_a_shared_permutation(P):
+    import torch
+    fs = []
+    perm = np.random.default_rng(5).permutation(70 * 16).astype(np.int32)
+    for k in range(2):
+        f = make(3, 16, 16, 1, 2 + k, 70, seed=(61, k))
+        f.perm = perm
+        fs.append(f)
+    As = [P.SpQRMatrix.from_logical(f) for f in fs]
+    # descriptors must name the same device permutation
+    As[1].desc.perm = As[0].desc.perm
+    xh = synth.make_x(fs[0].n, 1, seed=(62,))
+    ys = P.spqr_gemv_fused(As, dev(xh[0]))
+    torch.cuda.synchronize()
+    for f, y in zip(fs, ys):
+        assert rel_l2(y.cpu().numpy(), orc.matvec(f, xh)[0]) <= REL_L2
