@@ -286,7 +286,7 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
   static_assert((TC / 2) % 4 == 0, "x pairs are read as 16-byte LDS words");
   constexpr int TILE_BYTES = 16 * T::KW + 4 * T::SD;
   constexpr int MAX_WAVES = 16;
-  constexpr int XCH = 4;                     // 16-byte chunks of x a thread keeps in flight
+  constexpr int XCH = 4 * NB;                // 16-byte chunks of x a thread keeps in flight
   constexpr int KR = 4;                      // outlier chunks per thread requested ahead of the last dense step
   constexpr int KMAX = 8;                    // outlier chunks per thread and round at most
   constexpr int LONG_ROW = 512;              // rows with more entries are summed by all threads
@@ -301,7 +301,6 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
   const int pstride = 8 * chunk_cap;         // floats of products per vector
   __shared__ float red[MAX_WAVES][NB][TR];
   __shared__ float osum[NB][TR];
-  __shared__ float hred[2][MAX_WAVES];
   __shared__ float lred[NB][TR][MAX_WAVES];
   __shared__ int rp[TR + 1];
 
@@ -353,7 +352,16 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
 #pragma unroll
     for (int k = 0; k < XCH; ++k)            // clamped duplicates store the same value again
       dst[min(tid + k * nthreads, nvec - 1)] = xr[k];
-    for (int i = tid + XCH * nthreads; i < nvec; i += nthreads) dst[i] = reinterpret_cast<const u32x4*>(x)[i];
+    if constexpr (NB == 1) {                 // very long x: the rest, one chunk at a time
+      for (int i = tid + XCH * nthreads; i < nvec; i += nthreads) dst[i] = reinterpret_cast<const u32x4*>(x)[i];
+    } else {                                 // several vectors: further batches of XCH chunks
+      for (int i0 = tid + XCH * nthreads; i0 < nvec; i0 += XCH * nthreads) {
+#pragma unroll
+        for (int k = 0; k < XCH; ++k) xr[k] = reinterpret_cast<const u32x4*>(x)[min(i0 + k * nthreads, nvec - 1)];
+#pragma unroll
+        for (int k = 0; k < XCH; ++k) dst[min(i0 + k * nthreads, nvec - 1)] = xr[k];
+      }
+    }
     for (int j = (nvec << 3) + tid; j < NB * n; j += nthreads) xs[j] = x[j];
   } else {
     for (int j = tid; j < NB * n; j += nthreads) xs[j] = x[(j / n) * n + A.perm[j % n]];
@@ -525,7 +533,6 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
   // ---- slow path: rounds of chunk_cap chunks (up to KMAX per thread, all loads of a
   // round in flight together); long rows summed by all threads ----------------------
   if (tid < NB * TR) (&osum[0][0])[tid] = 0.f;
-  int par = 0;
   for (int c0 = 0; c0 < nchunks; c0 += chunk_cap) {      // workgroup-uniform
     const int c1 = min(nchunks, c0 + chunk_cap);
     if (c0 > 0) __syncthreads();                         // previous round's products are consumed
@@ -551,35 +558,41 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
     }
     __syncthreads();
     const int e0 = 8 * (c_lo + c0), e1 = 8 * (c_lo + c1);   // CSR range covered by this round
-    for (int r = g16; r < TR; r += ngroups) {
-      const int a = max(rpg[r], e0), b = min(rpg[r + 1], e1);
-      if (b > a && b - a <= LONG_ROW) {
+    // rows with a long slice in this round, voted as on the fast path; their partials per
+    // wavefront go through lred, one barrier for all of them
+    uint64_t rl = __builtin_amdgcn_ballot_w64(lane < TR && min(rp[vr + 1], e1) - max(rp[vr], e0) > LONG_ROW);
+    const bool some_long = rl != 0;
+    while (rl) {                                         // workgroup-uniform
+      const int r = __builtin_ctzll(rl);
+      rl &= rl - 1;
+      const int lo = max(rp[r], e0) - e0, hi = min(rp[r + 1], e1) - e0;
 #pragma unroll
-        for (int bi = 0; bi < NB; ++bi) {
-          float s = strided16_sum(prod + bi * pstride, a - e0, b - e0, l16);
-          s = row16_allreduce(s, lane);
-          if (l16 == 0) osum[bi][r] += s;
-        }
-      }
-    }
-    for (int r = 0; r < TR; ++r) {                       // workgroup-uniform
-      const int a = max(rpg[r], e0), b = min(rpg[r + 1], e1);
-      if (b - a <= LONG_ROW) continue;
       for (int bi = 0; bi < NB; ++bi) {
         const float* pb = prod + bi * pstride;
         float s = 0.f;
-        for (int i = a - e0 + tid; i < b - e0; i += 4 * nthreads) {
+        for (int i = lo + tid; i < hi; i += 4 * nthreads) {
           float v[4];
 #pragma unroll
-          for (int k = 0; k < 4; ++k) v[k] = pb[min(i + k * nthreads, b - e0 - 1)];
+          for (int k = 0; k < 4; ++k) v[k] = pb[min(i + k * nthreads, hi - 1)];
 #pragma unroll
-          for (int k = 0; k < 4; ++k) s += (i + k * nthreads < b - e0) ? v[k] : 0.f;
+          for (int k = 0; k < 4; ++k) s += (i + k * nthreads < hi) ? v[k] : 0.f;
         }
         s = wave_allreduce(s, lane);
-        if (lane == 0) hred[par][wave] = s;
-        __syncthreads();
-        if (tid == 0) { float t = 0.f; for (int w = 0; w < nwaves; ++w) t += hred[par][w]; osum[bi][r] += t; }
-        par ^= 1;                                        // the next sum must not overwrite what thread 0 reads
+        if (lane == 0) lred[bi][r][wave] = s;
+      }
+    }
+    if (some_long) __syncthreads();
+    for (int r = g16; r < TR; r += ngroups) {            // a row always meets the same 16 lanes: osum needs no barrier
+      const int a = max(rp[r], e0), b = min(rp[r + 1], e1);
+      if (b > a) {
+#pragma unroll
+        for (int bi = 0; bi < NB; ++bi) {
+          float s;
+          if (b - a > LONG_ROW) s = l16 < nwaves ? lred[bi][r][l16] : 0.f;
+          else s = strided16_sum(prod + bi * pstride, a - e0, b - e0, l16);
+          s = row16_allreduce(s, lane);
+          if (l16 == 0) osum[bi][r] += s;
+        }
       }
     }
   }
@@ -770,7 +783,7 @@ __device__ int g_check_words[4];
 //
 // LDS: x (NB vectors), then 32 bytes per outlier chunk and vector of a round.  A
 // round holds at least one chunk per thread (the common, single-barrier path)
-// and up to eight.  Static arrays (red, osum, hred, lred, rp) come on top; the
+// and up to eight.  Static arrays (red, osum, lred, rp) come on top; the
 // sum must stay within the CU's 160 KB.
 //
 // Wavefronts per workgroup: a strip has nsteps steps of 64 tiles.  With w
