@@ -73,6 +73,97 @@ __device__ __forceinline__ uint32_t pair_f16(const uint32_t* c, int q, const Pai
 }
 
 // ---------------------------------------------------------------------------
+// Code pairs of the dense loop: one shift serves several pairs.
+// A code sitting at bit o <= 6 (3-bit) / o <= 4 (4-bit) of its half-word is already
+// inside the binary16 mantissa: masking it in place and OR-ing an exponent gives
+//   K + q/2^W   with K = 2^(7-o) (3-bit: 128, 16, 2)  resp. 2^(6-o) (4-bit: 64, 4),
+// exactly representable, so only the codes in the upper bits of a half-word need
+// a shift, and one shift of the dword (by 9 resp. 8) brings all of them down at
+// once.  The price is an offset K that depends on the code's position ("class");
+// it is removed per tile with the class sums of the activations (see tile_fma).
+//   3-bit: pair e of a triple (e < 15) is code e%5 of dword e/5: codes 0,1,2 are
+//          classes 0,1,2, codes 3,4 (after >> 9) classes 0,1; the split pair e = 15
+//          is assembled at class 2.
+//   4-bit: pair q%4 of a dword: 0,1 are classes 0,1; 2,3 (after >> 8) classes 0,1.
+// ---------------------------------------------------------------------------
+// SHARED = false (tiles of 8 columns: 32 accumulators leave no registers for the class
+// bookkeeping) keeps one class with K = 1 and a shift per pair.
+template <int W, bool SHARED> struct CodeClass {
+  static constexpr int N = !SHARED ? 1 : (W == 3 ? 3 : 2);
+  static constexpr int of_pair(int q) {           // q: pair index inside the tile
+    if (!SHARED) return 0;
+    if (W == 4) return (q & 3) & 1;
+    const int e = q & 15;
+    return e == 15 ? 2 : (e % 5) % 3;
+  }
+  static constexpr float K(int c) {
+    return !SHARED ? 1.f : (W == 3 ? (c == 0 ? 128.f : c == 1 ? 16.f : 2.f) : (c == 0 ? 64.f : 4.f));
+  }
+};
+template <int TC> struct SharedShifts { static constexpr bool value = TC != 8; };
+
+struct ClassConsts {
+  uint32_t mask[3];    // SGPR: code bits of class c inside both half-words
+  uint32_t magic[3];   // VGPR: binary16 K(c) twice
+  uint32_t m0, m1, m2; // SGPR: single-bit masks of the split pair of a 3-bit triple
+};
+
+template <int W>
+__device__ __forceinline__ ClassConsts make_class_consts() {
+  ClassConsts k;
+  if constexpr (W == 3) {
+    k.mask[0] = in_sgpr(0x00070007u); k.mask[1] = in_sgpr(0x00380038u); k.mask[2] = in_sgpr(0x01C001C0u);
+    k.magic[0] = in_vgpr(0x58005800u); k.magic[1] = in_vgpr(0x4C004C00u); k.magic[2] = in_vgpr(0x40004000u);
+    k.m0 = in_sgpr(0x00400040u); k.m1 = in_sgpr(0x00800080u); k.m2 = in_sgpr(0x01000100u);
+  } else {
+    k.mask[0] = in_sgpr(0x000F000Fu); k.mask[1] = in_sgpr(0x00F000F0u); k.mask[2] = 0;
+    k.magic[0] = in_vgpr(0x54005400u); k.magic[1] = in_vgpr(0x44004400u); k.magic[2] = 0;
+    k.m0 = k.m1 = k.m2 = 0;
+  }
+  return k;
+}
+
+// The shifted copies of the dwords that hold pair q; refreshed when q enters a
+// new triple (3-bit) or dword (4-bit).  All indices are compile-time constants in
+// the unrolled loops, so this is three (one) shifts per 16 (4) pairs.
+template <int W> struct ShiftedWords { uint32_t s[W == 3 ? 3 : 1]; };
+
+template <int W>
+__device__ __forceinline__ void refresh_shifted(ShiftedWords<W>& sw, const uint32_t* c, int q) {
+  if constexpr (W == 3) {
+    if ((q & 15) == 0) {
+      const int t3 = q >> 4;
+      sw.s[0] = c[3 * t3] >> 9; sw.s[1] = c[3 * t3 + 1] >> 9; sw.s[2] = c[3 * t3 + 2] >> 9;
+    }
+  } else {
+    if ((q & 3) == 0) sw.s[0] = c[q >> 2] >> 8;
+  }
+}
+
+// binary16 pair (K + q_lo/2^W, K + q_hi/2^W), K = CodeClass<W>::K(of_pair(q))
+template <int W>
+__device__ __forceinline__ uint32_t pair_class_f16(const uint32_t* c, const ShiftedWords<W>& sw, int q,
+                                                   const ClassConsts& k) {
+  if constexpr (W == 4) {
+    const int e = q & 3;
+    const uint32_t src = e < 2 ? c[q >> 2] : sw.s[0];
+    return (src & k.mask[e & 1]) | k.magic[e & 1];
+  } else {
+    const int t3 = q >> 4, e = q & 15;
+    if (e < 15) {
+      const int j = e / 5, i = e % 5;
+      const uint32_t src = i < 3 ? c[3 * t3 + j] : sw.s[j];
+      return (src & k.mask[i % 3]) | k.magic[i % 3];
+    } else {                                         // bits 15 / 31 of the three dwords -> bits 6, 7, 8
+      uint32_t t = (sw.s[0] & k.m0) | k.magic[2];
+      t = ((c[3 * t3 + 1] >> 8) & k.m1) | t;
+      t = ((c[3 * t3 + 2] >> 7) & k.m2) | t;
+      return t;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
 // Fused GEMV for tiles of 256 codes.
 //   W     code width (3, 4)
 //   TR,TC tile rows / columns, TR*TC == 256
@@ -112,30 +203,47 @@ __device__ __forceinline__ void load_tile(TileRegs<W, TR, TC, AXIS>& t, const ui
   }
 }
 
+// Row phases: the class of the pair in tile row r, column pair p depends on
+// (r*PPR + p) % 16 for 3-bit codes, so rows repeat with period 16/PPR; 4-bit
+// classes depend on p alone.
+template <int W, int TC> struct RowPhases {
+  static constexpr int N = (W == 4 || TC / 2 >= 16 || !SharedShifts<TC>::value) ? 1 : 16 / (TC / 2);
+};
+
 // One tile's contribution for NB activation vectors (LDS rows of `xstride`
-// dwords).  Codes enter the dot products as 1 + q/2^W and the statistic codes as
-// 1 + s_q/8, 1 + z_q/8 (exact binary16 values); the offsets are removed with
-// per-tile sums.  acc[b][r] accumulates, per output row r and vector b:
-//   AXIS 1: sum_j (1 + q_rj/2^W) * u_j  with u_j = fp16(s_hat_j * x_j); csum[b]
-//           accumulates sum_j (2^W + z_hat_j) * u_j, so y_r = 2^W*acc[r] - csum.
-//   AXIS 0: s_hat_r * (2^W * sum_j (1 + q_rj/2^W) x_j - (2^W + z_hat_r) * sum_j x_j).
-// A pair is extracted once and used by all NB vectors.  `valid` false: the lane
-// adds exact zeros (every scale is forced to 0), so no branch surrounds the tile.
+// dwords).  Codes enter the dot products as K + q/2^W (K by class, see above) and
+// the statistic codes as 1 + s_q/8, 1 + z_q/8 (exact binary16 values); the offsets
+// are removed with per-tile sums.  acc[b][r] accumulates, per output row r and
+// vector b:
+//   AXIS 1: sum_j (K_rj + q_rj/2^W) * u_j  with u_j = fp16(s_hat_j * x_j);
+//           csum[b][h] accumulates, for the rows of phase h, sum_j (2^W*K_rj + z_hat_j) * u_j,
+//           so y_r = 2^W*acc[r] - csum[r % phases].
+//   AXIS 0: s_hat_r * (2^W * sum_j (K_rj + q_rj/2^W) x_j - sum_j (2^W*K_rj + z_hat_r) x_j).
+// The sums of K_rj*u_j come from one dot product per pair, phase and vector into
+// per-class sums.  A pair is extracted once and used by all NB vectors.  `valid`
+// false: the lane adds exact zeros (every scale is forced to 0), so no branch
+// surrounds the tile.
 template <int W, int TR, int TC, int AXIS, int NB>
 __device__ __forceinline__ void tile_fma(const TileRegs<W, TR, TC, AXIS>& t,
                                          const uint32_t* xpair /* TC/2 dwords in LDS, vector 0 */,
                                          int xstride, bool valid, float (&acc)[NB][TR],
-                                         float (&csum)[NB], const PairConsts& k, const PairConsts& k3) {
+                                         float (&csum)[NB][RowPhases<W, TC>::N], const ClassConsts& k,
+                                         const PairConsts& k1, const PairConsts& k3) {
   using T = TileRegs<W, TR, TC, AXIS>;
+  constexpr bool SHARED = SharedShifts<TC>::value;
+  using CC = CodeClass<W, SHARED>;
   constexpr int PPR = TC / 2;
+  constexpr int NPH = RowPhases<W, TC>::N;
   constexpr float SCALE = (float)(1 << W);
-  const half2_t ones = as_half2(k.magic);
+  const half2_t ones = as_half2(k3.magic);
   const uint32_t a = t.s[T::SD - 2], b = t.s[T::SD - 1];
   const float s_s = h2f((uint16_t)(a & 0xFFFF)), z_s = h2f((uint16_t)(a >> 16));
   const float s_z = h2f((uint16_t)(b & 0xFFFF)), z_z = h2f((uint16_t)(b >> 16));
   // s_hat = s_s*(s_q - z_s) = c1*(1 + s_q/8) + c2.  A lane without a tile of its own
   // (it holds a copy of the block's last tile) runs the same code with s_hat = 0.
   const float c1 = valid ? 8.f * s_s : 0.f, c2 = valid ? -s_s * z_s - 8.f * s_s : 0.f;
+  // z_hat = s_z*(z_q - z_z) = e1*(1 + z_q/8) + e2
+  const float e1 = 8.f * s_z, e2 = -s_z * z_z - e1;
 
   uint32_t xp[NB][PPR];
 #pragma unroll
@@ -147,10 +255,19 @@ __device__ __forceinline__ void tile_fma(const TileRegs<W, TR, TC, AXIS>& t,
     }
   }
 
-  if constexpr (AXIS == 1) {
-    float U[NB], Zd[NB];
+  float C[NB][NPH][CC::N];                     // per phase and class: sum of the activations it multiplies
 #pragma unroll
-    for (int bi = 0; bi < NB; ++bi) { U[bi] = 0.f; Zd[bi] = 0.f; }
+  for (int bi = 0; bi < NB; ++bi)
+#pragma unroll
+    for (int h = 0; h < NPH; ++h)
+#pragma unroll
+      for (int c = 0; c < CC::N; ++c) C[bi][h][c] = 0.f;
+  ShiftedWords<W> sw;
+
+  if constexpr (AXIS == 1) {
+    float Zd[NB];
+#pragma unroll
+    for (int bi = 0; bi < NB; ++bi) Zd[bi] = 0.f;
 #pragma unroll
     for (int p = 0; p < PPR; ++p) {
       const half2_t sq = as_half2(pair_f16<3>(t.s, p, k3));
@@ -160,17 +277,32 @@ __device__ __forceinline__ void tile_fma(const TileRegs<W, TR, TC, AXIS>& t,
       for (int bi = 0; bi < NB; ++bi) {
         const half2_t xv = as_half2(xp[bi][p]);
         half2_t u;
-        u.x = (_Float16)(s0 * (float)xv.x);
-        u.y = (_Float16)(s1 * (float)xv.y);
+        u.x = (_Float16)fmaf(s0, (float)xv.x, 0.f);   // binary16 source widened inside the multiply, one rounding
+        u.y = (_Float16)fmaf(s1, (float)xv.y, 0.f);
         xp[bi][p] = __builtin_bit_cast(uint32_t, u);   // x is not needed any more: keep u in its place
-        U[bi] = __builtin_amdgcn_fdot2(u, ones, U[bi], false);
+#pragma unroll
+        for (int h = 0; h < NPH; ++h) {
+          const int c = CC::of_pair(h * PPR + p);
+          C[bi][h][c] = __builtin_amdgcn_fdot2(u, ones, C[bi][h][c], false);
+        }
         Zd[bi] = __builtin_amdgcn_fdot2(u, zq, Zd[bi], false);
       }
     }
-    // sum_j (2^W + z_hat_j) u_j with z_hat_j = s_z*(z_q - z_z), sum_j z_q u_j = 8*(Zd - U)
+    // sum_j z_hat_j u_j = e1*Zd + e2*U;  sum_j 2^W*K_rj u_j = 2^W * sum_c K(c) * C[h][c]
 #pragma unroll
-    for (int bi = 0; bi < NB; ++bi)
-      csum[bi] = fmaf(SCALE - s_z * z_z - 8.f * s_z, U[bi], fmaf(8.f * s_z, Zd[bi], csum[bi]));
+    for (int bi = 0; bi < NB; ++bi) {
+      float U = C[bi][0][0];
+#pragma unroll
+      for (int c = 1; c < CC::N; ++c) U += C[bi][0][c];
+      const float zu = fmaf(e1, Zd[bi], e2 * U);
+#pragma unroll
+      for (int h = 0; h < NPH; ++h) {
+        float E = CC::K(0) * C[bi][h][0];
+#pragma unroll
+        for (int c = 1; c < CC::N; ++c) E = fmaf(CC::K(c), C[bi][h][c], E);
+        csum[bi][h] += fmaf(SCALE, E, zu);
+      }
+    }
 #pragma unroll
     for (int r = 0; r < TR; ++r) {
       float d[NB];
@@ -178,7 +310,8 @@ __device__ __forceinline__ void tile_fma(const TileRegs<W, TR, TC, AXIS>& t,
       for (int bi = 0; bi < NB; ++bi) d[bi] = acc[bi][r];
 #pragma unroll
       for (int p = 0; p < PPR; ++p) {
-        const half2_t q2 = as_half2(pair_f16<W>(t.c, r * PPR + p, k));
+        if constexpr (SHARED) refresh_shifted<W>(sw, t.c, r * PPR + p);
+        const half2_t q2 = as_half2(SHARED ? pair_class_f16<W>(t.c, sw, r * PPR + p, k) : pair_f16<W>(t.c, r * PPR + p, k1));
 #pragma unroll
         for (int bi = 0; bi < NB; ++bi) d[bi] = __builtin_amdgcn_fdot2(q2, as_half2(xp[bi][p]), d[bi], false);
       }
@@ -186,35 +319,50 @@ __device__ __forceinline__ void tile_fma(const TileRegs<W, TR, TC, AXIS>& t,
       for (int bi = 0; bi < NB; ++bi) acc[bi][r] = d[bi];
     }
   } else {
-    float X[NB];
+    float X[NB], SE[NB][NPH];
 #pragma unroll
     for (int bi = 0; bi < NB; ++bi) {
-      X[bi] = 0.f;
 #pragma unroll
-      for (int p = 0; p < PPR; ++p) X[bi] = __builtin_amdgcn_fdot2(as_half2(xp[bi][p]), ones, X[bi], false);
+      for (int p = 0; p < PPR; ++p) {
+#pragma unroll
+        for (int h = 0; h < NPH; ++h) {
+          const int c = CC::of_pair(h * PPR + p);
+          C[bi][h][c] = __builtin_amdgcn_fdot2(as_half2(xp[bi][p]), ones, C[bi][h][c], false);
+        }
+      }
+      X[bi] = C[bi][0][0];
+#pragma unroll
+      for (int c = 1; c < CC::N; ++c) X[bi] += C[bi][0][c];
+#pragma unroll
+      for (int h = 0; h < NPH; ++h) {
+        float E = CC::K(0) * C[bi][h][0];
+#pragma unroll
+        for (int c = 1; c < CC::N; ++c) E = fmaf(CC::K(c), C[bi][h][c], E);
+        SE[bi][h] = SCALE * E;
+      }
     }
-    // 2^W + z_hat = e1*(1 + z_q/8) + e2
-    const float e1 = 8.f * s_z, e2 = SCALE - s_z * z_z - e1;
 #pragma unroll
     for (int r2 = 0; r2 < TR / 2; ++r2) {
       const half2_t sq = as_half2(pair_f16<3>(t.s, r2, k3));
       const half2_t zq = as_half2(pair_f16<3>(t.s, T::B2 / 2 + r2, k3));
 #pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        const int r = 2 * r2 + h;
+      for (int h2 = 0; h2 < 2; ++h2) {
+        const int r = 2 * r2 + h2;
         float d[NB];
 #pragma unroll
         for (int bi = 0; bi < NB; ++bi) d[bi] = 0.f;
 #pragma unroll
         for (int p = 0; p < PPR; ++p) {
-          const half2_t q2 = as_half2(pair_f16<W>(t.c, r * PPR + p, k));
+          if constexpr (SHARED) refresh_shifted<W>(sw, t.c, r * PPR + p);
+          const half2_t q2 = as_half2(SHARED ? pair_class_f16<W>(t.c, sw, r * PPR + p, k) : pair_f16<W>(t.c, r * PPR + p, k1));
 #pragma unroll
           for (int bi = 0; bi < NB; ++bi) d[bi] = __builtin_amdgcn_fdot2(q2, as_half2(xp[bi][p]), d[bi], false);
         }
-        const float sh = fmaf((float)(h ? sq.y : sq.x), c1, c2);
-        const float zo = fmaf((float)(h ? zq.y : zq.x), e1, e2);
+        const float sh = fmaf((float)(h2 ? sq.y : sq.x), c1, c2);
+        const float zh = fmaf((float)(h2 ? zq.y : zq.x), e1, e2);      // z_hat_r
 #pragma unroll
-        for (int bi = 0; bi < NB; ++bi) acc[bi][r] = fmaf(sh, fmaf(SCALE, d[bi], -zo * X[bi]), acc[bi][r]);
+        for (int bi = 0; bi < NB; ++bi)
+          acc[bi][r] = fmaf(sh, fmaf(-zh, X[bi], fmaf(SCALE, d[bi], -SE[bi][r % NPH])), acc[bi][r]);   // big terms cancel first
       }
     }
   }
@@ -383,20 +531,24 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
   __syncthreads();                           // x is staged
 
   // ---- dense part -------------------------------------------------------------
-  float acc[NB][TR], csum[NB];
+  constexpr int NPH = RowPhases<W, TC>::N;
+  float acc[NB][TR], csum[NB][NPH];
 #pragma unroll
   for (int bi = 0; bi < NB; ++bi) {
-    csum[bi] = 0.f;
+#pragma unroll
+    for (int h = 0; h < NPH; ++h) csum[bi][h] = 0.f;
 #pragma unroll
     for (int r = 0; r < TR; ++r) acc[bi][r] = 0.f;
   }
-  const PairConsts kc = make_pair_consts<W>();
+  ClassConsts kc = {};
+  PairConsts k1 = {};
+  if constexpr (SharedShifts<TC>::value) kc = make_class_consts<W>(); else k1 = make_pair_consts<W>();
   const PairConsts k3 = make_pair_consts<3>();
   const uint32_t* xs32 = reinterpret_cast<const uint32_t*>(xs);
   const bool heavy = nchunks > nthreads;     // workgroup-uniform
 #define SPQR_TILE_FMA(t, L, st)                                                                           \
   tile_fma<W, TR, TC, AXIS, NB>(t, xs32 + (64 * (st) + min(lane, (L) - 1)) * (TC / 2), n >> 1, lane < (L), \
-                                acc, csum, kc, k3)
+                                acc, csum, kc, k1, k3)
   // Two steps per trip, registers ping-pong; the loop has its one exit at the
   // bottom (a second exit would be merged with it through a block that makes the
   // compiler wait for every load at the top of the loop).  t0 holds step `step`.
@@ -462,7 +614,7 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
   for (int bi = 0; bi < NB; ++bi) {
     if constexpr (AXIS == 1) {
 #pragma unroll
-      for (int r = 0; r < TR; ++r) acc[bi][r] = fmaf((float)(1 << W), acc[bi][r], -csum[bi]);
+      for (int r = 0; r < TR; ++r) acc[bi][r] = fmaf((float)(1 << W), acc[bi][r], -csum[bi][r % NPH]);
     }
     int row;
     const float rsum = wave_reduce_rows<TR>(acc[bi], lane, &row);

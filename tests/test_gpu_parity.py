@@ -153,14 +153,16 @@ def test_special_cases(P, axis):
     ref = orc.matvec_sparse_only(g, x)[0]
     assert rel_l2(y, ref) <= REL_L2
     # one-hot x extracts one column of W_hat.  With column groups the kernel
-    # rounds s_hat*x_j to binary16 once (relative 2^-11 of the dense part).
+    # rounds s_hat*x_j to binary16 once (relative 2^-11 of the dense part); the
+    # position-dependent code offsets (up to 128 against q/8) cancel in binary32
+    # and leave up to ~1e-5 of the column's scale.
     A = P.SpQRMatrix.from_logical(f)
     W = orc.reconstruct(f)
     D = orc.decode_dense(f)
     for j in (0, 17, f.n - 1):
         e = np.zeros(f.n, np.float16); e[j] = 1.0
         y = P.spqr_gemv(A, dev(e)).cpu().numpy()
-        assert np.all(np.abs(y - W[:, j]) <= 2.0 ** -11 * np.abs(D[:, j]) + 1e-6)
+        assert np.all(np.abs(y - W[:, j]) <= 2.0 ** -11 * np.abs(D[:, j]) + 2e-5 * np.max(np.abs(D[:, j])))
         assert rel_l2(y, W[:, j]) <= REL_L2
     # all-zero x
     y = P.spqr_gemv(A, dev(np.zeros(f.n, np.float16))).cpu().numpy()
