@@ -35,10 +35,11 @@ int to_device_matrix(const spqr_matrix_t* A, spqr::DevMatrix* D) {
 }
 
 // SPQR_FORCE_GENERIC=1 in the environment routes products through the
-// element-wise fallback kernel (used by tests to cover it on tuned shapes).
+// element-wise fallback kernel (tests cover it on tuned shapes this way); read
+// on every call.
 bool force_generic() {
-  static const bool v = [] { const char* e = std::getenv("SPQR_FORCE_GENERIC"); return e && e[0] == '1'; }();
-  return v;
+  const char* e = std::getenv("SPQR_FORCE_GENERIC");
+  return e && e[0] == '1';
 }
 
 }  // namespace

@@ -315,3 +315,20 @@ def test_fused_projections_with_a_shared_permutation(P):
     torch.cuda.synchronize()
     for f, y in zip(fs, ys):
         assert rel_l2(y.cpu().numpy(), orc.matvec(f, xh)[0]) <= REL_L2
+
+
+def test_fallback_kernel_agrees_with_the_tuned_one(P, monkeypatch):
+    """SPQR_FORCE_GENERIC=1 sends a tuned shape through the element-wise fallback kernel."""
+    f = make(3, 16, 16, 1, 2, 70, rate=0.03, structure="rows8cols4")
+    A = P.SpQRMatrix.from_logical(f)
+    X = synth.make_x(f.n, 3, seed=(67,))
+    ref = orc.matvec(f, X)
+    tuned = P.spqr_gemm_smallbatch(A, dev(X)).cpu().numpy()
+    monkeypatch.setenv("SPQR_FORCE_GENERIC", "1")
+    slow = P.spqr_gemm_smallbatch(A, dev(X)).cpu().numpy()
+    fused = [y.cpu().numpy() for y in P.spqr_gemv_fused([A, A], dev(X[0]))]
+    monkeypatch.delenv("SPQR_FORCE_GENERIC")
+    for k in range(3):
+        assert rel_l2(slow[k], ref[k]) <= 1e-5          # canonical binary32 decode, x used exactly
+        assert rel_l2(tuned[k], slow[k]) <= REL_L2
+    assert all(rel_l2(y, ref[0]) <= 1e-5 for y in fused)
