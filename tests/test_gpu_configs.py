@@ -120,3 +120,22 @@ def test_llama65b_shaped_config_resident_beside_filler(P):
         check_layer(P, f, (1,))
     finally:
         del filler
+
+
+def test_fused_projections_at_full_size(P):
+    """q/k/v and gate/up of the LLaMA-7B-shaped block in one launch each, against sampled oracle rows."""
+    import torch
+    specs = synth.config_layers(2)
+    for names in (("q", "k", "v"), ("gate", "up")):
+        idx = [i for i, sp in enumerate(specs) if sp.name in names]
+        fs = [synth.make_config_layer(2, i, group_axis=1) for i in idx]
+        As = [P.SpQRMatrix.from_logical(f) for f in fs]
+        X = synth.make_x(fs[0].n, 1, seed=(78, len(names)))
+        ys = P.spqr_gemv_fused(As, dev(X[0]))
+        torch.cuda.synchronize()
+        for f, y in zip(fs, ys):
+            rows = sample_rows(f)
+            ref = orc.matvec_rows(f, X, rows)[0]
+            got = y.cpu().numpy()[rows].astype(np.float64)
+            assert np.linalg.norm(got - ref) / np.linalg.norm(ref) <= REL_L2
+        del fs, As

@@ -332,3 +332,33 @@ def test_fallback_kernel_agrees_with_the_tuned_one(P, monkeypatch):
         assert rel_l2(slow[k], ref[k]) <= 1e-5          # canonical binary32 decode, x used exactly
         assert rel_l2(tuned[k], slow[k]) <= REL_L2
     assert all(rel_l2(y, ref[0]) <= 1e-5 for y in fused)
+
+
+def test_seeded_random_geometries_and_outlier_mixes(P):
+    """Many small seeded cases: every tuned tile shape and width, ragged blocks, one to many steps
+    per wavefront, batches 1-5, all outlier structures at rates from none to dense rows."""
+    import torch
+    rng = np.random.default_rng(20240607)
+    shapes = [(16, 16, 1), (16, 16, 0), (8, 32, 1), (8, 32, 0)]
+    structures = ["none", "uniform", "rows8cols4", "cols64", "zipf"]
+    worst = 0.0
+    for case in range(48):
+        b1, b2, axis = shapes[case % 4]
+        w = 3 + (case // 4) % 2
+        ntr = int(rng.integers(1, 5))
+        ntc = int(rng.choice([1, 3, 63, 64, 65, 127, 129, 200, 257, 515, 1030]))
+        st = structures[case % 5]
+        rate = 0.0 if st == "none" else float(rng.choice([0.002, 0.01, 0.05, 0.3]))
+        f = make(w, b1, b2, axis, ntr, ntc, rate=rate, structure=st, seed=(71, case))
+        A = P.SpQRMatrix.from_logical(f)
+        assert P.spqr_pack_check(A) == 0
+        b = int(rng.integers(1, 6))
+        X = synth.make_x(f.n, b, seed=(72, case))
+        ref = orc.matvec(f, X)
+        Y = (P.spqr_gemv(A, dev(X[0]))[None, :] if b == 1 else P.spqr_gemm_smallbatch(A, dev(X))).cpu().numpy()
+        torch.cuda.synchronize()
+        for k in range(b):
+            err = rel_l2(Y[k], ref[k])
+            worst = max(worst, err)
+            assert err <= REL_L2, (case, w, b1, b2, axis, ntr, ntc, st, rate, b, k, err)
+    assert worst > 0.0
