@@ -274,10 +274,21 @@ def main():
         b.record()
         torch.cuda.synchronize()
         us = a.elapsed_time(b) * 1e3 / (reps * args.copies)
+        # isolated launches: one event pair around every single launch (eager), pool rotation as above
+        iso = []
+        pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(240)]
+        for k, (e0, e1) in enumerate(pairs):
+            e0.record()
+            P.spqr_gemv(pool[li][k % args.copies], xs[li], out=ys[li])
+            e1.record()
+        torch.cuda.synchronize()
+        iso = sorted(e0.elapsed_time(e1) * 1e3 for e0, e1 in pairs[40:])
         per_layer[sp.name] = {"m": sp.m, "n": sp.n, "us": round(us, 3),
                               "compressed_MB": round(bytes_layer[li] / 1e6, 3),
                               "GBps": round(bytes_layer[li] / (us * 1e-6) / 1e9, 1),
-                              "frac_of_hbm_peak": round(bytes_layer[li] / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}
+                              "frac_of_hbm_peak": round(bytes_layer[li] / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+                              "isolated_us": {"p10": round(iso[len(iso) // 10], 2), "median": round(iso[len(iso) // 2], 2),
+                                              "p90": round(iso[9 * len(iso) // 10], 2)}}
 
     if args.sweep:
         run_sweep(args.sweep, P, synth, torch, dev)
