@@ -181,7 +181,16 @@ struct TileRegs {
   uint32_t s[SD];
 };
 
-template <int W, int TR, int TC, int AXIS>
+// STREAM: the tile is read once and not again soon (batch 1): load it past the
+// caches' retention (nontemporal).  Batches above 4 come back for the same tiles
+// one slice of vectors later and find them in the last-level cache otherwise.
+template <bool STREAM, typename V>
+__device__ __forceinline__ V load_once(const V* p) {
+  if constexpr (STREAM) return __builtin_nontemporal_load(p);
+  else return *p;
+}
+
+template <bool STREAM, int W, int TR, int TC, int AXIS>
 __device__ __forceinline__ void load_tile(TileRegs<W, TR, TC, AXIS>& t, const uint8_t* blk,
                                           int L, int lane) {
   using T = TileRegs<W, TR, TC, AXIS>;
@@ -189,16 +198,16 @@ __device__ __forceinline__ void load_tile(TileRegs<W, TR, TC, AXIS>& t, const ui
   const uint8_t* sb = blk + (int64_t)16 * T::KW * L;
 #pragma unroll
   for (int k = 0; k < T::SWF; ++k) {
-    u32x4 v = *reinterpret_cast<const u32x4*>(sb + ((int64_t)k * L + lane) * 16);
+    u32x4 v = load_once<STREAM>(reinterpret_cast<const u32x4*>(sb + ((int64_t)k * L + lane) * 16));
     t.s[4 * k] = v.x; t.s[4 * k + 1] = v.y; t.s[4 * k + 2] = v.z; t.s[4 * k + 3] = v.w;
   }
   const uint8_t* rb = sb + (int64_t)16 * T::SWF * L;
 #pragma unroll
   for (int k = 0; k < T::SR; ++k)
-    t.s[4 * T::SWF + k] = *reinterpret_cast<const uint32_t*>(rb + ((int64_t)k * L + lane) * 4);
+    t.s[4 * T::SWF + k] = load_once<STREAM>(reinterpret_cast<const uint32_t*>(rb + ((int64_t)k * L + lane) * 4));
 #pragma unroll
   for (int k = 0; k < T::KW; ++k) {
-    u32x4 v = *reinterpret_cast<const u32x4*>(blk + ((int64_t)k * L + lane) * 16);
+    u32x4 v = load_once<STREAM>(reinterpret_cast<const u32x4*>(blk + ((int64_t)k * L + lane) * 16));
     t.c[4 * k] = v.x; t.c[4 * k + 1] = v.y; t.c[4 * k + 2] = v.z; t.c[4 * k + 3] = v.w;
   }
 }
@@ -485,13 +494,13 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
   auto issue = [&](T& t, int st) -> int {    // returns the number of tiles in the step's block
     const bool real = st < nsteps;           // wave-uniform
     const int L = real ? min(64, ntc - 64 * st) : 1;
-    load_tile(t, strip_base + (int64_t)64 * (real ? st : 0) * TILE_BYTES, L, min(lane, L - 1));
+    load_tile<NB == 1>(t, strip_base + (int64_t)64 * (real ? st : 0) * TILE_BYTES, L, min(lane, L - 1));
     asm volatile("" ::: "memory");           // the loads stay here, ahead of the arithmetic on the other buffer
     return L;
   };
   int step = wave;                           // wave < nwaves <= nsteps: the first step always exists
   int L0 = min(64, ntc - 64 * step), L1 = 1;
-  load_tile(t0, strip_base + (int64_t)64 * step * TILE_BYTES, L0, min(lane, L0 - 1));
+  load_tile<NB == 1>(t0, strip_base + (int64_t)64 * step * TILE_BYTES, L0, min(lane, L0 - 1));
   __builtin_amdgcn_sched_barrier(0);
   rp[min(tid, TR)] = rp_mine;                // clamped duplicates store the same value again
 
@@ -525,8 +534,8 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
   {                                          // unconditional, like the tile loads: a thread without a chunk
     const bool have = tid < first_round;     // reads 16 bytes of the strip's first tile instead
     const u32x4* dummy = reinterpret_cast<const u32x4*>(strip_base);
-    pc = *(have ? col8 + c_lo + tid : dummy);
-    pv = *(have ? val8 + c_lo + tid : dummy);
+    pc = load_once<NB == 1>(have ? col8 + c_lo + tid : dummy);
+    pv = load_once<NB == 1>(have ? val8 + c_lo + tid : dummy);
   }
   __syncthreads();                           // x is staged
 
@@ -570,8 +579,8 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
     for (int k = 1; k < KR; ++k) {
       const int slot = tid + k * nthreads;
       const bool have = slot < chunk_cap && slot < nchunks;
-      lc[k - 1] = *(have ? col8 + c_lo + slot : dummy);
-      lv[k - 1] = *(have ? val8 + c_lo + slot : dummy);
+      lc[k - 1] = load_once<NB == 1>(have ? col8 + c_lo + slot : dummy);
+      lv[k - 1] = load_once<NB == 1>(have ? val8 + c_lo + slot : dummy);
     }
     asm volatile("" ::: "memory");
   }
@@ -583,7 +592,10 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
 #pragma unroll
     for (int k = KR; k < KMAX; ++k) {
       const int slot = tid + k * nthreads;
-      if (slot < chunk_cap && slot < nchunks) { lc[k - 1] = col8[c_lo + slot]; lv[k - 1] = val8[c_lo + slot]; }
+      if (slot < chunk_cap && slot < nchunks) {
+        lc[k - 1] = load_once<NB == 1>(col8 + c_lo + slot);
+        lv[k - 1] = load_once<NB == 1>(val8 + c_lo + slot);
+      }
     }
   }
   if (tid < first_round) {
@@ -693,7 +705,10 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
 #pragma unroll
       for (int k = 0; k < KMAX; ++k) {
         const int slot = tid + k * nthreads, j = c0 + slot;
-        if (slot < chunk_cap && j < c1) { cc[k] = col8[c_lo + j]; vv[k] = val8[c_lo + j]; }
+        if (slot < chunk_cap && j < c1) {
+          cc[k] = load_once<NB == 1>(col8 + c_lo + j);
+          vv[k] = load_once<NB == 1>(val8 + c_lo + j);
+        }
       }
 #pragma unroll
       for (int k = 0; k < KMAX; ++k) {
