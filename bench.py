@@ -25,7 +25,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch read back from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # command (scaled by a copy kernel of known size); None until measured.
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 22_074_000   # 22.03 MB fetched + 0.04 MB written, profiles/gemv_tile256_w3_16x16_axis1_config1.txt
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 22_064_000   # 22.02 MB fetched + 0.04 MB written, profiles/gemv_tile256_w3_16x16_axis1_config1.txt
 
 
 def algorithmic_bytes(A, batch=1):
