@@ -168,8 +168,19 @@ int spqr_pack_check(const spqr_matrix_t* A, uint32_t flags, void* stream);
 int spqr_gemv(const spqr_matrix_t* A, const uint16_t* x_f16, void* y, int y_dtype,
               void* stream);
 
-/* Y[b][m] = X[b][:] . W_hat^T for 1 <= b <= SPQR_MAX_BATCH; the weights are
- * read once per slice of up to 4 activation vectors.
+/* Y[b][m] = X[b][:] . W_hat^T for 1 <= b <= SPQR_MAX_BATCH (Sec. 4.2 dequantises
+ * to 16 bit and multiplies; the sparse part is a product of its own).
+ * Up to 4 vectors: one launch of the batch-1 kernel's NB-vector form.  More:
+ * either slices of up to 4 (weights read once per slice), or, for 16x16 tiles,
+ * binary32 output, perm == NULL and a batch / layer large enough to pay for it,
+ * the weights are read ONCE, dequantised to binary16 and multiplied on the
+ * matrix cores, then a second kernel adds the outliers.  That path takes
+ * (n+1)*32 + splits*b*m*4 bytes of device scratch from the stream's memory pool
+ * (hipMallocAsync / hipFreeAsync on `stream`, stream-ordered: safe with
+ * concurrent calls on other streams); if the pool refuses, the sliced path runs.
+ * SPQR_MFMA=0 or =1 in the environment forces one or the other where both apply.
+ * Results are deterministic (fixed summation order) on either path; the two
+ * differ by rounding only (both within the product tolerance).
  * X: [b][n] binary16 row-major.  Y: [b][m] of y_dtype, overwritten. */
 int spqr_gemm_smallbatch(const spqr_matrix_t* A, const uint16_t* X_f16, int b, void* Y,
                          int y_dtype, void* stream);

@@ -13,6 +13,7 @@
 //   workgroup, so y is written once, without atomics, in a fixed order.
 #include <hip/hip_runtime.h>
 #include <cstdlib>
+#include <type_traits>
 
 #include <algorithm>
 
@@ -781,6 +782,363 @@ gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restric
   gemv_tile256_body<W, TR, TC, AXIS, PERM, NB>(A, x, y, y_dtype, chunk_cap, blockIdx.x);
 }
 
+// ---------------------------------------------------------------------------
+// Batches above 4 on 16x16 tiles: the dense part on the matrix cores (weights
+// stream once for the whole batch), then a finishing kernel that adds the outliers.
+//
+// Dense part: P[split][b][rows] = X[b][cols of the split] . dequant(strip)^T in
+// binary32, no outliers.  A workgroup is 4 wavefronts = 4 consecutive strips that
+// walk the same steps of 64 tiles in lock-step, because they share the 16 x 1024
+// piece of X that belongs to the step: it is staged in LDS once per workgroup
+// (prefetched into registers one step ahead).  A lane still fetches one whole
+// tile (same loads, same layout as the GEMV).  An MFMA operand, though, wants
+// 16 rows x 4 columns across the 64 lanes, while here the lanes hold 64 different
+// tiles: so every lane dequantises its tile to binary16 (s_hat*(q - z_hat) evaluated
+// in binary32, one rounding -- the paper's kernel also "dequantizes to 16-bits",
+// Sec. 4.2) into its wavefront's LDS buffer, a quarter (4 columns) at a time to
+// keep the buffer small enough for two workgroups per CU.  One
+// v_mfma_f32_16x16x32_f16 then sums 8 tiles at once: its K index is (tile, column),
+// A: lane l = row l%16 of tiles 8j + 2(l/16) and the next, B: lane l = batch l%16, the
+// same two tiles' 4 columns of X; D[row][batch] accumulates over the whole column
+// range in 8 registers.
+// Batch rows beyond `batch` repeat the last one and are dropped at the end.
+// The steps of a matrix can be split over gridDim.y workgroups (few strips, many
+// columns); every split writes its own partial result.  If XT is given, the first
+// workgroup of every split also writes its pieces of X transposed for the finishing
+// kernel: XT[j][16] binary16, batch rows beyond `batch` zero, so that one outlier
+// (one column j) meets its 16 activations in one 32-byte line; line n is all zeros:
+// the place entry slots behind the end of a row read.
+// ---------------------------------------------------------------------------
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+constexpr int kMfmaStrips = 4;               // wavefronts = strips per workgroup
+constexpr int kMfmaTileStride = 36;          // dwords per tile quarter (16 rows x 8 bytes + 16: spreads the banks)
+constexpr int kMfmaXRow = 2048 + 8;          // bytes per batch row of the staged piece of X (514 dwords: rows 2 banks apart)
+constexpr size_t kMfmaLds = (size_t)kMfmaStrips * 64 * kMfmaTileStride * 4 + 16 * kMfmaXRow;
+static_assert(2 * (kMfmaLds + 1024) <= 160 * 1024, "two workgroups per CU");
+
+template <int W, int AXIS>
+__global__ void __launch_bounds__(64 * kMfmaStrips, 2)
+gemm_mfma16_kernel(DevMatrix A, const uint16_t* __restrict__ X, float* __restrict__ P, int64_t split_stride,
+                   int steps_per_split, int batch, uint16_t* __restrict__ XT) {
+  constexpr int TR = 16, TC = 16, PPR = TC / 2, S = kMfmaTileStride, NS = kMfmaStrips, NT = 64 * NS;
+  constexpr int UPT = 2048 / NT;             // 16-byte units of the X piece per thread
+  using T = TileRegs<W, TR, TC, AXIS>;
+  constexpr int TILE_BYTES = 16 * T::KW + 4 * T::SD;
+  constexpr float SCALE = (float)(1 << W);
+  extern __shared__ __align__(16) uint8_t smem[];
+  uint8_t* xbuf = smem + NS * 64 * S * 4;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n = A.g.n, ntc = A.g.ntc, m = A.g.m, ntr = A.g.ntr;
+  const int nsteps = (ntc + 63) >> 6;
+  const int s_lo = blockIdx.y * steps_per_split, s_hi = min(nsteps, s_lo + steps_per_split);   // never empty (host)
+  const int strip = blockIdx.x * NS + wave;
+  const bool active = strip < ntr;           // wave-uniform; an idle wavefront still stages X and meets the barriers
+  const uint8_t* strip_base = A.packed + (int64_t)min(strip, ntr - 1) * ntc * TILE_BYTES;
+  uint32_t* buf = reinterpret_cast<uint32_t*>(smem) + wave * 64 * S;
+  const int i16 = lane & 15, g4 = lane >> 4;
+  const PairConsts kc = make_pair_consts<W>();
+  const PairConsts k3 = make_pair_consts<3>();
+  float4_t D = {0.f, 0.f, 0.f, 0.f}, D1 = {0.f, 0.f, 0.f, 0.f};
+
+  // the piece of X of step st: unit u = 16 bytes = 8 columns of batch row u/128; loads unconditional (clamped)
+  u32x4 xr[UPT];
+  uint32_t xrow[UPT];                        // byte offset of the unit's (clamped) batch row in X
+#pragma unroll
+  for (int k = 0; k < UPT; ++k) xrow[k] = (uint32_t)min((tid + k * NT) >> 7, batch - 1) * (uint32_t)n * 2u;
+  const int xj = tid & 127;                  // NT is a multiple of 128: the unit's place in its row is the same for all k
+  auto fetch_x = [&](int st) {
+    const int sc = min(st, s_hi - 1);
+    const int L = min(64, ntc - 64 * sc);
+    const uint8_t* xs = reinterpret_cast<const uint8_t*>(X + (int64_t)1024 * sc);
+    const uint32_t jb = 16u * (uint32_t)min(xj, 2 * L - 1);
+#pragma unroll
+    for (int k = 0; k < UPT; ++k) xr[k] = *reinterpret_cast<const u32x4*>(xs + (xrow[k] + jb));
+    asm volatile("" ::: "memory");
+  };
+  auto store_x = [&](int st) {
+    const int L = min(64, ntc - 64 * st);
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+    // columns behind the last tile: zeros (finite), they meet zero weights
+    const bool keep = xj < 2 * L;
+#pragma unroll
+    for (int k = 0; k < UPT; ++k) {
+      const int b = (tid + k * NT) >> 7;
+      const u32x2 lo = {keep ? xr[k].x : 0u, keep ? xr[k].y : 0u}, hi = {keep ? xr[k].z : 0u, keep ? xr[k].w : 0u};
+      if (b < batch) {
+        u32x2* d = reinterpret_cast<u32x2*>(xbuf + b * kMfmaXRow + xj * 16);
+        d[0] = lo;
+        d[1] = hi;
+      }
+    }
+  };
+  auto issue = [&](T& t, int st) {
+    const bool real = st < s_hi;
+    const int L = real ? min(64, ntc - 64 * st) : 1;
+    load_tile<false>(t, strip_base + (int64_t)64 * (real ? st : s_lo) * TILE_BYTES, L, min(lane, L - 1));
+    asm volatile("" ::: "memory");
+  };
+  const uint32_t* afrag = buf + 2 * g4 * S + 2 * i16;
+  const uint32_t* xfrag = reinterpret_cast<const uint32_t*>(xbuf + min(i16, batch - 1) * kMfmaXRow) + 2 * g4 * (TC / 2);
+  // one step: publish its piece of X, then per quarter: dequantise 4 columns of this lane's tile, multiply
+  auto run_step = [&](const T& t, int st) {
+    const int L = min(64, ntc - 64 * st);
+    __syncthreads();                         // every wavefront is done with the previous piece of X
+    store_x(st);
+    fetch_x(st + 1);
+    __syncthreads();
+    if (XT != nullptr && blockIdx.x == 0) {  // the first workgroup of every split also writes the batch transposed
+#pragma unroll
+      for (int k = 0; k < 1024 / NT; ++k) {
+        const int c = tid + k * NT, j = 1024 * st + c;           // column c of the piece = column j of X
+        if (c < TC * L) {
+          uint32_t o[8];
+#pragma unroll
+          for (int q = 0; q < 8; ++q) {
+            const uint32_t lo = 2 * q < batch ? *reinterpret_cast<const uint16_t*>(xbuf + (2 * q) * kMfmaXRow + 2 * c) : 0u;
+            const uint32_t hi = 2 * q + 1 < batch ? *reinterpret_cast<const uint16_t*>(xbuf + (2 * q + 1) * kMfmaXRow + 2 * c) : 0u;
+            o[q] = lo | (hi << 16);
+          }
+          u32x4* d = reinterpret_cast<u32x4*>(XT + (int64_t)j * 16);
+          const u32x4 v0 = {o[0], o[1], o[2], o[3]}, v1 = {o[4], o[5], o[6], o[7]};
+          d[0] = v0;
+          d[1] = v1;
+        }
+      }
+      if (st == 0 && tid < 2) {              // the zero line behind the last column
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+        reinterpret_cast<u32x4*>(XT + (int64_t)n * 16)[tid] = zero;
+      }
+    }
+    const uint32_t a2 = t.s[T::SD - 2], b2 = t.s[T::SD - 1];
+    const float s_s = h2f((uint16_t)(a2 & 0xFFFF)), z_s = h2f((uint16_t)(a2 >> 16));
+    const float s_z = h2f((uint16_t)(b2 & 0xFFFF)), z_z = h2f((uint16_t)(b2 >> 16));
+    // w = s_hat*(q - z_hat) = fa*(1 + q/2^W) + fb with fa = 2^W*s_hat, fb = -s_hat*(2^W + z_hat), per group,
+    // where s_hat = s_s*(s_q - z_s) and z_hat = s_z*(z_q - z_z) and the extracted codes are 1 + code/8:
+    //   fa = c1*(1 + s_q/8) + c2,   -(2^W + z_hat)/2^W = e1*(1 + z_q/8) + e2,   fb = fa * that.
+    // A lane behind the step's last tile (its loads were clamped) writes a tile of zeros.
+    const bool live = lane < L;
+    const float c1 = live ? SCALE * 8.f * s_s : 0.f, c2 = live ? SCALE * (-s_s * z_s - 8.f * s_s) : 0.f;
+    const float e1 = -8.f * s_z / SCALE, e2 = -(SCALE - s_z * z_z - 8.f * s_z) / SCALE;
+    float fa[16], fb[16];
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+      const half2_t sq = as_half2(pair_f16<3>(t.s, p, k3));
+      const half2_t zq = as_half2(pair_f16<3>(t.s, 8 + p, k3));
+      fa[2 * p] = fmaf((float)sq.x, c1, c2);
+      fa[2 * p + 1] = fmaf((float)sq.y, c1, c2);
+      fb[2 * p] = fa[2 * p] * fmaf((float)zq.x, e1, e2);
+      fb[2 * p + 1] = fa[2 * p + 1] * fmaf((float)zq.y, e1, e2);
+    }
+    uint32_t* mine = buf + lane * S;
+#pragma unroll
+    for (int qd = 0; qd < 4; ++qd) {         // columns 4*qd .. 4*qd+3 of every tile
+#pragma unroll
+      for (int rr = 0; rr < TR / 2; ++rr) {
+        uint32_t o[4];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+#pragma unroll
+          for (int u = 0; u < 2; ++u) {
+            const int r = 2 * rr + h, p = 2 * qd + u;
+            const half2_t q2 = as_half2(pair_f16<W>(t.c, r * PPR + p, kc));
+            const int g0 = AXIS == 1 ? 2 * p : r, g1 = AXIS == 1 ? 2 * p + 1 : r;
+            half2_t w;
+            w.x = (_Float16)fmaf((float)q2.x, fa[g0], fb[g0]);
+            w.y = (_Float16)fmaf((float)q2.y, fa[g1], fb[g1]);
+            o[2 * h + u] = __builtin_bit_cast(uint32_t, w);
+          }
+        }
+        const u32x4 v = {o[0], o[1], o[2], o[3]};
+        *reinterpret_cast<u32x4*>(mine + 4 * rr) = v;        // rows 2rr and 2rr+1, 8 bytes each
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();       // the buffer is this wavefront's own: its LDS operations stay in order
+      uint32_t av[8][4], bv[8][4];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {          // tiles 8j .. 8j+7, two per 16 lanes
+        const uint32_t* pa = afrag + 8 * j * S;
+        const uint32_t* pb = xfrag + 8 * j * (TC / 2) + 2 * qd;
+        av[j][0] = pa[0]; av[j][1] = pa[1]; av[j][2] = pa[S]; av[j][3] = pa[S + 1];
+        bv[j][0] = pb[0]; bv[j][1] = pb[1]; bv[j][2] = pb[TC / 2]; bv[j][3] = pb[TC / 2 + 1];
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const uint32_t a4v[4] = {av[j][0], av[j][1], av[j][2], av[j][3]}, b4v[4] = {bv[j][0], bv[j][1], bv[j][2], bv[j][3]};
+        if (j & 1)
+          D1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, a4v), __builtin_bit_cast(half8_t, b4v), D1, 0, 0, 0);
+        else
+          D = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, a4v), __builtin_bit_cast(half8_t, b4v), D, 0, 0, 0);
+      }
+      __builtin_amdgcn_wave_barrier();       // the reads are issued before the next quarter overwrites the buffer
+    }
+  };
+
+  T t0, t1;
+  fetch_x(s_lo);
+  issue(t0, s_lo);
+  int st = s_lo;
+  while (st + 1 < s_hi) {                    // workgroup-uniform; two steps per trip, one exit at the bottom
+    issue(t1, st + 1);
+    run_step(t0, st);
+    issue(t0, st + 2);                       // a dummy behind the last step
+    run_step(t1, st + 1);
+    st += 2;
+  }
+  if (st < s_hi) run_step(t0, st);
+
+  // D[row 4*g4 + v][batch i16]
+  D += D1;
+  if (active && i16 < batch)
+    *reinterpret_cast<float4_t*>(P + (int64_t)blockIdx.y * split_stride + (int64_t)i16 * m + (int64_t)strip * TR + 4 * g4) = D;
+}
+
+// value of lane J (0 or 1) of the caller's pair of lanes, for both lanes of the pair
+template <int J>
+__device__ __forceinline__ uint32_t pair_broadcast(uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, J == 0 ? 0xA0 : 0xF5, 0xF, 0xF, false);   // quad_perm [J,J,2+J,2+J]
+}
+
+// Finishing kernel for up to 16 activation vectors:
+// Y[b][i] = sum_split P[split][b][i] + sum_k val_k * X[b][col_k]  (Sec. 4.2: the sparse
+// part is a separate product).  With one split P may be Y itself.
+// One workgroup of 512 threads per strip of 16 rows.  The strip's CSR entries pass
+// through LDS in chunks of 4096: every thread brings one aligned granule of 8
+// entries (the next chunk's is in flight meanwhile).  A pair of lanes works on one
+// part of one row, each lane on 8 of the 16 activation vectors (16 bytes of the
+// entry's line of XT), so no reduction across lanes exists: the pair walks its
+// entries in order, 4 per trip (each lane reads 2 of them from LDS and hands them to
+// its partner).  A row is cut into 16 contiguous parts (256 pairs = 16 rows x 16); a
+// row longer than LONG_ROW is dealt round-robin, two entries at a time, to all 256
+// pairs instead.  Parts are added in order by the row's owner: fixed order, one
+// writer per output.
+constexpr int kFinishThreads = 512;
+
+__global__ void __launch_bounds__(kFinishThreads, 8)
+finish_xt16_kernel(DevMatrix A, const uint16_t* __restrict__ XT, const float* P, int nsplit, int64_t split_stride,
+                   float* Y, int batch) {
+  constexpr int TR = 16, LONG_ROW = 512, NP = kFinishThreads / 2, PER_ROW = NP / TR, CHUNK = 8 * kFinishThreads;
+  constexpr int NG = kFinishThreads / 16;
+  __shared__ int rp[TR + 1];
+  __shared__ float part[NP][16];
+  __shared__ float part2[NG][16];
+  __shared__ __align__(16) uint16_t scol[CHUNK], sval[CHUNK];
+  const int tid = threadIdx.x, pr = tid >> 1, bq = tid & 1;
+  const int g = tid >> 4, b = tid & 15;      // the owner of Y[b][row g] for tid < 256
+  const int s = blockIdx.x, m = A.g.m;
+  if (tid <= TR) rp[tid] = A.row_ptr[s * TR + tid];
+  // the dense part of this thread's output: requested now, needed at the very end
+  const int64_t at = (int64_t)min(b, batch - 1) * m + (int64_t)s * TR + min(g, TR - 1);
+  float dense = 0.f;
+  for (int k = 0; k < nsplit; ++k) dense += P[k * split_stride + at];
+  __syncthreads();
+  const int e_lo = rp[0], e_hi = rp[TR];
+  if (nsplit == 1 && e_hi == e_lo) return;   // nothing to add (workgroup-uniform)
+  const uint8_t* xt16 = reinterpret_cast<const uint8_t*>(XT) + 16 * bq;
+  const uint32_t zoff = (uint32_t)A.g.n * 32u;
+  // Both lanes of the pair add the 4 entries at chunk positions i0 + bq and i0 + stride + bq (global index e0 + i),
+  // those inside [lo, hi) (hi never beyond the chunk); the others read the zero line of XT with value 0.
+  auto consume = [&](int e0, int i0, int stride, int lo, int hi, float (&acc)[8]) {
+    uint32_t off[2], val[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int i = i0 + h * stride + bq, e = e0 + i;
+      const bool ok = e >= lo && e < hi;
+      const int ic = min(i, CHUNK - 1);
+      off[h] = ok ? (uint32_t)scol[ic] * 32u : zoff;
+      val[h] = ok ? __builtin_bit_cast(uint32_t, h2f(sval[ic])) : 0u;
+    }
+    u32x4 xx[4];
+    float vv[4];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const uint32_t o[2] = {pair_broadcast<0>(off[h]), pair_broadcast<1>(off[h])};
+      const uint32_t v[2] = {pair_broadcast<0>(val[h]), pair_broadcast<1>(val[h])};
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        xx[2 * h + j] = *reinterpret_cast<const u32x4*>(xt16 + o[j]);
+        vv[2 * h + j] = __builtin_bit_cast(float, v[j]);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t w[4] = {xx[i].x, xx[i].y, xx[i].z, xx[i].w};
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        acc[2 * k] = fmaf(vv[i], h2f((uint16_t)(w[k] & 0xFFFFu)), acc[2 * k]);
+        acc[2 * k + 1] = fmaf(vv[i], h2f((uint16_t)(w[k] >> 16)), acc[2 * k + 1]);
+      }
+    }
+  };
+  float sum = 0.f;
+  if (e_hi > e_lo) {
+    const u32x4* col8 = reinterpret_cast<const u32x4*>(A.col);
+    const u32x4* val8 = reinterpret_cast<const u32x4*>(A.val);
+    const int g_lo = e_lo >> 3, ngran = ((e_hi - 1) >> 3) - g_lo + 1;
+    const u32x4 none = {0u, 0u, 0u, 0u};
+    u32x4 nc = tid < ngran ? col8[g_lo + tid] : none, nv = tid < ngran ? val8[g_lo + tid] : none;
+    // this pair's part of an ordinary row
+    const int my_r = pr / PER_ROW;
+    int a, z;
+    {
+      const int lo = rp[my_r], hi = rp[my_r + 1], len = hi - lo;
+      const int per = (len + PER_ROW - 1) / PER_ROW;
+      a = min(lo + (pr % PER_ROW) * per, hi);
+      z = len <= LONG_ROW ? min(a + per, hi) : a;
+    }
+    float acc[8], accl[8];                   // of the ordinary part, of the long row in progress
+#pragma unroll
+    for (int k = 0; k < 8; ++k) { acc[k] = 0.f; accl[k] = 0.f; }
+    for (int ch = 0; ch * kFinishThreads < ngran; ++ch) {         // workgroup-uniform
+      __syncthreads();                       // the previous chunk is consumed
+      reinterpret_cast<u32x4*>(scol)[tid] = nc;
+      reinterpret_cast<u32x4*>(sval)[tid] = nv;
+      __syncthreads();
+      const int gn = (ch + 1) * kFinishThreads + tid;
+      nc = gn < ngran ? col8[g_lo + gn] : none;
+      nv = gn < ngran ? val8[g_lo + gn] : none;
+      const int e0 = 8 * (g_lo + ch * kFinishThreads), e1 = e0 + CHUNK;   // the chunk's entries
+      // ordinary rows: what this chunk holds of the pair's part, 4 entries per trip
+      for (int e = max(a, e0); e < min(z, e1); e += 4) consume(e0, e - e0, 2, a, min(z, e1), acc);
+      // long rows that reach into this chunk, one after the other (uniform)
+      for (int r = 0; r < TR; ++r) {
+        const int lo = rp[r], hi = rp[r + 1];
+        if (hi - lo <= LONG_ROW || hi <= e0 || lo >= e1) continue;
+        const int i_lo = max(lo, e0) - e0, i_hi = min(hi, e1) - e0;
+        for (int i0 = (i_lo & ~1) + 2 * pr; i0 < i_hi; i0 += 4 * NP) consume(e0, i0, 2 * NP, lo, min(hi, e1), accl);
+        if (hi <= e1) {                      // the row ends here: add its 256 parts in two levels
+          __syncthreads();                   // the previous parts are consumed
+#pragma unroll
+          for (int k2 = 0; k2 < 8; ++k2) { part[pr][8 * bq + k2] = accl[k2]; accl[k2] = 0.f; }
+          __syncthreads();
+          float t = 0.f;
+#pragma unroll
+          for (int k = 0; k < NP / NG; ++k) t += part[g * (NP / NG) + k][b];
+          part2[g][b] = t;
+          __syncthreads();
+          if (g == r) {
+            t = 0.f;
+#pragma unroll
+            for (int k = 0; k < NG; ++k) t += part2[k][b];
+            sum = t;
+          }
+        }
+      }
+    }
+    __syncthreads();                         // the long rows' parts are consumed
+#pragma unroll
+    for (int k2 = 0; k2 < 8; ++k2) part[pr][8 * bq + k2] = acc[k2];
+    __syncthreads();
+    if (g < TR && rp[g + 1] - rp[g] <= LONG_ROW) {
+#pragma unroll
+      for (int k = 0; k < PER_ROW; ++k) sum += part[g * PER_ROW + k][b];
+    }
+  }
+  if (g < TR && b < batch && (rp[g + 1] > rp[g] || nsplit > 1)) Y[at] = dense + sum;
+}
+
 // Several matrices that share the input vector and the format (q/k/v, gate/up of
 // a decoder block) in one grid: strips [first[i], first[i+1]) belong to matrix i.
 // Every workgroup does exactly what it would do in a launch of its own matrix.
@@ -1076,12 +1434,102 @@ static hipError_t launch_tuned(const DevMatrix& A, const uint16_t* x, void* y, i
   return hipErrorInvalidValue;
 }
 
-// Y[b][m] = X[b][n] . W_hat^T.  The tuned kernel takes up to 4 activation vectors
-// per launch (weights stream once per launch); larger batches go in slices of 4.
+// ---- batches above 4 on 16x16 tiles: matrix-core dense pass + outlier pass ----
+// Steps per workgroup of the dense pass.  The chip holds two workgroups per CU at a
+// time; a workgroup costs its steps plus a start-up of about 0.7 step, a round of
+// workgroups that leaves half of the CUs with one workgroup runs its steps faster,
+// and every further split costs a partial result to write and read.  Ties go to
+// fewer splits.
+static int mfma_steps_per_split(int groups, int nsteps) {
+  const int slots = 2 * kCUs;
+  int best = nsteps;
+  double best_cost = 1e30;
+  for (int s = nsteps; s >= 1; --s) {
+    const int nsplit = (nsteps + s - 1) / s;
+    const long wgs = (long)groups * nsplit;
+    const long full = wgs / slots, rest = wgs % slots;
+    const double rounds = (double)full + (rest == 0 ? 0.0 : (rest > slots / 2 ? 1.0 : 0.6));
+    const double cost = rounds * (s + 0.7) + 0.05 * nsplit;
+    if (cost < best_cost - 1e-9) { best_cost = cost; best = s; }
+  }
+  return best;
+}
+
+// Dense pass and finishing pass.  Scratch (the batch transposed, n x 32 bytes, and the
+// partial results when the steps are split) is taken from and returned to the
+// stream's memory pool.  hipErrorNotSupported = no pool here; the caller takes the vector path.
+template <int W, int AXIS>
+static hipError_t launch_mfma16(const DevMatrix& A, const uint16_t* X, int b, float* Y, hipStream_t stream) {
+  const Geometry& g = A.g;
+  static bool ready = false;
+  if (!ready) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma16_kernel<W, AXIS>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMfmaLds);
+    if (e != hipSuccess) return e;
+    ready = true;
+  }
+  const int groups = (g.ntr + kMfmaStrips - 1) / kMfmaStrips;
+  const int nsteps = (g.ntc + 63) / 64;
+  const int steps_per_split = mfma_steps_per_split(groups, nsteps);
+  const int nsplit = (nsteps + steps_per_split - 1) / steps_per_split;
+  const bool sparse = A.nnz > 0;
+  const size_t xt_bytes = sparse ? ((size_t)g.n + 1) * 32 : 0;   // one more row: zeros
+  const size_t part_bytes = nsplit > 1 ? (size_t)nsplit * b * g.m * sizeof(float) : 0;
+  uint8_t* scratch = nullptr;
+  if (xt_bytes + part_bytes > 0) {
+    if (hipMallocAsync(reinterpret_cast<void**>(&scratch), xt_bytes + part_bytes, stream) != hipSuccess) {
+      (void)hipGetLastError();
+      return hipErrorNotSupported;
+    }
+  }
+  uint16_t* xt = reinterpret_cast<uint16_t*>(scratch);
+  float* part = nsplit > 1 ? reinterpret_cast<float*>(scratch + xt_bytes) : Y;
+  const int64_t split_stride = (int64_t)b * g.m;
+  hipLaunchKernelGGL((gemm_mfma16_kernel<W, AXIS>), dim3(groups, nsplit), dim3(64 * kMfmaStrips), kMfmaLds, stream,
+                     A, X, part, split_stride, steps_per_split, b, sparse ? xt : nullptr);
+  hipError_t e = hipGetLastError();
+  if (e == hipSuccess && (sparse || nsplit > 1)) {
+    hipLaunchKernelGGL(finish_xt16_kernel, dim3(g.ntr), dim3(kFinishThreads), 0, stream, A, xt, part, nsplit, split_stride, Y, b);
+    e = hipGetLastError();
+  }
+  if (scratch != nullptr) {
+    const hipError_t ef = hipFreeAsync(scratch, stream);
+    if (e == hipSuccess) e = ef;
+  }
+  return e;
+}
+
+// Whether a batch of b > 4 vectors takes the matrix-core path.  It pays one more launch and the
+// transposition through LDS, the vector path re-reads the weights once per 4 vectors: measured
+// on MI355X the matrix cores win from 12 vectors on for any layer, from 8 on for layers of 40 M
+// weights and from 5 on for layers of 100 M.  SPQR_MFMA=0 / =1 in the environment (read per
+// call) forces the vector / the matrix-core path wherever it applies (tests compare the two).
+static bool mfma_wanted(const Geometry& g, int b) {
+  const char* e = std::getenv("SPQR_MFMA");
+  if (e && e[0] == '0') return false;
+  if (e && e[0] == '1') return true;
+  const double weights = (double)g.m * (double)g.n;
+  return b >= 12 || (b >= 8 && weights >= 40e6) || weights >= 100e6;
+}
+
+// Y[b][m] = X[b][n] . W_hat^T.  Up to 4 activation vectors: the tuned vector
+// kernel, all of them in one launch.  More, on 16x16 tiles and where it pays: the
+// dense part on the matrix cores (weights stream once), then the finishing kernel
+// with the outliers.  Else slices of 4.
 hipError_t launch_gemm(const DevMatrix& A, const uint16_t* X, int b, void* Y, int y_dtype,
                        hipStream_t stream, bool force_generic) {
   const Geometry& g = A.g;
   const size_t ysz = y_dtype == SPQR_F32 ? 4 : 2;
+  if (b > 4 && !force_generic && y_dtype == SPQR_F32 && A.perm == nullptr && g.tile_rows == 16 &&
+      g.tile_cols == 16 && (g.w_bits == 3 || g.w_bits == 4) && mfma_wanted(g, b)) {
+    float* Yf = static_cast<float*>(Y);
+    hipError_t e = hipErrorNotSupported;
+    if (g.w_bits == 3 && g.axis == 1) e = launch_mfma16<3, 1>(A, X, b, Yf, stream);
+    else if (g.w_bits == 3 && g.axis == 0) e = launch_mfma16<3, 0>(A, X, b, Yf, stream);
+    else if (g.w_bits == 4 && g.axis == 1) e = launch_mfma16<4, 1>(A, X, b, Yf, stream);
+    else if (g.w_bits == 4 && g.axis == 0) e = launch_mfma16<4, 0>(A, X, b, Yf, stream);
+    if (e != hipErrorNotSupported) return e;
+  }
   int k = 0;
   while (k < b) {
     const uint16_t* xk = X + (size_t)k * g.n;
