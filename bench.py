@@ -149,6 +149,32 @@ def run_sweep(path, P, synth, torch, dev):
         json.dump(rows, fh, indent=1)
 
 
+def run_batch_probe(b, P, synth, torch, dev, axis):
+    """spqr_gemm_smallbatch at batch b on every distinct layer of configuration 3: the library's choice of path
+    against the vector path forced through the environment (read per call by the library)."""
+    rows, seen = [], set()
+    for li, sp in enumerate(synth.config_layers(3)):
+        if (sp.m, sp.n) in seen:
+            continue
+        seen.add((sp.m, sp.n))
+        f = synth.make_config_layer(3, li, group_axis=axis)
+        A = P.SpQRMatrix.from_logical(f, dev)
+        del f
+        copies = max(2, int(600e6 // A.compressed_bytes()) + 1)
+        X = torch.from_numpy(synth.make_x(sp.n, b, seed=(3, li, b))).to(dev)
+        us = time_layer(P, torch, A, X, copies)
+        os.environ["SPQR_MFMA"] = "0"
+        us_vec = time_layer(P, torch, A, X, copies)
+        del os.environ["SPQR_MFMA"]
+        nbytes = algorithmic_bytes(A, b)
+        rows.append({"layer": sp.name, "m": sp.m, "n": sp.n, "batch": b, "us": round(us, 2),
+                     "us_vector_path": round(us_vec, 2), "GBps": round(nbytes / us / 1e3, 1),
+                     "dense_TFLOPs": round(2.0 * sp.m * sp.n * b / us / 1e6, 2)})
+        del A
+        torch.cuda.empty_cache()
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -161,6 +187,9 @@ def main():
     ap.add_argument("--sweep", metavar="PATH", default=None,
                     help="also time every distinct layer of all five configurations (both group orientations, "
                          "the batch sizes each configuration names) and write the table as JSON to PATH")
+    ap.add_argument("--batch-probe", type=int, default=0, metavar="B",
+                    help="also time spqr_gemm_smallbatch at batch B on the distinct layers of configuration 3, on the "
+                         "path the library picks and on the vector path (SPQR_MFMA=0); adds \"batch_probe\" to the line")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run three 64 MiB device copies (a kernel of known traffic, for scaling rocprofv3 counters)")
     args = ap.parse_args()
@@ -293,6 +322,10 @@ def main():
     if args.sweep:
         run_sweep(args.sweep, P, synth, torch, dev)
 
+    batch_probe = None
+    if args.batch_probe:
+        batch_probe = run_batch_probe(args.batch_probe, P, synth, torch, dev, args.group_axis)
+
     if args.calibrate:
         src = torch.empty(64 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
         dst = torch.empty_like(src)
@@ -345,6 +378,8 @@ def main():
                      "avg_launch_us": round(avg_launch_s * 1e6, 3)},
         "cpu_baseline": cpu,
     }
+    if batch_probe is not None:
+        out["batch_probe"] = batch_probe
     print(json.dumps(out))
 
 

@@ -1441,6 +1441,10 @@ static hipError_t launch_tuned(const DevMatrix& A, const uint16_t* x, void* y, i
 // and every further split costs a partial result to write and read.  Ties go to
 // fewer splits.
 static int mfma_steps_per_split(int groups, int nsteps) {
+  if (const char* e = std::getenv("SPQR_MFMA_STEPS")) {        // pins it for tuning runs
+    const int v = std::atoi(e);
+    if (v >= 1) return v < nsteps ? v : nsteps;
+  }
   const int slots = 2 * kCUs;
   int best = nsteps;
   double best_cost = 1e30;
