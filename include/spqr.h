@@ -175,7 +175,7 @@ int spqr_gemv(const spqr_matrix_t* A, const uint16_t* x_f16, void* y, int y_dtyp
  * binary32 output, perm == NULL and a batch / layer large enough to pay for it,
  * the weights are read ONCE, dequantised to binary16 and multiplied on the
  * matrix cores, then a second kernel adds the outliers.  That path takes
- * (n+1)*32 + splits*b*m*4 bytes of device scratch from the stream's memory pool
+ * (n+1)*32 + (nnz/512 + 2)*64 + splits*b*m*4 bytes of device scratch from the stream's memory pool
  * (hipMallocAsync / hipFreeAsync on `stream`, stream-ordered: safe with
  * concurrent calls on other streams); if the pool refuses, the sliced path runs.
  * SPQR_MFMA=0 or =1 in the environment forces one or the other where both apply.

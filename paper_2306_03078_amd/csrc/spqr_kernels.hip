@@ -803,11 +803,8 @@ gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restric
 // range in 8 registers.
 // Batch rows beyond `batch` repeat the last one and are dropped at the end.
 // The steps of a matrix can be split over gridDim.y workgroups (few strips, many
-// columns); every split writes its own partial result.  If XT is given, the first
-// workgroup of every split also writes its pieces of X transposed for the finishing
-// kernel: XT[j][16] binary16, batch rows beyond `batch` zero, so that one outlier
-// (one column j) meets its 16 activations in one 32-byte line; line n is all zeros:
-// the place entry slots behind the end of a row read.
+// columns); every split writes its own partial result.  Workgroups behind the
+// dense ones (blockIdx.x >= groups) take the long outlier rows, see long_rows_block.
 // ---------------------------------------------------------------------------
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float float4_t __attribute__((ext_vector_type(4)));
@@ -817,10 +814,96 @@ constexpr int kMfmaXRow = 2048 + 8;          // bytes per batch row of the stage
 constexpr size_t kMfmaLds = (size_t)kMfmaStrips * 64 * kMfmaTileStride * 4 + 16 * kMfmaXRow;
 static_assert(2 * (kMfmaLds + 1024) <= 160 * 1024, "two workgroups per CU");
 
+// Outlier rows longer than kLongRow entries, for the batch path.  Such a row would keep the one CU that owns its
+// strip busy long after the others are done (every outlier is an L1 line look-up), so these rows are taken out of
+// the finishing kernel: extra workgroups of the dense kernel's grid (they run beside the dense workgroups and need
+// nothing from them) own a range of rows each, kLongParts of them the same range: they pick the long rows and
+// write, every kLongParts-th slice of kLongSlice entries each,
+// sum_k val_k * XT[col_k][b] for the 16 vectors
+// to slots[lo / kSlotGrain + k][16] for slice k of the row that starts at entry lo -- a long row has fewer slices
+// than multiples of kSlotGrain among its entry indices, so the slots of different rows never meet and the finishing
+// kernel finds them without a search.  A thread takes every NT-th entry of the slice (consecutive threads read
+// consecutive entries) with its whole 32-byte line of XT; the 16 sums are reduced over the lanes in a fixed order.
+constexpr int kLongRow = 512, kLongSlice = 2048, kLongParts = 4, kSlotGrain = 512;
+
+template <int NT>
+__device__ __forceinline__ void long_rows_block(const DevMatrix& A, const uint16_t* __restrict__ XT,
+                                                float* __restrict__ slots, int wg, int nwg, int part, int nparts,
+                                                uint8_t* smem) {
+  constexpr int EPT = kLongSlice / NT, NW = NT / 64;
+  int* rpl = reinterpret_cast<int*>(smem);                                   // NT row pointers
+  uint32_t* masks = reinterpret_cast<uint32_t*>(smem + 4 * NT);              // 2 per wavefront
+  float (*lred)[16] = reinterpret_cast<float (*)[16]>(smem + 4 * NT + 8 * NW);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int m = A.g.m;
+  const uint32_t zoff = (uint32_t)A.g.n * 32u;                               // the zero line of XT
+  const int rows_per = (m + nwg - 1) / nwg;                                  // < NT (host)
+  const int r0 = wg * rows_per, nrows = min(rows_per, m - r0);
+  if (nrows <= 0) return;                                                    // workgroup-uniform
+  if (tid <= nrows) rpl[tid] = A.row_ptr[r0 + tid];
+  __syncthreads();
+  const bool is_long = tid < nrows && rpl[min(tid, NT - 2) + 1] - rpl[min(tid, NT - 2)] > kLongRow;
+  const uint64_t bal = __builtin_amdgcn_ballot_w64(is_long);
+  if (lane == 0) { masks[2 * wave] = (uint32_t)bal; masks[2 * wave + 1] = (uint32_t)(bal >> 32); }
+  __syncthreads();
+  for (int w = 0; w < NW; ++w) {
+    uint64_t mask = (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)masks[2 * w]) |      // no sign extension
+                    ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)masks[2 * w + 1]) << 32);
+    while (mask) {                                                           // workgroup-uniform
+      const int r = 64 * w + __builtin_ctzll(mask);
+      mask &= mask - 1;
+      const int lo = rpl[r], hi = rpl[r + 1];
+      // slice k of row r goes to the workgroup with part == (k + r) % nparts: rows of one slice spread out too
+      for (int e0 = lo + ((part + nparts - r % nparts) % nparts) * kLongSlice; e0 < hi; e0 += nparts * kLongSlice) {
+        // all of the thread's entries first, then their lines of XT, then the arithmetic: one round trip each
+        uint32_t off[EPT];
+        float val[EPT];
+#pragma unroll
+        for (int i = 0; i < EPT; ++i) {
+          const int e = e0 + tid + NT * i;
+          const bool ok = e < hi;
+          off[i] = ok ? (uint32_t)A.col[e] * 32u : zoff;
+          val[i] = ok ? h2f(A.val[e]) : 0.f;
+        }
+        u32x4 x0[EPT], x1[EPT];
+#pragma unroll
+        for (int i = 0; i < EPT; ++i) {
+          const u32x4* line = reinterpret_cast<const u32x4*>(reinterpret_cast<const uint8_t*>(XT) + off[i]);
+          x0[i] = line[0];
+          x1[i] = line[1];
+        }
+        float acc[16];
+#pragma unroll
+        for (int b = 0; b < 16; ++b) acc[b] = 0.f;
+#pragma unroll
+        for (int i = 0; i < EPT; ++i) {
+          const uint32_t w[8] = {x0[i].x, x0[i].y, x0[i].z, x0[i].w, x1[i].x, x1[i].y, x1[i].z, x1[i].w};
+#pragma unroll
+          for (int k = 0; k < 8; ++k) {
+            acc[2 * k] = fmaf(val[i], h2f((uint16_t)(w[k] & 0xFFFFu)), acc[2 * k]);
+            acc[2 * k + 1] = fmaf(val[i], h2f((uint16_t)(w[k] >> 16)), acc[2 * k + 1]);
+          }
+        }
+        int row;
+        const float red = wave_reduce_rows<16>(acc, lane, &row);             // sum over the lanes of vector `row`
+        __syncthreads();                                                     // the previous slice's partials are consumed
+        lred[wave][row] = red;
+        __syncthreads();
+        if (tid < 16) {
+          float t = 0.f;
+#pragma unroll
+          for (int k = 0; k < NW; ++k) t += lred[k][tid];
+          slots[(int64_t)(lo / kSlotGrain + (e0 - lo) / kLongSlice) * 16 + tid] = t;
+        }
+      }
+    }
+  }
+}
+
 template <int W, int AXIS>
 __global__ void __launch_bounds__(64 * kMfmaStrips, 2)
 gemm_mfma16_kernel(DevMatrix A, const uint16_t* __restrict__ X, float* __restrict__ P, int64_t split_stride,
-                   int steps_per_split, int batch, uint16_t* __restrict__ XT) {
+                   int steps_per_split, int batch, const uint16_t* __restrict__ XT, float* __restrict__ slots, int groups) {
   constexpr int TR = 16, TC = 16, PPR = TC / 2, S = kMfmaTileStride, NS = kMfmaStrips, NT = 64 * NS;
   constexpr int UPT = 2048 / NT;             // 16-byte units of the X piece per thread
   using T = TileRegs<W, TR, TC, AXIS>;
@@ -828,6 +911,13 @@ gemm_mfma16_kernel(DevMatrix A, const uint16_t* __restrict__ X, float* __restric
   constexpr float SCALE = (float)(1 << W);
   extern __shared__ __align__(16) uint8_t smem[];
   uint8_t* xbuf = smem + NS * 64 * S * 4;
+  if ((int)blockIdx.x >= groups) {           // the workgroups behind the dense ones: long outlier rows
+    if (blockIdx.y == 0) {
+      const int idx = (int)blockIdx.x - groups, nidx = (int)gridDim.x - groups;
+      long_rows_block<NT>(A, XT, slots, idx / kLongParts, nidx / kLongParts, idx % kLongParts, kLongParts, smem);
+    }
+    return;
+  }
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -889,29 +979,6 @@ gemm_mfma16_kernel(DevMatrix A, const uint16_t* __restrict__ X, float* __restric
     store_x(st);
     fetch_x(st + 1);
     __syncthreads();
-    if (XT != nullptr && blockIdx.x == 0) {  // the first workgroup of every split also writes the batch transposed
-#pragma unroll
-      for (int k = 0; k < 1024 / NT; ++k) {
-        const int c = tid + k * NT, j = 1024 * st + c;           // column c of the piece = column j of X
-        if (c < TC * L) {
-          uint32_t o[8];
-#pragma unroll
-          for (int q = 0; q < 8; ++q) {
-            const uint32_t lo = 2 * q < batch ? *reinterpret_cast<const uint16_t*>(xbuf + (2 * q) * kMfmaXRow + 2 * c) : 0u;
-            const uint32_t hi = 2 * q + 1 < batch ? *reinterpret_cast<const uint16_t*>(xbuf + (2 * q + 1) * kMfmaXRow + 2 * c) : 0u;
-            o[q] = lo | (hi << 16);
-          }
-          u32x4* d = reinterpret_cast<u32x4*>(XT + (int64_t)j * 16);
-          const u32x4 v0 = {o[0], o[1], o[2], o[3]}, v1 = {o[4], o[5], o[6], o[7]};
-          d[0] = v0;
-          d[1] = v1;
-        }
-      }
-      if (st == 0 && tid < 2) {              // the zero line behind the last column
-        const u32x4 zero = {0u, 0u, 0u, 0u};
-        reinterpret_cast<u32x4*>(XT + (int64_t)n * 16)[tid] = zero;
-      }
-    }
     const uint32_t a2 = t.s[T::SD - 2], b2 = t.s[T::SD - 1];
     const float s_s = h2f((uint16_t)(a2 & 0xFFFF)), z_s = h2f((uint16_t)(a2 >> 16));
     const float s_z = h2f((uint16_t)(b2 & 0xFFFF)), z_z = h2f((uint16_t)(b2 >> 16));
@@ -995,6 +1062,26 @@ gemm_mfma16_kernel(DevMatrix A, const uint16_t* __restrict__ X, float* __restric
     *reinterpret_cast<float4_t*>(P + (int64_t)blockIdx.y * split_stride + (int64_t)i16 * m + (int64_t)strip * TR + 4 * g4) = D;
 }
 
+// The batch transposed for the outlier kernels: XT[j][16] binary16, batch rows beyond
+// `batch` zero, so that one outlier (one column j) meets its 16 activations in one
+// 32-byte line.  Line n is all zeros: the place entry slots behind the end of a row read.
+__global__ void __launch_bounds__(256)
+transpose_x16_kernel(const uint16_t* __restrict__ X, uint16_t* __restrict__ XT, int n, int batch) {
+  const int j = blockIdx.x * 256 + threadIdx.x;
+  if (j > n) return;
+  uint32_t o[8];
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    const uint32_t lo = (j < n && 2 * k < batch) ? X[(int64_t)(2 * k) * n + j] : 0u;
+    const uint32_t hi = (j < n && 2 * k + 1 < batch) ? X[(int64_t)(2 * k + 1) * n + j] : 0u;
+    o[k] = lo | (hi << 16);
+  }
+  u32x4* d = reinterpret_cast<u32x4*>(XT + (int64_t)j * 16);
+  const u32x4 v0 = {o[0], o[1], o[2], o[3]}, v1 = {o[4], o[5], o[6], o[7]};
+  d[0] = v0;
+  d[1] = v1;
+}
+
 // value of lane J (0 or 1) of the caller's pair of lanes, for both lanes of the pair
 template <int J>
 __device__ __forceinline__ uint32_t pair_broadcast(uint32_t v) {
@@ -1005,25 +1092,23 @@ __device__ __forceinline__ uint32_t pair_broadcast(uint32_t v) {
 // Y[b][i] = sum_split P[split][b][i] + sum_k val_k * X[b][col_k]  (Sec. 4.2: the sparse
 // part is a separate product).  With one split P may be Y itself.
 // One workgroup of 512 threads per strip of 16 rows.  The strip's CSR entries pass
-// through LDS in chunks of 4096: every thread brings one aligned granule of 8
-// entries (the next chunk's is in flight meanwhile).  A pair of lanes works on one
-// part of one row, each lane on 8 of the 16 activation vectors (16 bytes of the
-// entry's line of XT), so no reduction across lanes exists: the pair walks its
+// through LDS in chunks of 4096 (every thread brings one aligned granule of 8
+// entries; chunks that lie inside one long row are skipped).  A pair of lanes works
+// on one part of one row, each lane on 8 of the 16 activation vectors (16 bytes of
+// the entry's line of XT), so no reduction across lanes exists: the pair walks its
 // entries in order, 4 per trip (each lane reads 2 of them from LDS and hands them to
-// its partner).  A row is cut into 16 contiguous parts (256 pairs = 16 rows x 16); a
-// row longer than LONG_ROW is dealt round-robin, two entries at a time, to all 256
-// pairs instead.  Parts are added in order by the row's owner: fixed order, one
-// writer per output.
+// its partner).  A row is cut into 16 contiguous parts (256 pairs = 16 rows x 16);
+// parts are added in order by the row's owner.  A row longer than kLongRow comes
+// ready-made from long_rows_block: its owner adds the row's slots in order.  Fixed
+// order everywhere, one writer per output.
 constexpr int kFinishThreads = 512;
 
 __global__ void __launch_bounds__(kFinishThreads, 8)
-finish_xt16_kernel(DevMatrix A, const uint16_t* __restrict__ XT, const float* P, int nsplit, int64_t split_stride,
-                   float* Y, int batch) {
-  constexpr int TR = 16, LONG_ROW = 512, NP = kFinishThreads / 2, PER_ROW = NP / TR, CHUNK = 8 * kFinishThreads;
-  constexpr int NG = kFinishThreads / 16;
+finish_xt16_kernel(DevMatrix A, const uint16_t* __restrict__ XT, const float* __restrict__ slots, const float* P,
+                   int nsplit, int64_t split_stride, float* Y, int batch) {
+  constexpr int TR = 16, NP = kFinishThreads / 2, PER_ROW = NP / TR, CHUNK = 8 * kFinishThreads;
   __shared__ int rp[TR + 1];
   __shared__ float part[NP][16];
-  __shared__ float part2[NG][16];
   __shared__ __align__(16) uint16_t scol[CHUNK], sval[CHUNK];
   const int tid = threadIdx.x, pr = tid >> 1, bq = tid & 1;
   const int g = tid >> 4, b = tid & 15;      // the owner of Y[b][row g] for tid < 256
@@ -1038,13 +1123,13 @@ finish_xt16_kernel(DevMatrix A, const uint16_t* __restrict__ XT, const float* P,
   if (nsplit == 1 && e_hi == e_lo) return;   // nothing to add (workgroup-uniform)
   const uint8_t* xt16 = reinterpret_cast<const uint8_t*>(XT) + 16 * bq;
   const uint32_t zoff = (uint32_t)A.g.n * 32u;
-  // Both lanes of the pair add the 4 entries at chunk positions i0 + bq and i0 + stride + bq (global index e0 + i),
+  // Both lanes of the pair add the 4 entries at chunk positions i0 + bq and i0 + 2 + bq (global index e0 + i),
   // those inside [lo, hi) (hi never beyond the chunk); the others read the zero line of XT with value 0.
-  auto consume = [&](int e0, int i0, int stride, int lo, int hi, float (&acc)[8]) {
+  auto consume = [&](int e0, int i0, int lo, int hi, float (&acc)[8]) {
     uint32_t off[2], val[2];
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-      const int i = i0 + h * stride + bq, e = e0 + i;
+      const int i = i0 + 2 * h + bq, e = e0 + i;
       const bool ok = e >= lo && e < hi;
       const int ic = min(i, CHUNK - 1);
       off[h] = ok ? (uint32_t)scol[ic] * 32u : zoff;
@@ -1077,63 +1162,44 @@ finish_xt16_kernel(DevMatrix A, const uint16_t* __restrict__ XT, const float* P,
     const u32x4* col8 = reinterpret_cast<const u32x4*>(A.col);
     const u32x4* val8 = reinterpret_cast<const u32x4*>(A.val);
     const int g_lo = e_lo >> 3, ngran = ((e_hi - 1) >> 3) - g_lo + 1;
-    const u32x4 none = {0u, 0u, 0u, 0u};
-    u32x4 nc = tid < ngran ? col8[g_lo + tid] : none, nv = tid < ngran ? val8[g_lo + tid] : none;
-    // this pair's part of an ordinary row
-    const int my_r = pr / PER_ROW;
+    // this pair's part of an ordinary row (empty for a long row)
     int a, z;
     {
-      const int lo = rp[my_r], hi = rp[my_r + 1], len = hi - lo;
+      const int r = pr / PER_ROW;
+      const int lo = rp[r], hi = rp[r + 1], len = hi - lo;
       const int per = (len + PER_ROW - 1) / PER_ROW;
       a = min(lo + (pr % PER_ROW) * per, hi);
-      z = len <= LONG_ROW ? min(a + per, hi) : a;
+      z = len <= kLongRow ? min(a + per, hi) : a;
     }
-    float acc[8], accl[8];                   // of the ordinary part, of the long row in progress
+    float acc[8];
 #pragma unroll
-    for (int k = 0; k < 8; ++k) { acc[k] = 0.f; accl[k] = 0.f; }
+    for (int k = 0; k < 8; ++k) acc[k] = 0.f;
     for (int ch = 0; ch * kFinishThreads < ngran; ++ch) {         // workgroup-uniform
+      const int e0 = 8 * (g_lo + ch * kFinishThreads), e1 = e0 + CHUNK;   // the chunk's entries
+      bool skip = false;                     // nothing but one long row in it
+#pragma unroll
+      for (int r = 0; r < TR; ++r) skip = skip || (rp[r + 1] - rp[r] > kLongRow && rp[r] <= max(e0, e_lo) && rp[r + 1] >= min(e1, e_hi));
+      if (skip) continue;
+      const int gi = ch * kFinishThreads + tid;
+      const u32x4 none = {0u, 0u, 0u, 0u};
+      const u32x4 nc = gi < ngran ? col8[g_lo + gi] : none, nv = gi < ngran ? val8[g_lo + gi] : none;
       __syncthreads();                       // the previous chunk is consumed
       reinterpret_cast<u32x4*>(scol)[tid] = nc;
       reinterpret_cast<u32x4*>(sval)[tid] = nv;
       __syncthreads();
-      const int gn = (ch + 1) * kFinishThreads + tid;
-      nc = gn < ngran ? col8[g_lo + gn] : none;
-      nv = gn < ngran ? val8[g_lo + gn] : none;
-      const int e0 = 8 * (g_lo + ch * kFinishThreads), e1 = e0 + CHUNK;   // the chunk's entries
-      // ordinary rows: what this chunk holds of the pair's part, 4 entries per trip
-      for (int e = max(a, e0); e < min(z, e1); e += 4) consume(e0, e - e0, 2, a, min(z, e1), acc);
-      // long rows that reach into this chunk, one after the other (uniform)
-      for (int r = 0; r < TR; ++r) {
-        const int lo = rp[r], hi = rp[r + 1];
-        if (hi - lo <= LONG_ROW || hi <= e0 || lo >= e1) continue;
-        const int i_lo = max(lo, e0) - e0, i_hi = min(hi, e1) - e0;
-        for (int i0 = (i_lo & ~1) + 2 * pr; i0 < i_hi; i0 += 4 * NP) consume(e0, i0, 2 * NP, lo, min(hi, e1), accl);
-        if (hi <= e1) {                      // the row ends here: add its 256 parts in two levels
-          __syncthreads();                   // the previous parts are consumed
-#pragma unroll
-          for (int k2 = 0; k2 < 8; ++k2) { part[pr][8 * bq + k2] = accl[k2]; accl[k2] = 0.f; }
-          __syncthreads();
-          float t = 0.f;
-#pragma unroll
-          for (int k = 0; k < NP / NG; ++k) t += part[g * (NP / NG) + k][b];
-          part2[g][b] = t;
-          __syncthreads();
-          if (g == r) {
-            t = 0.f;
-#pragma unroll
-            for (int k = 0; k < NG; ++k) t += part2[k][b];
-            sum = t;
-          }
-        }
-      }
+      for (int e = max(a, e0); e < min(z, e1); e += 4) consume(e0, e - e0, a, min(z, e1), acc);
     }
-    __syncthreads();                         // the long rows' parts are consumed
 #pragma unroll
     for (int k2 = 0; k2 < 8; ++k2) part[pr][8 * bq + k2] = acc[k2];
     __syncthreads();
-    if (g < TR && rp[g + 1] - rp[g] <= LONG_ROW) {
+    if (g < TR) {
+      const int lo = rp[g], hi = rp[g + 1];
+      if (hi - lo <= kLongRow) {
 #pragma unroll
-      for (int k = 0; k < PER_ROW; ++k) sum += part[g * PER_ROW + k][b];
+        for (int k = 0; k < PER_ROW; ++k) sum += part[g * PER_ROW + k][b];
+      } else {
+        for (int e0 = lo; e0 < hi; e0 += kLongSlice) sum += slots[(int64_t)(lo / kSlotGrain + (e0 - lo) / kLongSlice) * 16 + b];
+      }
     }
   }
   if (g < TR && b < batch && (rp[g + 1] > rp[g] || nsplit > 1)) Y[at] = dense + sum;
@@ -1459,9 +1525,9 @@ static int mfma_steps_per_split(int groups, int nsteps) {
   return best;
 }
 
-// Dense pass and finishing pass.  Scratch (the batch transposed, n x 32 bytes, and the
-// partial results when the steps are split) is taken from and returned to the
-// stream's memory pool.  hipErrorNotSupported = no pool here; the caller takes the vector path.
+// Dense pass and finishing pass.  Scratch (the batch transposed, (n+1) x 32 bytes, the
+// sums of the long outlier rows, 64 bytes per 512 outliers, and the partial results
+// when the steps are split) is taken from and returned to the stream's memory pool.  hipErrorNotSupported = no pool here; the caller takes the vector path.
 template <int W, int AXIS>
 static hipError_t launch_mfma16(const DevMatrix& A, const uint16_t* X, int b, float* Y, hipStream_t stream) {
   const Geometry& g = A.g;
@@ -1478,22 +1544,41 @@ static hipError_t launch_mfma16(const DevMatrix& A, const uint16_t* X, int b, fl
   const int nsplit = (nsteps + steps_per_split - 1) / steps_per_split;
   const bool sparse = A.nnz > 0;
   const size_t xt_bytes = sparse ? ((size_t)g.n + 1) * 32 : 0;   // one more row: zeros
+  const size_t slot_bytes = sparse ? ((size_t)(A.nnz / kSlotGrain) + 2) * 64 : 0;
   const size_t part_bytes = nsplit > 1 ? (size_t)nsplit * b * g.m * sizeof(float) : 0;
   uint8_t* scratch = nullptr;
-  if (xt_bytes + part_bytes > 0) {
-    if (hipMallocAsync(reinterpret_cast<void**>(&scratch), xt_bytes + part_bytes, stream) != hipSuccess) {
+  if (xt_bytes + slot_bytes + part_bytes > 0) {
+    if (hipMallocAsync(reinterpret_cast<void**>(&scratch), xt_bytes + slot_bytes + part_bytes, stream) != hipSuccess) {
       (void)hipGetLastError();
       return hipErrorNotSupported;
     }
   }
   uint16_t* xt = reinterpret_cast<uint16_t*>(scratch);
-  float* part = nsplit > 1 ? reinterpret_cast<float*>(scratch + xt_bytes) : Y;
+  float* slots = reinterpret_cast<float*>(scratch + xt_bytes);
+  float* part = nsplit > 1 ? reinterpret_cast<float*>(scratch + xt_bytes + slot_bytes) : Y;
   const int64_t split_stride = (int64_t)b * g.m;
-  hipLaunchKernelGGL((gemm_mfma16_kernel<W, AXIS>), dim3(groups, nsplit), dim3(64 * kMfmaStrips), kMfmaLds, stream,
-                     A, X, part, split_stride, steps_per_split, b, sparse ? xt : nullptr);
-  hipError_t e = hipGetLastError();
+  // workgroups for the long outlier rows: kLongParts per range of rows, a range of fewer rows than a workgroup has
+  // threads, 128 ranges if the matrix is large (each of them costs a look at its row pointers, long rows or not)
+  constexpr int kNT = 64 * kMfmaStrips;
+  int extra = 0;
+  if (sparse) {
+    extra = (g.m + 15) / 16 < kCUs / 2 ? (g.m + 15) / 16 : kCUs / 2;
+    const int need = (g.m + kNT - 2) / (kNT - 1);
+    if (extra < need) extra = need;
+  }
+  hipError_t e = hipSuccess;
+  if (sparse) {
+    hipLaunchKernelGGL(transpose_x16_kernel, dim3((g.n + 256) / 256), dim3(256), 0, stream, X, xt, g.n, b);
+    e = hipGetLastError();
+  }
+  if (e == hipSuccess) {
+    hipLaunchKernelGGL((gemm_mfma16_kernel<W, AXIS>), dim3(groups + extra * kLongParts, nsplit), dim3(kNT), kMfmaLds, stream,
+                       A, X, part, split_stride, steps_per_split, b, xt, slots, groups);
+    e = hipGetLastError();
+  }
   if (e == hipSuccess && (sparse || nsplit > 1)) {
-    hipLaunchKernelGGL(finish_xt16_kernel, dim3(g.ntr), dim3(kFinishThreads), 0, stream, A, xt, part, nsplit, split_stride, Y, b);
+    hipLaunchKernelGGL(finish_xt16_kernel, dim3(g.ntr), dim3(kFinishThreads), 0, stream, A, xt, slots, part, nsplit,
+                       split_stride, Y, b);
     e = hipGetLastError();
   }
   if (scratch != nullptr) {
@@ -1503,9 +1588,9 @@ static hipError_t launch_mfma16(const DevMatrix& A, const uint16_t* X, int b, fl
   return e;
 }
 
-// Whether a batch of b > 4 vectors takes the matrix-core path.  It pays one more launch and the
+// Whether a batch of b > 4 vectors takes the matrix-core path.  It pays two more launches and the
 // transposition through LDS, the vector path re-reads the weights once per 4 vectors: measured
-// on MI355X the matrix cores win from 12 vectors on for any layer, from 8 on for layers of 40 M
+// on MI355X the matrix cores win from 13 vectors on for any layer, from 8 on for layers of 40 M
 // weights and from 5 on for layers of 100 M.  SPQR_MFMA=0 / =1 in the environment (read per
 // call) forces the vector / the matrix-core path wherever it applies (tests compare the two).
 static bool mfma_wanted(const Geometry& g, int b) {
@@ -1513,7 +1598,7 @@ static bool mfma_wanted(const Geometry& g, int b) {
   if (e && e[0] == '0') return false;
   if (e && e[0] == '1') return true;
   const double weights = (double)g.m * (double)g.n;
-  return b >= 12 || (b >= 8 && weights >= 40e6) || weights >= 100e6;
+  return b >= 13 || (b >= 8 && weights >= 40e6) || weights >= 100e6;
 }
 
 // Y[b][m] = X[b][n] . W_hat^T.  Up to 4 activation vectors: the tuned vector

@@ -118,9 +118,9 @@ def test_smallbatch_matches_oracle(P, w, b1, b2, axis, b):
     for k in range(b):
         assert rel_l2(Y[k], ref[k]) <= REL_L2, (k, rel_l2(Y[k], ref[k]))
     Yh = P.spqr_gemm_smallbatch(A, dev(X), y_dtype=P.SPQR_F16).cpu().numpy()
-    if b < 12 or (b1, b2) != (16, 16):
+    if b < 13 or (b1, b2) != (16, 16):
         assert np.array_equal(Yh.view(np.uint16), Y.astype(np.float16).view(np.uint16))
-    else:       # a layer this small: from 12 vectors on, binary32 output takes the matrix-core path, binary16 the vector path
+    else:       # a layer this small: from 13 vectors on, binary32 output takes the matrix-core path, binary16 the vector path
         for k in range(b):
             assert rel_l2(Yh[k], ref[k]) <= REL_L2
 
@@ -411,6 +411,35 @@ def test_matrix_core_batch_path_outlier_mixes(P, monkeypatch, structure, rate):
     Y = P.spqr_gemm_smallbatch(A, dev(X)).cpu().numpy()
     ref = orc.matvec(f, X)
     assert max(rel_l2(Y[k], ref[k]) for k in range(11)) <= REL_L2
+
+
+@pytest.mark.parametrize("ntc,rate", [(138, 0.95), (300, 0.45), (600, 0.45), (40, 0.9)])
+def test_matrix_core_long_rows_back_to_back(P, monkeypatch, ntc, rate):
+    """Rows that follow one another directly in the CSR arrays, all of one kind: two slices with a short second one
+    (about 2098 and 2160 entries; slices of neighbouring rows closer than 512 entries), three slices (4320), one
+    slice (576)."""
+    monkeypatch.setenv("SPQR_MFMA", "1")
+    f = make(3, 16, 16, 0, 3, ntc, rate=rate, structure="uniform", seed=(83, ntc))
+    assert np.diff(f.row_ptr).min() > 512
+    A = P.SpQRMatrix.from_logical(f)
+    for b in (16, 7):
+        X = synth.make_x(f.n, b, seed=(84, b))
+        Y = P.spqr_gemm_smallbatch(A, dev(X)).cpu().numpy()
+        ref = orc.matvec(f, X)
+        assert max(rel_l2(Y[k], ref[k]) for k in range(b)) <= REL_L2
+
+
+def test_matrix_core_long_rows_many_rows_per_workgroup(P, monkeypatch):
+    """A tall matrix: the workgroups that take the long rows own 80 rows each (row 31 of a
+    wavefront's 64 is bit 31 of the word its long-row mask is kept in), all of them long."""
+    monkeypatch.setenv("SPQR_MFMA", "1")
+    f = make(3, 16, 16, 1, 640, 144, rate=0.93, structure="uniform", seed=(85,))
+    assert f.m == 10240 and np.diff(f.row_ptr).min() > 2048
+    A = P.SpQRMatrix.from_logical(f)
+    X = synth.make_x(f.n, 9, seed=(86,))
+    Y = P.spqr_gemm_smallbatch(A, dev(X)).cpu().numpy()
+    ref = orc.matvec(f, X)
+    assert max(rel_l2(Y[k], ref[k]) for k in range(9)) <= REL_L2
 
 
 def test_matrix_core_batch_path_without_outliers_and_sparse_only(P, monkeypatch):
