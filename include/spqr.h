@@ -58,7 +58,7 @@ typedef enum spqr_status {
 } spqr_status;
 
 #define SPQR_LAYOUT_V1   1
-#define SPQR_MAX_BATCH  16
+#define SPQR_MAX_BATCH  256
 
 /* Output element types of y / Y. */
 #define SPQR_F32 0   /* IEEE binary32 (used for parity)            */
@@ -173,11 +173,12 @@ int spqr_gemv(const spqr_matrix_t* A, const uint16_t* x_f16, void* y, int y_dtyp
  * Up to 4 vectors: one launch of the batch-1 kernel's NB-vector form.  More:
  * either slices of up to 4 (weights read once per slice), or, for 16x16 tiles,
  * binary32 output, perm == NULL and a batch / layer large enough to pay for it,
- * the weights are read ONCE, dequantised to binary16 and multiplied on the
- * matrix cores, then a second kernel adds the outliers.  That path takes
- * (n+1)*32 + (nnz/512 + 2)*64 + splits*b*m*4 bytes of device scratch from the stream's memory pool
- * (hipMallocAsync / hipFreeAsync on `stream`, stream-ordered: safe with
- * concurrent calls on other streams); if the pool refuses, the sliced path runs.
+ * slices of up to 16: the weights are read once per slice, dequantised to
+ * binary16 and multiplied on the matrix cores, then a second kernel adds the
+ * outliers.  That path takes (n+1)*32 + (nnz/512 + 2)*64 + splits*16*m*4 bytes
+ * of device scratch per slice from the stream's memory pool (hipMallocAsync /
+ * hipFreeAsync on `stream`, stream-ordered: safe with concurrent calls on other
+ * streams); if the pool refuses, the slices of 4 run instead.
  * SPQR_MFMA=0 or =1 in the environment forces one or the other where both apply.
  * Results are deterministic (fixed summation order) on either path; the two
  * differ by rounding only (both within the product tolerance).

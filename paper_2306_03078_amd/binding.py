@@ -202,7 +202,7 @@ def spqr_gemv(A: SpQRMatrix, x, out=None, y_dtype: int = SPQR_F32, stream=None):
 
 
 def spqr_gemm_smallbatch(A: SpQRMatrix, X, out=None, y_dtype: int = SPQR_F32, stream=None):
-    """Y[b, m] = X[b, :] . W_hat^T, X: float16 device tensor [b, n], 1 <= b <= 16."""
+    """Y[b, m] = X[b, :] . W_hat^T, X: float16 device tensor [b, n], 1 <= b <= SPQR_MAX_BATCH (256)."""
     import torch
     assert X.dtype == torch.float16 and X.is_contiguous() and X.dim() == 2 and X.shape[1] == A.n
     b = int(X.shape[0])

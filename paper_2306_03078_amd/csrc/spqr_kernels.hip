@@ -12,6 +12,7 @@
 //   The strip's outliers (a contiguous CSR range) are handled by the same
 //   workgroup, so y is written once, without atomics, in a fixed order.
 #include <hip/hip_runtime.h>
+#include <atomic>
 #include <cstdlib>
 #include <type_traits>
 
@@ -1439,15 +1440,30 @@ static bool plan_launch(const Geometry& g, int nb, int max_waves, int slots, Lau
   return best > 0.0;
 }
 
+// Function attributes (the opt-in for more than 64 KB of dynamic LDS) are per device, and
+// several host threads may arrive here at once: what is remembered per kernel is kept per
+// device in atomics; a device number out of range is simply not remembered.
+constexpr int kMaxDevices = 64;
+struct PerDevice {
+  std::atomic<int> v[kMaxDevices];
+  int get(int d) const { return d >= 0 && d < kMaxDevices ? v[d].load(std::memory_order_acquire) : 0; }
+  void set(int d, int x) { if (d >= 0 && d < kMaxDevices) v[d].store(x, std::memory_order_release); }
+};
+static int current_device() {
+  int d = -1;
+  return hipGetDevice(&d) == hipSuccess ? d : -1;
+}
+
 template <int W, int TR, int TC, int AXIS, int NB>
 static hipError_t launch_tile256(const DevMatrix& A, const uint16_t* x, void* y, int y_dtype,
                                  hipStream_t stream) {
   constexpr int MAXW = WavesPerGroup<W, NB>::MAX;
   constexpr int MAX_DYNAMIC = 160 * 1024 - static_lds_bytes(TR, NB) - 1024;   // static + dynamic <= 160 KB
   // once per kernel: register count (-> wavefront slots per CU) and the opt-in for > 64 KB of dynamic LDS
-  static int slots[2] = {0, 0};
-  const int pi = A.perm ? 1 : 0;
-  if (slots[pi] == 0) {
+  static PerDevice known[2];                 // wavefront slots per CU of the instance, 0 = not asked yet
+  const int pi = A.perm ? 1 : 0, dev = current_device();
+  int slots = known[pi].get(dev);
+  if (slots == 0) {
     const void* fn = A.perm ? reinterpret_cast<const void*>(&gemv_tile256_kernel<W, TR, TC, AXIS, true, NB>)
                             : reinterpret_cast<const void*>(&gemv_tile256_kernel<W, TR, TC, AXIS, false, NB>);
     hipFuncAttributes fa;
@@ -1457,10 +1473,11 @@ static hipError_t launch_tile256(const DevMatrix& A, const uint16_t* x, void* y,
     if (e != hipSuccess) return e;
     int regs = (fa.numRegs + 7) & ~7; if (regs < 64) regs = 64;
     int per_simd = 512 / regs; if (per_simd > 8) per_simd = 8; if (per_simd < 1) per_simd = 1;
-    slots[pi] = 4 * per_simd;
+    slots = 4 * per_simd;
+    known[pi].set(dev, slots);
   }
   LaunchPlan plan = {0, 0, 0};
-  if (!plan_launch(A.g, NB, MAXW, slots[pi], &plan)) return hipErrorInvalidValue;
+  if (!plan_launch(A.g, NB, MAXW, slots, &plan)) return hipErrorInvalidValue;
   if (plan.lds > (size_t)MAX_DYNAMIC || plan.cap < 64 * plan.nw) return hipErrorInvalidValue;
   if (A.perm)
     hipLaunchKernelGGL((gemv_tile256_kernel<W, TR, TC, AXIS, true, NB>), dim3(A.g.ntr), dim3(64 * plan.nw),
@@ -1531,12 +1548,13 @@ static int mfma_steps_per_split(int groups, int nsteps) {
 template <int W, int AXIS>
 static hipError_t launch_mfma16(const DevMatrix& A, const uint16_t* X, int b, float* Y, hipStream_t stream) {
   const Geometry& g = A.g;
-  static bool ready = false;
-  if (!ready) {
+  static PerDevice ready;
+  const int dev = current_device();
+  if (!ready.get(dev)) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma16_kernel<W, AXIS>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMfmaLds);
     if (e != hipSuccess) return e;
-    ready = true;
+    ready.set(dev, 1);
   }
   const int groups = (g.ntr + kMfmaStrips - 1) / kMfmaStrips;
   const int nsteps = (g.ntc + 63) / 64;
@@ -1602,30 +1620,37 @@ static bool mfma_wanted(const Geometry& g, int b) {
 }
 
 // Y[b][m] = X[b][n] . W_hat^T.  Up to 4 activation vectors: the tuned vector
-// kernel, all of them in one launch.  More, on 16x16 tiles and where it pays: the
-// dense part on the matrix cores (weights stream once), then the finishing kernel
-// with the outliers.  Else slices of 4.
+// kernel, all of them in one launch.  More, on 16x16 tiles and where it pays: slices
+// of up to 16 with the dense part on the matrix cores (weights stream once per
+// slice), then the finishing kernel with the outliers.  Else slices of 4.
 hipError_t launch_gemm(const DevMatrix& A, const uint16_t* X, int b, void* Y, int y_dtype,
                        hipStream_t stream, bool force_generic) {
   const Geometry& g = A.g;
   const size_t ysz = y_dtype == SPQR_F32 ? 4 : 2;
-  if (b > 4 && !force_generic && y_dtype == SPQR_F32 && A.perm == nullptr && g.tile_rows == 16 &&
-      g.tile_cols == 16 && (g.w_bits == 3 || g.w_bits == 4) && mfma_wanted(g, b)) {
-    float* Yf = static_cast<float*>(Y);
-    hipError_t e = hipErrorNotSupported;
-    if (g.w_bits == 3 && g.axis == 1) e = launch_mfma16<3, 1>(A, X, b, Yf, stream);
-    else if (g.w_bits == 3 && g.axis == 0) e = launch_mfma16<3, 0>(A, X, b, Yf, stream);
-    else if (g.w_bits == 4 && g.axis == 1) e = launch_mfma16<4, 1>(A, X, b, Yf, stream);
-    else if (g.w_bits == 4 && g.axis == 0) e = launch_mfma16<4, 0>(A, X, b, Yf, stream);
-    if (e != hipErrorNotSupported) return e;
-  }
+  bool mfma_ok = !force_generic && y_dtype == SPQR_F32 && A.perm == nullptr && g.tile_rows == 16 &&
+                 g.tile_cols == 16 && (g.w_bits == 3 || g.w_bits == 4);
   int k = 0;
   while (k < b) {
     const uint16_t* xk = X + (size_t)k * g.n;
     void* yk = static_cast<uint8_t*>(Y) + (size_t)k * g.m * ysz;
-    const int nb = force_generic ? 0 : tuned_batch_width(g, b - k);
+    const int left = b - k;
     hipError_t e;
     int done = 1;
+    // the matrix-core path takes up to 16 vectors per pass over the weights
+    const int nb16 = left < 16 ? left : 16;
+    if (mfma_ok && left > 4 && mfma_wanted(g, nb16)) {
+      float* yf = static_cast<float*>(yk);
+      e = hipErrorNotSupported;
+      if (g.w_bits == 3 && g.axis == 1) e = launch_mfma16<3, 1>(A, xk, nb16, yf, stream);
+      else if (g.w_bits == 3 && g.axis == 0) e = launch_mfma16<3, 0>(A, xk, nb16, yf, stream);
+      else if (g.w_bits == 4 && g.axis == 1) e = launch_mfma16<4, 1>(A, xk, nb16, yf, stream);
+      else if (g.w_bits == 4 && g.axis == 0) e = launch_mfma16<4, 0>(A, xk, nb16, yf, stream);
+      if (e == hipErrorNotSupported) { mfma_ok = false; continue; }   // no memory pool here: the vector path from now on
+      if (e != hipSuccess) return e;
+      k += nb16;
+      continue;
+    }
+    const int nb = force_generic ? 0 : tuned_batch_width(g, left);
     if (nb == 4) { e = launch_tuned<4>(A, xk, yk, y_dtype, stream); done = 4; }
     else if (nb == 2) { e = launch_tuned<2>(A, xk, yk, y_dtype, stream); done = 2; }
     else if (nb == 1) { e = launch_tuned<1>(A, xk, yk, y_dtype, stream); }
@@ -1651,7 +1676,9 @@ static hipError_t launch_fused256(const DevMatrix* As, int count, const uint16_t
                                   int y_dtype, hipStream_t stream) {
   constexpr int MAXW = WavesPerGroup<W, 1>::MAX;
   constexpr int MAX_DYNAMIC = 160 * 1024 - static_lds_bytes(TR, 1) - 1024;
-  static int slots = 0;
+  static PerDevice known;
+  const int dev = current_device();
+  int slots = known.get(dev);
   const void* fn = reinterpret_cast<const void*>(&gemv_tile256_fused_kernel<W, TR, TC, AXIS>);
   if (slots == 0) {
     hipFuncAttributes fa;
@@ -1662,6 +1689,7 @@ static hipError_t launch_fused256(const DevMatrix* As, int count, const uint16_t
     int regs = (fa.numRegs + 7) & ~7; if (regs < 64) regs = 64;
     int per_simd = 512 / regs; if (per_simd > 8) per_simd = 8; if (per_simd < 1) per_simd = 1;
     slots = 4 * per_simd;
+    known.set(dev, slots);
   }
   FusedArgs F;
   F.count = count;

@@ -236,7 +236,7 @@ def test_pack_check_finds_planted_format_errors(P):
     lib = P.load_library()
     import ctypes as C
     y = torch.empty(f.m, dtype=torch.float32, device="cuda:0")
-    assert lib.spqr_gemm_smallbatch(C.byref(A.desc), x.data_ptr(), 17, y.data_ptr(), 0, None) == -8
+    assert lib.spqr_gemm_smallbatch(C.byref(A.desc), x.data_ptr(), 257, y.data_ptr(), 0, None) == -8
     assert lib.spqr_gemm_smallbatch(C.byref(A.desc), x.data_ptr(), 0, y.data_ptr(), 0, None) == -8
     assert lib.spqr_gemv(C.byref(A.desc), x.data_ptr(), y.data_ptr(), 5, None) == -10
     assert lib.spqr_dequant_dense(C.byref(A.desc), 9, y.data_ptr(), None) == -10
@@ -440,6 +440,21 @@ def test_matrix_core_long_rows_many_rows_per_workgroup(P, monkeypatch):
     Y = P.spqr_gemm_smallbatch(A, dev(X)).cpu().numpy()
     ref = orc.matvec(f, X)
     assert max(rel_l2(Y[k], ref[k]) for k in range(9)) <= REL_L2
+
+
+@pytest.mark.parametrize("b,mode", [(40, "1"), (33, "1"), (21, None), (64, "0")])
+def test_batches_above_16_go_in_slices(P, monkeypatch, b, mode):
+    """Slices of 16 on the matrix-core path (40 = 16 + 16 + 8; 33 leaves one vector), whatever the library's rule
+    picks for a layer this small (21 = 16 on the matrix cores + 5 on the vector path), slices of 4 on the vector path."""
+    if mode is not None:
+        monkeypatch.setenv("SPQR_MFMA", mode)
+    f = make(4, 16, 16, 1, 3, 70, rate=0.03, structure="rows8cols4", seed=(87,))
+    A = P.SpQRMatrix.from_logical(f)
+    X = synth.make_x(f.n, b, seed=(88, b))
+    Y = P.spqr_gemm_smallbatch(A, dev(X)).cpu().numpy()
+    ref = orc.matvec(f, X)
+    assert Y.shape == (b, f.m)
+    assert max(rel_l2(Y[k], ref[k]) for k in range(b)) <= REL_L2
 
 
 def test_matrix_core_batch_path_without_outliers_and_sparse_only(P, monkeypatch):
