@@ -809,11 +809,7 @@ gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restric
 // ---------------------------------------------------------------------------
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float float4_t __attribute__((ext_vector_type(4)));
-constexpr int kMfmaStrips = 4;               // wavefronts = strips per workgroup
 constexpr int kMfmaTileStride = 36;          // dwords per tile quarter (16 rows x 8 bytes + 16: spreads the banks)
-constexpr int kMfmaXRow = 2048 + 8;          // bytes per batch row of the staged piece of X (514 dwords: rows 2 banks apart)
-constexpr size_t kMfmaLds = (size_t)kMfmaStrips * 64 * kMfmaTileStride * 4 + 16 * kMfmaXRow;
-static_assert(2 * (kMfmaLds + 1024) <= 160 * 1024, "two workgroups per CU");
 
 // Outlier rows longer than kLongRow entries, for the batch path.  Such a row would keep the one CU that owns its
 // strip busy long after the others are done (every outlier is an L1 line look-up), so these rows are taken out of
@@ -901,12 +897,32 @@ __device__ __forceinline__ void long_rows_block(const DevMatrix& A, const uint16
   }
 }
 
-template <int W, int AXIS>
-__global__ void __launch_bounds__(64 * kMfmaStrips, 2)
-gemm_mfma16_kernel(DevMatrix A, const uint16_t* __restrict__ X, float* __restrict__ P, int64_t split_stride,
-                   int steps_per_split, int batch, const uint16_t* __restrict__ XT, float* __restrict__ slots, int groups) {
-  constexpr int TR = 16, TC = 16, PPR = TC / 2, S = kMfmaTileStride, NS = kMfmaStrips, NT = 64 * NS;
-  constexpr int UPT = 2048 / NT;             // 16-byte units of the X piece per thread
+// Shape of the dense kernel for a tile of TR x TC = 256 codes.  A phase covers PC = 64/TR columns of every tile
+// (a lane always writes 64 binary16 values = 128 bytes per phase: rows x PC columns), four phases per step.
+// The 8 K-values a lane supplies to one MFMA are PC columns of 8/PC tiles.  Strips per workgroup: what the LDS
+// allows next to the piece of X (16 batch rows x 64*TC columns): 8 x 32 tiles share a 64 KB piece among 8 strips.
+template <int TR, int TC> struct MfmaShape {
+  static constexpr int PC = 64 / TR;                       // columns per phase: 8, 4, 2
+  static constexpr int TPK = 8 / PC;                       // tiles per K-group of a lane: 1, 2, 4
+  static constexpr int MB = TR >= 16 ? TR / 16 : 1;        // blocks of 16 rows (an 8-row tile fills half a block)
+  static constexpr int NS = TC == 32 ? 8 : 4;              // strips = wavefronts per workgroup
+  static constexpr int WGS = TC == 32 ? 1 : 2;             // workgroups per CU
+  static constexpr int XROW = 128 * TC + 8;                // bytes per batch row of the staged piece of X
+  static constexpr size_t LDS = (size_t)NS * 64 * kMfmaTileStride * 4 + 16 * (size_t)XROW;
+  static_assert(WGS * (LDS + 1024) <= 160 * 1024, "the workgroups of a CU must fit its LDS");
+};
+
+template <int W, int TR, int TC, int AXIS>
+__global__ void __launch_bounds__((64 * MfmaShape<TR, TC>::NS), 2)
+gemm_mfma_kernel(DevMatrix A, const uint16_t* __restrict__ X, float* __restrict__ P, int64_t split_stride,
+                 int steps_per_split, int batch, const uint16_t* __restrict__ XT, float* __restrict__ slots, int groups) {
+  using SH = MfmaShape<TR, TC>;
+  constexpr int PPR = TC / 2, S = kMfmaTileStride, NS = SH::NS, NT = 64 * NS, PC = SH::PC, TPK = SH::TPK, MB = SH::MB;
+  constexpr int UROW = 8 * TC;               // 16-byte units of the X piece per batch row
+  constexpr int UPT = 16 * UROW / NT;        // ... per thread
+  constexpr int B2 = AXIS == 1 ? TC : TR;    // first-level groups per tile
+  constexpr int NM = 2 * PC;                 // MFMAs per phase and block of rows
+  static_assert(NT % UROW == 0 && TR * TC == 256, "shape");
   using T = TileRegs<W, TR, TC, AXIS>;
   constexpr int TILE_BYTES = 16 * T::KW + 4 * T::SD;
   constexpr float SCALE = (float)(1 << W);
@@ -932,19 +948,21 @@ gemm_mfma16_kernel(DevMatrix A, const uint16_t* __restrict__ X, float* __restric
   const int i16 = lane & 15, g4 = lane >> 4;
   const PairConsts kc = make_pair_consts<W>();
   const PairConsts k3 = make_pair_consts<3>();
-  float4_t D = {0.f, 0.f, 0.f, 0.f}, D1 = {0.f, 0.f, 0.f, 0.f};
+  float4_t D[MB][2];
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb) { D[mb][0] = float4_t{0.f, 0.f, 0.f, 0.f}; D[mb][1] = float4_t{0.f, 0.f, 0.f, 0.f}; }
 
-  // the piece of X of step st: unit u = 16 bytes = 8 columns of batch row u/128; loads unconditional (clamped)
+  // the piece of X of step st: unit u = 16 bytes = 8 columns of batch row u/UROW; loads unconditional (clamped)
   u32x4 xr[UPT];
   uint32_t xrow[UPT];                        // byte offset of the unit's (clamped) batch row in X
 #pragma unroll
-  for (int k = 0; k < UPT; ++k) xrow[k] = (uint32_t)min((tid + k * NT) >> 7, batch - 1) * (uint32_t)n * 2u;
-  const int xj = tid & 127;                  // NT is a multiple of 128: the unit's place in its row is the same for all k
+  for (int k = 0; k < UPT; ++k) xrow[k] = (uint32_t)min((tid + k * NT) / UROW, batch - 1) * (uint32_t)n * 2u;
+  const int xj = tid % UROW;                 // NT is a multiple of UROW: the unit's place in its row is the same for all k
   auto fetch_x = [&](int st) {
     const int sc = min(st, s_hi - 1);
     const int L = min(64, ntc - 64 * sc);
-    const uint8_t* xs = reinterpret_cast<const uint8_t*>(X + (int64_t)1024 * sc);
-    const uint32_t jb = 16u * (uint32_t)min(xj, 2 * L - 1);
+    const uint8_t* xs = reinterpret_cast<const uint8_t*>(X + (int64_t)(64 * TC) * sc);
+    const uint32_t jb = 16u * (uint32_t)min(xj, L * (TC / 8) - 1);
 #pragma unroll
     for (int k = 0; k < UPT; ++k) xr[k] = *reinterpret_cast<const u32x4*>(xs + (xrow[k] + jb));
     asm volatile("" ::: "memory");
@@ -953,13 +971,13 @@ gemm_mfma16_kernel(DevMatrix A, const uint16_t* __restrict__ X, float* __restric
     const int L = min(64, ntc - 64 * st);
     typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
     // columns behind the last tile: zeros (finite), they meet zero weights
-    const bool keep = xj < 2 * L;
+    const bool keep = xj < L * (TC / 8);
 #pragma unroll
     for (int k = 0; k < UPT; ++k) {
-      const int b = (tid + k * NT) >> 7;
+      const int b = (tid + k * NT) / UROW;
       const u32x2 lo = {keep ? xr[k].x : 0u, keep ? xr[k].y : 0u}, hi = {keep ? xr[k].z : 0u, keep ? xr[k].w : 0u};
       if (b < batch) {
-        u32x2* d = reinterpret_cast<u32x2*>(xbuf + b * kMfmaXRow + xj * 16);
+        u32x2* d = reinterpret_cast<u32x2*>(xbuf + b * SH::XROW + xj * 16);
         d[0] = lo;
         d[1] = hi;
       }
@@ -971,9 +989,11 @@ gemm_mfma16_kernel(DevMatrix A, const uint16_t* __restrict__ X, float* __restric
     load_tile<false>(t, strip_base + (int64_t)64 * (real ? st : s_lo) * TILE_BYTES, L, min(lane, L - 1));
     asm volatile("" ::: "memory");
   };
-  const uint32_t* afrag = buf + 2 * g4 * S + 2 * i16;
-  const uint32_t* xfrag = reinterpret_cast<const uint32_t*>(xbuf + min(i16, batch - 1) * kMfmaXRow) + 2 * g4 * (TC / 2);
-  // one step: publish its piece of X, then per quarter: dequantise 4 columns of this lane's tile, multiply
+  // operand fragments of MFMA j of a phase: tiles (4j + g4)*TPK .. +TPK-1, PC columns each.
+  // A: row i16 (+16 per block of rows; an 8-row tile repeats its rows, the copies are dropped at the end)
+  const uint32_t* afrag = buf + g4 * TPK * S + ((TR >= 16 ? i16 : (i16 & 7)) * PC) / 2;
+  const uint32_t* xfrag = reinterpret_cast<const uint32_t*>(xbuf + min(i16, batch - 1) * SH::XROW) + g4 * TPK * (TC / 2);
+  // one step: publish its piece of X, then per phase: dequantise PC columns of this lane's tile, multiply
   auto run_step = [&](const T& t, int st) {
     const int L = min(64, ntc - 64 * st);
     __syncthreads();                         // every wavefront is done with the previous piece of X
@@ -990,11 +1010,11 @@ gemm_mfma16_kernel(DevMatrix A, const uint16_t* __restrict__ X, float* __restric
     const bool live = lane < L;
     const float c1 = live ? SCALE * 8.f * s_s : 0.f, c2 = live ? SCALE * (-s_s * z_s - 8.f * s_s) : 0.f;
     const float e1 = -8.f * s_z / SCALE, e2 = -(SCALE - s_z * z_z - 8.f * s_z) / SCALE;
-    float fa[16], fb[16];
+    float fa[B2], fb[B2];
 #pragma unroll
-    for (int p = 0; p < 8; ++p) {
+    for (int p = 0; p < B2 / 2; ++p) {
       const half2_t sq = as_half2(pair_f16<3>(t.s, p, k3));
-      const half2_t zq = as_half2(pair_f16<3>(t.s, 8 + p, k3));
+      const half2_t zq = as_half2(pair_f16<3>(t.s, B2 / 2 + p, k3));
       fa[2 * p] = fmaf((float)sq.x, c1, c2);
       fa[2 * p + 1] = fmaf((float)sq.y, c1, c2);
       fb[2 * p] = fa[2 * p] * fmaf((float)zq.x, e1, e2);
@@ -1002,45 +1022,58 @@ gemm_mfma16_kernel(DevMatrix A, const uint16_t* __restrict__ X, float* __restric
     }
     uint32_t* mine = buf + lane * S;
 #pragma unroll
-    for (int qd = 0; qd < 4; ++qd) {         // columns 4*qd .. 4*qd+3 of every tile
+    for (int ph = 0; ph < 4; ++ph) {         // columns PC*ph .. PC*ph+PC-1 of every tile
+      // the lane's 64 values of the phase, row by row (PC/2 dwords per row), 16 bytes per store
 #pragma unroll
-      for (int rr = 0; rr < TR / 2; ++rr) {
+      for (int k4 = 0; k4 < 8; ++k4) {
         uint32_t o[4];
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-#pragma unroll
-          for (int u = 0; u < 2; ++u) {
-            const int r = 2 * rr + h, p = 2 * qd + u;
-            const half2_t q2 = as_half2(pair_f16<W>(t.c, r * PPR + p, kc));
-            const int g0 = AXIS == 1 ? 2 * p : r, g1 = AXIS == 1 ? 2 * p + 1 : r;
-            half2_t w;
-            w.x = (_Float16)fmaf((float)q2.x, fa[g0], fb[g0]);
-            w.y = (_Float16)fmaf((float)q2.y, fa[g1], fb[g1]);
-            o[2 * h + u] = __builtin_bit_cast(uint32_t, w);
-          }
+        for (int d = 0; d < 4; ++d) {
+          const int dw = 4 * k4 + d, r = dw / (PC / 2), p = (PC / 2) * ph + dw % (PC / 2);
+          const half2_t q2 = as_half2(pair_f16<W>(t.c, r * PPR + p, kc));
+          const int g0 = AXIS == 1 ? 2 * p : r, g1 = AXIS == 1 ? 2 * p + 1 : r;
+          half2_t w;
+          w.x = (_Float16)fmaf((float)q2.x, fa[g0], fb[g0]);
+          w.y = (_Float16)fmaf((float)q2.y, fa[g1], fb[g1]);
+          o[d] = __builtin_bit_cast(uint32_t, w);
         }
         const u32x4 v = {o[0], o[1], o[2], o[3]};
-        *reinterpret_cast<u32x4*>(mine + 4 * rr) = v;        // rows 2rr and 2rr+1, 8 bytes each
+        *reinterpret_cast<u32x4*>(mine + 4 * k4) = v;
       }
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();       // the buffer is this wavefront's own: its LDS operations stay in order
-      uint32_t av[8][4], bv[8][4];
+      constexpr int JG = NM < 8 ? NM : 8;    // MFMAs whose operands are in flight at a time
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {          // tiles 8j .. 8j+7, two per 16 lanes
-        const uint32_t* pa = afrag + 8 * j * S;
-        const uint32_t* pb = xfrag + 8 * j * (TC / 2) + 2 * qd;
-        av[j][0] = pa[0]; av[j][1] = pa[1]; av[j][2] = pa[S]; av[j][3] = pa[S + 1];
-        bv[j][0] = pb[0]; bv[j][1] = pb[1]; bv[j][2] = pb[TC / 2]; bv[j][3] = pb[TC / 2 + 1];
-      }
+      for (int j0 = 0; j0 < NM; j0 += JG) {
+        uint32_t av[MB][JG][4], bv[JG][4];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const uint32_t a4v[4] = {av[j][0], av[j][1], av[j][2], av[j][3]}, b4v[4] = {bv[j][0], bv[j][1], bv[j][2], bv[j][3]};
-        if (j & 1)
-          D1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, a4v), __builtin_bit_cast(half8_t, b4v), D1, 0, 0, 0);
-        else
-          D = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, a4v), __builtin_bit_cast(half8_t, b4v), D, 0, 0, 0);
+        for (int j = 0; j < JG; ++j) {
+#pragma unroll
+          for (int tt = 0; tt < TPK; ++tt) {
+            const int tile0 = (4 * (j0 + j)) * TPK + tt;         // + g4*TPK: in afrag / xfrag
+            const uint32_t* pb = xfrag + tile0 * (TC / 2) + (PC / 2) * ph;
+#pragma unroll
+            for (int d = 0; d < PC / 2; ++d) bv[j][tt * (PC / 2) + d] = pb[d];
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) {
+              const uint32_t* pa = afrag + tile0 * S + mb * (16 * PC / 2);
+#pragma unroll
+              for (int d = 0; d < PC / 2; ++d) av[mb][j][tt * (PC / 2) + d] = pa[d];
+            }
+          }
+        }
+#pragma unroll
+        for (int j = 0; j < JG; ++j) {
+          const uint32_t b4v[4] = {bv[j][0], bv[j][1], bv[j][2], bv[j][3]};
+#pragma unroll
+          for (int mb = 0; mb < MB; ++mb) {
+            const uint32_t a4v[4] = {av[mb][j][0], av[mb][j][1], av[mb][j][2], av[mb][j][3]};
+            D[mb][j & 1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, a4v),
+                                                                   __builtin_bit_cast(half8_t, b4v), D[mb][j & 1], 0, 0, 0);
+          }
+        }
       }
-      __builtin_amdgcn_wave_barrier();       // the reads are issued before the next quarter overwrites the buffer
+      __builtin_amdgcn_wave_barrier();       // the reads are issued before the next phase overwrites the buffer
     }
   };
 
@@ -1057,10 +1090,16 @@ gemm_mfma16_kernel(DevMatrix A, const uint16_t* __restrict__ X, float* __restric
   }
   if (st < s_hi) run_step(t0, st);
 
-  // D[row 4*g4 + v][batch i16]
-  D += D1;
-  if (active && i16 < batch)
-    *reinterpret_cast<float4_t*>(P + (int64_t)blockIdx.y * split_stride + (int64_t)i16 * m + (int64_t)strip * TR + 4 * g4) = D;
+  // D[mb][row 16*mb + 4*g4 + v][batch i16]
+  if (active && i16 < batch) {
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+      const float4_t d = D[mb][0] + D[mb][1];
+      if (16 * mb + 4 * g4 < TR)
+        *reinterpret_cast<float4_t*>(P + (int64_t)blockIdx.y * split_stride + (int64_t)i16 * m + (int64_t)strip * TR +
+                                     16 * mb + 4 * g4) = d;
+    }
+  }
 }
 
 // The batch transposed for the outlier kernels: XT[j][16] binary16, batch rows beyond
@@ -1114,9 +1153,9 @@ finish_xt16_kernel(DevMatrix A, const uint16_t* __restrict__ XT, const float* __
   const int tid = threadIdx.x, pr = tid >> 1, bq = tid & 1;
   const int g = tid >> 4, b = tid & 15;      // the owner of Y[b][row g] for tid < 256
   const int s = blockIdx.x, m = A.g.m;
-  if (tid <= TR) rp[tid] = A.row_ptr[s * TR + tid];
+  if (tid <= TR) rp[tid] = A.row_ptr[min(s * TR + tid, m)];      // rows behind the last one (m % 16 == 8) are empty
   // the dense part of this thread's output: requested now, needed at the very end
-  const int64_t at = (int64_t)min(b, batch - 1) * m + (int64_t)s * TR + min(g, TR - 1);
+  const int64_t at = (int64_t)min(b, batch - 1) * m + min(s * TR + min(g, TR - 1), m - 1);
   float dense = 0.f;
   for (int k = 0; k < nsplit; ++k) dense += P[k * split_stride + at];
   __syncthreads();
@@ -1203,7 +1242,7 @@ finish_xt16_kernel(DevMatrix A, const uint16_t* __restrict__ XT, const float* __
       }
     }
   }
-  if (g < TR && b < batch && (rp[g + 1] > rp[g] || nsplit > 1)) Y[at] = dense + sum;
+  if (g < TR && s * TR + g < m && b < batch && (rp[g + 1] > rp[g] || nsplit > 1)) Y[at] = dense + sum;
 }
 
 // Several matrices that share the input vector and the format (q/k/v, gate/up of
@@ -1518,17 +1557,15 @@ static hipError_t launch_tuned(const DevMatrix& A, const uint16_t* x, void* y, i
 }
 
 // ---- batches above 4 on 16x16 tiles: matrix-core dense pass + outlier pass ----
-// Steps per workgroup of the dense pass.  The chip holds two workgroups per CU at a
-// time; a workgroup costs its steps plus a start-up of about 0.7 step, a round of
-// workgroups that leaves half of the CUs with one workgroup runs its steps faster,
-// and every further split costs a partial result to write and read.  Ties go to
-// fewer splits.
-static int mfma_steps_per_split(int groups, int nsteps) {
+// Steps per workgroup of the dense pass.  The chip holds `slots` workgroups at a time; a
+// workgroup costs its steps plus a start-up of about 0.7 step, a round of workgroups
+// that leaves half of the slots empty runs its steps faster, and every further split
+// costs a partial result to write and read.  Ties go to fewer splits.
+static int mfma_steps_per_split(int groups, int nsteps, int slots) {
   if (const char* e = std::getenv("SPQR_MFMA_STEPS")) {        // pins it for tuning runs
     const int v = std::atoi(e);
     if (v >= 1) return v < nsteps ? v : nsteps;
   }
-  const int slots = 2 * kCUs;
   int best = nsteps;
   double best_cost = 1e30;
   for (int s = nsteps; s >= 1; --s) {
@@ -1542,23 +1579,25 @@ static int mfma_steps_per_split(int groups, int nsteps) {
   return best;
 }
 
-// Dense pass and finishing pass.  Scratch (the batch transposed, (n+1) x 32 bytes, the
-// sums of the long outlier rows, 64 bytes per 512 outliers, and the partial results
-// when the steps are split) is taken from and returned to the stream's memory pool.  hipErrorNotSupported = no pool here; the caller takes the vector path.
-template <int W, int AXIS>
-static hipError_t launch_mfma16(const DevMatrix& A, const uint16_t* X, int b, float* Y, hipStream_t stream) {
+// Transposition, dense pass (with the long outlier rows beside it) and finishing pass.  Scratch (the batch
+// transposed, (n+1) x 32 bytes, the sums of the long outlier rows, 64 bytes per 512 outliers, and the partial
+// results when the steps are split) is taken from and returned to the stream's memory pool.
+// hipErrorNotSupported = no pool here; the caller takes the vector path.
+template <int W, int TR, int TC, int AXIS>
+static hipError_t launch_mfma(const DevMatrix& A, const uint16_t* X, int b, float* Y, hipStream_t stream) {
+  using SH = MfmaShape<TR, TC>;
   const Geometry& g = A.g;
   static PerDevice ready;
   const int dev = current_device();
   if (!ready.get(dev)) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma16_kernel<W, AXIS>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMfmaLds);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_kernel<W, TR, TC, AXIS>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)SH::LDS);
     if (e != hipSuccess) return e;
     ready.set(dev, 1);
   }
-  const int groups = (g.ntr + kMfmaStrips - 1) / kMfmaStrips;
+  const int groups = (g.ntr + SH::NS - 1) / SH::NS;
   const int nsteps = (g.ntc + 63) / 64;
-  const int steps_per_split = mfma_steps_per_split(groups, nsteps);
+  const int steps_per_split = mfma_steps_per_split(groups, nsteps, SH::WGS * kCUs);
   const int nsplit = (nsteps + steps_per_split - 1) / steps_per_split;
   const bool sparse = A.nnz > 0;
   const size_t xt_bytes = sparse ? ((size_t)g.n + 1) * 32 : 0;   // one more row: zeros
@@ -1577,7 +1616,7 @@ static hipError_t launch_mfma16(const DevMatrix& A, const uint16_t* X, int b, fl
   const int64_t split_stride = (int64_t)b * g.m;
   // workgroups for the long outlier rows: kLongParts per range of rows, a range of fewer rows than a workgroup has
   // threads, 128 ranges if the matrix is large (each of them costs a look at its row pointers, long rows or not)
-  constexpr int kNT = 64 * kMfmaStrips;
+  constexpr int kNT = 64 * SH::NS;
   int extra = 0;
   if (sparse) {
     extra = (g.m + 15) / 16 < kCUs / 2 ? (g.m + 15) / 16 : kCUs / 2;
@@ -1590,12 +1629,12 @@ static hipError_t launch_mfma16(const DevMatrix& A, const uint16_t* X, int b, fl
     e = hipGetLastError();
   }
   if (e == hipSuccess) {
-    hipLaunchKernelGGL((gemm_mfma16_kernel<W, AXIS>), dim3(groups + extra * kLongParts, nsplit), dim3(kNT), kMfmaLds, stream,
-                       A, X, part, split_stride, steps_per_split, b, xt, slots, groups);
+    hipLaunchKernelGGL((gemm_mfma_kernel<W, TR, TC, AXIS>), dim3(groups + extra * kLongParts, nsplit), dim3(kNT), SH::LDS,
+                       stream, A, X, part, split_stride, steps_per_split, b, xt, slots, groups);
     e = hipGetLastError();
   }
   if (e == hipSuccess && (sparse || nsplit > 1)) {
-    hipLaunchKernelGGL(finish_xt16_kernel, dim3(g.ntr), dim3(kFinishThreads), 0, stream, A, xt, slots, part, nsplit,
+    hipLaunchKernelGGL(finish_xt16_kernel, dim3((g.m + 15) / 16), dim3(kFinishThreads), 0, stream, A, xt, slots, part, nsplit,
                        split_stride, Y, b);
     e = hipGetLastError();
   }
@@ -1627,8 +1666,12 @@ hipError_t launch_gemm(const DevMatrix& A, const uint16_t* X, int b, void* Y, in
                        hipStream_t stream, bool force_generic) {
   const Geometry& g = A.g;
   const size_t ysz = y_dtype == SPQR_F32 ? 4 : 2;
-  bool mfma_ok = !force_generic && y_dtype == SPQR_F32 && A.perm == nullptr && g.tile_rows == 16 &&
-                 g.tile_cols == 16 && (g.w_bits == 3 || g.w_bits == 4);
+  // tile shapes the matrix-core kernel is built for: the ones the vector kernel is tuned for
+  const bool shape16 = g.tile_rows == 16 && g.tile_cols == 16;
+  const bool shape8x32 = g.tile_rows == 8 && g.tile_cols == 32 && g.axis == 1;
+  const bool shape32x8 = g.tile_rows == 32 && g.tile_cols == 8 && g.axis == 0;
+  bool mfma_ok = !force_generic && y_dtype == SPQR_F32 && A.perm == nullptr && (g.w_bits == 3 || g.w_bits == 4) &&
+                 (shape16 || shape8x32 || shape32x8);
   int k = 0;
   while (k < b) {
     const uint16_t* xk = X + (size_t)k * g.n;
@@ -1641,10 +1684,12 @@ hipError_t launch_gemm(const DevMatrix& A, const uint16_t* X, int b, void* Y, in
     if (mfma_ok && left > 4 && mfma_wanted(g, nb16)) {
       float* yf = static_cast<float*>(yk);
       e = hipErrorNotSupported;
-      if (g.w_bits == 3 && g.axis == 1) e = launch_mfma16<3, 1>(A, xk, nb16, yf, stream);
-      else if (g.w_bits == 3 && g.axis == 0) e = launch_mfma16<3, 0>(A, xk, nb16, yf, stream);
-      else if (g.w_bits == 4 && g.axis == 1) e = launch_mfma16<4, 1>(A, xk, nb16, yf, stream);
-      else if (g.w_bits == 4 && g.axis == 0) e = launch_mfma16<4, 0>(A, xk, nb16, yf, stream);
+#define SPQR_MFMA_CASE(W_, TR_, TC_, AX_) \
+      if (g.w_bits == W_ && g.tile_rows == TR_ && g.tile_cols == TC_ && g.axis == AX_) \
+        e = launch_mfma<W_, TR_, TC_, AX_>(A, xk, nb16, yf, stream);
+      SPQR_MFMA_CASE(3, 16, 16, 1) SPQR_MFMA_CASE(3, 16, 16, 0) SPQR_MFMA_CASE(4, 16, 16, 1) SPQR_MFMA_CASE(4, 16, 16, 0)
+      SPQR_MFMA_CASE(3, 8, 32, 1) SPQR_MFMA_CASE(4, 8, 32, 1) SPQR_MFMA_CASE(3, 32, 8, 0) SPQR_MFMA_CASE(4, 32, 8, 0)
+#undef SPQR_MFMA_CASE
       if (e == hipErrorNotSupported) { mfma_ok = false; continue; }   // no memory pool here: the vector path from now on
       if (e != hipSuccess) return e;
       k += nb16;

@@ -118,7 +118,7 @@ def test_smallbatch_matches_oracle(P, w, b1, b2, axis, b):
     for k in range(b):
         assert rel_l2(Y[k], ref[k]) <= REL_L2, (k, rel_l2(Y[k], ref[k]))
     Yh = P.spqr_gemm_smallbatch(A, dev(X), y_dtype=P.SPQR_F16).cpu().numpy()
-    if b < 13 or (b1, b2) != (16, 16):
+    if b < 13:
         assert np.array_equal(Yh.view(np.uint16), Y.astype(np.float16).view(np.uint16))
     else:       # a layer this small: from 13 vectors on, binary32 output takes the matrix-core path, binary16 the vector path
         for k in range(b):
@@ -397,6 +397,30 @@ def test_matrix_core_batch_path(P, monkeypatch, w, axis, ntr, ntc, b):
     # deterministic
     Y2 = P.spqr_gemm_smallbatch(A, dev(X)).cpu().numpy()
     assert np.array_equal(Y.view(np.uint32), Y2.view(np.uint32))
+
+
+@pytest.mark.parametrize("w,axis,ntr,ntc", [(3, 1, 5, 70), (4, 1, 17, 33), (3, 0, 3, 130), (4, 0, 9, 300), (3, 1, 1, 9),
+                                            (3, 0, 1, 20), (4, 1, 8, 140)])
+@pytest.mark.parametrize("b", [5, 16, 23])
+def test_matrix_core_batch_path_8x32_tiles(P, monkeypatch, w, axis, ntr, ntc, b):
+    """beta1 = 8, beta2 = 32: tiles of 8 rows x 32 columns (groups along the rows, 8 strips per workgroup, an odd
+    number of strips leaves m % 16 == 8) and of 32 x 8 (groups along the columns, two blocks of 16 rows per tile)."""
+    import torch
+    monkeypatch.setenv("SPQR_MFMA", "1")
+    f = make(w, 8, 32, axis, ntr, ntc, rate=0.03, structure="rows8cols4" if ntc > 64 else "uniform", seed=(89, ntr, ntc))
+    A = P.SpQRMatrix.from_logical(f)
+    X = synth.make_x(f.n, b, seed=(90, b, ntc))
+    ref = orc.matvec(f, X)
+    Y = P.spqr_gemm_smallbatch(A, dev(X))
+    torch.cuda.synchronize()
+    Y = Y.cpu().numpy()
+    assert Y.shape == (b, f.m) and np.all(np.isfinite(Y))
+    for k in range(b):
+        assert rel_l2(Y[k], ref[k]) <= REL_L2, (k, rel_l2(Y[k], ref[k]))
+    monkeypatch.setenv("SPQR_MFMA", "0")
+    Yv = P.spqr_gemm_smallbatch(A, dev(X)).cpu().numpy()
+    for k in range(b):
+        assert rel_l2(Y[k], Yv[k]) <= REL_L2
 
 
 @pytest.mark.parametrize("structure,rate", [("zipf", 0.05), ("cols64", 0.08), ("rows8cols4", 0.3), ("uniform", 0.95),
