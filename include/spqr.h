@@ -172,11 +172,12 @@ int spqr_gemv(const spqr_matrix_t* A, const uint16_t* x_f16, void* y, int y_dtyp
  * to 16 bit and multiplies; the sparse part is a product of its own).
  * Up to 4 vectors: one launch of the batch-1 kernel's NB-vector form.  More:
  * either slices of up to 4 (weights read once per slice), or, for tiles of
- * 16x16, 8x32 (group_axis 1) and 32x8 (group_axis 0), binary32 output,
- * perm == NULL and a batch / layer large enough to pay for it,
+ * 16x16, 8x32 (group_axis 1) and 32x8 (group_axis 0) and a batch / layer
+ * large enough to pay for it,
  * slices of up to 16: the weights are read once per slice, dequantised to
  * binary16 and multiplied on the matrix cores, then a second kernel adds the
- * outliers.  That path takes (n+1)*32 + (nnz/512 + 2)*64 + splits*16*m*4 bytes
+ * outliers.  That path takes about (n+1)*32 + (nnz/512 + 2)*64 + splits*16*m*4
+ * (+ 32*n with a permutation) bytes
  * of device scratch per slice from the stream's memory pool (hipMallocAsync /
  * hipFreeAsync on `stream`, stream-ordered: safe with concurrent calls on other
  * streams); if the pool refuses, the slices of 4 run instead.

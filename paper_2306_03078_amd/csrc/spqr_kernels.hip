@@ -1102,24 +1102,36 @@ gemm_mfma_kernel(DevMatrix A, const uint16_t* __restrict__ X, float* __restrict_
   }
 }
 
-// The batch transposed for the outlier kernels: XT[j][16] binary16, batch rows beyond
-// `batch` zero, so that one outlier (one column j) meets its 16 activations in one
-// 32-byte line.  Line n is all zeros: the place entry slots behind the end of a row read.
+// Prepares the batch for the batch path.  With an input permutation, column j of the
+// matrix meets x[perm[j]] (act-order, Sec. 4 / Alg. 1: the quantiser reorders the input
+// dimension): XP[b][j] = X[b][perm[j]] is the batch in the matrix's column order, read by
+// the dense kernel in place of X.  For the outlier kernels, XT[j][16] binary16 is the same
+// transposed, batch rows beyond `batch` zero, so that one outlier (one column j) meets its
+// 16 activations in one 32-byte line; line n is all zeros: the place entry slots behind
+// the end of a row read.  Either output may be absent.
 __global__ void __launch_bounds__(256)
-transpose_x16_kernel(const uint16_t* __restrict__ X, uint16_t* __restrict__ XT, int n, int batch) {
+transpose_x16_kernel(const uint16_t* __restrict__ X, const int32_t* __restrict__ perm, uint16_t* __restrict__ XT,
+                     uint16_t* __restrict__ XP, int n, int batch) {
   const int j = blockIdx.x * 256 + threadIdx.x;
   if (j > n) return;
+  const int src = j < n ? (perm ? perm[j] : j) : 0;
   uint32_t o[8];
 #pragma unroll
   for (int k = 0; k < 8; ++k) {
-    const uint32_t lo = (j < n && 2 * k < batch) ? X[(int64_t)(2 * k) * n + j] : 0u;
-    const uint32_t hi = (j < n && 2 * k + 1 < batch) ? X[(int64_t)(2 * k + 1) * n + j] : 0u;
+    const uint32_t lo = (j < n && 2 * k < batch) ? X[(int64_t)(2 * k) * n + src] : 0u;
+    const uint32_t hi = (j < n && 2 * k + 1 < batch) ? X[(int64_t)(2 * k + 1) * n + src] : 0u;
     o[k] = lo | (hi << 16);
+    if (XP != nullptr && j < n) {
+      if (2 * k < batch) XP[(int64_t)(2 * k) * n + j] = (uint16_t)lo;
+      if (2 * k + 1 < batch) XP[(int64_t)(2 * k + 1) * n + j] = (uint16_t)hi;
+    }
   }
-  u32x4* d = reinterpret_cast<u32x4*>(XT + (int64_t)j * 16);
-  const u32x4 v0 = {o[0], o[1], o[2], o[3]}, v1 = {o[4], o[5], o[6], o[7]};
-  d[0] = v0;
-  d[1] = v1;
+  if (XT != nullptr) {
+    u32x4* d = reinterpret_cast<u32x4*>(XT + (int64_t)j * 16);
+    const u32x4 v0 = {o[0], o[1], o[2], o[3]}, v1 = {o[4], o[5], o[6], o[7]};
+    d[0] = v0;
+    d[1] = v1;
+  }
 }
 
 // value of lane J (0 or 1) of the caller's pair of lanes, for both lanes of the pair
@@ -1130,7 +1142,8 @@ __device__ __forceinline__ uint32_t pair_broadcast(uint32_t v) {
 
 // Finishing kernel for up to 16 activation vectors:
 // Y[b][i] = sum_split P[split][b][i] + sum_k val_k * X[b][col_k]  (Sec. 4.2: the sparse
-// part is a separate product).  With one split P may be Y itself.
+// part is a separate product), rounded to y_dtype.  With one split and binary32
+// output P may be Y itself.
 // One workgroup of 512 threads per strip of 16 rows.  The strip's CSR entries pass
 // through LDS in chunks of 4096 (every thread brings one aligned granule of 8
 // entries; chunks that lie inside one long row are skipped).  A pair of lanes works
@@ -1145,7 +1158,7 @@ constexpr int kFinishThreads = 512;
 
 __global__ void __launch_bounds__(kFinishThreads, 8)
 finish_xt16_kernel(DevMatrix A, const uint16_t* __restrict__ XT, const float* __restrict__ slots, const float* P,
-                   int nsplit, int64_t split_stride, float* Y, int batch) {
+                   int nsplit, int64_t split_stride, void* Y, int y_dtype, int batch) {
   constexpr int TR = 16, NP = kFinishThreads / 2, PER_ROW = NP / TR, CHUNK = 8 * kFinishThreads;
   __shared__ int rp[TR + 1];
   __shared__ float part[NP][16];
@@ -1160,7 +1173,8 @@ finish_xt16_kernel(DevMatrix A, const uint16_t* __restrict__ XT, const float* __
   for (int k = 0; k < nsplit; ++k) dense += P[k * split_stride + at];
   __syncthreads();
   const int e_lo = rp[0], e_hi = rp[TR];
-  if (nsplit == 1 && e_hi == e_lo) return;   // nothing to add (workgroup-uniform)
+  const bool inplace = static_cast<const void*>(P) == static_cast<const void*>(Y);   // one split, written to Y by the dense kernel
+  if (inplace && e_hi == e_lo) return;       // nothing to add (workgroup-uniform)
   const uint8_t* xt16 = reinterpret_cast<const uint8_t*>(XT) + 16 * bq;
   const uint32_t zoff = (uint32_t)A.g.n * 32u;
   // Both lanes of the pair add the 4 entries at chunk positions i0 + bq and i0 + 2 + bq (global index e0 + i),
@@ -1242,7 +1256,10 @@ finish_xt16_kernel(DevMatrix A, const uint16_t* __restrict__ XT, const float* __
       }
     }
   }
-  if (g < TR && s * TR + g < m && b < batch && (rp[g + 1] > rp[g] || nsplit > 1)) Y[at] = dense + sum;
+  if (g < TR && s * TR + g < m && b < batch && (rp[g + 1] > rp[g] || !inplace)) {
+    if (y_dtype == SPQR_F32) static_cast<float*>(Y)[at] = dense + sum;
+    else static_cast<uint16_t*>(Y)[at] = f2h_rne(dense + sum);
+  }
 }
 
 // Several matrices that share the input vector and the format (q/k/v, gate/up of
@@ -1580,11 +1597,12 @@ static int mfma_steps_per_split(int groups, int nsteps, int slots) {
 }
 
 // Transposition, dense pass (with the long outlier rows beside it) and finishing pass.  Scratch (the batch
-// transposed, (n+1) x 32 bytes, the sums of the long outlier rows, 64 bytes per 512 outliers, and the partial
-// results when the steps are split) is taken from and returned to the stream's memory pool.
+// transposed, (n+1) x 32 bytes, the sums of the long outlier rows, 64 bytes per 512 outliers, the batch in the
+// matrix's column order if there is a permutation, and the partial results when the steps are split or the
+// output is binary16) is taken from and returned to the stream's memory pool.
 // hipErrorNotSupported = no pool here; the caller takes the vector path.
 template <int W, int TR, int TC, int AXIS>
-static hipError_t launch_mfma(const DevMatrix& A, const uint16_t* X, int b, float* Y, hipStream_t stream) {
+static hipError_t launch_mfma(const DevMatrix& A, const uint16_t* X, int b, void* Y, int y_dtype, hipStream_t stream) {
   using SH = MfmaShape<TR, TC>;
   const Geometry& g = A.g;
   static PerDevice ready;
@@ -1599,20 +1617,25 @@ static hipError_t launch_mfma(const DevMatrix& A, const uint16_t* X, int b, floa
   const int nsteps = (g.ntc + 63) / 64;
   const int steps_per_split = mfma_steps_per_split(groups, nsteps, SH::WGS * kCUs);
   const int nsplit = (nsteps + steps_per_split - 1) / steps_per_split;
-  const bool sparse = A.nnz > 0;
-  const size_t xt_bytes = sparse ? ((size_t)g.n + 1) * 32 : 0;   // one more row: zeros
-  const size_t slot_bytes = sparse ? ((size_t)(A.nnz / kSlotGrain) + 2) * 64 : 0;
-  const size_t part_bytes = nsplit > 1 ? (size_t)nsplit * b * g.m * sizeof(float) : 0;
+  const bool sparse = A.nnz > 0, permuted = A.perm != nullptr;
+  const bool direct = nsplit == 1 && y_dtype == SPQR_F32;        // the dense kernel writes Y itself
+  auto up = [](size_t v) { return (v + 255) & ~(size_t)255; };
+  const size_t xt_bytes = sparse ? up(((size_t)g.n + 1) * 32) : 0;   // one more row: zeros
+  const size_t slot_bytes = sparse ? up(((size_t)(A.nnz / kSlotGrain) + 2) * 64) : 0;
+  const size_t xp_bytes = permuted ? up((size_t)b * g.n * 2) : 0;
+  const size_t part_bytes = direct ? 0 : (size_t)nsplit * b * g.m * sizeof(float);
   uint8_t* scratch = nullptr;
-  if (xt_bytes + slot_bytes + part_bytes > 0) {
-    if (hipMallocAsync(reinterpret_cast<void**>(&scratch), xt_bytes + slot_bytes + part_bytes, stream) != hipSuccess) {
+  if (xt_bytes + slot_bytes + xp_bytes + part_bytes > 0) {
+    if (hipMallocAsync(reinterpret_cast<void**>(&scratch), xt_bytes + slot_bytes + xp_bytes + part_bytes, stream) !=
+        hipSuccess) {
       (void)hipGetLastError();
       return hipErrorNotSupported;
     }
   }
-  uint16_t* xt = reinterpret_cast<uint16_t*>(scratch);
+  uint16_t* xt = sparse ? reinterpret_cast<uint16_t*>(scratch) : nullptr;
   float* slots = reinterpret_cast<float*>(scratch + xt_bytes);
-  float* part = nsplit > 1 ? reinterpret_cast<float*>(scratch + xt_bytes + slot_bytes) : Y;
+  uint16_t* xp = permuted ? reinterpret_cast<uint16_t*>(scratch + xt_bytes + slot_bytes) : nullptr;
+  float* part = direct ? static_cast<float*>(Y) : reinterpret_cast<float*>(scratch + xt_bytes + slot_bytes + xp_bytes);
   const int64_t split_stride = (int64_t)b * g.m;
   // workgroups for the long outlier rows: kLongParts per range of rows, a range of fewer rows than a workgroup has
   // threads, 128 ranges if the matrix is large (each of them costs a look at its row pointers, long rows or not)
@@ -1624,18 +1647,18 @@ static hipError_t launch_mfma(const DevMatrix& A, const uint16_t* X, int b, floa
     if (extra < need) extra = need;
   }
   hipError_t e = hipSuccess;
-  if (sparse) {
-    hipLaunchKernelGGL(transpose_x16_kernel, dim3((g.n + 256) / 256), dim3(256), 0, stream, X, xt, g.n, b);
+  if (sparse || permuted) {
+    hipLaunchKernelGGL(transpose_x16_kernel, dim3((g.n + 256) / 256), dim3(256), 0, stream, X, A.perm, xt, xp, g.n, b);
     e = hipGetLastError();
   }
   if (e == hipSuccess) {
     hipLaunchKernelGGL((gemm_mfma_kernel<W, TR, TC, AXIS>), dim3(groups + extra * kLongParts, nsplit), dim3(kNT), SH::LDS,
-                       stream, A, X, part, split_stride, steps_per_split, b, xt, slots, groups);
+                       stream, A, permuted ? xp : X, part, split_stride, steps_per_split, b, xt, slots, groups);
     e = hipGetLastError();
   }
-  if (e == hipSuccess && (sparse || nsplit > 1)) {
+  if (e == hipSuccess && (sparse || !direct)) {
     hipLaunchKernelGGL(finish_xt16_kernel, dim3((g.m + 15) / 16), dim3(kFinishThreads), 0, stream, A, xt, slots, part, nsplit,
-                       split_stride, Y, b);
+                       split_stride, Y, y_dtype, b);
     e = hipGetLastError();
   }
   if (scratch != nullptr) {
@@ -1670,8 +1693,7 @@ hipError_t launch_gemm(const DevMatrix& A, const uint16_t* X, int b, void* Y, in
   const bool shape16 = g.tile_rows == 16 && g.tile_cols == 16;
   const bool shape8x32 = g.tile_rows == 8 && g.tile_cols == 32 && g.axis == 1;
   const bool shape32x8 = g.tile_rows == 32 && g.tile_cols == 8 && g.axis == 0;
-  bool mfma_ok = !force_generic && y_dtype == SPQR_F32 && A.perm == nullptr && (g.w_bits == 3 || g.w_bits == 4) &&
-                 (shape16 || shape8x32 || shape32x8);
+  bool mfma_ok = !force_generic && (g.w_bits == 3 || g.w_bits == 4) && (shape16 || shape8x32 || shape32x8);
   int k = 0;
   while (k < b) {
     const uint16_t* xk = X + (size_t)k * g.n;
@@ -1682,11 +1704,10 @@ hipError_t launch_gemm(const DevMatrix& A, const uint16_t* X, int b, void* Y, in
     // the matrix-core path takes up to 16 vectors per pass over the weights
     const int nb16 = left < 16 ? left : 16;
     if (mfma_ok && left > 4 && mfma_wanted(g, nb16)) {
-      float* yf = static_cast<float*>(yk);
       e = hipErrorNotSupported;
 #define SPQR_MFMA_CASE(W_, TR_, TC_, AX_) \
       if (g.w_bits == W_ && g.tile_rows == TR_ && g.tile_cols == TC_ && g.axis == AX_) \
-        e = launch_mfma<W_, TR_, TC_, AX_>(A, xk, nb16, yf, stream);
+        e = launch_mfma<W_, TR_, TC_, AX_>(A, xk, nb16, yk, y_dtype, stream);
       SPQR_MFMA_CASE(3, 16, 16, 1) SPQR_MFMA_CASE(3, 16, 16, 0) SPQR_MFMA_CASE(4, 16, 16, 1) SPQR_MFMA_CASE(4, 16, 16, 0)
       SPQR_MFMA_CASE(3, 8, 32, 1) SPQR_MFMA_CASE(4, 8, 32, 1) SPQR_MFMA_CASE(3, 32, 8, 0) SPQR_MFMA_CASE(4, 32, 8, 0)
 #undef SPQR_MFMA_CASE

@@ -117,12 +117,9 @@ def test_smallbatch_matches_oracle(P, w, b1, b2, axis, b):
     assert Y.shape == (b, f.m)
     for k in range(b):
         assert rel_l2(Y[k], ref[k]) <= REL_L2, (k, rel_l2(Y[k], ref[k]))
+    # binary16 output = RNE of the binary32 output, on whichever path the batch takes
     Yh = P.spqr_gemm_smallbatch(A, dev(X), y_dtype=P.SPQR_F16).cpu().numpy()
-    if b < 13:
-        assert np.array_equal(Yh.view(np.uint16), Y.astype(np.float16).view(np.uint16))
-    else:       # a layer this small: from 13 vectors on, binary32 output takes the matrix-core path, binary16 the vector path
-        for k in range(b):
-            assert rel_l2(Yh[k], ref[k]) <= REL_L2
+    assert np.array_equal(Yh.view(np.uint16), Y.astype(np.float16).view(np.uint16))
 
 
 @pytest.mark.parametrize("structure,rate", [("none", 0.0), ("rows8cols4", 0.03), ("cols64", 0.08),
@@ -464,6 +461,29 @@ def test_matrix_core_long_rows_many_rows_per_workgroup(P, monkeypatch):
     Y = P.spqr_gemm_smallbatch(A, dev(X)).cpu().numpy()
     ref = orc.matvec(f, X)
     assert max(rel_l2(Y[k], ref[k]) for k in range(9)) <= REL_L2
+
+
+@pytest.mark.parametrize("w,b1,b2,axis,ntr,ntc", [(3, 16, 16, 1, 3, 70), (4, 16, 16, 0, 2, 130), (3, 8, 32, 1, 5, 40),
+                                                  (4, 8, 32, 0, 2, 300)])
+@pytest.mark.parametrize("b", [6, 16])
+def test_matrix_core_batch_path_with_permutation_and_f16_output(P, monkeypatch, w, b1, b2, axis, ntr, ntc, b):
+    """Act-order input permutation (column j of the matrix meets x[perm[j]]) and binary16 output on the batch path,
+    with and without outliers, one and several splits of the steps."""
+    monkeypatch.setenv("SPQR_MFMA", "1")
+    for rate in (0.03, 0.0):
+        f = make(w, b1, b2, axis, ntr, ntc, rate=rate, structure="uniform" if rate else "none", seed=(91, ntc, int(rate * 100)))
+        f.perm = np.random.default_rng(92 + ntc).permutation(f.n).astype(np.int32)
+        A = P.SpQRMatrix.from_logical(f)
+        X = synth.make_x(f.n, b, seed=(93, b))
+        ref = orc.matvec(f, X)
+        Y = P.spqr_gemm_smallbatch(A, dev(X)).cpu().numpy()
+        assert max(rel_l2(Y[k], ref[k]) for k in range(b)) <= REL_L2
+        Yh = P.spqr_gemm_smallbatch(A, dev(X), y_dtype=P.SPQR_F16).cpu().numpy()
+        assert np.array_equal(Yh.view(np.uint16), Y.astype(np.float16).view(np.uint16))
+        monkeypatch.setenv("SPQR_MFMA", "0")
+        Yv = P.spqr_gemm_smallbatch(A, dev(X)).cpu().numpy()
+        monkeypatch.setenv("SPQR_MFMA", "1")
+        assert max(rel_l2(Y[k], Yv[k]) for k in range(b)) <= REL_L2
 
 
 @pytest.mark.parametrize("b,mode", [(40, "1"), (33, "1"), (21, None), (64, "0")])
