@@ -176,7 +176,7 @@ int spqr_gemv(const spqr_matrix_t* A, const uint16_t* x_f16, void* y, int y_dtyp
  * large enough to pay for it,
  * slices of up to 16: the weights are read once per slice, dequantised to
  * binary16 and multiplied on the matrix cores, then a second kernel adds the
- * outliers.  That path takes about (n+1)*32 + (nnz/512 + 2)*64 + splits*16*m*4
+ * outliers.  That path takes about (n+1)*32 + (nnz/256 + 2)*64 + splits*16*m*4
  * (+ 32*n with a permutation) bytes
  * of device scratch per slice from the stream's memory pool (hipMallocAsync /
  * hipFreeAsync on `stream`, stream-ordered: safe with concurrent calls on other

@@ -811,7 +811,7 @@ typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float float4_t __attribute__((ext_vector_type(4)));
 constexpr int kMfmaTileStride = 36;          // dwords per tile quarter (16 rows x 8 bytes + 16: spreads the banks)
 
-// Outlier rows longer than kLongRow entries, for the batch path.  Such a row would keep the one CU that owns its
+// Outlier rows longer than `long_row` entries (far longer than the average row), for the batch path.  Such a row would keep the one CU that owns its
 // strip busy long after the others are done (every outlier is an L1 line look-up), so these rows are taken out of
 // the finishing kernel: extra workgroups of the dense kernel's grid (they run beside the dense workgroups and need
 // nothing from them) own a range of rows each, kLongParts of them the same range: they pick the long rows and
@@ -821,12 +821,12 @@ constexpr int kMfmaTileStride = 36;          // dwords per tile quarter (16 rows
 // than multiples of kSlotGrain among its entry indices, so the slots of different rows never meet and the finishing
 // kernel finds them without a search.  A thread takes every NT-th entry of the slice (consecutive threads read
 // consecutive entries) with its whole 32-byte line of XT; the 16 sums are reduced over the lanes in a fixed order.
-constexpr int kLongRow = 512, kLongSlice = 2048, kLongParts = 4, kSlotGrain = 512;
+constexpr int kLongRowMin = 256, kLongSlice = 2048, kLongParts = 4, kSlotGrain = 256;
 
 template <int NT>
 __device__ __forceinline__ void long_rows_block(const DevMatrix& A, const uint16_t* __restrict__ XT,
-                                                float* __restrict__ slots, int wg, int nwg, int part, int nparts,
-                                                uint8_t* smem) {
+                                                float* __restrict__ slots, int long_row, int wg, int nwg, int part,
+                                                int nparts, uint8_t* smem) {
   constexpr int EPT = kLongSlice / NT, NW = NT / 64;
   int* rpl = reinterpret_cast<int*>(smem);                                   // NT row pointers
   uint32_t* masks = reinterpret_cast<uint32_t*>(smem + 4 * NT);              // 2 per wavefront
@@ -839,7 +839,7 @@ __device__ __forceinline__ void long_rows_block(const DevMatrix& A, const uint16
   if (nrows <= 0) return;                                                    // workgroup-uniform
   if (tid <= nrows) rpl[tid] = A.row_ptr[r0 + tid];
   __syncthreads();
-  const bool is_long = tid < nrows && rpl[min(tid, NT - 2) + 1] - rpl[min(tid, NT - 2)] > kLongRow;
+  const bool is_long = tid < nrows && rpl[min(tid, NT - 2) + 1] - rpl[min(tid, NT - 2)] > long_row;
   const uint64_t bal = __builtin_amdgcn_ballot_w64(is_long);
   if (lane == 0) { masks[2 * wave] = (uint32_t)bal; masks[2 * wave + 1] = (uint32_t)(bal >> 32); }
   __syncthreads();
@@ -915,7 +915,8 @@ template <int TR, int TC> struct MfmaShape {
 template <int W, int TR, int TC, int AXIS>
 __global__ void __launch_bounds__((64 * MfmaShape<TR, TC>::NS), 2)
 gemm_mfma_kernel(DevMatrix A, const uint16_t* __restrict__ X, float* __restrict__ P, int64_t split_stride,
-                 int steps_per_split, int batch, const uint16_t* __restrict__ XT, float* __restrict__ slots, int groups) {
+                 int steps_per_split, int batch, const uint16_t* __restrict__ XT, float* __restrict__ slots, int long_row,
+                 int groups) {
   using SH = MfmaShape<TR, TC>;
   constexpr int PPR = TC / 2, S = kMfmaTileStride, NS = SH::NS, NT = 64 * NS, PC = SH::PC, TPK = SH::TPK, MB = SH::MB;
   constexpr int UROW = 8 * TC;               // 16-byte units of the X piece per batch row
@@ -931,7 +932,7 @@ gemm_mfma_kernel(DevMatrix A, const uint16_t* __restrict__ X, float* __restrict_
   if ((int)blockIdx.x >= groups) {           // the workgroups behind the dense ones: long outlier rows
     if (blockIdx.y == 0) {
       const int idx = (int)blockIdx.x - groups, nidx = (int)gridDim.x - groups;
-      long_rows_block<NT>(A, XT, slots, idx / kLongParts, nidx / kLongParts, idx % kLongParts, kLongParts, smem);
+      long_rows_block<NT>(A, XT, slots, long_row, idx / kLongParts, nidx / kLongParts, idx % kLongParts, kLongParts, smem);
     }
     return;
   }
@@ -1151,14 +1152,14 @@ __device__ __forceinline__ uint32_t pair_broadcast(uint32_t v) {
 // the entry's line of XT), so no reduction across lanes exists: the pair walks its
 // entries in order, 4 per trip (each lane reads 2 of them from LDS and hands them to
 // its partner).  A row is cut into 16 contiguous parts (256 pairs = 16 rows x 16);
-// parts are added in order by the row's owner.  A row longer than kLongRow comes
+// parts are added in order by the row's owner.  A row longer than long_row comes
 // ready-made from long_rows_block: its owner adds the row's slots in order.  Fixed
 // order everywhere, one writer per output.
 constexpr int kFinishThreads = 512;
 
 __global__ void __launch_bounds__(kFinishThreads, 8)
 finish_xt16_kernel(DevMatrix A, const uint16_t* __restrict__ XT, const float* __restrict__ slots, const float* P,
-                   int nsplit, int64_t split_stride, void* Y, int y_dtype, int batch) {
+                   int nsplit, int64_t split_stride, int long_row, void* Y, int y_dtype, int batch) {
   constexpr int TR = 16, NP = kFinishThreads / 2, PER_ROW = NP / TR, CHUNK = 8 * kFinishThreads;
   __shared__ int rp[TR + 1];
   __shared__ float part[NP][16];
@@ -1223,7 +1224,7 @@ finish_xt16_kernel(DevMatrix A, const uint16_t* __restrict__ XT, const float* __
       const int lo = rp[r], hi = rp[r + 1], len = hi - lo;
       const int per = (len + PER_ROW - 1) / PER_ROW;
       a = min(lo + (pr % PER_ROW) * per, hi);
-      z = len <= kLongRow ? min(a + per, hi) : a;
+      z = len <= long_row ? min(a + per, hi) : a;
     }
     float acc[8];
 #pragma unroll
@@ -1232,7 +1233,7 @@ finish_xt16_kernel(DevMatrix A, const uint16_t* __restrict__ XT, const float* __
       const int e0 = 8 * (g_lo + ch * kFinishThreads), e1 = e0 + CHUNK;   // the chunk's entries
       bool skip = false;                     // nothing but one long row in it
 #pragma unroll
-      for (int r = 0; r < TR; ++r) skip = skip || (rp[r + 1] - rp[r] > kLongRow && rp[r] <= max(e0, e_lo) && rp[r + 1] >= min(e1, e_hi));
+      for (int r = 0; r < TR; ++r) skip = skip || (rp[r + 1] - rp[r] > long_row && rp[r] <= max(e0, e_lo) && rp[r + 1] >= min(e1, e_hi));
       if (skip) continue;
       const int gi = ch * kFinishThreads + tid;
       const u32x4 none = {0u, 0u, 0u, 0u};
@@ -1248,7 +1249,7 @@ finish_xt16_kernel(DevMatrix A, const uint16_t* __restrict__ XT, const float* __
     __syncthreads();
     if (g < TR) {
       const int lo = rp[g], hi = rp[g + 1];
-      if (hi - lo <= kLongRow) {
+      if (hi - lo <= long_row) {
 #pragma unroll
         for (int k = 0; k < PER_ROW; ++k) sum += part[g * PER_ROW + k][b];
       } else {
@@ -1597,7 +1598,7 @@ static int mfma_steps_per_split(int groups, int nsteps, int slots) {
 }
 
 // Transposition, dense pass (with the long outlier rows beside it) and finishing pass.  Scratch (the batch
-// transposed, (n+1) x 32 bytes, the sums of the long outlier rows, 64 bytes per 512 outliers, the batch in the
+// transposed, (n+1) x 32 bytes, the sums of the long outlier rows, 64 bytes per 256 outliers, the batch in the
 // matrix's column order if there is a permutation, and the partial results when the steps are split or the
 // output is binary16) is taken from and returned to the stream's memory pool.
 // hipErrorNotSupported = no pool here; the caller takes the vector path.
@@ -1646,6 +1647,10 @@ static hipError_t launch_mfma(const DevMatrix& A, const uint16_t* X, int b, void
     const int need = (g.m + kNT - 2) / (kNT - 1);
     if (extra < need) extra = need;
   }
+  // a row is long if it holds far more outliers than the average row (and at least kLongRowMin): rows like the
+  // average one stay with their strip's workgroup in the finishing kernel, whatever the outlier rate
+  const int64_t avg_row = A.nnz / (g.m > 0 ? g.m : 1);
+  const int long_row = (int)(4 * avg_row > kLongRowMin ? (4 * avg_row < (1 << 30) ? 4 * avg_row : (1 << 30)) : kLongRowMin);
   hipError_t e = hipSuccess;
   if (sparse || permuted) {
     hipLaunchKernelGGL(transpose_x16_kernel, dim3((g.n + 256) / 256), dim3(256), 0, stream, X, A.perm, xt, xp, g.n, b);
@@ -1653,12 +1658,12 @@ static hipError_t launch_mfma(const DevMatrix& A, const uint16_t* X, int b, void
   }
   if (e == hipSuccess) {
     hipLaunchKernelGGL((gemm_mfma_kernel<W, TR, TC, AXIS>), dim3(groups + extra * kLongParts, nsplit), dim3(kNT), SH::LDS,
-                       stream, A, permuted ? xp : X, part, split_stride, steps_per_split, b, xt, slots, groups);
+                       stream, A, permuted ? xp : X, part, split_stride, steps_per_split, b, xt, slots, long_row, groups);
     e = hipGetLastError();
   }
   if (e == hipSuccess && (sparse || !direct)) {
     hipLaunchKernelGGL(finish_xt16_kernel, dim3((g.m + 15) / 16), dim3(kFinishThreads), 0, stream, A, xt, slots, part, nsplit,
-                       split_stride, Y, y_dtype, b);
+                       split_stride, long_row, Y, y_dtype, b);
     e = hipGetLastError();
   }
   if (scratch != nullptr) {

@@ -436,9 +436,8 @@ def test_matrix_core_batch_path_outlier_mixes(P, monkeypatch, structure, rate):
 
 @pytest.mark.parametrize("ntc,rate", [(138, 0.95), (300, 0.45), (600, 0.45), (40, 0.9)])
 def test_matrix_core_long_rows_back_to_back(P, monkeypatch, ntc, rate):
-    """Rows that follow one another directly in the CSR arrays, all of one kind: two slices with a short second one
-    (about 2098 and 2160 entries; slices of neighbouring rows closer than 512 entries), three slices (4320), one
-    slice (576)."""
+    """Every row about as long as the next (2098, 2160, 4320, 576 entries): none of them is far above the average,
+    so all stay in the finishing kernel, in 16 parts of up to 270 entries that cross the chunks of staged entries."""
     monkeypatch.setenv("SPQR_MFMA", "1")
     f = make(3, 16, 16, 0, 3, ntc, rate=rate, structure="uniform", seed=(83, ntc))
     assert np.diff(f.row_ptr).min() > 512
@@ -451,16 +450,48 @@ def test_matrix_core_long_rows_back_to_back(P, monkeypatch, ntc, rate):
 
 
 def test_matrix_core_long_rows_many_rows_per_workgroup(P, monkeypatch):
-    """A tall matrix: the workgroups that take the long rows own 80 rows each (row 31 of a
-    wavefront's 64 is bit 31 of the word its long-row mask is kept in), all of them long."""
+    """A tall matrix: the workgroups that take the long rows own 80 rows each; rows 31, 32, 63, 64 and 79 of every
+    80 hold 700 outliers, the others none (row 31 of a wavefront's 64 is bit 31 of the word its long-row mask is
+    kept in, rows 63 / 64 the seam between two wavefronts' masks)."""
     monkeypatch.setenv("SPQR_MFMA", "1")
-    f = make(3, 16, 16, 1, 640, 144, rate=0.93, structure="uniform", seed=(85,))
-    assert f.m == 10240 and np.diff(f.row_ptr).min() > 2048
+    f = make(3, 16, 16, 1, 640, 48, rate=0.0, structure="none", seed=(85,))
+    assert f.m == 10240 and f.n == 768
+    rng = np.random.default_rng(85)
+    counts = np.zeros(f.m, np.int64)
+    counts[np.isin(np.arange(f.m) % 80, (31, 32, 63, 64, 79))] = 700
+    f.row_ptr = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    f.col_idx = np.concatenate([np.sort(rng.choice(f.n, size=c, replace=False)) for c in counts if c]).astype(np.uint16)
+    f.val = rng.standard_normal(f.col_idx.shape[0]).astype(np.float16)
     A = P.SpQRMatrix.from_logical(f)
+    assert P.spqr_pack_check(A) == 0
     X = synth.make_x(f.n, 9, seed=(86,))
     Y = P.spqr_gemm_smallbatch(A, dev(X)).cpu().numpy()
     ref = orc.matvec(f, X)
     assert max(rel_l2(Y[k], ref[k]) for k in range(9)) <= REL_L2
+
+
+def test_matrix_core_long_rows_next_to_rows_like_the_average(P, monkeypatch):
+    """What counts as a long row depends on the average: with 30 % outliers everywhere (about 600 per row) plus two
+    full rows of 2080, only the full rows leave the finishing kernel; the others are cut into 16 parts of about 39."""
+    monkeypatch.setenv("SPQR_MFMA", "1")
+    f = make(4, 16, 16, 1, 5, 130, rate=0.3, structure="uniform", seed=(94,))
+    rng = np.random.default_rng(94)
+    counts = np.diff(f.row_ptr).astype(np.int64)
+    rows = [np.sort(f.col_idx[f.row_ptr[r]:f.row_ptr[r + 1]]) for r in range(f.m)]
+    vals = [f.val[f.row_ptr[r]:f.row_ptr[r + 1]] for r in range(f.m)]
+    for r in (7, 40):
+        rows[r] = np.arange(f.n, dtype=np.uint16)
+        vals[r] = rng.standard_normal(f.n).astype(np.float16)
+        counts[r] = f.n
+    f.row_ptr = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    f.col_idx = np.concatenate(rows).astype(np.uint16)
+    f.val = np.concatenate(vals).astype(np.float16)
+    A = P.SpQRMatrix.from_logical(f)
+    assert P.spqr_pack_check(A) == 0
+    X = synth.make_x(f.n, 12, seed=(95,))
+    Y = P.spqr_gemm_smallbatch(A, dev(X)).cpu().numpy()
+    ref = orc.matvec(f, X)
+    assert max(rel_l2(Y[k], ref[k]) for k in range(12)) <= REL_L2
 
 
 @pytest.mark.parametrize("w,b1,b2,axis,ntr,ntc", [(3, 16, 16, 1, 3, 70), (4, 16, 16, 0, 2, 130), (3, 8, 32, 1, 5, 40),
