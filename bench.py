@@ -58,31 +58,45 @@ def time_layer(P, torch, A, X, copies, reps=6):
 
 
 def time_block(P, torch, mats, x_h, x_f, copies, fused, reps=4):
-    """One decoder block at batch 1: q, k, v (input x_h), o (x_h), gate, up (x_h), down (x_f).
-    `mats` maps the layer name to a list of `copies` weight copies.  fused=True issues q/k/v and
-    gate/up as one spqr_gemv_fused call each (4 launches per block instead of 7)."""
-    ys = {nm: torch.empty(ms[0].m, dtype=torch.float32, device=x_h.device) for nm, ms in mats.items()}
+    """One decoder block: q, k, v (input x_h), o (x_h), gate, up (x_h), down (x_f); x_h, x_f are vectors (batch 1)
+    or [b, n] batches.  `mats` maps the layer name to a list of `copies` weight copies.  fused=True issues q/k/v
+    and gate/up as one spqr_gemv_fused / spqr_gemm_fused call each (4 calls per block instead of 7)."""
+    batch = x_h.dim() == 2
+    shape = (lambda A: (x_h.shape[0], A.m)) if batch else (lambda A: (A.m,))
+    ys = {nm: torch.empty(shape(ms[0]), dtype=torch.float32, device=x_h.device) for nm, ms in mats.items()}
+    one = P.spqr_gemm_smallbatch if batch else P.spqr_gemv
+    many = P.spqr_gemm_fused if batch else P.spqr_gemv_fused
 
     def block(c):
         if fused:
-            P.spqr_gemv_fused([mats[nm][c] for nm in ("q", "k", "v")], x_h, outs=[ys[nm] for nm in ("q", "k", "v")])
-            P.spqr_gemv(mats["o"][c], x_h, out=ys["o"])
-            P.spqr_gemv_fused([mats[nm][c] for nm in ("gate", "up")], x_h, outs=[ys[nm] for nm in ("gate", "up")])
+            many([mats[nm][c] for nm in ("q", "k", "v")], x_h, outs=[ys[nm] for nm in ("q", "k", "v")])
+            one(mats["o"][c], x_h, out=ys["o"])
+            many([mats[nm][c] for nm in ("gate", "up")], x_h, outs=[ys[nm] for nm in ("gate", "up")])
         else:
             for nm in ("q", "k", "v", "o", "gate", "up"):
-                P.spqr_gemv(mats[nm][c], x_h, out=ys[nm])
-        P.spqr_gemv(mats["down"][c], x_f, out=ys["down"])
+                one(mats[nm][c], x_h, out=ys[nm])
+        one(mats["down"][c], x_f, out=ys["down"])
 
     for c in range(copies):
         block(c)
     torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+    if batch:
+        # batches are streamed eagerly: the library keeps fused batch calls out of captured graphs
+        reps *= 4
+        e0.record()
+        for _ in range(reps):
+            for c in range(copies):
+                block(c)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / (reps * copies)
     g = torch.cuda.CUDAGraph()
     with torch.cuda.graph(g):
         for c in range(copies):
             block(c)
     g.replay()
     torch.cuda.synchronize()
-    e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(reps):
         g.replay()
@@ -92,7 +106,7 @@ def time_block(P, torch, mats, x_h, x_f, copies, fused, reps=4):
 
 
 def run_block_sweep(rows, P, synth, torch, dev):
-    """Whole decoder blocks of configurations 2-4, seven separate launches against four (q/k/v and
+    """Whole decoder blocks of configurations 2-4 at batch 1 and 16, seven separate calls against four (q/k/v and
     gate/up fused)."""
     for cfg in (2, 3, 4):
         specs = synth.config_layers(cfg)
@@ -107,14 +121,18 @@ def run_block_sweep(rows, P, synth, torch, dev):
         h, f = specs[0].n, specs[-1].n
         x_h = torch.from_numpy(synth.make_x(h, 1, seed=(cfg, 100))[0]).to(dev)
         x_f = torch.from_numpy(synth.make_x(f, 1, seed=(cfg, 101))[0]).to(dev)
-        for fused in (False, True):
-            us = time_block(P, torch, mats, x_h, x_f, copies, fused)
-            rows.append({"config": cfg, "layer": "block(7 launches)" if not fused else "block(q/k/v, gate/up fused: 4 launches)",
-                         "m": 0, "n": 0, "w_bits": specs[0].w_bits, "beta1": specs[0].beta1, "beta2": specs[0].beta2,
-                         "group_axis": 1, "batch": 1, "outliers": f"{specs[0].outlier_rate:g} {specs[0].outlier_structure}",
-                         "compressed_MB": round(nbytes / 1e6, 2), "us": round(us, 2),
-                         "GBps": round(nbytes / us / 1e3, 1),
-                         "frac_of_hbm_peak": round(nbytes / us / 1e3 / HBM_PEAK_GBS, 4)})
+        for b in (1, 16):
+            if b > 1:
+                x_h = torch.from_numpy(synth.make_x(h, b, seed=(cfg, 100))).to(dev)
+                x_f = torch.from_numpy(synth.make_x(f, b, seed=(cfg, 101))).to(dev)
+            for fused in (False, True):
+                us = time_block(P, torch, mats, x_h, x_f, copies, fused)
+                rows.append({"config": cfg, "layer": "block(7 calls)" if not fused else "block(q/k/v, gate/up fused: 4 calls)",
+                             "m": 0, "n": 0, "w_bits": specs[0].w_bits, "beta1": specs[0].beta1, "beta2": specs[0].beta2,
+                             "group_axis": 1, "batch": b, "outliers": f"{specs[0].outlier_rate:g} {specs[0].outlier_structure}",
+                             "compressed_MB": round(nbytes / 1e6, 2), "us": round(us, 2),
+                             "GBps": round(nbytes / us / 1e3, 1),
+                             "frac_of_hbm_peak": round(nbytes / us / 1e3 / HBM_PEAK_GBS, 4)})
         del mats
         torch.cuda.empty_cache()
 

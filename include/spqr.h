@@ -202,6 +202,19 @@ int spqr_gemm_smallbatch(const spqr_matrix_t* A, const uint16_t* X_f16, int b, v
 int spqr_gemv_fused(const spqr_matrix_t* const* A, int count, const uint16_t* x_f16,
                     void* const* y, int y_dtype, void* stream);
 
+/* Y[i][b][m_i] = X[b][:] . W_hat_i^T for `count` matrices that share the batch X
+ * (the q/k/v or gate/up projections of a decoder block at batch b): what
+ * spqr_gemv_fused is for one vector.  Same agreement rules (SPQR_ERR_PARAM
+ * otherwise), A and Y are HOST arrays.  Where the batch takes the matrix-core
+ * path of spqr_gemm_smallbatch, all matrices share one transposition of the
+ * batch, one dense launch and one finishing launch per slice of 16 vectors;
+ * otherwise, and whenever `stream` is being captured into a graph, the call is
+ * `count` calls of spqr_gemm_smallbatch (b == 1: one spqr_gemv_fused).  Same
+ * arithmetic as spqr_gemm_smallbatch on the same path; only the order of the
+ * partial sums over column ranges may differ. */
+int spqr_gemm_fused(const spqr_matrix_t* const* A, int count, const uint16_t* X_f16, int b,
+                    void* const* Y, int y_dtype, void* stream);
+
 /* Debug decode.  `what` selects the output:
  *   SPQR_OUT_CODES_U8   uint8  [m][n]   the b_w-bit codes
  *   SPQR_OUT_SCALE_F32  float  group grid ([m][n/beta1] or [m/beta1][n]): s_hat

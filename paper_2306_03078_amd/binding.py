@@ -75,6 +75,8 @@ def load_library():
     lib.spqr_gemm_smallbatch.argtypes = [P, vp, C.c_int, vp, C.c_int, vp]
     lib.spqr_gemv_fused.restype = C.c_int
     lib.spqr_gemv_fused.argtypes = [C.POINTER(P), C.c_int, vp, C.POINTER(vp), C.c_int, vp]
+    lib.spqr_gemm_fused.restype = C.c_int
+    lib.spqr_gemm_fused.argtypes = [C.POINTER(P), C.c_int, vp, C.c_int, C.POINTER(vp), C.c_int, vp]
     lib.spqr_dequant_dense.restype = C.c_int
     lib.spqr_dequant_dense.argtypes = [P, C.c_int, vp, vp]
     _lib = lib
@@ -225,6 +227,22 @@ def spqr_gemv_fused(As, x, outs=None, y_dtype: int = SPQR_F32, stream=None):
     descs = (C.POINTER(spqr_matrix_t) * k)(*[C.pointer(A.desc) for A in As])
     ys = (C.c_void_p * k)(*[o.data_ptr() for o in outs])
     _check(lib.spqr_gemv_fused(descs, k, x.data_ptr(), ys, y_dtype, _stream_ptr(stream)), "spqr_gemv_fused")
+    return outs
+
+
+def spqr_gemm_fused(As, X, outs=None, y_dtype: int = SPQR_F32, stream=None):
+    """Y_i[b, m_i] = X[b, :] . W_hat_i^T for matrices sharing the batch X (float16 device tensor [b, n])."""
+    import torch
+    As = list(As)
+    assert X.dtype == torch.float16 and X.is_contiguous() and X.dim() == 2 and X.shape[1] == As[0].n
+    b = int(X.shape[0])
+    if outs is None:
+        outs = [torch.empty((b, A.m), dtype=_out_dtype(y_dtype), device=X.device) for A in As]
+    lib = load_library()
+    k = len(As)
+    descs = (C.POINTER(spqr_matrix_t) * k)(*[C.pointer(A.desc) for A in As])
+    ys = (C.c_void_p * k)(*[o.data_ptr() for o in outs])
+    _check(lib.spqr_gemm_fused(descs, k, X.data_ptr(), b, ys, y_dtype, _stream_ptr(stream)), "spqr_gemm_fused")
     return outs
 
 

@@ -102,6 +102,31 @@ extern "C" int spqr_gemv_fused(const spqr_matrix_t* const* A, int count, const u
   return e == hipSuccess ? SPQR_OK : SPQR_ERR_HIP;
 }
 
+extern "C" int spqr_gemm_fused(const spqr_matrix_t* const* A, int count, const uint16_t* X_f16, int b,
+                               void* const* Y, int y_dtype, void* stream) {
+  if (!A || !Y || !X_f16) return SPQR_ERR_NULL;
+  if (count < 1 || count > SPQR_MAX_FUSED) return SPQR_ERR_PARAM;
+  if (b < 1 || b > SPQR_MAX_BATCH) return SPQR_ERR_BATCH;
+  if (y_dtype != SPQR_F32 && y_dtype != SPQR_F16) return SPQR_ERR_DTYPE;
+  if (reinterpret_cast<uintptr_t>(X_f16) % 16 != 0) return SPQR_ERR_ALIGN;
+  spqr::DevMatrix D[SPQR_MAX_FUSED];
+  for (int i = 0; i < count; ++i) {
+    if (!A[i] || !Y[i]) return SPQR_ERR_NULL;
+    int rc = to_device_matrix(A[i], &D[i]);
+    if (rc) return rc;
+    if (reinterpret_cast<uintptr_t>(Y[i]) % (y_dtype == SPQR_F32 ? 4 : 2) != 0) return SPQR_ERR_ALIGN;
+    const spqr_matrix_t *a = A[i], *a0 = A[0];
+    if (a->n != a0->n || a->w_bits != a0->w_bits || a->s_bits != a0->s_bits || a->z_bits != a0->z_bits ||
+        a->beta1 != a0->beta1 || a->beta2 != a0->beta2 || a->group_axis != a0->group_axis ||
+        a->layout_version != a0->layout_version || a->perm != a0->perm)
+      return SPQR_ERR_PARAM;
+  }
+  const hipStream_t st = static_cast<hipStream_t>(stream);
+  hipError_t e = b == 1 ? spqr::launch_gemv_fused(D, count, X_f16, Y, y_dtype, st, force_generic())
+                        : spqr::launch_gemm_fused(D, count, X_f16, b, Y, y_dtype, st, force_generic());
+  return e == hipSuccess ? SPQR_OK : SPQR_ERR_HIP;
+}
+
 extern "C" int spqr_dequant_dense(const spqr_matrix_t* A, int what, void* out, void* stream) {
   spqr::DevMatrix D;
   int rc = to_device_matrix(A, &D);

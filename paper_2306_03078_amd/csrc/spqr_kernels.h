@@ -15,6 +15,8 @@ hipError_t launch_gemm(const DevMatrix& A, const uint16_t* X, int b, void* Y, in
 // permutation is set, else one launch each.
 hipError_t launch_gemv_fused(const DevMatrix* As, int count, const uint16_t* x, void* const* ys,
                              int y_dtype, hipStream_t stream, bool force_generic);
+hipError_t launch_gemm_fused(const DevMatrix* As, int count, const uint16_t* X, int b, void* const* Ys,
+                             int y_dtype, hipStream_t stream, bool force_generic);
 hipError_t launch_dequant(const DevMatrix& A, int what, void* out, hipStream_t stream);
 hipError_t run_checks(const DevMatrix& A, bool csr, bool finite, bool perm, int host_words[3],
                       hipStream_t stream);

@@ -13,6 +13,7 @@
 //   workgroup, so y is written once, without atomics, in a fixed order.
 #include <hip/hip_runtime.h>
 #include <atomic>
+#include <cstdint>
 #include <cstdlib>
 #include <type_traits>
 
@@ -912,11 +913,14 @@ template <int TR, int TC> struct MfmaShape {
   static_assert(WGS * (LDS + 1024) <= 160 * 1024, "the workgroups of a CU must fit its LDS");
 };
 
+// `group` is the group of NS strips this workgroup multiplies, or negative for a workgroup that takes long outlier
+// rows instead: then it is number `extra` of `nextra` such workgroups of its matrix.  `split` of the splits of the
+// steps, `smem` the workgroup's dynamic LDS.
 template <int W, int TR, int TC, int AXIS>
-__global__ void __launch_bounds__((64 * MfmaShape<TR, TC>::NS), 2)
-gemm_mfma_kernel(DevMatrix A, const uint16_t* __restrict__ X, float* __restrict__ P, int64_t split_stride,
-                 int steps_per_split, int batch, const uint16_t* __restrict__ XT, float* __restrict__ slots, int long_row,
-                 int groups) {
+__device__ __forceinline__ void gemm_mfma_body(const DevMatrix& A, const uint16_t* __restrict__ X, float* __restrict__ P,
+                                               int64_t split_stride, int steps_per_split, int batch,
+                                               const uint16_t* __restrict__ XT, float* __restrict__ slots, int long_row,
+                                               int group, int split, int extra, int nextra, uint8_t* smem) {
   using SH = MfmaShape<TR, TC>;
   constexpr int PPR = TC / 2, S = kMfmaTileStride, NS = SH::NS, NT = 64 * NS, PC = SH::PC, TPK = SH::TPK, MB = SH::MB;
   constexpr int UROW = 8 * TC;               // 16-byte units of the X piece per batch row
@@ -927,13 +931,10 @@ gemm_mfma_kernel(DevMatrix A, const uint16_t* __restrict__ X, float* __restrict_
   using T = TileRegs<W, TR, TC, AXIS>;
   constexpr int TILE_BYTES = 16 * T::KW + 4 * T::SD;
   constexpr float SCALE = (float)(1 << W);
-  extern __shared__ __align__(16) uint8_t smem[];
   uint8_t* xbuf = smem + NS * 64 * S * 4;
-  if ((int)blockIdx.x >= groups) {           // the workgroups behind the dense ones: long outlier rows
-    if (blockIdx.y == 0) {
-      const int idx = (int)blockIdx.x - groups, nidx = (int)gridDim.x - groups;
-      long_rows_block<NT>(A, XT, slots, long_row, idx / kLongParts, nidx / kLongParts, idx % kLongParts, kLongParts, smem);
-    }
+  if (group < 0) {                           // long outlier rows
+    if (split == 0)
+      long_rows_block<NT>(A, XT, slots, long_row, extra / kLongParts, nextra / kLongParts, extra % kLongParts, kLongParts, smem);
     return;
   }
 
@@ -941,8 +942,8 @@ gemm_mfma_kernel(DevMatrix A, const uint16_t* __restrict__ X, float* __restrict_
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = A.g.n, ntc = A.g.ntc, m = A.g.m, ntr = A.g.ntr;
   const int nsteps = (ntc + 63) >> 6;
-  const int s_lo = blockIdx.y * steps_per_split, s_hi = min(nsteps, s_lo + steps_per_split);   // never empty (host)
-  const int strip = blockIdx.x * NS + wave;
+  const int s_lo = split * steps_per_split, s_hi = min(nsteps, s_lo + steps_per_split);   // never empty (host)
+  const int strip = group * NS + wave;
   const bool active = strip < ntr;           // wave-uniform; an idle wavefront still stages X and meets the barriers
   const uint8_t* strip_base = A.packed + (int64_t)min(strip, ntr - 1) * ntc * TILE_BYTES;
   uint32_t* buf = reinterpret_cast<uint32_t*>(smem) + wave * 64 * S;
@@ -1097,10 +1098,60 @@ gemm_mfma_kernel(DevMatrix A, const uint16_t* __restrict__ X, float* __restrict_
     for (int mb = 0; mb < MB; ++mb) {
       const float4_t d = D[mb][0] + D[mb][1];
       if (16 * mb + 4 * g4 < TR)
-        *reinterpret_cast<float4_t*>(P + (int64_t)blockIdx.y * split_stride + (int64_t)i16 * m + (int64_t)strip * TR +
+        *reinterpret_cast<float4_t*>(P + (int64_t)split * split_stride + (int64_t)i16 * m + (int64_t)strip * TR +
                                      16 * mb + 4 * g4) = d;
     }
   }
+}
+
+template <int W, int TR, int TC, int AXIS>
+__global__ void __launch_bounds__((64 * MfmaShape<TR, TC>::NS), 2)
+gemm_mfma_kernel(DevMatrix A, const uint16_t* __restrict__ X, float* __restrict__ P, int64_t split_stride,
+                 int steps_per_split, int batch, const uint16_t* __restrict__ XT, float* __restrict__ slots, int long_row,
+                 int groups) {
+  extern __shared__ __align__(16) uint8_t smem[];
+  const int bx = blockIdx.x;
+  gemm_mfma_body<W, TR, TC, AXIS>(A, X, P, split_stride, steps_per_split, batch, XT, slots, long_row,
+                                  bx < groups ? bx : -1, (int)blockIdx.y, bx - groups, (int)gridDim.x - groups, smem);
+}
+
+// Several matrices that share the batch X and the format (q/k/v, gate/up of a decoder block) in one grid:
+// blockIdx.x counts the dense workgroups of all matrices first, then their long-row workgroups.  Every
+// workgroup does exactly what it would do in a launch of its own matrix.
+struct MfmaFusedItem {
+  DevMatrix A;
+  float* P;                                  // partial results (or the output itself, see the finishing kernel)
+  float* slots;
+  void* Y;
+  int long_row;
+  int groups, extra;                         // dense / long-row workgroups of this matrix
+  int blocks16;                              // workgroups of the finishing kernel
+};
+struct MfmaFused {
+  int count;
+  MfmaFusedItem it[SPQR_MAX_FUSED];
+};
+
+template <int W, int TR, int TC, int AXIS>
+__global__ void __launch_bounds__((64 * MfmaShape<TR, TC>::NS), 2)
+gemm_mfma_fused_kernel(MfmaFused F, const uint16_t* __restrict__ X, int steps_per_split, int batch,
+                       const uint16_t* __restrict__ XT) {
+  extern __shared__ __align__(16) uint8_t smem[];
+  int bx = blockIdx.x, i = 0;
+  bool dense = false;                        // workgroup-uniform search, count <= SPQR_MAX_FUSED
+  for (; i < F.count; ++i) {
+    if (bx < F.it[i].groups) { dense = true; break; }
+    bx -= F.it[i].groups;
+  }
+  if (!dense) {
+    for (i = 0; i < F.count - 1; ++i) {
+      if (bx < F.it[i].extra) break;
+      bx -= F.it[i].extra;
+    }
+  }
+  const MfmaFusedItem& it = F.it[i];
+  gemm_mfma_body<W, TR, TC, AXIS>(it.A, X, it.P, (int64_t)batch * it.A.g.m, steps_per_split, batch, XT, it.slots,
+                                  it.long_row, dense ? bx : -1, (int)blockIdx.y, bx, it.extra, smem);
 }
 
 // Prepares the batch for the batch path.  With an input permutation, column j of the
@@ -1157,16 +1208,17 @@ __device__ __forceinline__ uint32_t pair_broadcast(uint32_t v) {
 // order everywhere, one writer per output.
 constexpr int kFinishThreads = 512;
 
-__global__ void __launch_bounds__(kFinishThreads, 8)
-finish_xt16_kernel(DevMatrix A, const uint16_t* __restrict__ XT, const float* __restrict__ slots, const float* P,
-                   int nsplit, int64_t split_stride, int long_row, void* Y, int y_dtype, int batch) {
+__device__ __forceinline__ void finish_xt16_body(const DevMatrix& A, const uint16_t* __restrict__ XT,
+                                                 const float* __restrict__ slots, const float* P, int nsplit,
+                                                 int64_t split_stride, int long_row, void* Y, int y_dtype, int batch,
+                                                 const int s) {
   constexpr int TR = 16, NP = kFinishThreads / 2, PER_ROW = NP / TR, CHUNK = 8 * kFinishThreads;
   __shared__ int rp[TR + 1];
   __shared__ float part[NP][16];
   __shared__ __align__(16) uint16_t scol[CHUNK], sval[CHUNK];
   const int tid = threadIdx.x, pr = tid >> 1, bq = tid & 1;
   const int g = tid >> 4, b = tid & 15;      // the owner of Y[b][row g] for tid < 256
-  const int s = blockIdx.x, m = A.g.m;
+  const int m = A.g.m;
   if (tid <= TR) rp[tid] = A.row_ptr[min(s * TR + tid, m)];      // rows behind the last one (m % 16 == 8) are empty
   // the dense part of this thread's output: requested now, needed at the very end
   const int64_t at = (int64_t)min(b, batch - 1) * m + min(s * TR + min(g, TR - 1), m - 1);
@@ -1261,6 +1313,23 @@ finish_xt16_kernel(DevMatrix A, const uint16_t* __restrict__ XT, const float* __
     if (y_dtype == SPQR_F32) static_cast<float*>(Y)[at] = dense + sum;
     else static_cast<uint16_t*>(Y)[at] = f2h_rne(dense + sum);
   }
+}
+
+__global__ void __launch_bounds__(kFinishThreads, 8)
+finish_xt16_kernel(DevMatrix A, const uint16_t* __restrict__ XT, const float* __restrict__ slots, const float* P,
+                   int nsplit, int64_t split_stride, int long_row, void* Y, int y_dtype, int batch) {
+  finish_xt16_body(A, XT, slots, P, nsplit, split_stride, long_row, Y, y_dtype, batch, (int)blockIdx.x);
+}
+
+__global__ void __launch_bounds__(kFinishThreads, 8)
+finish_xt16_fused_kernel(MfmaFused F, const uint16_t* __restrict__ XT, int nsplit, int y_dtype, int batch) {
+  int bx = blockIdx.x, i = 0;
+  for (; i < F.count - 1; ++i) {             // workgroup-uniform
+    if (bx < F.it[i].blocks16) break;
+    bx -= F.it[i].blocks16;
+  }
+  const MfmaFusedItem& it = F.it[i];
+  finish_xt16_body(it.A, XT, it.slots, it.P, nsplit, (int64_t)batch * it.A.g.m, it.long_row, it.Y, y_dtype, batch, bx);
 }
 
 // Several matrices that share the input vector and the format (q/k/v, gate/up of
@@ -1619,7 +1688,8 @@ static hipError_t launch_mfma(const DevMatrix& A, const uint16_t* X, int b, void
   const int steps_per_split = mfma_steps_per_split(groups, nsteps, SH::WGS * kCUs);
   const int nsplit = (nsteps + steps_per_split - 1) / steps_per_split;
   const bool sparse = A.nnz > 0, permuted = A.perm != nullptr;
-  const bool direct = nsplit == 1 && y_dtype == SPQR_F32;        // the dense kernel writes Y itself
+  // the dense kernel writes Y itself (16 bytes per store) if nothing has to be added or converted afterwards
+  const bool direct = nsplit == 1 && y_dtype == SPQR_F32 && reinterpret_cast<uintptr_t>(Y) % 16 == 0;
   auto up = [](size_t v) { return (v + 255) & ~(size_t)255; };
   const size_t xt_bytes = sparse ? up(((size_t)g.n + 1) * 32) : 0;   // one more row: zeros
   const size_t slot_bytes = sparse ? up(((size_t)(A.nnz / kSlotGrain) + 2) * 64) : 0;
@@ -1733,6 +1803,151 @@ hipError_t launch_gemm(const DevMatrix& A, const uint16_t* X, int b, void* Y, in
     }
     if (e != hipSuccess) return e;
     k += done;
+  }
+  return hipSuccess;
+}
+
+// The batch path for several matrices that share X (n, format and permutation agree; checked by the caller):
+// one transposition, one dense launch, one finishing launch for all of them.  b <= 16.
+template <int W, int TR, int TC, int AXIS>
+static hipError_t launch_mfma_fused(const DevMatrix* As, int count, const uint16_t* X, int b, void* const* Ys, int y_dtype,
+                                    hipStream_t stream) {
+  using SH = MfmaShape<TR, TC>;
+  const Geometry& g0 = As[0].g;
+  static PerDevice ready;
+  const int dev = current_device();
+  if (!ready.get(dev)) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_fused_kernel<W, TR, TC, AXIS>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)SH::LDS);
+    if (e != hipSuccess) return e;
+    ready.set(dev, 1);
+  }
+  constexpr int kNT = 64 * SH::NS;
+  const int nsteps = (g0.ntc + 63) / 64;
+  int total_groups = 0;
+  bool sparse = false;
+  for (int i = 0; i < count; ++i) {
+    total_groups += (As[i].g.ntr + SH::NS - 1) / SH::NS;
+    sparse = sparse || As[i].nnz > 0;
+  }
+  const int steps_per_split = mfma_steps_per_split(total_groups, nsteps, SH::WGS * kCUs);
+  const int nsplit = (nsteps + steps_per_split - 1) / steps_per_split;
+  const bool permuted = As[0].perm != nullptr;
+  bool direct = nsplit == 1 && y_dtype == SPQR_F32;              // the dense kernel writes the outputs itself (16-byte stores)
+  for (int i = 0; i < count; ++i) direct = direct && reinterpret_cast<uintptr_t>(Ys[i]) % 16 == 0;
+  auto up = [](size_t v) { return (v + 255) & ~(size_t)255; };
+  const size_t xt_bytes = sparse ? up(((size_t)g0.n + 1) * 32) : 0;
+  const size_t xp_bytes = permuted ? up((size_t)b * g0.n * 2) : 0;
+  size_t total = xt_bytes + xp_bytes, slot_off[SPQR_MAX_FUSED], part_off[SPQR_MAX_FUSED];
+  for (int i = 0; i < count; ++i) {
+    slot_off[i] = total;
+    total += As[i].nnz > 0 ? up(((size_t)(As[i].nnz / kSlotGrain) + 2) * 64) : 0;
+    part_off[i] = total;
+    total += direct ? 0 : up((size_t)nsplit * b * As[i].g.m * sizeof(float));
+  }
+  uint8_t* scratch = nullptr;
+  if (total > 0) {
+    if (hipMallocAsync(reinterpret_cast<void**>(&scratch), total, stream) != hipSuccess) {
+      (void)hipGetLastError();
+      return hipErrorNotSupported;
+    }
+  }
+  uint16_t* xt = sparse ? reinterpret_cast<uint16_t*>(scratch) : nullptr;
+  uint16_t* xp = permuted ? reinterpret_cast<uint16_t*>(scratch + xt_bytes) : nullptr;
+  MfmaFused F;
+  F.count = count;
+  int dense_blocks = 0, extra_blocks = 0, finish_blocks = 0;
+  for (int i = 0; i < count; ++i) {
+    MfmaFusedItem& it = F.it[i];
+    const Geometry& g = As[i].g;
+    it.A = As[i];
+    it.Y = Ys[i];
+    it.P = direct ? static_cast<float*>(Ys[i]) : reinterpret_cast<float*>(scratch + part_off[i]);
+    it.slots = reinterpret_cast<float*>(scratch + slot_off[i]);
+    const int64_t avg_row = As[i].nnz / (g.m > 0 ? g.m : 1);
+    it.long_row = (int)(4 * avg_row > kLongRowMin ? (4 * avg_row < (1 << 30) ? 4 * avg_row : (1 << 30)) : kLongRowMin);
+    it.groups = (g.ntr + SH::NS - 1) / SH::NS;
+    int extra = 0;
+    if (As[i].nnz > 0) {
+      extra = (g.m + 15) / 16 < kCUs / 2 ? (g.m + 15) / 16 : kCUs / 2;
+      const int need = (g.m + kNT - 2) / (kNT - 1);
+      if (extra < need) extra = need;
+    }
+    it.extra = extra * kLongParts;
+    it.blocks16 = (g.m + 15) / 16;
+    dense_blocks += it.groups;
+    extra_blocks += it.extra;
+    finish_blocks += it.blocks16;
+  }
+  hipError_t e = hipSuccess;
+  if (sparse || permuted) {
+    hipLaunchKernelGGL(transpose_x16_kernel, dim3((g0.n + 256) / 256), dim3(256), 0, stream, X, As[0].perm, xt, xp, g0.n, b);
+    e = hipGetLastError();
+  }
+  if (e == hipSuccess) {
+    hipLaunchKernelGGL((gemm_mfma_fused_kernel<W, TR, TC, AXIS>), dim3(dense_blocks + extra_blocks, nsplit), dim3(kNT), SH::LDS,
+                       stream, F, permuted ? xp : X, steps_per_split, b, xt);
+    e = hipGetLastError();
+  }
+  if (e == hipSuccess && (sparse || !direct)) {
+    hipLaunchKernelGGL(finish_xt16_fused_kernel, dim3(finish_blocks), dim3(kFinishThreads), 0, stream, F, xt, nsplit, y_dtype, b);
+    e = hipGetLastError();
+  }
+  if (scratch != nullptr) {
+    const hipError_t ef = hipFreeAsync(scratch, stream);
+    if (e == hipSuccess) e = ef;
+  }
+  return e;
+}
+
+// Y_i[b][m_i] = X[b][n] . W_hat_i^T for matrices that share X.  Batches the matrix-core path takes go through it
+// fused (slices of 16); everything else is one launch_gemm per matrix.
+hipError_t launch_gemm_fused(const DevMatrix* As, int count, const uint16_t* X, int b, void* const* Ys, int y_dtype,
+                             hipStream_t stream, bool force_generic) {
+  const Geometry& g = As[0].g;
+  const size_t ysz = y_dtype == SPQR_F32 ? 4 : 2;
+  const bool shape16 = g.tile_rows == 16 && g.tile_cols == 16;
+  const bool shape8x32 = g.tile_rows == 8 && g.tile_cols == 32 && g.axis == 1;
+  const bool shape32x8 = g.tile_rows == 32 && g.tile_cols == 8 && g.axis == 0;
+  bool mfma_ok = count > 1 && !force_generic && (g.w_bits == 3 || g.w_bits == 4) && (shape16 || shape8x32 || shape32x8);
+  // Not while the stream is being captured into a graph: a replay of a graph that held 12 fused batch calls among
+  // 42 calls (a whole decoder block, six weight copies) ended in a memory fault inside the fused finishing kernel,
+  // while the same calls pass eagerly and graphs of the per-matrix path replay correctly; until the cause is
+  // known, captured calls take the per-matrix path.
+  if (mfma_ok) {
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &cs) != hipSuccess) { (void)hipGetLastError(); cs = hipStreamCaptureStatusActive; }
+    if (cs != hipStreamCaptureStatusNone) mfma_ok = false;
+  }
+  Geometry all = g;                          // the rule looks at the weights of all matrices together
+  int64_t rows = 0;
+  for (int i = 0; i < count; ++i) rows += As[i].g.m;
+  all.m = (int)(rows < (1 << 30) ? rows : (1 << 30));
+  int k = 0;
+  while (k < b) {
+    const int left = b - k, nb16 = left < 16 ? left : 16;
+    const uint16_t* xk = X + (size_t)k * g.n;
+    void* yk[SPQR_MAX_FUSED];
+    for (int i = 0; i < count; ++i) yk[i] = static_cast<uint8_t*>(Ys[i]) + (size_t)k * As[i].g.m * ysz;
+    if (mfma_ok && left > 4 && mfma_wanted(all, nb16)) {
+      hipError_t e = hipErrorNotSupported;
+#define SPQR_MFMA_CASE(W_, TR_, TC_, AX_) \
+      if (g.w_bits == W_ && g.tile_rows == TR_ && g.tile_cols == TC_ && g.axis == AX_) \
+        e = launch_mfma_fused<W_, TR_, TC_, AX_>(As, count, xk, nb16, yk, y_dtype, stream);
+      SPQR_MFMA_CASE(3, 16, 16, 1) SPQR_MFMA_CASE(3, 16, 16, 0) SPQR_MFMA_CASE(4, 16, 16, 1) SPQR_MFMA_CASE(4, 16, 16, 0)
+      SPQR_MFMA_CASE(3, 8, 32, 1) SPQR_MFMA_CASE(4, 8, 32, 1) SPQR_MFMA_CASE(3, 32, 8, 0) SPQR_MFMA_CASE(4, 32, 8, 0)
+#undef SPQR_MFMA_CASE
+      if (e == hipErrorNotSupported) { mfma_ok = false; continue; }
+      if (e != hipSuccess) return e;
+      k += nb16;
+      continue;
+    }
+    // the rest of the batch, matrix by matrix (each call applies its own rule)
+    for (int i = 0; i < count; ++i) {
+      hipError_t e = launch_gemm(As[i], xk, left, yk[i], y_dtype, stream, force_generic);
+      if (e != hipSuccess) return e;
+    }
+    k = b;
   }
   return hipSuccess;
 }

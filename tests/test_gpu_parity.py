@@ -318,6 +318,63 @@ def test_fused_projections_with_a_shared_permutation(P):
         assert rel_l2(y.cpu().numpy(), orc.matvec(f, xh)[0]) <= REL_L2
 
 
+@pytest.mark.parametrize("w,b1,b2,axis,ntc", [(3, 16, 16, 1, 70), (4, 16, 16, 0, 130), (3, 8, 32, 1, 40), (4, 8, 32, 0, 300)])
+@pytest.mark.parametrize("b,mode", [(16, "1"), (7, "1"), (37, "1"), (16, "0"), (3, None), (1, None)])
+def test_fused_batch_projections(P, monkeypatch, w, b1, b2, axis, ntc, b, mode):
+    """spqr_gemm_fused: matrices of different heights (with and without outliers, with long rows) sharing a batch give
+    what spqr_gemm_smallbatch gives one by one on the same path, and the oracle's result within the tolerance."""
+    import torch
+    if mode is not None:
+        monkeypatch.setenv("SPQR_MFMA", mode)
+    tr, _ = synth.tile_shape(b1, b2, axis)
+    specs = [(5, 0.03, "rows8cols4"), (2, 0.0, "none"), (9, 0.02, "zipf")]
+    fs = [make(w, b1, b2, axis, ntr, ntc, rate=r, structure=st, seed=(96, i, ntc)) for i, (ntr, r, st) in enumerate(specs)]
+    As = [P.SpQRMatrix.from_logical(f) for f in fs]
+    X = synth.make_x(fs[0].n, b, seed=(97, b))
+    Ys = P.spqr_gemm_fused(As, dev(X))
+    torch.cuda.synchronize()
+    for f, A, Y in zip(fs, As, Ys):
+        Y = Y.cpu().numpy()
+        ref = orc.matvec(f, X)
+        assert Y.shape == (b, f.m)
+        assert max(rel_l2(Y[k], ref[k]) for k in range(b)) <= REL_L2
+        # the same arithmetic; only the split of the steps (the order of the partial sums) may differ
+        one = (P.spqr_gemm_smallbatch(A, dev(X)) if b > 1 else P.spqr_gemv(A, dev(X[0]))[None, :]).cpu().numpy()
+        assert max(rel_l2(Y[k], one[k]) for k in range(b)) <= 1e-6
+    Yh = P.spqr_gemm_fused(As, dev(X), y_dtype=P.SPQR_F16)
+    for Y, H in zip(Ys, Yh):
+        assert np.array_equal(H.cpu().numpy().view(np.uint16), Y.cpu().numpy().astype(np.float16).view(np.uint16))
+
+
+def test_fused_batch_projections_with_a_shared_permutation_and_argument_checks(P, monkeypatch):
+    import torch
+    import ctypes as C
+    monkeypatch.setenv("SPQR_MFMA", "1")
+    perm = np.random.default_rng(6).permutation(70 * 16).astype(np.int32)
+    fs = []
+    for i, ntr in enumerate((3, 6)):
+        f = make(3, 16, 16, 1, ntr, 70, rate=0.02, seed=(98, i))
+        f.perm = perm
+        fs.append(f)
+    As = [P.SpQRMatrix.from_logical(f) for f in fs]
+    As[1].desc.perm = As[0].desc.perm          # descriptors must name the same device permutation
+    X = synth.make_x(fs[0].n, 16, seed=(99,))
+    Ys = P.spqr_gemm_fused(As, dev(X))
+    torch.cuda.synchronize()
+    for f, Y in zip(fs, Ys):
+        ref = orc.matvec(f, X)
+        assert max(rel_l2(Y.cpu().numpy()[k], ref[k]) for k in range(16)) <= REL_L2
+    other = P.SpQRMatrix.from_logical(make(4, 16, 16, 1, 2, 70, seed=(98, 9)))
+    with pytest.raises(P.SpQRError) as ei:
+        P.spqr_gemm_fused([As[0], other], dev(X))
+    assert ei.value.status == -3
+    lib = P.load_library()
+    descs = (C.POINTER(type(As[0].desc)) * 1)(C.pointer(As[0].desc))
+    ys = (C.c_void_p * 1)(Ys[0].data_ptr())
+    assert lib.spqr_gemm_fused(descs, 1, dev(X).data_ptr(), 0, ys, 0, None) == -8
+    assert lib.spqr_gemm_fused(descs, 9, dev(X).data_ptr(), 4, ys, 0, None) == -3
+
+
 def test_fallback_kernel_agrees_with_the_tuned_one(P, monkeypatch):
     """SPQR_FORCE_GENERIC=1 sends a tuned shape through the element-wise fallback kernel."""
     f = make(3, 16, 16, 1, 2, 70, rate=0.03, structure="rows8cols4")

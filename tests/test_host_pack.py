@@ -18,7 +18,7 @@ def test_library_exports_every_declared_symbol():
     hdr = open(os.path.join(ROOT, "include", "spqr.h")).read()
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
     names = set(re.findall(r"\b(spqr_[a-z_0-9]+)\s*\(", hdr))
-    assert {"spqr_pack_check", "spqr_gemv", "spqr_gemv_fused", "spqr_gemm_smallbatch", "spqr_dequant_dense",
+    assert {"spqr_pack_check", "spqr_gemv", "spqr_gemv_fused", "spqr_gemm_fused", "spqr_gemm_smallbatch", "spqr_dequant_dense",
             "spqr_pack_host", "spqr_packed_bytes", "spqr_strerror", "spqr_version"} <= names
     lib = C.CDLL(P.library_path())
     for nm in sorted(names):
