@@ -138,4 +138,14 @@ def test_fused_projections_at_full_size(P):
             ref = orc.matvec_rows(f, X, rows)[0]
             got = y.cpu().numpy()[rows].astype(np.float64)
             assert np.linalg.norm(got - ref) / np.linalg.norm(ref) <= REL_L2
+        # the same projections at batch 16 (the matrix-core path, one launch set for all of them)
+        X16 = synth.make_x(fs[0].n, 16, seed=(79, len(names)))
+        Ys = P.spqr_gemm_fused(As, dev(X16))
+        torch.cuda.synchronize()
+        for f, Y in zip(fs, Ys):
+            rows = sample_rows(f)
+            ref = orc.matvec_rows(f, X16, rows)
+            got = Y.cpu().numpy()[:, rows].astype(np.float64)
+            for k in range(16):
+                assert np.linalg.norm(got[k] - ref[k]) / np.linalg.norm(ref[k]) <= REL_L2
         del fs, As
