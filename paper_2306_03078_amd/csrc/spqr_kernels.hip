@@ -166,6 +166,29 @@ __device__ __forceinline__ uint32_t pair_class_f16(const uint32_t* c, const Shif
   }
 }
 
+// The same with the shifts written out (no state carried between pairs; the compiler shares a shifted
+// dword between the pairs that are extracted next to each other).
+template <int W>
+__device__ __forceinline__ uint32_t pair_class_inline(const uint32_t* c, int q, const ClassConsts& k) {
+  if constexpr (W == 4) {
+    const int e = q & 3;
+    const uint32_t d = c[q >> 2], src = e < 2 ? d : (d >> 8);
+    return (src & k.mask[e & 1]) | k.magic[e & 1];
+  } else {
+    const int t3 = q >> 4, e = q & 15;
+    if (e < 15) {
+      const int j = e / 5, i = e % 5;
+      const uint32_t d = c[3 * t3 + j], src = i < 3 ? d : (d >> 9);
+      return (src & k.mask[i % 3]) | k.magic[i % 3];
+    } else {                                         // bits 15 / 31 of the three dwords -> bits 6, 7, 8
+      uint32_t t = ((c[3 * t3] >> 9) & k.m0) | k.magic[2];
+      t = ((c[3 * t3 + 1] >> 8) & k.m1) | t;
+      t = ((c[3 * t3 + 2] >> 7) & k.m2) | t;
+      return t;
+    }
+  }
+}
+
 // ---------------------------------------------------------------------------
 // Fused GEMV for tiles of 256 codes.
 //   W     code width (3, 4)
@@ -950,6 +973,11 @@ __device__ __forceinline__ void gemm_mfma_body(const DevMatrix& A, const uint16_
   const int i16 = lane & 15, g4 = lane >> 4;
   const PairConsts kc = make_pair_consts<W>();
   const PairConsts k3 = make_pair_consts<3>();
+  // Groups along the tile's columns, and the class of a code pair (the offset K its in-place extraction leaves,
+  // see CodeClass) a function of its column alone: then K folds into the column's additive constant and most
+  // shifts of the extraction go away.  True for 4-bit codes and for 3-bit codes in rows of 16 pairs.
+  constexpr bool FOLD = AXIS == 1 && (W == 4 || PPR == 16);
+  const ClassConsts kk = make_class_consts<W>();
   float4_t D[MB][2];
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb) { D[mb][0] = float4_t{0.f, 0.f, 0.f, 0.f}; D[mb][1] = float4_t{0.f, 0.f, 0.f, 0.f}; }
@@ -1021,6 +1049,11 @@ __device__ __forceinline__ void gemm_mfma_body(const DevMatrix& A, const uint16_
       fa[2 * p + 1] = fmaf((float)sq.y, c1, c2);
       fb[2 * p] = fa[2 * p] * fmaf((float)zq.x, e1, e2);
       fb[2 * p + 1] = fa[2 * p + 1] * fmaf((float)zq.y, e1, e2);
+      if constexpr (FOLD) {                  // the extracted value is K + code/2^W instead of 1 + code/2^W
+        const float K = CodeClass<W, true>::K(CodeClass<W, true>::of_pair(p));   // a constant once the loop is unrolled
+        fb[2 * p] = fmaf(1.f - K, fa[2 * p], fb[2 * p]);
+        fb[2 * p + 1] = fmaf(1.f - K, fa[2 * p + 1], fb[2 * p + 1]);
+      }
     }
     uint32_t* mine = buf + lane * S;
 #pragma unroll
@@ -1032,7 +1065,7 @@ __device__ __forceinline__ void gemm_mfma_body(const DevMatrix& A, const uint16_
 #pragma unroll
         for (int d = 0; d < 4; ++d) {
           const int dw = 4 * k4 + d, r = dw / (PC / 2), p = (PC / 2) * ph + dw % (PC / 2);
-          const half2_t q2 = as_half2(pair_f16<W>(t.c, r * PPR + p, kc));
+          const half2_t q2 = as_half2(FOLD ? pair_class_inline<W>(t.c, r * PPR + p, kk) : pair_f16<W>(t.c, r * PPR + p, kc));
           const int g0 = AXIS == 1 ? 2 * p : r, g1 = AXIS == 1 ? 2 * p + 1 : r;
           half2_t w;
           w.x = (_Float16)fmaf((float)q2.x, fa[g0], fb[g0]);
