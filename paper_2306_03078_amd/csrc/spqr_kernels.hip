@@ -939,7 +939,7 @@ template <int TR, int TC> struct MfmaShape {
 // `group` is the group of NS strips this workgroup multiplies, or negative for a workgroup that takes long outlier
 // rows instead: then it is number `extra` of `nextra` such workgroups of its matrix.  `split` of the splits of the
 // steps, `smem` the workgroup's dynamic LDS.
-template <int W, int TR, int TC, int AXIS>
+template <int W, int TR, int TC, int AXIS, bool ONE>
 __device__ __forceinline__ void gemm_mfma_body(const DevMatrix& A, const uint16_t* __restrict__ X, float* __restrict__ P,
                                                int64_t split_stride, int steps_per_split, int batch,
                                                const uint16_t* __restrict__ XT, float* __restrict__ slots, int long_row,
@@ -1028,7 +1028,7 @@ __device__ __forceinline__ void gemm_mfma_body(const DevMatrix& A, const uint16_
     const int L = min(64, ntc - 64 * st);
     __syncthreads();                         // every wavefront is done with the previous piece of X
     store_x(st);
-    fetch_x(st + 1);
+    if constexpr (!ONE) fetch_x(st + 1);
     __syncthreads();
     const uint32_t a2 = t.s[T::SD - 2], b2 = t.s[T::SD - 1];
     const float s_s = h2f((uint16_t)(a2 & 0xFFFF)), z_s = h2f((uint16_t)(a2 >> 16));
@@ -1112,18 +1112,25 @@ __device__ __forceinline__ void gemm_mfma_body(const DevMatrix& A, const uint16_
     }
   };
 
-  T t0, t1;
-  fetch_x(s_lo);
-  issue(t0, s_lo);
-  int st = s_lo;
-  while (st + 1 < s_hi) {                    // workgroup-uniform; two steps per trip, one exit at the bottom
-    issue(t1, st + 1);
-    run_step(t0, st);
-    issue(t0, st + 2);                       // a dummy behind the last step
-    run_step(t1, st + 1);
-    st += 2;
+  if constexpr (ONE) {                       // one step per workgroup: no second tile, no loop (fewer registers)
+    T t0;
+    fetch_x(s_lo);
+    issue(t0, s_lo);
+    run_step(t0, s_lo);
+  } else {
+    T t0, t1;
+    fetch_x(s_lo);
+    issue(t0, s_lo);
+    int st = s_lo;
+    while (st + 1 < s_hi) {                  // workgroup-uniform; two steps per trip, one exit at the bottom
+      issue(t1, st + 1);
+      run_step(t0, st);
+      issue(t0, st + 2);                     // a dummy behind the last step
+      run_step(t1, st + 1);
+      st += 2;
+    }
+    if (st < s_hi) run_step(t0, st);
   }
-  if (st < s_hi) run_step(t0, st);
 
   // D[mb][row 16*mb + 4*g4 + v][batch i16]
   if (active && i16 < batch) {
@@ -1144,8 +1151,18 @@ gemm_mfma_kernel(DevMatrix A, const uint16_t* __restrict__ X, float* __restrict_
                  int groups) {
   extern __shared__ __align__(16) uint8_t smem[];
   const int bx = blockIdx.x;
-  gemm_mfma_body<W, TR, TC, AXIS>(A, X, P, split_stride, steps_per_split, batch, XT, slots, long_row,
-                                  bx < groups ? bx : -1, (int)blockIdx.y, bx - groups, (int)gridDim.x - groups, smem);
+  gemm_mfma_body<W, TR, TC, AXIS, false>(A, X, P, split_stride, steps_per_split, batch, XT, slots, long_row,
+                                         bx < groups ? bx : -1, (int)blockIdx.y, bx - groups, (int)gridDim.x - groups, smem);
+}
+
+template <int W, int TR, int TC, int AXIS>
+__global__ void __launch_bounds__((64 * MfmaShape<TR, TC>::NS), (TC == 32 ? 2 : 3))
+gemm_mfma_one_kernel(DevMatrix A, const uint16_t* __restrict__ X, float* __restrict__ P, int64_t split_stride,
+                     int batch, const uint16_t* __restrict__ XT, float* __restrict__ slots, int long_row, int groups) {
+  extern __shared__ __align__(16) uint8_t smem[];
+  const int bx = blockIdx.x;
+  gemm_mfma_body<W, TR, TC, AXIS, true>(A, X, P, split_stride, 1, batch, XT, slots, long_row,
+                                        bx < groups ? bx : -1, (int)blockIdx.y, bx - groups, (int)gridDim.x - groups, smem);
 }
 
 // Several matrices that share the batch X and the format (q/k/v, gate/up of a decoder block) in one grid:
@@ -1183,7 +1200,7 @@ gemm_mfma_fused_kernel(MfmaFused F, const uint16_t* __restrict__ X, int steps_pe
     }
   }
   const MfmaFusedItem& it = F.it[i];
-  gemm_mfma_body<W, TR, TC, AXIS>(it.A, X, it.P, (int64_t)batch * it.A.g.m, steps_per_split, batch, XT, it.slots,
+  gemm_mfma_body<W, TR, TC, AXIS, false>(it.A, X, it.P, (int64_t)batch * it.A.g.m, steps_per_split, batch, XT, it.slots,
                                   it.long_row, dense ? bx : -1, (int)blockIdx.y, bx, it.extra, smem);
 }
 
@@ -1760,9 +1777,22 @@ static hipError_t launch_mfma(const DevMatrix& A, const uint16_t* X, int b, void
     e = hipGetLastError();
   }
   if (e == hipSuccess) {
-    hipLaunchKernelGGL((gemm_mfma_kernel<W, TR, TC, AXIS>), dim3(groups + extra * kLongParts, nsplit), dim3(kNT), SH::LDS,
-                       stream, A, permuted ? xp : X, part, split_stride, steps_per_split, b, xt, slots, long_row, groups);
-    e = hipGetLastError();
+    if (steps_per_split == 1) {
+      static PerDevice ready1;
+      if (!ready1.get(dev)) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_one_kernel<W, TR, TC, AXIS>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)SH::LDS);
+        if (e == hipSuccess) ready1.set(dev, 1);
+      }
+      const size_t lds_now = (size_t)SH::NS * 64 * kMfmaTileStride * 4 + (size_t)b * SH::XROW;   // only b rows of X are staged
+      if (e == hipSuccess)
+        hipLaunchKernelGGL((gemm_mfma_one_kernel<W, TR, TC, AXIS>), dim3(groups + extra * kLongParts, nsplit), dim3(kNT), lds_now,
+                           stream, A, permuted ? xp : X, part, split_stride, b, xt, slots, long_row, groups);
+    } else {
+      hipLaunchKernelGGL((gemm_mfma_kernel<W, TR, TC, AXIS>), dim3(groups + extra * kLongParts, nsplit), dim3(kNT), SH::LDS,
+                         stream, A, permuted ? xp : X, part, split_stride, steps_per_split, b, xt, slots, long_row, groups);
+    }
+    if (e == hipSuccess) e = hipGetLastError();
   }
   if (e == hipSuccess && (sparse || !direct)) {
     hipLaunchKernelGGL(finish_xt16_kernel, dim3((g.m + 15) / 16), dim3(kFinishThreads), 0, stream, A, xt, slots, part, nsplit,
