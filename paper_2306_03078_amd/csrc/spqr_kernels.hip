@@ -1182,8 +1182,8 @@ struct MfmaFused {
   MfmaFusedItem it[SPQR_MAX_FUSED];
 };
 
-template <int W, int TR, int TC, int AXIS>
-__global__ void __launch_bounds__((64 * MfmaShape<TR, TC>::NS), 2)
+template <int W, int TR, int TC, int AXIS, bool ONE>
+__global__ void __launch_bounds__((64 * MfmaShape<TR, TC>::NS), (ONE && TC != 32 ? 3 : 2))
 gemm_mfma_fused_kernel(MfmaFused F, const uint16_t* __restrict__ X, int steps_per_split, int batch,
                        const uint16_t* __restrict__ XT) {
   extern __shared__ __align__(16) uint8_t smem[];
@@ -1200,7 +1200,7 @@ gemm_mfma_fused_kernel(MfmaFused F, const uint16_t* __restrict__ X, int steps_pe
     }
   }
   const MfmaFusedItem& it = F.it[i];
-  gemm_mfma_body<W, TR, TC, AXIS, false>(it.A, X, it.P, (int64_t)batch * it.A.g.m, steps_per_split, batch, XT, it.slots,
+  gemm_mfma_body<W, TR, TC, AXIS, ONE>(it.A, X, it.P, (int64_t)batch * it.A.g.m, ONE ? 1 : steps_per_split, batch, XT, it.slots,
                                   it.long_row, dense ? bx : -1, (int)blockIdx.y, bx, it.extra, smem);
 }
 
@@ -1880,8 +1880,11 @@ static hipError_t launch_mfma_fused(const DevMatrix* As, int count, const uint16
   static PerDevice ready;
   const int dev = current_device();
   if (!ready.get(dev)) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_fused_kernel<W, TR, TC, AXIS>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_fused_kernel<W, TR, TC, AXIS, false>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)SH::LDS);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_fused_kernel<W, TR, TC, AXIS, true>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)SH::LDS);
     if (e != hipSuccess) return e;
     ready.set(dev, 1);
   }
@@ -1948,8 +1951,12 @@ static hipError_t launch_mfma_fused(const DevMatrix* As, int count, const uint16
     e = hipGetLastError();
   }
   if (e == hipSuccess) {
-    hipLaunchKernelGGL((gemm_mfma_fused_kernel<W, TR, TC, AXIS>), dim3(dense_blocks + extra_blocks, nsplit), dim3(kNT), SH::LDS,
-                       stream, F, permuted ? xp : X, steps_per_split, b, xt);
+    if (steps_per_split == 1)                // the variant without the second tile; only b rows of X are staged
+      hipLaunchKernelGGL((gemm_mfma_fused_kernel<W, TR, TC, AXIS, true>), dim3(dense_blocks + extra_blocks, nsplit), dim3(kNT),
+                         (size_t)SH::NS * 64 * kMfmaTileStride * 4 + (size_t)b * SH::XROW, stream, F, permuted ? xp : X, 1, b, xt);
+    else
+      hipLaunchKernelGGL((gemm_mfma_fused_kernel<W, TR, TC, AXIS, false>), dim3(dense_blocks + extra_blocks, nsplit), dim3(kNT),
+                         SH::LDS, stream, F, permuted ? xp : X, steps_per_split, b, xt);
     e = hipGetLastError();
   }
   if (e == hipSuccess && (sparse || !direct)) {
