@@ -15,6 +15,9 @@
 #include <atomic>
 #include <cstdint>
 #include <cstdlib>
+#include <mutex>
+#include <queue>
+#include <vector>
 #include <type_traits>
 
 #include <algorithm>
@@ -1694,25 +1697,60 @@ static hipError_t launch_tuned(const DevMatrix& A, const uint16_t* x, void* y, i
 }
 
 // ---- batches above 4 on 16x16 tiles: matrix-core dense pass + outlier pass ----
-// Steps per workgroup of the dense pass.  The chip holds `slots` workgroups at a time; a
-// workgroup costs its steps plus a start-up of about 0.7 step, a round of workgroups
-// that leaves half of the slots empty runs its steps faster, and every further split
-// costs a partial result to write and read.  Ties go to fewer splits.
-static int mfma_steps_per_split(int groups, int nsteps, int slots) {
+// Steps per workgroup of the dense pass, chosen by simulating the launch: the workgroups start in grid order
+// (split by split: the strip groups, behind those of the first split the long-row workgroups) on the first free of
+// the chip's workgroup slots; a dense workgroup costs its steps plus a start-up of 0.2 step, a long-row workgroup
+// 0.45 step, and every split 0.2 step for its partial result (written, and read again by the finishing kernel).
+// The shortest schedule wins, ties go to fewer splits.  The constants are fitted to sweeps over the steps on
+// MI355X (eight projection shapes of the 7B to 65B configurations at batch 8 and 16, every count of steps: the choice is
+// within 2.2 % of the best measured one).  slots1 = slots when a workgroup takes one step (the variant with fewer registers),
+// slots = otherwise.  Results are remembered per argument tuple (the simulation costs up to a few milliseconds).
+static double mfma_schedule_length(int groups, int nsteps, int s, int slots, int nlong) {
+  const int nsplit = (nsteps + s - 1) / s;
+  std::priority_queue<double, std::vector<double>, std::greater<double>> free_at;
+  for (int i = 0; i < slots; ++i) free_at.push(0.0);
+  double end = 0.0;
+  auto run = [&](int count, double cost) {
+    for (int i = 0; i < count; ++i) {
+      const double t = free_at.top() + cost;
+      free_at.pop();
+      free_at.push(t);
+      if (t > end) end = t;
+    }
+  };
+  for (int y = 0; y < nsplit; ++y) {
+    const int steps = s < nsteps - y * s ? s : nsteps - y * s;
+    run(groups, 0.2 + steps);
+    run(nlong, y == 0 ? 0.45 : 0.02);         // behind the first split they leave at once
+  }
+  return end + 0.2 * nsplit;
+}
+
+static int mfma_steps_per_split(int groups, int nsteps, int slots1, int slots, int nlong) {
   if (const char* e = std::getenv("SPQR_MFMA_STEPS")) {        // pins it for tuning runs
     const int v = std::atoi(e);
     if (v >= 1) return v < nsteps ? v : nsteps;
   }
+  struct Known { int groups, nsteps, slots1, slots, nlong, best; };
+  static std::mutex lock;
+  static std::vector<Known> known;
+  {
+    std::lock_guard<std::mutex> hold(lock);
+    for (const Known& k : known)
+      if (k.groups == groups && k.nsteps == nsteps && k.slots1 == slots1 && k.slots == slots && k.nlong == nlong) return k.best;
+  }
   int best = nsteps;
   double best_cost = 1e30;
-  for (int s = nsteps; s >= 1; --s) {
-    const int nsplit = (nsteps + s - 1) / s;
-    const long wgs = (long)groups * nsplit;
-    const long full = wgs / slots, rest = wgs % slots;
-    const double rounds = (double)full + (rest == 0 ? 0.0 : (rest > slots / 2 ? 1.0 : 0.6));
-    const double cost = rounds * (s + 0.7) + 0.05 * nsplit;
+  // candidates: every count of steps up to 32, and all of them in one workgroup; launches of more than
+  // 200 000 workgroups are not simulated (only very large matrices: any choice fills the chip)
+  for (int s = nsteps; s >= 1; s = (s > 32 ? 32 : s - 1)) {
+    const long wgs = (long)(groups + nlong) * ((nsteps + s - 1) / s);
+    if (wgs > 200000) continue;
+    const double cost = mfma_schedule_length(groups, nsteps, s, s == 1 ? slots1 : slots, nlong);
     if (cost < best_cost - 1e-9) { best_cost = cost; best = s; }
   }
+  std::lock_guard<std::mutex> hold(lock);
+  if (known.size() < 4096) known.push_back(Known{groups, nsteps, slots1, slots, nlong, best});
   return best;
 }
 
@@ -1735,9 +1773,20 @@ static hipError_t launch_mfma(const DevMatrix& A, const uint16_t* X, int b, void
   }
   const int groups = (g.ntr + SH::NS - 1) / SH::NS;
   const int nsteps = (g.ntc + 63) / 64;
-  const int steps_per_split = mfma_steps_per_split(groups, nsteps, SH::WGS * kCUs);
-  const int nsplit = (nsteps + steps_per_split - 1) / steps_per_split;
   const bool sparse = A.nnz > 0, permuted = A.perm != nullptr;
+  // workgroups for the long outlier rows: kLongParts per range of rows, a range of fewer rows than a workgroup has
+  // threads, 128 ranges if the matrix is large (each of them costs a look at its row pointers, long rows or not)
+  constexpr int kNT = 64 * SH::NS;
+  int extra = 0;
+  if (sparse) {
+    extra = (g.m + 15) / 16 < kCUs / 2 ? (g.m + 15) / 16 : kCUs / 2;
+    const int need = (g.m + kNT - 2) / (kNT - 1);
+    if (extra < need) extra = need;
+  }
+  // the one-step variant fits three workgroups on a CU while the staged batch rows leave the LDS for them
+  const int wgs1 = (TC != 32 && 3 * ((size_t)SH::NS * 64 * kMfmaTileStride * 4 + (size_t)b * SH::XROW + 1024) <= 160 * 1024) ? 3 : SH::WGS;
+  const int steps_per_split = mfma_steps_per_split(groups, nsteps, wgs1 * kCUs, SH::WGS * kCUs, extra * kLongParts);
+  const int nsplit = (nsteps + steps_per_split - 1) / steps_per_split;
   // the dense kernel writes Y itself (16 bytes per store) if nothing has to be added or converted afterwards
   const bool direct = nsplit == 1 && y_dtype == SPQR_F32 && reinterpret_cast<uintptr_t>(Y) % 16 == 0;
   auto up = [](size_t v) { return (v + 255) & ~(size_t)255; };
@@ -1758,15 +1807,6 @@ static hipError_t launch_mfma(const DevMatrix& A, const uint16_t* X, int b, void
   uint16_t* xp = permuted ? reinterpret_cast<uint16_t*>(scratch + xt_bytes + slot_bytes) : nullptr;
   float* part = direct ? static_cast<float*>(Y) : reinterpret_cast<float*>(scratch + xt_bytes + slot_bytes + xp_bytes);
   const int64_t split_stride = (int64_t)b * g.m;
-  // workgroups for the long outlier rows: kLongParts per range of rows, a range of fewer rows than a workgroup has
-  // threads, 128 ranges if the matrix is large (each of them costs a look at its row pointers, long rows or not)
-  constexpr int kNT = 64 * SH::NS;
-  int extra = 0;
-  if (sparse) {
-    extra = (g.m + 15) / 16 < kCUs / 2 ? (g.m + 15) / 16 : kCUs / 2;
-    const int need = (g.m + kNT - 2) / (kNT - 1);
-    if (extra < need) extra = need;
-  }
   // a row is long if it holds far more outliers than the average row (and at least kLongRowMin): rows like the
   // average one stay with their strip's workgroup in the finishing kernel, whatever the outlier rate
   const int64_t avg_row = A.nnz / (g.m > 0 ? g.m : 1);
@@ -1890,13 +1930,23 @@ static hipError_t launch_mfma_fused(const DevMatrix* As, int count, const uint16
   }
   constexpr int kNT = 64 * SH::NS;
   const int nsteps = (g0.ntc + 63) / 64;
-  int total_groups = 0;
+  int total_groups = 0, total_extra = 0, extras[SPQR_MAX_FUSED];
   bool sparse = false;
   for (int i = 0; i < count; ++i) {
-    total_groups += (As[i].g.ntr + SH::NS - 1) / SH::NS;
+    const Geometry& g = As[i].g;
+    total_groups += (g.ntr + SH::NS - 1) / SH::NS;
     sparse = sparse || As[i].nnz > 0;
+    int extra = 0;                           // workgroups for the long outlier rows, as in launch_mfma
+    if (As[i].nnz > 0) {
+      extra = (g.m + 15) / 16 < kCUs / 2 ? (g.m + 15) / 16 : kCUs / 2;
+      const int need = (g.m + kNT - 2) / (kNT - 1);
+      if (extra < need) extra = need;
+    }
+    extras[i] = extra * kLongParts;
+    total_extra += extras[i];
   }
-  const int steps_per_split = mfma_steps_per_split(total_groups, nsteps, SH::WGS * kCUs);
+  const int wgs1 = (TC != 32 && 3 * ((size_t)SH::NS * 64 * kMfmaTileStride * 4 + (size_t)b * SH::XROW + 1024) <= 160 * 1024) ? 3 : SH::WGS;
+  const int steps_per_split = mfma_steps_per_split(total_groups, nsteps, wgs1 * kCUs, SH::WGS * kCUs, total_extra);
   const int nsplit = (nsteps + steps_per_split - 1) / steps_per_split;
   const bool permuted = As[0].perm != nullptr;
   bool direct = nsplit == 1 && y_dtype == SPQR_F32;              // the dense kernel writes the outputs itself (16-byte stores)
@@ -1933,13 +1983,7 @@ static hipError_t launch_mfma_fused(const DevMatrix* As, int count, const uint16
     const int64_t avg_row = As[i].nnz / (g.m > 0 ? g.m : 1);
     it.long_row = (int)(4 * avg_row > kLongRowMin ? (4 * avg_row < (1 << 30) ? 4 * avg_row : (1 << 30)) : kLongRowMin);
     it.groups = (g.ntr + SH::NS - 1) / SH::NS;
-    int extra = 0;
-    if (As[i].nnz > 0) {
-      extra = (g.m + 15) / 16 < kCUs / 2 ? (g.m + 15) / 16 : kCUs / 2;
-      const int need = (g.m + kNT - 2) / (kNT - 1);
-      if (extra < need) extra = need;
-    }
-    it.extra = extra * kLongParts;
+    it.extra = extras[i];
     it.blocks16 = (g.m + 15) / 16;
     dense_blocks += it.groups;
     extra_blocks += it.extra;
