@@ -838,89 +838,119 @@ typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float float4_t __attribute__((ext_vector_type(4)));
 constexpr int kMfmaTileStride = 36;          // dwords per tile quarter (16 rows x 8 bytes + 16: spreads the banks)
 
-// Outlier rows longer than `long_row` entries (far longer than the average row), for the batch path.  Such a row would keep the one CU that owns its
-// strip busy long after the others are done (every outlier is an L1 line look-up), so these rows are taken out of
-// the finishing kernel: extra workgroups of the dense kernel's grid (they run beside the dense workgroups and need
-// nothing from them) own a range of rows each, kLongParts of them the same range: they pick the long rows and
-// write, every kLongParts-th slice of kLongSlice entries each,
+// Outlier rows longer than `long_row` entries (far longer than the average row), for the batch path.  Such a row
+// would keep the one CU that owns its strip busy long after the others are done (every outlier is an L1 line
+// look-up), so these rows are taken out of the finishing kernel: extra workgroups of the dense kernel's grid (they
+// run beside the dense workgroups and need nothing from them) compute, slice by slice of kLongSlice entries,
 // sum_k val_k * XT[col_k][b] for the 16 vectors
-// to slots[lo / kSlotGrain + k][16] for slice k of the row that starts at entry lo -- a long row has fewer slices
-// than multiples of kSlotGrain among its entry indices, so the slots of different rows never meet and the finishing
-// kernel finds them without a search.  A thread takes every NT-th entry of the slice (consecutive threads read
-// consecutive entries) with its whole 32-byte line of XT; the 16 sums are reduced over the lanes in a fixed order.
-constexpr int kLongRowMin = 256, kLongSlice = 2048, kLongParts = 4, kSlotGrain = 256;
+// into slots[lo / kSlotGrain + k][16] for slice k of the row that starts at entry lo -- a long row has no more
+// slices than multiples of kSlotGrain among its entry indices (ceil(len/512) <= floor(len/256) from len = 256 on),
+// so the slots of different rows never meet and the finishing kernel finds them without a search.
+// Work is shared out by entries, not by rows: workgroup wg of nwg owns the slices that start in its equal share
+// [a, z) of the entry indices, so heavy rows next to each other (or one row of many slices) spread over as many
+// workgroups as their entries fill.  It narrows the rows down to NT around the one that holds entry a by a search
+// all threads take part in (NT probes of the row pointers per round; none for up to NT rows, one for up to NT*NT),
+// then walks the rows from there, NT - 1 at a time, up to the first that starts at or behind z.  A slice is one wavefront's: a lane takes every 64th entry (consecutive lanes read
+// consecutive entries) with its whole 32-byte line of XT, all loads in flight at once; the 16 sums are reduced over
+// the lanes in a fixed order and written by the wavefront itself.  The wavefronts of a workgroup take its slices
+// in turn and meet only where the next rows are fetched.
+constexpr int kLongRowMin = 256, kLongSlice = 512, kSlotGrain = 256;
 
 template <int NT>
 __device__ __forceinline__ void long_rows_block(const DevMatrix& A, const uint16_t* __restrict__ XT,
-                                                float* __restrict__ slots, int long_row, int wg, int nwg, int part,
-                                                int nparts, uint8_t* smem) {
-  constexpr int EPT = kLongSlice / NT, NW = NT / 64;
+                                                float* __restrict__ slots, int long_row, int wg, int nwg, uint8_t* smem) {
+  constexpr int EPT = kLongSlice / 64, NW = NT / 64;
   int* rpl = reinterpret_cast<int*>(smem);                                   // NT row pointers
   uint32_t* masks = reinterpret_cast<uint32_t*>(smem + 4 * NT);              // 2 per wavefront
-  float (*lred)[16] = reinterpret_cast<float (*)[16]>(smem + 4 * NT + 8 * NW);
+  int* below = reinterpret_cast<int*>(smem + 4 * NT + 8 * NW);               // 1 per wavefront
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int m = A.g.m;
+  const int64_t nnz = A.nnz;
   const uint32_t zoff = (uint32_t)A.g.n * 32u;                               // the zero line of XT
-  const int rows_per = (m + nwg - 1) / nwg;                                  // < NT (host)
-  const int r0 = wg * rows_per, nrows = min(rows_per, m - r0);
-  if (nrows <= 0) return;                                                    // workgroup-uniform
-  if (tid <= nrows) rpl[tid] = A.row_ptr[r0 + tid];
-  __syncthreads();
-  const bool is_long = tid < nrows && rpl[min(tid, NT - 2) + 1] - rpl[min(tid, NT - 2)] > long_row;
-  const uint64_t bal = __builtin_amdgcn_ballot_w64(is_long);
-  if (lane == 0) { masks[2 * wave] = (uint32_t)bal; masks[2 * wave + 1] = (uint32_t)(bal >> 32); }
-  __syncthreads();
-  for (int w = 0; w < NW; ++w) {
-    uint64_t mask = (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)masks[2 * w]) |      // no sign extension
-                    ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)masks[2 * w + 1]) << 32);
-    while (mask) {                                                           // workgroup-uniform
-      const int r = 64 * w + __builtin_ctzll(mask);
-      mask &= mask - 1;
-      const int lo = rpl[r], hi = rpl[r + 1];
-      // slice k of row r goes to the workgroup with part == (k + r) % nparts: rows of one slice spread out too
-      for (int e0 = lo + ((part + nparts - r % nparts) % nparts) * kLongSlice; e0 < hi; e0 += nparts * kLongSlice) {
-        // all of the thread's entries first, then their lines of XT, then the arithmetic: one round trip each
-        uint32_t off[EPT];
-        float val[EPT];
+  int64_t per = (nnz + nwg - 1) / nwg;
+  if (per < kLongSlice) per = kLongSlice;
+  const int64_t a64 = (int64_t)wg * per;
+  if (a64 >= nnz) return;                                                    // workgroup-uniform
+  const int a = (int)a64, z = (int)(a64 + per < nnz ? a64 + per : nnz);
+  // the last row r with row_ptr[r] <= a lies in [L, H): row_ptr[L] <= a < row_ptr[H] throughout
+  int L = 0, H = m;
+  while (H - L > NT) {                                                       // workgroup-uniform
+    // probe t looks at the end of the t-th of NT parts of the bracket: distinct rows in (L, H], the last is H
+    const int span = H - L;
+    const bool is_below = A.row_ptr[L + (int)(((int64_t)(tid + 1) * span) / NT)] <= a;
+    const uint64_t bal = __builtin_amdgcn_ballot_w64(is_below);
+    if (lane == 0) below[wave] = __builtin_popcountll(bal);
+    __syncthreads();
+    int c = 0;                                                               // probes at or below a: a prefix of them,
 #pragma unroll
-        for (int i = 0; i < EPT; ++i) {
-          const int e = e0 + tid + NT * i;
-          const bool ok = e < hi;
-          off[i] = ok ? (uint32_t)A.col[e] * 32u : zoff;
-          val[i] = ok ? h2f(A.val[e]) : 0.f;
-        }
-        u32x4 x0[EPT], x1[EPT];
+    for (int k = 0; k < NW; ++k) c += below[k];                              // never all (row H is above a)
+    __syncthreads();
+    const int newL = c == 0 ? L : L + (int)(((int64_t)c * span) / NT);
+    H = L + (int)(((int64_t)(c + 1) * span) / NT);
+    L = newL;
+  }
+  // The rows from L on, NT - 1 at a time.  The row that holds entry a is among the first H - L <= NT of them; the
+  // rows before it end at or before a and own nothing here.
+  int taken = 0;                                                             // slices of this workgroup so far
+  for (int r0 = L; r0 < m;) {                                                // workgroup-uniform
+    const int nrows = min(NT - 1, m - r0);
+    if (tid <= nrows) rpl[tid] = A.row_ptr[r0 + tid];
+    __syncthreads();
+    const int t1 = min(tid, NT - 2);
+    const bool is_long = tid < nrows && rpl[t1 + 1] - rpl[t1] > long_row && rpl[t1] < z && rpl[t1 + 1] > a;
+    const uint64_t bal = __builtin_amdgcn_ballot_w64(is_long);
+    if (lane == 0) { masks[2 * wave] = (uint32_t)bal; masks[2 * wave + 1] = (uint32_t)(bal >> 32); }
+    __syncthreads();
+    for (int w = 0; w < NW; ++w) {
+      uint64_t mask = (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)masks[2 * w]) |      // no sign extension
+                      ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)masks[2 * w + 1]) << 32);
+      while (mask) {                                                         // workgroup-uniform
+        const int r = 64 * w + __builtin_ctzll(mask);
+        mask &= mask - 1;
+        const int lo = rpl[r], hi = rpl[r + 1];
+        // the row's slices that start in [a, z)
+        const int k0 = lo >= a ? 0 : (a - lo + kLongSlice - 1) / kLongSlice;
+        for (int k = k0; lo + k * kLongSlice < min(hi, z); ++k) {
+          if (taken++ % NW != wave) continue;                                // wavefront-uniform
+          const int e0 = lo + k * kLongSlice;
+          // all of the lane's entries first, then their lines of XT, then the arithmetic: one round trip each
+          uint32_t off[EPT];
+          float val[EPT];
 #pragma unroll
-        for (int i = 0; i < EPT; ++i) {
-          const u32x4* line = reinterpret_cast<const u32x4*>(reinterpret_cast<const uint8_t*>(XT) + off[i]);
-          x0[i] = line[0];
-          x1[i] = line[1];
-        }
-        float acc[16];
-#pragma unroll
-        for (int b = 0; b < 16; ++b) acc[b] = 0.f;
-#pragma unroll
-        for (int i = 0; i < EPT; ++i) {
-          const uint32_t w[8] = {x0[i].x, x0[i].y, x0[i].z, x0[i].w, x1[i].x, x1[i].y, x1[i].z, x1[i].w};
-#pragma unroll
-          for (int k = 0; k < 8; ++k) {
-            acc[2 * k] = fmaf(val[i], h2f((uint16_t)(w[k] & 0xFFFFu)), acc[2 * k]);
-            acc[2 * k + 1] = fmaf(val[i], h2f((uint16_t)(w[k] >> 16)), acc[2 * k + 1]);
+          for (int i = 0; i < EPT; ++i) {
+            const int e = e0 + lane + 64 * i;
+            const bool ok = e < hi;
+            off[i] = ok ? (uint32_t)A.col[e] * 32u : zoff;
+            val[i] = ok ? h2f(A.val[e]) : 0.f;
           }
-        }
-        int row;
-        const float red = wave_reduce_rows<16>(acc, lane, &row);             // sum over the lanes of vector `row`
-        __syncthreads();                                                     // the previous slice's partials are consumed
-        lred[wave][row] = red;
-        __syncthreads();
-        if (tid < 16) {
-          float t = 0.f;
+          u32x4 x0[EPT], x1[EPT];
 #pragma unroll
-          for (int k = 0; k < NW; ++k) t += lred[k][tid];
-          slots[(int64_t)(lo / kSlotGrain + (e0 - lo) / kLongSlice) * 16 + tid] = t;
+          for (int i = 0; i < EPT; ++i) {
+            const u32x4* line = reinterpret_cast<const u32x4*>(reinterpret_cast<const uint8_t*>(XT) + off[i]);
+            x0[i] = line[0];
+            x1[i] = line[1];
+          }
+          float acc[16];
+#pragma unroll
+          for (int b = 0; b < 16; ++b) acc[b] = 0.f;
+#pragma unroll
+          for (int i = 0; i < EPT; ++i) {
+            const uint32_t xw[8] = {x0[i].x, x0[i].y, x0[i].z, x0[i].w, x1[i].x, x1[i].y, x1[i].z, x1[i].w};
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+              acc[2 * q] = fmaf(val[i], h2f((uint16_t)(xw[q] & 0xFFFFu)), acc[2 * q]);
+              acc[2 * q + 1] = fmaf(val[i], h2f((uint16_t)(xw[q] >> 16)), acc[2 * q + 1]);
+            }
+          }
+          int row;
+          const float red = wave_reduce_rows<16>(acc, lane, &row);           // every lane: the sum of vector `row`
+          if ((lane & 3) == 0) slots[(int64_t)(lo / kSlotGrain + k) * 16 + row] = red;   // 4 lanes hold each sum
         }
       }
     }
+    if (rpl[nrows] >= z) break;                                              // the next row starts behind the share
+    r0 += nrows;
+    __syncthreads();                                                         // everyone is done with these row pointers
   }
 }
 
@@ -960,7 +990,7 @@ __device__ __forceinline__ void gemm_mfma_body(const DevMatrix& A, const uint16_
   uint8_t* xbuf = smem + NS * 64 * S * 4;
   if (group < 0) {                           // long outlier rows
     if (split == 0)
-      long_rows_block<NT>(A, XT, slots, long_row, extra / kLongParts, nextra / kLongParts, extra % kLongParts, kLongParts, smem);
+      long_rows_block<NT>(A, XT, slots, long_row, extra, nextra, smem);
     return;
   }
 
@@ -1699,8 +1729,8 @@ static hipError_t launch_tuned(const DevMatrix& A, const uint16_t* x, void* y, i
 // ---- batches above 4 on 16x16 tiles: matrix-core dense pass + outlier pass ----
 // Steps per workgroup of the dense pass, chosen by simulating the launch: the workgroups start in grid order
 // (split by split: the strip groups, behind those of the first split the long-row workgroups) on the first free of
-// the chip's workgroup slots; a dense workgroup costs its steps plus a start-up of 0.2 step, a long-row workgroup
-// 0.45 step, and every split 0.2 step for its partial result (written, and read again by the finishing kernel).
+// the chip's workgroup slots; a dense workgroup costs its steps plus a start-up of 0.3 step, a long-row workgroup
+// 0.45 step, and every split 0.3 step for its partial result (written, and read again by the finishing kernel).
 // The shortest schedule wins, ties go to fewer splits.  The constants are fitted to sweeps over the steps on
 // MI355X (eight projection shapes of the 7B to 65B configurations at batch 8 and 16, every count of steps: the choice is
 // within 2.2 % of the best measured one).  slots1 = slots when a workgroup takes one step (the variant with fewer registers),
@@ -1720,10 +1750,18 @@ static double mfma_schedule_length(int groups, int nsteps, int s, int slots, int
   };
   for (int y = 0; y < nsplit; ++y) {
     const int steps = s < nsteps - y * s ? s : nsteps - y * s;
-    run(groups, 0.2 + steps);
+    run(groups, 0.3 + steps);
     run(nlong, y == 0 ? 0.45 : 0.02);         // behind the first split they leave at once
   }
-  return end + 0.2 * nsplit;
+  return end + 0.3 * nsplit;
+}
+
+// Workgroups for the long outlier rows of a matrix: each owns an equal share of the entries (see long_rows_block)
+// and pays a look at the row pointers whether its share holds long rows or not: one per strip of 16 rows, 128 at most.
+static int long_row_workgroups(const DevMatrix& A) {
+  if (A.nnz <= 0) return 0;
+  const int strips = (A.g.m + 15) / 16;
+  return strips < kCUs / 2 ? strips : kCUs / 2;
 }
 
 static int mfma_steps_per_split(int groups, int nsteps, int slots1, int slots, int nlong) {
@@ -1774,18 +1812,11 @@ static hipError_t launch_mfma(const DevMatrix& A, const uint16_t* X, int b, void
   const int groups = (g.ntr + SH::NS - 1) / SH::NS;
   const int nsteps = (g.ntc + 63) / 64;
   const bool sparse = A.nnz > 0, permuted = A.perm != nullptr;
-  // workgroups for the long outlier rows: kLongParts per range of rows, a range of fewer rows than a workgroup has
-  // threads, 128 ranges if the matrix is large (each of them costs a look at its row pointers, long rows or not)
   constexpr int kNT = 64 * SH::NS;
-  int extra = 0;
-  if (sparse) {
-    extra = (g.m + 15) / 16 < kCUs / 2 ? (g.m + 15) / 16 : kCUs / 2;
-    const int need = (g.m + kNT - 2) / (kNT - 1);
-    if (extra < need) extra = need;
-  }
+  const int extra = long_row_workgroups(A);
   // the one-step variant fits three workgroups on a CU while the staged batch rows leave the LDS for them
   const int wgs1 = (TC != 32 && 3 * ((size_t)SH::NS * 64 * kMfmaTileStride * 4 + (size_t)b * SH::XROW + 1024) <= 160 * 1024) ? 3 : SH::WGS;
-  const int steps_per_split = mfma_steps_per_split(groups, nsteps, wgs1 * kCUs, SH::WGS * kCUs, extra * kLongParts);
+  const int steps_per_split = mfma_steps_per_split(groups, nsteps, wgs1 * kCUs, SH::WGS * kCUs, extra);
   const int nsplit = (nsteps + steps_per_split - 1) / steps_per_split;
   // the dense kernel writes Y itself (16 bytes per store) if nothing has to be added or converted afterwards
   const bool direct = nsplit == 1 && y_dtype == SPQR_F32 && reinterpret_cast<uintptr_t>(Y) % 16 == 0;
@@ -1826,10 +1857,10 @@ static hipError_t launch_mfma(const DevMatrix& A, const uint16_t* X, int b, void
       }
       const size_t lds_now = (size_t)SH::NS * 64 * kMfmaTileStride * 4 + (size_t)b * SH::XROW;   // only b rows of X are staged
       if (e == hipSuccess)
-        hipLaunchKernelGGL((gemm_mfma_one_kernel<W, TR, TC, AXIS>), dim3(groups + extra * kLongParts, nsplit), dim3(kNT), lds_now,
+        hipLaunchKernelGGL((gemm_mfma_one_kernel<W, TR, TC, AXIS>), dim3(groups + extra, nsplit), dim3(kNT), lds_now,
                            stream, A, permuted ? xp : X, part, split_stride, b, xt, slots, long_row, groups);
     } else {
-      hipLaunchKernelGGL((gemm_mfma_kernel<W, TR, TC, AXIS>), dim3(groups + extra * kLongParts, nsplit), dim3(kNT), SH::LDS,
+      hipLaunchKernelGGL((gemm_mfma_kernel<W, TR, TC, AXIS>), dim3(groups + extra, nsplit), dim3(kNT), SH::LDS,
                          stream, A, permuted ? xp : X, part, split_stride, steps_per_split, b, xt, slots, long_row, groups);
     }
     if (e == hipSuccess) e = hipGetLastError();
@@ -1936,13 +1967,7 @@ static hipError_t launch_mfma_fused(const DevMatrix* As, int count, const uint16
     const Geometry& g = As[i].g;
     total_groups += (g.ntr + SH::NS - 1) / SH::NS;
     sparse = sparse || As[i].nnz > 0;
-    int extra = 0;                           // workgroups for the long outlier rows, as in launch_mfma
-    if (As[i].nnz > 0) {
-      extra = (g.m + 15) / 16 < kCUs / 2 ? (g.m + 15) / 16 : kCUs / 2;
-      const int need = (g.m + kNT - 2) / (kNT - 1);
-      if (extra < need) extra = need;
-    }
-    extras[i] = extra * kLongParts;
+    extras[i] = long_row_workgroups(As[i]);
     total_extra += extras[i];
   }
   const int wgs1 = (TC != 32 && 3 * ((size_t)SH::NS * 64 * kMfmaTileStride * 4 + (size_t)b * SH::XROW + 1024) <= 160 * 1024) ? 3 : SH::WGS;

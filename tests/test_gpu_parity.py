@@ -527,6 +527,64 @@ def test_matrix_core_long_rows_many_rows_per_workgroup(P, monkeypatch):
     assert max(rel_l2(Y[k], ref[k]) for k in range(9)) <= REL_L2
 
 
+def _with_row_counts(f, counts, seed):
+    """Replaces the outliers of f by rows of the given lengths (sorted random columns, normal values)."""
+    rng = np.random.default_rng(seed)
+    f.row_ptr = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    f.col_idx = np.concatenate([np.sort(rng.choice(f.n, size=int(c), replace=False)) for c in counts if c]).astype(np.uint16)
+    f.val = rng.standard_normal(f.col_idx.shape[0]).astype(np.float16)
+    return f
+
+
+@pytest.mark.parametrize("w,b1,b2,axis,ntr,ntc", [(3, 16, 16, 1, 40, 140), (4, 8, 32, 1, 80, 70)])
+def test_matrix_core_long_rows_shared_out_by_entries(P, monkeypatch, w, b1, b2, axis, ntr, ntc):
+    """The long-row workgroups own equal shares of the entry indices, whatever the rows: a block of heavy rows next
+    to each other (full rows, rows of 513, 1024 and 1025 entries: one entry into a new slice, exact slices), rows
+    just at and just above what counts as long (256 / 257 entries), empty rows between them, and shares whose
+    bounds fall inside a row, on a slice bound and on a row bound."""
+    monkeypatch.setenv("SPQR_MFMA", "1")
+    f = make(w, b1, b2, axis, ntr, ntc, rate=0.0, structure="none", seed=(120, w))
+    assert f.n == 2240
+    counts = np.zeros(f.m, np.int64)
+    counts[100:108] = f.n                      # eight full rows in a block
+    counts[108] = 513
+    counts[110] = 1024
+    counts[111] = 1025
+    counts[300] = 256                          # not long: stays with the finishing kernel
+    counts[301] = 257                          # long
+    counts[f.m - 1] = 2000                     # the last row
+    counts[::7] += 3                           # a few entries in every 7th row
+    counts = np.minimum(counts, f.n)
+    _with_row_counts(f, counts, 120)
+    A = P.SpQRMatrix.from_logical(f)
+    assert P.spqr_pack_check(A) == 0
+    for b in (5, 16):
+        X = synth.make_x(f.n, b, seed=(121, b))
+        Y = P.spqr_gemm_smallbatch(A, dev(X)).cpu().numpy()
+        ref = orc.matvec(f, X)
+        assert max(rel_l2(Y[k], ref[k]) for k in range(b)) <= REL_L2, (w, b)
+
+
+def test_matrix_core_long_rows_of_a_very_tall_matrix(P, monkeypatch):
+    """More than 65536 rows: the search for a share's first row takes two rounds of probes.  Long rows at the very
+    top, around the probes' first bracket and at the bottom; the oracle is sampled on those rows and 64 others."""
+    monkeypatch.setenv("SPQR_MFMA", "1")
+    f = make(3, 16, 16, 1, 4200, 20, rate=0.0, structure="none", seed=(122,))
+    assert f.m == 67200 and f.n == 320
+    counts = np.zeros(f.m, np.int64)
+    heavy = (0, 1, 255, 256, 257, 262, 263, 30000, 65535, 65536, 67198, 67199)
+    counts[list(heavy)] = 300
+    counts[1000:60000:97] = 2
+    _with_row_counts(f, counts, 122)
+    A = P.SpQRMatrix.from_logical(f)
+    assert P.spqr_pack_check(A) == 0
+    X = synth.make_x(f.n, 7, seed=(123,))
+    Y = P.spqr_gemm_smallbatch(A, dev(X)).cpu().numpy()
+    rows = np.unique(np.concatenate([np.array(heavy), np.arange(1000, 60000, 97)[:32], np.random.default_rng(5).integers(0, f.m, 32)]))
+    ref = orc.matvec_rows(f, X, rows)
+    assert max(rel_l2(Y[k][rows], ref[k]) for k in range(7)) <= REL_L2
+
+
 def test_matrix_core_long_rows_next_to_rows_like_the_average(P, monkeypatch):
     """What counts as a long row depends on the average: with 30 % outliers everywhere (about 600 per row) plus two
     full rows of 2080, only the full rows leave the finishing kernel; the others are cut into 16 parts of about 39."""
