@@ -83,14 +83,19 @@ def time_block(P, torch, mats, x_h, x_f, copies, fused, reps=4):
     e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
     if batch:
         # batches are streamed eagerly: the library keeps fused batch calls out of captured graphs
+        # (the first timed round still pays for the growth of the stream's memory pool: the better of two counts)
         reps *= 4
-        e0.record()
-        for _ in range(reps):
-            for c in range(copies):
-                block(c)
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) * 1e3 / (reps * copies)
+        best = None
+        for _ in range(2):
+            e0.record()
+            for _ in range(reps):
+                for c in range(copies):
+                    block(c)
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / (reps * copies)
+            best = us if best is None else min(best, us)
+        return best
     g = torch.cuda.CUDAGraph()
     with torch.cuda.graph(g):
         for c in range(copies):

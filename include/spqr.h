@@ -178,9 +178,14 @@ int spqr_gemv(const spqr_matrix_t* A, const uint16_t* x_f16, void* y, int y_dtyp
  * binary16 and multiplied on the matrix cores, then a second kernel adds the
  * outliers.  That path takes about (n+1)*32 + (nnz/256 + 2)*64 + splits*16*m*4
  * (+ 32*n with a permutation) bytes
- * of device scratch per slice from the stream's memory pool (hipMallocAsync /
- * hipFreeAsync on `stream`, stream-ordered: safe with concurrent calls on other
- * streams); if the pool refuses, the slices of 4 run instead.
+ * of device scratch per slice.  The library keeps one scratch buffer per stream
+ * (up to 8 streams per device; grown on demand, which synchronises the stream;
+ * held until the process ends) and holds its lock while a call is enqueued:
+ * calls on different streams never share scratch, calls from several host
+ * threads on one stream are enqueued one after the other.  On a stream that is
+ * being captured (and on further streams) the scratch is a stream-ordered
+ * allocation from a memory pool of the library's own instead (allocation nodes
+ * of the graph).  If no scratch can be had, the slices of 4 run instead.
  * SPQR_MFMA=0 or =1 in the environment forces one or the other where both apply.
  * Results are deterministic (fixed summation order) on either path; the two
  * differ by rounding only (both within the product tolerance).

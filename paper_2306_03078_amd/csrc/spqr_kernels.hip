@@ -1756,6 +1756,113 @@ static double mfma_schedule_length(int groups, int nsteps, int s, int slots, int
   return end + 0.3 * nsplit;
 }
 
+// Scratch of the batch path.  A call on a stream that is not being captured takes the buffer the library keeps for
+// that stream: work on one stream runs in order, so its calls can share one buffer, and nothing is allocated or
+// freed per call (on this runtime a stream-ordered allocation waits on the host until the stream's earlier work is
+// done, which keeps the next call's launches from being queued behind the running one: about 5 us per call).  The
+// buffer grows when a call needs more (the stream is synchronised first) and is kept until the process ends; up to
+// kScratchStreams streams per device have one, further streams and captured calls allocate stream-ordered from a
+// memory pool of the library's own (one per device, unlimited release threshold), which a capture turns into
+// allocation nodes of the graph.  A buffer's lock is held while its call is enqueued: calls from several host
+// threads on one stream do not interleave their kernels.
+constexpr int kScratchStreams = 8;
+struct ScratchSlot {
+  std::mutex lock;                           // held while a call that uses the buffer is enqueued
+  hipStream_t stream = nullptr;
+  uint8_t* buf = nullptr;
+  size_t size = 0;
+  bool taken = false;
+};
+struct Scratch {
+  uint8_t* p = nullptr;
+  bool pooled = false;                       // stream-ordered allocation, to be freed on the stream
+  std::unique_lock<std::mutex> hold;
+};
+
+static hipMemPool_t scratch_pool(int dev) {
+  static std::mutex lock;
+  static hipMemPool_t pools[kMaxDevices];
+  static bool tried[kMaxDevices];
+  if (dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> hold(lock);
+  if (!tried[dev]) {
+    tried[dev] = true;
+    hipMemPoolProps props = {};
+    props.allocType = hipMemAllocationTypePinned;
+    props.handleTypes = hipMemHandleTypeNone;
+    props.location.type = hipMemLocationTypeDevice;
+    props.location.id = dev;
+    hipMemPool_t pool = nullptr;
+    if (hipMemPoolCreate(&pool, &props) == hipSuccess) {
+      uint64_t keep = UINT64_MAX;
+      if (hipMemPoolSetAttribute(pool, hipMemPoolAttrReleaseThreshold, &keep) == hipSuccess) pools[dev] = pool;
+      else (void)hipMemPoolDestroy(pool);
+    }
+    if (pools[dev] == nullptr) (void)hipGetLastError();
+  }
+  return pools[dev];
+}
+
+// hipErrorNotSupported: no scratch to be had (the caller takes the vector path).
+static hipError_t scratch_get(Scratch* sc, size_t bytes, int dev, hipStream_t stream) {
+  static std::mutex table_lock;
+  static ScratchSlot slots[kMaxDevices][kScratchStreams];
+  hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+  const bool capturing = hipStreamIsCapturing(stream, &cs) != hipSuccess || cs != hipStreamCaptureStatusNone;
+  ScratchSlot* slot = nullptr;
+  if (!capturing && dev >= 0 && dev < kMaxDevices) {
+    std::lock_guard<std::mutex> hold(table_lock);
+    for (int i = 0; i < kScratchStreams && slot == nullptr; ++i)
+      if (slots[dev][i].taken && slots[dev][i].stream == stream) slot = &slots[dev][i];
+    for (int i = 0; i < kScratchStreams && slot == nullptr; ++i)
+      if (!slots[dev][i].taken) {
+        slot = &slots[dev][i];
+        slot->taken = true;
+        slot->stream = stream;
+      }
+  }
+  if (slot != nullptr) {
+    sc->hold = std::unique_lock<std::mutex>(slot->lock);
+    if (slot->size < bytes) {
+      // the stream's earlier calls may still read the old buffer
+      if (slot->buf != nullptr && (hipStreamSynchronize(stream) != hipSuccess || hipFree(slot->buf) != hipSuccess)) {
+        (void)hipGetLastError();
+        sc->hold.unlock();
+        return hipErrorNotSupported;
+      }
+      slot->buf = nullptr;
+      slot->size = 0;
+      const size_t want = (bytes + bytes / 4 + 0xFFFFF) & ~(size_t)0xFFFFF;   // some room, whole megabytes
+      if (hipMalloc(reinterpret_cast<void**>(&slot->buf), want) != hipSuccess) {
+        (void)hipGetLastError();
+        slot->buf = nullptr;
+        sc->hold.unlock();
+        return hipErrorNotSupported;
+      }
+      slot->size = want;
+    }
+    sc->p = slot->buf;
+    sc->pooled = false;
+    return hipSuccess;
+  }
+  hipMemPool_t pool = scratch_pool(dev);
+  if (pool == nullptr || hipMallocFromPoolAsync(reinterpret_cast<void**>(&sc->p), bytes, pool, stream) != hipSuccess) {
+    (void)hipGetLastError();
+    sc->p = nullptr;
+    return hipErrorNotSupported;
+  }
+  sc->pooled = true;
+  return hipSuccess;
+}
+// after the call's last kernel is enqueued
+static hipError_t scratch_put(Scratch* sc, hipStream_t stream) {
+  hipError_t e = hipSuccess;
+  if (sc->pooled && sc->p != nullptr) e = hipFreeAsync(sc->p, stream);
+  if (sc->hold.owns_lock()) sc->hold.unlock();
+  sc->p = nullptr;
+  return e;
+}
+
 // Workgroups for the long outlier rows of a matrix: each owns an equal share of the entries (see long_rows_block)
 // and pays a look at the row pointers whether its share holds long rows or not: one per strip of 16 rows, 128 at most.
 static int long_row_workgroups(const DevMatrix& A) {
@@ -1795,8 +1902,8 @@ static int mfma_steps_per_split(int groups, int nsteps, int slots1, int slots, i
 // Transposition, dense pass (with the long outlier rows beside it) and finishing pass.  Scratch (the batch
 // transposed, (n+1) x 32 bytes, the sums of the long outlier rows, 64 bytes per 256 outliers, the batch in the
 // matrix's column order if there is a permutation, and the partial results when the steps are split or the
-// output is binary16) is taken from and returned to the stream's memory pool.
-// hipErrorNotSupported = no pool here; the caller takes the vector path.
+// output is binary16): see scratch_get.
+// hipErrorNotSupported = no scratch to be had; the caller takes the vector path.
 template <int W, int TR, int TC, int AXIS>
 static hipError_t launch_mfma(const DevMatrix& A, const uint16_t* X, int b, void* Y, int y_dtype, hipStream_t stream) {
   using SH = MfmaShape<TR, TC>;
@@ -1825,14 +1932,11 @@ static hipError_t launch_mfma(const DevMatrix& A, const uint16_t* X, int b, void
   const size_t slot_bytes = sparse ? up(((size_t)(A.nnz / kSlotGrain) + 2) * 64) : 0;
   const size_t xp_bytes = permuted ? up((size_t)b * g.n * 2) : 0;
   const size_t part_bytes = direct ? 0 : (size_t)nsplit * b * g.m * sizeof(float);
-  uint8_t* scratch = nullptr;
-  if (xt_bytes + slot_bytes + xp_bytes + part_bytes > 0) {
-    if (hipMallocAsync(reinterpret_cast<void**>(&scratch), xt_bytes + slot_bytes + xp_bytes + part_bytes, stream) !=
-        hipSuccess) {
-      (void)hipGetLastError();
-      return hipErrorNotSupported;
-    }
-  }
+  Scratch sc;
+  if (xt_bytes + slot_bytes + xp_bytes + part_bytes > 0 &&
+      scratch_get(&sc, xt_bytes + slot_bytes + xp_bytes + part_bytes, dev, stream) != hipSuccess)
+    return hipErrorNotSupported;
+  uint8_t* const scratch = sc.p;
   uint16_t* xt = sparse ? reinterpret_cast<uint16_t*>(scratch) : nullptr;
   float* slots = reinterpret_cast<float*>(scratch + xt_bytes);
   uint16_t* xp = permuted ? reinterpret_cast<uint16_t*>(scratch + xt_bytes + slot_bytes) : nullptr;
@@ -1870,11 +1974,8 @@ static hipError_t launch_mfma(const DevMatrix& A, const uint16_t* X, int b, void
                        split_stride, long_row, Y, y_dtype, b);
     e = hipGetLastError();
   }
-  if (scratch != nullptr) {
-    const hipError_t ef = hipFreeAsync(scratch, stream);
-    if (e == hipSuccess) e = ef;
-  }
-  return e;
+  const hipError_t ef = scratch_put(&sc, stream);
+  return e == hipSuccess ? ef : e;
 }
 
 // Whether a batch of b > 4 vectors takes the matrix-core path.  It pays two more launches and the
@@ -1986,13 +2087,9 @@ static hipError_t launch_mfma_fused(const DevMatrix* As, int count, const uint16
     part_off[i] = total;
     total += direct ? 0 : up((size_t)nsplit * b * As[i].g.m * sizeof(float));
   }
-  uint8_t* scratch = nullptr;
-  if (total > 0) {
-    if (hipMallocAsync(reinterpret_cast<void**>(&scratch), total, stream) != hipSuccess) {
-      (void)hipGetLastError();
-      return hipErrorNotSupported;
-    }
-  }
+  Scratch sc;
+  if (total > 0 && scratch_get(&sc, total, dev, stream) != hipSuccess) return hipErrorNotSupported;
+  uint8_t* const scratch = sc.p;
   uint16_t* xt = sparse ? reinterpret_cast<uint16_t*>(scratch) : nullptr;
   uint16_t* xp = permuted ? reinterpret_cast<uint16_t*>(scratch + xt_bytes) : nullptr;
   MfmaFused F;
@@ -2032,11 +2129,8 @@ static hipError_t launch_mfma_fused(const DevMatrix* As, int count, const uint16
     hipLaunchKernelGGL(finish_xt16_fused_kernel, dim3(finish_blocks), dim3(kFinishThreads), 0, stream, F, xt, nsplit, y_dtype, b);
     e = hipGetLastError();
   }
-  if (scratch != nullptr) {
-    const hipError_t ef = hipFreeAsync(scratch, stream);
-    if (e == hipSuccess) e = ef;
-  }
-  return e;
+  const hipError_t ef = scratch_put(&sc, stream);
+  return e == hipSuccess ? ef : e;
 }
 
 // Y_i[b][m_i] = X[b][n] . W_hat_i^T for matrices that share X.  Batches the matrix-core path takes go through it

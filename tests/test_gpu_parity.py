@@ -585,6 +585,62 @@ def test_matrix_core_long_rows_of_a_very_tall_matrix(P, monkeypatch):
     assert max(rel_l2(Y[k][rows], ref[k]) for k in range(7)) <= REL_L2
 
 
+def test_batch_scratch_is_kept_per_stream_grows_and_falls_back(P, monkeypatch):
+    """The batch path keeps one scratch buffer per stream: a small call, then a larger one on the same stream (the
+    buffer grows), calls on two streams in turn, and more streams than the library keeps buffers for (the rest
+    allocate stream-ordered).  Every result against the oracle."""
+    import torch
+    monkeypatch.setenv("SPQR_MFMA", "1")
+    small = make(3, 16, 16, 1, 4, 70, rate=0.02, structure="uniform", seed=(130,))
+    large = make(4, 16, 16, 1, 24, 140, rate=0.02, structure="uniform", seed=(131,))
+    As = {id(f): P.SpQRMatrix.from_logical(f) for f in (small, large)}
+    Xs = {id(f): synth.make_x(f.n, 16, seed=(132, f.n)) for f in (small, large)}
+    refs = {id(f): orc.matvec(f, Xs[id(f)]) for f in (small, large)}
+    streams = [torch.cuda.Stream() for _ in range(11)]
+    torch.cuda.synchronize()
+    outs = []
+    for f in (small, large, small):            # the same stream: grows once, then reused
+        with torch.cuda.stream(streams[0]):
+            outs.append((f, P.spqr_gemm_smallbatch(As[id(f)], dev(Xs[id(f)]))))
+    for k in range(6):                         # two streams in turn
+        f = (small, large)[k % 2]
+        with torch.cuda.stream(streams[1 + k % 2]):
+            outs.append((f, P.spqr_gemm_smallbatch(As[id(f)], dev(Xs[id(f)]))))
+    for st in streams[3:]:                     # 8 more streams: beyond the kept buffers
+        with torch.cuda.stream(st):
+            outs.append((large, P.spqr_gemm_smallbatch(As[id(large)], dev(Xs[id(large)]))))
+    torch.cuda.synchronize()
+    for f, Y in outs:
+        Y = Y.cpu().numpy()
+        assert max(rel_l2(Y[k], refs[id(f)][k]) for k in range(16)) <= REL_L2
+
+
+def test_batch_path_in_a_captured_graph_replays_like_the_eager_call(P, monkeypatch):
+    """Captured, the batch path allocates its scratch stream-ordered (allocation nodes of the graph).  Several
+    replays with eager calls and synchronisations in between, each compared bit for bit with the eager result."""
+    import torch
+    monkeypatch.setenv("SPQR_MFMA", "1")
+    f = make(4, 16, 16, 1, 12, 140, rate=0.02, structure="uniform", seed=(133,))
+    A = P.SpQRMatrix.from_logical(f)
+    X = dev(synth.make_x(f.n, 16, seed=(134,)))
+    eager = P.spqr_gemm_smallbatch(A, X).clone()
+    ref = orc.matvec(f, X.cpu().numpy())
+    assert max(rel_l2(eager.cpu().numpy()[k], ref[k]) for k in range(16)) <= REL_L2
+    Y = torch.zeros_like(eager)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        P.spqr_gemm_smallbatch(A, X, out=Y)
+    for rep in range(4):
+        Y.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(Y, eager), rep
+        other = P.spqr_gemm_smallbatch(A, X)       # eager work between the replays
+        torch.cuda.synchronize()
+        assert torch.equal(other, eager), rep
+
+
 def test_matrix_core_long_rows_next_to_rows_like_the_average(P, monkeypatch):
     """What counts as a long row depends on the average: with 30 % outliers everywhere (about 600 per row) plus two
     full rows of 2080, only the full rows leave the finishing kernel; the others are cut into 16 parts of about 39."""
