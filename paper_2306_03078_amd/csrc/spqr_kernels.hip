@@ -1761,9 +1761,10 @@ static double mfma_schedule_length(int groups, int nsteps, int s, int slots, int
 // freed per call (on this runtime a stream-ordered allocation waits on the host until the stream's earlier work is
 // done, which keeps the next call's launches from being queued behind the running one: about 5 us per call).  The
 // buffer grows when a call needs more (the stream is synchronised first) and is kept until the process ends; up to
-// kScratchStreams streams per device have one, further streams and captured calls allocate stream-ordered from a
-// memory pool of the library's own (one per device, unlimited release threshold), which a capture turns into
-// allocation nodes of the graph.  A buffer's lock is held while its call is enqueued: calls from several host
+// kScratchStreams streams per device have one; further streams allocate stream-ordered from a memory pool of the
+// library's own (one per device, unlimited release threshold), captured calls from the device's default pool, which
+// the capture turns into allocation nodes of the graph (graphs of many such calls replay correctly with it; with the
+// library's own pool the allocations of all but the first call of a capture failed).  A buffer's lock is held while its call is enqueued: calls from several host
 // threads on one stream do not interleave their kernels.
 constexpr int kScratchStreams = 8;
 struct ScratchSlot {
@@ -1845,8 +1846,11 @@ static hipError_t scratch_get(Scratch* sc, size_t bytes, int dev, hipStream_t st
     sc->pooled = false;
     return hipSuccess;
   }
-  hipMemPool_t pool = scratch_pool(dev);
-  if (pool == nullptr || hipMallocFromPoolAsync(reinterpret_cast<void**>(&sc->p), bytes, pool, stream) != hipSuccess) {
+  // captured: the device's default pool (allocation nodes of the graph); else the library's own pool
+  hipMemPool_t pool = capturing ? nullptr : scratch_pool(dev);
+  const hipError_t e = pool != nullptr ? hipMallocFromPoolAsync(reinterpret_cast<void**>(&sc->p), bytes, pool, stream)
+                                       : hipMallocAsync(reinterpret_cast<void**>(&sc->p), bytes, stream);
+  if (e != hipSuccess) {
     (void)hipGetLastError();
     sc->p = nullptr;
     return hipErrorNotSupported;
@@ -1979,16 +1983,23 @@ static hipError_t launch_mfma(const DevMatrix& A, const uint16_t* X, int b, void
 }
 
 // Whether a batch of b > 4 vectors takes the matrix-core path.  It pays two more launches and the
-// transposition through LDS, the vector path re-reads the weights once per 4 vectors: measured
-// on MI355X the matrix cores win from 13 vectors on for any layer, from 8 on for layers of 40 M
-// weights and from 5 on for layers of 100 M.  SPQR_MFMA=0 / =1 in the environment (read per
-// call) forces the vector / the matrix-core path wherever it applies (tests compare the two).
-static bool mfma_wanted(const Geometry& g, int b) {
+// transposition through LDS, the vector path re-reads the weights once per 4 vectors.  Measured on
+// MI355X with eager calls the matrix cores win from 8 vectors on for any layer and from 5 on for layers
+// of 30 M weights or more (4096^2 at b = 5 / 8 / 16: 15.4 / 15.7 / 18.0 us against 13.2 / 16.5 / 32.5;
+// 11008x4096: 26.6 / 26.9 / 28.2 against 31.6 / 45.3 / 89.4).  In a captured call the scratch is an
+// allocation node of the graph, about 10 us more per call: there from 13 vectors on for any layer,
+// from 8 on for layers of 40 M weights and from 5 on for layers of 100 M.  SPQR_MFMA=0 / =1 in the
+// environment (read per call) forces the vector / the matrix-core path wherever it applies (tests
+// compare the two).
+static bool mfma_wanted(const Geometry& g, int b, hipStream_t stream) {
   const char* e = std::getenv("SPQR_MFMA");
   if (e && e[0] == '0') return false;
   if (e && e[0] == '1') return true;
   const double weights = (double)g.m * (double)g.n;
-  return b >= 13 || (b >= 8 && weights >= 40e6) || weights >= 100e6;
+  hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+  const bool capturing = hipStreamIsCapturing(stream, &cs) != hipSuccess || cs != hipStreamCaptureStatusNone;
+  if (capturing) return b >= 13 || (b >= 8 && weights >= 40e6) || weights >= 100e6;
+  return b >= 8 || weights >= 30e6;
 }
 
 // Y[b][m] = X[b][n] . W_hat^T.  Up to 4 activation vectors: the tuned vector
@@ -2013,7 +2024,7 @@ hipError_t launch_gemm(const DevMatrix& A, const uint16_t* X, int b, void* Y, in
     int done = 1;
     // the matrix-core path takes up to 16 vectors per pass over the weights
     const int nb16 = left < 16 ? left : 16;
-    if (mfma_ok && left > 4 && mfma_wanted(g, nb16)) {
+    if (mfma_ok && left > 4 && mfma_wanted(g, nb16, stream)) {
       e = hipErrorNotSupported;
 #define SPQR_MFMA_CASE(W_, TR_, TC_, AX_) \
       if (g.w_bits == W_ && g.tile_rows == TR_ && g.tile_cols == TC_ && g.axis == AX_) \
@@ -2162,7 +2173,7 @@ hipError_t launch_gemm_fused(const DevMatrix* As, int count, const uint16_t* X, 
     const uint16_t* xk = X + (size_t)k * g.n;
     void* yk[SPQR_MAX_FUSED];
     for (int i = 0; i < count; ++i) yk[i] = static_cast<uint8_t*>(Ys[i]) + (size_t)k * As[i].g.m * ysz;
-    if (mfma_ok && left > 4 && mfma_wanted(all, nb16)) {
+    if (mfma_ok && left > 4 && mfma_wanted(all, nb16, stream)) {
       hipError_t e = hipErrorNotSupported;
 #define SPQR_MFMA_CASE(W_, TR_, TC_, AX_) \
       if (g.w_bits == W_ && g.tile_rows == TR_ && g.tile_cols == TC_ && g.axis == AX_) \
