@@ -507,9 +507,10 @@ def test_matrix_core_long_rows_back_to_back(P, monkeypatch, ntc, rate):
 
 
 def test_matrix_core_long_rows_many_rows_per_workgroup(P, monkeypatch):
-    """A tall matrix: the workgroups that take the long rows own 80 rows each; rows 31, 32, 63, 64 and 79 of every
-    80 hold 700 outliers, the others none (row 31 of a wavefront's 64 is bit 31 of the word its long-row mask is
-    kept in, rows 63 / 64 the seam between two wavefronts' masks)."""
+    """A tall matrix whose rows 31, 32, 63, 64 and 79 of every 80 hold 700 outliers, the others none: a workgroup
+    that takes long rows looks at 255 rows at a time and keeps which of them are long in one 64-bit mask per
+    wavefront (row 31 of a wavefront's 64 is bit 31 of the mask's low word, rows 63 / 64 the seam between two
+    wavefronts' masks)."""
     monkeypatch.setenv("SPQR_MFMA", "1")
     f = make(3, 16, 16, 1, 640, 48, rate=0.0, structure="none", seed=(85,))
     assert f.m == 10240 and f.n == 768
