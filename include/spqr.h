@@ -220,6 +220,27 @@ int spqr_gemv_fused(const spqr_matrix_t* const* A, int count, const uint16_t* x_
 int spqr_gemm_fused(const spqr_matrix_t* const* A, int count, const uint16_t* X_f16, int b,
                     void* const* Y, int y_dtype, void* stream);
 
+/* Launch plan of the matrix-core path of spqr_gemm_smallbatch / spqr_gemm_fused,
+ * for tuning and tests; host arithmetic only, no device is touched.  The dense
+ * launch walks every strip of tiles in steps of 64 tiles; `groups` workgroups
+ * (4 or 8 strips each) cover the rows, and the `nsteps` steps of a group are
+ * split among workgroups of `s` steps each (the last one may get fewer), every
+ * split writing a partial result.  Returns the s the library takes,
+ * 1 <= s <= nsteps: the one whose simulated schedule is shortest, where the
+ * workgroups start in grid order (split by split: the groups, behind those of
+ * the first split the `long_workgroups` workgroups of the long outlier rows) on
+ * the first free of `slots` places on the chip (`slots_one_step` places when
+ * s == 1: that kernel variant is smaller); a dense workgroup costs its steps
+ * + 0.3, a long-row workgroup 0.45 (0.02 behind later splits, where it leaves
+ * at once), every split 0.3 for its partial result; ties go to fewer splits.
+ * Candidates are s <= 32 and s = nsteps; a candidate whose launch has more
+ * than 200000 workgroups is passed over.
+ * SPQR_MFMA_STEPS=k in the environment pins s = min(k, nsteps).
+ * A negative return is an SPQR_ERR_* code (an argument below 1, or
+ * long_workgroups below 0). */
+int spqr_plan_batch_steps(int groups, int nsteps, int slots_one_step, int slots,
+                          int long_workgroups);
+
 /* Debug decode.  `what` selects the output:
  *   SPQR_OUT_CODES_U8   uint8  [m][n]   the b_w-bit codes
  *   SPQR_OUT_SCALE_F32  float  group grid ([m][n/beta1] or [m/beta1][n]): s_hat

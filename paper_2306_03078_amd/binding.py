@@ -79,6 +79,8 @@ def load_library():
     lib.spqr_gemm_fused.argtypes = [C.POINTER(P), C.c_int, vp, C.c_int, C.POINTER(vp), C.c_int, vp]
     lib.spqr_dequant_dense.restype = C.c_int
     lib.spqr_dequant_dense.argtypes = [P, C.c_int, vp, vp]
+    lib.spqr_plan_batch_steps.restype = C.c_int
+    lib.spqr_plan_batch_steps.argtypes = [C.c_int] * 5
     _lib = lib
     return lib
 
@@ -262,3 +264,11 @@ def spqr_dequant_dense(A: SpQRMatrix, what: int, stream=None):
     _check(load_library().spqr_dequant_dense(C.byref(A.desc), what, out.data_ptr(),
                                              _stream_ptr(stream)), "spqr_dequant_dense")
     return out
+
+
+def spqr_plan_batch_steps(groups: int, nsteps: int, slots_one_step: int, slots: int, long_workgroups: int) -> int:
+    """Steps per workgroup the batch path's dense launch would take (host arithmetic, no device needed)."""
+    rc = load_library().spqr_plan_batch_steps(groups, nsteps, slots_one_step, slots, long_workgroups)
+    if rc < 0:
+        _check(rc, "spqr_plan_batch_steps")
+    return rc

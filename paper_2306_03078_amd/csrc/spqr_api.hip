@@ -139,3 +139,8 @@ extern "C" int spqr_dequant_dense(const spqr_matrix_t* A, int what, void* out, v
   hipError_t e = spqr::launch_dequant(D, what, out, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? SPQR_OK : SPQR_ERR_HIP;
 }
+
+extern "C" int spqr_plan_batch_steps(int groups, int nsteps, int slots_one_step, int slots, int long_workgroups) {
+  if (groups < 1 || nsteps < 1 || slots_one_step < 1 || slots < 1 || long_workgroups < 0) return SPQR_ERR_PARAM;
+  return spqr::plan_batch_steps(groups, nsteps, slots_one_step, slots, long_workgroups);
+}

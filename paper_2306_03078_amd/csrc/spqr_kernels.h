@@ -21,4 +21,7 @@ hipError_t launch_dequant(const DevMatrix& A, int what, void* out, hipStream_t s
 hipError_t run_checks(const DevMatrix& A, bool csr, bool finite, bool perm, int host_words[3],
                       hipStream_t stream);
 
+// Steps of 64 tiles per workgroup of the batch path's dense launch (host arithmetic only, see the definition).
+int plan_batch_steps(int groups, int nsteps, int slots_one_step, int slots, int long_workgroups);
+
 }  // namespace spqr

@@ -1903,6 +1903,10 @@ static int mfma_steps_per_split(int groups, int nsteps, int slots1, int slots, i
   return best;
 }
 
+int plan_batch_steps(int groups, int nsteps, int slots_one_step, int slots, int long_workgroups) {
+  return mfma_steps_per_split(groups, nsteps, slots_one_step, slots, long_workgroups);
+}
+
 // Transposition, dense pass (with the long outlier rows beside it) and finishing pass.  Scratch (the batch
 // transposed, (n+1) x 32 bytes, the sums of the long outlier rows, 64 bytes per 256 outliers, the batch in the
 // matrix's column order if there is a permutation, and the partial results when the steps are split or the

@@ -19,7 +19,7 @@ def test_library_exports_every_declared_symbol():
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
     names = set(re.findall(r"\b(spqr_[a-z_0-9]+)\s*\(", hdr))
     assert {"spqr_pack_check", "spqr_gemv", "spqr_gemv_fused", "spqr_gemm_fused", "spqr_gemm_smallbatch", "spqr_dequant_dense",
-            "spqr_pack_host", "spqr_packed_bytes", "spqr_strerror", "spqr_version"} <= names
+            "spqr_pack_host", "spqr_packed_bytes", "spqr_strerror", "spqr_version", "spqr_plan_batch_steps"} <= names
     lib = C.CDLL(P.library_path())
     for nm in sorted(names):
         assert hasattr(lib, nm), nm
@@ -92,3 +92,57 @@ def test_host_side_descriptor_checks_need_no_gpu():
     assert lib.spqr_gemv(C.byref(d), None, None, 0, None) == -1      # packed is NULL
     d.layout_version = 2
     assert lib.spqr_dequant_dense(C.byref(d), 0, None, None) == -3
+
+
+def _schedule_length(groups, nsteps, s, slots, nlong):
+    """The launch plan's schedule, written out: workgroups in grid order, each on the place that is free first."""
+    import heapq
+    nsplit = -(-nsteps // s)
+    free = [0.0] * slots
+    end = 0.0
+    for y in range(nsplit):
+        steps = min(s, nsteps - y * s)
+        for count, cost in ((groups, 0.3 + steps), (nlong, 0.45 if y == 0 else 0.02)):
+            for _ in range(count):
+                t = heapq.heappop(free) + cost
+                heapq.heappush(free, t)
+                end = max(end, t)
+    return end + 0.3 * nsplit
+
+
+@pytest.mark.parametrize("groups,nsteps,slots1,slots,nlong", [
+    (64, 4, 512, 512, 128), (172, 4, 768, 512, 128), (64, 11, 512, 512, 128), (104, 7, 512, 512, 128),
+    (280, 7, 512, 512, 128), (104, 18, 512, 512, 128), (344, 4, 256, 256, 128), (128, 11, 256, 256, 128),
+    (1, 1, 512, 512, 0), (3, 40, 512, 512, 1), (2000, 2, 512, 512, 0), (312, 7, 768, 512, 384)])
+def test_batch_launch_plan_is_the_shortest_simulated_schedule(monkeypatch, groups, nsteps, slots1, slots, nlong):
+    monkeypatch.delenv("SPQR_MFMA_STEPS", raising=False)
+    lib = C.CDLL(P.library_path())
+    fn = lib.spqr_plan_batch_steps
+    fn.restype = C.c_int
+    fn.argtypes = [C.c_int] * 5
+    got = fn(groups, nsteps, slots1, slots, nlong)
+    assert 1 <= got <= nsteps
+    cands = [s for s in range(1, nsteps + 1) if s <= 32 or s == nsteps]
+    cost = {s: _schedule_length(groups, nsteps, s, slots1 if s == 1 else slots, nlong) for s in cands}
+    best = min(cost.values())
+    assert cost[got] <= best + 1e-6
+    assert got == max(s for s in cands if cost[s] <= best + 1e-9)       # ties: fewer splits
+    assert fn(groups, nsteps, slots1, slots, nlong) == got               # remembered, same answer
+
+
+def test_batch_launch_plan_arguments_and_the_pinned_choice(monkeypatch):
+    lib = C.CDLL(P.library_path())
+    fn = lib.spqr_plan_batch_steps
+    fn.restype = C.c_int
+    fn.argtypes = [C.c_int] * 5
+    for bad in ((0, 4, 512, 512, 0), (4, 0, 512, 512, 0), (4, 4, 0, 512, 0), (4, 4, 512, 0, 0), (4, 4, 512, 512, -1)):
+        assert fn(*bad) == -3                                            # SPQR_ERR_PARAM
+    assert fn(100, 1, 512, 512, 0) == 1
+    # one group: splitting buys parallelism, 9 steps never stay in one workgroup
+    assert fn(1, 9, 512, 512, 0) < 9
+    # far more groups than places and nothing to balance: whole strips per workgroup cost the fewest partial results
+    assert fn(512 * 40, 3, 512, 512, 0) == 3
+    monkeypatch.setenv("SPQR_MFMA_STEPS", "2")
+    assert fn(280, 7, 512, 512, 128) == 2
+    monkeypatch.setenv("SPQR_MFMA_STEPS", "50")
+    assert fn(280, 7, 512, 512, 128) == 7
