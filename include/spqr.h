@@ -183,9 +183,9 @@ int spqr_gemv(const spqr_matrix_t* A, const uint16_t* x_f16, void* y, int y_dtyp
  * held until the process ends) and holds its lock while a call is enqueued:
  * calls on different streams never share scratch, calls from several host
  * threads on one stream are enqueued one after the other.  On a stream that is
- * being captured (and on further streams) the scratch is a stream-ordered
- * allocation from a memory pool of the library's own instead (allocation nodes
- * of the graph).  If no scratch can be had, the slices of 4 run instead.
+ * being captured the scratch is a stream-ordered allocation from the device's
+ * default memory pool instead (allocation nodes of the graph, about 10 us more
+ * per call), on further streams one from a pool of the library's own.  If no scratch can be had, the slices of 4 run instead.
  * SPQR_MFMA=0 or =1 in the environment forces one or the other where both apply.
  * Results are deterministic (fixed summation order) on either path; the two
  * differ by rounding only (both within the product tolerance).
