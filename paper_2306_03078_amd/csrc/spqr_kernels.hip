@@ -885,6 +885,7 @@ __device__ __forceinline__ void long_rows_block(const DevMatrix& A, const uint16
 #pragma unroll
     for (int k = 0; k < NW; ++k) c += below[k];                              // never all (row H is above a)
     __syncthreads();
+    c = min(c, NT - 1);                      // (all only if row_ptr[m] < nnz, a broken descriptor: stay inside the bracket)
     const int newL = c == 0 ? L : L + (int)(((int64_t)c * span) / NT);
     H = L + (int)(((int64_t)(c + 1) * span) / NT);
     L = newL;
