@@ -105,6 +105,13 @@ def reconstruct(fmt):
 
 
 def _permuted(X, fmt):
+    """Activations in the stored column order: x'[j] = x[perm[j]].
+
+    An act-order quantiser (Sec. 5 ablations; App. B `permutation_order
+    act_order`) reorders the input dimension before Alg. 1's column sweep and
+    stores the matrix in that order: stored column j is original column
+    perm[j], hence W . x = sum_j W_stored[:, j] * x[perm[j]].
+    """
     X = np.atleast_2d(np.asarray(X)).astype(np.float64)
     perm = getattr(fmt, "perm", None)
     if perm is not None:

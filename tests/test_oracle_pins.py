@@ -313,3 +313,56 @@ def test_generator_csr_is_valid(structure):
         assert counts.max() == 512 and np.median(counts) < counts.mean()
     g = synth.make_matrix(256, 512, outlier_rate=0.02, outlier_structure=structure, seed=(1, 2))
     assert np.array_equal(f.Q, g.Q) and np.array_equal(f.col_idx, g.col_idx)
+
+
+# ---- act-order input permutation (Sec. 5 ablations, App. B `permutation_order act_order`) -------
+# An act-order quantiser reorders the INPUT dimension before the column sweep of Alg. 1 and stores
+# the matrix in that order: stored column j is column perm[j] of the original weight.  The product
+# with the original activations is  y = sum_j W_stored[:, j] * x[perm[j]].
+def test_permutation_hand_case_three_cycle():
+    f = tiny(16, 16, group_axis=0, outlier_rate=0.0)
+    W = orc.reconstruct(f)                      # stored column order
+    perm = np.arange(16, dtype=np.int32)
+    perm[[2, 5, 11]] = [5, 11, 2]               # a 3-cycle: stored column 2 <- x[5], 5 <- x[11], 11 <- x[2]
+    f.perm = perm
+    k = 5
+    x = np.zeros(16, dtype=np.float16); x[k] = 1.0
+    y = orc.matvec(f, x)[0]
+    j = int(np.nonzero(perm == k)[0][0])        # the stored column that meets x[k]: perm[j] = k -> j = 2
+    assert j == 2 and perm[k] == 11
+    assert np.array_equal(y, W[:, j])           # column j with perm[j] = k ...
+    assert not np.array_equal(y, W[:, perm[k]])  # ... and NOT column perm[k] (the inverse reading)
+    assert np.array_equal(orc.matvec_rows(f, x, np.arange(16))[0], W[:, j])
+    assert np.array_equal(np.array(brute.matvec(f, x)), W[:, j])
+
+
+@pytest.mark.parametrize("axis", [0, 1])
+def test_permutation_equals_unpermuting_the_stored_matrix(axis):
+    # Definition, independent of the oracle's own gather: scatter the stored columns back to the original
+    # order (W_orig[:, perm[j]] = W_stored[:, j]) and multiply by x as it is.
+    f = tiny(32, 48, group_axis=axis, outlier_rate=0.04)
+    rng = np.random.default_rng(21)
+    perm = rng.permutation(48).astype(np.int32)
+    Ws = orc.reconstruct(f)
+    W_orig = np.empty_like(Ws)
+    for j in range(48):
+        W_orig[:, perm[j]] = Ws[:, j]
+    X = synth.make_x(48, 3, seed=(22,))
+    ref = X.astype(np.float64) @ W_orig.T
+    f.perm = perm
+    assert np.allclose(orc.matvec(f, X), ref, rtol=1e-12, atol=1e-12)
+    assert np.allclose(orc.matvec_dense_only(f, X) + orc.matvec_sparse_only(f, X), ref, rtol=1e-12, atol=1e-12)
+    rows = np.array([0, 7, 31])
+    assert np.allclose(orc.matvec_rows(f, X, rows), ref[:, rows], rtol=1e-12, atol=1e-12)
+    for b in range(3):
+        assert np.allclose(np.array(brute.matvec(f, X[b])), ref[b], rtol=1e-12, atol=1e-12)
+
+
+def test_identity_permutation_is_a_no_op():
+    f = tiny(32, 32, outlier_rate=0.05)
+    X = synth.make_x(32, 2, seed=(23,))
+    ref = orc.matvec(f, X)
+    f.perm = np.arange(32, dtype=np.int32)
+    assert np.allclose(orc.matvec(f, X), ref, rtol=1e-14, atol=1e-14)   # a gathered copy may be summed in another order
+    assert np.array_equal(np.array(brute.matvec(f, X[0])), np.array(brute.matvec(
+        synth.SpQRLogical(**{**f.__dict__, "perm": None}), X[0])))
