@@ -1,0 +1,615 @@
+// The fused decode + matvec kernel for tiles of 256 codes (Sec. 4.2 "Inference
+// with SpQR", re-designed for CDNA4): device code only; launchers in spqr_gemv.hip.
+//
+//   one workgroup owns one strip of tile_rows output rows; its wavefronts split
+//   the input dimension in steps of 64 tiles; one lane owns one whole tile per
+//   step, so every load instruction of a wavefront reads one contiguous run of
+//   the packed buffer (16 bytes per lane) and a tile's statistics are decoded
+//   once and reused by all of its rows.  x is staged once per workgroup in LDS
+//   (it also serves the outlier gather).  Codes are turned into binary16 values
+//   K + q/2^b by one and-or per pair and multiplied with v_dot2_f32_f16 (fp32
+//   accumulation); the offset K is removed per tile.  The strip's outliers (a
+//   contiguous CSR range) are handled by the same workgroup, so y is written
+//   once, without atomics, in a fixed order.
+#pragma once
+#include "../../include/spqr.h"
+#include "spqr_tile.h"
+
+namespace spqr {
+
+// Row phases: the class of the pair in tile row r, column pair p depends on
+// (r*PPR + p) % 16 for 3-bit codes, so rows repeat with period 16/PPR; 4-bit
+// classes depend on p alone.
+template <int W, int TC> struct RowPhases {
+  static constexpr int N = (W == 4 || TC / 2 >= 16 || !SharedShifts<TC>::value) ? 1 : 16 / (TC / 2);
+};
+
+// One tile's contribution for NB activation vectors (LDS rows of `xstride`
+// dwords).  Codes enter the dot products as K + q/2^W (K by class, see above) and
+// the statistic codes as 1 + s_q/8, 1 + z_q/8 (exact binary16 values); the offsets
+// are removed with per-tile sums.  acc[b][r] accumulates, per output row r and
+// vector b:
+//   AXIS 1: sum_j (K_rj + q_rj/2^W) * u_j  with u_j = fp16(s_hat_j * x_j);
+//           csum[b][h] accumulates, for the rows of phase h, sum_j (2^W*K_rj + z_hat_j) * u_j,
+//           so y_r = 2^W*acc[r] - csum[r % phases].
+//   AXIS 0: s_hat_r * (2^W * sum_j (K_rj + q_rj/2^W) x_j - sum_j (2^W*K_rj + z_hat_r) x_j).
+// The sums of K_rj*u_j come from one dot product per pair, phase and vector into
+// per-class sums.  A pair is extracted once and used by all NB vectors.  `valid`
+// false: the lane adds exact zeros (every scale is forced to 0), so no branch
+// surrounds the tile.
+template <int W, int TR, int TC, int AXIS, int NB>
+__device__ __forceinline__ void tile_fma(const TileRegs<W, TR, TC, AXIS>& t,
+                                         const uint32_t* xpair /* TC/2 dwords in LDS, vector 0 */,
+                                         int xstride, bool valid, float (&acc)[NB][TR],
+                                         float (&csum)[NB][RowPhases<W, TC>::N], const ClassConsts& k,
+                                         const PairConsts& k1, const PairConsts& k3) {
+  using T = TileRegs<W, TR, TC, AXIS>;
+  constexpr bool SHARED = SharedShifts<TC>::value;
+  using CC = CodeClass<W, SHARED>;
+  constexpr int PPR = TC / 2;
+  constexpr int NPH = RowPhases<W, TC>::N;
+  constexpr float SCALE = (float)(1 << W);
+  const half2_t ones = as_half2(k3.magic);
+  const uint32_t a = t.s[T::SD - 2], b = t.s[T::SD - 1];
+  const float s_s = h2f((uint16_t)(a & 0xFFFF)), z_s = h2f((uint16_t)(a >> 16));
+  const float s_z = h2f((uint16_t)(b & 0xFFFF)), z_z = h2f((uint16_t)(b >> 16));
+  // s_hat = s_s*(s_q - z_s) = c1*(1 + s_q/8) + c2.  A lane without a tile of its own
+  // (it holds a copy of the block's last tile) runs the same code with s_hat = 0.
+  const float c1 = valid ? 8.f * s_s : 0.f, c2 = valid ? -s_s * z_s - 8.f * s_s : 0.f;
+  // z_hat = s_z*(z_q - z_z) = e1*(1 + z_q/8) + e2
+  const float e1 = 8.f * s_z, e2 = -s_z * z_z - e1;
+
+  uint32_t xp[NB][PPR];
+#pragma unroll
+  for (int bi = 0; bi < NB; ++bi) {
+#pragma unroll
+    for (int p = 0; p < PPR; p += 4) {
+      u32x4 v = *reinterpret_cast<const u32x4*>(xpair + bi * xstride + p);
+      xp[bi][p] = v.x; xp[bi][p + 1] = v.y; xp[bi][p + 2] = v.z; xp[bi][p + 3] = v.w;
+    }
+  }
+
+  float C[NB][NPH][CC::N];                     // per phase and class: sum of the activations it multiplies
+#pragma unroll
+  for (int bi = 0; bi < NB; ++bi)
+#pragma unroll
+    for (int h = 0; h < NPH; ++h)
+#pragma unroll
+      for (int c = 0; c < CC::N; ++c) C[bi][h][c] = 0.f;
+  ShiftedWords<W> sw;
+
+  if constexpr (AXIS == 1) {
+    float Zd[NB];
+#pragma unroll
+    for (int bi = 0; bi < NB; ++bi) Zd[bi] = 0.f;
+#pragma unroll
+    for (int p = 0; p < PPR; ++p) {
+      const half2_t sq = as_half2(pair_f16<3>(t.s, p, k3));
+      const half2_t zq = as_half2(pair_f16<3>(t.s, T::B2 / 2 + p, k3));
+      const float s0 = fmaf((float)sq.x, c1, c2), s1 = fmaf((float)sq.y, c1, c2);
+#pragma unroll
+      for (int bi = 0; bi < NB; ++bi) {
+        const half2_t xv = as_half2(xp[bi][p]);
+        half2_t u;
+        u.x = (_Float16)fmaf(s0, (float)xv.x, 0.f);   // binary16 source widened inside the multiply, one rounding
+        u.y = (_Float16)fmaf(s1, (float)xv.y, 0.f);
+        xp[bi][p] = __builtin_bit_cast(uint32_t, u);   // x is not needed any more: keep u in its place
+#pragma unroll
+        for (int h = 0; h < NPH; ++h) {
+          const int c = CC::of_pair(h * PPR + p);
+          C[bi][h][c] = __builtin_amdgcn_fdot2(u, ones, C[bi][h][c], false);
+        }
+        Zd[bi] = __builtin_amdgcn_fdot2(u, zq, Zd[bi], false);
+      }
+    }
+    // sum_j z_hat_j u_j = e1*Zd + e2*U;  sum_j 2^W*K_rj u_j = 2^W * sum_c K(c) * C[h][c]
+#pragma unroll
+    for (int bi = 0; bi < NB; ++bi) {
+      float U = C[bi][0][0];
+#pragma unroll
+      for (int c = 1; c < CC::N; ++c) U += C[bi][0][c];
+      const float zu = fmaf(e1, Zd[bi], e2 * U);
+#pragma unroll
+      for (int h = 0; h < NPH; ++h) {
+        float E = CC::K(0) * C[bi][h][0];
+#pragma unroll
+        for (int c = 1; c < CC::N; ++c) E = fmaf(CC::K(c), C[bi][h][c], E);
+        csum[bi][h] += fmaf(SCALE, E, zu);
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < TR; ++r) {
+      float d[NB];
+#pragma unroll
+      for (int bi = 0; bi < NB; ++bi) d[bi] = acc[bi][r];
+#pragma unroll
+      for (int p = 0; p < PPR; ++p) {
+        if constexpr (SHARED) refresh_shifted<W>(sw, t.c, r * PPR + p);
+        const half2_t q2 = as_half2(SHARED ? pair_class_f16<W>(t.c, sw, r * PPR + p, k) : pair_f16<W>(t.c, r * PPR + p, k1));
+#pragma unroll
+        for (int bi = 0; bi < NB; ++bi) d[bi] = __builtin_amdgcn_fdot2(q2, as_half2(xp[bi][p]), d[bi], false);
+      }
+#pragma unroll
+      for (int bi = 0; bi < NB; ++bi) acc[bi][r] = d[bi];
+    }
+  } else {
+    float X[NB], SE[NB][NPH];
+#pragma unroll
+    for (int bi = 0; bi < NB; ++bi) {
+#pragma unroll
+      for (int p = 0; p < PPR; ++p) {
+#pragma unroll
+        for (int h = 0; h < NPH; ++h) {
+          const int c = CC::of_pair(h * PPR + p);
+          C[bi][h][c] = __builtin_amdgcn_fdot2(as_half2(xp[bi][p]), ones, C[bi][h][c], false);
+        }
+      }
+      X[bi] = C[bi][0][0];
+#pragma unroll
+      for (int c = 1; c < CC::N; ++c) X[bi] += C[bi][0][c];
+#pragma unroll
+      for (int h = 0; h < NPH; ++h) {
+        float E = CC::K(0) * C[bi][h][0];
+#pragma unroll
+        for (int c = 1; c < CC::N; ++c) E = fmaf(CC::K(c), C[bi][h][c], E);
+        SE[bi][h] = SCALE * E;
+      }
+    }
+#pragma unroll
+    for (int r2 = 0; r2 < TR / 2; ++r2) {
+      const half2_t sq = as_half2(pair_f16<3>(t.s, r2, k3));
+      const half2_t zq = as_half2(pair_f16<3>(t.s, T::B2 / 2 + r2, k3));
+#pragma unroll
+      for (int h2 = 0; h2 < 2; ++h2) {
+        const int r = 2 * r2 + h2;
+        float d[NB];
+#pragma unroll
+        for (int bi = 0; bi < NB; ++bi) d[bi] = 0.f;
+#pragma unroll
+        for (int p = 0; p < PPR; ++p) {
+          if constexpr (SHARED) refresh_shifted<W>(sw, t.c, r * PPR + p);
+          const half2_t q2 = as_half2(SHARED ? pair_class_f16<W>(t.c, sw, r * PPR + p, k) : pair_f16<W>(t.c, r * PPR + p, k1));
+#pragma unroll
+          for (int bi = 0; bi < NB; ++bi) d[bi] = __builtin_amdgcn_fdot2(q2, as_half2(xp[bi][p]), d[bi], false);
+        }
+        const float sh = fmaf((float)(h2 ? sq.y : sq.x), c1, c2);
+        const float zh = fmaf((float)(h2 ? zq.y : zq.x), e1, e2);      // z_hat_r
+#pragma unroll
+        for (int bi = 0; bi < NB; ++bi)
+          acc[bi][r] = fmaf(sh, fmaf(-zh, X[bi], fmaf(SCALE, d[bi], -SE[bi][r % NPH])), acc[bi][r]);   // big terms cancel first
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Outliers of one strip (Sec. 4.2 "Storing outliers": entries sorted by row,
+// then column; one 32-bit running count per row).  The strip's entries are one
+// contiguous CSR range.  It is cut into aligned chunks of 8 entries (16 bytes
+// of column indices + 16 bytes of values) dealt to the threads of the
+// workgroup one each, whatever the rows' lengths; a thread multiplies its 8
+// values with x and parks the 8 products in LDS at their CSR position.  After
+// one barrier 16 lanes per row add that row's contiguous slice of products in
+// a fixed order.  No atomics, no search, one global round trip.
+// ---------------------------------------------------------------------------
+
+// Products of the 8 entries of chunk c (global chunk index); entries outside
+// [e_lo, e_hi) give 0.
+__device__ __forceinline__ void chunk_products(const uint16_t* xs, int e_lo, int e_hi, int c,
+                                               const u32x4& c8, const u32x4& v8, float (&p)[8]) {
+  const uint32_t cw[4] = {c8.x, c8.y, c8.z, c8.w};
+  const uint32_t vw[4] = {v8.x, v8.y, v8.z, v8.w};
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int e = 8 * c + i;
+    const bool ok = e >= e_lo && e < e_hi;
+    const uint32_t col = (i & 1) ? (cw[i >> 1] >> 16) : (cw[i >> 1] & 0xFFFFu);
+    const uint32_t val = (i & 1) ? (vw[i >> 1] >> 16) : (vw[i >> 1] & 0xFFFFu);
+    const float xv = h2f(xs[ok ? col : 0u]);
+    p[i] = ok ? h2f((uint16_t)val) * xv : 0.f;
+  }
+}
+
+__device__ __forceinline__ void store_products(float* prod, int slot, const float (&p)[8]) {
+  typedef float f32x4 __attribute__((ext_vector_type(4)));
+  f32x4 lo = {p[0], p[1], p[2], p[3]}, hi = {p[4], p[5], p[6], p[7]};
+  reinterpret_cast<f32x4*>(prod)[2 * slot] = lo;
+  reinterpret_cast<f32x4*>(prod)[2 * slot + 1] = hi;
+}
+
+// Sum of prod[i] for i in [lo, hi) by the 16 lanes of a group, eight reads in flight.
+__device__ __forceinline__ float strided16_sum(const float* prod, int lo, int hi, int l16) {
+  float s = 0.f;
+  for (int i = lo + l16; i < hi; i += 128) {
+    float v[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) v[k] = prod[min(i + 16 * k, hi - 1)];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) s += (i + 16 * k < hi) ? v[k] : 0.f;
+  }
+  return s;
+}
+
+// Workgroup size limits: 16 wavefronts leave the compiler 128 registers per
+// lane, 8 wavefronts 256; a 4-bit tile needs 32 code registers, twice with the
+// prefetch of the next step, and every further activation vector TR more
+// accumulators.
+template <int W, int NB> struct WavesPerGroup { static constexpr int MAX = (W == 3 && NB == 1) ? 16 : 8; };
+
+// NB activation vectors per launch: X holds NB rows of n binary16 values (row
+// stride n), Y NB rows of m outputs (row stride m).  NB = 1 is the GEMV.
+// `strip` is the strip of A this workgroup owns.
+template <int W, int TR, int TC, int AXIS, bool PERM, int NB>
+__device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint16_t* __restrict__ x,
+                                                  void* __restrict__ y, int y_dtype, int chunk_cap,
+                                                  const int strip) {
+  using T = TileRegs<W, TR, TC, AXIS>;
+  static_assert(TR * TC == 256, "tile must hold 256 codes");
+  static_assert((TC / 2) % 4 == 0, "x pairs are read as 16-byte LDS words");
+  constexpr int TILE_BYTES = 16 * T::KW + 4 * T::SD;
+  constexpr int MAX_WAVES = 16;
+  constexpr int XCH = 4 * NB;                // 16-byte chunks of x a thread keeps in flight
+  constexpr int KR = 4;                      // outlier chunks per thread requested ahead of the last dense step
+  constexpr int KMAX = 8;                    // outlier chunks per thread and round at most
+  constexpr int LONG_ROW = 512;              // rows with more entries are summed by all threads
+
+  // dynamic LDS: the NB x vectors | products of the outlier entries (8 floats per
+  // chunk and vector)
+  extern __shared__ __align__(16) uint8_t smem[];
+  uint16_t* xs = reinterpret_cast<uint16_t*>(smem);
+  const int n = A.g.n, ntc = A.g.ntc, m = A.g.m;
+  const int xbytes = (NB * n * 2 + 15) & ~15;
+  float* prod = reinterpret_cast<float*>(smem + xbytes);
+  const int pstride = 8 * chunk_cap;         // floats of products per vector
+  __shared__ float red[MAX_WAVES][NB][TR];
+  __shared__ float osum[NB][TR];
+  __shared__ float lred[NB][TR][MAX_WAVES];
+  __shared__ int rp[TR + 1];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // scalar: step indices and tile bases stay in SGPRs
+  const int nthreads = blockDim.x, nwaves = nthreads >> 6;
+  const int l16 = tid & 15, g16 = tid >> 4, ngroups = nthreads >> 4;
+  const int nsteps = (ntc + 63) >> 6;
+  const uint8_t* strip_base = A.packed + (int64_t)strip * ntc * TILE_BYTES;
+  const int32_t* rpg = A.row_ptr + (int64_t)strip * TR;
+
+  // ---- issue order: row pointers and x first (small, mostly cache hits), then
+  // the first tile.  Everything up to the barrier is straight-line code with
+  // clamped indices instead of branches, so that the wait before staging x
+  // covers the x loads only and never the big tile loads behind them. ------------
+  const int e_lo = rpg[0], e_hi = rpg[TR];   // uniform: scalar loads
+  const int rp_mine = rpg[min(tid, TR)];     // thread r <= TR carries row pointer r into LDS
+  const int nvec = (NB * n) >> 3;            // 16-byte chunks of the NB contiguous x vectors
+  u32x4 xr[XCH];
+  if constexpr (!PERM) {
+#pragma unroll
+    for (int k = 0; k < XCH; ++k)
+      xr[k] = reinterpret_cast<const u32x4*>(x)[min(tid + k * nthreads, nvec - 1)];
+  }
+  __builtin_amdgcn_sched_barrier(0);         // keep the x loads ahead of the tile loads
+
+  T t0, t1;
+  // Tile loads are never branched around: a step that does not exist loads one
+  // 16-byte word per load with all lanes on the strip's first tile (a single
+  // cache line, the result is ignored).  With no conditional load between a tile's
+  // loads and its use, the waits ahead of each code word count exactly the loads
+  // issued behind it, so a tile's arithmetic starts while its later words and the
+  // whole next tile are still in flight.
+  auto issue = [&](T& t, int st) -> int {    // returns the number of tiles in the step's block
+    const bool real = st < nsteps;           // wave-uniform
+    const int L = real ? min(64, ntc - 64 * st) : 1;
+    load_tile<NB == 1>(t, strip_base + (int64_t)64 * (real ? st : 0) * TILE_BYTES, L, min(lane, L - 1));
+    asm volatile("" ::: "memory");           // the loads stay here, ahead of the arithmetic on the other buffer
+    return L;
+  };
+  int step = wave;                           // wave < nwaves <= nsteps: the first step always exists
+  int L0 = min(64, ntc - 64 * step), L1 = 1;
+  load_tile<NB == 1>(t0, strip_base + (int64_t)64 * step * TILE_BYTES, L0, min(lane, L0 - 1));
+  __builtin_amdgcn_sched_barrier(0);
+  rp[min(tid, TR)] = rp_mine;                // clamped duplicates store the same value again
+
+  if constexpr (!PERM) {
+    u32x4* dst = reinterpret_cast<u32x4*>(xs);
+#pragma unroll
+    for (int k = 0; k < XCH; ++k)            // clamped duplicates store the same value again
+      dst[min(tid + k * nthreads, nvec - 1)] = xr[k];
+    if constexpr (NB == 1) {                 // very long x: the rest, one chunk at a time
+      for (int i = tid + XCH * nthreads; i < nvec; i += nthreads) dst[i] = reinterpret_cast<const u32x4*>(x)[i];
+    } else {                                 // several vectors: further batches of XCH chunks
+      for (int i0 = tid + XCH * nthreads; i0 < nvec; i0 += XCH * nthreads) {
+#pragma unroll
+        for (int k = 0; k < XCH; ++k) xr[k] = reinterpret_cast<const u32x4*>(x)[min(i0 + k * nthreads, nvec - 1)];
+#pragma unroll
+        for (int k = 0; k < XCH; ++k) dst[min(i0 + k * nthreads, nvec - 1)] = xr[k];
+      }
+    }
+    for (int j = (nvec << 3) + tid; j < NB * n; j += nthreads) xs[j] = x[j];
+  } else {
+    for (int j = tid; j < NB * n; j += nthreads) xs[j] = x[(j / n) * n + A.perm[j % n]];
+  }
+
+  // ---- outliers: fetch this thread's chunk now, use it after the dense part -----
+  const int c_lo = e_lo >> 3;
+  const int nchunks = e_hi > e_lo ? ((e_hi - 1) >> 3) - c_lo + 1 : 0;
+  const u32x4* col8 = reinterpret_cast<const u32x4*>(A.col);
+  const u32x4* val8 = reinterpret_cast<const u32x4*>(A.val);
+  const int first_round = min(nchunks, nthreads);        // nthreads <= chunk_cap <= KMAX*nthreads
+  u32x4 pc, pv;
+  {                                          // unconditional, like the tile loads: a thread without a chunk
+    const bool have = tid < first_round;     // reads 16 bytes of the strip's first tile instead
+    const u32x4* dummy = reinterpret_cast<const u32x4*>(strip_base);
+    pc = load_once<NB == 1>(have ? col8 + c_lo + tid : dummy);
+    pv = load_once<NB == 1>(have ? val8 + c_lo + tid : dummy);
+  }
+  __syncthreads();                           // x is staged
+
+  // ---- dense part -------------------------------------------------------------
+  constexpr int NPH = RowPhases<W, TC>::N;
+  float acc[NB][TR], csum[NB][NPH];
+#pragma unroll
+  for (int bi = 0; bi < NB; ++bi) {
+#pragma unroll
+    for (int h = 0; h < NPH; ++h) csum[bi][h] = 0.f;
+#pragma unroll
+    for (int r = 0; r < TR; ++r) acc[bi][r] = 0.f;
+  }
+  ClassConsts kc = {};
+  PairConsts k1 = {};
+  if constexpr (SharedShifts<TC>::value) kc = make_class_consts<W>(); else k1 = make_pair_consts<W>();
+  const PairConsts k3 = make_pair_consts<3>();
+  const uint32_t* xs32 = reinterpret_cast<const uint32_t*>(xs);
+  const bool heavy = nchunks > nthreads;     // workgroup-uniform
+#define SPQR_TILE_FMA(t, L, st)                                                                           \
+  tile_fma<W, TR, TC, AXIS, NB>(t, xs32 + (64 * (st) + min(lane, (L) - 1)) * (TC / 2), n >> 1, lane < (L), \
+                                acc, csum, kc, k1, k3)
+  // Two steps per trip, registers ping-pong; the loop has its one exit at the
+  // bottom (a second exit would be merged with it through a block that makes the
+  // compiler wait for every load at the top of the loop).  t0 holds step `step`.
+  while (step + nwaves < nsteps) {           // wave-uniform: at least two steps are left
+    L1 = issue(t1, step + nwaves);
+    SPQR_TILE_FMA(t0, L0, step);
+    L0 = issue(t0, step + 2 * nwaves);       // a dummy after the wavefront's last step
+    SPQR_TILE_FMA(t1, L1, step + nwaves);
+    step += 2 * nwaves;
+  }
+  // A strip with more outlier chunks than threads (slots tid + k*nthreads, k >= 1):
+  // the next KR-1 chunks of this thread are requested here, in the registers the
+  // other tile buffer has just left, and arrive under the wavefront's last dense
+  // step; the rest follow after it, all together.
+  u32x4 lc[KMAX - 1], lv[KMAX - 1];
+  {                                          // unconditional like the tile loads (dummy: the strip's first tile),
+    const u32x4* dummy = reinterpret_cast<const u32x4*>(strip_base);   // so that the waits stay exact
+#pragma unroll
+    for (int k = 1; k < KR; ++k) {
+      const int slot = tid + k * nthreads;
+      const bool have = slot < chunk_cap && slot < nchunks;
+      lc[k - 1] = load_once<NB == 1>(have ? col8 + c_lo + slot : dummy);
+      lv[k - 1] = load_once<NB == 1>(have ? val8 + c_lo + slot : dummy);
+    }
+    asm volatile("" ::: "memory");
+  }
+  if (step < nsteps) SPQR_TILE_FMA(t0, L0, step);
+#undef SPQR_TILE_FMA
+
+  // ---- outlier products of the first round -> LDS -------------------------------
+  if (heavy) {
+#pragma unroll
+    for (int k = KR; k < KMAX; ++k) {
+      const int slot = tid + k * nthreads;
+      if (slot < chunk_cap && slot < nchunks) {
+        lc[k - 1] = load_once<NB == 1>(col8 + c_lo + slot);
+        lv[k - 1] = load_once<NB == 1>(val8 + c_lo + slot);
+      }
+    }
+  }
+  if (tid < first_round) {
+#pragma unroll
+    for (int bi = 0; bi < NB; ++bi) {
+      float p[8];
+      chunk_products(xs + bi * n, e_lo, e_hi, c_lo + tid, pc, pv, p);
+      store_products(prod + bi * pstride, tid, p);
+    }
+  }
+  if (heavy) {
+#pragma unroll
+    for (int k = 1; k < KMAX; ++k) {
+      const int slot = tid + k * nthreads;
+      if (slot < chunk_cap && slot < nchunks) {
+#pragma unroll
+        for (int bi = 0; bi < NB; ++bi) {
+          float p[8];
+          chunk_products(xs + bi * n, e_lo, e_hi, c_lo + slot, lc[k - 1], lv[k - 1], p);
+          store_products(prod + bi * pstride, slot, p);
+        }
+      }
+    }
+  }
+
+  // ---- dense partials: lanes -> rows ---------------------------------------------
+#pragma unroll
+  for (int bi = 0; bi < NB; ++bi) {
+    if constexpr (AXIS == 1) {
+#pragma unroll
+      for (int r = 0; r < TR; ++r) acc[bi][r] = fmaf((float)(1 << W), acc[bi][r], -csum[bi][r % NPH]);
+    }
+    int row;
+    const float rsum = wave_reduce_rows<TR>(acc[bi], lane, &row);
+    if ((lane & ((64 / TR) - 1)) == 0) red[wave][bi][row] = rsum;
+  }
+
+  // Rows too long for 16 lanes, as a bit mask every wavefront works out for itself
+  // from the row pointers in LDS (TR <= 32 lanes vote), and this thread's first
+  // output row: both read ahead of the barrier, off the critical path behind it.
+  static_assert(TR <= 32, "one lane per row votes");
+  const int vr = min(lane, TR - 1);
+  uint64_t longs = __builtin_amdgcn_ballot_w64(lane < TR && rp[vr + 1] - rp[vr] > LONG_ROW);
+  const int r_long = longs ? __builtin_ctzll(longs) : 0;
+  const int lo_long = rp[r_long], hi_long = rp[r_long + 1];
+  const int r_first = min(g16, TR - 1);
+  const int a_first = rp[r_first], b_first = rp[r_first + 1];
+  // One barrier publishes products and partials.  Only a strip with more chunks
+  // than one round holds needs the slow path.
+  __syncthreads();
+  const bool slow = nchunks > chunk_cap;     // workgroup-uniform
+  const int base = 8 * c_lo;                 // CSR index of prod[0] in the first round
+  if (!slow) {
+    if (longs) {
+      // long rows: every thread adds a strided share, one partial per wavefront and row
+      bool first = true;
+      while (longs) {                        // workgroup-uniform
+        const int r = __builtin_ctzll(longs);
+        longs &= longs - 1;
+        const int lo = (first ? lo_long : rp[r]) - base, hi = (first ? hi_long : rp[r + 1]) - base;
+        first = false;
+#pragma unroll
+        for (int bi = 0; bi < NB; ++bi) {
+          const float* pb = prod + bi * pstride;
+          float s = 0.f;
+          for (int i = lo + tid; i < hi; i += 12 * nthreads) {
+            float v[12];
+#pragma unroll
+            for (int k = 0; k < 12; ++k) v[k] = pb[min(i + k * nthreads, hi - 1)];
+#pragma unroll
+            for (int k = 0; k < 12; ++k) s += (i + k * nthreads < hi) ? v[k] : 0.f;
+          }
+          s = wave_allreduce(s, lane);
+          if (lane == 0) lred[bi][r][wave] = s;
+        }
+      }
+      __syncthreads();
+    }
+    // 16 lanes per row: the row's products, plus one dense partial per wavefront
+    for (int r = g16; r < TR; r += ngroups) {
+      const int a = r == g16 ? a_first : rp[r], b = r == g16 ? b_first : rp[r + 1];
+#pragma unroll
+      for (int bi = 0; bi < NB; ++bi) {
+        float s;
+        if (b - a > LONG_ROW) s = l16 < nwaves ? lred[bi][r][l16] : 0.f;
+        else s = strided16_sum(prod + bi * pstride, a - base, b - base, l16);
+        if (l16 < nwaves) s += red[l16][bi][r];
+        s = row16_allreduce(s, lane);
+        if (l16 == 0) {
+          const int64_t i = (int64_t)bi * m + (int64_t)strip * TR + r;
+          if (y_dtype == SPQR_F32) reinterpret_cast<float*>(y)[i] = s;
+          else reinterpret_cast<uint16_t*>(y)[i] = f2h_rne(s);
+        }
+      }
+    }
+    return;
+  }
+
+  // ---- slow path: rounds of chunk_cap chunks (up to KMAX per thread, all loads of a
+  // round in flight together); long rows summed by all threads ----------------------
+  if (tid < NB * TR) (&osum[0][0])[tid] = 0.f;
+  for (int c0 = 0; c0 < nchunks; c0 += chunk_cap) {      // workgroup-uniform
+    const int c1 = min(nchunks, c0 + chunk_cap);
+    if (c0 > 0) __syncthreads();                         // previous round's products are consumed
+    if (c0 > 0) {                                        // round 0 is already in LDS
+      u32x4 cc[KMAX], vv[KMAX];
+#pragma unroll
+      for (int k = 0; k < KMAX; ++k) {
+        const int slot = tid + k * nthreads, j = c0 + slot;
+        if (slot < chunk_cap && j < c1) {
+          cc[k] = load_once<NB == 1>(col8 + c_lo + j);
+          vv[k] = load_once<NB == 1>(val8 + c_lo + j);
+        }
+      }
+#pragma unroll
+      for (int k = 0; k < KMAX; ++k) {
+        const int slot = tid + k * nthreads, j = c0 + slot;
+        if (slot < chunk_cap && j < c1) {
+#pragma unroll
+          for (int bi = 0; bi < NB; ++bi) {
+            float p[8];
+            chunk_products(xs + bi * n, e_lo, e_hi, c_lo + j, cc[k], vv[k], p);
+            store_products(prod + bi * pstride, slot, p);
+          }
+        }
+      }
+    }
+    __syncthreads();
+    const int e0 = 8 * (c_lo + c0), e1 = 8 * (c_lo + c1);   // CSR range covered by this round
+    // rows with a long slice in this round, voted as on the fast path; their partials per
+    // wavefront go through lred, one barrier for all of them
+    uint64_t rl = __builtin_amdgcn_ballot_w64(lane < TR && min(rp[vr + 1], e1) - max(rp[vr], e0) > LONG_ROW);
+    const bool some_long = rl != 0;
+    while (rl) {                                         // workgroup-uniform
+      const int r = __builtin_ctzll(rl);
+      rl &= rl - 1;
+      const int lo = max(rp[r], e0) - e0, hi = min(rp[r + 1], e1) - e0;
+#pragma unroll
+      for (int bi = 0; bi < NB; ++bi) {
+        const float* pb = prod + bi * pstride;
+        float s = 0.f;
+        for (int i = lo + tid; i < hi; i += 4 * nthreads) {
+          float v[4];
+#pragma unroll
+          for (int k = 0; k < 4; ++k) v[k] = pb[min(i + k * nthreads, hi - 1)];
+#pragma unroll
+          for (int k = 0; k < 4; ++k) s += (i + k * nthreads < hi) ? v[k] : 0.f;
+        }
+        s = wave_allreduce(s, lane);
+        if (lane == 0) lred[bi][r][wave] = s;
+      }
+    }
+    if (some_long) __syncthreads();
+    for (int r = g16; r < TR; r += ngroups) {            // a row always meets the same 16 lanes: osum needs no barrier
+      const int a = max(rp[r], e0), b = min(rp[r + 1], e1);
+      if (b > a) {
+#pragma unroll
+        for (int bi = 0; bi < NB; ++bi) {
+          float s;
+          if (b - a > LONG_ROW) s = l16 < nwaves ? lred[bi][r][l16] : 0.f;
+          else s = strided16_sum(prod + bi * pstride, a - e0, b - e0, l16);
+          s = row16_allreduce(s, lane);
+          if (l16 == 0) osum[bi][r] += s;
+        }
+      }
+    }
+  }
+  __syncthreads();
+  if (tid < NB * TR) {
+    const int bi = tid / TR, r = tid % TR;
+    float s = osum[bi][r];
+    for (int w = 0; w < nwaves; ++w) s += red[w][bi][r];
+    const int64_t i = (int64_t)bi * m + (int64_t)strip * TR + r;
+    if (y_dtype == SPQR_F32) reinterpret_cast<float*>(y)[i] = s;
+    else reinterpret_cast<uint16_t*>(y)[i] = f2h_rne(s);
+  }
+}
+
+template <int W, int TR, int TC, int AXIS, bool PERM, int NB>
+__global__ void __launch_bounds__((64 * WavesPerGroup<W, NB>::MAX))
+gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restrict__ y, int y_dtype,
+                    int chunk_cap) {
+  gemv_tile256_body<W, TR, TC, AXIS, PERM, NB>(A, x, y, y_dtype, chunk_cap, blockIdx.x);
+}
+
+// Several matrices that share the input vector and the format (q/k/v, gate/up of
+// a decoder block) in one grid: strips [first[i], first[i+1]) belong to matrix i.
+// Every workgroup does exactly what it would do in a launch of its own matrix.
+struct FusedArgs {
+  int count;
+  int first[SPQR_MAX_FUSED + 1];
+  Geometry g;                                // of matrix 0; m and ntr differ per matrix and are not used by the body
+  const uint8_t* packed[SPQR_MAX_FUSED];
+  const int32_t* row_ptr[SPQR_MAX_FUSED];
+  const uint16_t* col[SPQR_MAX_FUSED];
+  const uint16_t* val[SPQR_MAX_FUSED];
+  void* y[SPQR_MAX_FUSED];
+};
+
+template <int W, int TR, int TC, int AXIS>
+__global__ void __launch_bounds__((64 * WavesPerGroup<W, 1>::MAX))
+gemv_tile256_fused_kernel(FusedArgs F, const uint16_t* __restrict__ x, int y_dtype, int chunk_cap) {
+  int i = 0;
+  while (i + 1 < F.count && (int)blockIdx.x >= F.first[i + 1]) ++i;   // workgroup-uniform, count <= SPQR_MAX_FUSED
+  DevMatrix A;
+  A.g = F.g;
+  A.packed = F.packed[i]; A.row_ptr = F.row_ptr[i]; A.col = F.col[i]; A.val = F.val[i];
+  A.perm = nullptr; A.nnz = 0;
+  gemv_tile256_body<W, TR, TC, AXIS, false, 1>(A, x, F.y[i], y_dtype, chunk_cap, (int)blockIdx.x - F.first[i]);
+}
+
+}  // namespace spqr
