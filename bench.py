@@ -210,7 +210,7 @@ def run_sweep(path, P, synth, torch, dev):
 
 def run_batch_probe(b, P, synth, torch, dev, axis):
     """spqr_gemm_smallbatch at batch b on every distinct layer of configuration 3: the library's choice of path
-    against the vector path forced through the environment (read per call by the library)."""
+    against the vector path forced through spqr_set_option."""
     rows, seen = [], set()
     for li, sp in enumerate(synth.config_layers(3)):
         if (sp.m, sp.n) in seen:
@@ -222,9 +222,9 @@ def run_batch_probe(b, P, synth, torch, dev, axis):
         copies = max(2, int(600e6 // A.compressed_bytes()) + 1)
         X = torch.from_numpy(synth.make_x(sp.n, b, seed=(3, li, b))).to(dev)
         us = time_layer(P, torch, A, X, copies)
-        os.environ["SPQR_MFMA"] = "0"
+        P.spqr_set_option(P.SPQR_OPT_BATCH_PATH, P.SPQR_BATCH_PATH_VECTOR)
         us_vec = time_layer(P, torch, A, X, copies)
-        del os.environ["SPQR_MFMA"]
+        P.spqr_set_option(P.SPQR_OPT_BATCH_PATH, P.SPQR_BATCH_PATH_AUTO)
         nbytes = algorithmic_bytes(A, b)
         rows.append({"layer": sp.name, "m": sp.m, "n": sp.n, "batch": b, "us": round(us, 2),
                      "us_vector_path": round(us_vec, 2), "GBps": round(nbytes / us / 1e3, 1),

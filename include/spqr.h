@@ -26,11 +26,23 @@
  *      rows x beta2 columns.
  *
  * Pointers are DEVICE pointers unless a parameter says "host".  The library
- * never allocates, frees or keeps caller memory.  spqr_gemv, spqr_gemv_fused,
- * spqr_gemm_smallbatch and spqr_dequant_dense are asynchronous on the given
- * HIP stream (a hipStream_t passed as void*; NULL = the default stream) and
- * never synchronise.  Every entry point returns SPQR_OK (0) or a negative
- * spqr_status; nothing throws, aborts or prints.
+ * never frees or keeps caller memory.  The product and decode calls are
+ * asynchronous on the given HIP stream (a hipStream_t passed as void*;
+ * NULL = the default stream).  Who owns device scratch, and what that means:
+ *   - spqr_gemv, spqr_gemv_fused, spqr_gemv_grouped, spqr_dequant_dense and
+ *     batches of up to 3 vectors need no scratch: they allocate nothing and
+ *     never synchronise;
+ *   - spqr_gemm_smallbatch_ws / spqr_gemm_fused_ws take the scratch of the
+ *     larger batches from the caller (spqr_workspace_bytes says how much):
+ *     they allocate nothing, free nothing and never synchronise, on any stream,
+ *     captured or not;
+ *   - spqr_gemm_smallbatch / spqr_gemm_fused are conveniences over them with
+ *     scratch the library owns: one buffer per stream, kept until the process
+ *     ends and grown on demand, which does synchronise that stream and call
+ *     hipFree / hipMalloc (see spqr_gemm_smallbatch);
+ *   - spqr_pack_check synchronises and allocates 16 bytes for the call.
+ * Every entry point returns SPQR_OK (0) or a negative spqr_status; nothing
+ * throws, aborts or prints.
  */
 #ifndef SPQR_H_
 #define SPQR_H_
@@ -54,7 +66,8 @@ typedef enum spqr_status {
   SPQR_ERR_NONFINITE = -7,  /* a 16-bit statistic or outlier value is inf / nan     */
   SPQR_ERR_BATCH     = -8,  /* batch outside [1, SPQR_MAX_BATCH]                    */
   SPQR_ERR_HIP       = -9,  /* a HIP runtime call or kernel launch failed           */
-  SPQR_ERR_DTYPE     = -10  /* unknown output dtype / dequant selector              */
+  SPQR_ERR_DTYPE     = -10, /* unknown output dtype / dequant selector              */
+  SPQR_ERR_WORKSPACE = -11  /* the workspace is smaller than spqr_workspace_bytes() */
 } spqr_status;
 
 #define SPQR_LAYOUT_V1   1
@@ -170,28 +183,51 @@ int spqr_gemv(const spqr_matrix_t* A, const uint16_t* x_f16, void* y, int y_dtyp
 
 /* Y[b][m] = X[b][:] . W_hat^T for 1 <= b <= SPQR_MAX_BATCH (Sec. 4.2 dequantises
  * to 16 bit and multiplies; the sparse part is a product of its own).
- * Up to 4 vectors: one launch of the batch-1 kernel's NB-vector form.  More:
- * either slices of up to 4 (weights read once per slice), or, for tiles of
- * 16x16, 8x32 (group_axis 1) and 32x8 (group_axis 0) and a batch / layer
- * large enough to pay for it,
- * slices of up to 16: the weights are read once per slice, dequantised to
- * binary16 and multiplied on the matrix cores, then a second kernel adds the
- * outliers.  That path takes about (n+1)*32 + (nnz/256 + 2)*64 + splits*16*m*4
- * (+ 32*n with a permutation) bytes
- * of device scratch per slice.  The library keeps one scratch buffer per stream
- * (up to 8 streams per device; grown on demand, which synchronises the stream;
- * held until the process ends) and holds its lock while a call is enqueued:
- * calls on different streams never share scratch, calls from several host
- * threads on one stream are enqueued one after the other.  On a stream that is
- * being captured the scratch is a stream-ordered allocation from the device's
- * default memory pool instead (allocation nodes of the graph, about 10 us more
- * per call), on further streams one from a pool of the library's own.  If no scratch can be had, the slices of 4 run instead.
- * SPQR_MFMA=0 or =1 in the environment forces one or the other where both apply.
+ * Up to 3 vectors (4 on small layers): one launch of the batch-1 kernel's
+ * NB-vector form.  More: either slices of up to 4 (weights read once per
+ * slice), or, for tiles of 16x16, 8x32 (group_axis 1) and 32x8 (group_axis 0)
+ * and a batch / layer large enough to pay for it, slices of up to 16: the
+ * weights are read once per slice, dequantised to binary16 and multiplied on
+ * the matrix cores, then a second kernel adds the outliers.  That path needs
+ * device scratch, about (n+1)*32 + (nnz/256 + 2)*64 + splits*16*m*4 (+ 32*n
+ * with a permutation) bytes per slice.
+ * THIS entry point takes it from the library: one scratch buffer per stream
+ * (up to 8 streams per device), kept until the process ends and grown on
+ * demand -- growing synchronises the stream and calls hipFree and hipMalloc
+ * inside the call -- and it holds the buffer's lock while the call is
+ * enqueued: calls on different streams never share scratch, calls from several
+ * host threads on one stream are enqueued one after the other.  On a stream
+ * that is being captured the scratch is a stream-ordered allocation from the
+ * device's default memory pool instead (allocation nodes of the graph, about
+ * 10 us more per call), on further streams one from a pool of the library's
+ * own.  If no scratch can be had, the slices of 4 run instead.  Callers that
+ * must not allocate or synchronise use spqr_gemm_smallbatch_ws.
  * Results are deterministic (fixed summation order) on either path; the two
  * differ by rounding only (both within the product tolerance).
  * X: [b][n] binary16 row-major.  Y: [b][m] of y_dtype, overwritten. */
 int spqr_gemm_smallbatch(const spqr_matrix_t* A, const uint16_t* X_f16, int b, void* Y,
                          int y_dtype, void* stream);
+
+/* Bytes of device scratch spqr_gemm_smallbatch_ws (count = 1) or
+ * spqr_gemm_fused_ws need at most for these matrices and a batch of b; 0 if the
+ * call takes kernels that need none.  A is a HOST array of `count` descriptor
+ * pointers (1 <= count <= SPQR_MAX_FUSED; they must agree as for
+ * spqr_gemm_fused).  Host arithmetic only; a negative return is an SPQR_ERR_*
+ * code.  The value depends on the descriptors' shapes, nnz and perm, on b and
+ * on the options of spqr_set_option, not on pointers or the stream. */
+int64_t spqr_workspace_bytes(const spqr_matrix_t* const* A, int count, int b);
+
+/* spqr_gemm_smallbatch with scratch the CALLER owns (Sec. 4.2's product, as
+ * above): `workspace` is device memory, 256-byte aligned, of at least
+ * spqr_workspace_bytes(&A, 1, b) bytes (SPQR_ERR_WORKSPACE if smaller; it may
+ * be NULL when that is 0).  The call allocates nothing, frees nothing and
+ * never synchronises; which kernels run does not depend on whether `stream`
+ * is being captured, so a captured call records kernel nodes only.  The
+ * workspace is written by the call's kernels and may be reused by the next
+ * call on the same stream; calls that may overlap need workspaces of their
+ * own.  Same results as spqr_gemm_smallbatch on the same path. */
+int spqr_gemm_smallbatch_ws(const spqr_matrix_t* A, const uint16_t* X_f16, int b, void* Y,
+                            int y_dtype, void* workspace, int64_t workspace_bytes, void* stream);
 
 /* y[i][0..m_i) = W_hat_i . x for `count` (1..SPQR_MAX_FUSED) matrices that
  * share the input vector: the q/k/v or the gate/up projections of a decoder
@@ -214,34 +250,56 @@ int spqr_gemv_fused(const spqr_matrix_t* const* A, int count, const uint16_t* x_
  * path of spqr_gemm_smallbatch, all matrices share one transposition of the
  * batch, one dense launch and one finishing launch per slice of 16 vectors;
  * otherwise, and whenever `stream` is being captured into a graph, the call is
- * `count` calls of spqr_gemm_smallbatch (b == 1: one spqr_gemv_fused).  Same
+ * `count` calls of spqr_gemm_smallbatch (b == 1: one spqr_gemv_fused).  Scratch
+ * as for spqr_gemm_smallbatch (library-owned; spqr_gemm_fused_ws takes the
+ * caller's).  Same
  * arithmetic as spqr_gemm_smallbatch on the same path; only the order of the
  * partial sums over column ranges may differ. */
 int spqr_gemm_fused(const spqr_matrix_t* const* A, int count, const uint16_t* X_f16, int b,
                     void* const* Y, int y_dtype, void* stream);
 
-/* Launch plan of the matrix-core path of spqr_gemm_smallbatch / spqr_gemm_fused,
- * for tuning and tests; host arithmetic only, no device is touched.  The dense
- * launch walks every strip of tiles in steps of 64 tiles; `groups` workgroups
- * (4 or 8 strips each) cover the rows, and the `nsteps` steps of a group are
- * split among workgroups of `s` steps each (the last one may get fewer), every
- * split writing a partial result.  Returns the s the library takes,
- * 1 <= s <= nsteps: the one whose simulated schedule is shortest, where the
- * workgroups start in grid order (split by split: the groups, behind those of
- * the first split the `long_workgroups` workgroups of the long outlier rows) on
- * the first free of `slots` places on the chip (`slots_one_step` places when
- * s == 1: that kernel variant is smaller); a dense workgroup costs its steps
- * + 0.3, a long-row workgroup 0.45 (0.02 behind later splits, where it leaves
- * at once), every split 0.3 for its partial result; ties go to fewer splits.
- * Candidates are s <= 32 and s = nsteps; a candidate whose launch has more
- * than 200000 workgroups is passed over.
- * SPQR_MFMA_STEPS=k in the environment pins s = min(k, nsteps).
- * A negative return is an SPQR_ERR_* code (an argument below 1, or
- * long_workgroups below 0). */
-int spqr_plan_batch_steps(int groups, int nsteps, int slots_one_step, int slots,
-                          int long_workgroups);
+/* spqr_gemm_fused with scratch the caller owns: see spqr_gemm_smallbatch_ws;
+ * the workspace holds at least spqr_workspace_bytes(A, count, b) bytes. */
+int spqr_gemm_fused_ws(const spqr_matrix_t* const* A, int count, const uint16_t* X_f16, int b,
+                       void* const* Y, int y_dtype, void* workspace, int64_t workspace_bytes,
+                       void* stream);
 
-/* Debug decode.  `what` selects the output:
+/* y[i][0..m_i) = W_hat_i . x[i] for `count` (1..SPQR_MAX_GROUPED) matrices, each
+ * with an input vector of its own: all projections of a decoder block whose
+ * inputs are at hand (Sec. 5 times token-by-token generation: seven such
+ * products per block), in as few launches as possible.  A, x_f16 and y are HOST
+ * arrays.  Matrices that agree in n, w_bits, beta1, beta2 and group_axis, have
+ * a tuned kernel and no permutation run in ONE launch (up to SPQR_MAX_FUSED of
+ * them), every workgroup doing what it does in spqr_gemv; the others take a
+ * launch each.  Results equal spqr_gemv's, bit for bit.  No scratch, no
+ * allocation, no synchronisation. */
+#define SPQR_MAX_GROUPED 16
+int spqr_gemv_grouped(const spqr_matrix_t* const* A, int count, const uint16_t* const* x_f16,
+                      void* const* y, int y_dtype, void* stream);
+
+/* Process-wide switches for tuning runs and tests; production code never needs
+ * them (all are 0 at start).  Returns SPQR_ERR_PARAM for an unknown option or
+ * value.
+ *   SPQR_OPT_BATCH_PATH    SPQR_BATCH_PATH_AUTO (0): the library's rule picks the
+ *                          kernels of a batch; _VECTOR (1) / _MATRIX (2): slices
+ *                          of 4 on the vector kernel / slices of 16 on the
+ *                          matrix cores wherever both exist
+ *   SPQR_OPT_FORCE_GENERIC 1: every product takes the element-wise fallback
+ *                          kernel
+ *   SPQR_OPT_BATCH_STEPS   k > 0: the matrix-core path's dense launch gives every
+ *                          workgroup min(k, steps) steps of 64 tiles */
+#define SPQR_OPT_BATCH_PATH     0
+#define SPQR_OPT_FORCE_GENERIC  1
+#define SPQR_OPT_BATCH_STEPS    2
+#define SPQR_OPT_COUNT_         3
+#define SPQR_BATCH_PATH_AUTO    0
+#define SPQR_BATCH_PATH_VECTOR  1
+#define SPQR_BATCH_PATH_MATRIX  2
+int spqr_set_option(int option, int value);
+
+/* Debug decode (Alg. 1 `dequantize`, applied twice as in `fit_statistics`: first to
+ * the statistic codes with the tile's second-level scalars, then to the weight
+ * codes; Sec. 4.2's three parts of the representation).  `what` selects the output:
  *   SPQR_OUT_CODES_U8   uint8  [m][n]   the b_w-bit codes
  *   SPQR_OUT_SCALE_F32  float  group grid ([m][n/beta1] or [m/beta1][n]): s_hat
  *   SPQR_OUT_ZERO_F32   float  group grid: z_hat

@@ -20,6 +20,9 @@ SPQR_CHECK_CSR, SPQR_CHECK_NONFINITE, SPQR_CHECK_PERM = 1, 2, 4
 SPQR_OUT_CODES_U8, SPQR_OUT_SCALE_F32, SPQR_OUT_ZERO_F32 = 0, 1, 2
 SPQR_OUT_DENSE_F32, SPQR_OUT_DENSE_F16, SPQR_OUT_WITH_OUTLIERS = 3, 4, 0x100
 SPQR_LAYOUT_V1 = 1
+SPQR_OPT_BATCH_PATH, SPQR_OPT_FORCE_GENERIC, SPQR_OPT_BATCH_STEPS = 0, 1, 2
+SPQR_BATCH_PATH_AUTO, SPQR_BATCH_PATH_VECTOR, SPQR_BATCH_PATH_MATRIX = 0, 1, 2
+SPQR_ERR_WORKSPACE = -11
 
 
 class SpQRError(RuntimeError):
@@ -81,6 +84,16 @@ def load_library():
     lib.spqr_dequant_dense.argtypes = [P, C.c_int, vp, vp]
     lib.spqr_plan_batch_steps.restype = C.c_int
     lib.spqr_plan_batch_steps.argtypes = [C.c_int] * 5
+    lib.spqr_set_option.restype = C.c_int
+    lib.spqr_set_option.argtypes = [C.c_int, C.c_int]
+    lib.spqr_workspace_bytes.restype = i64
+    lib.spqr_workspace_bytes.argtypes = [C.POINTER(P), C.c_int, C.c_int]
+    lib.spqr_gemm_smallbatch_ws.restype = C.c_int
+    lib.spqr_gemm_smallbatch_ws.argtypes = [P, vp, C.c_int, vp, C.c_int, vp, i64, vp]
+    lib.spqr_gemm_fused_ws.restype = C.c_int
+    lib.spqr_gemm_fused_ws.argtypes = [C.POINTER(P), C.c_int, vp, C.c_int, C.POINTER(vp), C.c_int, vp, i64, vp]
+    lib.spqr_gemv_grouped.restype = C.c_int
+    lib.spqr_gemv_grouped.argtypes = [C.POINTER(P), C.c_int, C.POINTER(vp), C.POINTER(vp), C.c_int, vp]
     _lib = lib
     return lib
 
@@ -245,6 +258,75 @@ def spqr_gemm_fused(As, X, outs=None, y_dtype: int = SPQR_F32, stream=None):
     descs = (C.POINTER(spqr_matrix_t) * k)(*[C.pointer(A.desc) for A in As])
     ys = (C.c_void_p * k)(*[o.data_ptr() for o in outs])
     _check(lib.spqr_gemm_fused(descs, k, X.data_ptr(), b, ys, y_dtype, _stream_ptr(stream)), "spqr_gemm_fused")
+    return outs
+
+
+def spqr_set_option(option: int, value: int) -> None:
+    """Process-wide tuning / test switch (SPQR_OPT_*)."""
+    _check(load_library().spqr_set_option(int(option), int(value)), "spqr_set_option")
+
+
+def spqr_workspace_bytes(As, b: int) -> int:
+    """Device scratch the *_ws calls need at most for these matrices (one SpQRMatrix or a list) at batch b."""
+    As = [As] if isinstance(As, SpQRMatrix) else list(As)
+    k = len(As)
+    descs = (C.POINTER(spqr_matrix_t) * k)(*[C.pointer(A.desc) for A in As])
+    r = load_library().spqr_workspace_bytes(descs, k, int(b))
+    if r < 0:
+        raise SpQRError(int(r), "spqr_workspace_bytes")
+    return int(r)
+
+
+def _ws_args(workspace):
+    if workspace is None:
+        return None, 0
+    return workspace.data_ptr(), workspace.numel() * workspace.element_size()
+
+
+def spqr_gemm_smallbatch_ws(A: SpQRMatrix, X, workspace, out=None, y_dtype: int = SPQR_F32, stream=None):
+    """spqr_gemm_smallbatch with scratch in `workspace` (a device tensor, or None where none is needed)."""
+    import torch
+    assert X.dtype == torch.float16 and X.is_contiguous() and X.dim() == 2 and X.shape[1] == A.n
+    b = int(X.shape[0])
+    if out is None:
+        out = torch.empty((b, A.m), dtype=_out_dtype(y_dtype), device=X.device)
+    wp, wb = _ws_args(workspace)
+    _check(load_library().spqr_gemm_smallbatch_ws(C.byref(A.desc), X.data_ptr(), b, out.data_ptr(), y_dtype, wp, wb,
+                                                  _stream_ptr(stream)), "spqr_gemm_smallbatch_ws")
+    return out
+
+
+def spqr_gemm_fused_ws(As, X, workspace, outs=None, y_dtype: int = SPQR_F32, stream=None):
+    """spqr_gemm_fused with scratch in `workspace`."""
+    import torch
+    As = list(As)
+    assert X.dtype == torch.float16 and X.is_contiguous() and X.dim() == 2 and X.shape[1] == As[0].n
+    b = int(X.shape[0])
+    if outs is None:
+        outs = [torch.empty((b, A.m), dtype=_out_dtype(y_dtype), device=X.device) for A in As]
+    k = len(As)
+    descs = (C.POINTER(spqr_matrix_t) * k)(*[C.pointer(A.desc) for A in As])
+    ys = (C.c_void_p * k)(*[o.data_ptr() for o in outs])
+    wp, wb = _ws_args(workspace)
+    _check(load_library().spqr_gemm_fused_ws(descs, k, X.data_ptr(), b, ys, y_dtype, wp, wb, _stream_ptr(stream)),
+           "spqr_gemm_fused_ws")
+    return outs
+
+
+def spqr_gemv_grouped(As, xs, outs=None, y_dtype: int = SPQR_F32, stream=None):
+    """y_i[m_i] = W_hat_i . x_i for matrices with an input vector each; as few launches as possible."""
+    import torch
+    As, xs = list(As), list(xs)
+    assert len(As) == len(xs)
+    for A, x in zip(As, xs):
+        assert x.dtype == torch.float16 and x.is_contiguous() and x.numel() == A.n
+    if outs is None:
+        outs = [torch.empty(A.m, dtype=_out_dtype(y_dtype), device=x.device) for A, x in zip(As, xs)]
+    k = len(As)
+    descs = (C.POINTER(spqr_matrix_t) * k)(*[C.pointer(A.desc) for A in As])
+    xp = (C.c_void_p * k)(*[x.data_ptr() for x in xs])
+    ys = (C.c_void_p * k)(*[o.data_ptr() for o in outs])
+    _check(load_library().spqr_gemv_grouped(descs, k, xp, ys, y_dtype, _stream_ptr(stream)), "spqr_gemv_grouped")
     return outs
 
 

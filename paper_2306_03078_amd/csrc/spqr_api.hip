@@ -5,6 +5,7 @@
 
 #include "../../include/spqr.h"
 #include "spqr_kernels.h"
+#include "spqr_test_hooks.h"
 
 namespace {
 
@@ -34,12 +35,45 @@ int to_device_matrix(const spqr_matrix_t* A, spqr::DevMatrix* D) {
   return SPQR_OK;
 }
 
-// SPQR_FORCE_GENERIC=1 in the environment routes products through the
-// element-wise fallback kernel (tests cover it on tuned shapes this way); read
-// on every call.
-bool force_generic() {
-  const char* e = std::getenv("SPQR_FORCE_GENERIC");
-  return e && e[0] == '1';
+int hip_status(hipError_t e) {
+  if (e == hipSuccess) return SPQR_OK;
+  if (e == hipErrorOutOfMemory) return SPQR_ERR_WORKSPACE;   // the launchers' signal for a workspace that is too small
+  return SPQR_ERR_HIP;
+}
+
+// Checks shared by the batch entry points, the descriptors first; fills D[0..count).
+int check_batch_call(const spqr_matrix_t* const* A, int count, const uint16_t* X_f16, int b, void* const* Y,
+                     int y_dtype, spqr::DevMatrix* D) {
+  if (!A) return SPQR_ERR_NULL;
+  if (count < 1 || count > SPQR_MAX_FUSED) return SPQR_ERR_PARAM;
+  for (int i = 0; i < count; ++i) {
+    int rc = to_device_matrix(A[i], &D[i]);
+    if (rc) return rc;
+  }
+  if (!Y || !X_f16) return SPQR_ERR_NULL;
+  if (b < 1 || b > SPQR_MAX_BATCH) return SPQR_ERR_BATCH;
+  if (y_dtype != SPQR_F32 && y_dtype != SPQR_F16) return SPQR_ERR_DTYPE;
+  if (reinterpret_cast<uintptr_t>(X_f16) % 16 != 0) return SPQR_ERR_ALIGN;
+  for (int i = 0; i < count; ++i) {
+    if (!Y[i]) return SPQR_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(Y[i]) % (y_dtype == SPQR_F32 ? 4 : 2) != 0) return SPQR_ERR_ALIGN;
+    const spqr_matrix_t *a = A[i], *a0 = A[0];
+    if (a->n != a0->n || a->w_bits != a0->w_bits || a->s_bits != a0->s_bits || a->z_bits != a0->z_bits ||
+        a->beta1 != a0->beta1 || a->beta2 != a0->beta2 || a->group_axis != a0->group_axis ||
+        a->layout_version != a0->layout_version || a->perm != a0->perm)
+      return SPQR_ERR_PARAM;
+  }
+  return SPQR_OK;
+}
+
+int caller_workspace(void* workspace, int64_t workspace_bytes, spqr::Workspace* ws) {
+  if (workspace_bytes < 0) return SPQR_ERR_SIZE;
+  if (workspace_bytes > 0 && !workspace) return SPQR_ERR_NULL;
+  if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return SPQR_ERR_ALIGN;
+  ws->from_caller = true;
+  ws->p = static_cast<uint8_t*>(workspace);
+  ws->bytes = static_cast<size_t>(workspace_bytes);
+  return SPQR_OK;
 }
 
 }  // namespace
@@ -60,18 +94,24 @@ extern "C" int spqr_pack_check(const spqr_matrix_t* A, uint32_t flags, void* str
   return SPQR_OK;
 }
 
+extern "C" int spqr_set_option(int option, int value) {
+  bool ok = true;
+  switch (option) {
+    case SPQR_OPT_BATCH_PATH: ok = value >= SPQR_BATCH_PATH_AUTO && value <= SPQR_BATCH_PATH_MATRIX; break;
+    case SPQR_OPT_FORCE_GENERIC: ok = value == 0 || value == 1; break;
+    case SPQR_OPT_BATCH_STEPS: ok = value >= 0; break;
+    default: ok = false;
+  }
+  return ok && spqr::set_option(option, value) ? SPQR_OK : SPQR_ERR_PARAM;
+}
+
 extern "C" int spqr_gemm_smallbatch(const spqr_matrix_t* A, const uint16_t* X_f16, int b, void* Y,
                                     int y_dtype, void* stream) {
   spqr::DevMatrix D;
-  int rc = to_device_matrix(A, &D);
+  int rc = check_batch_call(&A, 1, X_f16, b, &Y, y_dtype, &D);
   if (rc) return rc;
-  if (!X_f16 || !Y) return SPQR_ERR_NULL;
-  if (b < 1 || b > SPQR_MAX_BATCH) return SPQR_ERR_BATCH;
-  if (y_dtype != SPQR_F32 && y_dtype != SPQR_F16) return SPQR_ERR_DTYPE;
-  if (reinterpret_cast<uintptr_t>(X_f16) % 16 != 0) return SPQR_ERR_ALIGN;
-  if (reinterpret_cast<uintptr_t>(Y) % (y_dtype == SPQR_F32 ? 4 : 2) != 0) return SPQR_ERR_ALIGN;
-  hipError_t e = spqr::launch_gemm(D, X_f16, b, Y, y_dtype, static_cast<hipStream_t>(stream), force_generic());
-  return e == hipSuccess ? SPQR_OK : SPQR_ERR_HIP;
+  spqr::Workspace library;
+  return hip_status(spqr::launch_gemm(D, X_f16, b, Y, y_dtype, static_cast<hipStream_t>(stream), library));
 }
 
 extern "C" int spqr_gemv(const spqr_matrix_t* A, const uint16_t* x_f16, void* y, int y_dtype,
@@ -79,52 +119,101 @@ extern "C" int spqr_gemv(const spqr_matrix_t* A, const uint16_t* x_f16, void* y,
   return spqr_gemm_smallbatch(A, x_f16, 1, y, y_dtype, stream);
 }
 
-extern "C" int spqr_gemv_fused(const spqr_matrix_t* const* A, int count, const uint16_t* x_f16,
-                               void* const* y, int y_dtype, void* stream) {
-  if (!A || !y || !x_f16) return SPQR_ERR_NULL;
+extern "C" int64_t spqr_workspace_bytes(const spqr_matrix_t* const* A, int count, int b) {
+  if (!A) return SPQR_ERR_NULL;
   if (count < 1 || count > SPQR_MAX_FUSED) return SPQR_ERR_PARAM;
-  if (y_dtype != SPQR_F32 && y_dtype != SPQR_F16) return SPQR_ERR_DTYPE;
-  if (reinterpret_cast<uintptr_t>(x_f16) % 16 != 0) return SPQR_ERR_ALIGN;
+  if (b < 1 || b > SPQR_MAX_BATCH) return SPQR_ERR_BATCH;
   spqr::DevMatrix D[SPQR_MAX_FUSED];
   for (int i = 0; i < count; ++i) {
-    if (!A[i] || !y[i]) return SPQR_ERR_NULL;
+    if (!A[i]) return SPQR_ERR_NULL;
     int rc = to_device_matrix(A[i], &D[i]);
     if (rc) return rc;
-    if (reinterpret_cast<uintptr_t>(y[i]) % (y_dtype == SPQR_F32 ? 4 : 2) != 0) return SPQR_ERR_ALIGN;
-    const spqr_matrix_t *a = A[i], *a0 = A[0];
-    if (a->n != a0->n || a->w_bits != a0->w_bits || a->s_bits != a0->s_bits || a->z_bits != a0->z_bits ||
-        a->beta1 != a0->beta1 || a->beta2 != a0->beta2 || a->group_axis != a0->group_axis ||
-        a->layout_version != a0->layout_version || a->perm != a0->perm)
+    if (A[i]->n != A[0]->n || A[i]->w_bits != A[0]->w_bits || A[i]->beta1 != A[0]->beta1 || A[i]->beta2 != A[0]->beta2 ||
+        A[i]->group_axis != A[0]->group_axis || A[i]->perm != A[0]->perm)
       return SPQR_ERR_PARAM;
   }
-  hipError_t e = spqr::launch_gemv_fused(D, count, x_f16, y, y_dtype, static_cast<hipStream_t>(stream),
-                                         force_generic());
-  return e == hipSuccess ? SPQR_OK : SPQR_ERR_HIP;
+  return static_cast<int64_t>(spqr::workspace_bound(D, count, b));
+}
+
+extern "C" int spqr_gemm_smallbatch_ws(const spqr_matrix_t* A, const uint16_t* X_f16, int b, void* Y, int y_dtype,
+                                       void* workspace, int64_t workspace_bytes, void* stream) {
+  spqr::DevMatrix D;
+  int rc = check_batch_call(&A, 1, X_f16, b, &Y, y_dtype, &D);
+  if (rc) return rc;
+  spqr::Workspace ws;
+  rc = caller_workspace(workspace, workspace_bytes, &ws);
+  if (rc) return rc;
+  return hip_status(spqr::launch_gemm(D, X_f16, b, Y, y_dtype, static_cast<hipStream_t>(stream), ws));
+}
+
+extern "C" int spqr_gemm_fused_ws(const spqr_matrix_t* const* A, int count, const uint16_t* X_f16, int b,
+                                  void* const* Y, int y_dtype, void* workspace, int64_t workspace_bytes,
+                                  void* stream) {
+  spqr::DevMatrix D[SPQR_MAX_FUSED];
+  int rc = check_batch_call(A, count, X_f16, b, Y, y_dtype, D);
+  if (rc) return rc;
+  spqr::Workspace ws;
+  rc = caller_workspace(workspace, workspace_bytes, &ws);
+  if (rc) return rc;
+  const hipStream_t st = static_cast<hipStream_t>(stream);
+  return hip_status(b == 1 ? spqr::launch_gemv_fused(D, count, X_f16, Y, y_dtype, st)
+                           : spqr::launch_gemm_fused(D, count, X_f16, b, Y, y_dtype, st, ws));
+}
+
+extern "C" int spqr_gemv_fused(const spqr_matrix_t* const* A, int count, const uint16_t* x_f16,
+                               void* const* y, int y_dtype, void* stream) {
+  spqr::DevMatrix D[SPQR_MAX_FUSED];
+  int rc = check_batch_call(A, count, x_f16, 1, y, y_dtype, D);
+  if (rc) return rc;
+  return hip_status(spqr::launch_gemv_fused(D, count, x_f16, y, y_dtype, static_cast<hipStream_t>(stream)));
+}
+
+extern "C" int spqr_gemv_grouped(const spqr_matrix_t* const* A, int count, const uint16_t* const* x_f16,
+                                 void* const* y, int y_dtype, void* stream) {
+  if (!A || !y || !x_f16) return SPQR_ERR_NULL;
+  if (count < 1 || count > SPQR_MAX_GROUPED) return SPQR_ERR_PARAM;
+  if (y_dtype != SPQR_F32 && y_dtype != SPQR_F16) return SPQR_ERR_DTYPE;
+  spqr::DevMatrix D[SPQR_MAX_GROUPED];
+  for (int i = 0; i < count; ++i) {
+    if (!A[i] || !y[i] || !x_f16[i]) return SPQR_ERR_NULL;
+    int rc = to_device_matrix(A[i], &D[i]);
+    if (rc) return rc;
+    if (reinterpret_cast<uintptr_t>(x_f16[i]) % 16 != 0) return SPQR_ERR_ALIGN;
+    if (reinterpret_cast<uintptr_t>(y[i]) % (y_dtype == SPQR_F32 ? 4 : 2) != 0) return SPQR_ERR_ALIGN;
+  }
+  // matrices that agree in format and n (and have no permutation) go together, up to SPQR_MAX_FUSED per launch,
+  // in the order given
+  bool done[SPQR_MAX_GROUPED] = {};
+  const hipStream_t st = static_cast<hipStream_t>(stream);
+  for (int i = 0; i < count; ++i) {
+    if (done[i]) continue;
+    spqr::DevMatrix G[SPQR_MAX_FUSED];
+    const uint16_t* xs[SPQR_MAX_FUSED];
+    void* ys[SPQR_MAX_FUSED];
+    int k = 0;
+    for (int j = i; j < count && k < SPQR_MAX_FUSED; ++j) {
+      const spqr_matrix_t *a = A[j], *a0 = A[i];
+      const bool same = a->n == a0->n && a->w_bits == a0->w_bits && a->beta1 == a0->beta1 && a->beta2 == a0->beta2 &&
+                        a->group_axis == a0->group_axis && a->perm == nullptr && a0->perm == nullptr;
+      if (done[j] || (j != i && !same)) continue;
+      G[k] = D[j]; xs[k] = x_f16[j]; ys[k] = y[j]; ++k;
+      done[j] = true;
+    }
+    const hipError_t e = spqr::launch_gemv_grouped(G, k, xs, ys, y_dtype, st);
+    if (e != hipSuccess) return SPQR_ERR_HIP;
+  }
+  return SPQR_OK;
 }
 
 extern "C" int spqr_gemm_fused(const spqr_matrix_t* const* A, int count, const uint16_t* X_f16, int b,
                                void* const* Y, int y_dtype, void* stream) {
-  if (!A || !Y || !X_f16) return SPQR_ERR_NULL;
-  if (count < 1 || count > SPQR_MAX_FUSED) return SPQR_ERR_PARAM;
-  if (b < 1 || b > SPQR_MAX_BATCH) return SPQR_ERR_BATCH;
-  if (y_dtype != SPQR_F32 && y_dtype != SPQR_F16) return SPQR_ERR_DTYPE;
-  if (reinterpret_cast<uintptr_t>(X_f16) % 16 != 0) return SPQR_ERR_ALIGN;
   spqr::DevMatrix D[SPQR_MAX_FUSED];
-  for (int i = 0; i < count; ++i) {
-    if (!A[i] || !Y[i]) return SPQR_ERR_NULL;
-    int rc = to_device_matrix(A[i], &D[i]);
-    if (rc) return rc;
-    if (reinterpret_cast<uintptr_t>(Y[i]) % (y_dtype == SPQR_F32 ? 4 : 2) != 0) return SPQR_ERR_ALIGN;
-    const spqr_matrix_t *a = A[i], *a0 = A[0];
-    if (a->n != a0->n || a->w_bits != a0->w_bits || a->s_bits != a0->s_bits || a->z_bits != a0->z_bits ||
-        a->beta1 != a0->beta1 || a->beta2 != a0->beta2 || a->group_axis != a0->group_axis ||
-        a->layout_version != a0->layout_version || a->perm != a0->perm)
-      return SPQR_ERR_PARAM;
-  }
+  int rc = check_batch_call(A, count, X_f16, b, Y, y_dtype, D);
+  if (rc) return rc;
   const hipStream_t st = static_cast<hipStream_t>(stream);
-  hipError_t e = b == 1 ? spqr::launch_gemv_fused(D, count, X_f16, Y, y_dtype, st, force_generic())
-                        : spqr::launch_gemm_fused(D, count, X_f16, b, Y, y_dtype, st, force_generic());
-  return e == hipSuccess ? SPQR_OK : SPQR_ERR_HIP;
+  spqr::Workspace library;
+  return hip_status(b == 1 ? spqr::launch_gemv_fused(D, count, X_f16, Y, y_dtype, st)
+                           : spqr::launch_gemm_fused(D, count, X_f16, b, Y, y_dtype, st, library));
 }
 
 extern "C" int spqr_dequant_dense(const spqr_matrix_t* A, int what, void* out, void* stream) {

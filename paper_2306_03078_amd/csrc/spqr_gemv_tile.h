@@ -238,11 +238,19 @@ template <int W, int NB> struct WavesPerGroup { static constexpr int MAX = (W ==
 
 // NB activation vectors per launch: X holds NB rows of n binary16 values (row
 // stride n), Y NB rows of m outputs (row stride m).  NB = 1 is the GEMV.
-// `strip` is the strip of A this workgroup owns.
+// The workgroup owns the R consecutive strips from `first_strip` on (those that
+// exist): R * TR <= RowsPerGroup rows, one contiguous CSR range.  Its wavefronts
+// are dealt to the strips P = nwaves / R each (the host makes nwaves = R * P and
+// P <= steps of a strip); wavefront `part` of a strip takes the steps part,
+// part + P, ...  One staging of x and one epilogue serve all R strips, and a
+// wavefront that has several steps keeps the next tile's loads in flight under
+// the current tile's arithmetic.
+template <int TR, int NB> struct RowsPerGroup { static constexpr int MAX = NB == 1 ? 64 : TR; };
+
 template <int W, int TR, int TC, int AXIS, bool PERM, int NB>
 __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint16_t* __restrict__ x,
                                                   void* __restrict__ y, int y_dtype, int chunk_cap,
-                                                  const int strip) {
+                                                  const int first_strip, const int R) {
   using T = TileRegs<W, TR, TC, AXIS>;
   static_assert(TR * TC == 256, "tile must hold 256 codes");
   static_assert((TC / 2) % 4 == 0, "x pairs are read as 16-byte LDS words");
@@ -252,6 +260,8 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
   constexpr int KR = 4;                      // outlier chunks per thread requested ahead of the last dense step
   constexpr int KMAX = 8;                    // outlier chunks per thread and round at most
   constexpr int LONG_ROW = 512;              // rows with more entries are summed by all threads
+  constexpr int ROWS_MAX = RowsPerGroup<TR, NB>::MAX;
+  static_assert(ROWS_MAX <= 64 && ROWS_MAX % TR == 0, "one lane per row votes on long rows");
 
   // dynamic LDS: the NB x vectors | products of the outlier entries (8 floats per
   // chunk and vector)
@@ -262,24 +272,30 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
   float* prod = reinterpret_cast<float*>(smem + xbytes);
   const int pstride = 8 * chunk_cap;         // floats of products per vector
   __shared__ float red[MAX_WAVES][NB][TR];
-  __shared__ float osum[NB][TR];
-  __shared__ float lred[NB][TR][MAX_WAVES];
-  __shared__ int rp[TR + 1];
+  __shared__ float osum[NB][ROWS_MAX];
+  __shared__ float lred[NB][ROWS_MAX][MAX_WAVES];
+  __shared__ int rp[ROWS_MAX + 1];
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // scalar: step indices and tile bases stay in SGPRs
   const int nthreads = blockDim.x, nwaves = nthreads >> 6;
   const int l16 = tid & 15, g16 = tid >> 4, ngroups = nthreads >> 4;
   const int nsteps = (ntc + 63) >> 6;
+  const int P = nwaves / R;                  // wavefronts per strip
+  const int sw = wave / P, part = wave - sw * P;
+  const bool live = first_strip + sw < A.g.ntr;                  // wave-uniform; false: a strip behind the last one
+  const int strip = min(first_strip + sw, A.g.ntr - 1);          // (the wavefront then adds zeros of the last strip)
+  const int row0 = first_strip * TR;
+  const int ROWS = min(R * TR, m - row0);    // rows of this workgroup
   const uint8_t* strip_base = A.packed + (int64_t)strip * ntc * TILE_BYTES;
-  const int32_t* rpg = A.row_ptr + (int64_t)strip * TR;
+  const int32_t* rpg = A.row_ptr + row0;
 
   // ---- issue order: row pointers and x first (small, mostly cache hits), then
   // the first tile.  Everything up to the barrier is straight-line code with
   // clamped indices instead of branches, so that the wait before staging x
   // covers the x loads only and never the big tile loads behind them. ------------
-  const int e_lo = rpg[0], e_hi = rpg[TR];   // uniform: scalar loads
-  const int rp_mine = rpg[min(tid, TR)];     // thread r <= TR carries row pointer r into LDS
+  const int e_lo = rpg[0], e_hi = rpg[ROWS]; // uniform: scalar loads
+  const int rp_mine = rpg[min(tid, ROWS)];   // thread r <= ROWS carries row pointer r into LDS (ROWS < 64 R <= threads)
   const int nvec = (NB * n) >> 3;            // 16-byte chunks of the NB contiguous x vectors
   u32x4 xr[XCH];
   if constexpr (!PERM) {
@@ -303,11 +319,11 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
     asm volatile("" ::: "memory");           // the loads stay here, ahead of the arithmetic on the other buffer
     return L;
   };
-  int step = wave;                           // wave < nwaves <= nsteps: the first step always exists
+  int step = part;                           // part < P <= nsteps: the first step always exists
   int L0 = min(64, ntc - 64 * step), L1 = 1;
   load_tile<NB == 1>(t0, strip_base + (int64_t)64 * step * TILE_BYTES, L0, min(lane, L0 - 1));
   __builtin_amdgcn_sched_barrier(0);
-  rp[min(tid, TR)] = rp_mine;                // clamped duplicates store the same value again
+  rp[min(tid, ROWS)] = rp_mine;              // clamped duplicates store the same value again
 
   if constexpr (!PERM) {
     u32x4* dst = reinterpret_cast<u32x4*>(xs);
@@ -361,17 +377,17 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
   const uint32_t* xs32 = reinterpret_cast<const uint32_t*>(xs);
   const bool heavy = nchunks > nthreads;     // workgroup-uniform
 #define SPQR_TILE_FMA(t, L, st)                                                                           \
-  tile_fma<W, TR, TC, AXIS, NB>(t, xs32 + (64 * (st) + min(lane, (L) - 1)) * (TC / 2), n >> 1, lane < (L), \
+  tile_fma<W, TR, TC, AXIS, NB>(t, xs32 + (64 * (st) + min(lane, (L) - 1)) * (TC / 2), n >> 1, live && lane < (L), \
                                 acc, csum, kc, k1, k3)
   // Two steps per trip, registers ping-pong; the loop has its one exit at the
   // bottom (a second exit would be merged with it through a block that makes the
   // compiler wait for every load at the top of the loop).  t0 holds step `step`.
-  while (step + nwaves < nsteps) {           // wave-uniform: at least two steps are left
-    L1 = issue(t1, step + nwaves);
+  while (step + P < nsteps) {                // wave-uniform: at least two steps are left
+    L1 = issue(t1, step + P);
     SPQR_TILE_FMA(t0, L0, step);
-    L0 = issue(t0, step + 2 * nwaves);       // a dummy after the wavefront's last step
-    SPQR_TILE_FMA(t1, L1, step + nwaves);
-    step += 2 * nwaves;
+    L0 = issue(t0, step + 2 * P);            // a dummy after the wavefront's last step
+    SPQR_TILE_FMA(t1, L1, step + P);
+    step += 2 * P;
   }
   // A strip with more outlier chunks than threads (slots tid + k*nthreads, k >= 1):
   // the next KR-1 chunks of this thread are requested here, in the registers the
@@ -441,12 +457,11 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
   // Rows too long for 16 lanes, as a bit mask every wavefront works out for itself
   // from the row pointers in LDS (TR <= 32 lanes vote), and this thread's first
   // output row: both read ahead of the barrier, off the critical path behind it.
-  static_assert(TR <= 32, "one lane per row votes");
-  const int vr = min(lane, TR - 1);
-  uint64_t longs = __builtin_amdgcn_ballot_w64(lane < TR && rp[vr + 1] - rp[vr] > LONG_ROW);
+  const int vr = min(lane, ROWS - 1);
+  uint64_t longs = __builtin_amdgcn_ballot_w64(lane < ROWS && rp[vr + 1] - rp[vr] > LONG_ROW);
   const int r_long = longs ? __builtin_ctzll(longs) : 0;
   const int lo_long = rp[r_long], hi_long = rp[r_long + 1];
-  const int r_first = min(g16, TR - 1);
+  const int r_first = min(g16, ROWS - 1);
   const int a_first = rp[r_first], b_first = rp[r_first + 1];
   // One barrier publishes products and partials.  Only a strip with more chunks
   // than one round holds needs the slow path.
@@ -480,17 +495,18 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
       __syncthreads();
     }
     // 16 lanes per row: the row's products, plus one dense partial per wavefront
-    for (int r = g16; r < TR; r += ngroups) {
+    for (int r = g16; r < ROWS; r += ngroups) {
       const int a = r == g16 ? a_first : rp[r], b = r == g16 ? b_first : rp[r + 1];
+      const int w0 = (r / TR) * P, rr = r % TR;        // the row's strip: its wavefronts, the row inside it
 #pragma unroll
       for (int bi = 0; bi < NB; ++bi) {
         float s;
         if (b - a > LONG_ROW) s = l16 < nwaves ? lred[bi][r][l16] : 0.f;
         else s = strided16_sum(prod + bi * pstride, a - base, b - base, l16);
-        if (l16 < nwaves) s += red[l16][bi][r];
+        if (l16 < P) s += red[w0 + l16][bi][rr];
         s = row16_allreduce(s, lane);
         if (l16 == 0) {
-          const int64_t i = (int64_t)bi * m + (int64_t)strip * TR + r;
+          const int64_t i = (int64_t)bi * m + row0 + r;
           if (y_dtype == SPQR_F32) reinterpret_cast<float*>(y)[i] = s;
           else reinterpret_cast<uint16_t*>(y)[i] = f2h_rne(s);
         }
@@ -501,7 +517,7 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
 
   // ---- slow path: rounds of chunk_cap chunks (up to KMAX per thread, all loads of a
   // round in flight together); long rows summed by all threads ----------------------
-  if (tid < NB * TR) (&osum[0][0])[tid] = 0.f;
+  for (int i = tid; i < NB * ROWS_MAX; i += nthreads) (&osum[0][0])[i] = 0.f;
   for (int c0 = 0; c0 < nchunks; c0 += chunk_cap) {      // workgroup-uniform
     const int c1 = min(nchunks, c0 + chunk_cap);
     if (c0 > 0) __syncthreads();                         // previous round's products are consumed
@@ -532,7 +548,7 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
     const int e0 = 8 * (c_lo + c0), e1 = 8 * (c_lo + c1);   // CSR range covered by this round
     // rows with a long slice in this round, voted as on the fast path; their partials per
     // wavefront go through lred, one barrier for all of them
-    uint64_t rl = __builtin_amdgcn_ballot_w64(lane < TR && min(rp[vr + 1], e1) - max(rp[vr], e0) > LONG_ROW);
+    uint64_t rl = __builtin_amdgcn_ballot_w64(lane < ROWS && min(rp[vr + 1], e1) - max(rp[vr], e0) > LONG_ROW);
     const bool some_long = rl != 0;
     while (rl) {                                         // workgroup-uniform
       const int r = __builtin_ctzll(rl);
@@ -554,7 +570,7 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
       }
     }
     if (some_long) __syncthreads();
-    for (int r = g16; r < TR; r += ngroups) {            // a row always meets the same 16 lanes: osum needs no barrier
+    for (int r = g16; r < ROWS; r += ngroups) {          // a row always meets the same 16 lanes: osum needs no barrier
       const int a = max(rp[r], e0), b = min(rp[r + 1], e1);
       if (b > a) {
 #pragma unroll
@@ -569,11 +585,11 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
     }
   }
   __syncthreads();
-  if (tid < NB * TR) {
-    const int bi = tid / TR, r = tid % TR;
+  for (int o = tid; o < NB * ROWS; o += nthreads) {
+    const int bi = o / ROWS, r = o % ROWS;
     float s = osum[bi][r];
-    for (int w = 0; w < nwaves; ++w) s += red[w][bi][r];
-    const int64_t i = (int64_t)bi * m + (int64_t)strip * TR + r;
+    for (int w = 0; w < P; ++w) s += red[(r / TR) * P + w][bi][r % TR];
+    const int64_t i = (int64_t)bi * m + row0 + r;
     if (y_dtype == SPQR_F32) reinterpret_cast<float*>(y)[i] = s;
     else reinterpret_cast<uint16_t*>(y)[i] = f2h_rne(s);
   }
@@ -582,34 +598,40 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
 template <int W, int TR, int TC, int AXIS, bool PERM, int NB>
 __global__ void __launch_bounds__((64 * WavesPerGroup<W, NB>::MAX))
 gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restrict__ y, int y_dtype,
-                    int chunk_cap) {
-  gemv_tile256_body<W, TR, TC, AXIS, PERM, NB>(A, x, y, y_dtype, chunk_cap, blockIdx.x);
+                    int chunk_cap, int strips_per_group) {
+  gemv_tile256_body<W, TR, TC, AXIS, PERM, NB>(A, x, y, y_dtype, chunk_cap, blockIdx.x * strips_per_group,
+                                               strips_per_group);
 }
 
-// Several matrices that share the input vector and the format (q/k/v, gate/up of
-// a decoder block) in one grid: strips [first[i], first[i+1]) belong to matrix i.
-// Every workgroup does exactly what it would do in a launch of its own matrix.
+// Several matrices of one format and one input width n (the q/k/v or gate/up projections of a
+// decoder block, or all projections of a block that read n inputs) in one grid: workgroups
+// [first[i], first[i+1]) belong to matrix i, each with its own input vector.  Every
+// workgroup does exactly what it would do in a launch of its own matrix.
 struct FusedArgs {
   int count;
   int first[SPQR_MAX_FUSED + 1];
-  Geometry g;                                // of matrix 0; m and ntr differ per matrix and are not used by the body
+  Geometry g;                                // of matrix 0; m and ntr are set per matrix below
+  int m[SPQR_MAX_FUSED];
   const uint8_t* packed[SPQR_MAX_FUSED];
   const int32_t* row_ptr[SPQR_MAX_FUSED];
   const uint16_t* col[SPQR_MAX_FUSED];
   const uint16_t* val[SPQR_MAX_FUSED];
+  const uint16_t* x[SPQR_MAX_FUSED];
   void* y[SPQR_MAX_FUSED];
 };
 
 template <int W, int TR, int TC, int AXIS>
 __global__ void __launch_bounds__((64 * WavesPerGroup<W, 1>::MAX))
-gemv_tile256_fused_kernel(FusedArgs F, const uint16_t* __restrict__ x, int y_dtype, int chunk_cap) {
+gemv_tile256_fused_kernel(FusedArgs F, int y_dtype, int chunk_cap, int strips_per_group) {
   int i = 0;
   while (i + 1 < F.count && (int)blockIdx.x >= F.first[i + 1]) ++i;   // workgroup-uniform, count <= SPQR_MAX_FUSED
   DevMatrix A;
   A.g = F.g;
+  A.g.m = F.m[i]; A.g.ntr = F.m[i] / TR;
   A.packed = F.packed[i]; A.row_ptr = F.row_ptr[i]; A.col = F.col[i]; A.val = F.val[i];
   A.perm = nullptr; A.nnz = 0;
-  gemv_tile256_body<W, TR, TC, AXIS, false, 1>(A, x, F.y[i], y_dtype, chunk_cap, (int)blockIdx.x - F.first[i]);
+  gemv_tile256_body<W, TR, TC, AXIS, false, 1>(A, F.x[i], F.y[i], y_dtype, chunk_cap,
+                                               ((int)blockIdx.x - F.first[i]) * strips_per_group, strips_per_group);
 }
 
 }  // namespace spqr

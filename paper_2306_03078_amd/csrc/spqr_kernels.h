@@ -4,6 +4,7 @@
 
 #include <atomic>
 
+#include "../../include/spqr.h"
 #include "spqr_device.h"
 
 namespace spqr {
@@ -24,13 +25,25 @@ inline int current_device() {
   return hipGetDevice(&d) == hipSuccess ? d : -1;
 }
 
+// Where a call's device scratch comes from.  from_caller: [p, p + bytes), 256-byte aligned, brought by the caller
+// (or the library's static array): the call allocates nothing, frees nothing and waits for nothing.  Otherwise the
+// library's own scratch, kept per stream (see spqr_mfma.hip).
+struct Workspace {
+  bool from_caller = false;
+  uint8_t* p = nullptr;
+  size_t bytes = 0;
+};
+
 // ---- spqr_dispatch.hip: what the C ABI calls ----
-hipError_t launch_gemv(const DevMatrix& A, const uint16_t* x, void* y, int y_dtype,
-                       hipStream_t stream, bool force_generic);
+int option(int which);                       // SPQR_OPT_* switches, 0 unless spqr_set_option changed them
+bool set_option(int which, int value);
+hipError_t launch_gemv(const DevMatrix& A, const uint16_t* x, void* y, int y_dtype, hipStream_t stream);
+// hipErrorOutOfMemory: the caller's workspace is too small (never with library scratch).
 hipError_t launch_gemm(const DevMatrix& A, const uint16_t* X, int b, void* Y, int y_dtype,
-                       hipStream_t stream, bool force_generic);
+                       hipStream_t stream, const Workspace& ws);
 hipError_t launch_gemm_fused(const DevMatrix* As, int count, const uint16_t* X, int b, void* const* Ys,
-                             int y_dtype, hipStream_t stream, bool force_generic);
+                             int y_dtype, hipStream_t stream, const Workspace& ws);
+size_t workspace_bound(const DevMatrix* As, int count, int b);
 
 // ---- spqr_gemv.hip: the vector kernel ----
 // Largest number of activation vectors (1, 2 or 4, at most `want`) one launch of the tuned kernel takes for this
@@ -42,16 +55,25 @@ hipError_t launch_tuned(const DevMatrix& A, const uint16_t* x, int nb, void* y, 
 // `count` matrices sharing x and the format, one launch when a tuned kernel exists and no
 // permutation is set, else one launch each.
 hipError_t launch_gemv_fused(const DevMatrix* As, int count, const uint16_t* x, void* const* ys,
-                             int y_dtype, hipStream_t stream, bool force_generic);
+                             int y_dtype, hipStream_t stream);
+// The same with one input vector per matrix (the matrices agree in n and format).
+hipError_t launch_gemv_grouped(const DevMatrix* As, int count, const uint16_t* const* xs, void* const* ys,
+                               int y_dtype, hipStream_t stream);
 
-// ---- spqr_mfma.hip: the matrix-core path for batches above 4 ----
-// Whether the path exists for this geometry / is worth taking for a batch of b vectors on this stream.
+// ---- spqr_mfma.hip: the matrix-core path for batches of 4 to 16 ----
+// Whether the path exists for this geometry / is worth taking for a batch of b vectors (alloc_nodes: the scratch
+// would be allocation nodes of a graph under capture).
 bool mfma_has_instance(const Geometry& g);
-bool mfma_wanted(const Geometry& g, int b, hipStream_t stream);
-// hipErrorNotSupported: no scratch to be had; the caller takes the vector path.  b <= 16.
-hipError_t launch_mfma(const DevMatrix& A, const uint16_t* X, int b, void* Y, int y_dtype, hipStream_t stream);
+bool mfma_wanted(const Geometry& g, int b, bool alloc_nodes);
+bool stream_is_capturing(hipStream_t stream);
+// hipErrorNotSupported: no library scratch to be had, the caller takes the vector path; hipErrorOutOfMemory: the
+// caller's workspace is too small.  b <= 16.
+hipError_t launch_mfma(const DevMatrix& A, const uint16_t* X, int b, void* Y, int y_dtype, hipStream_t stream,
+                       const Workspace& ws);
 hipError_t launch_mfma_fused(const DevMatrix* As, int count, const uint16_t* X, int b, void* const* Ys, int y_dtype,
-                             hipStream_t stream);
+                             hipStream_t stream, const Workspace& ws);
+// Upper bound of the scratch of such a call: one matrix at a time and, if `fused`, all of them in one launch set.
+size_t mfma_workspace_bound(const DevMatrix* As, int count, int b, bool fused);
 // Steps of 64 tiles per workgroup of the batch path's dense launch (host arithmetic only, see the definition).
 int plan_batch_steps(int groups, int nsteps, int slots_one_step, int slots, int long_workgroups);
 

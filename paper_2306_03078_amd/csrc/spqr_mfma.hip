@@ -769,10 +769,7 @@ static int long_row_workgroups(const DevMatrix& A) {
 }
 
 static int mfma_steps_per_split(int groups, int nsteps, int slots1, int slots, int nlong) {
-  if (const char* e = std::getenv("SPQR_MFMA_STEPS")) {        // pins it for tuning runs
-    const int v = std::atoi(e);
-    if (v >= 1) return v < nsteps ? v : nsteps;
-  }
+  if (const int v = option(SPQR_OPT_BATCH_STEPS); v >= 1) return v < nsteps ? v : nsteps;   // pinned (tuning, tests)
   struct Known { int groups, nsteps, slots1, slots, nlong, best; };
   static std::mutex lock;
   static std::vector<Known> known;
@@ -806,7 +803,8 @@ int plan_batch_steps(int groups, int nsteps, int slots_one_step, int slots, int 
 // output is binary16): see scratch_get.
 // hipErrorNotSupported = no scratch to be had; the caller takes the vector path.
 template <int W, int TR, int TC, int AXIS>
-static hipError_t launch_mfma_t(const DevMatrix& A, const uint16_t* X, int b, void* Y, int y_dtype, hipStream_t stream) {
+static hipError_t launch_mfma_t(const DevMatrix& A, const uint16_t* X, int b, void* Y, int y_dtype, hipStream_t stream,
+                                const Workspace& ws) {
   using SH = MfmaShape<TR, TC>;
   const Geometry& g = A.g;
   static PerDevice ready;
@@ -834,10 +832,16 @@ static hipError_t launch_mfma_t(const DevMatrix& A, const uint16_t* X, int b, vo
   const size_t xp_bytes = permuted ? up((size_t)b * g.n * 2) : 0;
   const size_t part_bytes = direct ? 0 : (size_t)nsplit * b * g.m * sizeof(float);
   Scratch sc;
-  if (xt_bytes + slot_bytes + xp_bytes + part_bytes > 0 &&
-      scratch_get(&sc, xt_bytes + slot_bytes + xp_bytes + part_bytes, dev, stream) != hipSuccess)
-    return hipErrorNotSupported;
-  uint8_t* const scratch = sc.p;
+  uint8_t* scratch = nullptr;
+  if (const size_t need = xt_bytes + slot_bytes + xp_bytes + part_bytes; need > 0) {
+    if (ws.from_caller) {                    // nothing is allocated, freed or waited for
+      if (ws.p == nullptr || ws.bytes < need) return hipErrorOutOfMemory;
+      scratch = ws.p;
+    } else {
+      if (scratch_get(&sc, need, dev, stream) != hipSuccess) return hipErrorNotSupported;
+      scratch = sc.p;
+    }
+  }
   uint16_t* xt = sparse ? reinterpret_cast<uint16_t*>(scratch) : nullptr;
   float* slots = reinterpret_cast<float*>(scratch + xt_bytes);
   uint16_t* xp = permuted ? reinterpret_cast<uint16_t*>(scratch + xt_bytes + slot_bytes) : nullptr;
@@ -883,27 +887,29 @@ static hipError_t launch_mfma_t(const DevMatrix& A, const uint16_t* X, int b, vo
 // transposition through LDS, the vector path re-reads the weights once per 4 vectors.  Measured on
 // MI355X with eager calls the matrix cores win from 8 vectors on for any layer and from 5 on for layers
 // of 30 M weights or more (4096^2 at b = 5 / 8 / 16: 15.4 / 15.7 / 18.0 us against 13.2 / 16.5 / 32.5;
-// 11008x4096: 26.6 / 26.9 / 28.2 against 31.6 / 45.3 / 89.4).  In a captured call the scratch is an
-// allocation node of the graph, about 10 us more per call: there from 13 vectors on for any layer,
-// from 8 on for layers of 40 M weights and from 5 on for layers of 100 M.  SPQR_MFMA=0 / =1 in the
-// environment (read per call) forces the vector / the matrix-core path wherever it applies (tests
+// 11008x4096: 26.6 / 26.9 / 28.2 against 31.6 / 45.3 / 89.4).  `alloc_nodes`: the call's scratch would be
+// allocation nodes of a graph under capture (library-owned scratch on a capturing stream), about 10 us more
+// per call: then from 13 vectors on for any layer, from 8 on for layers of 40 M weights and from 5 on for
+// layers of 100 M.  The option SPQR_OPT_BATCH_PATH forces one or the other wherever both apply (tests
 // compare the two).
-bool mfma_wanted(const Geometry& g, int b, hipStream_t stream) {
-  const char* e = std::getenv("SPQR_MFMA");
-  if (e && e[0] == '0') return false;
-  if (e && e[0] == '1') return true;
+bool mfma_wanted(const Geometry& g, int b, bool alloc_nodes) {
+  const int forced = option(SPQR_OPT_BATCH_PATH);
+  if (forced == SPQR_BATCH_PATH_VECTOR) return false;
+  if (forced == SPQR_BATCH_PATH_MATRIX) return true;
   const double weights = (double)g.m * (double)g.n;
-  hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
-  const bool capturing = hipStreamIsCapturing(stream, &cs) != hipSuccess || cs != hipStreamCaptureStatusNone;
-  if (capturing) return b >= 13 || (b >= 8 && weights >= 40e6) || weights >= 100e6;
+  if (alloc_nodes) return b >= 13 || (b >= 8 && weights >= 40e6) || weights >= 100e6;
   return b >= 8 || weights >= 30e6;
 }
 
-// The batch path for several matrices that share X (n, format and permutation agree; checked by the caller):
-// one transposition, one dense launch, one finishing launch for all of them.  b <= 16.
+bool stream_is_capturing(hipStream_t stream) {
+  hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(stream, &cs) != hipSuccess) { (void)hipGetLastError(); return true; }
+  return cs != hipStreamCaptureStatusNone;
+}
+
 template <int W, int TR, int TC, int AXIS>
 static hipError_t launch_mfma_fused_t(const DevMatrix* As, int count, const uint16_t* X, int b, void* const* Ys, int y_dtype,
-                                    hipStream_t stream) {
+                                      hipStream_t stream, const Workspace& ws) {
   using SH = MfmaShape<TR, TC>;
   const Geometry& g0 = As[0].g;
   static PerDevice ready;
@@ -945,8 +951,16 @@ static hipError_t launch_mfma_fused_t(const DevMatrix* As, int count, const uint
     total += direct ? 0 : up((size_t)nsplit * b * As[i].g.m * sizeof(float));
   }
   Scratch sc;
-  if (total > 0 && scratch_get(&sc, total, dev, stream) != hipSuccess) return hipErrorNotSupported;
-  uint8_t* const scratch = sc.p;
+  uint8_t* scratch = nullptr;
+  if (total > 0) {
+    if (ws.from_caller) {
+      if (ws.p == nullptr || ws.bytes < total) return hipErrorOutOfMemory;
+      scratch = ws.p;
+    } else {
+      if (scratch_get(&sc, total, dev, stream) != hipSuccess) return hipErrorNotSupported;
+      scratch = sc.p;
+    }
+  }
   uint16_t* xt = sparse ? reinterpret_cast<uint16_t*>(scratch) : nullptr;
   uint16_t* xp = permuted ? reinterpret_cast<uint16_t*>(scratch + xt_bytes) : nullptr;
   MfmaFused F;
@@ -991,6 +1005,58 @@ static hipError_t launch_mfma_fused_t(const DevMatrix* As, int count, const uint
 }
 
 
+#define SPQR_MFMA_INSTANCES(CASE) \
+  CASE(3, 16, 16, 1) CASE(3, 16, 16, 0) CASE(4, 16, 16, 1) CASE(4, 16, 16, 0) \
+  CASE(3, 8, 32, 1) CASE(4, 8, 32, 1) CASE(3, 32, 8, 0) CASE(4, 32, 8, 0)
+
+// Upper bound of the scratch a batch of b <= 16 vectors needs on this path (the launchers need less when the dense
+// kernel can write the output itself): for one matrix alone, and for `count` matrices in one fused launch set.
+template <int TR, int TC>
+static size_t mfma_scratch_bound(const DevMatrix* As, int count, int b, bool fused) {
+  using SH = MfmaShape<TR, TC>;
+  auto up = [](size_t v) { return (v + 255) & ~(size_t)255; };
+  const Geometry& g0 = As[0].g;
+  const int nsteps = (g0.ntc + 63) / 64;
+  const int wgs1 = (TC != 32 && 3 * ((size_t)SH::NS * 64 * kMfmaTileStride * 4 + (size_t)b * SH::XROW + 1024) <= 160 * 1024) ? 3 : SH::WGS;
+  int total_groups = 0, total_extra = 0;
+  bool sparse = false;
+  for (int i = 0; i < count; ++i) {
+    total_groups += (As[i].g.ntr + SH::NS - 1) / SH::NS;
+    total_extra += long_row_workgroups(As[i]);
+    sparse = sparse || As[i].nnz > 0;
+  }
+  size_t worst = 0;
+  if (fused) {
+    const int s = mfma_steps_per_split(total_groups, nsteps, wgs1 * kCUs, SH::WGS * kCUs, total_extra);
+    const int nsplit = (nsteps + s - 1) / s;
+    size_t total = (sparse ? up(((size_t)g0.n + 1) * 32) : 0) + (As[0].perm ? up((size_t)b * g0.n * 2) : 0);
+    for (int i = 0; i < count; ++i)
+      total += (As[i].nnz > 0 ? up(((size_t)(As[i].nnz / kSlotGrain) + 2) * 64) : 0) +
+               up((size_t)nsplit * b * As[i].g.m * sizeof(float));
+    worst = total;
+  }
+  for (int i = 0; i < count; ++i) {
+    const DevMatrix& A = As[i];
+    const int groups = (A.g.ntr + SH::NS - 1) / SH::NS;
+    const int s = mfma_steps_per_split(groups, nsteps, wgs1 * kCUs, SH::WGS * kCUs, long_row_workgroups(A));
+    const int nsplit = (nsteps + s - 1) / s;
+    const size_t need = (A.nnz > 0 ? up(((size_t)A.g.n + 1) * 32) + up(((size_t)(A.nnz / kSlotGrain) + 2) * 64) : 0) +
+                        (A.perm ? up((size_t)b * A.g.n * 2) : 0) + up((size_t)nsplit * b * A.g.m * sizeof(float));
+    if (need > worst) worst = need;
+  }
+  return worst;
+}
+
+size_t mfma_workspace_bound(const DevMatrix* As, int count, int b, bool fused) {
+  const Geometry& g = As[0].g;
+#define SPQR_MFMA_CASE(W_, TR_, TC_, AX_) \
+  if (g.w_bits == W_ && g.tile_rows == TR_ && g.tile_cols == TC_ && g.axis == AX_) \
+    return mfma_scratch_bound<TR_, TC_>(As, count, b, fused);
+  SPQR_MFMA_INSTANCES(SPQR_MFMA_CASE)
+#undef SPQR_MFMA_CASE
+  return 0;
+}
+
 // Tile shapes the matrix-core kernel is built for: the ones the vector kernel is tuned for.
 bool mfma_has_instance(const Geometry& g) {
   const bool shape16 = g.tile_rows == 16 && g.tile_cols == 16;
@@ -999,26 +1065,23 @@ bool mfma_has_instance(const Geometry& g) {
   return (g.w_bits == 3 || g.w_bits == 4) && (shape16 || shape8x32 || shape32x8);
 }
 
-#define SPQR_MFMA_INSTANCES(CASE) \
-  CASE(3, 16, 16, 1) CASE(3, 16, 16, 0) CASE(4, 16, 16, 1) CASE(4, 16, 16, 0) \
-  CASE(3, 8, 32, 1) CASE(4, 8, 32, 1) CASE(3, 32, 8, 0) CASE(4, 32, 8, 0)
-
-hipError_t launch_mfma(const DevMatrix& A, const uint16_t* X, int b, void* Y, int y_dtype, hipStream_t stream) {
+hipError_t launch_mfma(const DevMatrix& A, const uint16_t* X, int b, void* Y, int y_dtype, hipStream_t stream,
+                       const Workspace& ws) {
   const Geometry& g = A.g;
 #define SPQR_MFMA_CASE(W_, TR_, TC_, AX_) \
   if (g.w_bits == W_ && g.tile_rows == TR_ && g.tile_cols == TC_ && g.axis == AX_) \
-    return launch_mfma_t<W_, TR_, TC_, AX_>(A, X, b, Y, y_dtype, stream);
+    return launch_mfma_t<W_, TR_, TC_, AX_>(A, X, b, Y, y_dtype, stream, ws);
   SPQR_MFMA_INSTANCES(SPQR_MFMA_CASE)
 #undef SPQR_MFMA_CASE
   return hipErrorNotSupported;
 }
 
 hipError_t launch_mfma_fused(const DevMatrix* As, int count, const uint16_t* X, int b, void* const* Ys, int y_dtype,
-                             hipStream_t stream) {
+                             hipStream_t stream, const Workspace& ws) {
   const Geometry& g = As[0].g;
 #define SPQR_MFMA_CASE(W_, TR_, TC_, AX_) \
   if (g.w_bits == W_ && g.tile_rows == TR_ && g.tile_cols == TC_ && g.axis == AX_) \
-    return launch_mfma_fused_t<W_, TR_, TC_, AX_>(As, count, X, b, Ys, y_dtype, stream);
+    return launch_mfma_fused_t<W_, TR_, TC_, AX_>(As, count, X, b, Ys, y_dtype, stream, ws);
   SPQR_MFMA_INSTANCES(SPQR_MFMA_CASE)
 #undef SPQR_MFMA_CASE
   return hipErrorNotSupported;

@@ -140,9 +140,6 @@ __global__ void check_perm_kernel(DevMatrix A, int* flag) {
   if (p < 0 || p >= A.g.n) atomicMax(flag + 2, 1);
 }
 
-// Device-side result words of spqr_pack_check: [0] CSR status, [1] non-finite, [2] perm.
-__device__ int g_check_words[4];
-
 hipError_t launch_generic(const DevMatrix& A, const uint16_t* x, void* y, int y_dtype, hipStream_t stream) {
   const int rows_per_block = 4;
   hipLaunchKernelGGL(gemv_generic_kernel, dim3((A.g.m + rows_per_block - 1) / rows_per_block),
@@ -185,12 +182,12 @@ hipError_t launch_dequant(const DevMatrix& A, int what, void* out, hipStream_t s
   return hipGetLastError();
 }
 
-// Runs the selected device checks and copies the three result words to the host.
-hipError_t run_checks(const DevMatrix& A, bool csr, bool finite, bool perm, int host_words[3],
-                      hipStream_t stream) {
-  int* words = nullptr;
-  hipError_t e = hipGetSymbolAddress((void**)&words, HIP_SYMBOL(g_check_words));
-  if (e != hipSuccess) return e;
+// Runs the selected device checks and copies the three result words ([0] CSR status, [1] non-finite, [2] perm)
+// to the host.  The words live in 16 bytes of device memory allocated for this call alone, so that calls on
+// different streams never share them; the call synchronises anyway.
+static hipError_t run_checks_on(const DevMatrix& A, bool csr, bool finite, bool perm, int host_words[3],
+                                int* words, hipStream_t stream) {
+  hipError_t e = hipSuccess;
   for (int k = 0; k < 3; ++k)
     hipLaunchKernelGGL(fill_int_kernel, dim3(1), dim3(64), 0, stream, words + k, 0);
   const int bs = 256;
@@ -217,6 +214,17 @@ hipError_t run_checks(const DevMatrix& A, bool csr, bool finite, bool perm, int 
   e = hipMemcpyAsync(host_words, words, 3 * sizeof(int), hipMemcpyDeviceToHost, stream);
   if (e != hipSuccess) return e;
   return hipStreamSynchronize(stream);
+}
+
+hipError_t run_checks(const DevMatrix& A, bool csr, bool finite, bool perm, int host_words[3],
+                      hipStream_t stream) {
+  int* words = nullptr;
+  hipError_t e = hipMalloc(reinterpret_cast<void**>(&words), 4 * sizeof(int));
+  if (e != hipSuccess) return e;
+  e = run_checks_on(A, csr, finite, perm, host_words, words, stream);
+  if (e != hipSuccess) (void)hipStreamSynchronize(stream);      // nothing of this call may still use the words
+  const hipError_t ef = hipFree(words);
+  return e != hipSuccess ? e : ef;
 }
 
 }  // namespace spqr

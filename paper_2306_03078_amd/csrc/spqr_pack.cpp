@@ -125,6 +125,7 @@ extern "C" const char* spqr_strerror(int status) {
     case SPQR_ERR_BATCH:     return "batch size out of range";
     case SPQR_ERR_HIP:       return "HIP runtime call or kernel launch failed";
     case SPQR_ERR_DTYPE:     return "unknown output dtype or selector";
+    case SPQR_ERR_WORKSPACE: return "workspace smaller than spqr_workspace_bytes() says, or beyond the static scratch";
     default:                 return "unknown status";
   }
 }

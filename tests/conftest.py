@@ -25,3 +25,13 @@ def pytest_collection_modifyitems(config, items):
     for it in items:
         if "gpu" in it.keywords:
             it.add_marker(skip)
+
+
+@pytest.fixture(autouse=True)
+def _library_options_back_to_default(request):
+    """Tests steer the library through spqr_set_option (process-wide): every test leaves the defaults behind."""
+    yield
+    if "gpu" in request.keywords:
+        import paper_2306_03078_amd as P
+        for opt in (P.SPQR_OPT_BATCH_PATH, P.SPQR_OPT_FORCE_GENERIC, P.SPQR_OPT_BATCH_STEPS):
+            P.spqr_set_option(opt, 0)

@@ -348,7 +348,7 @@ def test_fused_batch_projections(P, monkeypatch, w, b1, b2, axis, ntc, b, mode):
     what spqr_gemm_smallbatch gives one by one on the same path, and the oracle's result within the tolerance."""
     import torch
     if mode is not None:
-        monkeypatch.setenv("SPQR_MFMA", mode)
+        P.spqr_set_option(P.SPQR_OPT_BATCH_PATH, P.SPQR_BATCH_PATH_MATRIX if mode == "1" else P.SPQR_BATCH_PATH_VECTOR)
     tr, _ = synth.tile_shape(b1, b2, axis)
     specs = [(5, 0.03, "rows8cols4"), (2, 0.0, "none"), (9, 0.02, "zipf")]
     fs = [make(w, b1, b2, axis, ntr, ntc, rate=r, structure=st, seed=(96, i, ntc)) for i, (ntr, r, st) in enumerate(specs)]
@@ -372,7 +372,7 @@ def test_fused_batch_projections(P, monkeypatch, w, b1, b2, axis, ntc, b, mode):
 def test_fused_batch_projections_with_a_shared_permutation_and_argument_checks(P, monkeypatch):
     import torch
     import ctypes as C
-    monkeypatch.setenv("SPQR_MFMA", "1")
+    P.spqr_set_option(P.SPQR_OPT_BATCH_PATH, P.SPQR_BATCH_PATH_MATRIX)
     perm = np.random.default_rng(6).permutation(70 * 16).astype(np.int32)
     fs = []
     for i, ntr in enumerate((3, 6)):
@@ -399,16 +399,16 @@ def test_fused_batch_projections_with_a_shared_permutation_and_argument_checks(P
 
 
 def test_fallback_kernel_agrees_with_the_tuned_one(P, monkeypatch):
-    """SPQR_FORCE_GENERIC=1 sends a tuned shape through the element-wise fallback kernel."""
+    """The option SPQR_OPT_FORCE_GENERIC sends a tuned shape through the element-wise fallback kernel."""
     f = make(3, 16, 16, 1, 2, 70, rate=0.03, structure="rows8cols4")
     A = P.SpQRMatrix.from_logical(f)
     X = synth.make_x(f.n, 3, seed=(67,))
     ref = orc.matvec(f, X)
     tuned = P.spqr_gemm_smallbatch(A, dev(X)).cpu().numpy()
-    monkeypatch.setenv("SPQR_FORCE_GENERIC", "1")
+    P.spqr_set_option(P.SPQR_OPT_FORCE_GENERIC, 1)
     slow = P.spqr_gemm_smallbatch(A, dev(X)).cpu().numpy()
     fused = [y.cpu().numpy() for y in P.spqr_gemv_fused([A, A], dev(X[0]))]
-    monkeypatch.delenv("SPQR_FORCE_GENERIC")
+    P.spqr_set_option(P.SPQR_OPT_FORCE_GENERIC, 0)
     for k in range(3):
         assert rel_l2(slow[k], ref[k]) <= 1e-5          # canonical binary32 decode, x used exactly
         assert rel_l2(tuned[k], slow[k]) <= REL_L2
@@ -452,10 +452,10 @@ def test_matrix_core_batch_path(P, monkeypatch, w, axis, ntr, ntc, b):
     """Batches above 4 on 16x16 tiles: dense part on the matrix cores (weights dequantised
     to binary16, one rounding; several strips per workgroup, ragged last workgroup), outliers
     added by a pass of their own.  Checked against the oracle and against the vector path
-    (SPQR_MFMA=0) on the same inputs.  The shapes cover one and many steps, steps split over
+    (SPQR_OPT_BATCH_PATH) on the same inputs.  The shapes cover one and many steps, steps split over
     workgroups with partial results, strips whose outliers pass through LDS in several chunks."""
     import torch
-    monkeypatch.setenv("SPQR_MFMA", "1")
+    P.spqr_set_option(P.SPQR_OPT_BATCH_PATH, P.SPQR_BATCH_PATH_MATRIX)
     f = make(w, 16, 16, axis, ntr, ntc, rate=0.03, structure="rows8cols4" if ntc > 64 else "uniform")
     A = P.SpQRMatrix.from_logical(f)
     X = synth.make_x(f.n, b, seed=(47, b, ntc))
@@ -466,9 +466,9 @@ def test_matrix_core_batch_path(P, monkeypatch, w, axis, ntr, ntc, b):
     assert Y.shape == (b, f.m) and np.all(np.isfinite(Y))
     for k in range(b):
         assert rel_l2(Y[k], ref[k]) <= REL_L2, (k, rel_l2(Y[k], ref[k]))
-    monkeypatch.setenv("SPQR_MFMA", "0")
+    P.spqr_set_option(P.SPQR_OPT_BATCH_PATH, P.SPQR_BATCH_PATH_VECTOR)
     Yv = P.spqr_gemm_smallbatch(A, dev(X)).cpu().numpy()
-    monkeypatch.setenv("SPQR_MFMA", "1")
+    P.spqr_set_option(P.SPQR_OPT_BATCH_PATH, P.SPQR_BATCH_PATH_MATRIX)
     for k in range(b):
         assert rel_l2(Y[k], Yv[k]) <= REL_L2
     # deterministic
@@ -483,7 +483,7 @@ def test_matrix_core_batch_path_8x32_tiles(P, monkeypatch, w, axis, ntr, ntc, b)
     """beta1 = 8, beta2 = 32: tiles of 8 rows x 32 columns (groups along the rows, 8 strips per workgroup, an odd
     number of strips leaves m % 16 == 8) and of 32 x 8 (groups along the columns, two blocks of 16 rows per tile)."""
     import torch
-    monkeypatch.setenv("SPQR_MFMA", "1")
+    P.spqr_set_option(P.SPQR_OPT_BATCH_PATH, P.SPQR_BATCH_PATH_MATRIX)
     f = make(w, 8, 32, axis, ntr, ntc, rate=0.03, structure="rows8cols4" if ntc > 64 else "uniform", seed=(89, ntr, ntc))
     A = P.SpQRMatrix.from_logical(f)
     X = synth.make_x(f.n, b, seed=(90, b, ntc))
@@ -494,7 +494,7 @@ def test_matrix_core_batch_path_8x32_tiles(P, monkeypatch, w, axis, ntr, ntc, b)
     assert Y.shape == (b, f.m) and np.all(np.isfinite(Y))
     for k in range(b):
         assert rel_l2(Y[k], ref[k]) <= REL_L2, (k, rel_l2(Y[k], ref[k]))
-    monkeypatch.setenv("SPQR_MFMA", "0")
+    P.spqr_set_option(P.SPQR_OPT_BATCH_PATH, P.SPQR_BATCH_PATH_VECTOR)
     Yv = P.spqr_gemm_smallbatch(A, dev(X)).cpu().numpy()
     for k in range(b):
         assert rel_l2(Y[k], Yv[k]) <= REL_L2
@@ -505,7 +505,7 @@ def test_matrix_core_batch_path_8x32_tiles(P, monkeypatch, w, axis, ntr, ntc, b)
 def test_matrix_core_batch_path_outlier_mixes(P, monkeypatch, structure, rate):
     """The finishing kernel of the batch path: rows dealt to all lanes, rows cut into parts that
     cross a chunk of staged entries (rate 0.2: 16 rows of about 416), nearly dense CSR."""
-    monkeypatch.setenv("SPQR_MFMA", "1")
+    P.spqr_set_option(P.SPQR_OPT_BATCH_PATH, P.SPQR_BATCH_PATH_MATRIX)
     f = make(4, 16, 16, 1, 5, 130, rate=rate, structure=structure, seed=(81, int(rate * 100)))
     A = P.SpQRMatrix.from_logical(f)
     X = synth.make_x(f.n, 11, seed=(82,))
@@ -518,7 +518,7 @@ def test_matrix_core_batch_path_outlier_mixes(P, monkeypatch, structure, rate):
 def test_matrix_core_long_rows_back_to_back(P, monkeypatch, ntc, rate):
     """Every row about as long as the next (2098, 2160, 4320, 576 entries): none of them is far above the average,
     so all stay in the finishing kernel, in 16 parts of up to 270 entries that cross the chunks of staged entries."""
-    monkeypatch.setenv("SPQR_MFMA", "1")
+    P.spqr_set_option(P.SPQR_OPT_BATCH_PATH, P.SPQR_BATCH_PATH_MATRIX)
     f = make(3, 16, 16, 0, 3, ntc, rate=rate, structure="uniform", seed=(83, ntc))
     assert np.diff(f.row_ptr).min() > 512
     A = P.SpQRMatrix.from_logical(f)
@@ -534,7 +534,7 @@ def test_matrix_core_long_rows_many_rows_per_workgroup(P, monkeypatch):
     that takes long rows looks at 255 rows at a time and keeps which of them are long in one 64-bit mask per
     wavefront (row 31 of a wavefront's 64 is bit 31 of the mask's low word, rows 63 / 64 the seam between two
     wavefronts' masks)."""
-    monkeypatch.setenv("SPQR_MFMA", "1")
+    P.spqr_set_option(P.SPQR_OPT_BATCH_PATH, P.SPQR_BATCH_PATH_MATRIX)
     f = make(3, 16, 16, 1, 640, 48, rate=0.0, structure="none", seed=(85,))
     assert f.m == 10240 and f.n == 768
     rng = np.random.default_rng(85)
@@ -566,7 +566,7 @@ def test_matrix_core_long_rows_shared_out_by_entries(P, monkeypatch, w, b1, b2, 
     to each other (full rows, rows of 513, 1024 and 1025 entries: one entry into a new slice, exact slices), rows
     just at and just above what counts as long (256 / 257 entries), empty rows between them, and shares whose
     bounds fall inside a row, on a slice bound and on a row bound."""
-    monkeypatch.setenv("SPQR_MFMA", "1")
+    P.spqr_set_option(P.SPQR_OPT_BATCH_PATH, P.SPQR_BATCH_PATH_MATRIX)
     f = make(w, b1, b2, axis, ntr, ntc, rate=0.0, structure="none", seed=(120, w))
     assert f.n == 2240
     counts = np.zeros(f.m, np.int64)
@@ -592,7 +592,7 @@ def test_matrix_core_long_rows_shared_out_by_entries(P, monkeypatch, w, b1, b2, 
 def test_matrix_core_long_rows_of_a_very_tall_matrix(P, monkeypatch):
     """More than 65536 rows: the search for a share's first row takes two rounds of probes.  Long rows at the very
     top, around the probes' first bracket and at the bottom; the oracle is sampled on those rows and 64 others."""
-    monkeypatch.setenv("SPQR_MFMA", "1")
+    P.spqr_set_option(P.SPQR_OPT_BATCH_PATH, P.SPQR_BATCH_PATH_MATRIX)
     f = make(3, 16, 16, 1, 4200, 20, rate=0.0, structure="none", seed=(122,))
     assert f.m == 67200 and f.n == 320
     counts = np.zeros(f.m, np.int64)
@@ -614,7 +614,7 @@ def test_batch_scratch_is_kept_per_stream_grows_and_falls_back(P, monkeypatch):
     buffer grows), calls on two streams in turn, and more streams than the library keeps buffers for (the rest
     allocate stream-ordered).  Every result against the oracle."""
     import torch
-    monkeypatch.setenv("SPQR_MFMA", "1")
+    P.spqr_set_option(P.SPQR_OPT_BATCH_PATH, P.SPQR_BATCH_PATH_MATRIX)
     small = make(3, 16, 16, 1, 4, 70, rate=0.02, structure="uniform", seed=(130,))
     large = make(4, 16, 16, 1, 24, 140, rate=0.02, structure="uniform", seed=(131,))
     As = {id(f): P.SpQRMatrix.from_logical(f) for f in (small, large)}
@@ -644,7 +644,7 @@ def test_batch_calls_from_two_host_threads_on_one_stream(P, monkeypatch):
     buffer, whose lock keeps their kernels from interleaving.  Every result against the oracle."""
     import threading
     import torch
-    monkeypatch.setenv("SPQR_MFMA", "1")
+    P.spqr_set_option(P.SPQR_OPT_BATCH_PATH, P.SPQR_BATCH_PATH_MATRIX)
     fs = [make(3, 16, 16, 1, 6, 70, rate=0.02, structure="uniform", seed=(140,)),
           make(4, 16, 16, 1, 10, 140, rate=0.02, structure="uniform", seed=(141,))]
     As = [P.SpQRMatrix.from_logical(f) for f in fs]
@@ -679,7 +679,7 @@ def test_batch_path_in_a_captured_graph_replays_like_the_eager_call(P, monkeypat
     """Captured, the batch path allocates its scratch stream-ordered (allocation nodes of the graph).  Several
     replays with eager calls and synchronisations in between, each compared bit for bit with the eager result."""
     import torch
-    monkeypatch.setenv("SPQR_MFMA", "1")
+    P.spqr_set_option(P.SPQR_OPT_BATCH_PATH, P.SPQR_BATCH_PATH_MATRIX)
     f = make(4, 16, 16, 1, 12, 140, rate=0.02, structure="uniform", seed=(133,))
     A = P.SpQRMatrix.from_logical(f)
     X = dev(synth.make_x(f.n, 16, seed=(134,)))
@@ -704,7 +704,7 @@ def test_batch_path_in_a_captured_graph_replays_like_the_eager_call(P, monkeypat
 def test_matrix_core_long_rows_next_to_rows_like_the_average(P, monkeypatch):
     """What counts as a long row depends on the average: with 30 % outliers everywhere (about 600 per row) plus two
     full rows of 2080, only the full rows leave the finishing kernel; the others are cut into 16 parts of about 39."""
-    monkeypatch.setenv("SPQR_MFMA", "1")
+    P.spqr_set_option(P.SPQR_OPT_BATCH_PATH, P.SPQR_BATCH_PATH_MATRIX)
     f = make(4, 16, 16, 1, 5, 130, rate=0.3, structure="uniform", seed=(94,))
     rng = np.random.default_rng(94)
     counts = np.diff(f.row_ptr).astype(np.int64)
@@ -731,7 +731,7 @@ def test_matrix_core_long_rows_next_to_rows_like_the_average(P, monkeypatch):
 def test_matrix_core_batch_path_with_permutation_and_f16_output(P, monkeypatch, w, b1, b2, axis, ntr, ntc, b):
     """Act-order input permutation (column j of the matrix meets x[perm[j]]) and binary16 output on the batch path,
     with and without outliers, one and several splits of the steps."""
-    monkeypatch.setenv("SPQR_MFMA", "1")
+    P.spqr_set_option(P.SPQR_OPT_BATCH_PATH, P.SPQR_BATCH_PATH_MATRIX)
     for rate in (0.03, 0.0):
         f = make(w, b1, b2, axis, ntr, ntc, rate=rate, structure="uniform" if rate else "none", seed=(91, ntc, int(rate * 100)))
         f.perm = np.random.default_rng(92 + ntc).permutation(f.n).astype(np.int32)
@@ -742,9 +742,9 @@ def test_matrix_core_batch_path_with_permutation_and_f16_output(P, monkeypatch, 
         assert max(rel_l2(Y[k], ref[k]) for k in range(b)) <= REL_L2
         Yh = P.spqr_gemm_smallbatch(A, dev(X), y_dtype=P.SPQR_F16).cpu().numpy()
         assert np.array_equal(Yh.view(np.uint16), Y.astype(np.float16).view(np.uint16))
-        monkeypatch.setenv("SPQR_MFMA", "0")
+        P.spqr_set_option(P.SPQR_OPT_BATCH_PATH, P.SPQR_BATCH_PATH_VECTOR)
         Yv = P.spqr_gemm_smallbatch(A, dev(X)).cpu().numpy()
-        monkeypatch.setenv("SPQR_MFMA", "1")
+        P.spqr_set_option(P.SPQR_OPT_BATCH_PATH, P.SPQR_BATCH_PATH_MATRIX)
         assert max(rel_l2(Y[k], Yv[k]) for k in range(b)) <= REL_L2
 
 
@@ -753,7 +753,7 @@ def test_batches_above_16_go_in_slices(P, monkeypatch, b, mode):
     """Slices of 16 on the matrix-core path (40 = 16 + 16 + 8; 33 leaves one vector), whatever the library's rule
     picks for a layer this small (21 = 16 on the matrix cores + 5 on the vector path), slices of 4 on the vector path."""
     if mode is not None:
-        monkeypatch.setenv("SPQR_MFMA", mode)
+        P.spqr_set_option(P.SPQR_OPT_BATCH_PATH, P.SPQR_BATCH_PATH_MATRIX if mode == "1" else P.SPQR_BATCH_PATH_VECTOR)
     f = make(4, 16, 16, 1, 3, 70, rate=0.03, structure="rows8cols4", seed=(87,))
     A = P.SpQRMatrix.from_logical(f)
     X = synth.make_x(f.n, b, seed=(88, b))
@@ -764,7 +764,7 @@ def test_batches_above_16_go_in_slices(P, monkeypatch, b, mode):
 
 
 def test_matrix_core_batch_path_without_outliers_and_sparse_only(P, monkeypatch):
-    monkeypatch.setenv("SPQR_MFMA", "1")
+    P.spqr_set_option(P.SPQR_OPT_BATCH_PATH, P.SPQR_BATCH_PATH_MATRIX)
     f = make(3, 16, 16, 1, 2, 70, rate=0.0, structure="none")
     A = P.SpQRMatrix.from_logical(f)
     X = synth.make_x(f.n, 16, seed=(48,))

@@ -14,14 +14,22 @@ from oracle import layout_reader, spqr_oracle as orc
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def test_library_exports_every_declared_symbol():
-    hdr = open(os.path.join(ROOT, "include", "spqr.h")).read()
+def _declared(path):
+    hdr = open(path).read()
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
-    names = set(re.findall(r"\b(spqr_[a-z_0-9]+)\s*\(", hdr))
-    assert {"spqr_pack_check", "spqr_gemv", "spqr_gemv_fused", "spqr_gemm_fused", "spqr_gemm_smallbatch", "spqr_dequant_dense",
-            "spqr_pack_host", "spqr_packed_bytes", "spqr_strerror", "spqr_version", "spqr_plan_batch_steps"} <= names
+    return set(re.findall(r"\b(spqr_[a-z_0-9]+)\s*\(", hdr))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared(os.path.join(ROOT, "include", "spqr.h"))
+    assert {"spqr_pack_check", "spqr_gemv", "spqr_gemv_fused", "spqr_gemv_grouped", "spqr_gemm_fused", "spqr_gemm_smallbatch",
+            "spqr_gemm_smallbatch_ws", "spqr_gemm_fused_ws", "spqr_workspace_bytes", "spqr_dequant_dense", "spqr_set_option",
+            "spqr_pack_host", "spqr_packed_bytes", "spqr_strerror", "spqr_version"} <= names
+    assert "spqr_plan_batch_steps" not in names      # a test hook, not part of the public interface
+    hooks = _declared(os.path.join(ROOT, "paper_2306_03078_amd", "csrc", "spqr_test_hooks.h"))
+    assert hooks == {"spqr_plan_batch_steps"}
     lib = C.CDLL(P.library_path())
-    for nm in sorted(names):
+    for nm in sorted(names | hooks):
         assert hasattr(lib, nm), nm
 
 
@@ -114,9 +122,9 @@ def _schedule_length(groups, nsteps, s, slots, nlong):
     (64, 4, 512, 512, 128), (172, 4, 768, 512, 128), (64, 11, 512, 512, 128), (104, 7, 512, 512, 128),
     (280, 7, 512, 512, 128), (104, 18, 512, 512, 128), (344, 4, 256, 256, 128), (128, 11, 256, 256, 128),
     (1, 1, 512, 512, 0), (3, 40, 512, 512, 1), (2000, 2, 512, 512, 0), (312, 7, 768, 512, 384)])
-def test_batch_launch_plan_is_the_shortest_simulated_schedule(monkeypatch, groups, nsteps, slots1, slots, nlong):
-    monkeypatch.delenv("SPQR_MFMA_STEPS", raising=False)
+def test_batch_launch_plan_is_the_shortest_simulated_schedule(groups, nsteps, slots1, slots, nlong):
     lib = C.CDLL(P.library_path())
+    assert lib.spqr_set_option(2, 0) == 0                                # SPQR_OPT_BATCH_STEPS: not pinned
     fn = lib.spqr_plan_batch_steps
     fn.restype = C.c_int
     fn.argtypes = [C.c_int] * 5
@@ -130,7 +138,7 @@ def test_batch_launch_plan_is_the_shortest_simulated_schedule(monkeypatch, group
     assert fn(groups, nsteps, slots1, slots, nlong) == got               # remembered, same answer
 
 
-def test_batch_launch_plan_arguments_and_the_pinned_choice(monkeypatch):
+def test_batch_launch_plan_arguments_and_the_pinned_choice():
     lib = C.CDLL(P.library_path())
     fn = lib.spqr_plan_batch_steps
     fn.restype = C.c_int
@@ -142,7 +150,11 @@ def test_batch_launch_plan_arguments_and_the_pinned_choice(monkeypatch):
     assert fn(1, 9, 512, 512, 0) < 9
     # far more groups than places and nothing to balance: whole strips per workgroup cost the fewest partial results
     assert fn(512 * 40, 3, 512, 512, 0) == 3
-    monkeypatch.setenv("SPQR_MFMA_STEPS", "2")
-    assert fn(280, 7, 512, 512, 128) == 2
-    monkeypatch.setenv("SPQR_MFMA_STEPS", "50")
-    assert fn(280, 7, 512, 512, 128) == 7
+    try:
+        assert lib.spqr_set_option(2, 2) == 0                            # SPQR_OPT_BATCH_STEPS
+        assert fn(280, 7, 512, 512, 128) == 2
+        assert lib.spqr_set_option(2, 50) == 0
+        assert fn(280, 7, 512, 512, 128) == 7
+    finally:
+        assert lib.spqr_set_option(2, 0) == 0
+    assert lib.spqr_set_option(2, -1) == -3 and lib.spqr_set_option(9, 0) == -3 and lib.spqr_set_option(0, 3) == -3
