@@ -40,6 +40,8 @@
  *     scratch the library owns: one buffer per stream, kept until the process
  *     ends and grown on demand, which does synchronise that stream and call
  *     hipFree / hipMalloc (see spqr_gemm_smallbatch);
+ *   - spqr_gemm_smallbatch_noalloc keeps the scratch in a static device array
+ *     (for callers that cannot allocate);
  *   - spqr_pack_check synchronises and allocates 16 bytes for the call.
  * Every entry point returns SPQR_OK (0) or a negative spqr_status; nothing
  * throws, aborts or prints.
@@ -228,6 +230,21 @@ int64_t spqr_workspace_bytes(const spqr_matrix_t* const* A, int count, int b);
  * own.  Same results as spqr_gemm_smallbatch on the same path. */
 int spqr_gemm_smallbatch_ws(const spqr_matrix_t* A, const uint16_t* X_f16, int b, void* Y,
                             int y_dtype, void* workspace, int64_t workspace_bytes, void* stream);
+
+/* For callers that cannot allocate device memory at all (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc):
+ * spqr_gemm_smallbatch with its scratch in a static device array of
+ * SPQR_STATIC_SCRATCH_BYTES that the library's code object carries (every GPU
+ * the library runs on holds it until the process ends).  A call whose
+ * spqr_workspace_bytes(&A, 1, b) exceeds that size returns SPQR_ERR_WORKSPACE
+ * and launches nothing.  No hipMalloc, hipFree or other allocating call is
+ * made; the first call on a device asks the runtime for the array's address.
+ * All calls on one GPU share the array: calls that may overlap on one GPU
+ * (different streams) race on it -- give such callers spqr_gemm_smallbatch_ws.
+ * Same results as spqr_gemm_smallbatch_ws. */
+#define SPQR_STATIC_SCRATCH_BYTES (32 * 1024 * 1024)
+int spqr_gemm_smallbatch_noalloc(const spqr_matrix_t* A, const uint16_t* X_f16, int b, void* Y,
+                                 int y_dtype, void* stream);
 
 /* y[i][0..m_i) = W_hat_i . x for `count` (1..SPQR_MAX_FUSED) matrices that
  * share the input vector: the q/k/v or the gate/up projections of a decoder

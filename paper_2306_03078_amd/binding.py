@@ -23,6 +23,7 @@ SPQR_LAYOUT_V1 = 1
 SPQR_OPT_BATCH_PATH, SPQR_OPT_FORCE_GENERIC, SPQR_OPT_BATCH_STEPS = 0, 1, 2
 SPQR_BATCH_PATH_AUTO, SPQR_BATCH_PATH_VECTOR, SPQR_BATCH_PATH_MATRIX = 0, 1, 2
 SPQR_ERR_WORKSPACE = -11
+SPQR_STATIC_SCRATCH_BYTES = 32 * 1024 * 1024
 
 
 class SpQRError(RuntimeError):
@@ -94,6 +95,8 @@ def load_library():
     lib.spqr_gemm_fused_ws.argtypes = [C.POINTER(P), C.c_int, vp, C.c_int, C.POINTER(vp), C.c_int, vp, i64, vp]
     lib.spqr_gemv_grouped.restype = C.c_int
     lib.spqr_gemv_grouped.argtypes = [C.POINTER(P), C.c_int, C.POINTER(vp), C.POINTER(vp), C.c_int, vp]
+    lib.spqr_gemm_smallbatch_noalloc.restype = C.c_int
+    lib.spqr_gemm_smallbatch_noalloc.argtypes = [P, vp, C.c_int, vp, C.c_int, vp]
     _lib = lib
     return lib
 
@@ -311,6 +314,15 @@ def spqr_gemm_fused_ws(As, X, workspace, outs=None, y_dtype: int = SPQR_F32, str
     _check(load_library().spqr_gemm_fused_ws(descs, k, X.data_ptr(), b, ys, y_dtype, wp, wb, _stream_ptr(stream)),
            "spqr_gemm_fused_ws")
     return outs
+
+
+def spqr_gemm_smallbatch_noalloc(A: SpQRMatrix, X, out, y_dtype: int = SPQR_F32, stream=None):
+    """spqr_gemm_smallbatch with scratch in the library's static device array; `out` is the caller's."""
+    import torch
+    assert X.dtype == torch.float16 and X.is_contiguous() and X.dim() == 2 and X.shape[1] == A.n
+    _check(load_library().spqr_gemm_smallbatch_noalloc(C.byref(A.desc), X.data_ptr(), int(X.shape[0]), out.data_ptr(),
+                                                       y_dtype, _stream_ptr(stream)), "spqr_gemm_smallbatch_noalloc")
+    return out
 
 
 def spqr_gemv_grouped(As, xs, outs=None, y_dtype: int = SPQR_F32, stream=None):

@@ -216,6 +216,18 @@ extern "C" int spqr_gemm_fused(const spqr_matrix_t* const* A, int count, const u
                            : spqr::launch_gemm_fused(D, count, X_f16, b, Y, y_dtype, st, library));
 }
 
+extern "C" int spqr_gemm_smallbatch_noalloc(const spqr_matrix_t* A, const uint16_t* X_f16, int b, void* Y,
+                                            int y_dtype, void* stream) {
+  spqr::DevMatrix D;
+  int rc = check_batch_call(&A, 1, X_f16, b, &Y, y_dtype, &D);
+  if (rc) return rc;
+  // sizes beyond the static array are refused before anything is launched
+  if (spqr::workspace_bound(&D, 1, b) > (size_t)SPQR_STATIC_SCRATCH_BYTES) return SPQR_ERR_WORKSPACE;
+  spqr::Workspace ws;
+  if (spqr::static_workspace(&ws) != hipSuccess) return SPQR_ERR_HIP;
+  return hip_status(spqr::launch_gemm(D, X_f16, b, Y, y_dtype, static_cast<hipStream_t>(stream), ws));
+}
+
 extern "C" int spqr_dequant_dense(const spqr_matrix_t* A, int what, void* out, void* stream) {
   spqr::DevMatrix D;
   int rc = to_device_matrix(A, &D);

@@ -74,6 +74,9 @@ hipError_t launch_mfma_fused(const DevMatrix* As, int count, const uint16_t* X, 
                              hipStream_t stream, const Workspace& ws);
 // Upper bound of the scratch of such a call: one matrix at a time and, if `fused`, all of them in one launch set.
 size_t mfma_workspace_bound(const DevMatrix* As, int count, int b, bool fused);
+// The library's static device array as a workspace (callers that cannot allocate); its size is
+// SPQR_STATIC_SCRATCH_BYTES.
+hipError_t static_workspace(Workspace* ws);
 // Steps of 64 tiles per workgroup of the batch path's dense launch (host arithmetic only, see the definition).
 int plan_batch_steps(int groups, int nsteps, int slots_one_step, int slots, int long_workgroups);
 

@@ -1057,6 +1057,34 @@ size_t mfma_workspace_bound(const DevMatrix* As, int count, int b, bool fused) {
   return 0;
 }
 
+// ---- scratch for callers that cannot allocate ------------------------------------------------------------
+// One array per device, resident from the moment the library's code is loaded on it until the process ends.
+// In host code its name stands for the symbol, not for a device address: the address is asked per device
+// (each GPU holds its own copy) and only that pointer is ever handed to kernels.  All calls on a device that
+// use it share it: calls that overlap on one GPU (different streams) race.  Nothing in it has to start at
+// zero: every word a batch call reads (the transposed batch with its zero line, the slots of the long rows,
+// the partial results) is written earlier in the same call.
+static __device__ __align__(256) uint8_t scratch[SPQR_STATIC_SCRATCH_BYTES];
+
+hipError_t static_workspace(Workspace* ws) {
+  static std::mutex lock;
+  static uint8_t* ptr[kMaxDevices];          // the array's address on each device, nullptr = not asked yet
+  const int dev = current_device();
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> hold(lock);
+  if (ptr[dev] == nullptr) {
+    void* p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (p == nullptr) return hipErrorInvalidSymbol;
+    ptr[dev] = static_cast<uint8_t*>(p);
+  }
+  ws->from_caller = true;
+  ws->p = ptr[dev];
+  ws->bytes = SPQR_STATIC_SCRATCH_BYTES;
+  return hipSuccess;
+}
+
 // Tile shapes the matrix-core kernel is built for: the ones the vector kernel is tuned for.
 bool mfma_has_instance(const Geometry& g) {
   const bool shape16 = g.tile_rows == 16 && g.tile_cols == 16;
