@@ -4,7 +4,10 @@
 A step is one pass of the hot path over one batch of synthetic input: the seven
 projections of one LLaMA-65B-shaped decoder block (configuration 4: q, k, v, o
 8192x8192, gate, up 22016x8192, down 8192x22016; 3-bit codes, beta1=8, beta2=32,
-2 % outliers of which 64 full columns), batch 1, i.e. seven spqr_gemv launches.
+2 % outliers of which 64 full columns), batch 1, each with its own input vector:
+one spqr_gemv_grouped call (two launches: the six projections that read 8192
+inputs, and `down`); --calls seven / fused issue them as seven spqr_gemv calls
+or as four calls (q/k/v and gate/up through spqr_gemv_fused).
 Successive steps visit distinct copies of the weights (a pool larger than twice
 the 256 MB last-level cache) so that every launch streams from HBM, and 60 GB of
 other allocations stay resident beside them.  Launches are replayed from a HIP
@@ -272,8 +275,9 @@ def main():
     ap.add_argument("--copies", type=int, default=3, help="distinct copies of the block's weights (470 MB each)")
     ap.add_argument("--group-axis", type=int, default=1)
     ap.add_argument("--filler-gb", type=int, default=60, help="other allocations kept resident beside the weights")
-    ap.add_argument("--fused", action="store_true",
-                    help="issue q/k/v and gate/up as one spqr_gemv_fused call each (4 calls per step instead of 7)")
+    ap.add_argument("--calls", choices=("grouped", "fused", "seven"), default="grouped",
+                    help="how a step issues the seven projections: one spqr_gemv_grouped call (2 launches), q/k/v and "
+                         "gate/up as one spqr_gemv_fused call each (4 launches), or seven spqr_gemv calls")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-configs", action="store_true", help="skip the per-layer figures of configurations 0-3")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
@@ -330,9 +334,11 @@ def main():
     gu = [i for i, nm in enumerate(names) if nm in ("gate", "up")]
     rest = [i for i in range(len(names)) if i not in qkv and i not in gu]
 
-    def run_step(k, fused):
+    def run_step(k, calls):
         c = k % copies
-        if fused:
+        if calls == "grouped":
+            P.spqr_gemv_grouped([pool[i][c] for i in range(len(base))], xs, outs=ys)
+        elif calls == "fused":
             P.spqr_gemv_fused([pool[i][c] for i in qkv], x_h, outs=[ys[i] for i in qkv])
             P.spqr_gemv_fused([pool[i][c] for i in gu], x_h, outs=[ys[i] for i in gu])
             for i in rest:
@@ -341,7 +347,7 @@ def main():
             for li in range(len(base)):
                 P.spqr_gemv(pool[li][c], xs[li], out=ys[li])
 
-    launches_per_step = (2 + len(rest)) if args.fused else len(base)
+    launches_per_step = {"grouped": len({sp.n for sp in specs}), "fused": 2 + len(rest), "seven": len(base)}[args.calls]
     stream = torch.cuda.current_stream()
     use_graph = not args.no_graph
     graph = None
@@ -350,13 +356,13 @@ def main():
         side.wait_stream(stream)
         with torch.cuda.stream(side):
             for k in range(copies):
-                run_step(k, args.fused)
+                run_step(k, args.calls)
         stream.wait_stream(side)
         torch.cuda.synchronize()
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
             for k in range(copies):
-                run_step(k, args.fused)
+                run_step(k, args.calls)
 
     def run_sweeps(nsweeps):                   # one sweep = one pass over the pool = `copies` steps
         for _ in range(nsweeps):
@@ -364,7 +370,7 @@ def main():
                 graph.replay()
             else:
                 for k in range(copies):
-                    run_step(k, args.fused)
+                    run_step(k, args.calls)
 
     e0 = torch.cuda.Event(enable_timing=True)
     e1 = torch.cuda.Event(enable_timing=True)
@@ -425,19 +431,23 @@ def main():
                               "frac_of_hbm_peak": round(bytes_layer[li] / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
                               "isolated_us": {"p10": round(iso[len(iso) // 10], 2), "median": round(iso[len(iso) // 2], 2),
                                               "p90": round(iso[9 * len(iso) // 10], 2)}}
-    # the block issued the other way (q/k/v and gate/up as one spqr_gemv_fused call each; with --fused: seven calls)
-    other = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(other):
-        for k in range(copies):
-            run_step(k, not args.fused)
-    other.replay()
-    torch.cuda.synchronize()
-    e0.record()
-    for _ in range(60):
+    # the block issued the other ways
+    other_us = {}
+    for calls in ("grouped", "fused", "seven"):
+        if calls == args.calls:
+            continue
+        other = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(other):
+            for k in range(copies):
+                run_step(k, calls)
         other.replay()
-    e1.record()
-    torch.cuda.synchronize()
-    other_us = e0.elapsed_time(e1) * 1e3 / (60 * copies)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(60):
+            other.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        other_us["block_us_%s_calls" % calls] = round(e0.elapsed_time(e1) * 1e3 / (60 * copies), 2)
     del pool, graph, other
     torch.cuda.empty_cache()
 
@@ -494,7 +504,7 @@ def main():
     assert max(parity) <= 1e-3, f"parity failed on the timed buffers: {parity}"
 
     tile = "8,32" if args.group_axis == 1 else "32,8"
-    kernel = ("gemv_tile256_kernel<3,%s,%d>" % (tile, args.group_axis))
+    kernel = ("gemv_tile256_%skernel<3,%s,%d>" % ("" if args.calls == "seven" else "fused_", tile, args.group_axis))
     kernel_key = "gemv_tile256_w3_%s_axis%d_config4_block" % (tile.replace(",", "x"), args.group_axis)
     out = {
         "metric": "SpQR GEMV µs/layer + achieved HBM GB/s (% of peak), batch 1",
@@ -510,12 +520,12 @@ def main():
         "config": {"workload": "config 4: one LLaMA-65B-shaped decoder block, q/k/v/o 8192x8192 + gate/up 22016x8192 + "
                                f"down 8192x22016, w=3, beta1=8, beta2=32, group_axis={args.group_axis}, 2% outliers "
                                f"(64 full columns + uniform), batch 1, beside {args.filler_gb} GB of filler allocations",
-                   "launches_per_step": launches_per_step, "fused_calls": bool(args.fused), "weight_copies": copies,
+                   "launches_per_step": launches_per_step, "calls": args.calls, "weight_copies": copies,
                    "pool_MB": round(pool_bytes / 1e6, 1), "graph_replay": bool(use_graph),
                    "wall_ms_per_step": round(wall * 1e3 / steps_timed, 6),
                    "parity_rel_l2": [float(f"{p:.3e}") for p in parity], "parity_checked_on": parity_kind},
         "layers": per_layer,
-        ("block_us_seven_calls" if args.fused else "block_us_fused_calls"): round(other_us, 2),
+        **other_us,
         "roofline": {"bound": "hbm", "achieved": round(step_bytes / launches_per_step / avg_launch_s / 1e9, 2),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(step_bytes / launches_per_step / avg_launch_s / 1e9 / HBM_PEAK_GBS, 4),
@@ -523,8 +533,8 @@ def main():
                      "kernel": kernel,
                      "algorithmic_bytes_per_launch": step_bytes // launches_per_step,
                      "avg_launch_us": round(avg_launch_s * 1e6, 3),
-                     "note": "per launch = mean over the step's launches (seven projections: 4 x 39.0 MB, "
-                             "2 x 104.8 MB, 1 x 104.7 MB of algorithmic bytes)"},
+                     "note": "per launch = mean over the step's launches; the seven projections hold 4 x 39.0 MB, "
+                             "2 x 104.8 MB and 1 x 104.7 MB of algorithmic bytes; all launches run the same kernel body"},
         "cpu_baseline": cpu,
     }
     if other_configs is not None:
