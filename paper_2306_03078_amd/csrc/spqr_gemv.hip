@@ -46,13 +46,17 @@ static bool plan_launch(const Geometry& g, int nb, int max_waves, int slots, Lau
     while (R > 1 && R * P > max_waves) --R;
     if (P > max_waves) P = max_waves;
   } else if (nb == 1) {
-    // Wavefronts per strip.  A wavefront pipelines its steps (the next tile's loads fly under the current
-    // tile's arithmetic), so few wide-enough workgroups beat many one-step wavefronts: 8 wavefronts when the
-    // strip has 8 steps or more, else 4 (both spread evenly over the four SIMDs and leave room for a second
-    // workgroup on the CU), else one per step.  Fitted to timings of the benchmark layers on MI355X.
-    const int cap8 = max_waves < 8 ? max_waves : 8;
-    P = nsteps < 4 ? nsteps : ((nsteps < cap8 ? nsteps : cap8) / 4) * 4;
-    R = 1;
+    // Wavefronts per strip and strips per workgroup, fitted to sweeps of (P, R) over the benchmark layers on
+    // MI355X (both tile shapes of either orientation, 3- and 4-bit).  Workgroups of four wavefronts, one step
+    // each, win wherever a strip has up to 8 steps: many small workgroups in every phase of their life keep
+    // both the memory pipeline and the vector ALUs fed (wider workgroups lose 10-60 % there).  Longer strips
+    // (the `down` projections: 11-18 steps): two strips per workgroup with two wavefronts each, so that every
+    // wavefront has several steps with the next tile in flight under the current one (-12 % on 8192x22016,
+    // -22 % on 6656x17920 against eight one-or-two-step wavefronts), as long as that still leaves more
+    // workgroups than compute units; else eight wavefronts on one strip.
+    if (nsteps <= 8) { P = nsteps < 4 ? nsteps : 4; R = 1; }
+    else if (g.ntr >= 400 && rmax >= 2) { P = 2; R = 2; }
+    else { P = max_waves < 8 ? max_waves : 8; R = 1; }
   } else {
     // several activation vectors: arithmetic dominates, so what counts is wavefronts resident on the CU and an
     // even split of the steps among them

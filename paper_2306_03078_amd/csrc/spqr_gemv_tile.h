@@ -37,6 +37,16 @@ template <int W, int TC> struct RowPhases {
 // per-class sums.  A pair is extracted once and used by all NB vectors.  `valid`
 // false: the lane adds exact zeros (every scale is forced to 0), so no branch
 // surrounds the tile.
+// (fp16(s0 * x.lo), fp16(s1 * x.hi)): the binary16 halves of xpair are widened inside the multiply and each
+// product is rounded once, straight into its half of the result (two instructions per pair).
+__device__ __forceinline__ uint32_t scaled_pair_f16(float s0, float s1, uint32_t xpair) {
+  uint32_t u;
+  asm("v_fma_mixlo_f16 %0, %1, %3, 0 op_sel_hi:[0,1,0]\n\t"
+      "v_fma_mixhi_f16 %0, %2, %3, 0 op_sel:[0,1,0] op_sel_hi:[0,1,0]"
+      : "=&v"(u) : "v"(s0), "v"(s1), "v"(xpair));
+  return u;
+}
+
 template <int W, int TR, int TC, int AXIS, int NB>
 __device__ __forceinline__ void tile_fma(const TileRegs<W, TR, TC, AXIS>& t,
                                          const uint32_t* xpair /* TC/2 dwords in LDS, vector 0 */,
@@ -89,10 +99,7 @@ __device__ __forceinline__ void tile_fma(const TileRegs<W, TR, TC, AXIS>& t,
       const float s0 = fmaf((float)sq.x, c1, c2), s1 = fmaf((float)sq.y, c1, c2);
 #pragma unroll
       for (int bi = 0; bi < NB; ++bi) {
-        const half2_t xv = as_half2(xp[bi][p]);
-        half2_t u;
-        u.x = (_Float16)fmaf(s0, (float)xv.x, 0.f);   // binary16 source widened inside the multiply, one rounding
-        u.y = (_Float16)fmaf(s1, (float)xv.y, 0.f);
+        const half2_t u = as_half2(scaled_pair_f16(s0, s1, xp[bi][p]));
         xp[bi][p] = __builtin_bit_cast(uint32_t, u);   // x is not needed any more: keep u in its place
 #pragma unroll
         for (int h = 0; h < NPH; ++h) {
@@ -193,20 +200,21 @@ __device__ __forceinline__ void tile_fma(const TileRegs<W, TR, TC, AXIS>& t,
 // a fixed order.  No atomics, no search, one global round trip.
 // ---------------------------------------------------------------------------
 
-// Products of the 8 entries of chunk c (global chunk index); entries outside
-// [e_lo, e_hi) give 0.
-__device__ __forceinline__ void chunk_products(const uint16_t* xs, int e_lo, int e_hi, int c,
+// Products of the 8 entries of one chunk.  A chunk at the edge of the workgroup's CSR range also holds entries
+// of its neighbours' rows (or, behind the matrix's last entry, whatever follows in the granule): their
+// products are parked like the others and never read, because the row sums only walk [row_ptr[r],
+// row_ptr[r+1]) of the workgroup's own rows; a column index is clamped to n - 1 so that the read of x stays
+// inside the staged vector whatever the entry holds.
+__device__ __forceinline__ void chunk_products(const uint16_t* xs, uint32_t last_col,
                                                const u32x4& c8, const u32x4& v8, float (&p)[8]) {
   const uint32_t cw[4] = {c8.x, c8.y, c8.z, c8.w};
   const uint32_t vw[4] = {v8.x, v8.y, v8.z, v8.w};
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    const int e = 8 * c + i;
-    const bool ok = e >= e_lo && e < e_hi;
     const uint32_t col = (i & 1) ? (cw[i >> 1] >> 16) : (cw[i >> 1] & 0xFFFFu);
-    const uint32_t val = (i & 1) ? (vw[i >> 1] >> 16) : (vw[i >> 1] & 0xFFFFu);
-    const float xv = h2f(xs[ok ? col : 0u]);
-    p[i] = ok ? h2f((uint16_t)val) * xv : 0.f;
+    const half2_t v2 = as_half2(vw[i >> 1]);
+    const _Float16 xv = __builtin_bit_cast(_Float16, xs[min(col, last_col)]);
+    p[i] = fmaf((float)((i & 1) ? v2.y : v2.x), (float)xv, 0.f);   // both binary16 sources widened inside the multiply
   }
 }
 
@@ -423,7 +431,7 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
 #pragma unroll
     for (int bi = 0; bi < NB; ++bi) {
       float p[8];
-      chunk_products(xs + bi * n, e_lo, e_hi, c_lo + tid, pc, pv, p);
+      chunk_products(xs + bi * n, (uint32_t)(n - 1), pc, pv, p);
       store_products(prod + bi * pstride, tid, p);
     }
   }
@@ -435,7 +443,7 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
 #pragma unroll
         for (int bi = 0; bi < NB; ++bi) {
           float p[8];
-          chunk_products(xs + bi * n, e_lo, e_hi, c_lo + slot, lc[k - 1], lv[k - 1], p);
+          chunk_products(xs + bi * n, (uint32_t)(n - 1), lc[k - 1], lv[k - 1], p);
           store_products(prod + bi * pstride, slot, p);
         }
       }
@@ -538,7 +546,7 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
 #pragma unroll
           for (int bi = 0; bi < NB; ++bi) {
             float p[8];
-            chunk_products(xs + bi * n, e_lo, e_hi, c_lo + j, cc[k], vv[k], p);
+            chunk_products(xs + bi * n, (uint32_t)(n - 1), cc[k], vv[k], p);
             store_products(prod + bi * pstride, slot, p);
           }
         }
