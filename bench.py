@@ -31,6 +31,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 MIN_TIMED_MS = 60.0      # the timed region is never shorter than this
+MIN_SWEEP_MS = 20.0      # the same for every figure of the per-layer and per-block sweeps
 
 
 def measured_traffic(kernel_key):
@@ -73,9 +74,12 @@ def time_layer(P, torch, A, X, copies, reps=6):
     with torch.cuda.graph(g):
         for M in pool:
             fn(M)
+    e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
     g.replay()
     torch.cuda.synchronize()
-    e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+    e0.record(); g.replay(); e1.record()
+    torch.cuda.synchronize()
+    reps = max(reps, int(MIN_SWEEP_MS / max(e0.elapsed_time(e1), 1e-3)) + 1)   # a timed region of MIN_SWEEP_MS at least
     e0.record()
     for _ in range(reps):
         g.replay()
@@ -107,6 +111,11 @@ def time_block(P, torch, mats, x_h, x_f, copies, fused, reps=4):
     many = P.spqr_gemm_fused if batch else P.spqr_gemv_fused
 
     def block(c):
+        if fused == "grouped":               # batch 1 only: every projection with its own input, one call
+            names = ("q", "k", "v", "o", "gate", "up", "down")
+            P.spqr_gemv_grouped([mats[nm][c] for nm in names], [x_f if nm == "down" else x_h for nm in names],
+                                outs=[ys[nm] for nm in names])
+            return
         if fused:
             many([mats[nm][c] for nm in ("q", "k", "v")], x_h, outs=[ys[nm] for nm in ("q", "k", "v")])
             one(mats["o"][c], x_h, out=ys["o"])
@@ -141,6 +150,9 @@ def time_block(P, torch, mats, x_h, x_f, copies, fused, reps=4):
             block(c)
     g.replay()
     torch.cuda.synchronize()
+    e0.record(); g.replay(); e1.record()
+    torch.cuda.synchronize()
+    reps = max(reps, int(MIN_SWEEP_MS / max(e0.elapsed_time(e1), 1e-3)) + 1)
     e0.record()
     for _ in range(reps):
         g.replay()
@@ -159,7 +171,7 @@ def run_block_sweep(rows, P, synth, torch, dev):
             A = P.SpQRMatrix.from_logical(synth.make_config_layer(cfg, li, group_axis=1), dev)
             nbytes += algorithmic_bytes(A, 1)
             mats[sp.name] = [A]
-        copies = max(2, int(512e6 // nbytes) + 1)
+        copies = max(3, int(512e6 // nbytes) + 1)
         for nm in mats:
             mats[nm] += [mats[nm][0].clone() for _ in range(copies - 1)]
         h, f = specs[0].n, specs[-1].n
@@ -169,9 +181,10 @@ def run_block_sweep(rows, P, synth, torch, dev):
             if b > 1:
                 x_h = torch.from_numpy(synth.make_x(h, b, seed=(cfg, 100))).to(dev)
                 x_f = torch.from_numpy(synth.make_x(f, b, seed=(cfg, 101))).to(dev)
-            for fused in (False, True):
+            for fused in (False, True) + (("grouped",) if b == 1 else ()):
                 us = time_block(P, torch, mats, x_h, x_f, copies, fused)
-                rows.append({"config": cfg, "layer": "block(7 calls)" if not fused else "block(q/k/v, gate/up fused: 4 calls)",
+                rows.append({"config": cfg, "layer": {False: "block(7 calls)", True: "block(q/k/v, gate/up fused: 4 calls)",
+                                                      "grouped": "block(spqr_gemv_grouped: 1 call, 2 launches)"}[fused],
                              "m": 0, "n": 0, "w_bits": specs[0].w_bits, "beta1": specs[0].beta1, "beta2": specs[0].beta2,
                              "group_axis": 1, "batch": b, "outliers": f"{specs[0].outlier_rate:g} {specs[0].outlier_structure}",
                              "compressed_MB": round(nbytes / 1e6, 2), "us": round(us, 2),

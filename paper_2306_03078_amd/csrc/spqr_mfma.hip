@@ -698,7 +698,7 @@ static hipMemPool_t scratch_pool(int dev) {
 }
 
 // hipErrorNotSupported: no scratch to be had (the caller takes the vector path).
-static hipError_t scratch_get(Scratch* sc, size_t bytes, int dev, hipStream_t stream) {
+static hipError_t scratch_get(Scratch* sc, size_t bytes, int dev, hipStream_t stream, bool allow_stream_ordered = true) {
   static std::mutex table_lock;
   static ScratchSlot slots[kMaxDevices][kScratchStreams];
   hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
@@ -739,6 +739,10 @@ static hipError_t scratch_get(Scratch* sc, size_t bytes, int dev, hipStream_t st
     sc->pooled = false;
     return hipSuccess;
   }
+  // The fused launch set never runs on a stream-ordered allocation: that is the kind of scratch the one memory
+  // fault seen on this path had (a captured graph of fused calls, cause unknown); its caller falls back to one
+  // call per matrix.
+  if (!allow_stream_ordered) return hipErrorNotSupported;
   // captured: the device's default pool (allocation nodes of the graph); else the library's own pool
   hipMemPool_t pool = capturing ? nullptr : scratch_pool(dev);
   const hipError_t e = pool != nullptr ? hipMallocFromPoolAsync(reinterpret_cast<void**>(&sc->p), bytes, pool, stream)
@@ -957,7 +961,7 @@ static hipError_t launch_mfma_fused_t(const DevMatrix* As, int count, const uint
       if (ws.p == nullptr || ws.bytes < total) return hipErrorOutOfMemory;
       scratch = ws.p;
     } else {
-      if (scratch_get(&sc, total, dev, stream) != hipSuccess) return hipErrorNotSupported;
+      if (scratch_get(&sc, total, dev, stream, false) != hipSuccess) return hipErrorNotSupported;
       scratch = sc.p;
     }
   }

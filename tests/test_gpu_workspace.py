@@ -240,3 +240,70 @@ def test_pack_check_on_two_streams_at_once(P):
     for t in threads:
         t.join()
     assert set(got[0]) == {0} and set(got[1]) == {-6}
+
+
+def test_captured_fused_batch_call_takes_the_per_matrix_path(P):
+    """spqr_gemm_fused on a capturing stream records one batch call per matrix (the fused launch set is kept out of
+    graphs, see the skipped test below); replays must give what eager per-matrix calls give, bit for bit."""
+    import torch
+    P.spqr_set_option(P.SPQR_OPT_BATCH_PATH, P.SPQR_BATCH_PATH_MATRIX)
+    fs = [make(4, 16, 16, 1, ntr, 140, rate=0.03, structure=st, seed=(56, ntr)) for ntr, st in ((6, "uniform"), (9, "rows8cols4"))]
+    As = [P.SpQRMatrix.from_logical(f) for f in fs]
+    X = dev(synth.make_x(fs[0].n, 16, seed=(57,)))
+    want = [P.spqr_gemm_smallbatch(A, X).clone() for A in As]
+    ws = torch.empty(P.spqr_workspace_bytes(As, 16), dtype=torch.uint8, device="cuda:0")
+    Ys = [torch.zeros_like(w) for w in want]
+    torch.cuda.synchronize()
+    types, ex, graph, st, hip = _graph_node_types(lambda s: P.spqr_gemm_fused_ws(As, X, ws, outs=Ys, stream=s))
+    assert all(t == 0 for t in types), types
+    for rep in range(3):
+        for Y in Ys:
+            Y.zero_()
+        torch.cuda.synchronize()
+        assert hip.hipGraphLaunch(ex, C.c_void_p(st.cuda_stream)) == 0
+        torch.cuda.synchronize()
+        for Y, w, f in zip(Ys, want, fs):
+            assert torch.equal(Y, w), rep
+    ref = [orc.matvec(f, X.cpu().numpy()) for f in fs]
+    for Y, r in zip(Ys, ref):
+        assert max(rel_l2(Y.cpu().numpy()[k], r[k]) for k in range(16)) <= REL_L2
+    assert hip.hipGraphExecDestroy(ex) == 0 and hip.hipGraphDestroy(graph) == 0
+
+
+@pytest.mark.skip(reason="GPU memory fault of unknown cause: a replay of a captured graph holding a whole decoder block "
+                         "with six weight copies (42 calls, 12 of them spqr_gemm_fused on the fused matrix-core launch "
+                         "set, scratch as allocation nodes) ended in a memory fault reported in the fused finishing "
+                         "kernel.  Checked on the CPU since: the fused kernels use no private segment and 1248 bytes of "
+                         "kernel arguments; every scratch offset of the launchers lies inside the exact-size workspace "
+                         "(the guarded-workspace tests above run the same kernels eagerly on exact-size scratch). No "
+                         "cause is shown, so the library keeps the fused launch set out of captured graphs and off "
+                         "stream-ordered scratch, and this case stays off the GPU.")
+def test_fused_launch_set_in_a_captured_decoder_block_graph(P):
+    """The case that faulted, kept for the day a cause is known: it needs the library's guard in launch_gemm_fused
+    (captured calls take the per-matrix path) lifted to mean anything."""
+    import torch
+    specs = synth.config_layers(2)
+    mats = {sp.name: P.SpQRMatrix.from_logical(synth.make_config_layer(2, i, group_axis=1)) for i, sp in enumerate(specs)}
+    copies = [{nm: (A if c == 0 else A.clone()) for nm, A in mats.items()} for c in range(6)]
+    x_h = dev(synth.make_x(specs[0].n, 16, seed=(58,)))
+    x_f = dev(synth.make_x(specs[-1].n, 16, seed=(59,)))
+    outs = {nm: torch.empty((16, A.m), dtype=torch.float32, device="cuda:0") for nm, A in mats.items()}
+
+    def block(c):
+        P.spqr_gemm_fused([copies[c][nm] for nm in ("q", "k", "v")], x_h, outs=[outs[nm] for nm in ("q", "k", "v")])
+        P.spqr_gemm_smallbatch(copies[c]["o"], x_h, out=outs["o"])
+        P.spqr_gemm_fused([copies[c][nm] for nm in ("gate", "up")], x_h, outs=[outs[nm] for nm in ("gate", "up")])
+        P.spqr_gemm_smallbatch(copies[c]["down"], x_f, out=outs["down"])
+
+    block(0)
+    torch.cuda.synchronize()
+    eager = {nm: t.clone() for nm, t in outs.items()}
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for c in range(6):
+            block(c)
+    for _ in range(3):
+        g.replay()
+        torch.cuda.synchronize()
+        for nm in outs:
+            assert torch.equal(outs[nm], eager[nm])
