@@ -54,8 +54,13 @@ static bool plan_launch(const Geometry& g, int nb, int max_waves, int slots, Lau
     // wavefront has several steps with the next tile in flight under the current one (-12 % on 8192x22016,
     // -22 % on 6656x17920 against eight one-or-two-step wavefronts), as long as that still leaves more
     // workgroups than compute units; else eight wavefronts on one strip.
-    if (nsteps <= 8) { P = nsteps < 4 ? nsteps : 4; R = 1; }
-    else if (g.ntr >= 400 && rmax >= 2) { P = 2; R = 2; }
+    // A launch with far more work than the chip holds at once (a large matrix, or several in one grid: four
+    // steps or more per wavefront slot) is bound by vector-ALU issue rather than by how fast it fills and drains
+    // the chip: there two wavefronts per strip, two steps each, save the per-wavefront overhead of every second
+    // step (-7 % at 4 steps per slot, -13 to -18 % at 6 to 9).
+    const double steps_per_slot = (double)g.ntr * nsteps / (16.0 * kCUs);
+    if (nsteps <= 8 && !(nsteps >= 4 && steps_per_slot >= 3.5 && rmax >= 2)) { P = nsteps < 4 ? nsteps : 4; R = 1; }
+    else if (nsteps <= 8 || (g.ntr >= 400 && rmax >= 2)) { P = 2; R = 2; }
     else { P = max_waves < 8 ? max_waves : 8; R = 1; }
   } else {
     // several activation vectors: arithmetic dominates, so what counts is wavefronts resident on the CU and an
