@@ -89,14 +89,31 @@ __device__ __forceinline__ void tile_fma(const TileRegs<W, TR, TC, AXIS>& t,
   ShiftedWords<W> sw;
 
   if constexpr (AXIS == 1) {
+    // The statistic codes are 3-bit pairs in the weight codes' format.  With 3-bit weights (and shared shifts) they
+    // are extracted the same way, in place, as K + code/8 with K by the pair's class: the scale's offset goes into the
+    // additive constant of its class (c2k), the zero's offset leaves with the class sums the weight codes need
+    // anyway, because pair PPR + p of the zero codes has the class of weight pair p in phase ZPH.
+    constexpr bool STATS_IN_PLACE = W == 3 && SHARED;
+    constexpr int ZPH = NPH == 1 ? 0 : 1;
+    static_assert(!STATS_IN_PLACE || (PPR % 16 == 0 && NPH == 1) || (PPR == 8 && NPH == 2), "class of a zero-code pair");
+    float c2k[3] = {c2, c2, c2};
+    ShiftedWords<3> sws, swz;
+    if constexpr (STATS_IN_PLACE) {
+      using C3 = CodeClass<3, true>;
+#pragma unroll
+      for (int c = 0; c < 3; ++c) c2k[c] = valid ? fmaf(-8.f * (C3::K(c) - 1.f), s_s, -s_s * z_s - 8.f * s_s) : 0.f;
+#pragma unroll
+      for (int j = 0; j < 3; ++j) { sws.s[j] = t.s[j] >> 9; swz.s[j] = t.s[3 * (PPR / 16) + j] >> 9; }
+    }
     float Zd[NB];
 #pragma unroll
     for (int bi = 0; bi < NB; ++bi) Zd[bi] = 0.f;
 #pragma unroll
     for (int p = 0; p < PPR; ++p) {
-      const half2_t sq = as_half2(pair_f16<3>(t.s, p, k3));
-      const half2_t zq = as_half2(pair_f16<3>(t.s, T::B2 / 2 + p, k3));
-      const float s0 = fmaf((float)sq.x, c1, c2), s1 = fmaf((float)sq.y, c1, c2);
+      const half2_t sq = as_half2(STATS_IN_PLACE ? pair_class_f16<3>(t.s, sws, p, k) : pair_f16<3>(t.s, p, k3));
+      const half2_t zq = as_half2(STATS_IN_PLACE ? pair_class_f16<3>(t.s, swz, T::B2 / 2 + p, k) : pair_f16<3>(t.s, T::B2 / 2 + p, k3));
+      const float c2p = STATS_IN_PLACE ? c2k[CodeClass<3, true>::of_pair(p)] : c2;
+      const float s0 = fmaf((float)sq.x, c1, c2p), s1 = fmaf((float)sq.y, c1, c2p);
 #pragma unroll
       for (int bi = 0; bi < NB; ++bi) {
         const half2_t u = as_half2(scaled_pair_f16(s0, s1, xp[bi][p]));
@@ -115,14 +132,18 @@ __device__ __forceinline__ void tile_fma(const TileRegs<W, TR, TC, AXIS>& t,
       float U = C[bi][0][0];
 #pragma unroll
       for (int c = 1; c < CC::N; ++c) U += C[bi][0][c];
-      const float zu = fmaf(e1, Zd[bi], e2 * U);
+      float E[NPH];
 #pragma unroll
       for (int h = 0; h < NPH; ++h) {
-        float E = CC::K(0) * C[bi][h][0];
+        E[h] = CC::K(0) * C[bi][h][0];
 #pragma unroll
-        for (int c = 1; c < CC::N; ++c) E = fmaf(CC::K(c), C[bi][h][c], E);
-        csum[bi][h] += fmaf(SCALE, E, zu);
+        for (int c = 1; c < CC::N; ++c) E[h] = fmaf(CC::K(c), C[bi][h][c], E[h]);
       }
+      // zero codes extracted in place carry their class offsets: sum_j (K - 1) u_j = E[ZPH] - U
+      const float zd = STATS_IN_PLACE ? Zd[bi] - E[ZPH] + U : Zd[bi];
+      const float zu = fmaf(e1, zd, e2 * U);
+#pragma unroll
+      for (int h = 0; h < NPH; ++h) csum[bi][h] += fmaf(SCALE, E[h], zu);
     }
 #pragma unroll
     for (int r = 0; r < TR; ++r) {
