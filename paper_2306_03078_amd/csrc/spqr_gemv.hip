@@ -137,15 +137,15 @@ static hipError_t launch_tile256(const DevMatrix& A, const uint16_t* x, void* y,
   const int nw = plan.P * plan.R;
   // what the kernel assumes of its launch: checked here, on the host
   if (plan.lds > (size_t)MAX_DYNAMIC || plan.cap < 64 * nw || nw > MAXW || plan.R * TR > RowsPerGroup<TR, NB>::MAX ||
-      plan.P > (A.g.ntc + 63) / 64 || plan.P < 1 || plan.R < 1)
+      plan.P > (A.g.ntc + 63) / 64 || plan.P < 1 || plan.R < 1 || plan.R > 8)
     return hipErrorInvalidValue;
   const dim3 grid((A.g.ntr + plan.R - 1) / plan.R), block(64 * nw);
   if (A.perm)
     hipLaunchKernelGGL((gemv_tile256_kernel<W, TR, TC, AXIS, true, NB>), grid, block, plan.lds, stream, A, x, y,
-                       y_dtype, plan.cap, plan.R);
+                       y_dtype, plan.cap, plan.R, plan.P);
   else
     hipLaunchKernelGGL((gemv_tile256_kernel<W, TR, TC, AXIS, false, NB>), grid, block, plan.lds, stream, A, x, y,
-                       y_dtype, plan.cap, plan.R);
+                       y_dtype, plan.cap, plan.R, plan.P);
   return hipGetLastError();
 }
 
@@ -208,7 +208,7 @@ static hipError_t launch_fused256(const DevMatrix* As, int count, const uint16_t
   if (!plan_launch(all, 1, MAXW, slots, &plan)) return hipErrorInvalidValue;
   const int nw = plan.P * plan.R;
   if (plan.lds > (size_t)MAX_DYNAMIC || plan.cap < 64 * nw || nw > MAXW || plan.R * TR > RowsPerGroup<TR, 1>::MAX ||
-      plan.P > (all.ntc + 63) / 64 || plan.P < 1 || plan.R < 1)
+      plan.P > (all.ntc + 63) / 64 || plan.P < 1 || plan.R < 1 || plan.R > 8)
     return hipErrorInvalidValue;
   FusedArgs F;
   F.count = count;
@@ -228,7 +228,7 @@ static hipError_t launch_fused256(const DevMatrix* As, int count, const uint16_t
     F.packed[i] = nullptr; F.row_ptr[i] = nullptr; F.col[i] = nullptr; F.val[i] = nullptr; F.x[i] = nullptr; F.y[i] = nullptr;
   }
   hipLaunchKernelGGL((gemv_tile256_fused_kernel<W, TR, TC, AXIS>), dim3(total), dim3(64 * nw), plan.lds, stream,
-                     F, y_dtype, plan.cap, plan.R);
+                     F, y_dtype, plan.cap, plan.R, plan.P);
   return hipGetLastError();
 }
 

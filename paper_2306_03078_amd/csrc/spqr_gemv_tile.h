@@ -269,8 +269,8 @@ template <int W, int NB> struct WavesPerGroup { static constexpr int MAX = (W ==
 // stride n), Y NB rows of m outputs (row stride m).  NB = 1 is the GEMV.
 // The workgroup owns the R consecutive strips from `first_strip` on (those that
 // exist): R * TR <= RowsPerGroup rows, one contiguous CSR range.  Its wavefronts
-// are dealt to the strips P = nwaves / R each (the host makes nwaves = R * P and
-// P <= steps of a strip); wavefront `part` of a strip takes the steps part,
+// are dealt to the strips P each (the host makes the workgroup R * P wavefronts,
+// R <= 8, and P <= steps of a strip); wavefront `part` of a strip takes the steps part,
 // part + P, ...  One staging of x and one epilogue serve all R strips, and a
 // wavefront that has several steps keeps the next tile's loads in flight under
 // the current tile's arithmetic.
@@ -279,7 +279,7 @@ template <int TR, int NB> struct RowsPerGroup { static constexpr int MAX = NB ==
 template <int W, int TR, int TC, int AXIS, bool PERM, int NB>
 __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint16_t* __restrict__ x,
                                                   void* __restrict__ y, int y_dtype, int chunk_cap,
-                                                  const int first_strip, const int R) {
+                                                  const int first_strip, const int R, const int P) {
   using T = TileRegs<W, TR, TC, AXIS>;
   static_assert(TR * TC == 256, "tile must hold 256 codes");
   static_assert((TC / 2) % 4 == 0, "x pairs are read as 16-byte LDS words");
@@ -310,8 +310,11 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
   const int nthreads = blockDim.x, nwaves = nthreads >> 6;
   const int l16 = tid & 15, g16 = tid >> 4, ngroups = nthreads >> 4;
   const int nsteps = (ntc + 63) >> 6;
-  const int P = nwaves / R;                  // wavefronts per strip
-  const int sw = wave / P, part = wave - sw * P;
+  // strip of this wavefront inside the workgroup, without a division: wave < R * P, R <= 8 (scalar compares)
+  int sw = 0;
+#pragma unroll
+  for (int k = 1; k < 8; ++k) sw += (wave >= k * P) ? 1 : 0;
+  const int part = wave - sw * P;
   const bool live = first_strip + sw < A.g.ntr;                  // wave-uniform; false: a strip behind the last one
   const int strip = min(first_strip + sw, A.g.ntr - 1);          // (the wavefront then adds zeros of the last strip)
   const int row0 = first_strip * TR;
@@ -627,9 +630,9 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
 template <int W, int TR, int TC, int AXIS, bool PERM, int NB>
 __global__ void __launch_bounds__((64 * WavesPerGroup<W, NB>::MAX))
 gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restrict__ y, int y_dtype,
-                    int chunk_cap, int strips_per_group) {
+                    int chunk_cap, int strips_per_group, int waves_per_strip) {
   gemv_tile256_body<W, TR, TC, AXIS, PERM, NB>(A, x, y, y_dtype, chunk_cap, blockIdx.x * strips_per_group,
-                                               strips_per_group);
+                                               strips_per_group, waves_per_strip);
 }
 
 // Several matrices of one format and one input width n (the q/k/v or gate/up projections of a
@@ -651,7 +654,7 @@ struct FusedArgs {
 
 template <int W, int TR, int TC, int AXIS>
 __global__ void __launch_bounds__((64 * WavesPerGroup<W, 1>::MAX))
-gemv_tile256_fused_kernel(FusedArgs F, int y_dtype, int chunk_cap, int strips_per_group) {
+gemv_tile256_fused_kernel(FusedArgs F, int y_dtype, int chunk_cap, int strips_per_group, int waves_per_strip) {
   int i = 0;
   while (i + 1 < F.count && (int)blockIdx.x >= F.first[i + 1]) ++i;   // workgroup-uniform, count <= SPQR_MAX_FUSED
   DevMatrix A;
@@ -660,7 +663,8 @@ gemv_tile256_fused_kernel(FusedArgs F, int y_dtype, int chunk_cap, int strips_pe
   A.packed = F.packed[i]; A.row_ptr = F.row_ptr[i]; A.col = F.col[i]; A.val = F.val[i];
   A.perm = nullptr; A.nnz = 0;
   gemv_tile256_body<W, TR, TC, AXIS, false, 1>(A, F.x[i], F.y[i], y_dtype, chunk_cap,
-                                               ((int)blockIdx.x - F.first[i]) * strips_per_group, strips_per_group);
+                                               ((int)blockIdx.x - F.first[i]) * strips_per_group, strips_per_group,
+                                               waves_per_strip);
 }
 
 }  // namespace spqr
