@@ -61,7 +61,7 @@ def algorithmic_bytes(A, batch=1):
 
 
 def time_layer(P, torch, A, X, copies, reps=6):
-    """Simple timing: graph of one launch per weight copy, replayed `reps` times (batches above 4: or streamed
+    """Simple timing: graph of one launch per weight copy, replayed `reps` times (batches of 4 and more: or streamed
     eagerly, whichever is faster)."""
     pool = [A] + [A.clone() for _ in range(copies - 1)]
     b = X.shape[0]
@@ -86,7 +86,7 @@ def time_layer(P, torch, A, X, copies, reps=6):
     e1.record()
     torch.cuda.synchronize()
     us = e0.elapsed_time(e1) * 1e3 / (reps * copies)
-    if b > 4:
+    if b >= 4:
         # The batch path's scratch is an allocation node per call in a graph (about 10 us each on this runtime) but a
         # buffer the library keeps per stream for eager calls: eager streaming as well, the better of the two counts.
         for _ in range(2):
@@ -249,7 +249,28 @@ def run_batch_probe(b, P, synth, torch, dev, axis):
         torch.cuda.empty_cache()
     return rows
 
-
+def run_batch_sweep(path, P, synth, torch, dev, axis):
+    """Batches 2..16 on the distinct layers of configurations 2, 3 and 4: the vector kernel's slices of 4 against the
+    matrix-core path (both forced through spqr_set_option) and the library's own choice; the table the rule in the
+    library's dispatch is read from.  Written as JSON to `path`."""
+    rows = []
+    for cfg in (2, 3, 4):
+        for li, sp in distinct_layers(synth, cfg):
+            A = P.SpQRMatrix.from_logical(synth.make_config_layer(cfg, li, group_axis=axis), dev)
+            copies = max(2, int(600e6 // A.compressed_bytes()) + 1)
+            for b in (2, 3, 4, 5, 6, 7, 8, 12, 16):
+                X = torch.from_numpy(synth.make_x(sp.n, b, seed=(cfg, li, b))).to(dev)
+                us = {}
+                for nm, opt in (("auto", P.SPQR_BATCH_PATH_AUTO), ("vector", P.SPQR_BATCH_PATH_VECTOR),
+                                ("matrix", P.SPQR_BATCH_PATH_MATRIX)):
+                    P.spqr_set_option(P.SPQR_OPT_BATCH_PATH, opt)
+                    us[nm] = round(time_layer(P, torch, A, X, copies), 2)
+                P.spqr_set_option(P.SPQR_OPT_BATCH_PATH, P.SPQR_BATCH_PATH_AUTO)
+                rows.append({"config": cfg, "layer": sp.name, "m": sp.m, "n": sp.n, "batch": b, **us})
+            del A
+            torch.cuda.empty_cache()
+    with open(path, "w") as fh:
+        json.dump(rows, fh, indent=1)
 
 
 def distinct_layers(synth, cfg):
@@ -300,6 +321,9 @@ def main():
     ap.add_argument("--batch-probe", type=int, default=0, metavar="B",
                     help="also time spqr_gemm_smallbatch at batch B on the distinct layers of configuration 3, on the "
                          "path the library picks and on the vector path; adds \"batch_probe\" to the line")
+    ap.add_argument("--batch-sweep", metavar="PATH", default=None,
+                    help="also time batches 2..16 on the distinct layers of configurations 2-4 on the vector path, the "
+                         "matrix-core path and the library's choice, and write the table as JSON to PATH")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run three 64 MiB device copies (a kernel of known traffic, for scaling rocprofv3 counters)")
     args = ap.parse_args()
@@ -472,6 +496,9 @@ def main():
 
     if args.sweep:
         run_sweep(args.sweep, P, synth, torch, dev)
+
+    if args.batch_sweep:
+        run_batch_sweep(args.batch_sweep, P, synth, torch, dev, args.group_axis)
 
     batch_probe = None
     if args.batch_probe:

@@ -889,9 +889,10 @@ static hipError_t launch_mfma_t(const DevMatrix& A, const uint16_t* X, int b, vo
 
 // Whether a batch of b > 4 vectors takes the matrix-core path.  It pays two more launches and the
 // transposition through LDS, the vector path re-reads the weights once per 4 vectors.  Measured on
-// MI355X with eager calls the matrix cores win from 8 vectors on for any layer and from 5 on for layers
-// of 30 M weights or more (4096^2 at b = 5 / 8 / 16: 15.4 / 15.7 / 18.0 us against 13.2 / 16.5 / 32.5;
-// 11008x4096: 26.6 / 26.9 / 28.2 against 31.6 / 45.3 / 89.4).  `alloc_nodes`: the call's scratch would be
+// MI355X with eager calls (a sweep of b = 2..16 over the layers of the 7B, 33B and 65B shapes, both paths forced)
+// the matrix cores win from 7 vectors on for any layer (4096^2 at b = 5 / 6 / 7 / 8: 19.9 / 20.0 / 20.0 / 20.1 us
+// against 17.4 / 19.6 / 25.2 / 23.8) and from 4 on for layers of 30 M weights or more (17920x6656 at b = 4:
+// about 52 us against 61; layers of 45 M weights are break-even at 4).  `alloc_nodes`: the call's scratch would be
 // allocation nodes of a graph under capture (library-owned scratch on a capturing stream), about 10 us more
 // per call: then from 13 vectors on for any layer, from 8 on for layers of 40 M weights and from 5 on for
 // layers of 100 M.  The option SPQR_OPT_BATCH_PATH forces one or the other wherever both apply (tests
@@ -902,7 +903,7 @@ bool mfma_wanted(const Geometry& g, int b, bool alloc_nodes) {
   if (forced == SPQR_BATCH_PATH_MATRIX) return true;
   const double weights = (double)g.m * (double)g.n;
   if (alloc_nodes) return b >= 13 || (b >= 8 && weights >= 40e6) || weights >= 100e6;
-  return b >= 8 || weights >= 30e6;
+  return b >= 7 || weights >= 30e6;
 }
 
 bool stream_is_capturing(hipStream_t stream) {
