@@ -15,8 +15,15 @@ def weight(fmt, i, j):
     else:
         gi, gj = i // b1, j          # group: row block i // beta1, column j
         ti, tj = i // b1, j // b2    # tile: beta2 columns of that row block
-    s_hat = float(fmt.s_s[ti, tj]) * (int(fmt.s_q[gi, gj]) - float(fmt.z_s[ti, tj]))
-    z_hat = float(fmt.s_z[ti, tj]) * (int(fmt.z_q[gi, gj]) - float(fmt.z_z[ti, tj]))
+    lay = getattr(fmt, "stat_layout", "bilevel")
+    if lay == "stats16":             # Sec. 5: statistics kept in 16 bit per group
+        s_hat, z_hat = float(fmt.s16[gi, gj]), float(fmt.z16[gi, gj])
+    else:
+        s_hat = float(fmt.s_s[ti, tj]) * (int(fmt.s_q[gi, gj]) - float(fmt.z_s[ti, tj]))
+        if lay == "round_zero":      # Sec. 5: the zero-point is the integer code
+            z_hat = float(int(fmt.z_q[gi, gj]))
+        else:
+            z_hat = float(fmt.s_z[ti, tj]) * (int(fmt.z_q[gi, gj]) - float(fmt.z_z[ti, tj]))
     return s_hat * (int(fmt.Q[i, j]) - z_hat)
 
 

@@ -19,9 +19,23 @@ inconsistent: s_s, z_s are the scale / zero of the quantiser fitted to the
 scales and s_z, z_z those of the quantiser fitted to the zeros, hence
 s_hat = s_s * (s_q - z_s) and z_hat = s_z * (z_q - z_z).
 
+Two variants of step 2 that the paper evaluates (Sec. 5, ablations), selected
+by the optional attribute `stat_layout`:
+
+  "round_zero"  the zero-point is a 3-bit integer: z_hat = z_q, used as it is;
+                scales keep their second level (s_s, z_s), zeros have none;
+  "stats16"     16-bit statistics: s_hat and z_hat are stored per group as
+                16-bit floats (s16, z16); no codes, no second level.
+
+Reading of "round zero": the text says the integer zero-point shrinks the
+footprint, which it only does if the zeros' second-level pair (s_z, z_z) is
+dropped, while the ablation table prints the unchanged 3.63 bits; the text is
+followed.  (A matrix of the other reading is an ordinary bilevel one with
+s_z = 1, z_z = 0, which decodes to the same values.)
+
 Functions take the logical arrays produced by `spqr_synth` (attribute access
 only: m, n, beta1, beta2, group_axis, Q, s_q, z_q, s_s, z_s, s_z, z_z,
-row_ptr, col_idx, val, optional perm).
+row_ptr, col_idx, val, optional perm, stat_layout, s16, z16).
 """
 from __future__ import annotations
 
@@ -49,9 +63,19 @@ def _to_groups(t, fmt):
     return np.repeat(np.repeat(t, rr, axis=0), cc, axis=1)
 
 
+def stat_layout(fmt):
+    return getattr(fmt, "stat_layout", "bilevel")
+
+
 def decode_stats(fmt):
-    """Step 2: first-level (s_hat, z_hat) per group, fp64 (Alg. 1 fit_statistics)."""
+    """Step 2: first-level (s_hat, z_hat) per group, fp64 (Alg. 1 fit_statistics;
+    Sec. 5 ablations for the two variants)."""
+    lay = stat_layout(fmt)
+    if lay == "stats16":
+        return fmt.s16.astype(np.float64), fmt.z16.astype(np.float64)
     s_hat = dequantize(fmt.s_q, _to_groups(fmt.s_s, fmt), _to_groups(fmt.z_s, fmt))
+    if lay == "round_zero":
+        return s_hat, fmt.z_q.astype(np.float64)
     z_hat = dequantize(fmt.z_q, _to_groups(fmt.s_z, fmt), _to_groups(fmt.z_z, fmt))
     return s_hat, z_hat
 
@@ -65,8 +89,13 @@ def decode_stats_f32(fmt):
     (one rounding); no fused multiply-add.
     """
     f = np.float32
+    lay = stat_layout(fmt)
+    if lay == "stats16":                    # a 16-bit float widens exactly
+        return fmt.s16.astype(f), fmt.z16.astype(f)
     s_hat = (_to_groups(fmt.s_s, fmt).astype(f)
              * (fmt.s_q.astype(f) - _to_groups(fmt.z_s, fmt).astype(f))).astype(f)
+    if lay == "round_zero":
+        return s_hat, fmt.z_q.astype(f)
     z_hat = (_to_groups(fmt.s_z, fmt).astype(f)
              * (fmt.z_q.astype(f) - _to_groups(fmt.z_z, fmt).astype(f))).astype(f)
     return s_hat, z_hat
@@ -164,3 +193,13 @@ def matvec_rows(fmt, X, rows):
 # --------------------------------------------------------------------------
 def average_bits(b_w, b_s, b_z, beta1, beta2, r_o=0.0):
     return b_w + (b_s + b_z) / beta1 + 64.0 / (beta1 * beta2) + 32.0 * r_o
+
+
+def average_bits_round_zero(b_w, b_s, b_z, beta1, beta2, r_o=0.0):
+    """Eq. 4 with one second-level pair per tile instead of two (Sec. 5, "round zero")."""
+    return b_w + (b_s + b_z) / beta1 + 32.0 / (beta1 * beta2) + 32.0 * r_o
+
+
+def average_bits_stats16(b_w, beta1, r_o=0.0):
+    """Eq. 4 for 16-bit first-level statistics and no second level (Sec. 5)."""
+    return b_w + 32.0 / beta1 + 32.0 * r_o

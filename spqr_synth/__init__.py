@@ -20,12 +20,21 @@ Geometry (notation of App. B of the paper: b_w, beta1, beta2):
   s_s, z_s, s_z, z_z  float16 [tile_rows_count, tile_cols_count]  one per tile
   row_ptr int32 [m+1] exclusive prefix; col_idx uint16 [nnz]; val float16 [nnz]
 
+Variants of the statistics (Sec. 5, ablations), selected by `stat_layout`:
+  "bilevel"     as above (the method's own format);
+  "round_zero"  the zero-point code z_q is the zero-point itself (an integer):
+                there is no s_z, z_z (both None);
+  "stats16"     first-level statistics kept in 16 bit: s16, z16 float16 arrays of
+                the shape of s_q, no codes and no second level (all None).
+
 Recipe (all draws in float64, rounded to float16 where the format stores
 float16; the rounded values are the ground truth for both sides):
   codes iid uniform over [0, 2^b_w); s_q, z_q iid uniform over [0, 8);
   s_s, s_z ~ U[0.01, 0.05), z_s, z_z ~ U[2, 5); outlier values ~ N(0, 0.2^2);
   x ~ N(0, 1).  Draw order: codes, s_q, z_q, s_s, z_s, s_z, z_z, outlier
   positions, outlier values.  x is drawn from its own stream.
+  "round_zero" makes the same draws and drops s_z, z_z.  "stats16" draws, in
+  place of the six statistic arrays, s16 ~ U[0.02, 0.2) and z16 ~ U[0, 2^b_w - 1).
 """
 from __future__ import annotations
 
@@ -62,6 +71,9 @@ class SpQRLogical:
     col_idx: np.ndarray
     val: np.ndarray
     perm: Optional[np.ndarray] = None   # optional input permutation (int32[n])
+    stat_layout: str = "bilevel"
+    s16: Optional[np.ndarray] = None    # "stats16" only
+    z16: Optional[np.ndarray] = None
 
     @property
     def nnz(self) -> int:
@@ -172,7 +184,7 @@ def outlier_positions(rng: np.random.Generator, m: int, n: int, rate: float,
 def make_matrix(m: int, n: int, *, w_bits: int = 3, beta1: int = 16, beta2: int = 16,
                 group_axis: int = 1, outlier_rate: float = 0.01,
                 outlier_structure: str = "uniform", seed=(0,),
-                s_bits: int = 3, z_bits: int = 3) -> SpQRLogical:
+                s_bits: int = 3, z_bits: int = 3, stat_layout: str = "bilevel") -> SpQRLogical:
     """Draw one logical SpQR matrix following the recipe in the module header."""
     tr, tc = tile_shape(beta1, beta2, group_axis)
     if m % tr or n % tc:
@@ -183,13 +195,24 @@ def make_matrix(m: int, n: int, *, w_bits: int = 3, beta1: int = 16, beta2: int 
     rng = _rng(*key)
     Q = rng.integers(0, 1 << w_bits, size=(m, n), dtype=np.uint8)
     gshape = (m, n // beta1) if group_axis == 0 else (m // beta1, n)
-    s_q = rng.integers(0, 1 << s_bits, size=gshape, dtype=np.uint8)
-    z_q = rng.integers(0, 1 << z_bits, size=gshape, dtype=np.uint8)
-    tshape = (m // tr, n // tc)
-    s_s = rng.uniform(0.01, 0.05, size=tshape).astype(np.float16)
-    z_s = rng.uniform(2.0, 5.0, size=tshape).astype(np.float16)
-    s_z = rng.uniform(0.01, 0.05, size=tshape).astype(np.float16)
-    z_z = rng.uniform(2.0, 5.0, size=tshape).astype(np.float16)
+    if stat_layout not in ("bilevel", "round_zero", "stats16"):
+        raise ValueError(f"unknown statistic layout {stat_layout!r}")
+    s16 = z16 = None
+    if stat_layout == "stats16":
+        s_q = z_q = s_s = z_s = s_z = z_z = None
+        s16 = rng.uniform(0.02, 0.2, size=gshape).astype(np.float16)
+        z16 = rng.uniform(0.0, (1 << w_bits) - 1, size=gshape).astype(np.float16)
+        s_bits = z_bits = 16
+    else:
+        s_q = rng.integers(0, 1 << s_bits, size=gshape, dtype=np.uint8)
+        z_q = rng.integers(0, 1 << z_bits, size=gshape, dtype=np.uint8)
+        tshape = (m // tr, n // tc)
+        s_s = rng.uniform(0.01, 0.05, size=tshape).astype(np.float16)
+        z_s = rng.uniform(2.0, 5.0, size=tshape).astype(np.float16)
+        s_z = rng.uniform(0.01, 0.05, size=tshape).astype(np.float16)
+        z_z = rng.uniform(2.0, 5.0, size=tshape).astype(np.float16)
+        if stat_layout == "round_zero":
+            s_z = z_z = None
     pos = outlier_positions(rng, m, n, outlier_rate, outlier_structure)
     rows = pos // n
     col_idx = (pos % n).astype(np.uint16)
@@ -198,7 +221,8 @@ def make_matrix(m: int, n: int, *, w_bits: int = 3, beta1: int = 16, beta2: int 
     row_ptr = np.cumsum(row_ptr).astype(np.int32)
     val = (0.2 * rng.standard_normal(pos.shape[0])).astype(np.float16)
     return SpQRLogical(m, n, w_bits, s_bits, z_bits, beta1, beta2, group_axis,
-                       Q, s_q, z_q, s_s, z_s, s_z, z_z, row_ptr, col_idx, val)
+                       Q, s_q, z_q, s_s, z_s, s_z, z_z, row_ptr, col_idx, val,
+                       stat_layout=stat_layout, s16=s16, z16=z16)
 
 
 def make_x(n: int, batch: int = 1, seed=(0,)) -> np.ndarray:

@@ -366,3 +366,142 @@ def test_identity_permutation_is_a_no_op():
     assert np.allclose(orc.matvec(f, X), ref, rtol=1e-14, atol=1e-14)   # a gathered copy may be summed in another order
     assert np.array_equal(np.array(brute.matvec(f, X[0])), np.array(brute.matvec(
         synth.SpQRLogical(**{**f.__dict__, "perm": None}), X[0])))
+
+
+# ---- statistic variants of the ablations (Sec. 5): integer zero-point, 16-bit statistics ----
+def _variant(m, n, layout, **kw):
+    kw.setdefault("seed", (13, m, n))
+    return synth.make_matrix(m, n, stat_layout=layout, **kw)
+
+
+def test_round_zero_hand_values():
+    # s_s = 0.5, z_s = 1, s_q = 3 -> s_hat = 1; zero-point = the code itself
+    for axis in (0, 1):
+        f = _variant(16, 16, "round_zero", group_axis=axis, outlier_rate=0.0)
+        assert f.s_z is None and f.z_z is None
+        f.Q[:] = 5; f.s_q[:] = 3; f.z_q[:] = 4
+        f.s_s[:] = 0.5; f.z_s[:] = 1.0
+        assert np.all(orc.reconstruct(f) == 1.0)          # 1 * (5 - 4)
+        f.z_q[:] = 7
+        assert np.all(orc.reconstruct(f) == -2.0)         # 1 * (5 - 7)
+        f.z_s[:] = 2.0
+        assert np.all(orc.reconstruct(f) == -1.0)         # 0.5 * (5 - 7)
+    # one group's zero code moves exactly that group (axis 1: rows [8r, 8r+8) of column j)
+    g = _variant(32, 32, "round_zero", beta1=8, beta2=16, group_axis=1, outlier_rate=0.0)
+    g.Q[:] = 1; g.s_q[:] = 1; g.z_q[:] = 0; g.s_s[:] = 1.0; g.z_s[:] = 0.0
+    g.z_q[2, 5] = 3
+    exp = np.ones((32, 32)); exp[16:24, 5] = -2.0
+    assert np.array_equal(orc.reconstruct(g), exp)
+
+
+@pytest.mark.parametrize("axis", [0, 1])
+def test_round_zero_is_bilevel_with_a_unit_zero_quantiser(axis):
+    # An integer zero-point is what the (already pinned) bilevel decode gives for s_z = 1, z_z = 0.
+    f = _variant(64, 96, "round_zero", w_bits=3, beta1=8, beta2=32, group_axis=axis, outlier_rate=0.03)
+    b = synth.make_matrix(64, 96, w_bits=3, beta1=8, beta2=32, group_axis=axis, outlier_rate=0.03,
+                          seed=(13, 64, 96))
+    assert np.array_equal(b.Q, f.Q) and np.array_equal(b.s_q, f.s_q) and np.array_equal(b.s_s, f.s_s)
+    b.s_z[:] = 1.0; b.z_z[:] = 0.0
+    assert np.array_equal(orc.reconstruct(f), orc.reconstruct(b))
+    x = synth.make_x(96, 2, seed=(5,))
+    assert np.array_equal(orc.matvec(f, x), orc.matvec(b, x))
+    # and it is not the bilevel decode of the drawn (s_z, z_z)
+    assert not np.allclose(orc.reconstruct(f), orc.reconstruct(
+        synth.make_matrix(64, 96, w_bits=3, beta1=8, beta2=32, group_axis=axis, outlier_rate=0.03, seed=(13, 64, 96))))
+
+
+def test_stats16_hand_values():
+    for axis in (0, 1):
+        f = _variant(16, 16, "stats16", group_axis=axis, outlier_rate=0.0)
+        assert f.s_q is None and f.s_s is None and f.s16.dtype == np.float16
+        f.Q[:] = 5; f.s16[:] = 0.5; f.z16[:] = 1.5
+        assert np.all(orc.reconstruct(f) == 1.75)         # 0.5 * (5 - 1.5)
+    # group indexing: axis 0, group = row i, columns [8c, 8c+8)
+    f = _variant(32, 32, "stats16", beta1=8, beta2=16, group_axis=0, outlier_rate=0.0)
+    f.Q[:] = 2; f.s16[:] = 1.0; f.z16[:] = 0.0
+    f.s16[5, 2] = 3.0
+    exp = np.full((32, 32), 2.0); exp[5, 16:24] = 6.0
+    assert np.array_equal(orc.reconstruct(f), exp)
+    f.s16[5, 2] = 1.0; f.z16[30, 0] = 0.5
+    exp = np.full((32, 32), 2.0); exp[30, 0:8] = 1.5
+    assert np.array_equal(orc.reconstruct(f), exp)
+    # axis 1, group = rows [8r, 8r+8) of column j
+    g = _variant(32, 32, "stats16", beta1=8, beta2=16, group_axis=1, outlier_rate=0.0)
+    g.Q[:] = 2; g.s16[:] = 1.0; g.z16[:] = 0.0
+    g.z16[1, 31] = 4.0
+    exp = np.full((32, 32), 2.0); exp[8:16, 31] = -2.0
+    assert np.array_equal(orc.reconstruct(g), exp)
+
+
+@pytest.mark.parametrize("axis", [0, 1])
+def test_stats16_equals_bilevel_whose_statistics_are_16_bit_numbers(axis):
+    # A bilevel matrix with s_s = 0.5, z_s = 1, s_z = 0.25, z_z = 2 decodes to statistics that are exact 16-bit
+    # floats; storing those directly must give the same matrix.
+    b = synth.make_matrix(48, 64, w_bits=4, beta1=16, beta2=16, group_axis=axis, outlier_rate=0.02, seed=(17,))
+    b.s_s[:] = 0.5; b.z_s[:] = 1.0; b.s_z[:] = 0.25; b.z_z[:] = 2.0
+    f = _variant(48, 64, "stats16", w_bits=4, beta1=16, beta2=16, group_axis=axis, outlier_rate=0.02, seed=(17,))
+    f.Q = b.Q; f.row_ptr, f.col_idx, f.val = b.row_ptr, b.col_idx, b.val
+    f.s16 = (0.5 * (b.s_q.astype(np.float64) - 1.0)).astype(np.float16)
+    f.z16 = (0.25 * (b.z_q.astype(np.float64) - 2.0)).astype(np.float16)
+    assert np.array_equal(orc.reconstruct(f), orc.reconstruct(b))
+
+
+@pytest.mark.parametrize("layout,w_bits,beta1,beta2,axis", [
+    ("round_zero", 3, 16, 16, 0), ("round_zero", 3, 8, 32, 1), ("round_zero", 4, 16, 16, 1),
+    ("stats16", 3, 16, 16, 0), ("stats16", 3, 48, 16, 1), ("stats16", 4, 8, 32, 0),
+])
+def test_variants_vectorised_equals_brute_force(layout, w_bits, beta1, beta2, axis):
+    tr, tc = synth.tile_shape(beta1, beta2, axis)
+    m, n = 2 * tr, 3 * tc
+    f = synth.make_matrix(m, n, w_bits=w_bits, beta1=beta1, beta2=beta2, group_axis=axis, outlier_rate=0.05,
+                          seed=(19, w_bits, beta1, beta2, axis), stat_layout=layout)
+    assert np.allclose(orc.reconstruct(f), np.array(brute.reconstruct(f)), rtol=1e-14, atol=1e-14)
+    x = synth.make_x(n, 1, seed=(3,))[0]
+    yb = np.array(brute.matvec(f, x))
+    assert np.allclose(orc.matvec(f, x)[0], yb, rtol=1e-12, atol=1e-12)
+    rows = np.array([0, m // 2, m - 1])
+    assert np.allclose(orc.matvec_rows(f, x, rows)[0], yb[rows], rtol=1e-12, atol=1e-12)
+    s32, z32 = orc.decode_stats_f32(f)
+    s64, z64 = orc.decode_stats(f)
+    assert np.allclose(s32, s64, rtol=1e-6) and np.allclose(z32, z64, rtol=1e-6, atol=1e-7)
+
+
+def test_stats16_inverts_the_min_max_quantiser():
+    # Alg. 1 without the second level: fit (s, z) per group of 16 weights, keep them as 16-bit floats,
+    # quantise with them; the decode is within half a step of every weight.
+    rng = np.random.default_rng(23)
+    f = _variant(16, 64, "stats16", w_bits=3, beta1=16, beta2=16, group_axis=0, outlier_rate=0.0)
+    W = rng.standard_normal((16, 64))
+    for i in range(16):
+        for c in range(4):
+            grp = W[i, 16 * c:16 * c + 16]
+            s, z = enc.fit_quantizer(grp, 3)
+            f.s16[i, c] = s; f.z16[i, c] = z
+            s16, z16 = float(f.s16[i, c]), float(f.z16[i, c])
+            f.Q[i, 16 * c:16 * c + 16] = np.clip(enc.quantize(grp, s16, z16), 0, 7)
+    err = np.abs(orc.reconstruct(f) - W)
+    step = np.repeat(f.s16.astype(np.float64), 16, axis=1)
+    # codes clipped at the range's ends can be off by the rounding of (s, z) to 16 bit: a little over half a step
+    assert np.all(err <= 0.5 * step * 1.02 + 1e-3)
+    assert np.max(err) > 0.2 * step.min()
+
+
+def test_average_bits_of_the_variants_printed_values():
+    path = os.path.join(os.path.dirname(__file__), "golden", "avg_bits_ablation.txt")
+    seen = 0
+    for line in open(path):
+        if line.startswith("#") or not line.strip():
+            continue
+        lay, b_w, b1, b2, printed, dec = line.split()
+        b_w, b1, b2, printed, dec = int(b_w), int(b1), int(b2), float(printed), int(dec)
+        if lay == "stats16":
+            v = orc.average_bits_stats16(b_w, b1)
+        else:
+            v = orc.average_bits(b_w, 3, 3, b1, b2)
+        assert abs(v - printed) <= 0.5 * 10 ** -dec + 1e-12, (lay, v, printed)
+        seen += 1
+    assert seen == 3
+    # one second-level pair less per tile of beta1*beta2 weights
+    assert orc.average_bits(3, 3, 3, 16, 16) - orc.average_bits_round_zero(3, 3, 3, 16, 16) == 32.0 / 256.0
+    assert orc.average_bits_round_zero(3, 3, 3, 16, 16) == 3.5
+    assert orc.average_bits_stats16(3, 16) == 5.0
