@@ -72,7 +72,14 @@ typedef enum spqr_status {
   SPQR_ERR_WORKSPACE = -11  /* the workspace is smaller than spqr_workspace_bytes() */
 } spqr_status;
 
-#define SPQR_LAYOUT_V1   1
+/* Values of spqr_matrix_t::layout_version: how a tile's statistics are stored.
+ * 1 is the method's own bilevel format (Sec. 4.2); 2 and 3 are the two variants
+ * the ablations of Sec. 5 evaluate. */
+#define SPQR_LAYOUT_V1          1  /* 3-bit (s_q, z_q) per group, (s_s, z_s, s_z, z_z) per tile   */
+#define SPQR_LAYOUT_ROUND_ZERO  2  /* "round zero": the 3-bit zero code IS the zero-point,
+                                      z_hat = z_q; the tile keeps (s_s, z_s) only                */
+#define SPQR_LAYOUT_STATS16     3  /* "16-bit statistics": binary16 (s_hat, z_hat) per group,
+                                      nothing per tile; s_bits = z_bits = 16                     */
 #define SPQR_MAX_BATCH  256
 
 /* Output element types of y / Y. */
@@ -82,12 +89,13 @@ typedef enum spqr_status {
 /*
  * One matrix in SpQR form (Sec. 4.2; hyper-parameter names of App. B).
  *
- * Supported: w_bits in {3, 4}; s_bits = z_bits = 3; beta2 a multiple of 16;
- * beta1 * beta2 * w_bits a multiple of 128; tile width even; n <= 65536;
- * m, n multiples of the tile.  Everything else returns SPQR_ERR_PARAM/SHAPE.
+ * Supported: w_bits in {3, 4}; s_bits = z_bits = 3 (16 for
+ * SPQR_LAYOUT_STATS16); beta2 a multiple of 16; beta1 * beta2 * w_bits a
+ * multiple of 128; tile width even; n <= 65536; m, n multiples of the tile.
+ * Everything else returns SPQR_ERR_PARAM/SHAPE.
  *
- * `packed` holds parts (1) and (2) in layout SPQR_LAYOUT_V1, written by
- * spqr_pack_host():
+ * `packed` holds parts (1) and (2), written by spqr_pack_host() /
+ * spqr_pack_host_layout().  Layout SPQR_LAYOUT_V1:
  *   - the matrix is cut into tiles (tile_rows x tile_cols as above), ordered
  *     row-major over the tile grid; every run of up to 64 consecutive tiles of
  *     one tile-row forms a block of L <= 64 tiles starting at byte
@@ -110,6 +118,17 @@ typedef enum spqr_status {
  *     z_q[0..beta2) (group index along the tile), are stored as 3-bit pairs
  *     in the same way; the last two statistic dwords are s_s | z_s<<16 and
  *     s_z | z_z<<16 (binary16 bit patterns).
+ * The other two layouts differ in the statistic dwords only:
+ *   - SPQR_LAYOUT_ROUND_ZERO: SD = 3*beta2/16 + 1: the same code dwords, then
+ *     s_s | z_s<<16; tile_bytes = (b_w + 6/beta1 + 32/(beta1*beta2)) * beta1*beta2/8;
+ *   - SPQR_LAYOUT_STATS16: SD = beta2: dword g is s_hat_g | z_hat_g<<16 (binary16
+ *     bit patterns) of group g of the tile; tile_bytes = (b_w + 32/beta1) * beta1*beta2/8
+ *     (beta2 only shapes the tile).
+ * Decode: SPQR_LAYOUT_ROUND_ZERO  s_hat = s_s * (s_q - z_s), z_hat = z_q;
+ *         SPQR_LAYOUT_STATS16     s_hat, z_hat as stored.
+ * Tiles of 256 codes have tuned kernels (batch 1 to 4 vectors at a time); the
+ * matrix-core batch path exists for SPQR_LAYOUT_V1 only, the other layouts run
+ * larger batches as slices of up to 4 vectors.
  *
  * Outliers: row_ptr[m+1] is the exclusive prefix of per-row counts
  * (row_ptr[0] = 0, row_ptr[m] = nnz); col_idx / out_val are sorted by row then
@@ -148,6 +167,11 @@ int64_t spqr_packed_bytes(int32_t m, int32_t n, int32_t w_bits, int32_t s_bits,
                           int32_t z_bits, int32_t beta1, int32_t beta2,
                           int32_t group_axis);
 
+/* The same for any layout_version (s_bits = z_bits = 16 for SPQR_LAYOUT_STATS16). */
+int64_t spqr_packed_bytes_layout(int32_t layout_version, int32_t m, int32_t n, int32_t w_bits,
+                                 int32_t s_bits, int32_t z_bits, int32_t beta1, int32_t beta2,
+                                 int32_t group_axis);
+
 /* Pack logical HOST arrays into layout V1 (HOST buffer `packed_out` of
  * spqr_packed_bytes() bytes, fully overwritten).
  *   Q      uint8 [m][n], codes < 2^w_bits
@@ -161,9 +185,22 @@ int spqr_pack_host(int32_t m, int32_t n, int32_t w_bits, int32_t s_bits, int32_t
                    const uint16_t* s_z, const uint16_t* z_z,
                    void* packed_out, int64_t packed_bytes);
 
+/* The same for any layout_version (Sec. 5, ablations "round zero" and "16-bit
+ * statistics"; SPQR_LAYOUT_V1 gives spqr_pack_host).  s_first / z_first, one
+ * entry per first-level group in the shapes above: uint8 codes < 8 for layouts
+ * 1 and 2, binary16 bit patterns (uint16) of s_hat / z_hat for layout 3.  The
+ * per-tile arrays a layout does not store are ignored and may be NULL (s_z, z_z
+ * for layout 2; all four for layout 3). */
+int spqr_pack_host_layout(int32_t layout_version, int32_t m, int32_t n, int32_t w_bits,
+                          int32_t s_bits, int32_t z_bits, int32_t beta1, int32_t beta2,
+                          int32_t group_axis, const uint8_t* Q, const void* s_first,
+                          const void* z_first, const uint16_t* s_s, const uint16_t* z_s,
+                          const uint16_t* s_z, const uint16_t* z_z, void* packed_out,
+                          int64_t packed_bytes);
+
 const char* spqr_strerror(int status);
 
-/* Library / layout version: (major<<16) | layout version. */
+/* Library / layout version: (major<<16) | highest layout version understood. */
 int32_t spqr_version(void);
 
 /* ---- device entry points ------------------------------------------------- */

@@ -1,4 +1,4 @@
-"""Independent reader of packed layout V1 (test infrastructure).
+"""Independent reader of the packed layouts (test infrastructure).
 
 Written from the normative layout text in include/spqr.h, not from the
 library's packer: it turns a packed byte buffer back into the logical arrays so
@@ -31,20 +31,23 @@ def _pairs_from_dwords(dw, bits, npairs):
     return lo, hi
 
 
-def read_packed(buf, m, n, w_bits, beta1, beta2, group_axis):
-    """Returns dict(Q, s_q, z_q, s_s, z_s, s_z, z_z) from a packed uint8 buffer."""
+def read_packed(buf, m, n, w_bits, beta1, beta2, group_axis, layout_version=1):
+    """Returns the logical arrays held by a packed uint8 buffer:
+    layout 1: Q, s_q, z_q, s_s, z_s, s_z, z_z; layout 2: the same without s_z, z_z;
+    layout 3: Q, s16, z16."""
     buf = np.ascontiguousarray(buf, dtype=np.uint8)
     tr_, tc_ = (beta2, beta1) if group_axis == 0 else (beta1, beta2)
     ntr, ntc = m // tr_, n // tc_
     kw = tr_ * tc_ * w_bits // 128
-    sd = 3 * beta2 // 16 + 2
+    nc = 3 * beta2 // 16                      # dwords of 3-bit statistic codes
+    sd = {1: nc + 2, 2: nc + 1, 3: beta2}[layout_version]
     swf, sr = sd // 4, sd % 4
     tile_bytes = 16 * kw + 4 * sd
     assert buf.size == ntr * ntc * tile_bytes
     Q = np.zeros((m, n), dtype=np.uint8)
     gshape = (m, n // beta1) if group_axis == 0 else (m // beta1, n)
-    s_q = np.zeros(gshape, dtype=np.uint8)
-    z_q = np.zeros(gshape, dtype=np.uint8)
+    s_q = np.zeros(gshape, dtype=np.uint16)   # 3-bit codes, or binary16 patterns for layout 3
+    z_q = np.zeros(gshape, dtype=np.uint16)
     st2 = {k: np.zeros((ntr, ntc), dtype=np.uint16) for k in ("s_s", "z_s", "s_z", "z_z")}
     ppr = tc_ // 2
     for tr in range(ntr):
@@ -64,21 +67,29 @@ def read_packed(buf, m, n, w_bits, beta1, beta2, group_axis):
             tile[:, :, 1::2] = hi.reshape(L, tr_, ppr)
             Q[tr * tr_:(tr + 1) * tr_, t0 * tc_:(t0 + L) * tc_] = \
                 tile.transpose(1, 0, 2).reshape(tr_, L * tc_)
-            slo, shi = _pairs_from_dwords(stat, 3, beta2)
-            seq = np.empty((L, 2 * beta2), dtype=np.uint8)
-            seq[:, 0::2] = slo
-            seq[:, 1::2] = shi
-            sq, zq = seq[:, :beta2], seq[:, beta2:]
+            if layout_version == 3:  # dword g of the tile: s | z << 16
+                sq, zq = stat & 0xFFFF, stat >> 16
+            else:
+                slo, shi = _pairs_from_dwords(stat, 3, beta2)
+                seq = np.empty((L, 2 * beta2), dtype=np.uint8)
+                seq[:, 0::2] = slo
+                seq[:, 1::2] = shi
+                sq, zq = seq[:, :beta2], seq[:, beta2:]
             if group_axis == 0:      # groups are the tile's rows: group grid [m, n/beta1]
                 s_q[tr * tr_:(tr + 1) * tr_, t0:t0 + L] = sq.T
                 z_q[tr * tr_:(tr + 1) * tr_, t0:t0 + L] = zq.T
             else:                    # groups are the tile's columns: group grid [m/beta1, n]
                 s_q[tr, t0 * tc_:(t0 + L) * tc_] = sq.reshape(-1)
                 z_q[tr, t0 * tc_:(t0 + L) * tc_] = zq.reshape(-1)
-            st2["s_s"][tr, t0:t0 + L] = stat[:, sd - 2] & 0xFFFF
-            st2["z_s"][tr, t0:t0 + L] = stat[:, sd - 2] >> 16
-            st2["s_z"][tr, t0:t0 + L] = stat[:, sd - 1] & 0xFFFF
-            st2["z_z"][tr, t0:t0 + L] = stat[:, sd - 1] >> 16
-    out = dict(Q=Q, s_q=s_q, z_q=z_q)
-    out.update({k: v.view(np.float16) for k, v in st2.items()})
+            if layout_version != 3:
+                st2["s_s"][tr, t0:t0 + L] = stat[:, nc] & 0xFFFF
+                st2["z_s"][tr, t0:t0 + L] = stat[:, nc] >> 16
+            if layout_version == 1:
+                st2["s_z"][tr, t0:t0 + L] = stat[:, nc + 1] & 0xFFFF
+                st2["z_z"][tr, t0:t0 + L] = stat[:, nc + 1] >> 16
+    if layout_version == 3:
+        return dict(Q=Q, s16=s_q.view(np.float16), z16=z_q.view(np.float16))
+    out = dict(Q=Q, s_q=s_q.astype(np.uint8), z_q=z_q.astype(np.uint8))
+    keep = ("s_s", "z_s", "s_z", "z_z") if layout_version == 1 else ("s_s", "z_s")
+    out.update({k: st2[k].view(np.float16) for k in keep})
     return out

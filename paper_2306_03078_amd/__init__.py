@@ -12,5 +12,5 @@ from .binding import (  # noqa: F401
     SPQR_BATCH_PATH_AUTO, SPQR_BATCH_PATH_VECTOR, SPQR_BATCH_PATH_MATRIX, SPQR_ERR_WORKSPACE, SPQR_STATIC_SCRATCH_BYTES,
     SPQR_F16, SPQR_F32, SPQR_CHECK_CSR, SPQR_CHECK_NONFINITE, SPQR_CHECK_PERM,
     SPQR_OUT_CODES_U8, SPQR_OUT_DENSE_F16, SPQR_OUT_DENSE_F32, SPQR_OUT_SCALE_F32,
-    SPQR_OUT_WITH_OUTLIERS, SPQR_OUT_ZERO_F32,
+    SPQR_OUT_WITH_OUTLIERS, SPQR_OUT_ZERO_F32, SPQR_LAYOUT_V1, SPQR_LAYOUT_ROUND_ZERO, SPQR_LAYOUT_STATS16,
 )

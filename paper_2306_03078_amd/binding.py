@@ -19,7 +19,8 @@ SPQR_F32, SPQR_F16 = 0, 1
 SPQR_CHECK_CSR, SPQR_CHECK_NONFINITE, SPQR_CHECK_PERM = 1, 2, 4
 SPQR_OUT_CODES_U8, SPQR_OUT_SCALE_F32, SPQR_OUT_ZERO_F32 = 0, 1, 2
 SPQR_OUT_DENSE_F32, SPQR_OUT_DENSE_F16, SPQR_OUT_WITH_OUTLIERS = 3, 4, 0x100
-SPQR_LAYOUT_V1 = 1
+SPQR_LAYOUT_V1, SPQR_LAYOUT_ROUND_ZERO, SPQR_LAYOUT_STATS16 = 1, 2, 3
+_LAYOUT_OF = {"bilevel": SPQR_LAYOUT_V1, "round_zero": SPQR_LAYOUT_ROUND_ZERO, "stats16": SPQR_LAYOUT_STATS16}
 SPQR_OPT_BATCH_PATH, SPQR_OPT_FORCE_GENERIC, SPQR_OPT_BATCH_STEPS = 0, 1, 2
 SPQR_BATCH_PATH_AUTO, SPQR_BATCH_PATH_VECTOR, SPQR_BATCH_PATH_MATRIX = 0, 1, 2
 SPQR_ERR_WORKSPACE = -11
@@ -67,6 +68,10 @@ def load_library():
     lib.spqr_packed_bytes.argtypes = [i32] * 8
     lib.spqr_pack_host.restype = C.c_int
     lib.spqr_pack_host.argtypes = [i32] * 8 + [vp] * 8 + [i64]
+    lib.spqr_packed_bytes_layout.restype = i64
+    lib.spqr_packed_bytes_layout.argtypes = [i32] * 9
+    lib.spqr_pack_host_layout.restype = C.c_int
+    lib.spqr_pack_host_layout.argtypes = [i32] * 9 + [vp] * 8 + [i64]
     lib.spqr_strerror.restype = C.c_char_p
     lib.spqr_strerror.argtypes = [C.c_int]
     lib.spqr_version.restype = i32
@@ -105,31 +110,47 @@ def spqr_strerror(status: int) -> str:
     return load_library().spqr_strerror(int(status)).decode()
 
 
-def packed_bytes(m, n, w_bits, s_bits, z_bits, beta1, beta2, group_axis) -> int:
-    r = load_library().spqr_packed_bytes(m, n, w_bits, s_bits, z_bits, beta1, beta2, group_axis)
+def packed_bytes(m, n, w_bits, s_bits, z_bits, beta1, beta2, group_axis, layout_version=SPQR_LAYOUT_V1) -> int:
+    lib = load_library()
+    if layout_version == SPQR_LAYOUT_V1:
+        r = lib.spqr_packed_bytes(m, n, w_bits, s_bits, z_bits, beta1, beta2, group_axis)
+    else:
+        r = lib.spqr_packed_bytes_layout(layout_version, m, n, w_bits, s_bits, z_bits, beta1, beta2, group_axis)
     if r < 0:
         raise SpQRError(int(r), "spqr_packed_bytes")
     return int(r)
 
 
-def _np_ptr(a: np.ndarray) -> int:
-    return a.ctypes.data
+def _np_ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data
+
+
+def layout_version_of(fmt) -> int:
+    return _LAYOUT_OF[getattr(fmt, "stat_layout", "bilevel")]
 
 
 def pack_host(fmt) -> np.ndarray:
     """Logical arrays (spqr_synth.SpQRLogical-like) -> packed uint8 host buffer."""
     lib = load_library()
+    lv = layout_version_of(fmt)
     nbytes = packed_bytes(fmt.m, fmt.n, fmt.w_bits, fmt.s_bits, fmt.z_bits, fmt.beta1, fmt.beta2,
-                          fmt.group_axis)
+                          fmt.group_axis, lv)
     out = np.empty(nbytes, dtype=np.uint8)
     Q = np.ascontiguousarray(fmt.Q, dtype=np.uint8)
-    s_q = np.ascontiguousarray(fmt.s_q, dtype=np.uint8)
-    z_q = np.ascontiguousarray(fmt.z_q, dtype=np.uint8)
-    st = [np.ascontiguousarray(a, dtype=np.float16).view(np.uint16)
+    if lv == SPQR_LAYOUT_STATS16:
+        first = [np.ascontiguousarray(a, dtype=np.float16).view(np.uint16) for a in (fmt.s16, fmt.z16)]
+    else:
+        first = [np.ascontiguousarray(a, dtype=np.uint8) for a in (fmt.s_q, fmt.z_q)]
+    st = [None if a is None else np.ascontiguousarray(a, dtype=np.float16).view(np.uint16)
           for a in (fmt.s_s, fmt.z_s, fmt.s_z, fmt.z_z)]
-    rc = lib.spqr_pack_host(fmt.m, fmt.n, fmt.w_bits, fmt.s_bits, fmt.z_bits, fmt.beta1, fmt.beta2,
-                            fmt.group_axis, _np_ptr(Q), _np_ptr(s_q), _np_ptr(z_q),
-                            *[_np_ptr(a) for a in st], _np_ptr(out), nbytes)
+    if lv == SPQR_LAYOUT_V1:
+        rc = lib.spqr_pack_host(fmt.m, fmt.n, fmt.w_bits, fmt.s_bits, fmt.z_bits, fmt.beta1, fmt.beta2,
+                                fmt.group_axis, _np_ptr(Q), _np_ptr(first[0]), _np_ptr(first[1]),
+                                *[_np_ptr(a) for a in st], _np_ptr(out), nbytes)
+    else:
+        rc = lib.spqr_pack_host_layout(lv, fmt.m, fmt.n, fmt.w_bits, fmt.s_bits, fmt.z_bits, fmt.beta1,
+                                       fmt.beta2, fmt.group_axis, _np_ptr(Q), _np_ptr(first[0]),
+                                       _np_ptr(first[1]), *[_np_ptr(a) for a in st], _np_ptr(out), nbytes)
     if rc != 0:
         raise SpQRError(rc, "spqr_pack_host")
     return out
@@ -146,7 +167,7 @@ class SpQRMatrix:
     descriptor points into them."""
 
     def __init__(self, m, n, w_bits, beta1, beta2, group_axis, packed, row_ptr, col_idx, val,
-                 perm=None, s_bits=3, z_bits=3):
+                 perm=None, s_bits=3, z_bits=3, layout_version=SPQR_LAYOUT_V1):
         self.m, self.n = int(m), int(n)
         self.w_bits, self.s_bits, self.z_bits = int(w_bits), int(s_bits), int(z_bits)
         self.beta1, self.beta2, self.group_axis = int(beta1), int(beta2), int(group_axis)
@@ -156,7 +177,8 @@ class SpQRMatrix:
         d.m, d.n = self.m, self.n
         d.w_bits, d.s_bits, d.z_bits = self.w_bits, self.s_bits, self.z_bits
         d.beta1, d.beta2, d.group_axis = self.beta1, self.beta2, self.group_axis
-        d.layout_version, d.reserved = SPQR_LAYOUT_V1, 0
+        self.layout_version = int(layout_version)
+        d.layout_version, d.reserved = self.layout_version, 0
         d.packed, d.packed_bytes = packed.data_ptr(), packed.numel()
         d.row_ptr = row_ptr.data_ptr()
         d.col_idx = col_idx.data_ptr() if self.nnz else None
@@ -184,14 +206,14 @@ class SpQRMatrix:
         if getattr(fmt, "perm", None) is not None:
             perm = torch.from_numpy(np.ascontiguousarray(fmt.perm, dtype=np.int32)).to(device)
         return cls(fmt.m, fmt.n, fmt.w_bits, fmt.beta1, fmt.beta2, fmt.group_axis, packed, row_ptr,
-                   col, val, perm, fmt.s_bits, fmt.z_bits)
+                   col, val, perm, fmt.s_bits, fmt.z_bits, layout_version_of(fmt))
 
     def clone(self):
         """A second copy of all device buffers (distinct addresses)."""
         return SpQRMatrix(self.m, self.n, self.w_bits, self.beta1, self.beta2, self.group_axis,
                           self.packed.clone(), self.row_ptr.clone(), self.col_idx.clone(),
                           self.val.clone(), None if self.perm is None else self.perm.clone(),
-                          self.s_bits, self.z_bits)
+                          self.s_bits, self.z_bits, self.layout_version)
 
 
 def _check(rc: int, where: str):

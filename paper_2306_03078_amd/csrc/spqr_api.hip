@@ -12,8 +12,8 @@ namespace {
 // O(1) checks shared by every device entry point.
 int to_device_matrix(const spqr_matrix_t* A, spqr::DevMatrix* D) {
   if (!A) return SPQR_ERR_NULL;
-  if (A->layout_version != SPQR_LAYOUT_V1 || A->reserved != 0) return SPQR_ERR_PARAM;
-  int rc = spqr::make_geometry(A->m, A->n, A->w_bits, A->s_bits, A->z_bits, A->beta1, A->beta2,
+  if (A->reserved != 0) return SPQR_ERR_PARAM;
+  int rc = spqr::make_geometry(A->layout_version, A->m, A->n, A->w_bits, A->s_bits, A->z_bits, A->beta1, A->beta2,
                                A->group_axis, &D->g);
   if (rc) return rc;
   if (!A->packed || !A->row_ptr) return SPQR_ERR_NULL;
@@ -194,7 +194,8 @@ extern "C" int spqr_gemv_grouped(const spqr_matrix_t* const* A, int count, const
     for (int j = i; j < count && k < SPQR_MAX_FUSED; ++j) {
       const spqr_matrix_t *a = A[j], *a0 = A[i];
       const bool same = a->n == a0->n && a->w_bits == a0->w_bits && a->beta1 == a0->beta1 && a->beta2 == a0->beta2 &&
-                        a->group_axis == a0->group_axis && a->perm == nullptr && a0->perm == nullptr;
+                        a->group_axis == a0->group_axis && a->layout_version == a0->layout_version &&
+                        a->perm == nullptr && a0->perm == nullptr;
       if (done[j] || (j != i && !same)) continue;
       G[k] = D[j]; xs[k] = x_f16[j]; ys[k] = y[j]; ++k;
       done[j] = true;

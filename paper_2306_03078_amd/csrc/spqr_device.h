@@ -155,15 +155,25 @@ __device__ inline uint32_t tile_stat_code(const Geometry& g, const uint8_t* pack
 
 // Canonical binary32 statistics of group `gi` of a tile: widen, subtract,
 // multiply, each rounded once (Alg. 1 dequantize applied to the statistic codes).
+// Integer zero-point (Sec. 5, "round zero"): z_hat is the code.  16-bit statistics
+// (Sec. 5): dword gi holds s | z << 16 as binary16, widened exactly.
 __device__ inline void tile_group_stats(const Geometry& g, const uint8_t* packed,
                                         int tr, int tc, int gi, float* s_hat, float* z_hat) {
-  const uint32_t a = ld32(packed, stat_dword_offset(g, tr, tc, g.sd - 2));
-  const uint32_t b = ld32(packed, stat_dword_offset(g, tr, tc, g.sd - 1));
+  if (g.layout == kStats16) {
+    const uint32_t d = ld32(packed, stat_dword_offset(g, tr, tc, gi));
+    *s_hat = h2f((uint16_t)(d & 0xFFFF));
+    *z_hat = h2f((uint16_t)(d >> 16));
+    return;
+  }
+  const int nc = 3 * g.beta2 / 16;             // dwords of statistic codes
+  const uint32_t a = ld32(packed, stat_dword_offset(g, tr, tc, nc));
   const float s_s = h2f((uint16_t)(a & 0xFFFF)), z_s = h2f((uint16_t)(a >> 16));
-  const float s_z = h2f((uint16_t)(b & 0xFFFF)), z_z = h2f((uint16_t)(b >> 16));
   const float sq = (float)tile_stat_code(g, packed, tr, tc, gi);
   const float zq = (float)tile_stat_code(g, packed, tr, tc, g.beta2 + gi);
   *s_hat = __fmul_rn(s_s, __fsub_rn(sq, z_s));
+  if (g.layout == kRoundZero) { *z_hat = zq; return; }
+  const uint32_t b = ld32(packed, stat_dword_offset(g, tr, tc, nc + 1));
+  const float s_z = h2f((uint16_t)(b & 0xFFFF)), z_z = h2f((uint16_t)(b >> 16));
   *z_hat = __fmul_rn(s_z, __fsub_rn(zq, z_z));
 }
 

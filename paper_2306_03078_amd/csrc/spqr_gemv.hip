@@ -1,11 +1,6 @@
-// Launchers of the fused decode + matvec kernel (spqr_gemv_tile.h): launch plan, instances, one launch
-// for several matrices that share the input vector.
-#include <hip/hip_runtime.h>
-#include <cstdint>
-
-#include "../../include/spqr.h"
-#include "spqr_gemv_tile.h"
-#include "spqr_kernels.h"
+// Host side of the fused decode + matvec kernel (spqr_gemv_tile.h): launch plan and the choice of the instance
+// (the instances themselves: spqr_gemv_l1/l2/l3.hip); one launch for several matrices of one format.
+#include "spqr_gemv_inst.h"
 
 namespace spqr {
 
@@ -19,18 +14,12 @@ namespace spqr {
 // per thread (the common, single-barrier path) and up to eight.  Static arrays (red, osum, lred, rp) come on
 // top; the sum must stay within the CU's 160 KB.
 // ---------------------------------------------------------------------------
-static constexpr int static_lds_bytes(int tr, int nb) {
-  const int rows = nb == 1 ? 64 : tr;        // RowsPerGroup<TR, NB>::MAX
-  return ((16 * nb * tr + nb * rows + 32 + nb * rows * 16 + rows + 1) * 4 + 1023) & ~1023;
-}
-struct LaunchPlan { int P; int R; int cap; size_t lds; };
-
 // Set by tuning harnesses that compile this file into a program of their own (never by the library): P > 0
 // pins the wavefronts per strip and the strips per workgroup.
 struct PlanPin { int P, R; };
 static PlanPin g_plan_pin = {0, 0};
 
-static bool plan_launch(const Geometry& g, int nb, int max_waves, int slots, LaunchPlan* out) {
+bool plan_launch(const Geometry& g, int nb, int max_waves, int slots, LaunchPlan* out) {
   const int nsteps = (g.ntc + 63) / 64;
   const int xbytes = (nb * g.n * 2 + 15) & ~15;
   const int fixed = static_lds_bytes(g.tile_rows, nb) + 1024;
@@ -105,7 +94,7 @@ static bool plan_launch(const Geometry& g, int nb, int max_waves, int slots, Lau
 
 // Wavefront slots per CU of a kernel (from its register count), asked once per device; also opts the kernel in
 // for more than 64 KB of dynamic LDS.
-static hipError_t kernel_slots(const void* fn, int max_dynamic, PerDevice* known, int* slots) {
+hipError_t kernel_slots(const void* fn, int max_dynamic, PerDevice* known, int* slots) {
   const int dev = current_device();
   *slots = known->get(dev);
   if (*slots != 0) return hipSuccess;
@@ -121,34 +110,6 @@ static hipError_t kernel_slots(const void* fn, int max_dynamic, PerDevice* known
   return hipSuccess;
 }
 
-template <int W, int TR, int TC, int AXIS, int NB>
-static hipError_t launch_tile256(const DevMatrix& A, const uint16_t* x, void* y, int y_dtype,
-                                 hipStream_t stream) {
-  constexpr int MAXW = WavesPerGroup<W, NB>::MAX;
-  constexpr int MAX_DYNAMIC = 160 * 1024 - static_lds_bytes(TR, NB) - 1024;   // static + dynamic <= 160 KB
-  static PerDevice known[2];                 // wavefront slots per CU of the instance, 0 = not asked yet
-  const void* fn = A.perm ? reinterpret_cast<const void*>(&gemv_tile256_kernel<W, TR, TC, AXIS, true, NB>)
-                          : reinterpret_cast<const void*>(&gemv_tile256_kernel<W, TR, TC, AXIS, false, NB>);
-  int slots = 0;
-  hipError_t e = kernel_slots(fn, MAX_DYNAMIC, &known[A.perm ? 1 : 0], &slots);
-  if (e != hipSuccess) return e;
-  LaunchPlan plan = {0, 0, 0, 0};
-  if (!plan_launch(A.g, NB, MAXW, slots, &plan)) return hipErrorInvalidValue;
-  const int nw = plan.P * plan.R;
-  // what the kernel assumes of its launch: checked here, on the host
-  if (plan.lds > (size_t)MAX_DYNAMIC || plan.cap < 64 * nw || nw > MAXW || plan.R * TR > RowsPerGroup<TR, NB>::MAX ||
-      plan.P > (A.g.ntc + 63) / 64 || plan.P < 1 || plan.R < 1 || plan.R > 8)
-    return hipErrorInvalidValue;
-  const dim3 grid((A.g.ntr + plan.R - 1) / plan.R), block(64 * nw);
-  if (A.perm)
-    hipLaunchKernelGGL((gemv_tile256_kernel<W, TR, TC, AXIS, true, NB>), grid, block, plan.lds, stream, A, x, y,
-                       y_dtype, plan.cap, plan.R, plan.P);
-  else
-    hipLaunchKernelGGL((gemv_tile256_kernel<W, TR, TC, AXIS, false, NB>), grid, block, plan.lds, stream, A, x, y,
-                       y_dtype, plan.cap, plan.R, plan.P);
-  return hipGetLastError();
-}
-
 // Largest number of activation vectors (1, 2 or 4, at most `want`) one launch of
 // the tuned kernel can take for this geometry; 0 if there is no tuned kernel.
 int tuned_batch_width(const Geometry& g, int want) {
@@ -156,6 +117,7 @@ int tuned_batch_width(const Geometry& g, int want) {
   const bool shape_ok = g.axis == 1 ? ((g.tile_rows == 16 && g.tile_cols == 16) || (g.tile_rows == 8 && g.tile_cols == 32))
                                     : ((g.tile_rows == 16 && g.tile_cols == 16) || (g.tile_rows == 32 && g.tile_cols == 8));
   if (!shape_ok) return 0;
+  if (g.layout != kBilevel) want = 1;        // the other statistic layouts are built for one vector per launch
   for (int nb = want >= 4 ? 4 : (want >= 2 ? 2 : 1); nb >= 1; nb >>= 1) {
     LaunchPlan plan = {0, 0, 0, 0};
     const int maxw = (g.w_bits == 3 && nb == 1) ? 16 : 8;
@@ -166,70 +128,10 @@ int tuned_batch_width(const Geometry& g, int want) {
 
 bool has_tuned_gemv(const Geometry& g) { return tuned_batch_width(g, 1) == 1; }
 
-// The instances that are built (a tuning harness may narrow the list to compile faster).
-#ifndef SPQR_GEMV_INSTANCES
-#define SPQR_GEMV_INSTANCES(CASE) \
-  CASE(3, 16, 16, 1) CASE(4, 16, 16, 1) CASE(3, 8, 32, 1) CASE(4, 8, 32, 1) \
-  CASE(3, 16, 16, 0) CASE(4, 16, 16, 0) CASE(3, 32, 8, 0) CASE(4, 32, 8, 0)
-#endif
-
-template <int NB>
-static hipError_t launch_tuned_nb(const DevMatrix& A, const uint16_t* x, void* y, int y_dtype, hipStream_t stream) {
-  const Geometry& g = A.g;
-#define SPQR_CASE(W_, TR_, TC_, AX_) \
-  if (g.w_bits == W_ && g.tile_rows == TR_ && g.tile_cols == TC_ && g.axis == AX_) \
-    return launch_tile256<W_, TR_, TC_, AX_, NB>(A, x, y, y_dtype, stream);
-  SPQR_GEMV_INSTANCES(SPQR_CASE)
-#undef SPQR_CASE
-  return hipErrorInvalidValue;
-}
-
 hipError_t launch_tuned(const DevMatrix& A, const uint16_t* x, int nb, void* y, int y_dtype, hipStream_t stream) {
-  if (nb == 4) return launch_tuned_nb<4>(A, x, y, y_dtype, stream);
-  if (nb == 2) return launch_tuned_nb<2>(A, x, y, y_dtype, stream);
-  if (nb == 1) return launch_tuned_nb<1>(A, x, y, y_dtype, stream);
-  return hipErrorInvalidValue;
-}
-
-template <int W, int TR, int TC, int AXIS>
-static hipError_t launch_fused256(const DevMatrix* As, int count, const uint16_t* const* xs, void* const* ys,
-                                  int y_dtype, hipStream_t stream) {
-  constexpr int MAXW = WavesPerGroup<W, 1>::MAX;
-  constexpr int MAX_DYNAMIC = 160 * 1024 - static_lds_bytes(TR, 1) - 1024;
-  static PerDevice known;
-  int slots = 0;
-  hipError_t e = kernel_slots(reinterpret_cast<const void*>(&gemv_tile256_fused_kernel<W, TR, TC, AXIS>), MAX_DYNAMIC,
-                              &known, &slots);
-  if (e != hipSuccess) return e;
-  Geometry all = As[0].g;                    // the plan sees the strips of all matrices
-  all.ntr = 0;
-  for (int i = 0; i < count; ++i) all.ntr += As[i].g.ntr;
-  LaunchPlan plan = {0, 0, 0, 0};
-  if (!plan_launch(all, 1, MAXW, slots, &plan)) return hipErrorInvalidValue;
-  const int nw = plan.P * plan.R;
-  if (plan.lds > (size_t)MAX_DYNAMIC || plan.cap < 64 * nw || nw > MAXW || plan.R * TR > RowsPerGroup<TR, 1>::MAX ||
-      plan.P > (all.ntc + 63) / 64 || plan.P < 1 || plan.R < 1 || plan.R > 8)
-    return hipErrorInvalidValue;
-  FusedArgs F;
-  F.count = count;
-  F.g = As[0].g;
-  int total = 0;                             // workgroups
-  for (int i = 0; i < count; ++i) {
-    F.first[i] = total;
-    total += (As[i].g.ntr + plan.R - 1) / plan.R;
-    F.m[i] = As[i].g.m;
-    F.packed[i] = As[i].packed; F.row_ptr[i] = As[i].row_ptr; F.col[i] = As[i].col; F.val[i] = As[i].val;
-    F.x[i] = xs[i];
-    F.y[i] = ys[i];
-  }
-  for (int i = count; i <= SPQR_MAX_FUSED; ++i) F.first[i] = total;
-  for (int i = count; i < SPQR_MAX_FUSED; ++i) {
-    F.m[i] = 0;
-    F.packed[i] = nullptr; F.row_ptr[i] = nullptr; F.col[i] = nullptr; F.val[i] = nullptr; F.x[i] = nullptr; F.y[i] = nullptr;
-  }
-  hipLaunchKernelGGL((gemv_tile256_fused_kernel<W, TR, TC, AXIS>), dim3(total), dim3(64 * nw), plan.lds, stream,
-                     F, y_dtype, plan.cap, plan.R, plan.P);
-  return hipGetLastError();
+  if (A.g.layout == kBilevel) return launch_tuned_l1(A, x, nb, y, y_dtype, stream);
+  if (A.g.layout == kRoundZero) return launch_tuned_l2(A, x, nb, y, y_dtype, stream);
+  return launch_tuned_l3(A, x, nb, y, y_dtype, stream);
 }
 
 // Matrices of one format and one n, each with its own input vector: one launch when a tuned kernel exists and
@@ -238,11 +140,9 @@ hipError_t launch_gemv_grouped(const DevMatrix* As, int count, const uint16_t* c
                                int y_dtype, hipStream_t stream) {
   const Geometry& g = As[0].g;
   if (count > 1 && option(SPQR_OPT_FORCE_GENERIC) == 0 && As[0].perm == nullptr && tuned_batch_width(g, 1) == 1) {
-#define SPQR_CASE(W_, TR_, TC_, AX_) \
-    if (g.w_bits == W_ && g.tile_rows == TR_ && g.tile_cols == TC_ && g.axis == AX_) \
-      return launch_fused256<W_, TR_, TC_, AX_>(As, count, xs, ys, y_dtype, stream);
-    SPQR_GEMV_INSTANCES(SPQR_CASE)
-#undef SPQR_CASE
+    if (g.layout == kBilevel) return launch_fused_l1(As, count, xs, ys, y_dtype, stream);
+    if (g.layout == kRoundZero) return launch_fused_l2(As, count, xs, ys, y_dtype, stream);
+    return launch_fused_l3(As, count, xs, ys, y_dtype, stream);
   }
   for (int i = 0; i < count; ++i) {
     hipError_t e = launch_gemv(As[i], xs[i], ys[i], y_dtype, stream);

@@ -1,0 +1,146 @@
+// Launch templates of the fused decode + matvec kernel and the macro that instantiates them for one statistic
+// layout: each layout's instances are a translation unit of their own (spqr_gemv_l1/l2/l3.hip), compiled side by
+// side.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <cstdint>
+
+#include "../../include/spqr.h"
+#include "spqr_gemv_tile.h"
+#include "spqr_kernels.h"
+
+namespace spqr {
+
+// Static LDS of the kernel (red, osum, lred, rp), rounded up; it and the dynamic part must stay within the
+// CU's 160 KB.
+static constexpr int static_lds_bytes(int tr, int nb) {
+  const int rows = nb == 1 ? 64 : tr;        // RowsPerGroup<TR, NB>::MAX
+  return ((16 * nb * tr + nb * rows + 32 + nb * rows * 16 + rows + 1) * 4 + 1023) & ~1023;
+}
+struct LaunchPlan { int P; int R; int cap; size_t lds; };
+
+
+// spqr_gemv.hip
+bool plan_launch(const Geometry& g, int nb, int max_waves, int slots, LaunchPlan* out);
+hipError_t kernel_slots(const void* fn, int max_dynamic, PerDevice* known, int* slots);
+// one pair per statistic layout (spqr_gemv_l1/l2/l3.hip)
+hipError_t launch_tuned_l1(const DevMatrix& A, const uint16_t* x, int nb, void* y, int y_dtype, hipStream_t stream);
+hipError_t launch_tuned_l2(const DevMatrix& A, const uint16_t* x, int nb, void* y, int y_dtype, hipStream_t stream);
+hipError_t launch_tuned_l3(const DevMatrix& A, const uint16_t* x, int nb, void* y, int y_dtype, hipStream_t stream);
+hipError_t launch_fused_l1(const DevMatrix* As, int count, const uint16_t* const* xs, void* const* ys, int y_dtype,
+                           hipStream_t stream);
+hipError_t launch_fused_l2(const DevMatrix* As, int count, const uint16_t* const* xs, void* const* ys, int y_dtype,
+                           hipStream_t stream);
+hipError_t launch_fused_l3(const DevMatrix* As, int count, const uint16_t* const* xs, void* const* ys, int y_dtype,
+                           hipStream_t stream);
+
+template <int W, int TR, int TC, int AXIS, int NB, int LV>
+static hipError_t launch_tile256(const DevMatrix& A, const uint16_t* x, void* y, int y_dtype,
+                                 hipStream_t stream) {
+  constexpr int MAXW = WavesPerGroup<W, NB>::MAX;
+  constexpr int MAX_DYNAMIC = 160 * 1024 - static_lds_bytes(TR, NB) - 1024;   // static + dynamic <= 160 KB
+  static PerDevice known[2];                 // wavefront slots per CU of the instance, 0 = not asked yet
+  const void* fn = A.perm ? reinterpret_cast<const void*>(&gemv_tile256_kernel<W, TR, TC, AXIS, true, NB, LV>)
+                          : reinterpret_cast<const void*>(&gemv_tile256_kernel<W, TR, TC, AXIS, false, NB, LV>);
+  int slots = 0;
+  hipError_t e = kernel_slots(fn, MAX_DYNAMIC, &known[A.perm ? 1 : 0], &slots);
+  if (e != hipSuccess) return e;
+  LaunchPlan plan = {0, 0, 0, 0};
+  if (!plan_launch(A.g, NB, MAXW, slots, &plan)) return hipErrorInvalidValue;
+  const int nw = plan.P * plan.R;
+  // what the kernel assumes of its launch and of the tile's size: checked here, on the host
+  using T = TileRegs<W, TR, TC, AXIS, LV>;
+  if (A.g.kw != T::KW || A.g.sd != T::SD || A.g.layout != LV) return hipErrorInvalidValue;
+  if (plan.lds > (size_t)MAX_DYNAMIC || plan.cap < 64 * nw || nw > MAXW || plan.R * TR > RowsPerGroup<TR, NB>::MAX ||
+      plan.P > (A.g.ntc + 63) / 64 || plan.P < 1 || plan.R < 1 || plan.R > 8)
+    return hipErrorInvalidValue;
+  const dim3 grid((A.g.ntr + plan.R - 1) / plan.R), block(64 * nw);
+  if (A.perm)
+    hipLaunchKernelGGL((gemv_tile256_kernel<W, TR, TC, AXIS, true, NB, LV>), grid, block, plan.lds, stream, A, x, y,
+                       y_dtype, plan.cap, plan.R, plan.P);
+  else
+    hipLaunchKernelGGL((gemv_tile256_kernel<W, TR, TC, AXIS, false, NB, LV>), grid, block, plan.lds, stream, A, x, y,
+                       y_dtype, plan.cap, plan.R, plan.P);
+  return hipGetLastError();
+}
+
+template <int W, int TR, int TC, int AXIS, int LV>
+static hipError_t launch_fused256(const DevMatrix* As, int count, const uint16_t* const* xs, void* const* ys,
+                                  int y_dtype, hipStream_t stream) {
+  constexpr int MAXW = WavesPerGroup<W, 1>::MAX;
+  constexpr int MAX_DYNAMIC = 160 * 1024 - static_lds_bytes(TR, 1) - 1024;
+  static PerDevice known;
+  int slots = 0;
+  hipError_t e = kernel_slots(reinterpret_cast<const void*>(&gemv_tile256_fused_kernel<W, TR, TC, AXIS, LV>), MAX_DYNAMIC,
+                              &known, &slots);
+  if (e != hipSuccess) return e;
+  Geometry all = As[0].g;                    // the plan sees the strips of all matrices
+  all.ntr = 0;
+  for (int i = 0; i < count; ++i) all.ntr += As[i].g.ntr;
+  LaunchPlan plan = {0, 0, 0, 0};
+  if (!plan_launch(all, 1, MAXW, slots, &plan)) return hipErrorInvalidValue;
+  const int nw = plan.P * plan.R;
+  using T = TileRegs<W, TR, TC, AXIS, LV>;
+  if (all.kw != T::KW || all.sd != T::SD || all.layout != LV) return hipErrorInvalidValue;
+  if (plan.lds > (size_t)MAX_DYNAMIC || plan.cap < 64 * nw || nw > MAXW || plan.R * TR > RowsPerGroup<TR, 1>::MAX ||
+      plan.P > (all.ntc + 63) / 64 || plan.P < 1 || plan.R < 1 || plan.R > 8)
+    return hipErrorInvalidValue;
+  FusedArgs F;
+  F.count = count;
+  F.g = As[0].g;
+  int total = 0;                             // workgroups
+  for (int i = 0; i < count; ++i) {
+    F.first[i] = total;
+    total += (As[i].g.ntr + plan.R - 1) / plan.R;
+    F.m[i] = As[i].g.m;
+    F.packed[i] = As[i].packed; F.row_ptr[i] = As[i].row_ptr; F.col[i] = As[i].col; F.val[i] = As[i].val;
+    F.x[i] = xs[i];
+    F.y[i] = ys[i];
+  }
+  for (int i = count; i <= SPQR_MAX_FUSED; ++i) F.first[i] = total;
+  for (int i = count; i < SPQR_MAX_FUSED; ++i) {
+    F.m[i] = 0;
+    F.packed[i] = nullptr; F.row_ptr[i] = nullptr; F.col[i] = nullptr; F.val[i] = nullptr; F.x[i] = nullptr; F.y[i] = nullptr;
+  }
+  hipLaunchKernelGGL((gemv_tile256_fused_kernel<W, TR, TC, AXIS, LV>), dim3(total), dim3(64 * nw), plan.lds, stream,
+                     F, y_dtype, plan.cap, plan.R, plan.P);
+  return hipGetLastError();
+}
+
+// Defines launch_tuned_l<LV> and launch_fused_l<LV> for the tile shapes in CASES (a list of
+// CASE(w_bits, tile_rows, tile_cols, group_axis)) and the vector counts NBS (SPQR_NB_124 or SPQR_NB_1).
+#define SPQR_NB_124(NBCASE) NBCASE(1) NBCASE(2) NBCASE(4)
+#define SPQR_NB_1(NBCASE) NBCASE(1)
+#define SPQR_DEFINE_GEMV_LAYOUT(LV, CASES, NBS)                                                                    \
+  template <int NB>                                                                                                \
+  static hipError_t launch_tuned_nb_(const DevMatrix& A, const uint16_t* x, void* y, int y_dtype,                  \
+                                     hipStream_t stream) {                                                         \
+    const Geometry& g = A.g;                                                                                       \
+    CASES(SPQR_TUNED_CASE_, LV)                                                                                    \
+    return hipErrorInvalidValue;                                                                                   \
+  }                                                                                                                \
+  hipError_t launch_tuned_l##LV(const DevMatrix& A, const uint16_t* x, int nb, void* y, int y_dtype,               \
+                                hipStream_t stream) {                                                              \
+    NBS(SPQR_NB_CASE_)                                                                                             \
+    return hipErrorInvalidValue;                                                                                   \
+  }                                                                                                                \
+  hipError_t launch_fused_l##LV(const DevMatrix* As, int count, const uint16_t* const* xs, void* const* ys,        \
+                                int y_dtype, hipStream_t stream) {                                                 \
+    const Geometry& g = As[0].g;                                                                                   \
+    CASES(SPQR_FUSED_CASE_, LV)                                                                                    \
+    return hipErrorInvalidValue;                                                                                   \
+  }
+#define SPQR_TUNED_CASE_(W_, TR_, TC_, AX_, LV_)                                              \
+  if (g.w_bits == W_ && g.tile_rows == TR_ && g.tile_cols == TC_ && g.axis == AX_)            \
+    return launch_tile256<W_, TR_, TC_, AX_, NB, LV_>(A, x, y, y_dtype, stream);
+#define SPQR_FUSED_CASE_(W_, TR_, TC_, AX_, LV_)                                              \
+  if (g.w_bits == W_ && g.tile_rows == TR_ && g.tile_cols == TC_ && g.axis == AX_)            \
+    return launch_fused256<W_, TR_, TC_, AX_, LV_>(As, count, xs, ys, y_dtype, stream);
+#define SPQR_NB_CASE_(NB_) if (nb == NB_) return launch_tuned_nb_<NB_>(A, x, y, y_dtype, stream);
+
+// The tile shapes with a tuned kernel (tuned_batch_width() in spqr_gemv.hip lists the same).
+#define SPQR_GEMV_SHAPES(CASE, LV)                                                          \
+  CASE(3, 16, 16, 1, LV) CASE(4, 16, 16, 1, LV) CASE(3, 8, 32, 1, LV) CASE(4, 8, 32, 1, LV) \
+  CASE(3, 16, 16, 0, LV) CASE(4, 16, 16, 0, LV) CASE(3, 32, 8, 0, LV) CASE(4, 32, 8, 0, LV)
+
+}  // namespace spqr

@@ -1,0 +1,6 @@
+// Instances of the fused decode + matvec kernel for the integer zero-point layout (Sec. 5, ablations): one activation vector per launch.
+#include "spqr_gemv_inst.h"
+
+namespace spqr {
+SPQR_DEFINE_GEMV_LAYOUT(2, SPQR_GEMV_SHAPES, SPQR_NB_1)
+}  // namespace spqr

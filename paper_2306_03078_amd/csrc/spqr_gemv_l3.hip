@@ -1,0 +1,6 @@
+// Instances of the fused decode + matvec kernel for the layout with 16-bit statistics (Sec. 5, ablations): one activation vector per launch.
+#include "spqr_gemv_inst.h"
+
+namespace spqr {
+SPQR_DEFINE_GEMV_LAYOUT(3, SPQR_GEMV_SHAPES, SPQR_NB_1)
+}  // namespace spqr

@@ -47,25 +47,38 @@ __device__ __forceinline__ uint32_t scaled_pair_f16(float s0, float s1, uint32_t
   return u;
 }
 
-template <int W, int TR, int TC, int AXIS, int NB>
-__device__ __forceinline__ void tile_fma(const TileRegs<W, TR, TC, AXIS>& t,
+// High halves of two dwords as one pair: (a >> 16) | (b & 0xFFFF0000).
+__device__ __forceinline__ uint32_t high_halves(uint32_t a, uint32_t b) {
+  return __builtin_amdgcn_perm(b, a, 0x07060302u);
+}
+
+template <int W, int TR, int TC, int AXIS, int NB, int LV>
+__device__ __forceinline__ void tile_fma(const TileRegs<W, TR, TC, AXIS, LV>& t,
                                          const uint32_t* xpair /* TC/2 dwords in LDS, vector 0 */,
                                          int xstride, bool valid, float (&acc)[NB][TR],
                                          float (&csum)[NB][RowPhases<W, TC>::N], const ClassConsts& k,
                                          const PairConsts& k1, const PairConsts& k3) {
-  using T = TileRegs<W, TR, TC, AXIS>;
+  using T = TileRegs<W, TR, TC, AXIS, LV>;
   constexpr bool SHARED = SharedShifts<TC>::value;
   using CC = CodeClass<W, SHARED>;
   constexpr int PPR = TC / 2;
   constexpr int NPH = RowPhases<W, TC>::N;
   constexpr float SCALE = (float)(1 << W);
+  constexpr bool CODES = LV != 3;            // first-level statistics are 3-bit codes
   const half2_t ones = as_half2(k3.magic);
-  const uint32_t a = t.s[T::SD - 2], b = t.s[T::SD - 1];
+  // Second-level statistics: layout 1 holds both pairs, layout 2 (integer zero-point: z_hat = z_q) the scales'
+  // pair only, which is layout 1 with s_z = 1, z_z = 0; layout 3 has binary16 (s_hat, z_hat) per group instead.
+  const uint32_t a = CODES ? t.s[T::NC] : 0u;
   const float s_s = h2f((uint16_t)(a & 0xFFFF)), z_s = h2f((uint16_t)(a >> 16));
-  const float s_z = h2f((uint16_t)(b & 0xFFFF)), z_z = h2f((uint16_t)(b >> 16));
+  float s_z = 1.f, z_z = 0.f;
+  if constexpr (LV == 1) {
+    const uint32_t b = t.s[T::NC + 1];
+    s_z = h2f((uint16_t)(b & 0xFFFF)); z_z = h2f((uint16_t)(b >> 16));
+  }
   // s_hat = s_s*(s_q - z_s) = c1*(1 + s_q/8) + c2.  A lane without a tile of its own
   // (it holds a copy of the block's last tile) runs the same code with s_hat = 0.
-  const float c1 = valid ? 8.f * s_s : 0.f, c2 = valid ? -s_s * z_s - 8.f * s_s : 0.f;
+  // (Layout 3: s_hat = c1 * s with c1 = 1 or 0.)
+  const float c1 = valid ? (CODES ? 8.f * s_s : 1.f) : 0.f, c2 = valid ? -s_s * z_s - 8.f * s_s : 0.f;
   // z_hat = s_z*(z_q - z_z) = e1*(1 + z_q/8) + e2
   const float e1 = 8.f * s_z, e2 = -s_z * z_z - e1;
 
@@ -93,7 +106,7 @@ __device__ __forceinline__ void tile_fma(const TileRegs<W, TR, TC, AXIS>& t,
     // are extracted the same way, in place, as K + code/8 with K by the pair's class: the scale's offset goes into the
     // additive constant of its class (c2k), the zero's offset leaves with the class sums the weight codes need
     // anyway, because pair PPR + p of the zero codes has the class of weight pair p in phase ZPH.
-    constexpr bool STATS_IN_PLACE = W == 3 && SHARED;
+    constexpr bool STATS_IN_PLACE = W == 3 && SHARED && CODES;
     constexpr int ZPH = NPH == 1 ? 0 : 1;
     static_assert(!STATS_IN_PLACE || (PPR % 16 == 0 && NPH == 1) || (PPR == 8 && NPH == 2), "class of a zero-code pair");
     float c2k[3] = {c2, c2, c2};
@@ -110,10 +123,18 @@ __device__ __forceinline__ void tile_fma(const TileRegs<W, TR, TC, AXIS>& t,
     for (int bi = 0; bi < NB; ++bi) Zd[bi] = 0.f;
 #pragma unroll
     for (int p = 0; p < PPR; ++p) {
-      const half2_t sq = as_half2(STATS_IN_PLACE ? pair_class_f16<3>(t.s, sws, p, k) : pair_f16<3>(t.s, p, k3));
-      const half2_t zq = as_half2(STATS_IN_PLACE ? pair_class_f16<3>(t.s, swz, T::B2 / 2 + p, k) : pair_f16<3>(t.s, T::B2 / 2 + p, k3));
-      const float c2p = STATS_IN_PLACE ? c2k[CodeClass<3, true>::of_pair(p)] : c2;
-      const float s0 = fmaf((float)sq.x, c1, c2p), s1 = fmaf((float)sq.y, c1, c2p);
+      half2_t zq;
+      float s0, s1;
+      if constexpr (CODES) {
+        const half2_t sq = as_half2(STATS_IN_PLACE ? pair_class_f16<3>(t.s, sws, p, k) : pair_f16<3>(t.s, p, k3));
+        zq = as_half2(STATS_IN_PLACE ? pair_class_f16<3>(t.s, swz, T::B2 / 2 + p, k) : pair_f16<3>(t.s, T::B2 / 2 + p, k3));
+        const float c2p = STATS_IN_PLACE ? c2k[CodeClass<3, true>::of_pair(p)] : c2;
+        s0 = fmaf((float)sq.x, c1, c2p); s1 = fmaf((float)sq.y, c1, c2p);
+      } else {                               // dword j of the statistics: s_hat_j | z_hat_j << 16
+        const uint32_t d0 = t.s[2 * p], d1 = t.s[2 * p + 1];
+        s0 = c1 * h2f((uint16_t)(d0 & 0xFFFF)); s1 = c1 * h2f((uint16_t)(d1 & 0xFFFF));
+        zq = as_half2(high_halves(d0, d1));
+      }
 #pragma unroll
       for (int bi = 0; bi < NB; ++bi) {
         const half2_t u = as_half2(scaled_pair_f16(s0, s1, xp[bi][p]));
@@ -141,7 +162,7 @@ __device__ __forceinline__ void tile_fma(const TileRegs<W, TR, TC, AXIS>& t,
       }
       // zero codes extracted in place carry their class offsets: sum_j (K - 1) u_j = E[ZPH] - U
       const float zd = STATS_IN_PLACE ? Zd[bi] - E[ZPH] + U : Zd[bi];
-      const float zu = fmaf(e1, zd, e2 * U);
+      const float zu = CODES ? fmaf(e1, zd, e2 * U) : zd;          // layout 3: zq held z_hat itself
 #pragma unroll
       for (int h = 0; h < NPH; ++h) csum[bi][h] += fmaf(SCALE, E[h], zu);
     }
@@ -185,8 +206,14 @@ __device__ __forceinline__ void tile_fma(const TileRegs<W, TR, TC, AXIS>& t,
     }
 #pragma unroll
     for (int r2 = 0; r2 < TR / 2; ++r2) {
-      const half2_t sq = as_half2(pair_f16<3>(t.s, r2, k3));
-      const half2_t zq = as_half2(pair_f16<3>(t.s, T::B2 / 2 + r2, k3));
+      half2_t sq, zq;
+      if constexpr (CODES) {
+        sq = as_half2(pair_f16<3>(t.s, r2, k3));
+        zq = as_half2(pair_f16<3>(t.s, T::B2 / 2 + r2, k3));
+      } else {                               // dword r of the statistics: s_hat_r | z_hat_r << 16
+        sq = as_half2(__builtin_amdgcn_perm(t.s[2 * r2 + 1], t.s[2 * r2], 0x05040100u));   // the two low halves
+        zq = as_half2(high_halves(t.s[2 * r2], t.s[2 * r2 + 1]));
+      }
 #pragma unroll
       for (int h2 = 0; h2 < 2; ++h2) {
         const int r = 2 * r2 + h2;
@@ -200,8 +227,8 @@ __device__ __forceinline__ void tile_fma(const TileRegs<W, TR, TC, AXIS>& t,
 #pragma unroll
           for (int bi = 0; bi < NB; ++bi) d[bi] = __builtin_amdgcn_fdot2(q2, as_half2(xp[bi][p]), d[bi], false);
         }
-        const float sh = fmaf((float)(h2 ? sq.y : sq.x), c1, c2);
-        const float zh = fmaf((float)(h2 ? zq.y : zq.x), e1, e2);      // z_hat_r
+        const float sh = CODES ? fmaf((float)(h2 ? sq.y : sq.x), c1, c2) : c1 * (float)(h2 ? sq.y : sq.x);
+        const float zh = CODES ? fmaf((float)(h2 ? zq.y : zq.x), e1, e2) : (float)(h2 ? zq.y : zq.x);   // z_hat_r
 #pragma unroll
         for (int bi = 0; bi < NB; ++bi)
           acc[bi][r] = fmaf(sh, fmaf(-zh, X[bi], fmaf(SCALE, d[bi], -SE[bi][r % NPH])), acc[bi][r]);   // big terms cancel first
@@ -276,11 +303,11 @@ template <int W, int NB> struct WavesPerGroup { static constexpr int MAX = (W ==
 // the current tile's arithmetic.
 template <int TR, int NB> struct RowsPerGroup { static constexpr int MAX = NB == 1 ? 64 : TR; };
 
-template <int W, int TR, int TC, int AXIS, bool PERM, int NB>
+template <int W, int TR, int TC, int AXIS, bool PERM, int NB, int LV>
 __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint16_t* __restrict__ x,
                                                   void* __restrict__ y, int y_dtype, int chunk_cap,
                                                   const int first_strip, const int R, const int P) {
-  using T = TileRegs<W, TR, TC, AXIS>;
+  using T = TileRegs<W, TR, TC, AXIS, LV>;
   static_assert(TR * TC == 256, "tile must hold 256 codes");
   static_assert((TC / 2) % 4 == 0, "x pairs are read as 16-byte LDS words");
   constexpr int TILE_BYTES = 16 * T::KW + 4 * T::SD;
@@ -409,7 +436,7 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
   const uint32_t* xs32 = reinterpret_cast<const uint32_t*>(xs);
   const bool heavy = nchunks > nthreads;     // workgroup-uniform
 #define SPQR_TILE_FMA(t, L, st)                                                                           \
-  tile_fma<W, TR, TC, AXIS, NB>(t, xs32 + (64 * (st) + min(lane, (L) - 1)) * (TC / 2), n >> 1, live && lane < (L), \
+  tile_fma<W, TR, TC, AXIS, NB, LV>(t, xs32 + (64 * (st) + min(lane, (L) - 1)) * (TC / 2), n >> 1, live && lane < (L), \
                                 acc, csum, kc, k1, k3)
   // Two steps per trip, registers ping-pong; the loop has its one exit at the
   // bottom (a second exit would be merged with it through a block that makes the
@@ -627,11 +654,11 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
   }
 }
 
-template <int W, int TR, int TC, int AXIS, bool PERM, int NB>
+template <int W, int TR, int TC, int AXIS, bool PERM, int NB, int LV = 1>
 __global__ void __launch_bounds__((64 * WavesPerGroup<W, NB>::MAX))
 gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restrict__ y, int y_dtype,
                     int chunk_cap, int strips_per_group, int waves_per_strip) {
-  gemv_tile256_body<W, TR, TC, AXIS, PERM, NB>(A, x, y, y_dtype, chunk_cap, blockIdx.x * strips_per_group,
+  gemv_tile256_body<W, TR, TC, AXIS, PERM, NB, LV>(A, x, y, y_dtype, chunk_cap, blockIdx.x * strips_per_group,
                                                strips_per_group, waves_per_strip);
 }
 
@@ -652,7 +679,7 @@ struct FusedArgs {
   void* y[SPQR_MAX_FUSED];
 };
 
-template <int W, int TR, int TC, int AXIS>
+template <int W, int TR, int TC, int AXIS, int LV = 1>
 __global__ void __launch_bounds__((64 * WavesPerGroup<W, 1>::MAX))
 gemv_tile256_fused_kernel(FusedArgs F, int y_dtype, int chunk_cap, int strips_per_group, int waves_per_strip) {
   int i = 0;
@@ -662,7 +689,7 @@ gemv_tile256_fused_kernel(FusedArgs F, int y_dtype, int chunk_cap, int strips_pe
   A.g.m = F.m[i]; A.g.ntr = F.m[i] / TR;
   A.packed = F.packed[i]; A.row_ptr = F.row_ptr[i]; A.col = F.col[i]; A.val = F.val[i];
   A.perm = nullptr; A.nnz = 0;
-  gemv_tile256_body<W, TR, TC, AXIS, false, 1>(A, F.x[i], F.y[i], y_dtype, chunk_cap,
+  gemv_tile256_body<W, TR, TC, AXIS, false, 1, LV>(A, F.x[i], F.y[i], y_dtype, chunk_cap,
                                                ((int)blockIdx.x - F.first[i]) * strips_per_group, strips_per_group,
                                                waves_per_strip);
 }

@@ -1,4 +1,4 @@
-// Geometry of packed layout V1 (see include/spqr.h for the normative text).
+// Geometry of the packed layouts (see include/spqr.h for the normative text).
 // Shared by the host packer, the validators and the kernels of this library.
 #pragma once
 #include <stdint.h>
@@ -13,21 +13,28 @@ namespace spqr {
 
 constexpr int kBlockTiles = 64;   // tiles per interleave block = lanes per wavefront
 
+// Statistic layouts (values of spqr_matrix_t::layout_version).
+constexpr int kBilevel = 1;       // 3-bit codes per group, (s_s, z_s, s_z, z_z) per tile
+constexpr int kRoundZero = 2;     // the zero code is the zero-point; (s_s, z_s) per tile
+constexpr int kStats16 = 3;       // binary16 (s, z) per group, nothing per tile
+
 struct Geometry {
   int32_t m, n, w_bits, beta1, beta2, axis;
   int32_t tile_rows, tile_cols;   // (beta2, beta1) for axis 0, (beta1, beta2) for axis 1
   int32_t ntr, ntc;               // tile grid
   int32_t kw;                     // 16-byte code words per tile
-  int32_t sd;                     // statistic dwords per tile (incl. the 2 second-level dwords)
+  int32_t sd;                     // statistic dwords per tile (incl. the second-level dwords)
   int32_t swf, sr;                // full statistic words, remaining dwords
   int32_t tile_bytes;
+  int32_t layout;                 // kBilevel, kRoundZero, kStats16
 };
 
 // Returns 0 or a negative spqr_status value (-2 shape, -3 param).
-SPQR_HD int make_geometry(int32_t m, int32_t n, int32_t w_bits, int32_t s_bits, int32_t z_bits,
+SPQR_HD int make_geometry(int32_t layout, int32_t m, int32_t n, int32_t w_bits, int32_t s_bits, int32_t z_bits,
                           int32_t beta1, int32_t beta2, int32_t axis, Geometry* g) {
+  if (layout != kBilevel && layout != kRoundZero && layout != kStats16) return -3;
   if (w_bits != 3 && w_bits != 4) return -3;
-  if (s_bits != 3 || z_bits != 3) return -3;
+  if (layout == kStats16 ? (s_bits != 16 || z_bits != 16) : (s_bits != 3 || z_bits != 3)) return -3;
   if (axis != 0 && axis != 1) return -3;
   if (beta1 < 1 || beta2 < 16 || beta1 > 4096 || beta2 > 4096) return -3;
   if (beta2 % 16 != 0) return -3;
@@ -41,7 +48,8 @@ SPQR_HD int make_geometry(int32_t m, int32_t n, int32_t w_bits, int32_t s_bits, 
   g->tile_rows = tr; g->tile_cols = tc;
   g->ntr = m / tr; g->ntc = n / tc;
   g->kw = (int32_t)(((int64_t)tr * tc * w_bits) / 128);
-  g->sd = 3 * beta2 / 16 + 2;
+  g->layout = layout;
+  g->sd = layout == kStats16 ? beta2 : 3 * beta2 / 16 + (layout == kRoundZero ? 1 : 2);
   g->swf = g->sd / 4; g->sr = g->sd % 4;
   g->tile_bytes = 16 * g->kw + 4 * g->sd;
   return 0;

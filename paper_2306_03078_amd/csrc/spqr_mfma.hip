@@ -1095,7 +1095,7 @@ bool mfma_has_instance(const Geometry& g) {
   const bool shape16 = g.tile_rows == 16 && g.tile_cols == 16;
   const bool shape8x32 = g.tile_rows == 8 && g.tile_cols == 32 && g.axis == 1;
   const bool shape32x8 = g.tile_rows == 32 && g.tile_cols == 8 && g.axis == 0;
-  return (g.w_bits == 3 || g.w_bits == 4) && (shape16 || shape8x32 || shape32x8);
+  return g.layout == kBilevel && (g.w_bits == 3 || g.w_bits == 4) && (shape16 || shape8x32 || shape32x8);
 }
 
 hipError_t launch_mfma(const DevMatrix& A, const uint16_t* X, int b, void* Y, int y_dtype, hipStream_t stream,

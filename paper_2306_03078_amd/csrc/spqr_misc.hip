@@ -126,10 +126,13 @@ __global__ void check_stats2_kernel(DevMatrix A, int* flag) {
   const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (t >= (int64_t)A.g.ntr * A.g.ntc) return;
   const int tr = (int)(t / A.g.ntc), tc = (int)(t % A.g.ntc);
-  const uint32_t a = ld32(A.packed, stat_dword_offset(A.g, tr, tc, A.g.sd - 2));
-  const uint32_t b = ld32(A.packed, stat_dword_offset(A.g, tr, tc, A.g.sd - 1));
-  const bool bad = (a & 0x7C00u) == 0x7C00u || (a & 0x7C000000u) == 0x7C000000u
-                || (b & 0x7C00u) == 0x7C00u || (b & 0x7C000000u) == 0x7C000000u;
+  // the dwords that hold binary16 numbers: the second-level ones behind the codes, or all of them
+  const int first = A.g.layout == kStats16 ? 0 : 3 * A.g.beta2 / 16;
+  bool bad = false;
+  for (int d = first; d < A.g.sd; ++d) {
+    const uint32_t a = ld32(A.packed, stat_dword_offset(A.g, tr, tc, d));
+    bad = bad || (a & 0x7C00u) == 0x7C00u || (a & 0x7C000000u) == 0x7C000000u;
+  }
   if (bad) atomicMax(flag + 1, 1);
 }
 

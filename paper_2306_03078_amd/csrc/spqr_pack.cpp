@@ -1,4 +1,4 @@
-// Host-side packer and size model for layout V1.  No GPU calls.
+// Host-side packer and size model of the packed layouts.  No GPU calls.
 #include <algorithm>
 #include <atomic>
 #include <cstring>
@@ -13,8 +13,14 @@ using spqr::Geometry;
 extern "C" int64_t spqr_packed_bytes(int32_t m, int32_t n, int32_t w_bits, int32_t s_bits,
                                      int32_t z_bits, int32_t beta1, int32_t beta2,
                                      int32_t group_axis) {
+  return spqr_packed_bytes_layout(SPQR_LAYOUT_V1, m, n, w_bits, s_bits, z_bits, beta1, beta2, group_axis);
+}
+
+extern "C" int64_t spqr_packed_bytes_layout(int32_t layout_version, int32_t m, int32_t n, int32_t w_bits,
+                                            int32_t s_bits, int32_t z_bits, int32_t beta1, int32_t beta2,
+                                            int32_t group_axis) {
   Geometry g;
-  int rc = spqr::make_geometry(m, n, w_bits, s_bits, z_bits, beta1, beta2, group_axis, &g);
+  int rc = spqr::make_geometry(layout_version, m, n, w_bits, s_bits, z_bits, beta1, beta2, group_axis, &g);
   if (rc) return rc;
   return (int64_t)g.ntr * g.ntc * g.tile_bytes;
 }
@@ -40,11 +46,28 @@ extern "C" int spqr_pack_host(int32_t m, int32_t n, int32_t w_bits, int32_t s_bi
                               const uint16_t* s_s, const uint16_t* z_s,
                               const uint16_t* s_z, const uint16_t* z_z,
                               void* packed_out, int64_t packed_bytes) {
-  if (!Q || !s_q || !z_q || !s_s || !z_s || !s_z || !z_z || !packed_out) return SPQR_ERR_NULL;
+  return spqr_pack_host_layout(SPQR_LAYOUT_V1, m, n, w_bits, s_bits, z_bits, beta1, beta2, group_axis, Q, s_q, z_q,
+                               s_s, z_s, s_z, z_z, packed_out, packed_bytes);
+}
+
+extern "C" int spqr_pack_host_layout(int32_t layout_version, int32_t m, int32_t n, int32_t w_bits,
+                                     int32_t s_bits, int32_t z_bits, int32_t beta1, int32_t beta2,
+                                     int32_t group_axis, const uint8_t* Q, const void* s_first,
+                                     const void* z_first, const uint16_t* s_s, const uint16_t* z_s,
+                                     const uint16_t* s_z, const uint16_t* z_z, void* packed_out,
+                                     int64_t packed_bytes) {
   Geometry g;
-  int rc = spqr::make_geometry(m, n, w_bits, s_bits, z_bits, beta1, beta2, group_axis, &g);
+  int rc = spqr::make_geometry(layout_version, m, n, w_bits, s_bits, z_bits, beta1, beta2, group_axis, &g);
   if (rc) return rc;
+  const bool codes = g.layout != spqr::kStats16;     // first-level statistics are 3-bit codes
+  if (!Q || !s_first || !z_first || !packed_out) return SPQR_ERR_NULL;
+  if (codes && (!s_s || !z_s)) return SPQR_ERR_NULL;
+  if (g.layout == spqr::kBilevel && (!s_z || !z_z)) return SPQR_ERR_NULL;
   if (packed_bytes != (int64_t)g.ntr * g.ntc * g.tile_bytes) return SPQR_ERR_SIZE;
+  const uint8_t* s_q = static_cast<const uint8_t*>(s_first);
+  const uint8_t* z_q = static_cast<const uint8_t*>(z_first);
+  const uint16_t* s16 = static_cast<const uint16_t*>(s_first);
+  const uint16_t* z16 = static_cast<const uint16_t*>(z_first);
 
   uint8_t* out = static_cast<uint8_t*>(packed_out);
   const int cd = 4 * g.kw;                 // code dwords per tile
@@ -68,24 +91,31 @@ extern "C" int spqr_pack_host(int32_t m, int32_t n, int32_t w_bits, int32_t s_bi
             put_pair(code.data(), w_bits, r * ppr + p, lo, hi);
           }
         }
-        // statistic codes of the beta2 groups of this tile: s_q[0..beta2), z_q[0..beta2)
-        for (int which = 0; which < 2; ++which) {
-          const uint8_t* src = which == 0 ? s_q : z_q;
-          for (int gq = 0; gq < beta2 / 2; ++gq) {
-            uint32_t v[2];
-            for (int h = 0; h < 2; ++h) {
-              int gi = 2 * gq + h;
-              int64_t idx = group_axis == 0 ? (r0 + gi) * gcols + tc        // group = row of the tile
-                                            : (int64_t)tr * gcols + c0 + gi; // group = column of the tile
-              v[h] = src[idx];
-              if (v[h] >= 8u) { bad.store(1); v[h] &= 7u; }
-            }
-            put_pair(stat.data(), 3, which * (beta2 / 2) + gq, v[0], v[1]);
-          }
-        }
         const int64_t t = (int64_t)tr * g.ntc + tc;
-        stat[g.sd - 2] = (uint32_t)s_s[t] | ((uint32_t)z_s[t] << 16);
-        stat[g.sd - 1] = (uint32_t)s_z[t] | ((uint32_t)z_z[t] << 16);
+        auto group_index = [&](int gi) -> int64_t {
+          return group_axis == 0 ? (r0 + gi) * gcols + tc            // group = row of the tile
+                                 : (int64_t)tr * gcols + c0 + gi;    // group = column of the tile
+        };
+        if (codes) {
+          // statistic codes of the beta2 groups of this tile: s_q[0..beta2), z_q[0..beta2)
+          for (int which = 0; which < 2; ++which) {
+            const uint8_t* src = which == 0 ? s_q : z_q;
+            for (int gq = 0; gq < beta2 / 2; ++gq) {
+              uint32_t v[2];
+              for (int h = 0; h < 2; ++h) {
+                v[h] = src[group_index(2 * gq + h)];
+                if (v[h] >= 8u) { bad.store(1); v[h] &= 7u; }
+              }
+              put_pair(stat.data(), 3, which * (beta2 / 2) + gq, v[0], v[1]);
+            }
+          }
+          const int nc = 3 * beta2 / 16;
+          stat[nc] = (uint32_t)s_s[t] | ((uint32_t)z_s[t] << 16);
+          if (g.layout == spqr::kBilevel) stat[nc + 1] = (uint32_t)s_z[t] | ((uint32_t)z_z[t] << 16);
+        } else {
+          for (int gi = 0; gi < beta2; ++gi)
+            stat[gi] = (uint32_t)s16[group_index(gi)] | ((uint32_t)z16[group_index(gi)] << 16);
+        }
         for (int d = 0; d < cd; ++d)
           std::memcpy(out + spqr::code_dword_offset(g, tr, tc, d), &code[d], 4);
         for (int d = 0; d < g.sd; ++d)
@@ -130,4 +160,4 @@ extern "C" const char* spqr_strerror(int status) {
   }
 }
 
-extern "C" int32_t spqr_version(void) { return (1 << 16) | SPQR_LAYOUT_V1; }
+extern "C" int32_t spqr_version(void) { return (1 << 16) | SPQR_LAYOUT_STATS16; }

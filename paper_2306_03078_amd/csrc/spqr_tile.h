@@ -180,11 +180,13 @@ __device__ __forceinline__ uint32_t pair_class_inline(const uint32_t* c, int q, 
 // Grid: one workgroup per strip of TR rows; blockDim.x = 64 * (waves per workgroup).
 // Dynamic LDS: n binary16 values of x (rounded up to 16 bytes).
 // ---------------------------------------------------------------------------
-template <int W, int TR, int TC, int AXIS>
+//   LV    statistic layout: 1 bilevel, 2 integer zero-point, 3 binary16 statistics per group
+template <int W, int TR, int TC, int AXIS, int LV = 1>
 struct TileRegs {
   static constexpr int KW = 256 * W / 128;
   static constexpr int B2 = AXIS == 0 ? TR : TC;
-  static constexpr int SD = 3 * B2 / 16 + 2;
+  static constexpr int NC = 3 * B2 / 16;     // dwords of 3-bit statistic codes (layouts 1 and 2)
+  static constexpr int SD = LV == 3 ? B2 : NC + (LV == 2 ? 1 : 2);
   static constexpr int SWF = SD / 4, SR = SD % 4;
   uint32_t c[4 * KW];
   uint32_t s[SD];
@@ -199,10 +201,10 @@ __device__ __forceinline__ V load_once(const V* p) {
   else return *p;
 }
 
-template <bool STREAM, int W, int TR, int TC, int AXIS>
-__device__ __forceinline__ void load_tile(TileRegs<W, TR, TC, AXIS>& t, const uint8_t* blk,
+template <bool STREAM, int W, int TR, int TC, int AXIS, int LV>
+__device__ __forceinline__ void load_tile(TileRegs<W, TR, TC, AXIS, LV>& t, const uint8_t* blk,
                                           int L, int lane) {
-  using T = TileRegs<W, TR, TC, AXIS>;
+  using T = TileRegs<W, TR, TC, AXIS, LV>;
   // statistics first: the tile's work starts with them (loads complete in order)
   const uint8_t* sb = blk + (int64_t)16 * T::KW * L;
 #pragma unroll

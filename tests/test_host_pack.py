@@ -24,7 +24,8 @@ def test_library_exports_every_declared_symbol():
     names = _declared(os.path.join(ROOT, "include", "spqr.h"))
     assert {"spqr_pack_check", "spqr_gemv", "spqr_gemv_fused", "spqr_gemv_grouped", "spqr_gemm_fused", "spqr_gemm_smallbatch",
             "spqr_gemm_smallbatch_ws", "spqr_gemm_fused_ws", "spqr_workspace_bytes", "spqr_dequant_dense", "spqr_set_option",
-            "spqr_pack_host", "spqr_packed_bytes", "spqr_strerror", "spqr_version"} <= names
+            "spqr_pack_host", "spqr_packed_bytes", "spqr_pack_host_layout", "spqr_packed_bytes_layout", "spqr_strerror",
+            "spqr_version"} <= names
     assert "spqr_plan_batch_steps" not in names      # a test hook, not part of the public interface
     hooks = _declared(os.path.join(ROOT, "paper_2306_03078_amd", "csrc", "spqr_test_hooks.h"))
     assert hooks == {"spqr_plan_batch_steps"}
@@ -42,6 +43,23 @@ def test_packed_size_is_the_papers_size_model(w, b1, b2, axis):
     m, n = 3 * tr, 5 * tc
     nbytes = P.packed_bytes(m, n, w, 3, 3, b1, b2, axis)
     assert 8.0 * nbytes / (m * n) == orc.average_bits(w, 3, 3, b1, b2)
+
+
+@pytest.mark.parametrize("w,b1,b2", [(3, 16, 16), (4, 16, 16), (3, 8, 32), (3, 48, 16), (4, 8, 64)])
+@pytest.mark.parametrize("axis", [0, 1])
+def test_packed_size_of_the_statistic_variants(w, b1, b2, axis):
+    # Sec. 5 ablations: integer zero-point (one second-level pair per tile), 16-bit statistics (none); no padding.
+    tr, tc = synth.tile_shape(b1, b2, axis)
+    m, n = 3 * tr, 5 * tc
+    assert 8.0 * P.packed_bytes(m, n, w, 3, 3, b1, b2, axis, P.SPQR_LAYOUT_ROUND_ZERO) / (m * n) \
+        == orc.average_bits_round_zero(w, 3, 3, b1, b2)
+    assert 8.0 * P.packed_bytes(m, n, w, 16, 16, b1, b2, axis, P.SPQR_LAYOUT_STATS16) / (m * n) \
+        == orc.average_bits_stats16(w, b1)
+    lib = P.load_library()
+    assert lib.spqr_packed_bytes_layout(P.SPQR_LAYOUT_STATS16, m, n, w, 3, 3, b1, b2, axis) == -3
+    assert lib.spqr_packed_bytes_layout(P.SPQR_LAYOUT_ROUND_ZERO, m, n, w, 16, 16, b1, b2, axis) == -3
+    assert lib.spqr_packed_bytes_layout(4, m, n, w, 3, 3, b1, b2, axis) == -3
+    assert lib.spqr_packed_bytes_layout(1, m, n, w, 3, 3, b1, b2, axis) == P.packed_bytes(m, n, w, 3, 3, b1, b2, axis)
 
 
 def test_printed_bit_counts_for_config_tiles():
@@ -80,6 +98,29 @@ def test_pack_round_trip_through_independent_reader(w, b1, b2, axis, ntr, ntc):
         assert np.array_equal(got[k].view(np.uint16), getattr(f, k).view(np.uint16)), k
 
 
+@pytest.mark.parametrize("layout,lv", [("round_zero", 2), ("stats16", 3)])
+@pytest.mark.parametrize("w,b1,b2,axis,ntr,ntc", [
+    (3, 16, 16, 1, 2, 3), (3, 16, 16, 0, 3, 70), (4, 16, 16, 1, 2, 130), (3, 8, 32, 1, 3, 65), (3, 8, 32, 0, 2, 129),
+    (3, 48, 16, 0, 2, 5), (4, 32, 64, 1, 2, 3),
+])
+def test_variant_pack_round_trip_through_independent_reader(layout, lv, w, b1, b2, axis, ntr, ntc):
+    tr, tc = synth.tile_shape(b1, b2, axis)
+    f = synth.make_matrix(ntr * tr, ntc * tc, w_bits=w, beta1=b1, beta2=b2, group_axis=axis, outlier_rate=0.0,
+                          seed=(22, w, b1, b2, axis), stat_layout=layout)
+    got = layout_reader.read_packed(P.pack_host(f), f.m, f.n, w, b1, b2, axis, lv)
+    assert np.array_equal(got["Q"], f.Q)
+    if lv == 2:
+        assert set(got) == {"Q", "s_q", "z_q", "s_s", "z_s"}
+        keys = ("s_q", "z_q", "s_s", "z_s")
+    else:
+        assert set(got) == {"Q", "s16", "z16"}
+        keys = ("s16", "z16")
+    for k in keys:
+        a, b = got[k], getattr(f, k)
+        assert np.array_equal(a.view(np.uint16) if a.dtype == np.float16 else a,
+                              b.view(np.uint16) if b.dtype == np.float16 else b), k
+
+
 def test_packer_rejects_out_of_range_codes():
     f = synth.make_matrix(32, 32, outlier_rate=0.0)
     f.Q[3, 3] = 9
@@ -99,6 +140,10 @@ def test_host_side_descriptor_checks_need_no_gpu():
     d.w_bits = 3
     assert lib.spqr_gemv(C.byref(d), None, None, 0, None) == -1      # packed is NULL
     d.layout_version = 2
+    assert lib.spqr_dequant_dense(C.byref(d), 0, None, None) == -1   # the integer zero-point layout: packed is NULL
+    d.layout_version = 3
+    assert lib.spqr_dequant_dense(C.byref(d), 0, None, None) == -3   # 16-bit statistics need s_bits = z_bits = 16
+    d.layout_version = 4
     assert lib.spqr_dequant_dense(C.byref(d), 0, None, None) == -3
 
 
