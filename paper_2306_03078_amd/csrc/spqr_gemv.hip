@@ -120,7 +120,7 @@ int tuned_batch_width(const Geometry& g, int want) {
   if (g.layout != kBilevel) want = 1;        // the other statistic layouts are built for one vector per launch
   for (int nb = want >= 4 ? 4 : (want >= 2 ? 2 : 1); nb >= 1; nb >>= 1) {
     LaunchPlan plan = {0, 0, 0, 0};
-    const int maxw = (g.w_bits == 3 && nb == 1) ? 16 : 8;
+    const int maxw = (g.w_bits == 3 && nb == 1 && g.layout != kStats16) ? 16 : 8;   // WavesPerGroup
     if (plan_launch(g, nb, maxw, 8, &plan)) return nb;   // 8 slots: the lowest occupancy any instance has
   }
   return 0;

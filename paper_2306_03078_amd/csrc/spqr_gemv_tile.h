@@ -290,7 +290,10 @@ __device__ __forceinline__ float strided16_sum(const float* prod, int lo, int hi
 // lane, 8 wavefronts 256; a 4-bit tile needs 32 code registers, twice with the
 // prefetch of the next step, and every further activation vector TR more
 // accumulators.
-template <int W, int NB> struct WavesPerGroup { static constexpr int MAX = (W == 3 && NB == 1) ? 16 : 8; };
+// Layout 3 keeps beta2 statistic dwords per tile instead of 8: it needs the 256.
+template <int W, int NB, int LV = 1> struct WavesPerGroup {
+  static constexpr int MAX = (W == 3 && NB == 1 && LV != 3) ? 16 : 8;
+};
 
 // NB activation vectors per launch: X holds NB rows of n binary16 values (row
 // stride n), Y NB rows of m outputs (row stride m).  NB = 1 is the GEMV.
@@ -655,7 +658,7 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
 }
 
 template <int W, int TR, int TC, int AXIS, bool PERM, int NB, int LV = 1>
-__global__ void __launch_bounds__((64 * WavesPerGroup<W, NB>::MAX))
+__global__ void __launch_bounds__((64 * WavesPerGroup<W, NB, LV>::MAX))
 gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restrict__ y, int y_dtype,
                     int chunk_cap, int strips_per_group, int waves_per_strip) {
   gemv_tile256_body<W, TR, TC, AXIS, PERM, NB, LV>(A, x, y, y_dtype, chunk_cap, blockIdx.x * strips_per_group,
@@ -680,7 +683,7 @@ struct FusedArgs {
 };
 
 template <int W, int TR, int TC, int AXIS, int LV = 1>
-__global__ void __launch_bounds__((64 * WavesPerGroup<W, 1>::MAX))
+__global__ void __launch_bounds__((64 * WavesPerGroup<W, 1, LV>::MAX))
 gemv_tile256_fused_kernel(FusedArgs F, int y_dtype, int chunk_cap, int strips_per_group, int waves_per_strip) {
   int i = 0;
   while (i + 1 < F.count && (int)blockIdx.x >= F.first[i + 1]) ++i;   // workgroup-uniform, count <= SPQR_MAX_FUSED
