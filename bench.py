@@ -219,6 +219,23 @@ def run_sweep(path, P, synth, torch, dev):
                                  "frac_of_hbm_peak": round(nbytes / us / 1e3 / HBM_PEAK_GBS, 4)})
                 del A
                 torch.cuda.empty_cache()
+    # the statistic variants of the ablations (Sec. 5) on the largest and the headline-config shapes, batch 1
+    for cfg, li in ((1, 0), (4, 0), (4, 4), (4, 6)):
+        sp = synth.config_layers(cfg)[li]
+        for lay in ("round_zero", "stats16"):
+            A = P.SpQRMatrix.from_logical(synth.make_config_layer(cfg, li, group_axis=1, stat_layout=lay), dev)
+            copies = max(2, int(600e6 // A.compressed_bytes()) + 1)
+            X = torch.from_numpy(synth.make_x(sp.n, 1, seed=(cfg, li, 1))).to(dev)
+            us = time_layer(P, torch, A, X, copies)
+            nbytes = algorithmic_bytes(A, 1)
+            rows.append({"config": cfg, "layer": f"{sp.name} [{lay}]", "m": sp.m, "n": sp.n, "w_bits": sp.w_bits,
+                         "beta1": sp.beta1, "beta2": sp.beta2, "group_axis": 1, "batch": 1,
+                         "outliers": f"{sp.outlier_rate:g} {sp.outlier_structure}",
+                         "compressed_MB": round(nbytes / 1e6, 2), "us": round(us, 2),
+                         "GBps": round(nbytes / us / 1e3, 1),
+                         "frac_of_hbm_peak": round(nbytes / us / 1e3 / HBM_PEAK_GBS, 4)})
+            del A
+            torch.cuda.empty_cache()
     run_block_sweep(rows, P, synth, torch, dev)
     with open(path, "w") as fh:
         json.dump(rows, fh, indent=1)

@@ -272,7 +272,7 @@ def config_layers(cfg: int) -> List[LayerSpec]:
     return list(CONFIGS[cfg])
 
 
-def make_config_layer(cfg: int, layer: int, group_axis: int = 1) -> SpQRLogical:
+def make_config_layer(cfg: int, layer: int, group_axis: int = 1, stat_layout: str = "bilevel") -> SpQRLogical:
     """Logical matrix of layer `layer` of configuration `cfg`.
 
     Seed key is (cfg, layer); configuration 0 therefore uses seed (0, 0).
@@ -280,4 +280,4 @@ def make_config_layer(cfg: int, layer: int, group_axis: int = 1) -> SpQRLogical:
     sp = CONFIGS[cfg][layer]
     return make_matrix(sp.m, sp.n, w_bits=sp.w_bits, beta1=sp.beta1, beta2=sp.beta2,
                        group_axis=group_axis, outlier_rate=sp.outlier_rate,
-                       outlier_structure=sp.outlier_structure, seed=(cfg, layer))
+                       outlier_structure=sp.outlier_structure, seed=(cfg, layer), stat_layout=stat_layout)
