@@ -112,15 +112,20 @@ hipError_t kernel_slots(const void* fn, int max_dynamic, PerDevice* known, int* 
 
 // Largest number of activation vectors (1, 2 or 4, at most `want`) one launch of
 // the tuned kernel can take for this geometry; 0 if there is no tuned kernel.
+static bool wide_tile(const Geometry& g) {   // 8 x 64, 3-bit, group_axis 1, bilevel: its own instance, one vector per launch
+  return g.tile_rows == 8 && g.tile_cols == 64 && g.axis == 1 && g.w_bits == 3 && g.layout == kBilevel;
+}
+
 int tuned_batch_width(const Geometry& g, int want) {
-  if (g.tile_rows * g.tile_cols != 256) return 0;
-  const bool shape_ok = g.axis == 1 ? ((g.tile_rows == 16 && g.tile_cols == 16) || (g.tile_rows == 8 && g.tile_cols == 32))
-                                    : ((g.tile_rows == 16 && g.tile_cols == 16) || (g.tile_rows == 32 && g.tile_cols == 8));
+  const bool wide = wide_tile(g);
+  if (g.tile_rows * g.tile_cols != 256 && !wide) return 0;
+  const bool shape_ok = wide || (g.axis == 1 ? ((g.tile_rows == 16 && g.tile_cols == 16) || (g.tile_rows == 8 && g.tile_cols == 32))
+                                             : ((g.tile_rows == 16 && g.tile_cols == 16) || (g.tile_rows == 32 && g.tile_cols == 8)));
   if (!shape_ok) return 0;
-  if (g.layout != kBilevel) want = 1;        // the other statistic layouts are built for one vector per launch
+  if (g.layout != kBilevel || wide) want = 1;  // built for one vector per launch
   for (int nb = want >= 4 ? 4 : (want >= 2 ? 2 : 1); nb >= 1; nb >>= 1) {
     LaunchPlan plan = {0, 0, 0, 0};
-    const int maxw = (g.w_bits == 3 && nb == 1 && g.layout != kStats16) ? 16 : 8;   // WavesPerGroup
+    const int maxw = (g.w_bits == 3 && nb == 1 && g.layout != kStats16 && !wide) ? 16 : 8;   // WavesPerGroup
     if (plan_launch(g, nb, maxw, 8, &plan)) return nb;   // 8 slots: the lowest occupancy any instance has
   }
   return 0;
@@ -129,6 +134,7 @@ int tuned_batch_width(const Geometry& g, int want) {
 bool has_tuned_gemv(const Geometry& g) { return tuned_batch_width(g, 1) == 1; }
 
 hipError_t launch_tuned(const DevMatrix& A, const uint16_t* x, int nb, void* y, int y_dtype, hipStream_t stream) {
+  if (wide_tile(A.g)) return launch_tuned_l1w(A, x, nb, y, y_dtype, stream);
   if (A.g.layout == kBilevel) return launch_tuned_l1(A, x, nb, y, y_dtype, stream);
   if (A.g.layout == kRoundZero) return launch_tuned_l2(A, x, nb, y, y_dtype, stream);
   return launch_tuned_l3(A, x, nb, y, y_dtype, stream);
@@ -140,6 +146,7 @@ hipError_t launch_gemv_grouped(const DevMatrix* As, int count, const uint16_t* c
                                int y_dtype, hipStream_t stream) {
   const Geometry& g = As[0].g;
   if (count > 1 && option(SPQR_OPT_FORCE_GENERIC) == 0 && As[0].perm == nullptr && tuned_batch_width(g, 1) == 1) {
+    if (wide_tile(g)) return launch_fused_l1w(As, count, xs, ys, y_dtype, stream);
     if (g.layout == kBilevel) return launch_fused_l1(As, count, xs, ys, y_dtype, stream);
     if (g.layout == kRoundZero) return launch_fused_l2(As, count, xs, ys, y_dtype, stream);
     return launch_fused_l3(As, count, xs, ys, y_dtype, stream);

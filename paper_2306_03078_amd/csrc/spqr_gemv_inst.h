@@ -23,10 +23,13 @@ struct LaunchPlan { int P; int R; int cap; size_t lds; };
 // spqr_gemv.hip
 bool plan_launch(const Geometry& g, int nb, int max_waves, int slots, LaunchPlan* out);
 hipError_t kernel_slots(const void* fn, int max_dynamic, PerDevice* known, int* slots);
-// one pair per statistic layout (spqr_gemv_l1/l2/l3.hip)
+// one pair per statistic layout (spqr_gemv_l1/l2/l3.hip), one for the 8 x 64 tiles of layout 1 (spqr_gemv_l1w.hip)
 hipError_t launch_tuned_l1(const DevMatrix& A, const uint16_t* x, int nb, void* y, int y_dtype, hipStream_t stream);
 hipError_t launch_tuned_l2(const DevMatrix& A, const uint16_t* x, int nb, void* y, int y_dtype, hipStream_t stream);
 hipError_t launch_tuned_l3(const DevMatrix& A, const uint16_t* x, int nb, void* y, int y_dtype, hipStream_t stream);
+hipError_t launch_tuned_l1w(const DevMatrix& A, const uint16_t* x, int nb, void* y, int y_dtype, hipStream_t stream);
+hipError_t launch_fused_l1w(const DevMatrix* As, int count, const uint16_t* const* xs, void* const* ys, int y_dtype,
+                            hipStream_t stream);
 hipError_t launch_fused_l1(const DevMatrix* As, int count, const uint16_t* const* xs, void* const* ys, int y_dtype,
                            hipStream_t stream);
 hipError_t launch_fused_l2(const DevMatrix* As, int count, const uint16_t* const* xs, void* const* ys, int y_dtype,
@@ -37,7 +40,7 @@ hipError_t launch_fused_l3(const DevMatrix* As, int count, const uint16_t* const
 template <int W, int TR, int TC, int AXIS, int NB, int LV>
 static hipError_t launch_tile256(const DevMatrix& A, const uint16_t* x, void* y, int y_dtype,
                                  hipStream_t stream) {
-  constexpr int MAXW = WavesPerGroup<W, NB, LV>::MAX;
+  constexpr int MAXW = WavesPerGroup<W, NB, LV, TR * TC>::MAX;
   constexpr int MAX_DYNAMIC = 160 * 1024 - static_lds_bytes(TR, NB) - 1024;   // static + dynamic <= 160 KB
   static PerDevice known[2];                 // wavefront slots per CU of the instance, 0 = not asked yet
   const void* fn = A.perm ? reinterpret_cast<const void*>(&gemv_tile256_kernel<W, TR, TC, AXIS, true, NB, LV>)
@@ -67,7 +70,7 @@ static hipError_t launch_tile256(const DevMatrix& A, const uint16_t* x, void* y,
 template <int W, int TR, int TC, int AXIS, int LV>
 static hipError_t launch_fused256(const DevMatrix* As, int count, const uint16_t* const* xs, void* const* ys,
                                   int y_dtype, hipStream_t stream) {
-  constexpr int MAXW = WavesPerGroup<W, 1, LV>::MAX;
+  constexpr int MAXW = WavesPerGroup<W, 1, LV, TR * TC>::MAX;
   constexpr int MAX_DYNAMIC = 160 * 1024 - static_lds_bytes(TR, 1) - 1024;
   static PerDevice known;
   int slots = 0;
@@ -107,11 +110,11 @@ static hipError_t launch_fused256(const DevMatrix* As, int count, const uint16_t
   return hipGetLastError();
 }
 
-// Defines launch_tuned_l<LV> and launch_fused_l<LV> for the tile shapes in CASES (a list of
-// CASE(w_bits, tile_rows, tile_cols, group_axis)) and the vector counts NBS (SPQR_NB_124 or SPQR_NB_1).
+// Defines launch_tuned_<NAME> and launch_fused_<NAME> for the tile shapes in CASES (a list of
+// CASE(w_bits, tile_rows, tile_cols, group_axis, layout)) and the vector counts NBS (SPQR_NB_124 or SPQR_NB_1).
 #define SPQR_NB_124(NBCASE) NBCASE(1) NBCASE(2) NBCASE(4)
 #define SPQR_NB_1(NBCASE) NBCASE(1)
-#define SPQR_DEFINE_GEMV_LAYOUT(LV, CASES, NBS)                                                                    \
+#define SPQR_DEFINE_GEMV_UNIT(NAME, LV, CASES, NBS)                                                                  \
   template <int NB>                                                                                                \
   static hipError_t launch_tuned_nb_(const DevMatrix& A, const uint16_t* x, void* y, int y_dtype,                  \
                                      hipStream_t stream) {                                                         \
@@ -119,12 +122,12 @@ static hipError_t launch_fused256(const DevMatrix* As, int count, const uint16_t
     CASES(SPQR_TUNED_CASE_, LV)                                                                                    \
     return hipErrorInvalidValue;                                                                                   \
   }                                                                                                                \
-  hipError_t launch_tuned_l##LV(const DevMatrix& A, const uint16_t* x, int nb, void* y, int y_dtype,               \
+  hipError_t launch_tuned_##NAME(const DevMatrix& A, const uint16_t* x, int nb, void* y, int y_dtype,               \
                                 hipStream_t stream) {                                                              \
     NBS(SPQR_NB_CASE_)                                                                                             \
     return hipErrorInvalidValue;                                                                                   \
   }                                                                                                                \
-  hipError_t launch_fused_l##LV(const DevMatrix* As, int count, const uint16_t* const* xs, void* const* ys,        \
+  hipError_t launch_fused_##NAME(const DevMatrix* As, int count, const uint16_t* const* xs, void* const* ys,        \
                                 int y_dtype, hipStream_t stream) {                                                 \
     const Geometry& g = As[0].g;                                                                                   \
     CASES(SPQR_FUSED_CASE_, LV)                                                                                    \
@@ -142,5 +145,7 @@ static hipError_t launch_fused256(const DevMatrix* As, int count, const uint16_t
 #define SPQR_GEMV_SHAPES(CASE, LV)                                                          \
   CASE(3, 16, 16, 1, LV) CASE(4, 16, 16, 1, LV) CASE(3, 8, 32, 1, LV) CASE(4, 8, 32, 1, LV) \
   CASE(3, 16, 16, 0, LV) CASE(4, 16, 16, 0, LV) CASE(3, 32, 8, 0, LV) CASE(4, 32, 8, 0, LV)
+// beta1 = 8, beta2 = 64 (the size-matched setting of Sec. 5), 3-bit, group_axis 1
+#define SPQR_GEMV_WIDE_SHAPES(CASE, LV) CASE(3, 8, 64, 1, LV)
 
 }  // namespace spqr

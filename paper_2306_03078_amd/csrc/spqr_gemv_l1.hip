@@ -2,5 +2,5 @@
 #include "spqr_gemv_inst.h"
 
 namespace spqr {
-SPQR_DEFINE_GEMV_LAYOUT(1, SPQR_GEMV_SHAPES, SPQR_NB_124)
+SPQR_DEFINE_GEMV_UNIT(l1, 1, SPQR_GEMV_SHAPES, SPQR_NB_124)
 }  // namespace spqr

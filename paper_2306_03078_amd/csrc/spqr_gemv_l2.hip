@@ -2,5 +2,5 @@
 #include "spqr_gemv_inst.h"
 
 namespace spqr {
-SPQR_DEFINE_GEMV_LAYOUT(2, SPQR_GEMV_SHAPES, SPQR_NB_1)
+SPQR_DEFINE_GEMV_UNIT(l2, 2, SPQR_GEMV_SHAPES, SPQR_NB_1)
 }  // namespace spqr

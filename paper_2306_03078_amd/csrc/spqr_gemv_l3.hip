@@ -2,5 +2,5 @@
 #include "spqr_gemv_inst.h"
 
 namespace spqr {
-SPQR_DEFINE_GEMV_LAYOUT(3, SPQR_GEMV_SHAPES, SPQR_NB_1)
+SPQR_DEFINE_GEMV_UNIT(l3, 3, SPQR_GEMV_SHAPES, SPQR_NB_1)
 }  // namespace spqr

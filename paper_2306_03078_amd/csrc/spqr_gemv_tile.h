@@ -52,16 +52,22 @@ __device__ __forceinline__ uint32_t high_halves(uint32_t a, uint32_t b) {
   return __builtin_amdgcn_perm(b, a, 0x07060302u);
 }
 
-template <int W, int TR, int TC, int AXIS, int NB, int LV>
-__device__ __forceinline__ void tile_fma(const TileRegs<W, TR, TC, AXIS, LV>& t,
+// A tile wider than 32 columns (8 x 64, group_axis 1: Sec. 5's beta2 = 64) is worked off in column halves: TC is the
+// width of the view, TCF the tile's, H the half; a half has whole 3-bit triples per row (TC / 2 = 16 pairs), so
+// classes, phases and shifted words are those of an 8 x 32 tile.
+template <int W, int TR, int TC, int AXIS, int NB, int LV, int TCF = TC, int H = 0>
+__device__ __forceinline__ void tile_fma(const TileRegs<W, TR, TCF, AXIS, LV>& t,
                                          const uint32_t* xpair /* TC/2 dwords in LDS, vector 0 */,
                                          int xstride, bool valid, float (&acc)[NB][TR],
                                          float (&csum)[NB][RowPhases<W, TC>::N], const ClassConsts& k,
                                          const PairConsts& k1, const PairConsts& k3) {
-  using T = TileRegs<W, TR, TC, AXIS, LV>;
+  using T = TileRegs<W, TR, TCF, AXIS, LV>;
+  static_assert(TCF == TC || (AXIS == 1 && TC == 32 && TCF == 2 * TC && H < 2), "column halves of an 8 x 64 tile");
   constexpr bool SHARED = SharedShifts<TC>::value;
   using CC = CodeClass<W, SHARED>;
-  constexpr int PPR = TC / 2;
+  constexpr int PPR = TC / 2;                // pairs per row of the view
+  constexpr int PPRF = TCF / 2;              // pairs per row of the tile
+  constexpr int P0 = H * PPR;                // first pair of the view inside a row, first group pair of the view
   constexpr int NPH = RowPhases<W, TC>::N;
   constexpr float SCALE = (float)(1 << W);
   constexpr bool CODES = LV != 3;            // first-level statistics are 3-bit codes
@@ -116,7 +122,10 @@ __device__ __forceinline__ void tile_fma(const TileRegs<W, TR, TC, AXIS, LV>& t,
 #pragma unroll
       for (int c = 0; c < 3; ++c) c2k[c] = valid ? fmaf(-8.f * (C3::K(c) - 1.f), s_s, -s_s * z_s - 8.f * s_s) : 0.f;
 #pragma unroll
-      for (int j = 0; j < 3; ++j) { sws.s[j] = t.s[j] >> 9; swz.s[j] = t.s[3 * (PPR / 16) + j] >> 9; }
+      for (int j = 0; j < 3; ++j) {           // the triples that hold the view's scale and zero codes
+        sws.s[j] = t.s[3 * (P0 / 16) + j] >> 9;
+        swz.s[j] = t.s[3 * ((T::B2 / 2 + P0) / 16) + j] >> 9;
+      }
     }
     float Zd[NB];
 #pragma unroll
@@ -126,12 +135,13 @@ __device__ __forceinline__ void tile_fma(const TileRegs<W, TR, TC, AXIS, LV>& t,
       half2_t zq;
       float s0, s1;
       if constexpr (CODES) {
-        const half2_t sq = as_half2(STATS_IN_PLACE ? pair_class_f16<3>(t.s, sws, p, k) : pair_f16<3>(t.s, p, k3));
-        zq = as_half2(STATS_IN_PLACE ? pair_class_f16<3>(t.s, swz, T::B2 / 2 + p, k) : pair_f16<3>(t.s, T::B2 / 2 + p, k3));
+        const half2_t sq = as_half2(STATS_IN_PLACE ? pair_class_f16<3>(t.s, sws, P0 + p, k) : pair_f16<3>(t.s, P0 + p, k3));
+        zq = as_half2(STATS_IN_PLACE ? pair_class_f16<3>(t.s, swz, T::B2 / 2 + P0 + p, k)
+                                     : pair_f16<3>(t.s, T::B2 / 2 + P0 + p, k3));
         const float c2p = STATS_IN_PLACE ? c2k[CodeClass<3, true>::of_pair(p)] : c2;
         s0 = fmaf((float)sq.x, c1, c2p); s1 = fmaf((float)sq.y, c1, c2p);
       } else {                               // dword j of the statistics: s_hat_j | z_hat_j << 16
-        const uint32_t d0 = t.s[2 * p], d1 = t.s[2 * p + 1];
+        const uint32_t d0 = t.s[2 * (P0 + p)], d1 = t.s[2 * (P0 + p) + 1];
         s0 = c1 * h2f((uint16_t)(d0 & 0xFFFF)); s1 = c1 * h2f((uint16_t)(d1 & 0xFFFF));
         zq = as_half2(high_halves(d0, d1));
       }
@@ -173,8 +183,9 @@ __device__ __forceinline__ void tile_fma(const TileRegs<W, TR, TC, AXIS, LV>& t,
       for (int bi = 0; bi < NB; ++bi) d[bi] = acc[bi][r];
 #pragma unroll
       for (int p = 0; p < PPR; ++p) {
-        if constexpr (SHARED) refresh_shifted<W>(sw, t.c, r * PPR + p);
-        const half2_t q2 = as_half2(SHARED ? pair_class_f16<W>(t.c, sw, r * PPR + p, k) : pair_f16<W>(t.c, r * PPR + p, k1));
+        const int q = r * PPRF + P0 + p;     // pair of the tile
+        if constexpr (SHARED) refresh_shifted<W>(sw, t.c, q);
+        const half2_t q2 = as_half2(SHARED ? pair_class_f16<W>(t.c, sw, q, k) : pair_f16<W>(t.c, q, k1));
 #pragma unroll
         for (int bi = 0; bi < NB; ++bi) d[bi] = __builtin_amdgcn_fdot2(q2, as_half2(xp[bi][p]), d[bi], false);
       }
@@ -291,8 +302,9 @@ __device__ __forceinline__ float strided16_sum(const float* prod, int lo, int hi
 // prefetch of the next step, and every further activation vector TR more
 // accumulators.
 // Layout 3 keeps beta2 statistic dwords per tile instead of 8: it needs the 256.
-template <int W, int NB, int LV = 1> struct WavesPerGroup {
-  static constexpr int MAX = (W == 3 && NB == 1 && LV != 3) ? 16 : 8;
+// So does a tile of 512 codes (48 code registers per buffer).
+template <int W, int NB, int LV = 1, int CODES = 256> struct WavesPerGroup {
+  static constexpr int MAX = (W == 3 && NB == 1 && LV != 3 && CODES == 256) ? 16 : 8;
 };
 
 // NB activation vectors per launch: X holds NB rows of n binary16 values (row
@@ -311,8 +323,9 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
                                                   void* __restrict__ y, int y_dtype, int chunk_cap,
                                                   const int first_strip, const int R, const int P) {
   using T = TileRegs<W, TR, TC, AXIS, LV>;
-  static_assert(TR * TC == 256, "tile must hold 256 codes");
+  static_assert(TR * TC == 256 || (TR == 8 && TC == 64 && AXIS == 1), "tiles of 256 codes, or 8 x 64");
   static_assert((TC / 2) % 4 == 0, "x pairs are read as 16-byte LDS words");
+  constexpr int TCV = TR * TC == 256 ? TC : TC / 2;      // columns tile_fma takes at a time
   constexpr int TILE_BYTES = 16 * T::KW + 4 * T::SD;
   constexpr int MAX_WAVES = 16;
   constexpr int XCH = 4 * NB;                // 16-byte chunks of x a thread keeps in flight
@@ -423,7 +436,7 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
   __syncthreads();                           // x is staged
 
   // ---- dense part -------------------------------------------------------------
-  constexpr int NPH = RowPhases<W, TC>::N;
+  constexpr int NPH = RowPhases<W, TCV>::N;
   float acc[NB][TR], csum[NB][NPH];
 #pragma unroll
   for (int bi = 0; bi < NB; ++bi) {
@@ -434,13 +447,18 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
   }
   ClassConsts kc = {};
   PairConsts k1 = {};
-  if constexpr (SharedShifts<TC>::value) kc = make_class_consts<W>(); else k1 = make_pair_consts<W>();
+  if constexpr (SharedShifts<TCV>::value) kc = make_class_consts<W>(); else k1 = make_pair_consts<W>();
   const PairConsts k3 = make_pair_consts<3>();
   const uint32_t* xs32 = reinterpret_cast<const uint32_t*>(xs);
   const bool heavy = nchunks > nthreads;     // workgroup-uniform
-#define SPQR_TILE_FMA(t, L, st)                                                                           \
-  tile_fma<W, TR, TC, AXIS, NB, LV>(t, xs32 + (64 * (st) + min(lane, (L) - 1)) * (TC / 2), n >> 1, live && lane < (L), \
-                                acc, csum, kc, k1, k3)
+#define SPQR_TILE_FMA(t, L, st)                                                                            \
+  do {                                                                                                     \
+    const uint32_t* xt_ = xs32 + (64 * (st) + min(lane, (L) - 1)) * (TC / 2);                              \
+    const bool valid_ = live && lane < (L);                                                                \
+    tile_fma<W, TR, TCV, AXIS, NB, LV, TC, 0>(t, xt_, n >> 1, valid_, acc, csum, kc, k1, k3);             \
+    if constexpr (TCV != TC)                                                                               \
+      tile_fma<W, TR, TCV, AXIS, NB, LV, TC, 1>(t, xt_ + TCV / 2, n >> 1, valid_, acc, csum, kc, k1, k3); \
+  } while (0)
   // Two steps per trip, registers ping-pong; the loop has its one exit at the
   // bottom (a second exit would be merged with it through a block that makes the
   // compiler wait for every load at the top of the loop).  t0 holds step `step`.
@@ -658,7 +676,7 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
 }
 
 template <int W, int TR, int TC, int AXIS, bool PERM, int NB, int LV = 1>
-__global__ void __launch_bounds__((64 * WavesPerGroup<W, NB, LV>::MAX))
+__global__ void __launch_bounds__((64 * WavesPerGroup<W, NB, LV, TR * TC>::MAX))
 gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restrict__ y, int y_dtype,
                     int chunk_cap, int strips_per_group, int waves_per_strip) {
   gemv_tile256_body<W, TR, TC, AXIS, PERM, NB, LV>(A, x, y, y_dtype, chunk_cap, blockIdx.x * strips_per_group,
@@ -683,7 +701,7 @@ struct FusedArgs {
 };
 
 template <int W, int TR, int TC, int AXIS, int LV = 1>
-__global__ void __launch_bounds__((64 * WavesPerGroup<W, 1, LV>::MAX))
+__global__ void __launch_bounds__((64 * WavesPerGroup<W, 1, LV, TR * TC>::MAX))
 gemv_tile256_fused_kernel(FusedArgs F, int y_dtype, int chunk_cap, int strips_per_group, int waves_per_strip) {
   int i = 0;
   while (i + 1 < F.count && (int)blockIdx.x >= F.first[i + 1]) ++i;   // workgroup-uniform, count <= SPQR_MAX_FUSED

@@ -173,9 +173,9 @@ __device__ __forceinline__ uint32_t pair_class_inline(const uint32_t* c, int q, 
 }
 
 // ---------------------------------------------------------------------------
-// Fused GEMV for tiles of 256 codes.
+// Fused GEMV for tiles of 256 codes (and of 8 x 64 codes, group_axis 1).
 //   W     code width (3, 4)
-//   TR,TC tile rows / columns, TR*TC == 256
+//   TR,TC tile rows / columns, TR*TC == 256 (512)
 //   AXIS  0: groups are tile rows (beta2 = TR), 1: groups are tile columns (beta2 = TC)
 // Grid: one workgroup per strip of TR rows; blockDim.x = 64 * (waves per workgroup).
 // Dynamic LDS: n binary16 values of x (rounded up to 16 bytes).
@@ -183,7 +183,7 @@ __device__ __forceinline__ uint32_t pair_class_inline(const uint32_t* c, int q, 
 //   LV    statistic layout: 1 bilevel, 2 integer zero-point, 3 binary16 statistics per group
 template <int W, int TR, int TC, int AXIS, int LV = 1>
 struct TileRegs {
-  static constexpr int KW = 256 * W / 128;
+  static constexpr int KW = TR * TC * W / 128;
   static constexpr int B2 = AXIS == 0 ? TR : TC;
   static constexpr int NC = 3 * B2 / 16;     // dwords of 3-bit statistic codes (layouts 1 and 2)
   static constexpr int SD = LV == 3 ? B2 : NC + (LV == 2 ? 1 : 2);

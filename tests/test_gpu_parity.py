@@ -48,6 +48,8 @@ SHAPES = [
     (3, 8, 32, 1, 5, 67), (3, 8, 32, 0, 2, 1100), (4, 8, 32, 1, 2, 64), (4, 8, 32, 0, 1, 129),
     (3, 16, 16, 1, 1, 1), (3, 16, 16, 1, 2, 1100),
     (3, 16, 32, 0, 2, 5), (4, 32, 16, 1, 2, 9),          # no tuned kernel: generic path
+    (3, 8, 64, 1, 5, 67), (3, 8, 64, 1, 3, 700), (3, 8, 64, 1, 1, 1),   # beta2 = 64: tiles of 8 x 64, column halves
+    (3, 8, 64, 0, 1, 9), (4, 8, 64, 1, 2, 5),            # beta2 = 64 without a tuned kernel
 ]
 
 
@@ -106,7 +108,7 @@ def test_gemv_matches_oracle(P, w, b1, b2, axis, ntr, ntc):
 
 
 @pytest.mark.parametrize("w,b1,b2,axis", [(3, 16, 16, 1), (3, 16, 16, 0), (4, 16, 16, 1), (3, 8, 32, 1),
-                                          (3, 8, 32, 0)])
+                                          (3, 8, 32, 0), (3, 8, 64, 1)])
 @pytest.mark.parametrize("b", [1, 2, 3, 4, 8, 16])
 def test_smallbatch_matches_oracle(P, w, b1, b2, axis, b):
     f = make(w, b1, b2, axis, 3, 70)
@@ -125,7 +127,7 @@ def test_smallbatch_matches_oracle(P, w, b1, b2, axis, b):
 @pytest.mark.parametrize("structure,rate", [("none", 0.0), ("rows8cols4", 0.03), ("cols64", 0.08),
                                             ("zipf", 0.02), ("uniform", 0.3), ("uniform", 0.003),
                                             ("uniform", 0.95), ("zipf", 0.2)])
-@pytest.mark.parametrize("w,b1,b2,axis", [(3, 16, 16, 0), (3, 16, 16, 1), (3, 8, 32, 1), (4, 8, 32, 0)])
+@pytest.mark.parametrize("w,b1,b2,axis", [(3, 16, 16, 0), (3, 16, 16, 1), (3, 8, 32, 1), (4, 8, 32, 0), (3, 8, 64, 1)])
 def test_outlier_structures(P, structure, rate, w, b1, b2, axis):
     # full rows, full columns, Zipf row counts, nearly empty rows (chunks spanning
     # several rows, empty rows) and strips with more entries than one round holds
@@ -289,7 +291,7 @@ def test_runs_on_a_side_stream(P):
     assert rel_l2(y.cpu().numpy(), orc.matvec(f, synth.make_x(f.n, 1, seed=(73,)))[0]) <= REL_L2
 
 
-@pytest.mark.parametrize("w,b1,b2,axis,ntc", [(3, 16, 16, 1, 70), (4, 16, 16, 0, 130), (3, 8, 32, 1, 67),
+@pytest.mark.parametrize("w,b1,b2,axis,ntc", [(3, 16, 16, 1, 70), (4, 16, 16, 0, 130), (3, 8, 32, 1, 67), (3, 8, 64, 1, 67),
                                               (3, 32, 16, 1, 9)])          # the last has no tuned kernel
 def test_fused_projections_share_one_input(P, w, b1, b2, axis, ntc):
     """q/k/v-like: several matrices of different heights fed by one x, one call.
