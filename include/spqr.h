@@ -241,8 +241,16 @@ int spqr_gemv(const spqr_matrix_t* A, const uint16_t* x_f16, void* y, int y_dtyp
  * 10 us more per call), on further streams one from a pool of the library's
  * own.  If no scratch can be had, the slices of 4 run instead.  Callers that
  * must not allocate or synchronise use spqr_gemm_smallbatch_ws.
- * Results are deterministic (fixed summation order) on either path; the two
- * differ by rounding only (both within the product tolerance).
+ * Large batches (48 vectors and more, the prompt phase of Sec. 5 "Inference
+ * Time"; tiles of 256 codes, SPQR_LAYOUT_V1, Y 16-byte aligned): the matrix is
+ * dequantised once into a dense binary16 copy in scratch (2 bytes per weight,
+ * rows padded to a multiple of 64 columns; with a permutation b*n*2 bytes more),
+ * the outliers are added into the copy, and one matrix-core kernel multiplies
+ * the whole batch with it.  Where that much scratch cannot be had (a captured
+ * call without a workspace, a workspace smaller than spqr_workspace_bytes says)
+ * the slices of 16 run instead.
+ * Results are deterministic (fixed summation order) on every path; the paths
+ * differ by rounding only (all within the product tolerance).
  * X: [b][n] binary16 row-major.  Y: [b][m] of y_dtype, overwritten. */
 int spqr_gemm_smallbatch(const spqr_matrix_t* A, const uint16_t* X_f16, int b, void* Y,
                          int y_dtype, void* stream);
@@ -337,18 +345,24 @@ int spqr_gemv_grouped(const spqr_matrix_t* const* A, int count, const uint16_t* 
  *   SPQR_OPT_BATCH_PATH    SPQR_BATCH_PATH_AUTO (0): the library's rule picks the
  *                          kernels of a batch; _VECTOR (1) / _MATRIX (2): slices
  *                          of 4 on the vector kernel / slices of 16 on the
- *                          matrix cores wherever both exist
+ *                          matrix cores wherever both exist (and never the dense
+ *                          copy); _DENSE (3): the dense-copy path of large
+ *                          batches for any batch it exists for
  *   SPQR_OPT_FORCE_GENERIC 1: every product takes the element-wise fallback
  *                          kernel
  *   SPQR_OPT_BATCH_STEPS   k > 0: the matrix-core path's dense launch gives every
- *                          workgroup min(k, steps) steps of 64 tiles */
+ *                          workgroup min(k, steps) steps of 64 tiles
+ *   SPQR_OPT_DENSE_ROWS    64 or 128: rows per workgroup of the large-batch
+ *                          multiply (0: the library's rule) */
 #define SPQR_OPT_BATCH_PATH     0
 #define SPQR_OPT_FORCE_GENERIC  1
 #define SPQR_OPT_BATCH_STEPS    2
-#define SPQR_OPT_COUNT_         3
+#define SPQR_OPT_DENSE_ROWS     3
+#define SPQR_OPT_COUNT_         4
 #define SPQR_BATCH_PATH_AUTO    0
 #define SPQR_BATCH_PATH_VECTOR  1
 #define SPQR_BATCH_PATH_MATRIX  2
+#define SPQR_BATCH_PATH_DENSE   3
 int spqr_set_option(int option, int value);
 
 /* Debug decode (Alg. 1 `dequantize`, applied twice as in `fit_statistics`: first to

@@ -97,9 +97,10 @@ extern "C" int spqr_pack_check(const spqr_matrix_t* A, uint32_t flags, void* str
 extern "C" int spqr_set_option(int option, int value) {
   bool ok = true;
   switch (option) {
-    case SPQR_OPT_BATCH_PATH: ok = value >= SPQR_BATCH_PATH_AUTO && value <= SPQR_BATCH_PATH_MATRIX; break;
+    case SPQR_OPT_BATCH_PATH: ok = value >= SPQR_BATCH_PATH_AUTO && value <= SPQR_BATCH_PATH_DENSE; break;
     case SPQR_OPT_FORCE_GENERIC: ok = value == 0 || value == 1; break;
     case SPQR_OPT_BATCH_STEPS: ok = value >= 0; break;
+    case SPQR_OPT_DENSE_ROWS: ok = value == 0 || value == 64 || value == 128; break;
     default: ok = false;
   }
   return ok && spqr::set_option(option, value) ? SPQR_OK : SPQR_ERR_PARAM;
@@ -223,7 +224,7 @@ extern "C" int spqr_gemm_smallbatch_noalloc(const spqr_matrix_t* A, const uint16
   int rc = check_batch_call(&A, 1, X_f16, b, &Y, y_dtype, &D);
   if (rc) return rc;
   // sizes beyond the static array are refused before anything is launched
-  if (spqr::workspace_bound(&D, 1, b) > (size_t)SPQR_STATIC_SCRATCH_BYTES) return SPQR_ERR_WORKSPACE;
+  if (spqr::workspace_bound(&D, 1, b, false) > (size_t)SPQR_STATIC_SCRATCH_BYTES) return SPQR_ERR_WORKSPACE;
   spqr::Workspace ws;
   if (spqr::static_workspace(&ws) != hipSuccess) return SPQR_ERR_HIP;
   return hip_status(spqr::launch_gemm(D, X_f16, b, Y, y_dtype, static_cast<hipStream_t>(stream), ws));

@@ -37,6 +37,12 @@ hipError_t launch_gemm(const DevMatrix& A, const uint16_t* X, int b, void* Y, in
   const bool force_generic = option(SPQR_OPT_FORCE_GENERIC) != 0;
   bool mfma_ok = !force_generic && mfma_has_instance(g);
   const bool alloc_nodes = mfma_ok && !ws.from_caller && b >= kMfmaMinBatch && stream_is_capturing(stream);
+  // A large batch: one dense binary16 copy of the matrix in scratch, one matrix-core multiply for all vectors.
+  if (!force_generic && prefill_has_instance(g) && prefill_wanted(g, b) &&
+      reinterpret_cast<uintptr_t>(Y) % 16 == 0) {
+    const hipError_t e = launch_prefill_scratch(A, X, b, Y, y_dtype, stream, ws);
+    if (e != hipErrorNotSupported) return e;   // no scratch of that size: the slices below
+  }
   int k = 0;
   while (k < b) {
     const uint16_t* xk = X + (size_t)k * g.n;
@@ -111,9 +117,16 @@ hipError_t launch_gemm_fused(const DevMatrix* As, int count, const uint16_t* X, 
 // Device scratch a product of these matrices with a batch of b needs at most when the caller brings it
 // (0: the call takes kernels that need none).  One matrix: launch_gemm; several: launch_gemm_fused, which may
 // fall back to one launch_gemm per matrix, so the bound covers both.
-size_t workspace_bound(const DevMatrix* As, int count, int b) {
-  if (option(SPQR_OPT_FORCE_GENERIC) != 0 || !mfma_has_instance(As[0].g) || b < kMfmaMinBatch) return 0;
+size_t workspace_bound(const DevMatrix* As, int count, int b, bool with_dense_copy) {
+  if (option(SPQR_OPT_FORCE_GENERIC) != 0) return 0;
   size_t worst = 0;
+  // a large batch: the dense copy of one matrix at a time (a smaller workspace sends the call to the slices of 16)
+  if (with_dense_copy && prefill_has_instance(As[0].g) && prefill_wanted(As[0].g, b))
+    for (int i = 0; i < count; ++i) {
+      const size_t need = prefill_workspace_bytes(As[i], b);
+      if (need > worst) worst = need;
+    }
+  if (!mfma_has_instance(As[0].g) || b < kMfmaMinBatch) return worst;
   // slices of 16, then the rest: the needs of min(b, 16) vectors and of the last slice bound all of them
   const int sizes[2] = {b < 16 ? b : 16, b % 16};
   for (int si = 0; si < 2; ++si) {

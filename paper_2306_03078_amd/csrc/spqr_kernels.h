@@ -43,7 +43,7 @@ hipError_t launch_gemm(const DevMatrix& A, const uint16_t* X, int b, void* Y, in
                        hipStream_t stream, const Workspace& ws);
 hipError_t launch_gemm_fused(const DevMatrix* As, int count, const uint16_t* X, int b, void* const* Ys,
                              int y_dtype, hipStream_t stream, const Workspace& ws);
-size_t workspace_bound(const DevMatrix* As, int count, int b);
+size_t workspace_bound(const DevMatrix* As, int count, int b, bool with_dense_copy = true);
 
 // ---- spqr_gemv.hip: the vector kernel ----
 // Largest number of activation vectors (1, 2 or 4, at most `want`) one launch of the tuned kernel takes for this
@@ -79,6 +79,20 @@ size_t mfma_workspace_bound(const DevMatrix* As, int count, int b, bool fused);
 hipError_t static_workspace(Workspace* ws);
 // Steps of 64 tiles per workgroup of the batch path's dense launch (host arithmetic only, see the definition).
 int plan_batch_steps(int groups, int nsteps, int slots_one_step, int slots, int long_workgroups);
+
+// Large batches through a dense binary16 copy of the matrix (spqr_prefill.hip) on the library's scratch or the
+// caller's workspace.  hipErrorNotSupported: no scratch of that size to be had (or the stream is being captured
+// and the library would have to allocate it): the caller takes the slices of 16.
+hipError_t launch_prefill_scratch(const DevMatrix& A, const uint16_t* X, int b, void* Y, int y_dtype, hipStream_t stream,
+                                  const Workspace& ws);
+
+// ---- spqr_prefill.hip: large batches ----
+bool prefill_has_instance(const Geometry& g);
+bool prefill_wanted(const Geometry& g, int b);
+size_t prefill_workspace_bytes(const DevMatrix& A, int b);
+// `scratch`: prefill_workspace_bytes(A, b) bytes, 256-byte aligned; Y 16-byte aligned.
+hipError_t launch_prefill(const DevMatrix& A, const uint16_t* X, int b, void* Y, int y_dtype, hipStream_t stream,
+                          uint8_t* scratch);
 
 // ---- spqr_misc.hip: fallback product, debug decode, validation ----
 hipError_t launch_generic(const DevMatrix& A, const uint16_t* x, void* y, int y_dtype, hipStream_t stream);

@@ -25,8 +25,8 @@ namespace spqr {
 // tile (same loads, same layout as the GEMV).  An MFMA operand, though, wants
 // 16 rows x 4 columns across the 64 lanes, while here the lanes hold 64 different
 // tiles: so every lane dequantises its tile to binary16 (s_hat*(q - z_hat) evaluated
-// in binary32, one rounding -- the paper's kernel also "dequantizes to 16-bits",
-// Sec. 4.2) into its wavefront's LDS buffer, a quarter (4 columns) at a time to
+// in binary32, one rounding -- the kernel of Sec. 4.2 multiplies 16-bit weights
+// as well) into its wavefront's LDS buffer, a quarter (4 columns) at a time to
 // keep the buffer small enough for two workgroups per CU.  One
 // v_mfma_f32_16x16x32_f16 then sums 8 tiles at once: its K index is (tile, column),
 // A: lane l = row l%16 of tiles 8j + 2(l/16) and the next, B: lane l = batch l%16, the
@@ -900,7 +900,7 @@ static hipError_t launch_mfma_t(const DevMatrix& A, const uint16_t* X, int b, vo
 bool mfma_wanted(const Geometry& g, int b, bool alloc_nodes) {
   const int forced = option(SPQR_OPT_BATCH_PATH);
   if (forced == SPQR_BATCH_PATH_VECTOR) return false;
-  if (forced == SPQR_BATCH_PATH_MATRIX) return true;
+  if (forced == SPQR_BATCH_PATH_MATRIX) return true;   // (_DENSE: the rule below, for calls the dense copy cannot take)
   const double weights = (double)g.m * (double)g.n;
   if (alloc_nodes) return b >= 13 || (b >= 8 && weights >= 40e6) || weights >= 100e6;
   return b >= 7 || weights >= 30e6;
@@ -1060,6 +1060,21 @@ size_t mfma_workspace_bound(const DevMatrix* As, int count, int b, bool fused) {
   SPQR_MFMA_INSTANCES(SPQR_MFMA_CASE)
 #undef SPQR_MFMA_CASE
   return 0;
+}
+
+hipError_t launch_prefill_scratch(const DevMatrix& A, const uint16_t* X, int b, void* Y, int y_dtype, hipStream_t stream,
+                                  const Workspace& ws) {
+  const size_t need = prefill_workspace_bytes(A, b);
+  if (ws.from_caller) {
+    if (ws.p == nullptr || ws.bytes < need) return hipErrorNotSupported;
+    return launch_prefill(A, X, b, Y, y_dtype, stream, ws.p);
+  }
+  // the dense copy is far too large for allocation nodes of a graph, and stream-ordered allocations wait on the host
+  Scratch sc;
+  if (scratch_get(&sc, need, current_device(), stream, false) != hipSuccess) return hipErrorNotSupported;
+  const hipError_t e = launch_prefill(A, X, b, Y, y_dtype, stream, sc.p);
+  const hipError_t ef = scratch_put(&sc, stream);
+  return e == hipSuccess ? ef : e;
 }
 
 // ---- scratch for callers that cannot allocate ------------------------------------------------------------

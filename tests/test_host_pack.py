@@ -202,4 +202,5 @@ def test_batch_launch_plan_arguments_and_the_pinned_choice():
         assert fn(280, 7, 512, 512, 128) == 7
     finally:
         assert lib.spqr_set_option(2, 0) == 0
-    assert lib.spqr_set_option(2, -1) == -3 and lib.spqr_set_option(9, 0) == -3 and lib.spqr_set_option(0, 3) == -3
+    assert lib.spqr_set_option(2, -1) == -3 and lib.spqr_set_option(9, 0) == -3 and lib.spqr_set_option(0, 4) == -3
+        assert lib.spqr_set_option(3, 96) == -3 and lib.spqr_set_option(3, 64) == 0 and lib.spqr_set_option(3, 0) == 0   # SPQR_OPT_DENSE_ROWS
