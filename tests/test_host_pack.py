@@ -203,4 +203,4 @@ def test_batch_launch_plan_arguments_and_the_pinned_choice():
     finally:
         assert lib.spqr_set_option(2, 0) == 0
     assert lib.spqr_set_option(2, -1) == -3 and lib.spqr_set_option(9, 0) == -3 and lib.spqr_set_option(0, 4) == -3
-        assert lib.spqr_set_option(3, 96) == -3 and lib.spqr_set_option(3, 64) == 0 and lib.spqr_set_option(3, 0) == 0   # SPQR_OPT_DENSE_ROWS
+    assert lib.spqr_set_option(3, 96) == -3 and lib.spqr_set_option(3, 64) == 0 and lib.spqr_set_option(3, 0) == 0   # SPQR_OPT_DENSE_ROWS
