@@ -268,8 +268,9 @@ def run_batch_probe(b, P, synth, torch, dev, axis):
 
 def run_batch_sweep(path, P, synth, torch, dev, axis):
     """Batches 2..16 on the distinct layers of configurations 2, 3 and 4: the vector kernel's slices of 4 against the
-    matrix-core path (both forced through spqr_set_option) and the library's own choice; the table the rule in the
-    library's dispatch is read from.  Written as JSON to `path`."""
+    matrix-core path (both forced through spqr_set_option) and the library's own choice; batches 32..256: the
+    matrix-core slices of 16 against the dense-copy path.  The tables the rules in the library's dispatch are read
+    from.  Written as JSON to `path`."""
     rows = []
     for cfg in (2, 3, 4):
         for li, sp in distinct_layers(synth, cfg):
@@ -284,6 +285,17 @@ def run_batch_sweep(path, P, synth, torch, dev, axis):
                     us[nm] = round(time_layer(P, torch, A, X, copies), 2)
                 P.spqr_set_option(P.SPQR_OPT_BATCH_PATH, P.SPQR_BATCH_PATH_AUTO)
                 rows.append({"config": cfg, "layer": sp.name, "m": sp.m, "n": sp.n, "batch": b, **us})
+            # large batches: the slices of 16 against the dense-copy path
+            for b in (32, 48, 64, 96, 128, 256):
+                X = torch.from_numpy(synth.make_x(sp.n, b, seed=(cfg, li, b))).to(dev)
+                us = {}
+                for nm, opt in (("auto", P.SPQR_BATCH_PATH_AUTO), ("matrix", P.SPQR_BATCH_PATH_MATRIX),
+                                ("dense", P.SPQR_BATCH_PATH_DENSE)):
+                    P.spqr_set_option(P.SPQR_OPT_BATCH_PATH, opt)
+                    us[nm] = round(time_layer(P, torch, A, X, min(copies, 3), reps=2), 2)
+                P.spqr_set_option(P.SPQR_OPT_BATCH_PATH, P.SPQR_BATCH_PATH_AUTO)
+                rows.append({"config": cfg, "layer": sp.name, "m": sp.m, "n": sp.n, "batch": b, **us,
+                             "auto_TFLOPs": round(2.0 * sp.m * sp.n * b / us["auto"] / 1e6, 1)})
             del A
             torch.cuda.empty_cache()
     with open(path, "w") as fh:

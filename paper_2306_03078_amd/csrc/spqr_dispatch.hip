@@ -38,7 +38,7 @@ hipError_t launch_gemm(const DevMatrix& A, const uint16_t* X, int b, void* Y, in
   bool mfma_ok = !force_generic && mfma_has_instance(g);
   const bool alloc_nodes = mfma_ok && !ws.from_caller && b >= kMfmaMinBatch && stream_is_capturing(stream);
   // A large batch: one dense binary16 copy of the matrix in scratch, one matrix-core multiply for all vectors.
-  if (!force_generic && prefill_has_instance(g) && prefill_wanted(g, b) &&
+  if (!force_generic && prefill_has_instance(g) && prefill_wanted(A, b) &&
       reinterpret_cast<uintptr_t>(Y) % 16 == 0) {
     const hipError_t e = launch_prefill_scratch(A, X, b, Y, y_dtype, stream, ws);
     if (e != hipErrorNotSupported) return e;   // no scratch of that size: the slices below
@@ -91,6 +91,10 @@ hipError_t launch_gemm_fused(const DevMatrix* As, int count, const uint16_t* X, 
   // known, captured calls take the per-matrix path.
   const bool capturing = mfma_ok && b >= kMfmaMinBatch && stream_is_capturing(stream);
   if (capturing) mfma_ok = false;
+  // a large batch: every matrix through its dense copy (launch_gemm falls back to the slices where it cannot)
+  bool dense = !force_generic && prefill_has_instance(g);
+  for (int i = 0; i < count && dense; ++i) dense = prefill_wanted(As[i], b);
+  if (dense) mfma_ok = false;
   int k = 0;
   while (k < b) {
     const int left = b - k, nb16 = left < 16 ? left : 16;
@@ -121,8 +125,9 @@ size_t workspace_bound(const DevMatrix* As, int count, int b, bool with_dense_co
   if (option(SPQR_OPT_FORCE_GENERIC) != 0) return 0;
   size_t worst = 0;
   // a large batch: the dense copy of one matrix at a time (a smaller workspace sends the call to the slices of 16)
-  if (with_dense_copy && prefill_has_instance(As[0].g) && prefill_wanted(As[0].g, b))
+  if (with_dense_copy && prefill_has_instance(As[0].g))
     for (int i = 0; i < count; ++i) {
+      if (!prefill_wanted(As[i], b)) continue;
       const size_t need = prefill_workspace_bytes(As[i], b);
       if (need > worst) worst = need;
     }

@@ -88,7 +88,7 @@ hipError_t launch_prefill_scratch(const DevMatrix& A, const uint16_t* X, int b, 
 
 // ---- spqr_prefill.hip: large batches ----
 bool prefill_has_instance(const Geometry& g);
-bool prefill_wanted(const Geometry& g, int b);
+bool prefill_wanted(const DevMatrix& A, int b);
 size_t prefill_workspace_bytes(const DevMatrix& A, int b);
 // `scratch`: prefill_workspace_bytes(A, b) bytes, 256-byte aligned; Y 16-byte aligned.
 hipError_t launch_prefill(const DevMatrix& A, const uint16_t* X, int b, void* Y, int y_dtype, hipStream_t stream,

@@ -126,7 +126,7 @@ constexpr int kGemmBK = 64, kGemmLds = 72;     // k per block, LDS row stride in
 template <int BR, int BV>
 __global__ void __launch_bounds__(256, 2)
 gemm_f16_tn_kernel(const uint16_t* __restrict__ X, int b, int n, const uint16_t* __restrict__ Wd, int ldw, int m,
-                   void* __restrict__ Y, int y_dtype) {
+                   void* Y, int y_dtype, int blocks_per_split) {
   constexpr int BK = kGemmBK, LD = kGemmLds;
   constexpr int NRB = BR / 32;               // row blocks of 16 per wavefront
   constexpr int NVB = BV / 32;               // vector blocks of 16 per wavefront
@@ -139,7 +139,10 @@ gemm_f16_tn_kernel(const uint16_t* __restrict__ X, int b, int n, const uint16_t*
   const int wr = wave & 1, wv = wave >> 1;
   const int i16 = lane & 15, g4 = lane >> 4;
   const int row0 = blockIdx.x * BR, vec0 = blockIdx.y * BV;
-  const int nk = ldw / BK;
+  // blocks of k of this workgroup: split blockIdx.z of gridDim.z (never empty: the host sizes the splits); with
+  // several splits Y is the binary32 partial result [split][b][m]
+  const int kt_lo = blockIdx.z * blocks_per_split, kt_hi = min(ldw / BK, kt_lo + blocks_per_split);
+  if (gridDim.z > 1) Y = reinterpret_cast<float*>(Y) + (int64_t)blockIdx.z * b * m;
 
   // chunk c of a block: row c / 8 of the tile, k = 8 * (c % 8): 8 consecutive threads read 128 contiguous bytes
   const uint16_t* wsrc[WCH];
@@ -184,12 +187,12 @@ gemm_f16_tn_kernel(const uint16_t* __restrict__ X, int b, int n, const uint16_t*
 #pragma unroll
     for (int vb = 0; vb < NVB; ++vb) D[rb][vb] = float4_t{0.f, 0.f, 0.f, 0.f};
 
-  fetch(0);
+  fetch(kt_lo);
   stash(0);
   __syncthreads();
-  for (int kt = 0; kt < nk; ++kt) {          // workgroup-uniform
-    const int buf = kt & 1;
-    if (kt + 1 < nk) fetch(kt + 1);
+  for (int kt = kt_lo; kt < kt_hi; ++kt) {   // workgroup-uniform
+    const int buf = (kt - kt_lo) & 1;
+    if (kt + 1 < kt_hi) fetch(kt + 1);
     const uint16_t* a0 = As + buf * BR * LD + (wr * (BR / 2) + i16) * LD + 8 * g4;
     const uint16_t* b0 = Bs + buf * BV * LD + (wv * (BV / 2) + i16) * LD + 8 * g4;
 #pragma unroll
@@ -205,7 +208,7 @@ gemm_f16_tn_kernel(const uint16_t* __restrict__ X, int b, int n, const uint16_t*
         for (int vb = 0; vb < NVB; ++vb)
           D[rb][vb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af[rb], bf[vb], D[rb][vb], 0, 0, 0);
     }
-    if (kt + 1 < nk) stash(buf ^ 1);         // the other buffer: everyone left it at the previous barrier
+    if (kt + 1 < kt_hi) stash(buf ^ 1);      // the other buffer: everyone left it at the previous barrier
     __syncthreads();
   }
 
@@ -244,20 +247,26 @@ bool prefill_has_instance(const Geometry& g) {
   return shape16 || shape8x32 || shape32x8;
 }
 
-// Whether a batch of b vectors goes through the dense copy: the copy costs one pass over the compressed weights
-// and one write of 2 bytes per weight, the slices of 16 a pass over the compressed weights each.
-bool prefill_wanted(const Geometry& g, int b) {
+// Whether a batch of b vectors goes through the dense copy: the copy costs one pass over the compressed weights,
+// one write of 2 bytes per weight and a scattered read-modify-write per outlier, whatever the batch; the slices of
+// 16 cost a pass over the compressed weights each.  Measured on the 7B to 65B shapes (batches of 32 to 256, both
+// paths forced): the copy wins from 48 vectors on layers of up to 120 M weights (4096^2 at 48: 34 against 56 us;
+// 17920x6656: 144 against 156), from 64 on 8192^2 with 2 % outliers and from 96 on the layers of 180 M weights
+// (22016x8192 at 64 / 96: 326 / 355 against 289 / 433); at 256 vectors it is 3.4 to 6.8 times faster.
+bool prefill_wanted(const DevMatrix& A, int b) {
   const int forced = option(SPQR_OPT_BATCH_PATH);
   if (forced == SPQR_BATCH_PATH_DENSE) return true;
   if (forced != SPQR_BATCH_PATH_AUTO) return false;
-  (void)g;
-  return b >= 48;
+  const double from = (double)A.g.m * (double)A.g.n / 2.5e6 + (double)A.nnz / 1.5e5;
+  return b >= 48 && (double)b >= from;
 }
 
-// Scratch of one call: the dense copy, then the batch in column order if there is a permutation.
+// Scratch of one call: the dense copy, the batch in column order if there is a permutation, the partial results if
+// the multiply splits k (up to 8 splits: bounded without looking at the options).
 size_t prefill_workspace_bytes(const DevMatrix& A, int b) {
   auto up = [](size_t v) { return (v + 255) & ~(size_t)255; };
-  return up((size_t)A.g.m * padded_columns(A.g.n) * 2) + (A.perm != nullptr ? up((size_t)b * A.g.n * 2) : 0);
+  return up((size_t)A.g.m * padded_columns(A.g.n) * 2) + (A.perm != nullptr ? up((size_t)b * A.g.n * 2) : 0) +
+         up((size_t)8 * b * A.g.m * sizeof(float));
 }
 
 template <int W, int TR, int TC, int AXIS>
@@ -268,9 +277,20 @@ static hipError_t launch_dequant_tiles(const DevMatrix& A, uint16_t* Wd, int ldw
   return hipGetLastError();
 }
 
+// Y[i] = sum over the splits of P[split][i], in the order of the splits, rounded once to the output type.
+__global__ void __launch_bounds__(256)
+sum_splits_kernel(const float* __restrict__ P, int splits, int64_t count, void* __restrict__ Y, int y_dtype) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= count) return;
+  float s = P[i];
+  for (int k = 1; k < splits; ++k) s += P[(int64_t)k * count + i];
+  if (y_dtype == SPQR_F32) reinterpret_cast<float*>(Y)[i] = s;
+  else reinterpret_cast<uint16_t*>(Y)[i] = f2h_rne(s);
+}
+
 template <int BR, int BV>
 static hipError_t launch_dense_gemm_t(const uint16_t* X, int b, int n, const uint16_t* Wd, int ldw, int m, void* Y,
-                                      int y_dtype, hipStream_t stream) {
+                                      int y_dtype, int splits, int blocks_per_split, hipStream_t stream) {
   constexpr int lds = 2 * (BR + BV) * kGemmLds * 2;
   static PerDevice ready;                    // more than 64 KB of LDS per workgroup is an opt-in per kernel and device
   const int dev = current_device();
@@ -280,24 +300,54 @@ static hipError_t launch_dense_gemm_t(const uint16_t* X, int b, int n, const uin
     if (e != hipSuccess) return e;
     ready.set(dev, 1);
   }
-  hipLaunchKernelGGL((gemm_f16_tn_kernel<BR, BV>), dim3((m + BR - 1) / BR, (b + BV - 1) / BV), dim3(256), lds, stream,
-                     X, b, n, Wd, ldw, m, Y, y_dtype);
+  hipLaunchKernelGGL((gemm_f16_tn_kernel<BR, BV>), dim3((m + BR - 1) / BR, (b + BV - 1) / BV, splits), dim3(256), lds,
+                     stream, X, b, n, Wd, ldw, m, Y, splits > 1 ? SPQR_F32 : y_dtype, blocks_per_split);
   return hipGetLastError();
 }
 
-// Tile of the multiply: 128 vectors per workgroup above 64 vectors; 128 rows where that still gives every CU a
-// workgroup, else 64 (measured on the 7B to 65B shapes at 64, 128 and 256 vectors: 64 rows win by 5 to 20 % wherever
-// 128 would leave CUs idle, 128 rows by 20 % on 17920x6656 and 22016x8192 at 256 vectors) (SPQR_OPT_DENSE_ROWS pins it for tuning runs).
+// Tile and splits of the multiply.  128 rows x 128 vectors per workgroup (64 vectors for batches up to 64, 64 rows
+// for matrices of up to 64 rows); where that leaves CUs without a workgroup (few rows, a small batch), the blocks of
+// k are split over up to 8 workgroups of at least 8 blocks each, which write binary32 partial results that a second
+// kernel adds in a fixed order.  Measured on the 7B to 65B shapes at 64 to 256 vectors: 128 rows with splits beat
+// 64 rows without (8192x22016 at 128 vectors: 373 against 537 us for the whole call, 6656x17920 at 256: 265 against
+// 327), 128 x 128 without splits beats 64 x 128 by 20 % where both fill the chip.  SPQR_OPT_DENSE_ROWS pins the
+// rows for tuning runs.
+struct DensePlan { int br, bv, splits, blocks_per_split; };
+static DensePlan plan_dense_gemm(int b, int m, int ldw) {
+  const int forced = option(SPQR_OPT_DENSE_ROWS);
+  DensePlan p;
+  p.br = (forced == 64 || forced == 128) ? forced : (m <= 64 ? 64 : 128);
+  p.bv = b <= 64 ? 64 : 128;
+  const int nk = ldw / kGemmBK;
+  p.splits = 1; p.blocks_per_split = nk;
+  const int64_t wgs = (int64_t)((m + p.br - 1) / p.br) * ((b + p.bv - 1) / p.bv);
+  if (wgs < kCUs) {
+    int s = (int)((2 * kCUs) / wgs);
+    if (s > 8) s = 8;
+    if (s > nk / 8) s = nk / 8;
+    if (s > 1) {
+      p.blocks_per_split = (nk + s - 1) / s;
+      p.splits = (nk + p.blocks_per_split - 1) / p.blocks_per_split;   // no empty split
+    }
+  }
+  return p;
+}
+
+// `partial`: plan.splits * b * m floats if the plan splits k, else unused.
 static hipError_t launch_dense_gemm(const uint16_t* X, int b, int n, const uint16_t* Wd, int ldw, int m, void* Y,
-                                    int y_dtype, hipStream_t stream) {
-  const bool wide = b > 64;
-  const int vtiles = wide ? (b + 127) / 128 : 1;
-  int br = option(SPQR_OPT_DENSE_ROWS);
-  if (br != 64 && br != 128) br = (int64_t)((m + 127) / 128) * vtiles >= kCUs ? 128 : 64;
-  if (wide) return br == 128 ? launch_dense_gemm_t<128, 128>(X, b, n, Wd, ldw, m, Y, y_dtype, stream)
-                             : launch_dense_gemm_t<64, 128>(X, b, n, Wd, ldw, m, Y, y_dtype, stream);
-  return br == 128 ? launch_dense_gemm_t<128, 64>(X, b, n, Wd, ldw, m, Y, y_dtype, stream)
-                   : launch_dense_gemm_t<64, 64>(X, b, n, Wd, ldw, m, Y, y_dtype, stream);
+                                    int y_dtype, float* partial, hipStream_t stream) {
+  const DensePlan p = plan_dense_gemm(b, m, ldw);
+  void* out = p.splits > 1 ? static_cast<void*>(partial) : Y;
+  hipError_t e;
+  if (p.bv == 128) e = p.br == 128 ? launch_dense_gemm_t<128, 128>(X, b, n, Wd, ldw, m, out, y_dtype, p.splits, p.blocks_per_split, stream)
+                                   : launch_dense_gemm_t<64, 128>(X, b, n, Wd, ldw, m, out, y_dtype, p.splits, p.blocks_per_split, stream);
+  else e = p.br == 128 ? launch_dense_gemm_t<128, 64>(X, b, n, Wd, ldw, m, out, y_dtype, p.splits, p.blocks_per_split, stream)
+                       : launch_dense_gemm_t<64, 64>(X, b, n, Wd, ldw, m, out, y_dtype, p.splits, p.blocks_per_split, stream);
+  if (e != hipSuccess || p.splits == 1) return e;
+  const int64_t count = (int64_t)b * m;
+  hipLaunchKernelGGL(sum_splits_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, stream, partial, p.splits, count,
+                     Y, y_dtype);
+  return hipGetLastError();
 }
 
 // Y[b][m] = X[b][n] . W_hat^T for a large batch.  `scratch`: prefill_workspace_bytes(A, b) bytes, 256-byte aligned.
@@ -310,7 +360,9 @@ hipError_t launch_prefill(const DevMatrix& A, const uint16_t* X, int b, void* Y,
   const int ldw = padded_columns(g.n);
   uint16_t* Wd = reinterpret_cast<uint16_t*>(scratch);
   const size_t wd_bytes = ((size_t)g.m * ldw * 2 + 255) & ~(size_t)255;
+  const size_t xp_bytes = A.perm != nullptr ? ((size_t)b * g.n * 2 + 255) & ~(size_t)255 : 0;
   uint16_t* XP = A.perm != nullptr ? reinterpret_cast<uint16_t*>(scratch + wd_bytes) : nullptr;
+  float* partial = reinterpret_cast<float*>(scratch + wd_bytes + xp_bytes);
   hipError_t e = hipErrorInvalidValue;
 #define SPQR_CASE(W_, TR_, TC_, AX_) \
   if (g.w_bits == W_ && g.tile_rows == TR_ && g.tile_cols == TC_ && g.axis == AX_) \
@@ -334,7 +386,7 @@ hipError_t launch_prefill(const DevMatrix& A, const uint16_t* X, int b, void* Y,
     if ((e = hipGetLastError()) != hipSuccess) return e;
     Xin = XP;
   }
-  return launch_dense_gemm(Xin, b, g.n, Wd, ldw, g.m, Y, y_dtype, stream);
+  return launch_dense_gemm(Xin, b, g.n, Wd, ldw, g.m, Y, y_dtype, partial, stream);
 }
 
 }  // namespace spqr
