@@ -353,12 +353,16 @@ int spqr_gemv_grouped(const spqr_matrix_t* const* A, int count, const uint16_t* 
  *   SPQR_OPT_BATCH_STEPS   k > 0: the matrix-core path's dense launch gives every
  *                          workgroup min(k, steps) steps of 64 tiles
  *   SPQR_OPT_DENSE_ROWS    64 or 128: rows per workgroup of the large-batch
- *                          multiply (0: the library's rule) */
+ *                          multiply (0: the library's rule)
+ *   SPQR_OPT_GEMV_PLAN     16 * P + R > 0: the batch-1 kernel runs with P
+ *                          wavefronts per strip and R strips per workgroup
+ *                          (clamped to what the matrix and the kernel allow) */
 #define SPQR_OPT_BATCH_PATH     0
 #define SPQR_OPT_FORCE_GENERIC  1
 #define SPQR_OPT_BATCH_STEPS    2
 #define SPQR_OPT_DENSE_ROWS     3
-#define SPQR_OPT_COUNT_         4
+#define SPQR_OPT_GEMV_PLAN      4
+#define SPQR_OPT_COUNT_         5
 #define SPQR_BATCH_PATH_AUTO    0
 #define SPQR_BATCH_PATH_VECTOR  1
 #define SPQR_BATCH_PATH_MATRIX  2

@@ -21,7 +21,7 @@ SPQR_OUT_CODES_U8, SPQR_OUT_SCALE_F32, SPQR_OUT_ZERO_F32 = 0, 1, 2
 SPQR_OUT_DENSE_F32, SPQR_OUT_DENSE_F16, SPQR_OUT_WITH_OUTLIERS = 3, 4, 0x100
 SPQR_LAYOUT_V1, SPQR_LAYOUT_ROUND_ZERO, SPQR_LAYOUT_STATS16 = 1, 2, 3
 _LAYOUT_OF = {"bilevel": SPQR_LAYOUT_V1, "round_zero": SPQR_LAYOUT_ROUND_ZERO, "stats16": SPQR_LAYOUT_STATS16}
-SPQR_OPT_BATCH_PATH, SPQR_OPT_FORCE_GENERIC, SPQR_OPT_BATCH_STEPS, SPQR_OPT_DENSE_ROWS = 0, 1, 2, 3
+SPQR_OPT_BATCH_PATH, SPQR_OPT_FORCE_GENERIC, SPQR_OPT_BATCH_STEPS, SPQR_OPT_DENSE_ROWS, SPQR_OPT_GEMV_PLAN = 0, 1, 2, 3, 4
 SPQR_BATCH_PATH_AUTO, SPQR_BATCH_PATH_VECTOR, SPQR_BATCH_PATH_MATRIX, SPQR_BATCH_PATH_DENSE = 0, 1, 2, 3
 SPQR_ERR_WORKSPACE = -11
 SPQR_STATIC_SCRATCH_BYTES = 32 * 1024 * 1024

@@ -101,6 +101,7 @@ extern "C" int spqr_set_option(int option, int value) {
     case SPQR_OPT_FORCE_GENERIC: ok = value == 0 || value == 1; break;
     case SPQR_OPT_BATCH_STEPS: ok = value >= 0; break;
     case SPQR_OPT_DENSE_ROWS: ok = value == 0 || value == 64 || value == 128; break;
+    case SPQR_OPT_GEMV_PLAN: ok = value >= 0 && value < 16 * 17; break;
     default: ok = false;
   }
   return ok && spqr::set_option(option, value) ? SPQR_OK : SPQR_ERR_PARAM;

@@ -14,11 +14,6 @@ namespace spqr {
 // per thread (the common, single-barrier path) and up to eight.  Static arrays (red, osum, lred, rp) come on
 // top; the sum must stay within the CU's 160 KB.
 // ---------------------------------------------------------------------------
-// Set by tuning harnesses that compile this file into a program of their own (never by the library): P > 0
-// pins the wavefronts per strip and the strips per workgroup.
-struct PlanPin { int P, R; };
-static PlanPin g_plan_pin = {0, 0};
-
 bool plan_launch(const Geometry& g, int nb, int max_waves, int slots, LaunchPlan* out) {
   const int nsteps = (g.ntc + 63) / 64;
   const int xbytes = (nb * g.n * 2 + 15) & ~15;
@@ -29,9 +24,10 @@ bool plan_launch(const Geometry& g, int nb, int max_waves, int slots, LaunchPlan
   const int widest = max_waves < nsteps ? max_waves : nsteps;
   if (xbytes + 32 * nb * 64 * ((widest + 1) / 2) > max_dynamic) return false;
   int P = 0, R = 1;
-  if (g_plan_pin.P > 0) {
-    P = g_plan_pin.P < nsteps ? g_plan_pin.P : nsteps;
-    R = g_plan_pin.R < 1 ? 1 : (g_plan_pin.R > rmax ? rmax : g_plan_pin.R);
+  if (const int pin = option(SPQR_OPT_GEMV_PLAN); pin > 0 && nb == 1) {   // tuning runs: 16 * P + R
+    const int pin_p = pin >> 4, pin_r = pin & 15;
+    P = pin_p < 1 ? 1 : (pin_p < nsteps ? pin_p : nsteps);
+    R = pin_r < 1 ? 1 : (pin_r > rmax ? rmax : pin_r);
     while (R > 1 && R * P > max_waves) --R;
     if (P > max_waves) P = max_waves;
   } else if (nb == 1) {

@@ -33,5 +33,5 @@ def _library_options_back_to_default(request):
     yield
     if "gpu" in request.keywords:
         import paper_2306_03078_amd as P
-        for opt in (P.SPQR_OPT_BATCH_PATH, P.SPQR_OPT_FORCE_GENERIC, P.SPQR_OPT_BATCH_STEPS, P.SPQR_OPT_DENSE_ROWS):
+        for opt in (P.SPQR_OPT_BATCH_PATH, P.SPQR_OPT_FORCE_GENERIC, P.SPQR_OPT_BATCH_STEPS, P.SPQR_OPT_DENSE_ROWS, P.SPQR_OPT_GEMV_PLAN):
             P.spqr_set_option(opt, 0)
