@@ -311,6 +311,23 @@ def distinct_layers(synth, cfg):
     return out
 
 
+def run_batches(P, synth, torch, dev, axis):
+    """Batches of 16 and 256 vectors on the distinct layers of configuration 3 (the library's choice of path:
+    slices of 16 on the matrix cores, the dense-copy path at 256), same timing protocol as --sweep."""
+    out = []
+    for li, sp in distinct_layers(synth, 3):
+        A = P.SpQRMatrix.from_logical(synth.make_config_layer(3, li, group_axis=axis), dev)
+        copies = max(2, int(600e6 // A.compressed_bytes()) + 1)
+        for b in (16, 256):
+            X = torch.from_numpy(synth.make_x(sp.n, b, seed=(3, li, b))).to(dev)
+            us = time_layer(P, torch, A, X, copies, reps=3)
+            out.append({"config": 3, "layer": sp.name, "m": sp.m, "n": sp.n, "batch": b, "us": round(us, 2),
+                        "TFLOPs": round(2.0 * sp.m * sp.n * b / us / 1e6, 2)})
+        del A
+        torch.cuda.empty_cache()
+    return out
+
+
 def run_other_configs(P, synth, torch, dev, cfgs_axes):
     """Batch-1 figures of the other configurations' distinct layers (same protocol as --sweep, batch 1 only)."""
     out = []
@@ -517,8 +534,9 @@ def main():
     del pool, graph, other
     torch.cuda.empty_cache()
 
-    other_configs = None
+    other_configs = batches = None
     if not args.no_configs:
+        batches = run_batches(P, synth, torch, dev, args.group_axis)
         other_configs = run_other_configs(P, synth, torch, dev,
                                           [(0, args.group_axis), (1, args.group_axis), (2, args.group_axis),
                                            (3, args.group_axis), (4, 1 - args.group_axis)])
@@ -608,6 +626,7 @@ def main():
     }
     if other_configs is not None:
         out["other_configs_batch1"] = other_configs
+        out["batches_config3"] = batches
     if batch_probe is not None:
         out["batch_probe"] = batch_probe
     print(json.dumps(out))

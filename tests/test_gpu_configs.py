@@ -143,3 +143,39 @@ def test_fused_projections_at_full_size(P):
             check_outputs(y.cpu().numpy()[None, :], ref[:1], ("fused", f.m, f.n, 1))
             check_outputs(Y.cpu().numpy(), ref[1:], ("fused", f.m, f.n, 16))
         del fs, As
+
+
+def test_large_batches_at_full_size(P):
+    """256 and 64 vectors on the LLaMA-33B- and 65B-shaped layers (the dense-copy path, with and without split k):
+    every output element against the oracle."""
+    for cfg, name, b in ((3, "gate", 256), (3, "down", 256), (4, "q", 64), (4, "down", 128)):
+        i = [k for k, sp in enumerate(synth.config_layers(cfg)) if sp.name == name][0]
+        f = synth.make_config_layer(cfg, i, group_axis=1)
+        A = P.SpQRMatrix.from_logical(f)
+        assert P.spqr_workspace_bytes([A], b) >= 2 * f.m * f.n        # the path with the dense copy is the one taken
+        X = synth.make_x(f.n, b, seed=(80, b))
+        Y = P.spqr_gemm_smallbatch(A, dev(X)).cpu().numpy()
+        check_outputs(Y, orc.matvec(f, X), ("dense copy", cfg, name, b))
+        del f, A
+
+
+def test_grouped_block_at_full_size(P):
+    """All seven projections of the LLaMA-65B-shaped block in one spqr_gemv_grouped call (what bench.py times)."""
+    import torch
+    specs = synth.config_layers(4)
+    fs = [synth.make_config_layer(4, i, group_axis=1) for i in range(len(specs))]
+    As = [P.SpQRMatrix.from_logical(f) for f in fs]
+    xs = [synth.make_x(f.n, 1, seed=(81, i)) for i, f in enumerate(fs)]
+    ys = P.spqr_gemv_grouped(As, [dev(x[0]) for x in xs])
+    torch.cuda.synchronize()
+    for f, x, y in zip(fs, xs, ys):
+        check_outputs(y.cpu().numpy()[None, :], orc.matvec(f, x), ("grouped", f.m, f.n))
+
+
+@pytest.mark.parametrize("layout", ["round_zero", "stats16"])
+def test_statistic_variants_at_full_size(P, layout):
+    """The two statistic layouts of the ablations on the largest layer shape and on a 7B-shaped one."""
+    for cfg, i in ((4, 4), (1, 0)):
+        f = synth.make_config_layer(cfg, i, group_axis=1, stat_layout=layout)
+        check_layer(P, f, (1,), check_codes=True)
+        del f
