@@ -126,9 +126,10 @@ typedef enum spqr_status {
  *     (beta2 only shapes the tile).
  * Decode: SPQR_LAYOUT_ROUND_ZERO  s_hat = s_s * (s_q - z_s), z_hat = z_q;
  *         SPQR_LAYOUT_STATS16     s_hat, z_hat as stored.
- * Tiles of 256 codes have tuned kernels (batch 1 to 4 vectors at a time); the
- * matrix-core batch path exists for SPQR_LAYOUT_V1 only, the other layouts run
- * larger batches as slices of up to 4 vectors.
+ * Tiles of 256 codes have tuned batch-1 kernels in every layout; the slices of
+ * 16 on the matrix cores exist for SPQR_LAYOUT_V1 only: the other layouts run a
+ * few vectors as passes of the batch-1 kernel and a dozen and more through the
+ * dense copy (see spqr_gemm_smallbatch).
  *
  * Outliers: row_ptr[m+1] is the exclusive prefix of per-row counts
  * (row_ptr[0] = 0, row_ptr[m] = nnz); col_idx / out_val are sorted by row then
@@ -241,8 +242,9 @@ int spqr_gemv(const spqr_matrix_t* A, const uint16_t* x_f16, void* y, int y_dtyp
  * 10 us more per call), on further streams one from a pool of the library's
  * own.  If no scratch can be had, the slices of 4 run instead.  Callers that
  * must not allocate or synchronise use spqr_gemm_smallbatch_ws.
- * Large batches (48 vectors and more, the prompt phase of Sec. 5 "Inference
- * Time"; tiles of 256 codes, SPQR_LAYOUT_V1, Y 16-byte aligned): the matrix is
+ * Large batches (48 vectors and more, 12 where no slices of 16 exist; the
+ * prompt phase of Sec. 5 "Inference Time"; tiles of 256 codes in any layout
+ * and 3-bit tiles of 8 x 64, Y 16-byte aligned): the matrix is
  * dequantised once into a dense binary16 copy in scratch (2 bytes per weight,
  * rows padded to a multiple of 64 columns; with a permutation b*n*2 bytes more),
  * the outliers are added into the copy, and one matrix-core kernel multiplies

@@ -21,10 +21,11 @@ typedef float float4_t __attribute__((ext_vector_type(4)));
 // its tile into binary16, w = s_hat * (q - z_hat) evaluated in binary32 and rounded once, and writes it row
 // by row: consecutive lanes hold consecutive column blocks, so a row of the step is one contiguous run.
 // ---------------------------------------------------------------------------
-template <int W, int TR, int TC, int AXIS>
+// LV: the statistic layout (1 bilevel, 2 integer zero-point, 3 binary16 statistics per group).
+template <int W, int TR, int TC, int AXIS, int LV>
 __global__ void __launch_bounds__(256)
 dequant_tiles_f16_kernel(DevMatrix A, uint16_t* __restrict__ Wd, int ldw) {
-  using T = TileRegs<W, TR, TC, AXIS>;
+  using T = TileRegs<W, TR, TC, AXIS, LV>;
   constexpr int TILE_BYTES = 16 * T::KW + 4 * T::SD;
   constexpr int PPR = TC / 2, B2 = T::B2;
   constexpr float SCALE = (float)(1 << W);
@@ -38,21 +39,34 @@ dequant_tiles_f16_kernel(DevMatrix A, uint16_t* __restrict__ Wd, int ldw) {
   load_tile<true>(t, A.packed + ((int64_t)strip * ntc + (int64_t)64 * step) * TILE_BYTES, L, min(lane, L - 1));
   const PairConsts kc = make_pair_consts<W>();
   const PairConsts k3 = make_pair_consts<3>();
-  const uint32_t a2 = t.s[T::NC], b2 = t.s[T::NC + 1];
-  const float s_s = h2f((uint16_t)(a2 & 0xFFFF)), z_s = h2f((uint16_t)(a2 >> 16));
-  const float s_z = h2f((uint16_t)(b2 & 0xFFFF)), z_z = h2f((uint16_t)(b2 >> 16));
-  // w = fa * (1 + q/2^W) + fb with fa = 2^W * s_hat, fb = -s_hat * (2^W + z_hat); the extracted codes are 1 + code/8
-  const float c1 = SCALE * 8.f * s_s, c2 = SCALE * (-s_s * z_s - 8.f * s_s);
-  const float e1 = -8.f * s_z / SCALE, e2 = -(SCALE - s_z * z_z - 8.f * s_z) / SCALE;
+  // w = fa * (1 + q/2^W) + fb with fa = 2^W * s_hat, fb = -s_hat * (2^W + z_hat), per group
   float fa[B2], fb[B2];
+  if constexpr (LV == 3) {                   // dword g of the statistics: s_hat | z_hat << 16
 #pragma unroll
-  for (int p = 0; p < B2 / 2; ++p) {
-    const half2_t sq = as_half2(pair_f16<3>(t.s, p, k3));
-    const half2_t zq = as_half2(pair_f16<3>(t.s, B2 / 2 + p, k3));
-    fa[2 * p] = fmaf((float)sq.x, c1, c2);
-    fa[2 * p + 1] = fmaf((float)sq.y, c1, c2);
-    fb[2 * p] = fa[2 * p] * fmaf((float)zq.x, e1, e2);
-    fb[2 * p + 1] = fa[2 * p + 1] * fmaf((float)zq.y, e1, e2);
+    for (int g = 0; g < B2; ++g) {
+      const float sh = h2f((uint16_t)(t.s[g] & 0xFFFF)), zh = h2f((uint16_t)(t.s[g] >> 16));
+      fa[g] = SCALE * sh;
+      fb[g] = -sh * (SCALE + zh);
+    }
+  } else {                                   // 3-bit codes, extracted as 1 + code/8; layout 2: z_hat = z_q (s_z = 1, z_z = 0)
+    const uint32_t a2 = t.s[T::NC];
+    const float s_s = h2f((uint16_t)(a2 & 0xFFFF)), z_s = h2f((uint16_t)(a2 >> 16));
+    float s_z = 1.f, z_z = 0.f;
+    if constexpr (LV == 1) {
+      const uint32_t b2 = t.s[T::NC + 1];
+      s_z = h2f((uint16_t)(b2 & 0xFFFF)); z_z = h2f((uint16_t)(b2 >> 16));
+    }
+    const float c1 = SCALE * 8.f * s_s, c2 = SCALE * (-s_s * z_s - 8.f * s_s);
+    const float e1 = -8.f * s_z / SCALE, e2 = -(SCALE - s_z * z_z - 8.f * s_z) / SCALE;
+#pragma unroll
+    for (int p = 0; p < B2 / 2; ++p) {
+      const half2_t sq = as_half2(pair_f16<3>(t.s, p, k3));
+      const half2_t zq = as_half2(pair_f16<3>(t.s, B2 / 2 + p, k3));
+      fa[2 * p] = fmaf((float)sq.x, c1, c2);
+      fa[2 * p + 1] = fmaf((float)sq.y, c1, c2);
+      fb[2 * p] = fa[2 * p] * fmaf((float)zq.x, e1, e2);
+      fb[2 * p + 1] = fa[2 * p + 1] * fmaf((float)zq.y, e1, e2);
+    }
   }
   if (lane >= L) return;                     // a lane behind the step's last tile held a copy of it
   uint16_t* out = Wd + ((int64_t)strip * TR) * ldw + ((int64_t)64 * step + lane) * TC;
@@ -239,12 +253,14 @@ gemm_f16_tn_kernel(const uint16_t* __restrict__ X, int b, int n, const uint16_t*
 // ---------------------------------------------------------------------------
 static int padded_columns(int n) { return (n + kGemmBK - 1) / kGemmBK * kGemmBK; }
 
+// Tiles of 256 codes in every statistic layout, and the 8 x 64 tiles of the bilevel layout (3-bit, group_axis 1).
 bool prefill_has_instance(const Geometry& g) {
-  if (g.layout != kBilevel || (g.w_bits != 3 && g.w_bits != 4) || g.m % 8 != 0 || g.n % 8 != 0) return false;
+  if ((g.w_bits != 3 && g.w_bits != 4) || g.m % 8 != 0 || g.n % 8 != 0) return false;
   const bool shape16 = g.tile_rows == 16 && g.tile_cols == 16;
   const bool shape8x32 = g.tile_rows == 8 && g.tile_cols == 32 && g.axis == 1;
   const bool shape32x8 = g.tile_rows == 32 && g.tile_cols == 8 && g.axis == 0;
-  return shape16 || shape8x32 || shape32x8;
+  const bool wide = g.tile_rows == 8 && g.tile_cols == 64 && g.axis == 1 && g.w_bits == 3 && g.layout == kBilevel;
+  return shape16 || shape8x32 || shape32x8 || wide;
 }
 
 // Whether a batch of b vectors goes through the dense copy: the copy costs one pass over the compressed weights,
@@ -257,6 +273,9 @@ bool prefill_wanted(const DevMatrix& A, int b) {
   const int forced = option(SPQR_OPT_BATCH_PATH);
   if (forced == SPQR_BATCH_PATH_DENSE) return true;
   if (forced != SPQR_BATCH_PATH_AUTO) return false;
+  // formats without slices of 16 (the other statistic layouts, 8 x 64 tiles) pay a pass of the batch-1 kernel per
+  // vector instead: the copy pays off from about a dozen vectors on
+  if (!mfma_has_instance(A.g)) return b >= 12;
   const double from = (double)A.g.m * (double)A.g.n / 2.5e6 + (double)A.nnz / 1.5e5;
   return b >= 48 && (double)b >= from;
 }
@@ -269,10 +288,12 @@ size_t prefill_workspace_bytes(const DevMatrix& A, int b) {
          up((size_t)8 * b * A.g.m * sizeof(float));
 }
 
-template <int W, int TR, int TC, int AXIS>
+template <int W, int TR, int TC, int AXIS, int LV>
 static hipError_t launch_dequant_tiles(const DevMatrix& A, uint16_t* Wd, int ldw, hipStream_t stream) {
+  using T = TileRegs<W, TR, TC, AXIS, LV>;
+  if (A.g.kw != T::KW || A.g.sd != T::SD || A.g.layout != LV) return hipErrorInvalidValue;   // the tile the kernel loads
   const int nsteps = (A.g.ntc + 63) / 64;
-  hipLaunchKernelGGL((dequant_tiles_f16_kernel<W, TR, TC, AXIS>), dim3((nsteps + 3) / 4, A.g.ntr), dim3(256), 0, stream,
+  hipLaunchKernelGGL((dequant_tiles_f16_kernel<W, TR, TC, AXIS, LV>), dim3((nsteps + 3) / 4, A.g.ntr), dim3(256), 0, stream,
                      A, Wd, ldw);
   return hipGetLastError();
 }
@@ -364,11 +385,14 @@ hipError_t launch_prefill(const DevMatrix& A, const uint16_t* X, int b, void* Y,
   uint16_t* XP = A.perm != nullptr ? reinterpret_cast<uint16_t*>(scratch + wd_bytes) : nullptr;
   float* partial = reinterpret_cast<float*>(scratch + wd_bytes + xp_bytes);
   hipError_t e = hipErrorInvalidValue;
-#define SPQR_CASE(W_, TR_, TC_, AX_) \
-  if (g.w_bits == W_ && g.tile_rows == TR_ && g.tile_cols == TC_ && g.axis == AX_) \
-    e = launch_dequant_tiles<W_, TR_, TC_, AX_>(A, Wd, ldw, stream);
-  SPQR_CASE(3, 16, 16, 1) SPQR_CASE(4, 16, 16, 1) SPQR_CASE(3, 8, 32, 1) SPQR_CASE(4, 8, 32, 1)
-  SPQR_CASE(3, 16, 16, 0) SPQR_CASE(4, 16, 16, 0) SPQR_CASE(3, 32, 8, 0) SPQR_CASE(4, 32, 8, 0)
+#define SPQR_CASE(W_, TR_, TC_, AX_, LV_) \
+  if (g.w_bits == W_ && g.tile_rows == TR_ && g.tile_cols == TC_ && g.axis == AX_ && g.layout == LV_) \
+    e = launch_dequant_tiles<W_, TR_, TC_, AX_, LV_>(A, Wd, ldw, stream);
+#define SPQR_SHAPES(LV_) \
+  SPQR_CASE(3, 16, 16, 1, LV_) SPQR_CASE(4, 16, 16, 1, LV_) SPQR_CASE(3, 8, 32, 1, LV_) SPQR_CASE(4, 8, 32, 1, LV_) \
+  SPQR_CASE(3, 16, 16, 0, LV_) SPQR_CASE(4, 16, 16, 0, LV_) SPQR_CASE(3, 32, 8, 0, LV_) SPQR_CASE(4, 32, 8, 0, LV_)
+  SPQR_SHAPES(1) SPQR_SHAPES(2) SPQR_SHAPES(3) SPQR_CASE(3, 8, 64, 1, 1)
+#undef SPQR_SHAPES
 #undef SPQR_CASE
   if (e != hipSuccess) return e;
   if (ldw > g.n) {

@@ -48,6 +48,7 @@ def check(P, f, A, X, Y):
 # rows not a multiple of the 128-row block, columns not a multiple of the 64-column block (padding), several row
 # blocks and k blocks, every tile shape with an instance
 SHAPES = [
+    (3, 8, 64, 1, 11, 19),                   # tiles of 8 x 64
     (3, 16, 16, 1, 3, 67), (3, 16, 16, 0, 9, 130), (4, 16, 16, 1, 17, 40), (4, 16, 16, 0, 2, 65),
     (3, 8, 32, 1, 21, 33), (3, 8, 32, 0, 5, 271), (4, 8, 32, 1, 40, 9), (4, 8, 32, 0, 1, 129),
 ]
