@@ -358,6 +358,8 @@ def main():
     ap.add_argument("--calls", choices=("grouped", "fused", "seven"), default="grouped",
                     help="how a step issues the seven projections: one spqr_gemv_grouped call (2 launches), q/k/v and "
                          "gate/up as one spqr_gemv_fused call each (4 launches), or seven spqr_gemv calls")
+    ap.add_argument("--block-config", type=int, choices=(2, 3, 4), default=4,
+                    help="the configuration whose decoder block is the step (4, the headline workload, by default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-configs", action="store_true", help="skip the per-layer figures of configurations 0-3")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
@@ -389,7 +391,7 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
 
-    cfg = 4
+    cfg = args.block_config
     specs = synth.config_layers(cfg)
     names = [sp.name for sp in specs]
     # 60 GB of other allocations stay resident while the block runs (sizing for 288 GB of HBM)
@@ -590,9 +592,15 @@ def main():
         parity_kind = "sampled rows"
     assert max(parity) <= 1e-3, f"parity failed on the timed buffers: {parity}"
 
-    tile = "8,32" if args.group_axis == 1 else "32,8"
-    kernel = ("gemv_tile256_%skernel<3,%s,%d>" % ("" if args.calls == "seven" else "fused_", tile, args.group_axis))
-    kernel_key = "gemv_tile256_w3_%s_axis%d_config4_block" % (tile.replace(",", "x"), args.group_axis)
+    sp0 = specs[0]
+    tr, tc = synth.tile_shape(sp0.beta1, sp0.beta2, args.group_axis)
+    tile = f"{tr},{tc}"
+    kernel = ("gemv_tile256_%skernel<%d,%s,%d>" % ("" if args.calls == "seven" else "fused_", sp0.w_bits, tile, args.group_axis))
+    kernel_key = "gemv_tile256_w%d_%s_axis%d_config%d_block" % (sp0.w_bits, tile.replace(",", "x"), args.group_axis, cfg)
+    model = {2: "LLaMA-7B", 3: "LLaMA-33B", 4: "LLaMA-65B"}[cfg]
+    shapes = {}
+    for spx, nb in zip(specs, bytes_layer):
+        shapes.setdefault((spx.m, spx.n), [0, nb])[0] += 1
     out = {
         "metric": "SpQR GEMV µs/layer + achieved HBM GB/s (% of peak), batch 1",
         "value": round(gbs, 2),
@@ -604,9 +612,11 @@ def main():
         "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "config 4: one LLaMA-65B-shaped decoder block, q/k/v/o 8192x8192 + gate/up 22016x8192 + "
-                               f"down 8192x22016, w=3, beta1=8, beta2=32, group_axis={args.group_axis}, 2% outliers "
-                               f"(64 full columns + uniform), batch 1, beside {args.filler_gb} GB of filler allocations",
+        "config": {"workload": f"config {cfg}: one {model}-shaped decoder block, q/k/v/o {specs[0].m}x{specs[0].n} + gate/up "
+                               f"{specs[4].m}x{specs[4].n} + down {specs[6].m}x{specs[6].n}, w={sp0.w_bits}, "
+                               f"beta1={sp0.beta1}, beta2={sp0.beta2}, group_axis={args.group_axis}, "
+                               f"{100 * sp0.outlier_rate:g}% outliers ({sp0.outlier_structure}), batch 1, beside "
+                               f"{args.filler_gb} GB of filler allocations",
                    "launches_per_step": launches_per_step, "calls": args.calls, "weight_copies": copies,
                    "pool_MB": round(pool_bytes / 1e6, 1), "graph_replay": bool(use_graph),
                    "wall_ms_per_step": round(wall * 1e3 / steps_timed, 6),
@@ -620,8 +630,9 @@ def main():
                      "kernel": kernel,
                      "algorithmic_bytes_per_launch": step_bytes // launches_per_step,
                      "avg_launch_us": round(avg_launch_s * 1e6, 3),
-                     "note": "per launch = mean over the step's launches; the seven projections hold 4 x 39.0 MB, "
-                             "2 x 104.8 MB and 1 x 104.7 MB of algorithmic bytes; all launches run the same kernel body"},
+                     "note": "per launch = mean over the step's launches; the seven projections hold "
+                             + ", ".join(f"{c} x {nb / 1e6:.1f} MB" for c, nb in shapes.values())
+                             + " of algorithmic bytes; all launches run the same kernel body"},
         "cpu_baseline": cpu,
     }
     if other_configs is not None:

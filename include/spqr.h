@@ -140,6 +140,11 @@ typedef enum spqr_status {
  * whole; it shares its 16 aligned bytes, hence its page, with that entry, and
  * what lies behind entry nnz-1 is ignored.
  *
+ * max_row_nnz is a hint for the launch plan only (never for correctness): an
+ * upper estimate of the longest outlier row, 0 if unknown.  A matrix with rows
+ * of thousands of outliers (Sec. 3.2 finds whole rows of sensitive weights)
+ * gets wider workgroups for the strips that own them.
+ *
  * perm (optional, NULL = identity) is an input permutation of length n: the
  * product is taken with x'[j] = x[perm[j]] (act-order checkpoints, Sec. 5).
  */
@@ -149,7 +154,7 @@ typedef struct spqr_matrix_t {
   int32_t beta1, beta2;
   int32_t group_axis;
   int32_t layout_version;
-  int32_t reserved;           /* must be 0 */
+  int32_t max_row_nnz;        /* optional hint, >= 0: the largest number of outliers in one row, 0 = unknown */
   const void*     packed;     /* device, 16-byte aligned */
   int64_t         packed_bytes;
   const int32_t*  row_ptr;    /* device, m+1 entries */

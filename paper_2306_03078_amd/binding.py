@@ -38,7 +38,7 @@ class spqr_matrix_t(C.Structure):
         ("m", C.c_int32), ("n", C.c_int32),
         ("w_bits", C.c_int32), ("s_bits", C.c_int32), ("z_bits", C.c_int32),
         ("beta1", C.c_int32), ("beta2", C.c_int32),
-        ("group_axis", C.c_int32), ("layout_version", C.c_int32), ("reserved", C.c_int32),
+        ("group_axis", C.c_int32), ("layout_version", C.c_int32), ("max_row_nnz", C.c_int32),
         ("packed", C.c_void_p), ("packed_bytes", C.c_int64),
         ("row_ptr", C.c_void_p), ("col_idx", C.c_void_p), ("out_val", C.c_void_p),
         ("nnz", C.c_int64), ("perm", C.c_void_p),
@@ -167,7 +167,7 @@ class SpQRMatrix:
     descriptor points into them."""
 
     def __init__(self, m, n, w_bits, beta1, beta2, group_axis, packed, row_ptr, col_idx, val,
-                 perm=None, s_bits=3, z_bits=3, layout_version=SPQR_LAYOUT_V1):
+                 perm=None, s_bits=3, z_bits=3, layout_version=SPQR_LAYOUT_V1, max_row_nnz=0):
         self.m, self.n = int(m), int(n)
         self.w_bits, self.s_bits, self.z_bits = int(w_bits), int(s_bits), int(z_bits)
         self.beta1, self.beta2, self.group_axis = int(beta1), int(beta2), int(group_axis)
@@ -178,7 +178,8 @@ class SpQRMatrix:
         d.w_bits, d.s_bits, d.z_bits = self.w_bits, self.s_bits, self.z_bits
         d.beta1, d.beta2, d.group_axis = self.beta1, self.beta2, self.group_axis
         self.layout_version = int(layout_version)
-        d.layout_version, d.reserved = self.layout_version, 0
+        self.max_row_nnz = int(max_row_nnz)
+        d.layout_version, d.max_row_nnz = self.layout_version, self.max_row_nnz
         d.packed, d.packed_bytes = packed.data_ptr(), packed.numel()
         d.row_ptr = row_ptr.data_ptr()
         d.col_idx = col_idx.data_ptr() if self.nnz else None
@@ -206,14 +207,15 @@ class SpQRMatrix:
         if getattr(fmt, "perm", None) is not None:
             perm = torch.from_numpy(np.ascontiguousarray(fmt.perm, dtype=np.int32)).to(device)
         return cls(fmt.m, fmt.n, fmt.w_bits, fmt.beta1, fmt.beta2, fmt.group_axis, packed, row_ptr,
-                   col, val, perm, fmt.s_bits, fmt.z_bits, layout_version_of(fmt))
+                   col, val, perm, fmt.s_bits, fmt.z_bits, layout_version_of(fmt),
+                   int(np.diff(np.asarray(fmt.row_ptr, dtype=np.int64)).max()) if fmt.m > 0 else 0)
 
     def clone(self):
         """A second copy of all device buffers (distinct addresses)."""
         return SpQRMatrix(self.m, self.n, self.w_bits, self.beta1, self.beta2, self.group_axis,
                           self.packed.clone(), self.row_ptr.clone(), self.col_idx.clone(),
                           self.val.clone(), None if self.perm is None else self.perm.clone(),
-                          self.s_bits, self.z_bits, self.layout_version)
+                          self.s_bits, self.z_bits, self.layout_version, self.max_row_nnz)
 
 
 def _check(rc: int, where: str):

@@ -12,7 +12,7 @@ namespace {
 // O(1) checks shared by every device entry point.
 int to_device_matrix(const spqr_matrix_t* A, spqr::DevMatrix* D) {
   if (!A) return SPQR_ERR_NULL;
-  if (A->reserved != 0) return SPQR_ERR_PARAM;
+  if (A->max_row_nnz < 0) return SPQR_ERR_PARAM;
   int rc = spqr::make_geometry(A->layout_version, A->m, A->n, A->w_bits, A->s_bits, A->z_bits, A->beta1, A->beta2,
                                A->group_axis, &D->g);
   if (rc) return rc;
@@ -32,6 +32,7 @@ int to_device_matrix(const spqr_matrix_t* A, spqr::DevMatrix* D) {
   D->val = A->out_val;
   D->perm = A->perm;
   D->nnz = A->nnz;
+  D->max_row_nnz = A->max_row_nnz;
   return SPQR_OK;
 }
 

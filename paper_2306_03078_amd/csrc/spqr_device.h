@@ -19,6 +19,7 @@ struct DevMatrix {
   const uint16_t* val;
   const int32_t* perm;
   int64_t nnz;
+  int32_t max_row_nnz;            // hint for the launch plan: longest outlier row, 0 = unknown
 };
 
 __device__ __forceinline__ float h2f(uint16_t bits) {

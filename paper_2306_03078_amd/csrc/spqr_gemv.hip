@@ -14,7 +14,7 @@ namespace spqr {
 // per thread (the common, single-barrier path) and up to eight.  Static arrays (red, osum, lred, rp) come on
 // top; the sum must stay within the CU's 160 KB.
 // ---------------------------------------------------------------------------
-bool plan_launch(const Geometry& g, int nb, int max_waves, int slots, LaunchPlan* out) {
+bool plan_launch(const Geometry& g, int nb, int max_waves, int slots, LaunchPlan* out, int max_row_nnz) {
   const int nsteps = (g.ntc + 63) / 64;
   const int xbytes = (nb * g.n * 2 + 15) & ~15;
   const int fixed = static_lds_bytes(g.tile_rows, nb) + 1024;
@@ -45,6 +45,11 @@ bool plan_launch(const Geometry& g, int nb, int max_waves, int slots, LaunchPlan
     // step (-7 % at 4 steps per slot, -13 to -18 % at 6 to 9).
     const double steps_per_slot = (double)g.ntr * nsteps / (16.0 * kCUs);
     if (nsteps <= 8 && !(nsteps >= 4 && steps_per_slot >= 3.5 && rmax >= 2)) { P = nsteps < 4 ? nsteps : 4; R = 1; }
+    // A row of very many outliers (the caller's hint) makes its strip's workgroup the last to finish: if the row
+    // does not fit the one round of 8 chunks per thread that four wavefronts hold in LDS (16384 entries), eight
+    // wavefronts take it in one (6656x17920 with Zipf row counts, rows of up to 17920 entries: 21.4 against
+    // 26.4 us; rows that fit, e.g. 11008 entries in 4096x11008, are slower with eight: 11.9 against 9.9).
+    else if (nsteps > 8 && max_row_nnz > 16000 && rmax >= 2 && max_waves >= 8) { P = 4; R = 2; }
     else if (nsteps <= 8 || (g.ntr >= 400 && rmax >= 2)) { P = 2; R = 2; }
     else { P = max_waves < 8 ? max_waves : 8; R = 1; }
   } else {

@@ -21,7 +21,7 @@ struct LaunchPlan { int P; int R; int cap; size_t lds; };
 
 
 // spqr_gemv.hip
-bool plan_launch(const Geometry& g, int nb, int max_waves, int slots, LaunchPlan* out);
+bool plan_launch(const Geometry& g, int nb, int max_waves, int slots, LaunchPlan* out, int max_row_nnz = 0);
 hipError_t kernel_slots(const void* fn, int max_dynamic, PerDevice* known, int* slots);
 // one pair per statistic layout (spqr_gemv_l1/l2/l3.hip), one for the 8 x 64 tiles of layout 1 (spqr_gemv_l1w.hip)
 hipError_t launch_tuned_l1(const DevMatrix& A, const uint16_t* x, int nb, void* y, int y_dtype, hipStream_t stream);
@@ -49,7 +49,7 @@ static hipError_t launch_tile256(const DevMatrix& A, const uint16_t* x, void* y,
   hipError_t e = kernel_slots(fn, MAX_DYNAMIC, &known[A.perm ? 1 : 0], &slots);
   if (e != hipSuccess) return e;
   LaunchPlan plan = {0, 0, 0, 0};
-  if (!plan_launch(A.g, NB, MAXW, slots, &plan)) return hipErrorInvalidValue;
+  if (!plan_launch(A.g, NB, MAXW, slots, &plan, A.max_row_nnz)) return hipErrorInvalidValue;
   const int nw = plan.P * plan.R;
   // what the kernel assumes of its launch and of the tile's size: checked here, on the host
   using T = TileRegs<W, TR, TC, AXIS, LV>;
@@ -79,9 +79,13 @@ static hipError_t launch_fused256(const DevMatrix* As, int count, const uint16_t
   if (e != hipSuccess) return e;
   Geometry all = As[0].g;                    // the plan sees the strips of all matrices
   all.ntr = 0;
-  for (int i = 0; i < count; ++i) all.ntr += As[i].g.ntr;
+  int longest = 0;                           // the longest outlier row any of them is said to have
+  for (int i = 0; i < count; ++i) {
+    all.ntr += As[i].g.ntr;
+    if (As[i].max_row_nnz > longest) longest = As[i].max_row_nnz;
+  }
   LaunchPlan plan = {0, 0, 0, 0};
-  if (!plan_launch(all, 1, MAXW, slots, &plan)) return hipErrorInvalidValue;
+  if (!plan_launch(all, 1, MAXW, slots, &plan, longest)) return hipErrorInvalidValue;
   const int nw = plan.P * plan.R;
   using T = TileRegs<W, TR, TC, AXIS, LV>;
   if (all.kw != T::KW || all.sd != T::SD || all.layout != LV) return hipErrorInvalidValue;

@@ -139,6 +139,9 @@ def test_host_side_descriptor_checks_need_no_gpu():
     assert lib.spqr_gemv(C.byref(d), None, None, 0, None) == -3
     d.w_bits = 3
     assert lib.spqr_gemv(C.byref(d), None, None, 0, None) == -1      # packed is NULL
+    d.max_row_nnz = -5
+    assert lib.spqr_gemv(C.byref(d), None, None, 0, None) == -3      # the hint is a count
+    d.max_row_nnz = 0
     d.layout_version = 2
     assert lib.spqr_dequant_dense(C.byref(d), 0, None, None) == -1   # the integer zero-point layout: packed is NULL
     d.layout_version = 3
