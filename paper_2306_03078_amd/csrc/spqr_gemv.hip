@@ -14,7 +14,7 @@ namespace spqr {
 // per thread (the common, single-barrier path) and up to eight.  Static arrays (red, osum, lred, rp) come on
 // top; the sum must stay within the CU's 160 KB.
 // ---------------------------------------------------------------------------
-bool plan_launch(const Geometry& g, int nb, int max_waves, int slots, LaunchPlan* out, int max_row_nnz) {
+bool plan_launch(const Geometry& g, int nb, int max_waves, int slots, LaunchPlan* out, int max_row_nnz, bool mf) {
   const int nsteps = (g.ntc + 63) / 64;
   const int xbytes = (nb * g.n * 2 + 15) & ~15;
   const int fixed = static_lds_bytes(g.tile_rows, nb) + 1024;
@@ -44,7 +44,15 @@ bool plan_launch(const Geometry& g, int nb, int max_waves, int slots, LaunchPlan
     // the chip: there two wavefronts per strip, two steps each, save the per-wavefront overhead of every second
     // step (-7 % at 4 steps per slot, -13 to -18 % at 6 to 9).
     const double steps_per_slot = (double)g.ntr * nsteps / (16.0 * kCUs);
-    if (nsteps <= 8 && !(nsteps >= 4 && steps_per_slot >= 3.5 && rmax >= 2)) { P = nsteps < 4 ? nsteps : 4; R = 1; }
+    // Instances whose row dot products run on the matrix cores (mf) hold three wavefronts per SIMD and are less
+    // bound by vector-ALU issue: one wavefront per strip with all of its steps, four strips per workgroup, wins on
+    // the large launches (six projections of a 65B block in one grid: 65.4 against 67.3 us with two two-step
+    // wavefronts per strip) and on long strips with at least a workgroup per compute unit (8192x22016: 23.0 against
+    // 23.6); a single 22016x8192 takes two two-step wavefronts (23.7 against 25.4 with four one-step ones).
+    if (mf && rmax >= 4 && max_waves >= 4 && max_row_nnz <= 16000 &&
+        ((nsteps <= 8 && nsteps >= 4 && steps_per_slot >= 3.5) || (nsteps > 8 && g.ntr >= 4 * kCUs))) { P = 1; R = 4; }
+    else if (mf && rmax >= 2 && nsteps <= 8 && nsteps >= 4 && steps_per_slot >= 2.0) { P = 2; R = 2; }
+    else if (nsteps <= 8 && !(nsteps >= 4 && steps_per_slot >= 3.5 && rmax >= 2)) { P = nsteps < 4 ? nsteps : 4; R = 1; }
     // A row of very many outliers (the caller's hint) makes its strip's workgroup the last to finish: if the row
     // does not fit the one round of 8 chunks per thread that four wavefronts hold in LDS (16384 entries), eight
     // wavefronts take it in one (6656x17920 with Zipf row counts, rows of up to 17920 entries: 21.4 against
@@ -126,7 +134,9 @@ int tuned_batch_width(const Geometry& g, int want) {
   if (g.layout != kBilevel || wide) want = 1;  // built for one vector per launch
   for (int nb = want >= 4 ? 4 : (want >= 2 ? 2 : 1); nb >= 1; nb >>= 1) {
     LaunchPlan plan = {0, 0, 0, 0};
-    const int maxw = (g.w_bits == 3 && nb == 1 && g.layout != kStats16 && !wide) ? 16 : 8;   // WavesPerGroup
+    const bool mf = RowDotsOnMatrixCores<3, 8, 32, 1, 1, 1>::value && g.w_bits == 3 && g.tile_rows == 8 &&
+                    g.tile_cols == 32 && g.axis == 1 && nb == 1 && g.layout == kBilevel;
+    const int maxw = (g.w_bits == 3 && nb == 1 && g.layout != kStats16 && !wide && !mf) ? 16 : 8;   // WavesPerGroup
     if (plan_launch(g, nb, maxw, 8, &plan)) return nb;   // 8 slots: the lowest occupancy any instance has
   }
   return 0;

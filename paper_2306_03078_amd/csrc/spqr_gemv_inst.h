@@ -21,7 +21,7 @@ struct LaunchPlan { int P; int R; int cap; size_t lds; };
 
 
 // spqr_gemv.hip
-bool plan_launch(const Geometry& g, int nb, int max_waves, int slots, LaunchPlan* out, int max_row_nnz = 0);
+bool plan_launch(const Geometry& g, int nb, int max_waves, int slots, LaunchPlan* out, int max_row_nnz = 0, bool mf = false);
 hipError_t kernel_slots(const void* fn, int max_dynamic, PerDevice* known, int* slots);
 // one pair per statistic layout (spqr_gemv_l1/l2/l3.hip), one for the 8 x 64 tiles of layout 1 (spqr_gemv_l1w.hip)
 hipError_t launch_tuned_l1(const DevMatrix& A, const uint16_t* x, int nb, void* y, int y_dtype, hipStream_t stream);
@@ -40,7 +40,7 @@ hipError_t launch_fused_l3(const DevMatrix* As, int count, const uint16_t* const
 template <int W, int TR, int TC, int AXIS, int NB, int LV>
 static hipError_t launch_tile256(const DevMatrix& A, const uint16_t* x, void* y, int y_dtype,
                                  hipStream_t stream) {
-  constexpr int MAXW = WavesPerGroup<W, NB, LV, TR * TC>::MAX;
+  constexpr int MAXW = WavesPerGroup<W, NB, LV, TR * TC, RowDotsOnMatrixCores<W, TR, TC, AXIS, NB, LV>::value>::MAX;
   constexpr int MAX_DYNAMIC = 160 * 1024 - static_lds_bytes(TR, NB) - 1024;   // static + dynamic <= 160 KB
   static PerDevice known[2];                 // wavefront slots per CU of the instance, 0 = not asked yet
   const void* fn = A.perm ? reinterpret_cast<const void*>(&gemv_tile256_kernel<W, TR, TC, AXIS, true, NB, LV>)
@@ -49,7 +49,7 @@ static hipError_t launch_tile256(const DevMatrix& A, const uint16_t* x, void* y,
   hipError_t e = kernel_slots(fn, MAX_DYNAMIC, &known[A.perm ? 1 : 0], &slots);
   if (e != hipSuccess) return e;
   LaunchPlan plan = {0, 0, 0, 0};
-  if (!plan_launch(A.g, NB, MAXW, slots, &plan, A.max_row_nnz)) return hipErrorInvalidValue;
+  if (!plan_launch(A.g, NB, MAXW, slots, &plan, A.max_row_nnz, RowDotsOnMatrixCores<W, TR, TC, AXIS, NB, LV>::value)) return hipErrorInvalidValue;
   const int nw = plan.P * plan.R;
   // what the kernel assumes of its launch and of the tile's size: checked here, on the host
   using T = TileRegs<W, TR, TC, AXIS, LV>;
@@ -70,7 +70,7 @@ static hipError_t launch_tile256(const DevMatrix& A, const uint16_t* x, void* y,
 template <int W, int TR, int TC, int AXIS, int LV>
 static hipError_t launch_fused256(const DevMatrix* As, int count, const uint16_t* const* xs, void* const* ys,
                                   int y_dtype, hipStream_t stream) {
-  constexpr int MAXW = WavesPerGroup<W, 1, LV, TR * TC>::MAX;
+  constexpr int MAXW = WavesPerGroup<W, 1, LV, TR * TC, RowDotsOnMatrixCores<W, TR, TC, AXIS, 1, LV>::value>::MAX;
   constexpr int MAX_DYNAMIC = 160 * 1024 - static_lds_bytes(TR, 1) - 1024;
   static PerDevice known;
   int slots = 0;
@@ -85,7 +85,7 @@ static hipError_t launch_fused256(const DevMatrix* As, int count, const uint16_t
     if (As[i].max_row_nnz > longest) longest = As[i].max_row_nnz;
   }
   LaunchPlan plan = {0, 0, 0, 0};
-  if (!plan_launch(all, 1, MAXW, slots, &plan, longest)) return hipErrorInvalidValue;
+  if (!plan_launch(all, 1, MAXW, slots, &plan, longest, RowDotsOnMatrixCores<W, TR, TC, AXIS, 1, LV>::value)) return hipErrorInvalidValue;
   const int nw = plan.P * plan.R;
   using T = TileRegs<W, TR, TC, AXIS, LV>;
   if (all.kw != T::KW || all.sd != T::SD || all.layout != LV) return hipErrorInvalidValue;

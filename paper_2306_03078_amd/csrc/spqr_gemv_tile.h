@@ -24,6 +24,23 @@ template <int W, int TC> struct RowPhases {
   static constexpr int N = (W == 4 || TC / 2 >= 16 || !SharedShifts<TC>::value) ? 1 : 16 / (TC / 2);
 };
 
+// Row dot products on the matrix cores.  The vector ALU is what bounds a launch much larger than the chip, and half
+// of a tile's instructions are the v_dot2 of its code pairs.  v_mfma_f32_4x4x4_16b_f16 works on 16 independent
+// blocks of 4 lanes: D_b[i][j] = sum_k A_b[i][k] * B_b[k][j], lane 4b + i supplying row i of A (4 binary16 values)
+// and lane 4b + j column j of B.  With a lane's two extracted code pairs as its A values and the matching two pairs of
+// u as its B values, the diagonal element D_b[l % 4][l % 4] is the lane's own dot product over four columns (the
+// other twelve products of a block pair one lane's codes with another lane's activations and are ignored); it sits
+// in register l % 4 of the lane's four result registers, whichever way the block's result is laid out.  One
+// instruction replaces two v_dot2 and runs beside the vector ALU; a tile row keeps four accumulators instead of one.
+#ifndef SPQR_ROW_DOTS_MFMA
+#define SPQR_ROW_DOTS_MFMA 1
+#endif
+template <int W, int TR, int TC, int AXIS, int NB, int LV> struct RowDotsOnMatrixCores {
+  static constexpr bool value = SPQR_ROW_DOTS_MFMA && W == 3 && TR == 8 && TC == 32 && AXIS == 1 && NB == 1 && LV == 1;
+};
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+
 // One tile's contribution for NB activation vectors (LDS rows of `xstride`
 // dwords).  Codes enter the dot products as K + q/2^W (K by class, see above) and
 // the statistic codes as 1 + s_q/8, 1 + z_q/8 (exact binary16 values); the offsets
@@ -55,10 +72,12 @@ __device__ __forceinline__ uint32_t high_halves(uint32_t a, uint32_t b) {
 // A tile wider than 32 columns (8 x 64, group_axis 1: Sec. 5's beta2 = 64) is worked off in column halves: TC is the
 // width of the view, TCF the tile's, H the half; a half has whole 3-bit triples per row (TC / 2 = 16 pairs), so
 // classes, phases and shifted words are those of an 8 x 32 tile.
-template <int W, int TR, int TC, int AXIS, int NB, int LV, int TCF = TC, int H = 0>
+// MF: the row dot products go to the matrix cores and accumulate in accm (four registers per row, the lane's own
+// sum in register lane % 4); acc is then left alone.
+template <int W, int TR, int TC, int AXIS, int NB, int LV, int TCF = TC, int H = 0, bool MF = false>
 __device__ __forceinline__ void tile_fma(const TileRegs<W, TR, TCF, AXIS, LV>& t,
                                          const uint32_t* xpair /* TC/2 dwords in LDS, vector 0 */,
-                                         int xstride, bool valid, float (&acc)[NB][TR],
+                                         int xstride, bool valid, float (&acc)[NB][TR], f32x4 (&accm)[MF ? TR : 1],
                                          float (&csum)[NB][RowPhases<W, TC>::N], const ClassConsts& k,
                                          const PairConsts& k1, const PairConsts& k3) {
   using T = TileRegs<W, TR, TCF, AXIS, LV>;
@@ -176,6 +195,25 @@ __device__ __forceinline__ void tile_fma(const TileRegs<W, TR, TCF, AXIS, LV>& t
 #pragma unroll
       for (int h = 0; h < NPH; ++h) csum[bi][h] += fmaf(SCALE, E[h], zu);
     }
+    if constexpr (MF) {
+      static_assert(NB == 1 && SHARED && PPR % 2 == 0, "two code pairs per matrix instruction");
+#pragma unroll
+      for (int r = 0; r < TR; ++r) {
+        f32x4 d = accm[r];
+#pragma unroll
+        for (int p = 0; p < PPR; p += 2) {
+          const int q = r * PPRF + P0 + p;
+          refresh_shifted<W>(sw, t.c, q);
+          const uint32_t qa = pair_class_f16<W>(t.c, sw, q, k);
+          refresh_shifted<W>(sw, t.c, q + 1);
+          const uint32_t qb = pair_class_f16<W>(t.c, sw, q + 1, k);
+          typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+          const u32x2 a2 = {qa, qb}, b2 = {xp[0][p], xp[0][p + 1]};
+          d = __builtin_amdgcn_mfma_f32_4x4x4f16(__builtin_bit_cast(half4_t, a2), __builtin_bit_cast(half4_t, b2), d, 0, 0, 0);
+        }
+        accm[r] = d;
+      }
+    } else {
 #pragma unroll
     for (int r = 0; r < TR; ++r) {
       float d[NB];
@@ -191,6 +229,7 @@ __device__ __forceinline__ void tile_fma(const TileRegs<W, TR, TCF, AXIS, LV>& t
       }
 #pragma unroll
       for (int bi = 0; bi < NB; ++bi) acc[bi][r] = d[bi];
+    }
     }
   } else {
     float X[NB], SE[NB][NPH];
@@ -278,7 +317,6 @@ __device__ __forceinline__ void chunk_products(const uint16_t* xs, uint32_t last
 }
 
 __device__ __forceinline__ void store_products(float* prod, int slot, const float (&p)[8]) {
-  typedef float f32x4 __attribute__((ext_vector_type(4)));
   f32x4 lo = {p[0], p[1], p[2], p[3]}, hi = {p[4], p[5], p[6], p[7]};
   reinterpret_cast<f32x4*>(prod)[2 * slot] = lo;
   reinterpret_cast<f32x4*>(prod)[2 * slot + 1] = hi;
@@ -303,8 +341,9 @@ __device__ __forceinline__ float strided16_sum(const float* prod, int lo, int hi
 // accumulators.
 // Layout 3 keeps beta2 statistic dwords per tile instead of 8: it needs the 256.
 // So does a tile of 512 codes (48 code registers per buffer).
-template <int W, int NB, int LV = 1, int CODES = 256> struct WavesPerGroup {
-  static constexpr int MAX = (W == 3 && NB == 1 && LV != 3 && CODES == 256) ? 16 : 8;
+// And so do the four accumulators per row of the instances whose row dot products run on the matrix cores (MF).
+template <int W, int NB, int LV = 1, int CODES = 256, bool MF = false> struct WavesPerGroup {
+  static constexpr int MAX = (W == 3 && NB == 1 && LV != 3 && CODES == 256 && !MF) ? 16 : 8;
 };
 
 // NB activation vectors per launch: X holds NB rows of n binary16 values (row
@@ -437,7 +476,11 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
 
   // ---- dense part -------------------------------------------------------------
   constexpr int NPH = RowPhases<W, TCV>::N;
+  constexpr bool MF = RowDotsOnMatrixCores<W, TR, TC, AXIS, NB, LV>::value;
   float acc[NB][TR], csum[NB][NPH];
+  f32x4 accm[MF ? TR : 1];
+#pragma unroll
+  for (int r = 0; r < (MF ? TR : 1); ++r) accm[r] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int bi = 0; bi < NB; ++bi) {
 #pragma unroll
@@ -455,9 +498,9 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
   do {                                                                                                     \
     const uint32_t* xt_ = xs32 + (64 * (st) + min(lane, (L) - 1)) * (TC / 2);                              \
     const bool valid_ = live && lane < (L);                                                                \
-    tile_fma<W, TR, TCV, AXIS, NB, LV, TC, 0>(t, xt_, n >> 1, valid_, acc, csum, kc, k1, k3);             \
-    if constexpr (TCV != TC)                                                                               \
-      tile_fma<W, TR, TCV, AXIS, NB, LV, TC, 1>(t, xt_ + TCV / 2, n >> 1, valid_, acc, csum, kc, k1, k3); \
+    tile_fma<W, TR, TCV, AXIS, NB, LV, TC, 0, MF>(t, xt_, n >> 1, valid_, acc, accm, csum, kc, k1, k3);             \
+    if constexpr (TCV != TC)                                                                                         \
+      tile_fma<W, TR, TCV, AXIS, NB, LV, TC, 1, MF>(t, xt_ + TCV / 2, n >> 1, valid_, acc, accm, csum, kc, k1, k3); \
   } while (0)
   // Two steps per trip, registers ping-pong; the loop has its one exit at the
   // bottom (a second exit would be merged with it through a block that makes the
@@ -523,6 +566,14 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
   }
 
   // ---- dense partials: lanes -> rows ---------------------------------------------
+  if constexpr (MF) {                        // the lane's own sums out of the matrix cores' result registers
+    const int t4 = lane & 3;
+#pragma unroll
+    for (int r = 0; r < TR; ++r) {
+      const f32x4 d = accm[r];
+      acc[0][r] = t4 == 0 ? d.x : (t4 == 1 ? d.y : (t4 == 2 ? d.z : d.w));
+    }
+  }
 #pragma unroll
   for (int bi = 0; bi < NB; ++bi) {
     if constexpr (AXIS == 1) {
@@ -676,7 +727,7 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
 }
 
 template <int W, int TR, int TC, int AXIS, bool PERM, int NB, int LV = 1>
-__global__ void __launch_bounds__((64 * WavesPerGroup<W, NB, LV, TR * TC>::MAX))
+__global__ void __launch_bounds__((64 * WavesPerGroup<W, NB, LV, TR * TC, RowDotsOnMatrixCores<W, TR, TC, AXIS, NB, LV>::value>::MAX))
 gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restrict__ y, int y_dtype,
                     int chunk_cap, int strips_per_group, int waves_per_strip) {
   gemv_tile256_body<W, TR, TC, AXIS, PERM, NB, LV>(A, x, y, y_dtype, chunk_cap, blockIdx.x * strips_per_group,
@@ -701,7 +752,7 @@ struct FusedArgs {
 };
 
 template <int W, int TR, int TC, int AXIS, int LV = 1>
-__global__ void __launch_bounds__((64 * WavesPerGroup<W, 1, LV, TR * TC>::MAX))
+__global__ void __launch_bounds__((64 * WavesPerGroup<W, 1, LV, TR * TC, RowDotsOnMatrixCores<W, TR, TC, AXIS, 1, LV>::value>::MAX))
 gemv_tile256_fused_kernel(FusedArgs F, int y_dtype, int chunk_cap, int strips_per_group, int waves_per_strip) {
   int i = 0;
   while (i + 1 < F.count && (int)blockIdx.x >= F.first[i + 1]) ++i;   // workgroup-uniform, count <= SPQR_MAX_FUSED
