@@ -444,15 +444,12 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
 #pragma unroll
     for (int k = 0; k < XCH; ++k)            // clamped duplicates store the same value again
       dst[min(tid + k * nthreads, nvec - 1)] = xr[k];
-    if constexpr (NB == 1) {                 // very long x: the rest, one chunk at a time
-      for (int i = tid + XCH * nthreads; i < nvec; i += nthreads) dst[i] = reinterpret_cast<const u32x4*>(x)[i];
-    } else {                                 // several vectors: further batches of XCH chunks
-      for (int i0 = tid + XCH * nthreads; i0 < nvec; i0 += XCH * nthreads) {
+    // a long x (or several vectors): further batches of XCH chunks, the loads of a batch in flight together
+    for (int i0 = tid + XCH * nthreads; i0 < nvec; i0 += XCH * nthreads) {
 #pragma unroll
-        for (int k = 0; k < XCH; ++k) xr[k] = reinterpret_cast<const u32x4*>(x)[min(i0 + k * nthreads, nvec - 1)];
+      for (int k = 0; k < XCH; ++k) xr[k] = reinterpret_cast<const u32x4*>(x)[min(i0 + k * nthreads, nvec - 1)];
 #pragma unroll
-        for (int k = 0; k < XCH; ++k) dst[min(i0 + k * nthreads, nvec - 1)] = xr[k];
-      }
+      for (int k = 0; k < XCH; ++k) dst[min(i0 + k * nthreads, nvec - 1)] = xr[k];
     }
     for (int j = (nvec << 3) + tid; j < NB * n; j += nthreads) xs[j] = x[j];
   } else {
