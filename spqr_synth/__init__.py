@@ -45,7 +45,7 @@ import numpy as np
 
 __all__ = [
     "SpQRLogical", "tile_shape", "make_matrix", "make_x", "outlier_positions",
-    "LayerSpec", "CONFIGS", "config_layers", "make_config_layer",
+    "LayerSpec", "CONFIGS", "config_layers", "make_config_layer", "make_quantizer_problem",
 ]
 
 
@@ -281,3 +281,21 @@ def make_config_layer(cfg: int, layer: int, group_axis: int = 1, stat_layout: st
     return make_matrix(sp.m, sp.n, w_bits=sp.w_bits, beta1=sp.beta1, beta2=sp.beta2,
                        group_axis=group_axis, outlier_rate=sp.outlier_rate,
                        outlier_structure=sp.outlier_structure, seed=(cfg, layer), stat_layout=stat_layout)
+
+
+def make_quantizer_problem(seed: int, m: int, n: int, d: Optional[int] = None, corr: float = 0.3,
+                           heavy: float = 0.02) -> Tuple[np.ndarray, np.ndarray]:
+    """Seeded inputs of the quantiser (Alg. 1): a weight matrix W[m, n] and calibration inputs X[n, d].
+
+    W ~ N(0, 0.05^2) with a fraction `heavy` of the entries scaled by 6 (the isolated sensitive weights of
+    Sec. 3.2); X = A G with G ~ N(0, 1)[n, d] and A = I + corr / sqrt(n) * N(0, 1)[n, n] (spectral norm of the mixing about 2 corr
+    whatever the width, so the Hessian's condition number stays in the hundreds), so that the Hessian 2 X X^T has
+    the correlated inputs the error feedback exploits.  d defaults to 4 n.  These stand in for a trained layer and
+    its calibration activations, which are not available here.
+    """
+    rng = _rng(9000 + seed, m, n)
+    W = rng.normal(0.0, 0.05, (m, n))
+    W[rng.random((m, n)) < heavy] *= 6.0
+    A = rng.normal(size=(n, n)) * (corr / np.sqrt(n)) + np.eye(n)
+    X = A @ rng.normal(size=(n, d or 4 * n))
+    return W, X

@@ -27,6 +27,10 @@ def test_library_exports_every_declared_symbol():
             "spqr_pack_host", "spqr_packed_bytes", "spqr_pack_host_layout", "spqr_packed_bytes_layout", "spqr_strerror",
             "spqr_version"} <= names
     assert "spqr_plan_batch_steps" not in names      # a test hook, not part of the public interface
+    enc = _declared(os.path.join(ROOT, "include", "spqr_encode.h"))
+    assert {"spqr_hessian", "spqr_inverse_cholesky", "spqr_inverse_cholesky_workspace_bytes", "spqr_quantize",
+            "spqr_quantize_workspace_bytes", "spqr_gather_outliers"} == enc
+    names = names | enc
     hooks = _declared(os.path.join(ROOT, "paper_2306_03078_amd", "csrc", "spqr_test_hooks.h"))
     assert hooks == {"spqr_plan_batch_steps"}
     lib = C.CDLL(P.library_path())
