@@ -107,9 +107,86 @@ struct SweepArgs {
   spqr_quantized_t out;
 };
 
+constexpr int kSuper = 64;                   // columns whose error feedback to the far columns is applied in one pass
+
+// LDS of the sweep (dynamic: more than 64 KB).
+template <int B1> struct SweepLds {
+  static constexpr int CB = B1 >= 8 ? 8 : 4;             // columns per chunk of the feedback
+  double esb[kSuper][kRows];                             // errors E of the current super-block's columns
+  double utile[kWaves][kSuper][CB];                      // per wavefront: the piece of H^ic of its current chunk
+  double wbs[B1][kRows];                                 // the block's columns
+  double ublk[B1][B1];                                   // the block's corner of H^ic
+  uint32_t omask[kWaves][kRows];
+  uint8_t qs[kRows][B1], ms[kRows][B1];
+  uint16_t vs[kRows][B1];
+};
+
+// Line 14 / line 16 for the columns [k_begin, k_end): W[:, k] -= E[:, j] * H^ic[urow0 + j, k] for j = 0 .. rows - 1, in
+// that order, one product and one difference at a time.  esrc[j][lane] is E of column urow0 + j.  Chunks of CB
+// columns are dealt to the wavefronts; a chunk's columns of W and its rows x CB piece of H^ic are requested one
+// chunk ahead; the piece passes through a corner of LDS that belongs to the wavefront, from where every lane reads
+// the same numbers (broadcast reads).  (k_end - k_begin) is a multiple of CB.
+template <int CB>
+__device__ __forceinline__ void feedback(double* __restrict__ Wt, const double* __restrict__ U, int m, int n, int rrow,
+                                         bool live, int lane, int wave, int urow0, int rows, int k_begin, int k_end,
+                                         const double (*esrc)[kRows], double (*ut)[CB]) {
+  constexpr int PER = kSuper * CB / 64;                  // values of the largest piece per lane
+  const uint32_t roff = (uint32_t)rrow * 8u;             // a column's address = its uniform base + this 32-bit offset
+  const int cells = rows * CB;
+  int k0 = k_begin + CB * wave;
+  if (k0 >= k_end) return;                               // wave-uniform
+  double cur[CB], nxt[CB], ucur[PER], unxt[PER];
+#pragma unroll
+  for (int q = 0; q < CB; ++q) cur[q] = *reinterpret_cast<const double*>(reinterpret_cast<const char*>(Wt + (size_t)(k0 + q) * m) + roff);
+#pragma unroll
+  for (int p = 0; p < PER; ++p) {
+    const int idx = min(lane + 64 * p, cells - 1);
+    ucur[p] = U[(size_t)(urow0 + idx / CB) * n + k0 + idx % CB];
+  }
+  for (; k0 < k_end; k0 += CB * kWaves) {                // wave-uniform
+    const int k1 = k0 + CB * kWaves < k_end ? k0 + CB * kWaves : k0;   // behind the last chunk: the same one again, unused
+#pragma unroll
+    for (int q = 0; q < CB; ++q) nxt[q] = *reinterpret_cast<const double*>(reinterpret_cast<const char*>(Wt + (size_t)(k1 + q) * m) + roff);
+#pragma unroll
+    for (int p = 0; p < PER; ++p) {
+      const int idx = min(lane + 64 * p, cells - 1);
+      unxt[p] = U[(size_t)(urow0 + idx / CB) * n + k1 + idx % CB];
+    }
+#pragma unroll
+    for (int p = 0; p < PER; ++p) {
+      const int idx = lane + 64 * p;
+      if (idx < cells) ut[idx / CB][idx % CB] = ucur[p];
+    }
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll 2
+    for (int j = 0; j < rows; ++j) {
+      const double ej = esrc[j][lane];
+#pragma unroll
+      for (int q = 0; q < CB; q += 2) {
+        typedef double f64x2 __attribute__((ext_vector_type(2)));
+        const f64x2 uu = *reinterpret_cast<const f64x2*>(&ut[j][q]);
+        cur[q] = cur[q] - ej * uu.x;
+        cur[q + 1] = cur[q + 1] - ej * uu.y;
+      }
+    }
+    __builtin_amdgcn_wave_barrier();
+    if (live) {
+#pragma unroll
+      for (int q = 0; q < CB; ++q) *reinterpret_cast<double*>(reinterpret_cast<char*>(Wt + (size_t)(k0 + q) * m) + roff) = cur[q];
+    }
+#pragma unroll
+    for (int q = 0; q < CB; ++q) cur[q] = nxt[q];
+#pragma unroll
+    for (int p = 0; p < PER; ++p) ucur[p] = unxt[p];
+  }
+}
+
 template <int B1>
 __global__ void __launch_bounds__(64 * kWaves) sweep_kernel(SweepArgs a) {
-  __shared__ uint32_t omask[kWaves][kRows];
+  using Lds = SweepLds<B1>;
+  constexpr int CB = Lds::CB;
+  extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+  Lds& S = *reinterpret_cast<Lds*>(smem);
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int m = a.m, n = a.n;
@@ -120,132 +197,124 @@ __global__ void __launch_bounds__(64 * kWaves) sweep_kernel(SweepArgs a) {
   const double* __restrict__ U = a.U;
   double* __restrict__ Wt = a.Wt;
 
-  for (int g = 0; g < ng; ++g) {
-    const int i = g * B1;
-    double wb[B1], hd[B1];
+  // Super-blocks of kSuper columns: inside one, a block's errors reach the super-block's remaining columns at once
+  // (they are needed next); the columns right of the super-block receive all of its errors in one pass afterwards,
+  // column by column in the same order j = 0, 1, ... - the same operations on every weight as updating after every
+  // block, with 1 / (kSuper / B1) of the traffic over the working copy.
+  for (int sb = 0; sb < n; sb += kSuper) {
+    const int sbw = min(kSuper, n - sb);
+    for (int i = sb; i < sb + sbw; i += B1) {
+      const int g = i / B1;
+      // the block's B1 x B1 corner of H^ic (rows i.., columns i..) for everybody, and its columns of W
+      for (int idx = threadIdx.x; idx < B1 * B1; idx += 64 * kWaves)
+        S.ublk[idx / B1][idx % B1] = U[(size_t)(i + idx / B1) * n + i + idx % B1];
+      if (wave == 0) {
+        double wb[B1];
 #pragma unroll
-    for (int c = 0; c < B1; ++c) {
-      wb[c] = Wt[(size_t)(i + c) * m + rrow];
-      hd[c] = U[(size_t)(i + c) * n + (i + c)];
-    }
-    // ---- outliers(): this wavefront's share of the leave-one-out tests (line 8) ----
-    uint32_t mine = 0;
-    if (a.tau < INFINITY) {
-      double base;
-      {
-        double lo = wb[0], hi = wb[0];
+        for (int c = 0; c < B1; ++c) wb[c] = Wt[(size_t)(i + c) * m + rrow];
 #pragma unroll
-        for (int c = 1; c < B1; ++c) { lo = fmin(lo, wb[c]); hi = fmax(hi, wb[c]); }
-        double s, z;
-        fit_from_range(lo, hi, a.w_top, &s, &z);
-        double t = 0.0;
-#pragma unroll
-        for (int c = 0; c < B1; ++c) {
-          const double e = (wb[c] - s * (quantize(wb[c], s, z, a.w_top) - z)) / hd[c];
-          t = t + e * e;
-        }
-        base = t;
+        for (int c = 0; c < B1; ++c) S.wbs[c][lane] = wb[c];
       }
-      for (int x = wave; x < B1; x += kWaves) {      // candidate column x (wave-uniform)
-        double lo = INFINITY, hi = -INFINITY;
-#pragma unroll
-        for (int c = 0; c < B1; ++c) {
-          if (c != x) { lo = fmin(lo, wb[c]); hi = fmax(hi, wb[c]); }
-        }
-        if (B1 == 1) { lo = 0.0; hi = 0.0; }
-        double s, z;
-        fit_from_range(lo, hi, a.w_top, &s, &z);
-        double t = 0.0;
-#pragma unroll
-        for (int c = 0; c < B1; ++c) {
-          if (c != x) {
-            const double e = (wb[c] - s * (quantize(wb[c], s, z, a.w_top) - z)) / hd[c];
-            t = t + e * e;
+      __syncthreads();
+
+      // ---- outliers(): this wavefront's share of the leave-one-out tests (line 8).  The loops over the group stay
+      // rolled: a division is a dozen instructions, and sixteen of them side by side cost more registers than a lane
+      // has. ----
+      uint32_t mine = 0;
+      if (a.tau < INFINITY) {
+        auto group_error = [&](int x) -> double {        // summed error of the group without column x (-1: all columns)
+          double lo = INFINITY, hi = -INFINITY;
+#pragma unroll 4
+          for (int c = 0; c < B1; ++c) {
+            const double v = S.wbs[c][lane];
+            if (c != x) { lo = fmin(lo, v); hi = fmax(hi, v); }
           }
+          double s, z;
+          fit_from_range(lo, hi, a.w_top, &s, &z);
+          double t = 0.0;
+#pragma unroll 2
+          for (int c = 0; c < B1; ++c) {
+            if (c != x) {
+              const double v = S.wbs[c][lane];
+              const double e = (v - s * (quantize(v, s, z, a.w_top) - z)) / S.ublk[c][c];
+              t = t + e * e;
+            }
+          }
+          return t;
+        };
+        const double base = group_error(-1);
+        for (int x = wave; x < B1; x += kWaves)          // candidate column x (wave-uniform)
+          if ((base - group_error(x)) > a.tau) mine |= 1u << x;
+      }
+      S.omask[wave][lane] = mine;
+      __syncthreads();
+
+      // ---- fit_statistics() (line 9) and lines 10-15 by the first wavefront alone: the block's columns are taken
+      // one after the other, each depending on the one before, so there is nothing to share out; the loops stay
+      // rolled over the copy of the block in LDS, which now belongs to this wavefront (the others are past their
+      // tests).  The errors go to LDS for everybody's feedback passes. ----
+      if (wave == 0) {
+        uint32_t om = 0;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) om |= S.omask[w][lane];
+        double s_hat, z_hat;
+        uint8_t sq, zq;
+        uint16_t ssb, zsb, szb, zzb;
+        {
+          double lo = INFINITY, hi = -INFINITY;
+#pragma unroll 4
+          for (int c = 0; c < B1; ++c) {
+            const double v = S.wbs[c][lane];
+            if (!((om >> c) & 1u)) { lo = fmin(lo, v); hi = fmax(hi, v); }
+          }
+          if (lo > hi) { lo = 0.0; hi = 0.0; }   // nothing left
+          double s1, z1;
+          fit_from_range(lo, hi, a.w_top, &s1, &z1);
+          second_level(s1, a.beta2, a.s_top, &s_hat, &sq, &ssb, &zsb);
+          second_level(z1, a.beta2, a.z_top, &z_hat, &zq, &szb, &zzb);
         }
-        if ((base - t) > a.tau) mine |= 1u << x;
+#pragma unroll 1
+        for (int c = 0; c < B1; ++c) {
+          const bool is_out = (om >> c) & 1u;
+          const double v = S.wbs[c][lane];
+          const double q = quantize(v, s_hat, z_hat, a.w_top);
+          const double wq = s_hat * (q - z_hat);
+          const double ec = (v - wq) / S.ublk[c][c] * (is_out ? 0.0 : 1.0);
+          S.esb[i - sb + c][lane] = ec;
+#pragma unroll 4
+          for (int k = c; k < B1; ++k) S.wbs[k][lane] = S.wbs[k][lane] - ec * S.ublk[c][k];     // line 14, inside the block
+          S.qs[lane][c] = (uint8_t)q;
+          S.ms[lane][c] = is_out ? 1 : 0;
+          S.vs[lane][c] = is_out ? f64_to_f16_bits(S.wbs[c][lane] - wq) : (uint16_t)0;
+        }
+        if (live) {
+          const size_t at = (size_t)row * n + i;
+#pragma unroll
+          for (int k = 0; k < B1 / 4; ++k) {
+            reinterpret_cast<uint32_t*>(a.out.Q + at)[k] = reinterpret_cast<const uint32_t*>(S.qs[lane])[k];
+            reinterpret_cast<uint32_t*>(a.out.outlier_mask + at)[k] = reinterpret_cast<const uint32_t*>(S.ms[lane])[k];
+          }
+#pragma unroll
+          for (int k = 0; k < B1 / 2; ++k)
+            reinterpret_cast<uint32_t*>(a.out.outlier_val + at)[k] = reinterpret_cast<const uint32_t*>(S.vs[lane])[k];
+          a.out.s_q[(size_t)row * ng + g] = sq;
+          a.out.z_q[(size_t)row * ng + g] = zq;
+          if ((row % a.beta2) == 0) {
+            const size_t t = (size_t)(row / a.beta2) * ng + g;
+            a.out.s_s[t] = ssb; a.out.z_s[t] = zsb; a.out.s_z[t] = szb; a.out.z_z[t] = zzb;
+          }
+#pragma unroll 4
+          for (int c = 0; c < B1; ++c) Wt[(size_t)(i + c) * m + row] = S.wbs[c][lane];
+        }
       }
+      __syncthreads();
+      // ---- line 16 for the rest of the super-block ----
+      feedback<CB>(Wt, U, m, n, rrow, live, lane, wave, i, B1, i + B1, sb + sbw, S.esb + (i - sb), S.utile[wave]);
+      __syncthreads();       // the next block's columns are complete; wbs, ublk, omask are free again
     }
-    omask[wave][lane] = mine;
+    // ---- line 16 for everything right of the super-block: all of its errors in one pass ----
+    feedback<CB>(Wt, U, m, n, rrow, live, lane, wave, sb, sbw, sb + sbw, n, S.esb, S.utile[wave]);
     __syncthreads();
-    uint32_t om = 0;
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) om |= omask[w][lane];
-
-    // ---- fit_statistics() (line 9): first level without the outliers, then the second level ----
-    double s_hat, z_hat;
-    uint8_t sq, zq;
-    uint16_t ssb, zsb, szb, zzb;
-    {
-      double lo = INFINITY, hi = -INFINITY;
-#pragma unroll
-      for (int c = 0; c < B1; ++c) {
-        if (!((om >> c) & 1u)) { lo = fmin(lo, wb[c]); hi = fmax(hi, wb[c]); }
-      }
-      if (lo > hi) { lo = 0.0; hi = 0.0; }   // nothing left
-      double s1, z1;
-      fit_from_range(lo, hi, a.w_top, &s1, &z1);
-      second_level(s1, a.beta2, a.s_top, &s_hat, &sq, &ssb, &zsb);
-      second_level(z1, a.beta2, a.z_top, &z_hat, &zq, &szb, &zzb);
-    }
-
-    // ---- lines 10-15: the block's columns, one after the other ----
-    double e[B1];
-    uint32_t qpack[B1 / 4], mpack[B1 / 4], vpack[B1 / 2];
-#pragma unroll
-    for (int k = 0; k < B1 / 4; ++k) { qpack[k] = 0; mpack[k] = 0; }
-#pragma unroll
-    for (int k = 0; k < B1 / 2; ++k) vpack[k] = 0;
-#pragma unroll
-    for (int c = 0; c < B1; ++c) {
-      const bool is_out = (om >> c) & 1u;
-      const double q = quantize(wb[c], s_hat, z_hat, a.w_top);
-      const double wq = s_hat * (q - z_hat);
-      e[c] = (wb[c] - wq) / hd[c] * (is_out ? 0.0 : 1.0);
-#pragma unroll
-      for (int k = c; k < B1; ++k) wb[k] = wb[k] - e[c] * U[(size_t)(i + c) * n + (i + k)];
-      qpack[c / 4] |= (uint32_t)q << (8 * (c % 4));
-      mpack[c / 4] |= (is_out ? 1u : 0u) << (8 * (c % 4));
-      const uint16_t vb = is_out ? f64_to_f16_bits(wb[c] - wq) : (uint16_t)0;
-      vpack[c / 2] |= (uint32_t)vb << (16 * (c % 2));
-    }
-    if (wave == 0 && live) {
-      const size_t at = (size_t)row * n + i;
-#pragma unroll
-      for (int k = 0; k < B1 / 4; ++k) {
-        reinterpret_cast<uint32_t*>(a.out.Q + at)[k] = qpack[k];
-        reinterpret_cast<uint32_t*>(a.out.outlier_mask + at)[k] = mpack[k];
-      }
-#pragma unroll
-      for (int k = 0; k < B1 / 2; ++k) reinterpret_cast<uint32_t*>(a.out.outlier_val + at)[k] = vpack[k];
-      a.out.s_q[(size_t)row * ng + g] = sq;
-      a.out.z_q[(size_t)row * ng + g] = zq;
-      if ((row % a.beta2) == 0) {
-        const size_t t = (size_t)(row / a.beta2) * ng + g;
-        a.out.s_s[t] = ssb; a.out.z_s[t] = zsb; a.out.s_z[t] = szb; a.out.z_z[t] = zzb;
-      }
-#pragma unroll
-      for (int c = 0; c < B1; ++c) Wt[(size_t)(i + c) * m + row] = wb[c];
-    }
-
-    // ---- line 16: the columns right of the block, in chunks of 4 dealt to the wavefronts ----
-    for (int k0 = i + B1 + 4 * wave; k0 < n; k0 += 4 * kWaves) {
-      double c0 = Wt[(size_t)k0 * m + rrow], c1 = Wt[(size_t)(k0 + 1) * m + rrow];
-      double c2 = Wt[(size_t)(k0 + 2) * m + rrow], c3 = Wt[(size_t)(k0 + 3) * m + rrow];
-#pragma unroll
-      for (int j = 0; j < B1; ++j) {
-        const double* u = U + (size_t)(i + j) * n + k0;      // wave-uniform: scalar loads
-        c0 = c0 - e[j] * u[0];
-        c1 = c1 - e[j] * u[1];
-        c2 = c2 - e[j] * u[2];
-        c3 = c3 - e[j] * u[3];
-      }
-      if (live) {
-        Wt[(size_t)k0 * m + row] = c0; Wt[(size_t)(k0 + 1) * m + row] = c1;
-        Wt[(size_t)(k0 + 2) * m + row] = c2; Wt[(size_t)(k0 + 3) * m + row] = c3;
-      }
-    }
-    __syncthreads();       // the next block's columns are complete, and omask is free again
   }
 }
 
@@ -318,6 +387,18 @@ __global__ void __launch_bounds__(256) gather_kernel(const uint8_t* __restrict__
   }
 }
 
+// The sweep's LDS exceeds the 64 KB a kernel gets without asking: the opt-in is per device and is asked for on every
+// call (a cheap host call; nothing is remembered, so nothing has to be guarded between threads).
+template <int B1>
+hipError_t launch_sweep(dim3 grid, dim3 block, hipStream_t st, const SweepArgs& a) {
+  const int lds = (int)sizeof(SweepLds<B1>);
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sweep_kernel<B1>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(sweep_kernel<B1>, grid, block, lds, st, a);
+  return hipGetLastError();
+}
+
 }  // namespace spqr_enc
 
 extern "C" {
@@ -356,12 +437,14 @@ int spqr_quantize(const double* W, const double* Hic, int32_t m, int32_t n, int3
   const dim3 tgrid((n + 31) / 32, (m + 31) / 32);
   hipLaunchKernelGGL(transpose_kernel, tgrid, dim3(256), 0, st, W, a.Wt, m, n);
   const dim3 grid((m + kRows - 1) / kRows), block(64 * kWaves);
+  hipError_t e = hipSuccess;
   switch (beta1) {
-    case 4: hipLaunchKernelGGL(sweep_kernel<4>, grid, block, 0, st, a); break;
-    case 8: hipLaunchKernelGGL(sweep_kernel<8>, grid, block, 0, st, a); break;
-    case 16: hipLaunchKernelGGL(sweep_kernel<16>, grid, block, 0, st, a); break;
-    default: hipLaunchKernelGGL(sweep_kernel<32>, grid, block, 0, st, a); break;
+    case 4: e = launch_sweep<4>(grid, block, st, a); break;
+    case 8: e = launch_sweep<8>(grid, block, st, a); break;
+    case 16: e = launch_sweep<16>(grid, block, st, a); break;
+    default: e = launch_sweep<32>(grid, block, st, a); break;
   }
+  if (e != hipSuccess) return SPQR_ERR_HIP;
   if (out->W_final) {
     const dim3 bgrid((m + 31) / 32, (n + 31) / 32);
     hipLaunchKernelGGL(transpose_kernel, bgrid, dim3(256), 0, st, a.Wt, out->W_final, n, m);

@@ -71,29 +71,45 @@ def spqr_inverse_cholesky(H, lam: float, workspace=None, stream=None):
     return U
 
 
-def spqr_quantize(W, Hic, w_bits, beta1, beta2, tau, s_bits=3, z_bits=3, want_final=True, workspace=None, stream=None):
-    """Alg. 1 lines 4-20 on device tensors W[m, n], Hic[n, n] (float64).  Returns the logical SpQR arrays
-    (group_axis 0) as host NumPy arrays in the form spqr_synth.SpQRLogical / the oracles use, plus W_final."""
+def spqr_quantize_device(W, Hic, w_bits, beta1, beta2, tau, s_bits=3, z_bits=3, want_final=True, workspace=None,
+                         outputs=None, stream=None):
+    """Alg. 1 lines 4-20 on device tensors W[m, n], Hic[n, n] (float64): enqueues the sweep and returns the
+    dictionary of output device tensors (see spqr_quantized_t in include/spqr_encode.h).  Asynchronous."""
     import torch
     assert W.dtype == torch.float64 and W.is_contiguous() and Hic.dtype == torch.float64 and Hic.is_contiguous()
     m, n = (int(v) for v in W.shape)
     dev = W.device
     lib = _lib()
     ng, nt = n // max(1, beta1), m // max(1, beta2)
-    t = dict(Q=torch.empty((m, n), dtype=torch.uint8, device=dev),
-             s_q=torch.empty((m, ng), dtype=torch.uint8, device=dev), z_q=torch.empty((m, ng), dtype=torch.uint8, device=dev),
-             s_s=torch.empty((nt, ng), dtype=torch.float16, device=dev), z_s=torch.empty((nt, ng), dtype=torch.float16, device=dev),
-             s_z=torch.empty((nt, ng), dtype=torch.float16, device=dev), z_z=torch.empty((nt, ng), dtype=torch.float16, device=dev),
-             outlier_mask=torch.empty((m, n), dtype=torch.uint8, device=dev),
-             outlier_val=torch.empty((m, n), dtype=torch.float16, device=dev),
-             row_ptr=torch.empty(m + 1, dtype=torch.int32, device=dev),
-             W_final=torch.empty((m, n), dtype=torch.float64, device=dev) if want_final else None)
+    t = outputs
+    if t is None:
+        t = dict(Q=torch.empty((m, n), dtype=torch.uint8, device=dev),
+                 s_q=torch.empty((m, ng), dtype=torch.uint8, device=dev), z_q=torch.empty((m, ng), dtype=torch.uint8, device=dev),
+                 s_s=torch.empty((nt, ng), dtype=torch.float16, device=dev), z_s=torch.empty((nt, ng), dtype=torch.float16, device=dev),
+                 s_z=torch.empty((nt, ng), dtype=torch.float16, device=dev), z_z=torch.empty((nt, ng), dtype=torch.float16, device=dev),
+                 outlier_mask=torch.empty((m, n), dtype=torch.uint8, device=dev),
+                 outlier_val=torch.empty((m, n), dtype=torch.float16, device=dev),
+                 row_ptr=torch.empty(m + 1, dtype=torch.int32, device=dev),
+                 W_final=torch.empty((m, n), dtype=torch.float64, device=dev) if want_final else None)
     out = spqr_quantized_t(**{k: (None if v is None else v.data_ptr()) for k, v in t.items()})
     need = int(lib.spqr_quantize_workspace_bytes(m, n))
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
     _check(lib.spqr_quantize(W.data_ptr(), Hic.data_ptr(), m, n, w_bits, s_bits, z_bits, beta1, beta2, float(tau),
                              C.byref(out), workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)), "spqr_quantize")
+    t["workspace"] = workspace                # keeps the scratch alive while the kernels run
+    return t
+
+
+def spqr_quantize(W, Hic, w_bits, beta1, beta2, tau, s_bits=3, z_bits=3, want_final=True, workspace=None, stream=None):
+    """spqr_quantize_device + spqr_gather_outliers, results copied to the host: the logical SpQR arrays
+    (group_axis 0) as NumPy arrays in the form spqr_synth.SpQRLogical / the oracles use, plus W_final."""
+    import torch
+    m, n = (int(v) for v in W.shape)
+    dev = W.device
+    lib = _lib()
+    t = spqr_quantize_device(W, Hic, w_bits, beta1, beta2, tau, s_bits, z_bits, want_final, workspace, None, stream)
+    t.pop("workspace")
     s = torch.cuda.current_stream() if stream is None else stream
     s.synchronize()
     nnz = int(t["row_ptr"][-1].item())
