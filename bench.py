@@ -347,6 +347,72 @@ def run_other_configs(P, synth, torch, dev, cfgs_axes):
     return out
 
 
+def run_encoder(torch, dev, with_cpu):
+    """The quantiser (Alg. 1) on one 4096 x 4096 layer: H = 2 X X^T, its inverse factor, the sweep.  Inputs are drawn
+    on the device from a seeded generator (W ~ N(0, 0.05^2) with 2 % of the entries six times larger, X = A G with
+    A = I + 0.3 / sqrt(n) N(0, 1)); the first 64 rows (one workgroup of the sweep; rows of different tiles are
+    independent) are re-run by the CPU oracle on the same H^ic and compared bit for bit, and that oracle run is the
+    CPU baseline."""
+    import numpy as np
+    import paper_2306_03078_amd.encode_binding as E
+    m = n = 4096; d = 4096; bits, b1, b2, tau, lam = 3, 16, 16, 20.0, 0.1
+    gen = torch.Generator(device=dev); gen.manual_seed(1234)
+    X = torch.randn(n, d, dtype=torch.float64, device=dev, generator=gen)
+    A = torch.eye(n, dtype=torch.float64, device=dev) + 0.3 / n ** 0.5 * torch.randn(n, n, dtype=torch.float64, device=dev, generator=gen)
+    X = A @ X
+    W = 0.05 * torch.randn(m, n, dtype=torch.float64, device=dev, generator=gen)
+    W[torch.rand(m, n, device=dev, generator=gen) < 0.02] *= 6
+    del A
+
+    def timed(fn, reps):
+        fn(); torch.cuda.synchronize()
+        a = torch.cuda.Event(enable_timing=True); b = torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            r = fn()
+        b.record(); torch.cuda.synchronize()
+        return r, a.elapsed_time(b) / reps
+    H, t_h = timed(lambda: E.spqr_hessian(X), 3)
+    ws = torch.empty(E._lib().spqr_inverse_cholesky_workspace_bytes(n), dtype=torch.uint8, device=dev)
+    U, t_c = timed(lambda: E.spqr_inverse_cholesky(H, lam, workspace=ws), 3)
+    del ws
+    outs = E.spqr_quantize_device(W, U, bits, b1, b2, tau, want_final=False)
+    wsq = outs.pop("workspace")
+    _, t_q = timed(lambda: E.spqr_quantize_device(W, U, bits, b1, b2, tau, want_final=False, outputs=outs, workspace=wsq), 3)
+    nnz = int(outs["row_ptr"][-1].item())
+    ops = float(m) * n * n           # one product and one difference per weight and earlier column of its row
+    res = {"workload": f"{m}x{n} layer, {d} calibration vectors, w={bits}, beta1={b1}, beta2={b2}, tau={tau}, lambda={lam}, "
+                       "group_axis=0 (Alg. 1's orientation), binary64",
+           "hessian_ms": round(t_h, 3), "hessian_TFLOPs": round(2.0 * n * n * d / t_h / 1e9, 2),
+           "inverse_cholesky_ms": round(t_c, 3), "quantize_ms": round(t_q, 3),
+           "weights_per_s": round(m * n / (t_q * 1e-3), 1), "outlier_rate": round(nnz / (m * n), 5),
+           "roofline": {"bound": "alu", "kernel": "sweep_kernel<16>", "unit": "Tops/s",
+                        "achieved": round(ops / (t_q * 1e-3) / 1e12, 3), "peak": 39.3,
+                        "frac": round(ops / (t_q * 1e-3) / 1e12 / 39.3, 4),
+                        "note": "binary64 products and differences of the error feedback, never fused (m n^2 of them); "
+                                "peak = half the 78.6 TFLOP/s binary64 vector rate, which counts a fused multiply-add "
+                                "as two; the launch has m / 64 = 64 workgroups for 256 compute units"}}
+    if with_cpu:
+        from oracle import spqr_encoder as enc
+        rows = 64
+        Wn = W[:rows].cpu().numpy(); Un = U.cpu().numpy()
+        t = time.perf_counter()
+        ref = enc.spqr_quantize(Wn, Un, bits, b1, b2, tau)
+        dt = time.perf_counter() - t
+        same = all(np.array_equal(outs[k][:rows].cpu().numpy().view(np.uint8) if outs[k].dtype == torch.uint8 else outs[k][:rows].cpu().numpy(),
+                                  np.asarray(getattr(ref, k))) for k in ("Q", "s_q", "z_q"))
+        same = same and np.array_equal(outs["outlier_mask"][:rows].cpu().numpy().astype(bool), ref.is_outlier)
+        same = same and all(np.array_equal(outs[k][:rows // b2].cpu().numpy().view(np.uint16), np.asarray(getattr(ref, k)).view(np.uint16))
+                            for k in ("s_s", "z_s", "s_z", "z_z"))
+        assert same, "encoder parity failed on the timed buffers"
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        res["parity"] = f"rows 0..{rows - 1}: codes, statistic codes, second-level statistics and outlier mask bit-exact"
+        res["cpu_baseline"] = {"value": round(rows * n / dt, 1), "unit": "weights/s", "cores": int(threads), "kind": "oracle",
+                               "sample": f"the sweep on the first {rows} rows of the layer (H^ic given), {dt:.2f} s"}
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -362,6 +428,7 @@ def main():
                     help="the configuration whose decoder block is the step (4, the headline workload, by default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-configs", action="store_true", help="skip the per-layer figures of configurations 0-3")
+    ap.add_argument("--no-encoder", action="store_true", help="skip the timing of the quantiser (Alg. 1)")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--sweep", metavar="PATH", default=None,
                     help="also time every distinct layer of all five configurations (both group orientations, "
@@ -543,6 +610,10 @@ def main():
                                           [(0, args.group_axis), (1, args.group_axis), (2, args.group_axis),
                                            (3, args.group_axis), (4, 1 - args.group_axis)])
 
+    encoder = None
+    if not args.no_encoder and not args.no_configs:
+        encoder = run_encoder(torch, dev, not args.no_cpu_baseline)
+
     if args.sweep:
         run_sweep(args.sweep, P, synth, torch, dev)
 
@@ -638,6 +709,8 @@ def main():
     if other_configs is not None:
         out["other_configs_batch1"] = other_configs
         out["batches_config3"] = batches
+    if encoder is not None:
+        out["encoder"] = encoder
     if batch_probe is not None:
         out["batch_probe"] = batch_probe
     print(json.dumps(out))
