@@ -429,6 +429,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-configs", action="store_true", help="skip the per-layer figures of configurations 0-3")
     ap.add_argument("--no-encoder", action="store_true", help="skip the timing of the quantiser (Alg. 1)")
+    ap.add_argument("--encoder-only", action="store_true", help="time the quantiser (Alg. 1) alone and print its figures")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--sweep", metavar="PATH", default=None,
                     help="also time every distinct layer of all five configurations (both group orientations, "
@@ -457,6 +458,9 @@ def main():
         sys.exit(2)
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.encoder_only:
+        print(json.dumps({"encoder": run_encoder(torch, dev, not args.no_cpu_baseline)}))
+        return
 
     cfg = args.block_config
     specs = synth.config_layers(cfg)
