@@ -348,14 +348,14 @@ def run_other_configs(P, synth, torch, dev, cfgs_axes):
 
 
 def run_encoder(torch, dev, with_cpu):
-    """The quantiser (Alg. 1) on one 4096 x 4096 layer: H = 2 X X^T, its inverse factor, the sweep.  Inputs are drawn
+    """The quantiser (Alg. 1) on one 11008 x 4096 layer (the gate / up projection of configurations 1 and 2): H = 2 X X^T, its inverse factor, the sweep.  Inputs are drawn
     on the device from a seeded generator (W ~ N(0, 0.05^2) with 2 % of the entries six times larger, X = A G with
     A = I + 0.3 / sqrt(n) N(0, 1)); the first 64 rows (one workgroup of the sweep; rows of different tiles are
     independent) are re-run by the CPU oracle on the same H^ic and compared bit for bit, and that oracle run is the
     CPU baseline."""
     import numpy as np
     import paper_2306_03078_amd.encode_binding as E
-    m = n = 4096; d = 4096; bits, b1, b2, tau, lam = 3, 16, 16, 20.0, 0.1
+    m, n, d = 11008, 4096, 4096; bits, b1, b2, tau, lam = 3, 16, 16, 20.0, 0.1
     gen = torch.Generator(device=dev); gen.manual_seed(1234)
     X = torch.randn(n, d, dtype=torch.float64, device=dev, generator=gen)
     A = torch.eye(n, dtype=torch.float64, device=dev) + 0.3 / n ** 0.5 * torch.randn(n, n, dtype=torch.float64, device=dev, generator=gen)
@@ -391,7 +391,7 @@ def run_encoder(torch, dev, with_cpu):
                         "frac": round(ops / (t_q * 1e-3) / 1e12 / 39.3, 4),
                         "note": "binary64 products and differences of the error feedback, never fused (m n^2 of them); "
                                 "peak = half the 78.6 TFLOP/s binary64 vector rate, which counts a fused multiply-add "
-                                "as two; the launch has m / 64 = 64 workgroups for 256 compute units"}}
+                                f"as two; the launch has m / 64 = {m // 64} workgroups for 256 compute units"}}
     if with_cpu:
         from oracle import spqr_encoder as enc
         rows = 64

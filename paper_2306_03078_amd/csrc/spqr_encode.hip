@@ -22,7 +22,13 @@
 
 namespace spqr_enc {
 
-constexpr int kWaves = 8;                    // wavefronts per workgroup of the sweep
+#ifndef SPQR_SWEEP_WAVES
+#define SPQR_SWEEP_WAVES 16
+#endif
+#ifndef SPQR_SWEEP_PREFETCH
+#define SPQR_SWEEP_PREFETCH 0       // a chunk ahead in registers: pays with 8 wavefronts per workgroup, not with 16 (4 per SIMD hide the loads)
+#endif
+constexpr int kWaves = SPQR_SWEEP_WAVES;     // wavefronts per workgroup of the sweep
 constexpr int kRows = 64;                    // rows per workgroup: one per lane
 
 // binary64 -> binary16, round to nearest even, in one rounding (integer arithmetic on the bit pattern).
@@ -145,12 +151,14 @@ __device__ __forceinline__ void feedback(double* __restrict__ Wt, const double* 
   }
   for (; k0 < k_end; k0 += CB * kWaves) {                // wave-uniform
     const int k1 = k0 + CB * kWaves < k_end ? k0 + CB * kWaves : k0;   // behind the last chunk: the same one again, unused
+    if (SPQR_SWEEP_PREFETCH) {
 #pragma unroll
     for (int q = 0; q < CB; ++q) nxt[q] = *reinterpret_cast<const double*>(reinterpret_cast<const char*>(Wt + (size_t)(k1 + q) * m) + roff);
 #pragma unroll
     for (int p = 0; p < PER; ++p) {
       const int idx = min(lane + 64 * p, cells - 1);
       unxt[p] = U[(size_t)(urow0 + idx / CB) * n + k1 + idx % CB];
+    }
     }
 #pragma unroll
     for (int p = 0; p < PER; ++p) {
@@ -174,10 +182,20 @@ __device__ __forceinline__ void feedback(double* __restrict__ Wt, const double* 
 #pragma unroll
       for (int q = 0; q < CB; ++q) *reinterpret_cast<double*>(reinterpret_cast<char*>(Wt + (size_t)(k0 + q) * m) + roff) = cur[q];
     }
+    if (SPQR_SWEEP_PREFETCH) {
 #pragma unroll
-    for (int q = 0; q < CB; ++q) cur[q] = nxt[q];
+      for (int q = 0; q < CB; ++q) cur[q] = nxt[q];
 #pragma unroll
-    for (int p = 0; p < PER; ++p) ucur[p] = unxt[p];
+      for (int p = 0; p < PER; ++p) ucur[p] = unxt[p];
+    } else if (k1 != k0) {
+#pragma unroll
+      for (int q = 0; q < CB; ++q) cur[q] = *reinterpret_cast<const double*>(reinterpret_cast<const char*>(Wt + (size_t)(k1 + q) * m) + roff);
+#pragma unroll
+      for (int p = 0; p < PER; ++p) {
+        const int idx = min(lane + 64 * p, cells - 1);
+        ucur[p] = U[(size_t)(urow0 + idx / CB) * n + k1 + idx % CB];
+      }
+    }
   }
 }
 
