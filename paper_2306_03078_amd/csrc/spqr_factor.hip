@@ -8,8 +8,10 @@
 //   init      L <- lower triangle of J A J, padded with an identity to a multiple of 64
 //   per block column k (64 wide): potrf of the diagonal block and its inverse (one workgroup, in LDS);
 //             the panel below times that inverse (transposed); the trailing lower triangle minus panel x panel^T
-//   trtri     X = L^-1 by block forward substitution, one workgroup per slice of 16 columns of X (columns of an
-//             inverse are independent), using the diagonal blocks' inverses
+//   trtri     X = L^-1 by doubling: with L = [[A, 0], [C, B]], L^-1 = [[A^-1, 0], [-B^-1 C A^-1, B^-1]].  Level s joins
+//             neighbouring diagonal blocks of 64 * 2^s: two launches of 64 x 64 tile products per level (T = C A^-1,
+//             then -B^-1 T written over C), every tile of every pair in parallel.  The inverse ends up where L was
+//             (strictly lower blocks) plus the diagonal blocks' inverses from the potrf step.
 //   final     U[i][j] = X[n-1-i][n-1-j] for j >= i
 //
 // MI355X runs binary64 fused multiply-adds on the vector ALU at the rate of its binary64 matrix instructions, so
@@ -35,6 +37,33 @@ __device__ __forceinline__ void tile_nt(double (&acc)[4][4], int K, FA fa, FB fb
       const int idx = t + 256 * q, ii = idx >> 4, kk = idx & 15;
       As[kk][ii] = fa(ii, k0 + kk);
       Bs[kk][ii] = fb(ii, k0 + kk);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < KC; ++kk) {
+      double av[4], bv[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) { av[r] = As[kk][ty * 4 + r]; bv[r] = Bs[kk][tx * 4 + r]; }
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) acc[r][c] = fma(av[r], bv[c], acc[r][c]);
+    }
+    __syncthreads();
+  }
+}
+
+// acc[r][c] += sum_{kb <= k < ke} fa(ty*4 + r, k) * fb(k, tx*4 + c): the second operand given by rows (k, j).
+template <class FA, class FB>
+__device__ __forceinline__ void tile_nn(double (&acc)[4][4], int kb, int ke, FA fa, FB fb, double (*As)[NB + 1],
+                                        double (*Bs)[NB + 1]) {
+  const int t = threadIdx.x, tx = t & 15, ty = t >> 4;
+  for (int k0 = kb; k0 < ke; k0 += KC) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int idx = t + 256 * q;
+      As[idx & 15][idx >> 4] = fa(idx >> 4, k0 + (idx & 15));      // consecutive threads: consecutive k of one row
+      Bs[idx >> 6][idx & 63] = fb(k0 + (idx >> 6), idx & 63);      // consecutive threads: consecutive j of one row k
     }
     __syncthreads();
 #pragma unroll
@@ -88,43 +117,47 @@ __global__ void __launch_bounds__(256) init_reversed_kernel(const double* __rest
   L[idx] = v;
 }
 
-// Diagonal block kb: Cholesky factor in place, its inverse to Dinv[kb].
-__global__ void __launch_bounds__(256) potrf_diag_kernel(double* __restrict__ L, int np, int kb, double* __restrict__ Dinv) {
-  __shared__ double D[NB][NB], V[NB][NB];   // 64 KB: the static limit, so no padding
-  const int t = threadIdx.x;
+// Diagonal block kb: Cholesky factor in place, its inverse to Dinv[kb].  One wavefront, a lane per row, the block in
+// LDS: the 64 steps depend on each other, so there is nothing for more wavefronts to do but wait at barriers (a
+// wavefront's LDS operations complete in order: no barrier between a step's writes and the next step's reads).
+__global__ void __launch_bounds__(64) potrf_diag_kernel(double* __restrict__ L, int np, int kb, double* __restrict__ Dinv) {
+  __shared__ double D[NB][NB + 1];
+  const int lane = threadIdx.x;
   double* blk = L + (size_t)kb * NB * np + (size_t)kb * NB;
-  for (int idx = t; idx < NB * NB; idx += 256) D[idx >> 6][idx & 63] = blk[(size_t)(idx >> 6) * np + (idx & 63)];
-  __syncthreads();
+  for (int idx = lane; idx < NB * NB; idx += 64) D[idx >> 6][idx & 63] = blk[(size_t)(idx >> 6) * np + (idx & 63)];
+  __builtin_amdgcn_s_waitcnt(0);
+  __builtin_amdgcn_wave_barrier();
   for (int j = 0; j < NB; ++j) {
-    if (t == 0) D[j][j] = sqrt(D[j][j]);
-    __syncthreads();
-    if (t > j && t < NB) D[t][j] = D[t][j] / D[j][j];
-    __syncthreads();
-    // trailing update of the lower triangle: rows i > j, columns j < k <= i
-    const int rem = NB - 1 - j;
-    for (int idx = t; idx < rem * rem; idx += 256) {
-      const int i = j + 1 + idx / rem, k = j + 1 + idx % rem;
-      if (k <= i) D[i][k] = fma(-D[i][j], D[k][j], D[i][k]);
+    const double djj = sqrt(D[j][j]);
+    const double lij = D[lane][j] / djj;
+    if (lane == j) D[j][j] = djj;
+    else if (lane > j) D[lane][j] = lij;
+    __builtin_amdgcn_wave_barrier();
+    for (int k = j + 1; k < NB; ++k) {       // row `lane`, columns j < k <= lane
+      const double lkj = D[k][j];
+      if (k <= lane) D[lane][k] = fma(-lij, lkj, D[lane][k]);
     }
-    __syncthreads();
+    __builtin_amdgcn_wave_barrier();
   }
-  // inverse of the lower triangular block, one column per thread
-  if (t < NB) {
-    const int c = t;
-    for (int i = 0; i < c; ++i) V[i][c] = 0.0;
-    V[c][c] = 1.0 / D[c][c];
-    for (int i = c + 1; i < NB; ++i) {
-      double s = 0.0;
-      for (int k = c; k < i; ++k) s = fma(D[i][k], V[k][c], s);
-      V[i][c] = -s / D[i][i];
-    }
-  }
-  __syncthreads();
+  // inverse of the lower triangular block: column `lane`, kept in registers while it is built
   double* inv = Dinv + (size_t)kb * NB * NB;
-  for (int idx = t; idx < NB * NB; idx += 256) {
+  {
+    const int c = lane;
+    double v[NB];
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+      double s = 0.0;
+#pragma unroll
+      for (int k = 0; k < i; ++k) s = fma(D[i][k], v[k], s);        // v[k] = 0 above the diagonal of the inverse
+      const double dii = D[i][i];
+      v[i] = i < c ? 0.0 : (i == c ? 1.0 / dii : -s / dii);
+    }
+#pragma unroll
+    for (int i = 0; i < NB; ++i) inv[i * NB + c] = v[i];
+  }
+  for (int idx = lane; idx < NB * NB; idx += 64) {
     const int i = idx >> 6, k = idx & 63;
     blk[(size_t)i * np + k] = k <= i ? D[i][k] : 0.0;
-    inv[idx] = V[i][k];
   }
 }
 
@@ -164,61 +197,60 @@ __global__ void __launch_bounds__(256) syrk_kernel(double* __restrict__ L, int n
     for (int c = 0; c < 4; ++c) blk[(size_t)(ty * 4 + r) * np + tx * 4 + c] -= acc[r][c];
 }
 
-// X = L^-1, 16 columns per workgroup: X[kb] = inv(L_kk) (its 16 columns); for ib > kb:
-// X[ib] = -inv(L_ii) . sum_{kb <= jb < ib} L[ib, jb] . X[jb].
-__global__ void __launch_bounds__(256) trtri_kernel(const double* __restrict__ L, int np, const double* __restrict__ Dinv,
-                                                   double* __restrict__ X) {
-  __shared__ double Ls[NB][NB + 1], Xs[NB][17], Ss[NB][17];
-  const int t = threadIdx.x;
-  const int c0 = blockIdx.x * 16, kb = c0 / NB, nb = np / NB;
-  const int r = t >> 2, cq = (t & 3) * 4;
-  // rows above the diagonal block are zero
-  for (int idx = t; idx < kb * NB * 16; idx += 256) X[(size_t)(idx >> 4) * np + c0 + (idx & 15)] = 0.0;
-  {
-    const double* inv = Dinv + (size_t)kb * NB * NB;
-    for (int idx = t; idx < NB * 16; idx += 256) {
-      const int i = idx >> 4, c = idx & 15;
-      X[(size_t)(kb * NB + i) * np + c0 + c] = inv[i * NB + (c0 - kb * NB) + c];
-    }
-  }
-  __syncthreads();
-  for (int ib = kb + 1; ib < nb; ++ib) {
-    double s[4] = {0.0, 0.0, 0.0, 0.0};
-    for (int jb = kb; jb < ib; ++jb) {
-      const double* lb = L + (size_t)ib * NB * np + (size_t)jb * NB;
-      for (int idx = t; idx < NB * NB; idx += 256) Ls[idx >> 6][idx & 63] = lb[(size_t)(idx >> 6) * np + (idx & 63)];
-      for (int idx = t; idx < NB * 16; idx += 256) Xs[idx >> 4][idx & 15] = X[(size_t)(jb * NB + (idx >> 4)) * np + c0 + (idx & 15)];
-      __syncthreads();
-#pragma unroll 8
-      for (int k = 0; k < NB; ++k) {
-        const double l = Ls[r][k];
-#pragma unroll
-        for (int c = 0; c < 4; ++c) s[c] = fma(l, Xs[k][cq + c], s[c]);
-      }
-      __syncthreads();
-    }
-#pragma unroll
-    for (int c = 0; c < 4; ++c) Ss[r][cq + c] = s[c];
-    const double* inv = Dinv + (size_t)ib * NB * NB;
-    for (int idx = t; idx < NB * NB; idx += 256) Ls[idx >> 6][idx & 63] = inv[idx];
-    __syncthreads();
-    double o[4] = {0.0, 0.0, 0.0, 0.0};
-    for (int k = 0; k <= r; ++k) {
-      const double l = Ls[r][k];
-#pragma unroll
-      for (int c = 0; c < 4; ++c) o[c] = fma(l, Ss[k][cq + c], o[c]);
-    }
-#pragma unroll
-    for (int c = 0; c < 4; ++c) X[(size_t)(ib * NB + r) * np + c0 + cq + c] = -o[c];
-    __syncthreads();       // this block row of X is read back as X[jb] from the next ib on
-  }
+// Element (r, c), r >= c, of the inverse as far as it is built: the diagonal 64-blocks live in Dinv, the blocks
+// below them where L was.
+__device__ __forceinline__ double inverse_at(const double* __restrict__ L, const double* __restrict__ Dinv, int np,
+                                             int r, int c) {
+  const int rb = r >> 6, cb = c >> 6;
+  if (rb == cb) return Dinv[(size_t)rb * NB * NB + (r & 63) * NB + (c & 63)];
+  return rb > cb ? L[(size_t)r * np + c] : 0.0;
 }
 
-__global__ void __launch_bounds__(256) unreverse_kernel(const double* __restrict__ X, int n, int np, double* __restrict__ U) {
+// Level with diagonal blocks of `b` rows: pair p joins A = [2pb, 2pb + b) and B = [2pb + b, min(2pb + 2b, np)).
+// Step 1: T = C . A^-1 into `T` (at C's place);  C = L[B rows, A columns].
+__global__ void __launch_bounds__(256) trtri_step1_kernel(const double* __restrict__ L, const double* __restrict__ Dinv,
+                                                         int np, int b, double* __restrict__ T) {
+  __shared__ double As[KC][NB + 1], Bs[KC][NB + 1];
+  const int a0 = 2 * b * blockIdx.z, b0 = a0 + b;
+  const int i0 = b0 + blockIdx.y * NB, j0 = blockIdx.x * NB;        // tile: rows i0.. (in B), columns a0 + j0.. (in A)
+  if (i0 >= np) return;                                              // B is shorter than b, or missing
+  double acc[4][4] = {};
+  auto fa = [&](int i, int k) { return L[(size_t)(i0 + i) * np + a0 + k]; };
+  auto fb = [&](int k, int j) { return inverse_at(L, Dinv, np, a0 + k, a0 + j0 + j); };
+  tile_nn(acc, j0, b, fa, fb, As, Bs);                               // A^-1 is lower triangular: rows k >= j0 only
+  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+#pragma unroll
+  for (int r = 0; r < 4; ++r)
+#pragma unroll
+    for (int c = 0; c < 4; ++c) T[(size_t)(i0 + ty * 4 + r) * np + a0 + j0 + tx * 4 + c] = acc[r][c];
+}
+
+// Step 2: -B^-1 . T over C.
+__global__ void __launch_bounds__(256) trtri_step2_kernel(double* __restrict__ L, const double* __restrict__ Dinv, int np,
+                                                         int b, const double* __restrict__ T) {
+  __shared__ double As[KC][NB + 1], Bs[KC][NB + 1];
+  const int a0 = 2 * b * blockIdx.z, b0 = a0 + b;
+  const int i0 = blockIdx.y * NB, j0 = blockIdx.x * NB;              // tile: rows b0 + i0.., columns a0 + j0..
+  if (b0 + i0 >= np) return;
+  double acc[4][4] = {};
+  // B^-1 (lower triangular, rows / columns relative to b0): its blocks left of the diagonal were written by the
+  // lower levels, which are complete; this level writes blocks of C only
+  auto fa = [&](int i, int k) { return inverse_at(L, Dinv, np, b0 + i0 + i, b0 + k); };
+  auto fb = [&](int k, int j) { return T[(size_t)(b0 + k) * np + a0 + j0 + j]; };
+  tile_nn(acc, 0, i0 + NB, fa, fb, As, Bs);
+  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+#pragma unroll
+  for (int r = 0; r < 4; ++r)
+#pragma unroll
+    for (int c = 0; c < 4; ++c) L[(size_t)(b0 + i0 + ty * 4 + r) * np + a0 + j0 + tx * 4 + c] = -acc[r][c];
+}
+
+__global__ void __launch_bounds__(256) unreverse_kernel(const double* __restrict__ L, const double* __restrict__ Dinv, int n,
+                                                       int np, double* __restrict__ U) {
   const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (idx >= (size_t)n * n) return;
   const int i = (int)(idx / n), j = (int)(idx % n);
-  U[idx] = j >= i ? X[(size_t)(n - 1 - i) * np + (n - 1 - j)] : 0.0;
+  U[idx] = j >= i ? inverse_at(L, Dinv, np, n - 1 - i, n - 1 - j) : 0.0;
 }
 
 }  // namespace spqr_fac
@@ -259,15 +291,19 @@ int spqr_inverse_cholesky(const double* H, int32_t n, double lambda, double* Hic
   const unsigned cells = (unsigned)(((size_t)np * np + 255) / 256);
   hipLaunchKernelGGL(init_reversed_kernel, dim3(cells), dim3(256), 0, st, H, n, np, lambda, L);
   for (int kb = 0; kb < nb; ++kb) {
-    hipLaunchKernelGGL(potrf_diag_kernel, dim3(1), dim3(256), 0, st, L, np, kb, Dinv);
+    hipLaunchKernelGGL(potrf_diag_kernel, dim3(1), dim3(64), 0, st, L, np, kb, Dinv);
     const int rest = nb - kb - 1;
     if (rest > 0) {
       hipLaunchKernelGGL(trsm_panel_kernel, dim3(rest), dim3(256), 0, st, L, np, kb, Dinv);
       hipLaunchKernelGGL(syrk_kernel, dim3(rest, rest), dim3(256), 0, st, L, np, kb);
     }
   }
-  hipLaunchKernelGGL(trtri_kernel, dim3(np / 16), dim3(256), 0, st, L, np, Dinv, X);
-  hipLaunchKernelGGL(unreverse_kernel, dim3((unsigned)(((size_t)n * n + 255) / 256)), dim3(256), 0, st, X, n, np, Hic);
+  for (int b = NB; b < np; b *= 2) {
+    const int tiles = b / NB, pairs = (np + 2 * b - 1) / (2 * b);
+    hipLaunchKernelGGL(trtri_step1_kernel, dim3(tiles, tiles, pairs), dim3(256), 0, st, L, Dinv, np, b, X);
+    hipLaunchKernelGGL(trtri_step2_kernel, dim3(tiles, tiles, pairs), dim3(256), 0, st, L, Dinv, np, b, X);
+  }
+  hipLaunchKernelGGL(unreverse_kernel, dim3((unsigned)(((size_t)n * n + 255) / 256)), dim3(256), 0, st, L, Dinv, n, np, Hic);
   return hipGetLastError() == hipSuccess ? SPQR_OK : SPQR_ERR_HIP;
 }
 

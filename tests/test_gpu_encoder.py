@@ -44,7 +44,7 @@ def test_hessian(E, n, d):
     assert np.abs(H - ref).max() <= 1e-11 * np.abs(ref).max()
 
 
-@pytest.mark.parametrize("n,lam", [(64, 0.5), (96, 0.05), (200, 1.0), (256, 0.01), (640, 0.1)])
+@pytest.mark.parametrize("n,lam", [(64, 0.5), (96, 0.05), (200, 1.0), (256, 0.01), (640, 0.1), (1000, 0.1), (1472, 0.2)])
 def test_inverse_cholesky(E, n, lam):
     _, X = synth.make_quantizer_problem(2, 16, n)
     H = enc.hessian(X)
