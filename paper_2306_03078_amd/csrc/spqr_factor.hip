@@ -117,47 +117,60 @@ __global__ void __launch_bounds__(256) init_reversed_kernel(const double* __rest
   L[idx] = v;
 }
 
-// Diagonal block kb: Cholesky factor in place, its inverse to Dinv[kb].  One wavefront, a lane per row, the block in
-// LDS: the 64 steps depend on each other, so there is nothing for more wavefronts to do but wait at barriers (a
-// wavefront's LDS operations complete in order: no barrier between a step's writes and the next step's reads).
+// A lane's double as every lane sees it (v_readlane: the source lane is uniform).
+__device__ __forceinline__ double readlane_f64(double v, int src) {
+  const uint64_t b = __builtin_bit_cast(uint64_t, v);
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)b, src);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(b >> 32), src);
+  return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+}
+
+// Diagonal block kb: Cholesky factor in place, its inverse to Dinv[kb].  One wavefront, a lane per row, the row in
+// registers: the 64 steps depend on each other, so there is nothing for more wavefronts to do but wait at barriers.
+// Column j of the factor reaches the other rows through v_readlane (lane k holds L[k][j]), not through memory.
 __global__ void __launch_bounds__(64) potrf_diag_kernel(double* __restrict__ L, int np, int kb, double* __restrict__ Dinv) {
   __shared__ double D[NB][NB + 1];
   const int lane = threadIdx.x;
   double* blk = L + (size_t)kb * NB * np + (size_t)kb * NB;
-  for (int idx = lane; idx < NB * NB; idx += 64) D[idx >> 6][idx & 63] = blk[(size_t)(idx >> 6) * np + (idx & 63)];
+  double r[NB];                              // row `lane` of the block
+  for (int idx = lane; idx < NB * NB; idx += 64) D[idx >> 6][idx & 63] = blk[(size_t)(idx >> 6) * np + (idx & 63)];   // coalesced
   __builtin_amdgcn_s_waitcnt(0);
   __builtin_amdgcn_wave_barrier();
+#pragma unroll
+  for (int k = 0; k < NB; ++k) r[k] = D[lane][k];
+  __builtin_amdgcn_wave_barrier();
+#pragma unroll
   for (int j = 0; j < NB; ++j) {
-    const double djj = sqrt(D[j][j]);
-    const double lij = D[lane][j] / djj;
-    if (lane == j) D[j][j] = djj;
-    else if (lane > j) D[lane][j] = lij;
-    __builtin_amdgcn_wave_barrier();
-    for (int k = j + 1; k < NB; ++k) {       // row `lane`, columns j < k <= lane
-      const double lkj = D[k][j];
-      if (k <= lane) D[lane][k] = fma(-lij, lkj, D[lane][k]);
-    }
-    __builtin_amdgcn_wave_barrier();
+    const double djj = sqrt(readlane_f64(r[j], j));
+    const double lij = r[j] / djj;           // L[lane][j] for lane > j
+    r[j] = lane == j ? djj : lij;
+#pragma unroll
+    for (int k = j + 1; k < NB; ++k) r[k] = fma(-lij, readlane_f64(lij, k), r[k]);   // meaningful for k <= lane
   }
-  // inverse of the lower triangular block: column `lane`, kept in registers while it is built
+#pragma unroll
+  for (int k = 0; k < NB; ++k) {
+    D[lane][k] = k <= lane ? r[k] : 0.0;
+  }
+  __builtin_amdgcn_s_waitcnt(0);
+  __builtin_amdgcn_wave_barrier();
+  for (int idx = lane; idx < NB * NB; idx += 64) blk[(size_t)(idx >> 6) * np + (idx & 63)] = D[idx >> 6][idx & 63];
+  // inverse of the lower triangular block: column `lane`, kept in registers while it is built (the factor is read
+  // from LDS, every lane the same element); two running sums halve the chain of dependent additions
   double* inv = Dinv + (size_t)kb * NB * NB;
   {
     const int c = lane;
     double v[NB];
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
-      double s = 0.0;
+      double s0 = 0.0, s1 = 0.0;
 #pragma unroll
-      for (int k = 0; k < i; ++k) s = fma(D[i][k], v[k], s);        // v[k] = 0 above the diagonal of the inverse
+      for (int k = 0; k + 1 < i; k += 2) { s0 = fma(D[i][k], v[k], s0); s1 = fma(D[i][k + 1], v[k + 1], s1); }
+      if (i & 1) s0 = fma(D[i][i - 1], v[i - 1], s0);
       const double dii = D[i][i];
-      v[i] = i < c ? 0.0 : (i == c ? 1.0 / dii : -s / dii);
+      v[i] = i < c ? 0.0 : (i == c ? 1.0 / dii : -(s0 + s1) / dii);    // v[k] = 0 above the diagonal of the inverse
     }
 #pragma unroll
     for (int i = 0; i < NB; ++i) inv[i * NB + c] = v[i];
-  }
-  for (int idx = lane; idx < NB * NB; idx += 64) {
-    const int i = idx >> 6, k = idx & 63;
-    blk[(size_t)i * np + k] = k <= i ? D[i][k] : 0.0;
   }
 }
 
