@@ -25,11 +25,13 @@ namespace spqr_fac {
 
 constexpr int NB = 64;                       // block size of the factorisation
 constexpr int KC = 16;                       // depth of one LDS stage of a tile product
+constexpr int LP = NB + 4;                   // padded row of a staged operand (rows stay 32-byte aligned)
 
-// acc[r][c] += sum_{k < K} fa(ty*4 + r, k) * fb(tx*4 + c, k): a 64 x 64 tile by 256 threads.
+// acc[r][c] += sum_{k < K} fa(ty*4 + r, k) * fb(tx + 16*c, k): a 64 x 64 tile by 256 threads; a thread's four columns
+// are 16 apart, so that the lanes of a wavefront read consecutive words of a staged row (no bank conflicts).
 template <class FA, class FB>
-__device__ __forceinline__ void tile_nt(double (&acc)[4][4], int K, FA fa, FB fb, double (*As)[NB + 1],
-                                        double (*Bs)[NB + 1]) {
+__device__ __forceinline__ void tile_nt(double (&acc)[4][4], int K, FA fa, FB fb, double (*As)[LP],
+                                        double (*Bs)[LP]) {
   const int t = threadIdx.x, tx = t & 15, ty = t >> 4;
   for (int k0 = 0; k0 < K; k0 += KC) {
 #pragma unroll
@@ -43,7 +45,7 @@ __device__ __forceinline__ void tile_nt(double (&acc)[4][4], int K, FA fa, FB fb
     for (int kk = 0; kk < KC; ++kk) {
       double av[4], bv[4];
 #pragma unroll
-      for (int r = 0; r < 4; ++r) { av[r] = As[kk][ty * 4 + r]; bv[r] = Bs[kk][tx * 4 + r]; }
+      for (int r = 0; r < 4; ++r) { av[r] = As[kk][ty * 4 + r]; bv[r] = Bs[kk][tx + 16 * r]; }
 #pragma unroll
       for (int r = 0; r < 4; ++r)
 #pragma unroll
@@ -53,10 +55,10 @@ __device__ __forceinline__ void tile_nt(double (&acc)[4][4], int K, FA fa, FB fb
   }
 }
 
-// acc[r][c] += sum_{kb <= k < ke} fa(ty*4 + r, k) * fb(k, tx*4 + c): the second operand given by rows (k, j).
+// acc[r][c] += sum_{kb <= k < ke} fa(ty*4 + r, k) * fb(k, tx + 16*c): the second operand given by rows (k, j).
 template <class FA, class FB>
-__device__ __forceinline__ void tile_nn(double (&acc)[4][4], int kb, int ke, FA fa, FB fb, double (*As)[NB + 1],
-                                        double (*Bs)[NB + 1]) {
+__device__ __forceinline__ void tile_nn(double (&acc)[4][4], int kb, int ke, FA fa, FB fb, double (*As)[LP],
+                                        double (*Bs)[LP]) {
   const int t = threadIdx.x, tx = t & 15, ty = t >> 4;
   for (int k0 = kb; k0 < ke; k0 += KC) {
 #pragma unroll
@@ -70,7 +72,7 @@ __device__ __forceinline__ void tile_nn(double (&acc)[4][4], int kb, int ke, FA 
     for (int kk = 0; kk < KC; ++kk) {
       double av[4], bv[4];
 #pragma unroll
-      for (int r = 0; r < 4; ++r) { av[r] = As[kk][ty * 4 + r]; bv[r] = Bs[kk][tx * 4 + r]; }
+      for (int r = 0; r < 4; ++r) { av[r] = As[kk][ty * 4 + r]; bv[r] = Bs[kk][tx + 16 * r]; }
 #pragma unroll
       for (int r = 0; r < 4; ++r)
 #pragma unroll
@@ -82,7 +84,7 @@ __device__ __forceinline__ void tile_nn(double (&acc)[4][4], int kb, int ke, FA 
 
 // H = 2 X X^T, tiles on and above the diagonal, mirrored.
 __global__ void __launch_bounds__(256) hessian_kernel(const double* __restrict__ X, int n, int d, double* __restrict__ H) {
-  __shared__ double As[KC][NB + 1], Bs[KC][NB + 1];
+  __shared__ __attribute__((aligned(32))) double As[KC][LP], Bs[KC][LP];
   const int bi = blockIdx.y, bj = blockIdx.x;
   if (bj < bi) return;
   const int i0 = bi * NB, j0 = bj * NB;
@@ -95,7 +97,7 @@ __global__ void __launch_bounds__(256) hessian_kernel(const double* __restrict__
   for (int r = 0; r < 4; ++r)
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
-      const int i = i0 + ty * 4 + r, j = j0 + tx * 4 + c;
+      const int i = i0 + ty * 4 + r, j = j0 + tx + 16 * c;
       if (i < n && j < n) {
         const double v = 2.0 * acc[r][c];
         H[(size_t)i * n + j] = v;
@@ -176,7 +178,7 @@ __global__ void __launch_bounds__(64) potrf_diag_kernel(double* __restrict__ L, 
 
 // Panel below diagonal block kb: A[ib, kb] <- A[ib, kb] . inv(L_kk)^T
 __global__ void __launch_bounds__(256) trsm_panel_kernel(double* __restrict__ L, int np, int kb, const double* __restrict__ Dinv) {
-  __shared__ double As[KC][NB + 1], Bs[KC][NB + 1];
+  __shared__ __attribute__((aligned(32))) double As[KC][LP], Bs[KC][LP];
   const int ib = kb + 1 + blockIdx.x;
   double* blk = L + (size_t)ib * NB * np + (size_t)kb * NB;
   const double* inv = Dinv + (size_t)kb * NB * NB;
@@ -188,12 +190,12 @@ __global__ void __launch_bounds__(256) trsm_panel_kernel(double* __restrict__ L,
 #pragma unroll
   for (int r = 0; r < 4; ++r)
 #pragma unroll
-    for (int c = 0; c < 4; ++c) blk[(size_t)(ty * 4 + r) * np + tx * 4 + c] = acc[r][c];
+    for (int c = 0; c < 4; ++c) blk[(size_t)(ty * 4 + r) * np + tx + 16 * c] = acc[r][c];
 }
 
 // Trailing update: A[ib, jb] -= P_ib . P_jb^T for kb < jb <= ib.
 __global__ void __launch_bounds__(256) syrk_kernel(double* __restrict__ L, int np, int kb) {
-  __shared__ double As[KC][NB + 1], Bs[KC][NB + 1];
+  __shared__ __attribute__((aligned(32))) double As[KC][LP], Bs[KC][LP];
   const int ib = kb + 1 + blockIdx.y, jb = kb + 1 + blockIdx.x;
   if (jb > ib) return;
   const double* pi = L + (size_t)ib * NB * np + (size_t)kb * NB;
@@ -207,7 +209,7 @@ __global__ void __launch_bounds__(256) syrk_kernel(double* __restrict__ L, int n
 #pragma unroll
   for (int r = 0; r < 4; ++r)
 #pragma unroll
-    for (int c = 0; c < 4; ++c) blk[(size_t)(ty * 4 + r) * np + tx * 4 + c] -= acc[r][c];
+    for (int c = 0; c < 4; ++c) blk[(size_t)(ty * 4 + r) * np + tx + 16 * c] -= acc[r][c];
 }
 
 // Element (r, c), r >= c, of the inverse as far as it is built: the diagonal 64-blocks live in Dinv, the blocks
@@ -223,7 +225,7 @@ __device__ __forceinline__ double inverse_at(const double* __restrict__ L, const
 // Step 1: T = C . A^-1 into `T` (at C's place);  C = L[B rows, A columns].
 __global__ void __launch_bounds__(256) trtri_step1_kernel(const double* __restrict__ L, const double* __restrict__ Dinv,
                                                          int np, int b, double* __restrict__ T) {
-  __shared__ double As[KC][NB + 1], Bs[KC][NB + 1];
+  __shared__ __attribute__((aligned(32))) double As[KC][LP], Bs[KC][LP];
   const int a0 = 2 * b * blockIdx.z, b0 = a0 + b;
   const int i0 = b0 + blockIdx.y * NB, j0 = blockIdx.x * NB;        // tile: rows i0.. (in B), columns a0 + j0.. (in A)
   if (i0 >= np) return;                                              // B is shorter than b, or missing
@@ -235,13 +237,13 @@ __global__ void __launch_bounds__(256) trtri_step1_kernel(const double* __restri
 #pragma unroll
   for (int r = 0; r < 4; ++r)
 #pragma unroll
-    for (int c = 0; c < 4; ++c) T[(size_t)(i0 + ty * 4 + r) * np + a0 + j0 + tx * 4 + c] = acc[r][c];
+    for (int c = 0; c < 4; ++c) T[(size_t)(i0 + ty * 4 + r) * np + a0 + j0 + tx + 16 * c] = acc[r][c];
 }
 
 // Step 2: -B^-1 . T over C.
 __global__ void __launch_bounds__(256) trtri_step2_kernel(double* __restrict__ L, const double* __restrict__ Dinv, int np,
                                                          int b, const double* __restrict__ T) {
-  __shared__ double As[KC][NB + 1], Bs[KC][NB + 1];
+  __shared__ __attribute__((aligned(32))) double As[KC][LP], Bs[KC][LP];
   const int a0 = 2 * b * blockIdx.z, b0 = a0 + b;
   const int i0 = blockIdx.y * NB, j0 = blockIdx.x * NB;              // tile: rows b0 + i0.., columns a0 + j0..
   if (b0 + i0 >= np) return;
@@ -255,7 +257,7 @@ __global__ void __launch_bounds__(256) trtri_step2_kernel(double* __restrict__ L
 #pragma unroll
   for (int r = 0; r < 4; ++r)
 #pragma unroll
-    for (int c = 0; c < 4; ++c) L[(size_t)(b0 + i0 + ty * 4 + r) * np + a0 + j0 + tx * 4 + c] = -acc[r][c];
+    for (int c = 0; c < 4; ++c) L[(size_t)(b0 + i0 + ty * 4 + r) * np + a0 + j0 + tx + 16 * c] = -acc[r][c];
 }
 
 __global__ void __launch_bounds__(256) unreverse_kernel(const double* __restrict__ L, const double* __restrict__ Dinv, int n,
