@@ -49,7 +49,11 @@ bool plan_launch(const Geometry& g, int nb, int max_waves, int slots, LaunchPlan
     // the large launches (six projections of a 65B block in one grid: 65.4 against 67.3 us with two two-step
     // wavefronts per strip) and on long strips with at least a workgroup per compute unit (8192x22016: 23.0 against
     // 23.6); a single 22016x8192 takes two two-step wavefronts (23.7 against 25.4 with four one-step ones).
-    if (mf && rmax >= 4 && max_waves >= 4 && max_row_nnz <= 16000 &&
+    // Strips of 32 rows (beta2 = 32 along the rows: 32 accumulators per lane, two strips per workgroup at most): four
+    // wavefronts on one strip whatever its length (22016x8192: 28.1 against 33.2 us for two strips of two wavefronts,
+    // 8192x22016: 25.4 against 26.0 for eight wavefronts, six 65B projections in one grid: 81.1 against 82.6-85.8).
+    if (g.tile_rows >= 32 && nsteps >= 4 && max_waves >= 4 && max_row_nnz <= 16000) { P = 4; R = 1; }
+    else if (mf && rmax >= 4 && max_waves >= 4 && max_row_nnz <= 16000 &&
         ((nsteps <= 8 && nsteps >= 4 && steps_per_slot >= 3.5) || (nsteps > 8 && g.ntr >= 4 * kCUs))) { P = 1; R = 4; }
     else if (mf && rmax >= 2 && nsteps <= 8 && nsteps >= 4 && steps_per_slot >= 2.0) { P = 2; R = 2; }
     else if (nsteps <= 8 && !(nsteps >= 4 && steps_per_slot >= 3.5 && rmax >= 2)) { P = nsteps < 4 ? nsteps : 4; R = 1; }
