@@ -140,7 +140,7 @@ int tuned_batch_width(const Geometry& g, int want) {
     LaunchPlan plan = {0, 0, 0, 0};
     const bool mf = RowDotsOnMatrixCores<3, 8, 32, 1, 1, 1>::value && g.w_bits == 3 && g.tile_rows == 8 &&
                     g.tile_cols == 32 && g.axis == 1 && nb == 1 && g.layout == kBilevel;
-    const int maxw = (g.w_bits == 3 && nb == 1 && g.layout != kStats16 && !wide && !mf) ? 16 : 8;   // WavesPerGroup
+    const int maxw = (g.w_bits == 3 && nb == 1 && g.layout != kStats16 && !wide && !mf && g.tile_rows < 32) ? 16 : 8;   // WavesPerGroup
     if (plan_launch(g, nb, maxw, 8, &plan)) return nb;   // 8 slots: the lowest occupancy any instance has
   }
   return 0;

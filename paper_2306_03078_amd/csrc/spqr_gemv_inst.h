@@ -40,7 +40,7 @@ hipError_t launch_fused_l3(const DevMatrix* As, int count, const uint16_t* const
 template <int W, int TR, int TC, int AXIS, int NB, int LV>
 static hipError_t launch_tile256(const DevMatrix& A, const uint16_t* x, void* y, int y_dtype,
                                  hipStream_t stream) {
-  constexpr int MAXW = WavesPerGroup<W, NB, LV, TR * TC, RowDotsOnMatrixCores<W, TR, TC, AXIS, NB, LV>::value>::MAX;
+  constexpr int MAXW = WavesPerGroup<W, NB, LV, TR * TC, LargeRegisterBudget<W, TR, TC, AXIS, NB, LV>::value>::MAX;
   constexpr int MAX_DYNAMIC = 160 * 1024 - static_lds_bytes(TR, NB) - 1024;   // static + dynamic <= 160 KB
   static PerDevice known[2];                 // wavefront slots per CU of the instance, 0 = not asked yet
   const void* fn = A.perm ? reinterpret_cast<const void*>(&gemv_tile256_kernel<W, TR, TC, AXIS, true, NB, LV>)
@@ -70,7 +70,7 @@ static hipError_t launch_tile256(const DevMatrix& A, const uint16_t* x, void* y,
 template <int W, int TR, int TC, int AXIS, int LV>
 static hipError_t launch_fused256(const DevMatrix* As, int count, const uint16_t* const* xs, void* const* ys,
                                   int y_dtype, hipStream_t stream) {
-  constexpr int MAXW = WavesPerGroup<W, 1, LV, TR * TC, RowDotsOnMatrixCores<W, TR, TC, AXIS, 1, LV>::value>::MAX;
+  constexpr int MAXW = WavesPerGroup<W, 1, LV, TR * TC, LargeRegisterBudget<W, TR, TC, AXIS, 1, LV>::value>::MAX;
   constexpr int MAX_DYNAMIC = 160 * 1024 - static_lds_bytes(TR, 1) - 1024;
   static PerDevice known;
   int slots = 0;

@@ -38,6 +38,12 @@ template <int W, int TC> struct RowPhases {
 template <int W, int TR, int TC, int AXIS, int NB, int LV> struct RowDotsOnMatrixCores {
   static constexpr bool value = SPQR_ROW_DOTS_MFMA && W == 3 && TR == 8 && TC == 32 && AXIS == 1 && NB == 1 && LV == 1;
 };
+// Instances built for workgroups of at most 8 wavefronts (up to 168 registers at three wavefronts per SIMD): those with
+// four accumulators per row, and strips of 32 rows (32 accumulators plus the class bookkeeping: 143 registers; under
+// the 128 of a 16-wavefront workgroup they spilled, and 22016x8192 took 28.1 instead of 25.3 us).
+template <int W, int TR, int TC, int AXIS, int NB, int LV> struct LargeRegisterBudget {
+  static constexpr bool value = RowDotsOnMatrixCores<W, TR, TC, AXIS, NB, LV>::value || TR >= 32;
+};
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
 
@@ -724,7 +730,7 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
 }
 
 template <int W, int TR, int TC, int AXIS, bool PERM, int NB, int LV = 1>
-__global__ void __launch_bounds__((64 * WavesPerGroup<W, NB, LV, TR * TC, RowDotsOnMatrixCores<W, TR, TC, AXIS, NB, LV>::value>::MAX))
+__global__ void __launch_bounds__((64 * WavesPerGroup<W, NB, LV, TR * TC, LargeRegisterBudget<W, TR, TC, AXIS, NB, LV>::value>::MAX))
 gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restrict__ y, int y_dtype,
                     int chunk_cap, int strips_per_group, int waves_per_strip) {
   gemv_tile256_body<W, TR, TC, AXIS, PERM, NB, LV>(A, x, y, y_dtype, chunk_cap, blockIdx.x * strips_per_group,
@@ -749,7 +755,7 @@ struct FusedArgs {
 };
 
 template <int W, int TR, int TC, int AXIS, int LV = 1>
-__global__ void __launch_bounds__((64 * WavesPerGroup<W, 1, LV, TR * TC, RowDotsOnMatrixCores<W, TR, TC, AXIS, 1, LV>::value>::MAX))
+__global__ void __launch_bounds__((64 * WavesPerGroup<W, 1, LV, TR * TC, LargeRegisterBudget<W, TR, TC, AXIS, 1, LV>::value>::MAX))
 gemv_tile256_fused_kernel(FusedArgs F, int y_dtype, int chunk_cap, int strips_per_group, int waves_per_strip) {
   int i = 0;
   while (i + 1 < F.count && (int)blockIdx.x >= F.first[i + 1]) ++i;   // workgroup-uniform, count <= SPQR_MAX_FUSED

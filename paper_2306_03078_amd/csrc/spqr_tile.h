@@ -72,8 +72,8 @@ __device__ __forceinline__ uint32_t pair_f16(const uint32_t* c, int q, const Pai
 //          is assembled at class 2.
 //   4-bit: pair q%4 of a dword: 0,1 are classes 0,1; 2,3 (after >> 8) classes 0,1.
 // ---------------------------------------------------------------------------
-// SHARED = false (tiles of 8 columns: 32 accumulators leave no registers for the class
-// bookkeeping) keeps one class with K = 1 and a shift per pair.
+// SHARED = false keeps one class with K = 1 and a shift per pair (not used by any instance now: tiles of 8 columns,
+// 32 accumulators per lane, take the class bookkeeping too since they are built for the larger register budget).
 template <int W, bool SHARED> struct CodeClass {
   static constexpr int N = !SHARED ? 1 : (W == 3 ? 3 : 2);
   static constexpr int of_pair(int q) {           // q: pair index inside the tile
@@ -86,7 +86,7 @@ template <int W, bool SHARED> struct CodeClass {
     return !SHARED ? 1.f : (W == 3 ? (c == 0 ? 128.f : c == 1 ? 16.f : 2.f) : (c == 0 ? 64.f : 4.f));
   }
 };
-template <int TC> struct SharedShifts { static constexpr bool value = TC != 8; };
+template <int TC> struct SharedShifts { static constexpr bool value = true; };
 
 struct ClassConsts {
   uint32_t mask[3];    // SGPR: code bits of class c inside both half-words
