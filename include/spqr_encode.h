@@ -14,6 +14,7 @@
  *                                    statistic fit without the outliers (fit_statistics()), and the column sweep:
  *                                    quantize, E = (W - w_q) / H^ic_jj (0 at outliers), W -= E . H^ic
  *   spqr_gather_outliers   line 19:  the outlier set as CSR arrays, by row, then by column
+ *   spqr_act_order, spqr_permute_columns, spqr_permute_symmetric: the activation-order heuristic around it (App. B)
  *
  * Arithmetic: binary64 throughout.  spqr_quantize performs exactly one correctly rounded binary64 operation per
  * step of the algorithm, elementwise, sums and updates in column order, never fused: given the same W, H^ic and
@@ -65,6 +66,20 @@ size_t spqr_inverse_cholesky_workspace_bytes(int32_t n);
  * must be positive definite: otherwise Hic holds NaNs (nothing is reported: no synchronisation). */
 int spqr_inverse_cholesky(const double* H, int32_t n, double lambda, double* Hic, void* workspace,
                           size_t workspace_bytes, void* stream);
+
+/* The activation-order heuristic (App. B: `permutation_order act_order`; Sec. 5 ablations), which the paper names
+ * without defining it; reading taken: the input columns are quantised in the order of decreasing Hessian diagonal
+ * (the inputs with the largest second moments first), ties to the smaller index.  perm[j] (n entries, int32) = the
+ * original column that is processed and STORED as column j: the caller quantises spqr_permute_columns(W, perm) with
+ * the factor of spqr_permute_symmetric(H, perm) and hands `perm` to the product calls (spqr_matrix_t::perm), which
+ * multiply stored column j with x[perm[j]].  workspace: 256-byte aligned, spqr_act_order_workspace_bytes(n) bytes.
+ * n <= 65536.  The order is a pure function of diag(H): bit-exact against a stable sort. */
+size_t spqr_act_order_workspace_bytes(int32_t n);
+int spqr_act_order(const double* H, int32_t n, int32_t* perm, void* workspace, size_t workspace_bytes, void* stream);
+/* W_out[i][j] = W[i][perm[j]] (m x n, row-major binary64; W_out != W). */
+int spqr_permute_columns(const double* W, int32_t m, int32_t n, const int32_t* perm, double* W_out, void* stream);
+/* H_out[i][j] = H[perm[i]][perm[j]] (n x n; H_out != H). */
+int spqr_permute_symmetric(const double* H, int32_t n, const int32_t* perm, double* H_out, void* stream);
 
 /* What spqr_quantize writes (all caller-allocated, sizes in elements):
  *   Q            uint8  [m][n]               codes in [0, 2^w_bits)

@@ -40,6 +40,11 @@ Readings (where the printed algorithm is silent, garbled or at odds with the tex
   Q10 gather_outlier_matrix: the format keeps a code under every outlier and adds the stored value on top of the
       de-quantised code (Sec. 4.2), so the stored value is binary16(W_final[r, c] - s_hat * (Q[r, c] - z_hat)),
       with W_final the weight as the sweep left it (adjusted by the error feedback of earlier columns).
+  Q11 "act_order" (App. B's permutation_order; Sec. 5: "the GPTQ activation order heuristic") is named, not defined.
+      Reading: the input columns are processed in the order of decreasing Hessian diagonal (the inputs with the
+      largest second moments first), ties to the smaller index.  perm[j] is the original column that is processed
+      and stored as column j: W and H are permuted before Alg. 1 runs and the stored matrix meets x[perm[j]] at
+      inference (the decoder oracle's `perm`).
 """
 from __future__ import annotations
 
@@ -192,6 +197,21 @@ def spqr_quantize(W, Hic, bits, beta1, beta2, tau, s_bits=3, z_bits=3):
         Q=Q.astype(np.uint8), s_q=Sq.astype(np.uint8), z_q=Zq.astype(np.uint8),
         s_s=Ss.astype(np.float16), z_s=Zs.astype(np.float16), s_z=Sz.astype(np.float16), z_z=Zz.astype(np.float16),
         row_ptr=row_ptr, col_idx=cols.astype(np.uint16), val=val, W_final=W, is_outlier=O, E=E, s_hat=Shat, z_hat=Zhat)
+
+
+def act_order(H):
+    """Q11: column order by decreasing diag(H), ties to the smaller index."""
+    return np.argsort(-np.diagonal(np.asarray(H, dtype=np.float64)), kind="stable").astype(np.int32)
+
+
+def spqr_quantize_act_order(W, X, bits, beta1, beta2, tau, lam, s_bits=3, z_bits=3):
+    """SpQRQuantize with the activation-order heuristic: the result describes W[:, perm] and carries perm."""
+    H = hessian(X)
+    perm = act_order(H)
+    r = spqr_quantize(np.asarray(W, dtype=np.float64)[:, perm], inverse_cholesky(H[np.ix_(perm, perm)], lam), bits, beta1,
+                      beta2, tau, s_bits, z_bits)
+    r.perm = perm
+    return r
 
 
 def spqr_quantize_from_calibration(W, X, bits, beta1, beta2, tau, lam, s_bits=3, z_bits=3):

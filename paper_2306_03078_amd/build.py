@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libspqr.so")
-SOURCES = ["spqr_pack.cpp", "spqr_api.hip", "spqr_dispatch.hip", "spqr_gemv.hip", "spqr_gemv_l1.hip", "spqr_gemv_l1w.hip", "spqr_gemv_l2.hip", "spqr_gemv_l3.hip", "spqr_mfma.hip", "spqr_prefill.hip", "spqr_misc.hip", "spqr_encode.hip", "spqr_factor.hip"]
+SOURCES = ["spqr_pack.cpp", "spqr_api.hip", "spqr_dispatch.hip", "spqr_gemv.hip", "spqr_gemv_l1.hip", "spqr_gemv_l1w.hip", "spqr_gemv_l2.hip", "spqr_gemv_l3.hip", "spqr_mfma.hip", "spqr_prefill.hip", "spqr_misc.hip", "spqr_encode.hip", "spqr_factor.hip", "spqr_order.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          # packed-FP32 VALU forms are kept out of the generated code on purpose
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

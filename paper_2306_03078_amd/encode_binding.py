@@ -38,6 +38,14 @@ def _lib():
         lib.spqr_quantize.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, i32, dbl, C.POINTER(spqr_quantized_t), vp, sz, vp]
         lib.spqr_gather_outliers.restype = C.c_int
         lib.spqr_gather_outliers.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp]
+        lib.spqr_act_order_workspace_bytes.restype = sz
+        lib.spqr_act_order_workspace_bytes.argtypes = [i32]
+        lib.spqr_act_order.restype = C.c_int
+        lib.spqr_act_order.argtypes = [vp, i32, vp, vp, sz, vp]
+        lib.spqr_permute_columns.restype = C.c_int
+        lib.spqr_permute_columns.argtypes = [vp, i32, i32, vp, vp, vp]
+        lib.spqr_permute_symmetric.restype = C.c_int
+        lib.spqr_permute_symmetric.argtypes = [vp, i32, vp, vp, vp]
         _ready = True
     return lib
 
@@ -69,6 +77,39 @@ def spqr_inverse_cholesky(H, lam: float, workspace=None, stream=None):
     _check(_lib().spqr_inverse_cholesky(H.data_ptr(), n, float(lam), U.data_ptr(), workspace.data_ptr(),
                                         workspace.numel(), _stream_ptr(stream)), "spqr_inverse_cholesky")
     return U
+
+
+def spqr_act_order(H, stream=None):
+    """perm (int32 device tensor [n]): the columns in the order of decreasing diag(H), ties to the smaller index."""
+    import torch
+    assert H.dtype == torch.float64 and H.is_contiguous() and H.dim() == 2 and H.shape[0] == H.shape[1]
+    n = int(H.shape[0])
+    ws = torch.empty(max(256, int(_lib().spqr_act_order_workspace_bytes(n))), dtype=torch.uint8, device=H.device)
+    perm = torch.empty(n, dtype=torch.int32, device=H.device)
+    _check(_lib().spqr_act_order(H.data_ptr(), n, perm.data_ptr(), ws.data_ptr(), ws.numel(), _stream_ptr(stream)), "spqr_act_order")
+    s = torch.cuda.current_stream() if stream is None else stream
+    s.synchronize()                           # the scratch goes out of scope here
+    return perm
+
+
+def spqr_permute_columns(W, perm, stream=None):
+    """W[:, perm] for a float64 device tensor W[m, n]."""
+    import torch
+    assert W.dtype == torch.float64 and W.is_contiguous() and perm.dtype == torch.int32 and perm.numel() == W.shape[1]
+    out = torch.empty_like(W)
+    _check(_lib().spqr_permute_columns(W.data_ptr(), int(W.shape[0]), int(W.shape[1]), perm.data_ptr(), out.data_ptr(),
+                                       _stream_ptr(stream)), "spqr_permute_columns")
+    return out
+
+
+def spqr_permute_symmetric(H, perm, stream=None):
+    """H[perm][:, perm] for a float64 device tensor H[n, n]."""
+    import torch
+    assert H.dtype == torch.float64 and H.is_contiguous() and perm.dtype == torch.int32 and perm.numel() == H.shape[0]
+    out = torch.empty_like(H)
+    _check(_lib().spqr_permute_symmetric(H.data_ptr(), int(H.shape[0]), perm.data_ptr(), out.data_ptr(), _stream_ptr(stream)),
+           "spqr_permute_symmetric")
+    return out
 
 
 def spqr_quantize_device(W, Hic, w_bits, beta1, beta2, tau, s_bits=3, z_bits=3, want_final=True, workspace=None,

@@ -158,3 +158,30 @@ def test_vectorised_equals_scalar_loops(bits, b1, b2, tau, m, n):
     assert np.array_equal(r.val, b["val"]) and np.array_equal(r.W_final, b["W_final"])
     if tau < 1:
         assert 0 < r.row_ptr[-1] < m * n
+
+
+def test_act_order_reading_and_direction():
+    # order: decreasing diagonal, ties to the smaller index
+    H = np.diag([3.0, 7.0, 3.0, 9.0, 7.0])
+    assert list(enc.act_order(H)) == [3, 1, 4, 0, 2]
+    assert list(enc.act_order(np.diag([5.0, 4.0, 3.0]))) == [0, 1, 2]
+    # direction: the stored matrix is W[:, perm] and meets x[perm[j]]: with 8-bit codes (error ~ 1e-3 of the weights) the
+    # decoder oracle's product with `perm` reproduces W x; with the inverse permutation it does not
+    W, X = _problem(8, 32, 48)
+    X = X * np.linspace(0.5, 3.0, 48)[::-1, None] * np.where(np.arange(48) % 2, 1.0, 0.3)[:, None]   # distinct input scales
+    r = enc.spqr_quantize_act_order(W, X, 8, 16, 16, 1e9, 0.01)
+    assert sorted(r.perm) == list(range(48)) and list(r.perm) != list(range(48))
+    d = np.diagonal(enc.hessian(X))[r.perm]
+    assert (np.diff(d) <= 0).all()
+    # (on a calibration input: the error feedback minimises the error on those, not on arbitrary vectors)
+    x = (X[:, :1].T / np.abs(X).max()).astype(np.float16)
+    want = W @ x[0].astype(np.float64)
+    y = orc.matvec(r, x)[0]
+    assert np.linalg.norm(y - want) <= 2e-2 * np.linalg.norm(want)
+    inv = np.empty_like(r.perm); inv[r.perm] = np.arange(48)
+    wrong = enc.spqr_quantize_act_order(W, X, 8, 16, 16, 1e9, 0.01); wrong.perm = inv
+    assert np.linalg.norm(orc.matvec(wrong, x)[0] - want) > 0.3 * np.linalg.norm(want)
+    # the sweep itself is Alg. 1 on the permuted problem
+    H = enc.hessian(X)
+    ref = enc.spqr_quantize(W[:, r.perm], enc.inverse_cholesky(H[np.ix_(r.perm, r.perm)], 0.01), 8, 16, 16, 1e9)
+    assert np.array_equal(ref.Q, r.Q)

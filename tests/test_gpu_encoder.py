@@ -137,6 +137,40 @@ def test_whole_chain_on_the_gpu(E):
     torch.cuda.synchronize()
 
 
+def test_act_order_and_permutations(E):
+    import torch
+    import paper_2306_03078_amd as P
+    rng = np.random.default_rng(3)
+    for n in (1, 5, 64, 200, 777, 2048):
+        d = np.round(rng.uniform(0.5, 3.0, n), 2)          # rounding makes ties
+        H = np.diag(d) + 0.0
+        perm = E.spqr_act_order(dev(H)).cpu().numpy()
+        assert np.array_equal(perm, enc.act_order(H)), n
+    m, n = 64, 96
+    W, X = synth.make_quantizer_problem(31, m, n)
+    X = X * np.linspace(0.5, 3.0, n)[::-1, None] * np.where(np.arange(n) % 2, 1.0, 0.3)[:, None]
+    Hd = E.spqr_hessian(dev(X))
+    perm_d = E.spqr_act_order(Hd)
+    perm = perm_d.cpu().numpy()
+    Hn = Hd.cpu().numpy()
+    assert np.array_equal(perm, enc.act_order(Hn))
+    assert np.array_equal(E.spqr_permute_columns(dev(W), perm_d).cpu().numpy(), W[:, perm])
+    assert np.array_equal(E.spqr_permute_symmetric(Hd, perm_d).cpu().numpy(), Hn[np.ix_(perm, perm)])
+    # the whole chain with the heuristic, into the product kernel with its permuted input
+    U = E.spqr_inverse_cholesky(E.spqr_permute_symmetric(Hd, perm_d), 0.05)
+    got = E.spqr_quantize(E.spqr_permute_columns(dev(W), perm_d), U, 4, 16, 16, float("inf"))
+    got.perm = perm
+    A = P.SpQRMatrix.from_logical(got)
+    assert P.spqr_pack_check(A) == 0
+    x = (X[:, :1].T / np.abs(X).max()).astype(np.float16)     # a calibration input: what the error feedback protects
+    y = P.spqr_gemv(A, dev(x[0])).cpu().numpy().astype(np.float64)
+    want = orc.matvec(got, x)[0]
+    assert np.linalg.norm(y - want) <= 1e-3 * np.linalg.norm(want)
+    exact = W @ x[0].astype(np.float64)
+    assert np.linalg.norm(y - exact) <= 0.1 * np.linalg.norm(exact)      # 4-bit weights: a few per cent
+    torch.cuda.synchronize()
+
+
 def test_argument_checks(E):
     import torch
     W = torch.zeros((64, 64), dtype=torch.float64, device="cuda:0")

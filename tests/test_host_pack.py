@@ -29,7 +29,8 @@ def test_library_exports_every_declared_symbol():
     assert "spqr_plan_batch_steps" not in names      # a test hook, not part of the public interface
     enc = _declared(os.path.join(ROOT, "include", "spqr_encode.h"))
     assert {"spqr_hessian", "spqr_inverse_cholesky", "spqr_inverse_cholesky_workspace_bytes", "spqr_quantize",
-            "spqr_quantize_workspace_bytes", "spqr_gather_outliers"} == enc
+            "spqr_quantize_workspace_bytes", "spqr_gather_outliers", "spqr_act_order", "spqr_act_order_workspace_bytes",
+            "spqr_permute_columns", "spqr_permute_symmetric"} == enc
     names = names | enc
     hooks = _declared(os.path.join(ROOT, "paper_2306_03078_amd", "csrc", "spqr_test_hooks.h"))
     assert hooks == {"spqr_plan_batch_steps"}
