@@ -52,7 +52,10 @@ bool plan_launch(const Geometry& g, int nb, int max_waves, int slots, LaunchPlan
     // Strips of 32 rows (beta2 = 32 along the rows: 32 accumulators per lane, two strips per workgroup at most): four
     // wavefronts on one strip whatever its length (22016x8192: 28.1 against 33.2 us for two strips of two wavefronts,
     // 8192x22016: 25.4 against 26.0 for eight wavefronts, six 65B projections in one grid: 81.1 against 82.6-85.8).
-    if (g.tile_rows >= 32 && nsteps >= 4 && max_waves >= 4 && max_row_nnz <= 16000) { P = 4; R = 1; }
+    // Tiles of 8 x 64 (a step covers 4096 columns, so strips are short): two strips of two wavefronts (22016x8192: 23.8
+    // against 26.0 us for one strip of two, 8192^2: 10.4 against 12.2, 8192x22016: 24.6 against 28.1 for four on one strip).
+    if (g.tile_rows == 8 && g.tile_cols == 64 && nsteps >= 2 && max_waves >= 4 && max_row_nnz <= 16000) { P = 2; R = 2; }
+    else if (g.tile_rows >= 32 && nsteps >= 4 && max_waves >= 4 && max_row_nnz <= 16000) { P = 4; R = 1; }
     else if (mf && rmax >= 4 && max_waves >= 4 && max_row_nnz <= 16000 &&
         ((nsteps <= 8 && nsteps >= 4 && steps_per_slot >= 3.5) || (nsteps > 8 && g.ntr >= 4 * kCUs))) { P = 1; R = 4; }
     else if (mf && rmax >= 2 && nsteps <= 8 && nsteps >= 4 && steps_per_slot >= 2.0) { P = 2; R = 2; }
