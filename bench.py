@@ -5,9 +5,11 @@ A step is one pass of the hot path over one batch of synthetic input: the seven
 projections of one LLaMA-65B-shaped decoder block (configuration 4: q, k, v, o
 8192x8192, gate, up 22016x8192, down 8192x22016; 3-bit codes, beta1=8, beta2=32,
 2 % outliers of which 64 full columns), batch 1, each with its own input vector:
-one spqr_gemv_grouped call (two launches: the six projections that read 8192
-inputs, and `down`); --calls seven / fused issue them as seven spqr_gemv calls
-or as four calls (q/k/v and gate/up through spqr_gemv_fused).
+one spqr_gemv_grouped call (ONE launch: `down`, whose input is wider, rides
+along in the grid of the six projections that read 8192 inputs; the launches
+of a step are counted from a stream capture); --calls seven / fused issue them
+as seven spqr_gemv calls or as four calls (q/k/v and gate/up through
+spqr_gemv_fused).
 Successive steps visit distinct copies of the weights (a pool larger than twice
 the 256 MB last-level cache) so that every launch streams from HBM, and 60 GB of
 other allocations stay resident beside them.  Launches are replayed from a HIP
@@ -53,6 +55,35 @@ def measured_traffic(kernel_key):
         if mt:
             return int(mt.group(1))
     return None
+
+
+def count_launches(torch, fn):
+    """Kernel launches of `fn()`: the kernel nodes of a throw-away stream capture of it."""
+    import ctypes as C
+    hip = C.CDLL("libamdhip64.so")
+    st = torch.cuda.Stream()
+    sp = C.c_void_p(st.cuda_stream)
+    graph = C.c_void_p()
+    with torch.cuda.stream(st):
+        if hip.hipStreamBeginCapture(sp, C.c_int(2)) != 0:                # hipStreamCaptureModeRelaxed
+            raise RuntimeError("hipStreamBeginCapture failed")
+        try:
+            fn()
+        finally:
+            rc = hip.hipStreamEndCapture(sp, C.byref(graph))
+    if rc != 0 or not graph.value:
+        raise RuntimeError("hipStreamEndCapture failed")
+    n = C.c_size_t(0)
+    hip.hipGraphGetNodes(graph, None, C.byref(n))
+    nodes = (C.c_void_p * max(1, n.value))()
+    hip.hipGraphGetNodes(graph, nodes, C.byref(n))
+    kernels = 0
+    for k in range(n.value):
+        t = C.c_int(-1)
+        hip.hipGraphNodeGetType(C.c_void_p(nodes[k]), C.byref(t))
+        kernels += t.value == 0                                            # hipGraphNodeTypeKernel
+    hip.hipGraphDestroy(graph)
+    return kernels
 
 
 def algorithmic_bytes(A, batch=1):
@@ -184,7 +215,7 @@ def run_block_sweep(rows, P, synth, torch, dev):
             for fused in (False, True) + (("grouped",) if b == 1 else ()):
                 us = time_block(P, torch, mats, x_h, x_f, copies, fused)
                 rows.append({"config": cfg, "layer": {False: "block(7 calls)", True: "block(q/k/v, gate/up fused: 4 calls)",
-                                                      "grouped": "block(spqr_gemv_grouped: 1 call, 2 launches)"}[fused],
+                                                      "grouped": "block(spqr_gemv_grouped: 1 call)"}[fused],
                              "m": 0, "n": 0, "w_bits": specs[0].w_bits, "beta1": specs[0].beta1, "beta2": specs[0].beta2,
                              "group_axis": 1, "batch": b, "outliers": f"{specs[0].outlier_rate:g} {specs[0].outlier_structure}",
                              "compressed_MB": round(nbytes / 1e6, 2), "us": round(us, 2),
@@ -422,7 +453,7 @@ def main():
     ap.add_argument("--group-axis", type=int, default=1)
     ap.add_argument("--filler-gb", type=int, default=60, help="other allocations kept resident beside the weights")
     ap.add_argument("--calls", choices=("grouped", "fused", "seven"), default="grouped",
-                    help="how a step issues the seven projections: one spqr_gemv_grouped call (2 launches), q/k/v and "
+                    help="how a step issues the seven projections: one spqr_gemv_grouped call, q/k/v and "
                          "gate/up as one spqr_gemv_fused call each (4 launches), or seven spqr_gemv calls")
     ap.add_argument("--block-config", type=int, choices=(2, 3, 4), default=4,
                     help="the configuration whose decoder block is the step (4, the headline workload, by default)")
@@ -503,7 +534,9 @@ def main():
             for li in range(len(base)):
                 P.spqr_gemv(pool[li][c], xs[li], out=ys[li])
 
-    launches_per_step = {"grouped": len({sp.n for sp in specs}), "fused": 2 + len(rest), "seven": len(base)}[args.calls]
+    run_step(0, args.calls)
+    torch.cuda.synchronize()
+    launches_per_step = count_launches(torch, lambda: run_step(0, args.calls))
     stream = torch.cuda.current_stream()
     use_graph = not args.no_graph
     graph = None

@@ -337,11 +337,17 @@ int spqr_gemm_fused_ws(const spqr_matrix_t* const* A, int count, const uint16_t*
  * with an input vector of its own: all projections of a decoder block whose
  * inputs are at hand (Sec. 5 times token-by-token generation: seven such
  * products per block), in as few launches as possible.  A, x_f16 and y are HOST
- * arrays.  Matrices that agree in n, w_bits, beta1, beta2 and group_axis, have
- * a tuned kernel and no permutation run in ONE launch (up to SPQR_MAX_FUSED of
- * them), every workgroup doing what it does in spqr_gemv; the others take a
- * launch each.  Results equal spqr_gemv's, bit for bit.  No scratch, no
- * allocation, no synchronisation. */
+ * arrays.  Matrices that agree in w_bits, beta1, beta2, group_axis and layout,
+ * have a tuned kernel and no permutation run in ONE launch (up to
+ * SPQR_MAX_FUSED of them); the others take a launch each.  The input width n
+ * with the most rows sizes that launch, and every workgroup of such a matrix
+ * does what it does in spqr_gemv: those results equal spqr_gemv's bit for bit.
+ * A matrix of another width joins the launch if the launch's LDS serves it: a
+ * wider one needs max_row_nnz > 0 (the hint then tells that a workgroup's
+ * outliers fit one round; an understated hint costs time, never correctness);
+ * its partial sums over column ranges may meet in another order than in
+ * spqr_gemv (same arithmetic otherwise).  A matrix that cannot join waits for
+ * the next launch of the call.  No scratch, no allocation, no synchronisation. */
 #define SPQR_MAX_GROUPED 16
 int spqr_gemv_grouped(const spqr_matrix_t* const* A, int count, const uint16_t* const* x_f16,
                       void* const* y, int y_dtype, void* stream);

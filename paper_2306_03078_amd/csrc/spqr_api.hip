@@ -184,8 +184,8 @@ extern "C" int spqr_gemv_grouped(const spqr_matrix_t* const* A, int count, const
     if (reinterpret_cast<uintptr_t>(x_f16[i]) % 16 != 0) return SPQR_ERR_ALIGN;
     if (reinterpret_cast<uintptr_t>(y[i]) % (y_dtype == SPQR_F32 ? 4 : 2) != 0) return SPQR_ERR_ALIGN;
   }
-  // matrices that agree in format and n (and have no permutation) go together, up to SPQR_MAX_FUSED per launch,
-  // in the order given
+  // matrices that agree in format (and have no permutation) go together, up to SPQR_MAX_FUSED at a time, in the
+  // order given; the launcher sorts them by input width
   bool done[SPQR_MAX_GROUPED] = {};
   const hipStream_t st = static_cast<hipStream_t>(stream);
   for (int i = 0; i < count; ++i) {
@@ -196,7 +196,7 @@ extern "C" int spqr_gemv_grouped(const spqr_matrix_t* const* A, int count, const
     int k = 0;
     for (int j = i; j < count && k < SPQR_MAX_FUSED; ++j) {
       const spqr_matrix_t *a = A[j], *a0 = A[i];
-      const bool same = a->n == a0->n && a->w_bits == a0->w_bits && a->beta1 == a0->beta1 && a->beta2 == a0->beta2 &&
+      const bool same = a->w_bits == a0->w_bits && a->beta1 == a0->beta1 && a->beta2 == a0->beta2 &&
                         a->group_axis == a0->group_axis && a->layout_version == a0->layout_version &&
                         a->perm == nullptr && a0->perm == nullptr;
       if (done[j] || (j != i && !same)) continue;

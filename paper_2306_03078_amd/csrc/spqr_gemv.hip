@@ -105,6 +105,7 @@ bool plan_launch(const Geometry& g, int nb, int max_waves, int slots, LaunchPlan
   if (room > (max_dynamic - xbytes) / (32 * nb)) room = (max_dynamic - xbytes) / (32 * nb);
   const int cap = room < 8 * 64 * w ? room : 8 * 64 * w;
   out->P = P; out->R = R; out->cap = cap; out->lds = (size_t)xbytes + (size_t)32 * nb * cap;
+  out->lds_room = (size_t)xbytes + (size_t)32 * nb * room;
   return true;
 }
 
@@ -158,16 +159,40 @@ hipError_t launch_tuned(const DevMatrix& A, const uint16_t* x, int nb, void* y, 
   return launch_tuned_l3(A, x, nb, y, y_dtype, stream);
 }
 
-// Matrices of one format and one n, each with its own input vector: one launch when a tuned kernel exists and
-// no permutation is set, else one launch each.
+// Matrices of one format, each with its own input vector: one launch when a tuned kernel exists and no
+// permutation is set, else one launch each.  Input widths may differ: the width with the most strips sizes the
+// launch, and the launcher says which of the other matrices it could take along (`taken`); the rest go round again.
 hipError_t launch_gemv_grouped(const DevMatrix* As, int count, const uint16_t* const* xs, void* const* ys,
                                int y_dtype, hipStream_t stream) {
-  const Geometry& g = As[0].g;
-  if (count > 1 && option(SPQR_OPT_FORCE_GENERIC) == 0 && As[0].perm == nullptr && tuned_batch_width(g, 1) == 1) {
-    if (wide_tile(g)) return launch_fused_l1w(As, count, xs, ys, y_dtype, stream);
-    if (g.layout == kBilevel) return launch_fused_l1(As, count, xs, ys, y_dtype, stream);
-    if (g.layout == kRoundZero) return launch_fused_l2(As, count, xs, ys, y_dtype, stream);
-    return launch_fused_l3(As, count, xs, ys, y_dtype, stream);
+  if (count > 1 && count <= SPQR_MAX_FUSED && option(SPQR_OPT_FORCE_GENERIC) == 0) {
+    bool perm = false;
+    for (int i = 0; i < count; ++i) perm = perm || As[i].perm != nullptr;
+    // the base width: most strips; its matrices first
+    int base = 0; int64_t best = -1;
+    for (int i = 0; i < count; ++i) {
+      int64_t strips = 0;
+      for (int j = 0; j < count; ++j) if (As[j].g.n == As[i].g.n) strips += As[j].g.ntr;
+      if (strips > best) { best = strips; base = i; }
+    }
+    const Geometry& g = As[base].g;
+    if (!perm && tuned_batch_width(g, 1) == 1) {
+      DevMatrix G[SPQR_MAX_FUSED]; const uint16_t* gx[SPQR_MAX_FUSED]; void* gy[SPQR_MAX_FUSED];
+      int k = 0;
+      for (int pass = 0; pass < 2; ++pass)
+        for (int i = 0; i < count; ++i)
+          if ((As[i].g.n == As[base].g.n) == (pass == 0)) { G[k] = As[i]; gx[k] = xs[i]; gy[k] = ys[i]; ++k; }
+      uint32_t taken = 0;
+      hipError_t e;
+      if (wide_tile(g)) e = launch_fused_l1w(G, count, gx, gy, y_dtype, stream, &taken);
+      else if (g.layout == kBilevel) e = launch_fused_l1(G, count, gx, gy, y_dtype, stream, &taken);
+      else if (g.layout == kRoundZero) e = launch_fused_l2(G, count, gx, gy, y_dtype, stream, &taken);
+      else e = launch_fused_l3(G, count, gx, gy, y_dtype, stream, &taken);
+      if (e != hipSuccess) return e;
+      k = 0;                                 // what the launch left behind (never a matrix of the base width)
+      for (int i = 0; i < count; ++i)
+        if (!(taken >> i & 1)) { G[k] = G[i]; gx[k] = gx[i]; gy[k] = gy[i]; ++k; }
+      return k > 0 ? launch_gemv_grouped(G, k, gx, gy, y_dtype, stream) : hipSuccess;
+    }
   }
   for (int i = 0; i < count; ++i) {
     hipError_t e = launch_gemv(As[i], xs[i], ys[i], y_dtype, stream);

@@ -366,7 +366,8 @@ template <int TR, int NB> struct RowsPerGroup { static constexpr int MAX = NB ==
 template <int W, int TR, int TC, int AXIS, bool PERM, int NB, int LV>
 __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint16_t* __restrict__ x,
                                                   void* __restrict__ y, int y_dtype, int chunk_cap,
-                                                  const int first_strip, const int R, const int P) {
+                                                  const int first_strip, const int R, const int P,
+                                                  const bool shared_lds = false) {
   using T = TileRegs<W, TR, TC, AXIS, LV>;
   static_assert(TR * TC == 256 || (TR == 8 && TC == 64 && AXIS == 1), "tiles of 256 codes, or 8 x 64");
   static_assert((TC / 2) % 4 == 0, "x pairs are read as 16-byte LDS words");
@@ -381,12 +382,15 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
   static_assert(ROWS_MAX <= 64 && ROWS_MAX % TR == 0, "one lane per row votes on long rows");
 
   // dynamic LDS: the NB x vectors | products of the outlier entries (8 floats per
-  // chunk and vector)
+  // chunk and vector).  shared_lds (one vector, no permutation; a launch whose LDS was sized for narrower matrices):
+  // the products take the place of x once every wavefront is done with it -- they wait in registers for one more
+  // barrier -- and a strip with more chunks than that holds reads x from global memory instead.
   extern __shared__ __align__(16) uint8_t smem[];
   uint16_t* xs = reinterpret_cast<uint16_t*>(smem);
   const int n = A.g.n, ntc = A.g.ntc, m = A.g.m;
   const int xbytes = (NB * n * 2 + 15) & ~15;
-  float* prod = reinterpret_cast<float*>(smem + xbytes);
+  const bool alias = NB == 1 && !PERM && shared_lds;     // workgroup-uniform
+  float* prod = reinterpret_cast<float*>(smem + (alias ? 0 : xbytes));
   const int pstride = 8 * chunk_cap;         // floats of products per vector
   __shared__ float red[MAX_WAVES][NB][TR];
   __shared__ float osum[NB][ROWS_MAX];
@@ -545,24 +549,27 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
       }
     }
   }
-  if (tid < first_round) {
+  const bool slow = nchunks > chunk_cap;     // workgroup-uniform: more chunks than one round holds
+  if (!alias) {
+    if (tid < first_round) {
 #pragma unroll
-    for (int bi = 0; bi < NB; ++bi) {
-      float p[8];
-      chunk_products(xs + bi * n, (uint32_t)(n - 1), pc, pv, p);
-      store_products(prod + bi * pstride, tid, p);
+      for (int bi = 0; bi < NB; ++bi) {
+        float p[8];
+        chunk_products(xs + bi * n, (uint32_t)(n - 1), pc, pv, p);
+        store_products(prod + bi * pstride, tid, p);
+      }
     }
-  }
-  if (heavy) {
+    if (heavy) {
 #pragma unroll
-    for (int k = 1; k < KMAX; ++k) {
-      const int slot = tid + k * nthreads;
-      if (slot < chunk_cap && slot < nchunks) {
+      for (int k = 1; k < KMAX; ++k) {
+        const int slot = tid + k * nthreads;
+        if (slot < chunk_cap && slot < nchunks) {
 #pragma unroll
-        for (int bi = 0; bi < NB; ++bi) {
-          float p[8];
-          chunk_products(xs + bi * n, (uint32_t)(n - 1), lc[k - 1], lv[k - 1], p);
-          store_products(prod + bi * pstride, slot, p);
+          for (int bi = 0; bi < NB; ++bi) {
+            float p[8];
+            chunk_products(xs + bi * n, (uint32_t)(n - 1), lc[k - 1], lv[k - 1], p);
+            store_products(prod + bi * pstride, slot, p);
+          }
         }
       }
     }
@@ -588,6 +595,36 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
     if ((lane & ((64 / TR) - 1)) == 0) red[wave][bi][row] = rsum;
   }
 
+  if constexpr (NB == 1 && !PERM) {
+    if (alias && !slow) {
+      // the products of a chunk in the registers of its columns and values, parked once x is no longer read
+      auto in_place = [&](u32x4& c8, u32x4& v8) {
+        float p[8];
+        chunk_products(xs, (uint32_t)(n - 1), c8, v8, p);
+        c8 = u32x4{__float_as_uint(p[0]), __float_as_uint(p[1]), __float_as_uint(p[2]), __float_as_uint(p[3])};
+        v8 = u32x4{__float_as_uint(p[4]), __float_as_uint(p[5]), __float_as_uint(p[6]), __float_as_uint(p[7])};
+      };
+      if (tid < first_round) in_place(pc, pv);
+      if (heavy) {
+#pragma unroll
+        for (int k = 1; k < KMAX; ++k) {
+          const int slot = tid + k * nthreads;
+          if (slot < chunk_cap && slot < nchunks) in_place(lc[k - 1], lv[k - 1]);
+        }
+      }
+      __syncthreads();                       // every wavefront has left x behind
+      u32x4* park = reinterpret_cast<u32x4*>(prod);
+      if (tid < first_round) { park[2 * tid] = pc; park[2 * tid + 1] = pv; }
+      if (heavy) {
+#pragma unroll
+        for (int k = 1; k < KMAX; ++k) {
+          const int slot = tid + k * nthreads;
+          if (slot < chunk_cap && slot < nchunks) { park[2 * slot] = lc[k - 1]; park[2 * slot + 1] = lv[k - 1]; }
+        }
+      }
+    }
+  }
+
   // Rows too long for 16 lanes, as a bit mask every wavefront works out for itself
   // from the row pointers in LDS (TR <= 32 lanes vote), and this thread's first
   // output row: both read ahead of the barrier, off the critical path behind it.
@@ -600,7 +637,6 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
   // One barrier publishes products and partials.  Only a strip with more chunks
   // than one round holds needs the slow path.
   __syncthreads();
-  const bool slow = nchunks > chunk_cap;     // workgroup-uniform
   const int base = 8 * c_lo;                 // CSR index of prod[0] in the first round
   if (!slow) {
     if (longs) {
@@ -655,7 +691,7 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
   for (int c0 = 0; c0 < nchunks; c0 += chunk_cap) {      // workgroup-uniform
     const int c1 = min(nchunks, c0 + chunk_cap);
     if (c0 > 0) __syncthreads();                         // previous round's products are consumed
-    if (c0 > 0) {                                        // round 0 is already in LDS
+    if (c0 > 0 || alias) {                               // round 0 is already in LDS (unless x was in its place)
       u32x4 cc[KMAX], vv[KMAX];
 #pragma unroll
       for (int k = 0; k < KMAX; ++k) {
@@ -672,7 +708,8 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
 #pragma unroll
           for (int bi = 0; bi < NB; ++bi) {
             float p[8];
-            chunk_products(xs + bi * n, (uint32_t)(n - 1), cc[k], vv[k], p);
+            if (alias) chunk_products(x, (uint32_t)(n - 1), cc[k], vv[k], p);     // x in LDS is being overwritten
+            else chunk_products(xs + bi * n, (uint32_t)(n - 1), cc[k], vv[k], p);
             store_products(prod + bi * pstride, slot, p);
           }
         }
@@ -737,15 +774,19 @@ gemv_tile256_kernel(DevMatrix A, const uint16_t* __restrict__ x, void* __restric
                                                strips_per_group, waves_per_strip);
 }
 
-// Several matrices of one format and one input width n (the q/k/v or gate/up projections of a
-// decoder block, or all projections of a block that read n inputs) in one grid: workgroups
-// [first[i], first[i+1]) belong to matrix i, each with its own input vector.  Every
-// workgroup does exactly what it would do in a launch of its own matrix.
+// Several matrices of one format (the q/k/v or gate/up projections of a decoder block, or all
+// projections of a block) in one grid: workgroups [first[i], first[i+1]) belong to matrix i, each
+// with its own input vector and its own plan.  A workgroup of a matrix as wide as the launch's
+// LDS was sized for does exactly what it would do in a launch of its own matrix.
 struct FusedArgs {
   int count;
   int first[SPQR_MAX_FUSED + 1];
-  Geometry g;                                // of matrix 0; m and ntr are set per matrix below
+  Geometry g;                                // of matrix 0; m, ntr, n and ntc are set per matrix below
   int m[SPQR_MAX_FUSED];
+  int n[SPQR_MAX_FUSED];
+  int R[SPQR_MAX_FUSED], P[SPQR_MAX_FUSED];  // strips per workgroup, wavefronts per strip (R * P = the launch's wavefronts)
+  int cap[SPQR_MAX_FUSED];                   // outlier chunks of a round
+  int shared_lds[SPQR_MAX_FUSED];            // 1: the products take the place of x (a matrix wider than the launch's LDS was sized for)
   const uint8_t* packed[SPQR_MAX_FUSED];
   const int32_t* row_ptr[SPQR_MAX_FUSED];
   const uint16_t* col[SPQR_MAX_FUSED];
@@ -756,17 +797,18 @@ struct FusedArgs {
 
 template <int W, int TR, int TC, int AXIS, int LV = 1>
 __global__ void __launch_bounds__((64 * WavesPerGroup<W, 1, LV, TR * TC, LargeRegisterBudget<W, TR, TC, AXIS, 1, LV>::value>::MAX))
-gemv_tile256_fused_kernel(FusedArgs F, int y_dtype, int chunk_cap, int strips_per_group, int waves_per_strip) {
+gemv_tile256_fused_kernel(FusedArgs F, int y_dtype) {
   int i = 0;
   while (i + 1 < F.count && (int)blockIdx.x >= F.first[i + 1]) ++i;   // workgroup-uniform, count <= SPQR_MAX_FUSED
   DevMatrix A;
   A.g = F.g;
   A.g.m = F.m[i]; A.g.ntr = F.m[i] / TR;
+  A.g.n = F.n[i]; A.g.ntc = F.n[i] / TC;
   A.packed = F.packed[i]; A.row_ptr = F.row_ptr[i]; A.col = F.col[i]; A.val = F.val[i];
   A.perm = nullptr; A.nnz = 0;
-  gemv_tile256_body<W, TR, TC, AXIS, false, 1, LV>(A, F.x[i], F.y[i], y_dtype, chunk_cap,
-                                               ((int)blockIdx.x - F.first[i]) * strips_per_group, strips_per_group,
-                                               waves_per_strip);
+  const int R = F.R[i];
+  gemv_tile256_body<W, TR, TC, AXIS, false, 1, LV>(A, F.x[i], F.y[i], y_dtype, F.cap[i],
+                                               ((int)blockIdx.x - F.first[i]) * R, R, F.P[i], F.shared_lds[i] != 0);
 }
 
 }  // namespace spqr

@@ -181,6 +181,51 @@ def test_captured_batch_call_with_caller_workspace_is_kernel_nodes_only(P):
     assert hip.hipGraphExecDestroy(ex) == 0 and hip.hipGraphDestroy(graph) == 0
 
 
+@pytest.mark.parametrize("w,b1,b2,axis", [(3, 8, 32, 1), (4, 16, 16, 1), (3, 8, 32, 0), (3, 8, 64, 1), (4, 16, 16, 0)])
+def test_grouped_call_mixed_input_widths(P, w, b1, b2, axis):
+    """Matrices of one format and different input widths in one grouped call: those of the width with the most
+    strips size the launch; a narrower one rides along with the same plan, a wider one with the outlier products
+    in the place of x (its workgroups' chunks fit one round by the hint on the longest row), and one whose hint
+    understates its rows (set by hand here) still gives the right result, reading x from global memory."""
+    import torch
+    fs = [make(w, b1, b2, axis, 5, 200, rate=0.03, structure="cols64", seed=(80, 0)),
+          make(w, b1, b2, axis, 9, 200, rate=0.02, structure="uniform", seed=(80, 1)),
+          make(w, b1, b2, axis, 7, 400, rate=0.03, structure="uniform", seed=(80, 2)),      # wider: more chunks than threads
+          make(w, b1, b2, axis, 4, 196, rate=0.02, structure="uniform", seed=(80, 3)),      # narrower
+          make(w, b1, b2, axis, 6, 200, rate=0.0, structure="none", seed=(80, 4)),
+          make(w, b1, b2, axis, 5, 400, rate=0.25, structure="rows8cols4", seed=(80, 5)),   # wider, hint understated below
+          make(w, b1, b2, axis, 3, 40, rate=0.02, structure="uniform", seed=(80, 6))]       # too short for some plans
+    As = [P.SpQRMatrix.from_logical(f) for f in fs]
+    assert all(A.desc.max_row_nnz > 0 for A in As if A.desc.nnz > 0)
+    As[5].desc.max_row_nnz = 1
+    xs = [dev(synth.make_x(f.n, 1, seed=(81, i))[0]) for i, f in enumerate(fs)]
+    for y_dtype, tol in ((P.SPQR_F32, 1e-4), (P.SPQR_F16, 2e-3)):
+        ys = P.spqr_gemv_grouped(As, xs, y_dtype=y_dtype)
+        torch.cuda.synchronize()
+        for i, (f, A, x, y) in enumerate(zip(fs, As, xs, ys)):
+            one = P.spqr_gemv(A, x, y_dtype=y_dtype)
+            if f.n == fs[0].n:
+                assert torch.equal(y, one), i
+            else:                                # another plan: the partial sums of a row meet in another order
+                d = (y.double() - one.double()).abs().max().item()
+                assert d <= tol * one.double().abs().max().item(), (i, d)
+            assert rel_l2(y.cpu().numpy(), orc.matvec(f, x.cpu().numpy())[0]) <= REL_L2, i
+    # two launches at most: the last matrix may have fewer steps than the plan has wavefronts per strip, the
+    # others share one
+    outs = [torch.empty(f.m, dtype=torch.float32, device="cuda:0") for f in fs]
+    types, ex, graph, st, hip = _graph_node_types(lambda s: P.spqr_gemv_grouped(As, xs, outs=outs, stream=s))
+    assert types in ([0], [0, 0]), types                                 # hipGraphNodeTypeKernel == 0
+    assert hip.hipGraphLaunch(ex, C.c_void_p(st.cuda_stream)) == 0
+    torch.cuda.synchronize()
+    for y, z in zip(P.spqr_gemv_grouped(As, xs), outs):
+        assert torch.equal(y, z)
+    assert hip.hipGraphExecDestroy(ex) == 0 and hip.hipGraphDestroy(graph) == 0
+    # the same call twice gives the same bits
+    again = P.spqr_gemv_grouped(As, xs)
+    for y, z in zip(P.spqr_gemv_grouped(As, xs), again):
+        assert torch.equal(y, z)
+
+
 def test_grouped_call_equals_one_call_per_matrix(P):
     """All projections of a small decoder-block-like set, each with its own input: matrices of one format and width
     share a launch, a 4-bit one, one with a permutation and one without a tuned kernel take their own; every
