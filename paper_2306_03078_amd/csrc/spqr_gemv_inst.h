@@ -127,8 +127,22 @@ static hipError_t launch_fused256(const DevMatrix* As, int count, const uint16_t
       if (need > plan.lds_room) continue;
       cap = (int)(need / 32);
       if (cap > 8 * 64 * nw) cap = 8 * 64 * nw;
-      // a workgroup's R * TR rows: at most that many longest rows, in chunks of 8 entries, plus the two ragged ends
-      if (As[i].max_row_nnz <= 0 || (int64_t)R * TR * As[i].max_row_nnz / 8 + 2 > cap) continue;
+      // A workgroup's R * TR rows: at most that many longest rows, in chunks of 8 entries, plus the two ragged
+      // ends.  Where a few rows are long (full rows), their workgroups go through rounds on the LDS left behind x
+      // (a chunk per thread at least), as long as the average workgroup has room to spare and the launch is long
+      // enough for those workgroups, the first of the grid, to end before the others do (steps of 64 tiles per
+      // wavefront slot of the chip; LLaMA-33B block, rows of up to 17920 outliers, 8.9 steps per slot: 69.0 ->
+      // 60.7 us; LLaMA-7B block, 8 full rows of 11008, 2.3 steps per slot: 31.4 -> 34.4 us).
+      if (As[i].max_row_nnz <= 0) continue;
+      if ((int64_t)R * TR * As[i].max_row_nnz / 8 + 2 > cap) {
+        const int64_t spare = ((int64_t)plan.lds_room - (int64_t)xbytes) / 32;
+        const int64_t typical = (int64_t)((double)As[i].nnz / g.m * R * TR / 8.0 * 1.5) + 2;
+        const double steps_per_slot = (double)all.ntr * ((all.ntc + 63) / 64) / ((double)slots * kCUs);
+        if (spare < 64 * nw || typical > cap || steps_per_slot < 6.0) continue;
+        need = plan.lds_room;                // all the LDS this residency has
+        cap = (int)(need / 32);
+        if (cap > 8 * 64 * nw) cap = 8 * 64 * nw;
+      }
       shared = 1;
     }
     if (cap < 64 * nw || g.kw != T::KW || g.sd != T::SD || g.layout != LV) continue;
@@ -136,7 +150,7 @@ static hipError_t launch_fused256(const DevMatrix* As, int count, const uint16_t
     F.first[k] = total;
     total += (g.ntr + R - 1) / R;
     F.m[k] = g.m; F.n[k] = g.n;
-    F.R[k] = R; F.P[k] = P; F.cap[k] = cap; F.shared_lds[k] = shared;
+    F.R[k] = R; F.P[k] = P; F.cap[k] = cap; F.shared_lds[k] = shared; F.spare_cap[k] = 0;
     F.packed[k] = As[i].packed; F.row_ptr[k] = As[i].row_ptr; F.col[k] = As[i].col; F.val[k] = As[i].val;
     F.x[k] = xs[i];
     F.y[k] = ys[i];
@@ -144,9 +158,13 @@ static hipError_t launch_fused256(const DevMatrix* As, int count, const uint16_t
     ++k;
   }
   F.count = k;
+  for (int i = 0; i < k; ++i) {              // the LDS behind x, now that the launch's size is known
+    const int64_t spare = ((int64_t)lds - (((int64_t)F.n[i] * 2 + 15) & ~(int64_t)15)) / 32;
+    if (F.shared_lds[i]) F.spare_cap[i] = spare < 0 ? 0 : (spare > F.cap[i] ? F.cap[i] : (int)spare);
+  }
   for (int i = k; i <= SPQR_MAX_FUSED; ++i) F.first[i] = total;
   for (int i = k; i < SPQR_MAX_FUSED; ++i) {
-    F.m[i] = 0; F.n[i] = 0; F.R[i] = 1; F.P[i] = 1; F.cap[i] = 0; F.shared_lds[i] = 0;
+    F.m[i] = 0; F.n[i] = 0; F.R[i] = 1; F.P[i] = 1; F.cap[i] = 0; F.shared_lds[i] = 0; F.spare_cap[i] = 0;
     F.packed[i] = nullptr; F.row_ptr[i] = nullptr; F.col[i] = nullptr; F.val[i] = nullptr; F.x[i] = nullptr; F.y[i] = nullptr;
   }
   if (lds > (size_t)MAX_DYNAMIC || k < 1) return hipErrorInvalidValue;

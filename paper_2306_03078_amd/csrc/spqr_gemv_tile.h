@@ -367,7 +367,7 @@ template <int W, int TR, int TC, int AXIS, bool PERM, int NB, int LV>
 __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint16_t* __restrict__ x,
                                                   void* __restrict__ y, int y_dtype, int chunk_cap,
                                                   const int first_strip, const int R, const int P,
-                                                  const bool shared_lds = false) {
+                                                  const bool shared_lds = false, const int spare_cap = 0) {
   using T = TileRegs<W, TR, TC, AXIS, LV>;
   static_assert(TR * TC == 256 || (TR == 8 && TC == 64 && AXIS == 1), "tiles of 256 codes, or 8 x 64");
   static_assert((TC / 2) % 4 == 0, "x pairs are read as 16-byte LDS words");
@@ -384,7 +384,8 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
   // dynamic LDS: the NB x vectors | products of the outlier entries (8 floats per
   // chunk and vector).  shared_lds (one vector, no permutation; a launch whose LDS was sized for narrower matrices):
   // the products take the place of x once every wavefront is done with it -- they wait in registers for one more
-  // barrier -- and a strip with more chunks than that holds reads x from global memory instead.
+  // barrier -- and a strip with more chunks than that holds goes through rounds of the `spare_cap` chunks that the
+  // LDS behind x holds (x stays where it is), or, if that is less than a chunk per thread, reads x from global memory.
   extern __shared__ __align__(16) uint8_t smem[];
   uint16_t* xs = reinterpret_cast<uint16_t*>(smem);
   const int n = A.g.n, ntc = A.g.ntc, m = A.g.m;
@@ -687,6 +688,11 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
 
   // ---- slow path: rounds of chunk_cap chunks (up to KMAX per thread, all loads of a
   // round in flight together); long rows summed by all threads ----------------------
+  const bool x_global = alias && spare_cap < nthreads;   // workgroup-uniform
+  if (alias && !x_global) {                              // x stays, the rounds use what is left behind it
+    prod = reinterpret_cast<float*>(smem + xbytes);
+    chunk_cap = spare_cap;
+  }
   for (int i = tid; i < NB * ROWS_MAX; i += nthreads) (&osum[0][0])[i] = 0.f;
   for (int c0 = 0; c0 < nchunks; c0 += chunk_cap) {      // workgroup-uniform
     const int c1 = min(nchunks, c0 + chunk_cap);
@@ -708,7 +714,7 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
 #pragma unroll
           for (int bi = 0; bi < NB; ++bi) {
             float p[8];
-            if (alias) chunk_products(x, (uint32_t)(n - 1), cc[k], vv[k], p);     // x in LDS is being overwritten
+            if (x_global) chunk_products(x, (uint32_t)(n - 1), cc[k], vv[k], p);  // x in LDS is being overwritten
             else chunk_products(xs + bi * n, (uint32_t)(n - 1), cc[k], vv[k], p);
             store_products(prod + bi * pstride, slot, p);
           }
@@ -787,6 +793,7 @@ struct FusedArgs {
   int R[SPQR_MAX_FUSED], P[SPQR_MAX_FUSED];  // strips per workgroup, wavefronts per strip (R * P = the launch's wavefronts)
   int cap[SPQR_MAX_FUSED];                   // outlier chunks of a round
   int shared_lds[SPQR_MAX_FUSED];            // 1: the products take the place of x (a matrix wider than the launch's LDS was sized for)
+  int spare_cap[SPQR_MAX_FUSED];             // chunks the LDS behind x holds then
   const uint8_t* packed[SPQR_MAX_FUSED];
   const int32_t* row_ptr[SPQR_MAX_FUSED];
   const uint16_t* col[SPQR_MAX_FUSED];
@@ -808,7 +815,7 @@ gemv_tile256_fused_kernel(FusedArgs F, int y_dtype) {
   A.perm = nullptr; A.nnz = 0;
   const int R = F.R[i];
   gemv_tile256_body<W, TR, TC, AXIS, false, 1, LV>(A, F.x[i], F.y[i], y_dtype, F.cap[i],
-                                               ((int)blockIdx.x - F.first[i]) * R, R, F.P[i], F.shared_lds[i] != 0);
+                                               ((int)blockIdx.x - F.first[i]) * R, R, F.P[i], F.shared_lds[i] != 0, F.spare_cap[i]);
 }
 
 }  // namespace spqr

@@ -159,11 +159,14 @@ def test_large_batches_at_full_size(P):
         del f, A
 
 
-def test_grouped_block_at_full_size(P):
-    """All seven projections of the LLaMA-65B-shaped block in one spqr_gemv_grouped call (what bench.py times)."""
+@pytest.mark.parametrize("cfg", [4, 3])
+def test_grouped_block_at_full_size(P, cfg):
+    """All seven projections of the LLaMA-65B-shaped block in one spqr_gemv_grouped call (what bench.py times: one
+    launch, `down` with its products in the place of x), and of the LLaMA-33B-shaped one (one launch too: the
+    workgroups of `down` that own a row of thousands of outliers go through rounds on the LDS behind x)."""
     import torch
-    specs = synth.config_layers(4)
-    fs = [synth.make_config_layer(4, i, group_axis=1) for i in range(len(specs))]
+    specs = synth.config_layers(cfg)
+    fs = [synth.make_config_layer(cfg, i, group_axis=1) for i in range(len(specs))]
     As = [P.SpQRMatrix.from_logical(f) for f in fs]
     xs = [synth.make_x(f.n, 1, seed=(81, i)) for i, f in enumerate(fs)]
     ys = P.spqr_gemv_grouped(As, [dev(x[0]) for x in xs])

@@ -195,9 +195,14 @@ def test_grouped_call_mixed_input_widths(P, w, b1, b2, axis):
           make(w, b1, b2, axis, 6, 200, rate=0.0, structure="none", seed=(80, 4)),
           make(w, b1, b2, axis, 5, 400, rate=0.25, structure="rows8cols4", seed=(80, 5)),   # wider, hint understated below
           make(w, b1, b2, axis, 3, 40, rate=0.02, structure="uniform", seed=(80, 6))]       # too short for some plans
+    if (w, b1, b2, axis) == (3, 8, 32, 1):
+        # so wide that its x leaves less than a chunk per thread of the launch's LDS free (78336 bytes for this
+        # plan: 12800 of x and a round of 2048 chunks), and far more chunks than a round: x from global memory
+        fs.append(make(w, b1, b2, axis, 2, 1100, rate=0.25, structure="rows8cols4", seed=(80, 7)))
     As = [P.SpQRMatrix.from_logical(f) for f in fs]
     assert all(A.desc.max_row_nnz > 0 for A in As if A.desc.nnz > 0)
-    As[5].desc.max_row_nnz = 1
+    for A in As[5:6] + As[7:]:
+        A.desc.max_row_nnz = 1
     xs = [dev(synth.make_x(f.n, 1, seed=(81, i))[0]) for i, f in enumerate(fs)]
     for y_dtype, tol in ((P.SPQR_F32, 1e-4), (P.SPQR_F16, 2e-3)):
         ys = P.spqr_gemv_grouped(As, xs, y_dtype=y_dtype)
