@@ -117,6 +117,8 @@ def time_layer(P, torch, A, X, copies, reps=6):
     e0.record(); g.replay(); e1.record()
     torch.cuda.synchronize()
     reps = max(reps, int(MIN_SWEEP_MS / max(e0.elapsed_time(e1), 1e-3)) + 1)   # a timed region of MIN_SWEEP_MS at least
+    for _ in range(2 * reps):                # and twice that as warm-up running into it (see MIN_WARM_MS)
+        g.replay()
     e0.record()
     for _ in range(reps):
         g.replay()
@@ -190,6 +192,8 @@ def time_block(P, torch, mats, x_h, x_f, copies, fused, reps=4):
     e0.record(); g.replay(); e1.record()
     torch.cuda.synchronize()
     reps = max(reps, int(MIN_SWEEP_MS / max(e0.elapsed_time(e1), 1e-3)) + 1)
+    for _ in range(2 * reps):
+        g.replay()
     e0.record()
     for _ in range(reps):
         g.replay()
