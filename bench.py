@@ -752,7 +752,8 @@ def main():
         "roofline": {"bound": "hbm", "achieved": round(step_bytes / launches_per_step / avg_launch_s / 1e9, 2),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(step_bytes / launches_per_step / avg_launch_s / 1e9 / HBM_PEAK_GBS, 4),
-                     "traffic": measured_traffic(kernel_key),
+                     # the profile holds the one-launch block: no figure for another way of issuing the step
+                     "traffic": measured_traffic(kernel_key) if args.calls == "grouped" and launches_per_step == 1 else None,
                      "kernel": kernel,
                      "algorithmic_bytes_per_launch": step_bytes // launches_per_step,
                      "avg_launch_us": round(avg_launch_s * 1e6, 3),
