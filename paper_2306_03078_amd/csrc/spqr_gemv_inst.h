@@ -132,7 +132,7 @@ static hipError_t launch_fused256(const DevMatrix* As, int count, const uint16_t
       // (a chunk per thread at least), as long as the average workgroup has room to spare and the launch is long
       // enough for those workgroups, the first of the grid, to end before the others do (steps of 64 tiles per
       // wavefront slot of the chip; LLaMA-33B block, rows of up to 17920 outliers, 8.9 steps per slot: 69.0 ->
-      // 60.7 us; LLaMA-7B block, 8 full rows of 11008, 2.3 steps per slot: 31.4 -> 34.4 us).
+      // 60.7 us; LLaMA-7B block, 8 full rows of 11008 of which two in one workgroup, 2.3 steps per slot: 31.0 -> 32.8 us).
       if (As[i].max_row_nnz <= 0 && As[i].nnz != 0) continue;   // no hint (a matrix without outliers needs none)
       if ((int64_t)R * TR * As[i].max_row_nnz / 8 + 2 > cap) {
         const int64_t spare = ((int64_t)plan.lds_room - (int64_t)xbytes) / 32;

@@ -385,7 +385,8 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
   // chunk and vector).  shared_lds (one vector, no permutation; a launch whose LDS was sized for narrower matrices):
   // the products take the place of x once every wavefront is done with it -- they wait in registers for one more
   // barrier -- and a strip with more chunks than that holds goes through rounds of the `spare_cap` chunks that the
-  // LDS behind x holds (x stays where it is), or, if that is less than a chunk per thread, reads x from global memory.
+  // LDS behind x holds (x stays where it is), or, if that is less than a chunk per thread or would take more than two
+  // rounds, through rounds of the whole LDS with x read from global memory.
   extern __shared__ __align__(16) uint8_t smem[];
   uint16_t* xs = reinterpret_cast<uint16_t*>(smem);
   const int n = A.g.n, ntc = A.g.ntc, m = A.g.m;
@@ -688,7 +689,9 @@ __device__ __forceinline__ void gemv_tile256_body(const DevMatrix& A, const uint
 
   // ---- slow path: rounds of chunk_cap chunks (up to KMAX per thread, all loads of a
   // round in flight together); long rows summed by all threads ----------------------
-  const bool x_global = alias && spare_cap < nthreads;   // workgroup-uniform
+  // more than two such rounds: rounds of the whole LDS with x from global memory are fewer and faster (a workgroup
+  // with two full rows of 11008 outliers: the 7B-shaped block 34.4 -> 32.8 us)
+  const bool x_global = alias && (spare_cap < nthreads || nchunks > 2 * spare_cap);   // workgroup-uniform
   if (alias && !x_global) {                              // x stays, the rounds use what is left behind it
     prod = reinterpret_cast<float*>(smem + xbytes);
     chunk_cap = spare_cap;

@@ -200,9 +200,11 @@ def test_grouped_call_mixed_input_widths(P, w, b1, b2, axis):
         # plan: 12800 of x and a round of 2048 chunks), and far more chunks than a round: x from global memory
         fs.append(make(w, b1, b2, axis, 2, 1100, rate=0.25, structure="rows8cols4", seed=(80, 7)))
         fs.append(make(w, b1, b2, axis, 3, 300, rate=0.0, structure="none", seed=(80, 8)))   # wider, no outliers at all
+        # wider, hint understated, between one and two rounds of the LDS behind its x (1648 chunks): rounds there
+        fs.append(make(w, b1, b2, axis, 4, 400, rate=0.10, structure="uniform", seed=(80, 9)))
     As = [P.SpQRMatrix.from_logical(f) for f in fs]
     assert all(A.desc.max_row_nnz > 0 for A in As if A.desc.nnz > 0)
-    for A in As[5:6] + As[7:8]:
+    for A in As[5:6] + As[7:8] + As[9:]:
         A.desc.max_row_nnz = 1
     xs = [dev(synth.make_x(f.n, 1, seed=(81, i))[0]) for i, f in enumerate(fs)]
     for y_dtype, tol in ((P.SPQR_F32, 1e-4), (P.SPQR_F16, 2e-3)):
