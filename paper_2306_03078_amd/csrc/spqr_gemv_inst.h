@@ -128,17 +128,20 @@ static hipError_t launch_fused256(const DevMatrix* As, int count, const uint16_t
       cap = (int)(need / 32);
       if (cap > 8 * 64 * nw) cap = 8 * 64 * nw;
       // A workgroup's R * TR rows: at most that many longest rows, in chunks of 8 entries, plus the two ragged
-      // ends.  Where a few rows are long (full rows), their workgroups go through rounds on the LDS left behind x
-      // (a chunk per thread at least), as long as the average workgroup has room to spare and the launch is long
-      // enough for those workgroups, the first of the grid, to end before the others do (steps of 64 tiles per
-      // wavefront slot of the chip; LLaMA-33B block, rows of up to 17920 outliers, 8.9 steps per slot: 69.0 ->
-      // 60.7 us; LLaMA-7B block, 8 full rows of 11008 of which two in one workgroup, 2.3 steps per slot: 31.0 -> 32.8 us).
+      // ends.  Where a few rows are long (full rows), the matrix takes one strip per workgroup with all wavefronts
+      // on it (half the rows and half the steps per wavefront for the workgroup that owns such a row), and those
+      // workgroups go through rounds (see the kernel) -- as long as the average workgroup has room to spare and
+      // the launch is long enough for them, the first of the grid, to end before the others do (steps of 64 tiles
+      // per wavefront slot of the chip: LLaMA-33B block, rows of up to 17920 outliers, 8.9 steps per slot: 69.0 ->
+      // 60.0 us; LLaMA-7B block, 8 full rows of 11008 of which two in one strip, 2.3: 30.0 -> 29.2 us, with the
+      // full rows in 8 strips 28.7 -> 23.4 us; gate, up and down of that block alone, 1.3: 24.7 -> 27.2 us).
       if (As[i].max_row_nnz <= 0 && As[i].nnz != 0) continue;   // no hint (a matrix without outliers needs none)
       if ((int64_t)R * TR * As[i].max_row_nnz / 8 + 2 > cap) {
         const int64_t spare = ((int64_t)plan.lds_room - (int64_t)xbytes) / 32;
+        if (nsteps >= nw) { P = nw; R = 1; }
         const int64_t typical = (int64_t)((double)As[i].nnz / g.m * R * TR / 8.0 * 1.5) + 2;
         const double steps_per_slot = (double)all.ntr * ((all.ntc + 63) / 64) / ((double)slots * kCUs);
-        if (spare < 64 * nw || typical > cap || steps_per_slot < 6.0) continue;
+        if (spare < 64 * nw || typical > cap || steps_per_slot < 2.0) continue;
         need = plan.lds_room;                // all the LDS this residency has
         cap = (int)(need / 32);
         if (cap > 8 * 64 * nw) cap = 8 * 64 * nw;

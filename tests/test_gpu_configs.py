@@ -159,11 +159,11 @@ def test_large_batches_at_full_size(P):
         del f, A
 
 
-@pytest.mark.parametrize("cfg", [4, 3])
+@pytest.mark.parametrize("cfg", [4, 3, 2])
 def test_grouped_block_at_full_size(P, cfg):
     """All seven projections of the LLaMA-65B-shaped block in one spqr_gemv_grouped call (what bench.py times: one
-    launch, `down` with its products in the place of x), and of the LLaMA-33B-shaped one (one launch too: the
-    workgroups of `down` that own a row of thousands of outliers go through rounds on the LDS behind x)."""
+    launch, `down` with its products in the place of x), and of the LLaMA-33B- and 7B-shaped ones (one launch too:
+    the workgroups of `down` that own rows of thousands of outliers go through rounds)."""
     import torch
     specs = synth.config_layers(cfg)
     fs = [synth.make_config_layer(cfg, i, group_axis=1) for i in range(len(specs))]
