@@ -68,25 +68,18 @@ bool plan_launch(const Geometry& g, int nb, int max_waves, int slots, LaunchPlan
     else if (nsteps <= 8 || (g.ntr >= 400 && rmax >= 2)) { P = 2; R = 2; }
     else { P = max_waves < 8 ? max_waves : 8; R = 1; }
   } else {
-    // several activation vectors: arithmetic dominates, so what counts is wavefronts resident on the CU and an
-    // even split of the steps among them
-    double best = -1.0;
-    for (int w = 1; w <= max_waves && w <= nsteps; ++w) {
-      int groups = slots / w; if (groups < 1) groups = 1;
-      const int need = xbytes + 32 * nb * 64 * w;
-      if (need > max_dynamic) continue;
-      const int by_lds = (160 * 1024) / (need + fixed);
-      if (groups > by_lds) groups = by_lds;
-      if (groups < 1) continue;
-      const int wanted = (g.ntr + kCUs - 1) / kCUs;    // a small grid never puts more workgroups on a CU
-      const int share = groups < wanted ? groups : wanted;
-      int resident = w * share; if (resident > slots) resident = slots;
-      const int per_wave = (nsteps + w - 1) / w;
-      const double even = (double)nsteps / ((double)w * per_wave);
-      const double score = (double)resident * (0.75 + 0.25 * even) * (w % 4 == 0 ? 1.05 : 1.0) * (share >= 2 ? 1.03 : 1.0) + 1e-3 * w;
-      if (score > best) { best = score; P = w; }
-    }
-    if (P == 0) return false;
+    // several activation vectors (one strip per workgroup): four wavefronts per strip, as for one vector -- swept
+    // over 1..8 wavefronts on eight benchmark layers at 2 and 4 vectors: four is best or tied on every one (against
+    // a rule that maximised the resident wavefronts: 6656x6656 at 2 vectors 16.4 -> 11.5 us, 17920x6656 at 4 vectors
+    // 51.5 -> 44.7, 8192x22016 at 2 vectors 44.3 -> 39.3; many small workgroups in every phase of their life again).
+    // A very long outlier row (the caller's hint) is summed by all threads of its workgroup: eight wavefronts then
+    // (full rows of 11008 entries, 4096x11008 at 2 / 4 vectors: 18.2 / 36.3 against 20.8 / 40.4 us with four; rows
+    // of 17920 entries, 6656x17920: 39.8 against 41.9; rows of up to 6656 entries are faster with four: 17.0
+    // against 18.0 on 6656x6656, 30.0 against 39.6 on 17920x6656).
+    (void)slots;
+    const int want = max_row_nnz > 8192 ? 8 : 4;
+    P = nsteps < want ? nsteps : want;
+    if (P > max_waves) P = max_waves;
   }
   // the widest plan that fits the LDS: x + one chunk per thread
   while (P > 1 && xbytes + 32 * nb * 64 * R * P > max_dynamic) { if (R > 1) --R; else --P; }
