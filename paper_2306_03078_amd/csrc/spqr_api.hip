@@ -5,6 +5,7 @@
 
 #include "../../include/spqr.h"
 #include "spqr_kernels.h"
+#include "spqr_gemv_inst.h"
 #include "spqr_test_hooks.h"
 
 namespace {
@@ -248,4 +249,32 @@ extern "C" int spqr_dequant_dense(const spqr_matrix_t* A, int what, void* out, v
 extern "C" int spqr_plan_batch_steps(int groups, int nsteps, int slots_one_step, int slots, int long_workgroups) {
   if (groups < 1 || nsteps < 1 || slots_one_step < 1 || slots < 1 || long_workgroups < 0) return SPQR_ERR_PARAM;
   return spqr::plan_batch_steps(groups, nsteps, slots_one_step, slots, long_workgroups);
+}
+
+extern "C" int spqr_plan_grouped(int count, const int32_t* m, const int32_t* n, const int32_t* max_row_nnz,
+                                 const int64_t* nnz, int w_bits, int beta1, int beta2, int group_axis, int layout_version,
+                                 int max_waves, int slots, int row_dots_on_matrix_cores, int32_t* entries,
+                                 int32_t* wavefronts, int64_t* lds_bytes) {
+  if (!m || !n || !max_row_nnz || !nnz || !entries || !wavefronts || !lds_bytes) return SPQR_ERR_NULL;
+  if (count < 1 || count > SPQR_MAX_FUSED || max_waves < 1 || max_waves > 16 || slots < 1 || slots > 32) return SPQR_ERR_PARAM;
+  spqr::DevMatrix D[SPQR_MAX_FUSED];
+  const int sbits = layout_version == spqr::kStats16 ? 16 : 3;
+  for (int i = 0; i < count; ++i) {
+    if (max_row_nnz[i] < 0 || nnz[i] < 0) return SPQR_ERR_PARAM;
+    const int rc = spqr::make_geometry(layout_version, m[i], n[i], w_bits, sbits, sbits, beta1, beta2, group_axis, &D[i].g);
+    if (rc) return rc;
+    D[i].packed = nullptr; D[i].row_ptr = nullptr; D[i].col = nullptr; D[i].val = nullptr; D[i].perm = nullptr;
+    D[i].nnz = nnz[i]; D[i].max_row_nnz = max_row_nnz[i];
+  }
+  spqr::GroupedPlan gp;
+  if (!spqr::plan_grouped(D, count, max_waves, slots, row_dots_on_matrix_cores != 0, &gp)) return SPQR_ERR_PARAM;
+  for (int j = 0; j < gp.count; ++j) {
+    const spqr::GroupedEntry& e = gp.e[j];
+    int32_t* o = entries + 7 * j;
+    o[0] = e.index; o[1] = e.R; o[2] = e.P; o[3] = e.cap; o[4] = e.shared; o[5] = e.spare_cap;
+    o[6] = (D[e.index].g.ntr + e.R - 1) / e.R;
+  }
+  *wavefronts = gp.nw;
+  *lds_bytes = (int64_t)gp.lds;
+  return gp.count;
 }

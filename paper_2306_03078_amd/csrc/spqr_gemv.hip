@@ -102,6 +102,96 @@ bool plan_launch(const Geometry& g, int nb, int max_waves, int slots, LaunchPlan
   return true;
 }
 
+// ---------------------------------------------------------------------------
+// Plan of one grouped launch (host arithmetic only).  The matrices of the width of As[0] (the caller puts them
+// first) size the launch: its plan and its dynamic LDS.  A matrix of another width rides along if that LDS serves it
+// too: a narrower one with the same plan (its x leaves the products more room), a wider one with the outlier
+// products in the place of x (see the kernel), provided the caller's hint on the longest outlier row says that a
+// workgroup's chunks then fit one round -- or, failing that, that only a few workgroups are that heavy and the
+// launch is long enough to cover them.  Matrices that do not fit are left out (the caller launches them next).
+// ---------------------------------------------------------------------------
+bool plan_grouped(const DevMatrix* As, int count, int max_waves, int slots, bool mf, GroupedPlan* out) {
+  out->count = 0; out->nw = 0; out->lds = 0;
+  if (count < 1 || count > SPQR_MAX_FUSED) return false;
+  const Geometry& g0 = As[0].g;
+  const int TR = g0.tile_rows, n0 = g0.n;
+  const int rows_max = 64;                   // RowsPerGroup<TR, 1>::MAX
+  const size_t max_dynamic = 160 * 1024 - static_lds_bytes(TR, 1) - 1024;
+  Geometry all = g0;                         // the plan sees the strips of all matrices of the base width
+  all.ntr = 0;
+  int longest = 0;                           // the longest outlier row any of them is said to have
+  for (int i = 0; i < count; ++i) {
+    if (As[i].g.n != n0) continue;
+    all.ntr += As[i].g.ntr;
+    if (As[i].max_row_nnz > longest) longest = As[i].max_row_nnz;
+  }
+  LaunchPlan plan = {0, 0, 0, 0, 0};
+  if (!plan_launch(all, 1, max_waves, slots, &plan, longest, mf)) return false;
+  const int nw = plan.P * plan.R;
+  if (plan.lds > max_dynamic || plan.lds_room > max_dynamic || plan.lds_room < plan.lds || plan.cap < 64 * nw ||
+      nw > max_waves || plan.R * TR > rows_max || plan.P > (all.ntc + 63) / 64 || plan.P < 1 || plan.R < 1 || plan.R > 8)
+    return false;
+  size_t lds = plan.lds;
+  int k = 0;
+  // The wider matrices come first in the grid: their wavefronts have the most steps, and the launch ends when its
+  // last workgroup does (65B block: 80.5 against 81.5 us with them last).
+  for (int pass = 0; pass < 2; ++pass)
+  for (int i = 0; i < count; ++i) {
+    const Geometry& g = As[i].g;
+    if ((g.n > n0) != (pass == 0)) continue;
+    const int nsteps = (g.ntc + 63) / 64;
+    const size_t xbytes = ((size_t)g.n * 2 + 15) & ~(size_t)15;
+    int R = plan.R, P = plan.P, cap = plan.cap, shared = 0;
+    size_t need = plan.lds;
+    if (g.n < n0) {                          // its x is shorter: the same plan, the products get the difference
+      if (P > nsteps) continue;
+      cap = (int)((plan.lds - xbytes) / 32);
+      if (cap > 8 * 64 * nw) cap = 8 * 64 * nw;
+    } else if (g.n > n0) {                   // its x is longer: the products wait and take its place
+      if (nw % 2 != 0 || nsteps < 2 || (nw / 2) * TR > rows_max || nw / 2 > 8) continue;
+      P = 2; R = nw / 2;
+      need = xbytes > plan.lds ? xbytes : plan.lds;
+      if (need > plan.lds_room) continue;
+      cap = (int)(need / 32);
+      if (cap > 8 * 64 * nw) cap = 8 * 64 * nw;
+      // A workgroup's R * TR rows: at most that many longest rows, in chunks of 8 entries, plus the two ragged
+      // ends.  Where a few rows are long (full rows), the matrix takes one strip per workgroup with all wavefronts
+      // on it (half the rows and half the steps per wavefront for the workgroup that owns such a row), and those
+      // workgroups go through rounds (see the kernel) -- as long as the average workgroup has room to spare and
+      // the launch is long enough for them, the first of the grid, to end before the others do (steps of 64 tiles
+      // per wavefront slot of the chip: LLaMA-33B block, rows of up to 17920 outliers, 8.9 steps per slot: 69.0 ->
+      // 60.0 us; LLaMA-7B block, 8 full rows of 11008 of which two in one strip, 2.3: 30.0 -> 29.2 us, with the
+      // full rows in 8 strips 28.7 -> 23.4 us; gate, up and down of that block alone, 1.3: 24.7 -> 27.2 us).
+      if (As[i].max_row_nnz <= 0 && As[i].nnz != 0) continue;   // no hint (a matrix without outliers needs none)
+      if ((int64_t)R * TR * As[i].max_row_nnz / 8 + 2 > cap) {
+        const int64_t spare = ((int64_t)plan.lds_room - (int64_t)xbytes) / 32;
+        if (nsteps >= nw) { P = nw; R = 1; }
+        const int64_t typical = (int64_t)((double)As[i].nnz / g.m * R * TR / 8.0 * 1.5) + 2;
+        const double steps_per_slot = (double)all.ntr * ((all.ntc + 63) / 64) / ((double)slots * kCUs);
+        if (spare < 64 * nw || typical > cap || steps_per_slot < 2.0) continue;
+        need = plan.lds_room;                // all the LDS this residency has
+        cap = (int)(need / 32);
+        if (cap > 8 * 64 * nw) cap = 8 * 64 * nw;
+      }
+      shared = 1;
+    }
+    if (cap < 64 * nw || g.kw != g0.kw || g.sd != g0.sd || g.layout != g0.layout || g.tile_rows != g0.tile_rows ||
+        g.tile_cols != g0.tile_cols)
+      continue;
+    if (need > lds) lds = need;
+    out->e[k] = GroupedEntry{i, R, P, cap, shared, 0};
+    ++k;
+  }
+  if (k < 1 || lds > max_dynamic) return false;
+  for (int j = 0; j < k; ++j) {              // the LDS behind x, now that the launch's size is known
+    GroupedEntry& en = out->e[j];
+    const int64_t spare = ((int64_t)lds - (((int64_t)As[en.index].g.n * 2 + 15) & ~(int64_t)15)) / 32;
+    if (en.shared) en.spare_cap = spare < 0 ? 0 : (spare > en.cap ? en.cap : (int)spare);
+  }
+  out->count = k; out->nw = nw; out->lds = lds;
+  return true;
+}
+
 // Wavefront slots per CU of a kernel (from its register count), asked once per device; also opts the kernel in
 // for more than 64 KB of dynamic LDS.
 hipError_t kernel_slots(const void* fn, int max_dynamic, PerDevice* known, int* slots) {

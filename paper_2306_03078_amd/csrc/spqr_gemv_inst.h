@@ -24,6 +24,12 @@ struct LaunchPlan { int P; int R; int cap; size_t lds; size_t lds_room; };
 // spqr_gemv.hip
 bool plan_launch(const Geometry& g, int nb, int max_waves, int slots, LaunchPlan* out, int max_row_nnz = 0, bool mf = false);
 hipError_t kernel_slots(const void* fn, int max_dynamic, PerDevice* known, int* slots);
+// A grouped launch: table entry k is matrix e[k].index with its plan (R strips per workgroup, P wavefronts per strip),
+// the chunks of a round of outlier products, whether those take the place of x (`shared`) and, if so, the chunks
+// the LDS behind x holds; nw = R * P wavefronts per workgroup, lds = the launch's dynamic LDS.
+struct GroupedEntry { int index, R, P, cap, shared, spare_cap; };
+struct GroupedPlan { int count; GroupedEntry e[SPQR_MAX_FUSED]; int nw; size_t lds; };
+bool plan_grouped(const DevMatrix* As, int count, int max_waves, int slots, bool mf, GroupedPlan* out);
 // one pair per statistic layout (spqr_gemv_l1/l2/l3.hip), one for the 8 x 64 tiles of layout 1 (spqr_gemv_l1w.hip)
 hipError_t launch_tuned_l1(const DevMatrix& A, const uint16_t* x, int nb, void* y, int y_dtype, hipStream_t stream);
 hipError_t launch_tuned_l2(const DevMatrix& A, const uint16_t* x, int nb, void* y, int y_dtype, hipStream_t stream);
@@ -69,10 +75,8 @@ static hipError_t launch_tile256(const DevMatrix& A, const uint16_t* x, void* y,
 }
 
 // One launch for matrices of one format.  Those of the width of As[0] (the caller puts them first) size the launch:
-// its plan and its dynamic LDS.  A matrix of another width rides along if that LDS serves it too: a narrower one
-// with the same plan (its x leaves the products more room), a wider one with two wavefronts per strip and the
-// outlier products in the place of x (see the kernel), provided the caller's hint on the longest outlier row says
-// that a workgroup's chunks then fit one round.  Bit i of `taken` is set for every matrix launched.
+// its plan and its dynamic LDS.  Which of the others ride along, and how, is plan_grouped()'s decision (spqr_gemv.hip).
+// Bit i of `taken` is set for every matrix launched.
 template <int W, int TR, int TC, int AXIS, int LV>
 static hipError_t launch_fused256(const DevMatrix* As, int count, const uint16_t* const* xs, void* const* ys,
                                   int y_dtype, hipStream_t stream, uint32_t* taken) {
@@ -85,93 +89,43 @@ static hipError_t launch_fused256(const DevMatrix* As, int count, const uint16_t
   hipError_t e = kernel_slots(reinterpret_cast<const void*>(&gemv_tile256_fused_kernel<W, TR, TC, AXIS, LV>), MAX_DYNAMIC,
                               &known, &slots);
   if (e != hipSuccess) return e;
-  const int n0 = As[0].g.n;
-  Geometry all = As[0].g;                    // the plan sees the strips of all matrices of the base width
-  all.ntr = 0;
-  int longest = 0;                           // the longest outlier row any of them is said to have
-  for (int i = 0; i < count; ++i) {
-    if (As[i].g.n != n0) continue;
-    all.ntr += As[i].g.ntr;
-    if (As[i].max_row_nnz > longest) longest = As[i].max_row_nnz;
-  }
-  LaunchPlan plan = {0, 0, 0, 0, 0};
-  if (!plan_launch(all, 1, MAXW, slots, &plan, longest, RowDotsOnMatrixCores<W, TR, TC, AXIS, 1, LV>::value)) return hipErrorInvalidValue;
-  const int nw = plan.P * plan.R;
   using T = TileRegs<W, TR, TC, AXIS, LV>;
-  if (all.kw != T::KW || all.sd != T::SD || all.layout != LV) return hipErrorInvalidValue;
-  if (plan.lds > (size_t)MAX_DYNAMIC || plan.lds_room > (size_t)MAX_DYNAMIC || plan.lds_room < plan.lds || plan.cap < 64 * nw ||
-      nw > MAXW || plan.R * TR > RowsPerGroup<TR, 1>::MAX || plan.P > (all.ntc + 63) / 64 || plan.P < 1 || plan.R < 1 || plan.R > 8)
-    return hipErrorInvalidValue;
+  const Geometry& g0 = As[0].g;
+  if (g0.kw != T::KW || g0.sd != T::SD || g0.layout != LV || g0.tile_rows != TR || g0.tile_cols != TC) return hipErrorInvalidValue;
+  GroupedPlan gp;
+  if (!plan_grouped(As, count, MAXW, slots, RowDotsOnMatrixCores<W, TR, TC, AXIS, 1, LV>::value, &gp)) return hipErrorInvalidValue;
+  // what the kernel assumes of its launch: checked here, on the host
+  const int nw = gp.nw;
+  if (gp.count < 1 || gp.count > SPQR_MAX_FUSED || gp.lds > (size_t)MAX_DYNAMIC || nw < 1 || nw > MAXW) return hipErrorInvalidValue;
   FusedArgs F;
-  F.g = As[0].g;
-  size_t lds = plan.lds;
-  int total = 0, k = 0;                      // workgroups, table entries
-  // The wider matrices come first in the grid: their wavefronts have the most steps, and the launch ends when its
-  // last workgroup does (65B block: 80.5 against 81.5 us with them last).
-  for (int pass = 0; pass < 2; ++pass)
-  for (int i = 0; i < count; ++i) {
-    const Geometry& g = As[i].g;
-    if ((g.n > n0) != (pass == 0)) continue;
-    const int nsteps = (g.ntc + 63) / 64;
+  F.g = g0;
+  int total = 0;                             // workgroups
+  for (int k = 0; k < gp.count; ++k) {
+    const GroupedEntry& en = gp.e[k];
+    if (en.index < 0 || en.index >= count) return hipErrorInvalidValue;
+    const DevMatrix& A = As[en.index];
+    const Geometry& g = A.g;
     const size_t xbytes = ((size_t)g.n * 2 + 15) & ~(size_t)15;
-    int R = plan.R, P = plan.P, cap = plan.cap, shared = 0;
-    size_t need = plan.lds;
-    if (g.n < n0) {                          // its x is shorter: the same plan, the products get the difference
-      if (P > nsteps) continue;
-      cap = (int)((plan.lds - xbytes) / 32);
-      if (cap > 8 * 64 * nw) cap = 8 * 64 * nw;
-    } else if (g.n > n0) {                   // its x is longer: the products wait and take its place
-      if (nw % 2 != 0 || nsteps < 2 || (nw / 2) * TR > RowsPerGroup<TR, 1>::MAX || nw / 2 > 8) continue;
-      P = 2; R = nw / 2;
-      need = xbytes > plan.lds ? xbytes : plan.lds;
-      if (need > plan.lds_room) continue;
-      cap = (int)(need / 32);
-      if (cap > 8 * 64 * nw) cap = 8 * 64 * nw;
-      // A workgroup's R * TR rows: at most that many longest rows, in chunks of 8 entries, plus the two ragged
-      // ends.  Where a few rows are long (full rows), the matrix takes one strip per workgroup with all wavefronts
-      // on it (half the rows and half the steps per wavefront for the workgroup that owns such a row), and those
-      // workgroups go through rounds (see the kernel) -- as long as the average workgroup has room to spare and
-      // the launch is long enough for them, the first of the grid, to end before the others do (steps of 64 tiles
-      // per wavefront slot of the chip: LLaMA-33B block, rows of up to 17920 outliers, 8.9 steps per slot: 69.0 ->
-      // 60.0 us; LLaMA-7B block, 8 full rows of 11008 of which two in one strip, 2.3: 30.0 -> 29.2 us, with the
-      // full rows in 8 strips 28.7 -> 23.4 us; gate, up and down of that block alone, 1.3: 24.7 -> 27.2 us).
-      if (As[i].max_row_nnz <= 0 && As[i].nnz != 0) continue;   // no hint (a matrix without outliers needs none)
-      if ((int64_t)R * TR * As[i].max_row_nnz / 8 + 2 > cap) {
-        const int64_t spare = ((int64_t)plan.lds_room - (int64_t)xbytes) / 32;
-        if (nsteps >= nw) { P = nw; R = 1; }
-        const int64_t typical = (int64_t)((double)As[i].nnz / g.m * R * TR / 8.0 * 1.5) + 2;
-        const double steps_per_slot = (double)all.ntr * ((all.ntc + 63) / 64) / ((double)slots * kCUs);
-        if (spare < 64 * nw || typical > cap || steps_per_slot < 2.0) continue;
-        need = plan.lds_room;                // all the LDS this residency has
-        cap = (int)(need / 32);
-        if (cap > 8 * 64 * nw) cap = 8 * 64 * nw;
-      }
-      shared = 1;
-    }
-    if (cap < 64 * nw || g.kw != T::KW || g.sd != T::SD || g.layout != LV) continue;
-    if (need > lds) lds = need;
+    if (en.R < 1 || en.R > 8 || en.P < 1 || en.R * en.P != nw || en.R * TR > RowsPerGroup<TR, 1>::MAX || en.P > (g.ntc + 63) / 64 ||
+        en.cap < 64 * nw || en.cap > 8 * 64 * nw || g.kw != T::KW || g.sd != T::SD || g.layout != LV || xbytes > gp.lds ||
+        (size_t)32 * en.cap + (en.shared ? 0 : xbytes) > gp.lds || (en.shared && xbytes + (size_t)32 * en.spare_cap > gp.lds))
+      return hipErrorInvalidValue;
     F.first[k] = total;
-    total += (g.ntr + R - 1) / R;
+    total += (g.ntr + en.R - 1) / en.R;
     F.m[k] = g.m; F.n[k] = g.n;
-    F.R[k] = R; F.P[k] = P; F.cap[k] = cap; F.shared_lds[k] = shared; F.spare_cap[k] = 0;
-    F.packed[k] = As[i].packed; F.row_ptr[k] = As[i].row_ptr; F.col[k] = As[i].col; F.val[k] = As[i].val;
-    F.x[k] = xs[i];
-    F.y[k] = ys[i];
-    *taken |= 1u << i;
-    ++k;
+    F.R[k] = en.R; F.P[k] = en.P; F.cap[k] = en.cap; F.shared_lds[k] = en.shared; F.spare_cap[k] = en.spare_cap;
+    F.packed[k] = A.packed; F.row_ptr[k] = A.row_ptr; F.col[k] = A.col; F.val[k] = A.val;
+    F.x[k] = xs[en.index];
+    F.y[k] = ys[en.index];
+    *taken |= 1u << en.index;
   }
-  F.count = k;
-  for (int i = 0; i < k; ++i) {              // the LDS behind x, now that the launch's size is known
-    const int64_t spare = ((int64_t)lds - (((int64_t)F.n[i] * 2 + 15) & ~(int64_t)15)) / 32;
-    if (F.shared_lds[i]) F.spare_cap[i] = spare < 0 ? 0 : (spare > F.cap[i] ? F.cap[i] : (int)spare);
-  }
-  for (int i = k; i <= SPQR_MAX_FUSED; ++i) F.first[i] = total;
-  for (int i = k; i < SPQR_MAX_FUSED; ++i) {
+  F.count = gp.count;
+  for (int i = gp.count; i <= SPQR_MAX_FUSED; ++i) F.first[i] = total;
+  for (int i = gp.count; i < SPQR_MAX_FUSED; ++i) {
     F.m[i] = 0; F.n[i] = 0; F.R[i] = 1; F.P[i] = 1; F.cap[i] = 0; F.shared_lds[i] = 0; F.spare_cap[i] = 0;
     F.packed[i] = nullptr; F.row_ptr[i] = nullptr; F.col[i] = nullptr; F.val[i] = nullptr; F.x[i] = nullptr; F.y[i] = nullptr;
   }
-  if (lds > (size_t)MAX_DYNAMIC || k < 1) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((gemv_tile256_fused_kernel<W, TR, TC, AXIS, LV>), dim3(total), dim3(64 * nw), lds, stream, F, y_dtype);
+  hipLaunchKernelGGL((gemv_tile256_fused_kernel<W, TR, TC, AXIS, LV>), dim3(total), dim3(64 * nw), gp.lds, stream, F, y_dtype);
   return hipGetLastError();
 }
 

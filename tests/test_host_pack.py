@@ -33,7 +33,7 @@ def test_library_exports_every_declared_symbol():
             "spqr_permute_columns", "spqr_permute_symmetric"} == enc
     names = names | enc
     hooks = _declared(os.path.join(ROOT, "paper_2306_03078_amd", "csrc", "spqr_test_hooks.h"))
-    assert hooks == {"spqr_plan_batch_steps"}
+    assert hooks == {"spqr_plan_batch_steps", "spqr_plan_grouped"}
     lib = C.CDLL(P.library_path())
     for nm in sorted(names | hooks):
         assert hasattr(lib, nm), nm
@@ -212,3 +212,115 @@ def test_batch_launch_plan_arguments_and_the_pinned_choice():
         assert lib.spqr_set_option(2, 0) == 0
     assert lib.spqr_set_option(2, -1) == -3 and lib.spqr_set_option(9, 0) == -3 and lib.spqr_set_option(0, 4) == -3
     assert lib.spqr_set_option(3, 96) == -3 and lib.spqr_set_option(3, 64) == 0 and lib.spqr_set_option(3, 0) == 0   # SPQR_OPT_DENSE_ROWS
+
+
+# ---- plan of a grouped batch-1 launch (host arithmetic; the launcher checks the same invariants before it launches) ----
+
+def _plan_grouped(ms, ns, hints, nnz, w, b1, b2, axis, layout, max_waves, slots, mf):
+    lib = C.CDLL(P.library_path())
+    fn = lib.spqr_plan_grouped
+    fn.restype = C.c_int
+    k = len(ms)
+    I, L = C.c_int32 * k, C.c_int64 * k
+    ent, nw, lds = (C.c_int32 * (7 * k))(), C.c_int32(), C.c_int64()
+    rc = fn(k, I(*ms), I(*ns), I(*hints), L(*nnz), w, b1, b2, axis, layout, max_waves, slots, mf, ent, C.byref(nw), C.byref(lds))
+    return rc, [tuple(ent[7 * j:7 * j + 7]) for j in range(max(rc, 0))], nw.value, lds.value
+
+
+def _check_grouped_plan(entries, nw, lds, ms, ns, hints, tr, tc, max_waves):
+    """What the kernel assumes of every table entry."""
+    assert 1 <= nw <= max_waves and lds <= 160 * 1024
+    assert len({e[0] for e in entries}) == len(entries)
+    for idx, R, Pw, cap, shared, spare, wgs in entries:
+        m, n = ms[idx], ns[idx]
+        xbytes = (2 * n + 15) // 16 * 16
+        assert R * Pw == nw and R * tr <= 64 and 1 <= Pw <= -(-(n // tc) // 64)
+        assert 64 * nw <= cap <= 8 * 64 * nw                       # a chunk per thread at least, eight at most
+        assert wgs == -(-(m // tr) // R)
+        assert xbytes <= lds
+        if shared:
+            assert 32 * cap <= lds and xbytes + 32 * spare <= lds and spare <= cap
+        else:
+            assert xbytes + 32 * cap <= lds and spare == 0
+    wide = [e for e in entries if ns[e[0]] > ns[0]]
+    assert entries[:len(wide)] == wide                             # the wider matrices first in the grid
+    assert all(e[4] == 1 for e in wide) and all(e[4] == 0 for e in entries[len(wide):])
+
+
+def test_grouped_plan_of_the_65b_block_takes_down_along_with_its_products_over_x():
+    ms, ns = [8192] * 4 + [22016] * 2 + [8192], [8192] * 6 + [22016]
+    hints = [205, 204, 203, 202, 207, 201, 509]
+    nnz = [int(0.02 * m * n) for m, n in zip(ms, ns)]
+    rc, ent, nw, lds = _plan_grouped(ms, ns, hints, nnz, 3, 8, 32, 1, 1, 8, 12, 1)
+    assert rc == 7 and nw == 4
+    _check_grouped_plan(ent, nw, lds, ms, ns, hints, 8, 32, 8)
+    down = ent[0]
+    assert down[0] == 6 and down[1:3] == (2, 2) and down[4] == 1 and down[6] == 512
+    assert 2 * 8 * 509 // 8 + 2 <= down[3]                         # by the hint, a workgroup's chunks fit one round
+    assert all(e[1:3] == (4, 1) for e in ent[1:])                  # the six: four strips, one wavefront each
+    assert 3 * (lds + 6144) <= 160 * 1024                          # three workgroups per compute unit still
+    # without the hint on down's longest row it waits for a launch of its own; without outliers it needs none
+    rc, ent, nw, lds = _plan_grouped(ms, ns, hints[:6] + [0], nnz, 3, 8, 32, 1, 1, 8, 12, 1)
+    assert rc == 6 and all(e[0] != 6 for e in ent)
+    rc, ent, nw, lds = _plan_grouped(ms, ns, hints[:6] + [0], nnz[:6] + [0], 3, 8, 32, 1, 1, 8, 12, 1)
+    assert rc == 7 and ent[0][0] == 6 and ent[0][4] == 1
+
+
+def test_grouped_plan_with_long_outlier_rows_depends_on_the_length_of_the_launch():
+    # LLaMA-33B shapes, rows of up to n outliers: one strip per workgroup for down, rounds on the LDS behind x
+    ms, ns = [6656] * 4 + [17920] * 2 + [6656], [6656] * 6 + [17920]
+    nnz = [int(0.01 * m * n) for m, n in zip(ms, ns)]
+    rc, ent, nw, lds = _plan_grouped(ms, ns, ns, nnz, 4, 16, 16, 1, 1, 8, 12, 0)
+    assert rc == 7
+    _check_grouped_plan(ent, nw, lds, ms, ns, ns, 16, 16, 8)
+    assert ent[0][0] == 6 and ent[0][1:3] == (1, nw) and ent[0][4] == 1 and ent[0][5] >= 64 * nw
+    # LLaMA-7B shapes: the whole block is long enough (2.3 steps per wavefront slot), q and down alone are not
+    ms, ns = [4096] * 4 + [11008] * 2 + [4096], [4096] * 6 + [11008]
+    nnz = [int(0.01 * m * n) for m, n in zip(ms, ns)]
+    rc, ent, nw, lds = _plan_grouped(ms, ns, ns, nnz, 3, 16, 16, 1, 1, 16, 16, 0)
+    assert rc == 7 and ent[0][0] == 6 and ent[0][1:3] == (1, nw)
+    _check_grouped_plan(ent, nw, lds, ms, ns, ns, 16, 16, 16)
+    rc, ent, nw, lds = _plan_grouped([4096, 4096], [4096, 11008], [4096, 11008], [167772, 450888], 3, 16, 16, 1, 1, 16, 16, 0)
+    assert rc == 1 and ent[0][0] == 0
+    # the same pair with short rows everywhere: together
+    rc, ent, nw, lds = _plan_grouped([4096, 4096], [4096, 11008], [66, 145], [167772, 450888], 3, 16, 16, 1, 1, 16, 16, 0)
+    assert rc == 2 and ent[0][0] == 1 and ent[0][4] == 1
+    _check_grouped_plan(ent, nw, lds, [4096, 4096], [4096, 11008], [66, 145], 16, 16, 16)
+
+
+@pytest.mark.parametrize("w,b1,b2,axis,tr,tc,max_waves,slots,mf", [
+    (3, 8, 32, 1, 8, 32, 8, 12, 1), (4, 16, 16, 1, 16, 16, 8, 12, 0), (3, 16, 16, 0, 16, 16, 16, 16, 0),
+    (3, 8, 32, 0, 32, 8, 8, 12, 0), (4, 8, 32, 0, 32, 8, 8, 8, 0)])
+def test_grouped_plans_keep_the_kernels_invariants(w, b1, b2, axis, tr, tc, max_waves, slots, mf):
+    rng = np.random.default_rng(7)
+    for _ in range(200):
+        k = int(rng.integers(1, 9))
+        base_n = tc * int(rng.integers(20, 400))
+        ns = [base_n] + [base_n if rng.random() < 0.5 else tc * int(rng.integers(20, 1500)) for _ in range(k - 1)]
+        ns = [min(n, 65536 // tc * tc) for n in ns]
+        ms = [tr * int(rng.integers(1, 3000)) for _ in range(k)]
+        nnz = [int(rng.choice([0.0, 0.005, 0.02, 0.1]) * m * n) for m, n in zip(ms, ns)]
+        hints = [0 if z == 0 else int(rng.choice([0, max(1, 2 * z // m), n])) for z, m, n in zip(nnz, ms, ns)]
+        rc, ent, nw, lds = _plan_grouped(ms, ns, hints, nnz, w, b1, b2, axis, 1, max_waves, slots, mf)
+        if rc < 0:
+            assert rc == -3                                        # no plan (an x that does not fit the LDS)
+            continue
+        assert 1 <= rc <= k and any(e[0] == 0 for e in ent)        # the base matrix is always taken
+        _check_grouped_plan(ent, nw, lds, ms, ns, hints, tr, tc, max_waves)
+        for idx, R, Pw, cap, shared, spare, wgs in ent:
+            if shared and nnz[idx]:
+                assert hints[idx] > 0                              # never without a hint
+
+
+def test_grouped_plan_arguments():
+    lib = C.CDLL(P.library_path())
+    fn = lib.spqr_plan_grouped
+    fn.restype = C.c_int
+    one32, one64 = (C.c_int32 * 1)(4096), (C.c_int64 * 1)(0)
+    ent, nw, lds = (C.c_int32 * 7)(), C.c_int32(), C.c_int64()
+    assert fn(1, one32, one32, one32, one64, 3, 16, 16, 1, 1, 16, 16, 0, ent, C.byref(nw), C.byref(lds)) == 1
+    assert fn(0, one32, one32, one32, one64, 3, 16, 16, 1, 1, 16, 16, 0, ent, C.byref(nw), C.byref(lds)) == -3
+    assert fn(1, one32, one32, one32, one64, 3, 16, 16, 1, 1, 0, 16, 0, ent, C.byref(nw), C.byref(lds)) == -3
+    assert fn(1, None, one32, one32, one64, 3, 16, 16, 1, 1, 16, 16, 0, ent, C.byref(nw), C.byref(lds)) == -1
+    assert fn(1, one32, one32, one32, one64, 5, 16, 16, 1, 1, 16, 16, 0, ent, C.byref(nw), C.byref(lds)) == -3   # w_bits
+
