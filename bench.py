@@ -388,6 +388,50 @@ def run_other_configs(P, synth, torch, dev, cfgs_axes):
     return out
 
 
+def run_other_blocks(P, synth, torch, dev, cfgs, axis):
+    """Whole decoder blocks of the other configurations at batch 1: one spqr_gemv_grouped call per step (its launches
+    counted from a stream capture), graph replay over distinct weight copies, warm-up running into the timed region."""
+    out = []
+    for cfg in cfgs:
+        specs = synth.config_layers(cfg)
+        base = [P.SpQRMatrix.from_logical(synth.make_config_layer(cfg, li, group_axis=axis), dev) for li in range(len(specs))]
+        nbytes = sum(algorithmic_bytes(A, 1) for A in base)
+        copies = max(3, int(600e6 // nbytes) + 1)
+        pool = [base] + [[A.clone() for A in base] for _ in range(copies - 1)]
+        xs = [torch.from_numpy(synth.make_x(sp.n, 1, seed=(cfg, li, 2))[0]).to(dev) for li, sp in enumerate(specs)]
+        ys = [torch.empty(sp.m, dtype=torch.float32, device=dev) for sp in specs]
+        P.spqr_gemv_grouped(pool[0], xs, outs=ys)
+        torch.cuda.synchronize()
+        launches = count_launches(torch, lambda: P.spqr_gemv_grouped(pool[0], xs, outs=ys))
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for c in range(copies):
+                P.spqr_gemv_grouped(pool[c], xs, outs=ys)
+        e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+        g.replay()
+        torch.cuda.synchronize()
+        e0.record(); g.replay(); e1.record()
+        torch.cuda.synchronize()
+        reps = int(2 * MIN_SWEEP_MS / max(e0.elapsed_time(e1), 1e-3)) + 1
+        for _ in range(2 * reps):
+            g.replay()
+        e0.record()
+        for _ in range(reps):
+            g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / (reps * copies)
+        out.append({"config": cfg, "block": "q, k, v, o %dx%d + gate, up %dx%d + down %dx%d" % (
+                        specs[0].m, specs[0].n, specs[4].m, specs[4].n, specs[6].m, specs[6].n),
+                    "w_bits": specs[0].w_bits, "beta1": specs[0].beta1, "beta2": specs[0].beta2, "group_axis": axis,
+                    "outliers": f"{specs[0].outlier_rate:g} {specs[0].outlier_structure}", "launches_per_step": launches,
+                    "compressed_MB": round(nbytes / 1e6, 2), "us": round(us, 2), "GBps": round(nbytes / us / 1e3, 1),
+                    "frac_of_hbm_peak": round(nbytes / us / 1e3 / HBM_PEAK_GBS, 4)})
+        del pool, base, g
+        torch.cuda.empty_cache()
+    return out
+
+
 def run_encoder(torch, dev, with_cpu):
     """The quantiser (Alg. 1) on one 11008 x 4096 layer (the gate / up projection of configurations 1 and 2): H = 2 X X^T, its inverse factor, the sweep.  Inputs are drawn
     on the device from a seeded generator (W ~ N(0, 0.05^2) with 2 % of the entries six times larger, X = A G with
@@ -657,9 +701,10 @@ def main():
     del pool, graph, other
     torch.cuda.empty_cache()
 
-    other_configs = batches = None
+    other_configs = batches = other_blocks = None
     if not args.no_configs:
         batches = run_batches(P, synth, torch, dev, args.group_axis)
+        other_blocks = run_other_blocks(P, synth, torch, dev, [c for c in (2, 3) if c != cfg], args.group_axis)
         other_configs = run_other_configs(P, synth, torch, dev,
                                           [(0, args.group_axis), (1, args.group_axis), (2, args.group_axis),
                                            (3, args.group_axis), (4, 1 - args.group_axis)])
@@ -764,6 +809,7 @@ def main():
     }
     if other_configs is not None:
         out["other_configs_batch1"] = other_configs
+        out["other_blocks_batch1"] = other_blocks
         out["batches_config3"] = batches
     if encoder is not None:
         out["encoder"] = encoder
