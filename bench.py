@@ -40,6 +40,7 @@ MIN_WARM_MS = 200.0      # nor is the warm-up that runs into it without a pause:
                          # after idle the chip runs up to 35 % slower (launch durations under the tracer: 79 us, then
                          # 108, back to 80 within 30 ms), and what is reported is the sustained rate
 MIN_SWEEP_MS = 20.0      # the same for every figure of the per-layer and per-block sweeps
+SWEEPS_PER_GRAPH = 8     # passes over the pool of weight copies captured into the graph of the timed step
 
 
 def measured_traffic(kernel_key):
@@ -603,12 +604,15 @@ def main():
         stream.wait_stream(side)
         torch.cuda.synchronize()
         graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            for k in range(copies):
-                run_step(k, args.calls)
+        with torch.cuda.graph(graph):          # SWEEPS_PER_GRAPH passes over the pool per replay: the few us between
+            for _ in range(SWEEPS_PER_GRAPH):  # two replays are shared by that many steps
+                for k in range(copies):
+                    run_step(k, args.calls)
+    unit = SWEEPS_PER_GRAPH if graph is not None else 1     # sweeps come in units of this many
 
     def run_sweeps(nsweeps):                   # one sweep = one pass over the pool = `copies` steps
-        for _ in range(nsweeps):
+        assert nsweeps % unit == 0
+        for _ in range(nsweeps // unit):
             if graph is not None:
                 graph.replay()
             else:
@@ -618,15 +622,15 @@ def main():
     e0 = torch.cuda.Event(enable_timing=True)
     e1 = torch.cuda.Event(enable_timing=True)
     # two sweeps, then one that is timed to size the warm-up and the timed region
-    run_sweeps(2)
+    run_sweeps(2 * unit)
     torch.cuda.synchronize()
-    e0.record(); run_sweeps(1); e1.record()
+    e0.record(); run_sweeps(unit); e1.record()
     torch.cuda.synchronize()
-    est_ms_per_step = max(e0.elapsed_time(e1) / copies, 1e-3)
+    est_ms_per_step = max(e0.elapsed_time(e1) / (unit * copies), 1e-3)
     # warm-up: at least the requested steps and MIN_WARM_MS of work; the timed region follows it on the stream
     # without a host synchronisation in between; it is cut into four windows to show how steady the rate is
-    warm_sweeps = math.ceil(max(args.warmup, MIN_WARM_MS / est_ms_per_step) / copies)
-    nsweeps = 4 * math.ceil(max(args.steps, MIN_TIMED_MS / est_ms_per_step) / (4 * copies))
+    warm_sweeps = unit * math.ceil(max(args.warmup, MIN_WARM_MS / est_ms_per_step) / (unit * copies))
+    nsweeps = 4 * unit * math.ceil(max(args.steps, MIN_TIMED_MS / est_ms_per_step) / (4 * unit * copies))
     steps_timed = nsweeps * copies
     marks = [torch.cuda.Event(enable_timing=True) for _ in range(5)]
     t0 = time.perf_counter()
@@ -789,7 +793,7 @@ def main():
                                f"{100 * sp0.outlier_rate:g}% outliers ({sp0.outlier_structure}), batch 1, beside "
                                f"{args.filler_gb} GB of filler allocations",
                    "launches_per_step": launches_per_step, "calls": args.calls, "weight_copies": copies,
-                   "pool_MB": round(pool_bytes / 1e6, 1), "graph_replay": bool(use_graph),
+                   "pool_MB": round(pool_bytes / 1e6, 1), "graph_replay": bool(use_graph), "steps_per_graph": unit * copies,
                    "wall_ms_per_step": round(wall * 1e3 / steps_timed, 6),
                    "parity_rel_l2": [float(f"{p:.3e}") for p in parity], "parity_checked_on": parity_kind},
         "layers": per_layer,
